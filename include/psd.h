@@ -1,0 +1,220 @@
+/*
+ * psd.h -- C ABI of the MI355X (gfx950) library for the Parallel Speculative Decoding
+ * (PSD) denoising step of masked-diffusion language models.
+ *
+ * One loop iteration of the paper's Alg. 1 is
+ *     stage 1  forward -> (x_hat, c) on the masked positions of the active block  (Sec. 3.1)
+ *              T = pi(x, c); commit x_hat on T                                      (Eq. 1)
+ *     stage 2  sigma = residual masks by step-t confidence; K drafts               (Eq. 2)
+ *     stage 3  one batched forward over the K drafts; hierarchical acceptance over
+ *              the draft DAG; advance to the deepest accepted draft                 (Sec. 3.2)
+ * and every step runs in hand-written HIP kernels behind the calls below.
+ *
+ * Conventions
+ *   - Every function returns an int32 status: PSD_OK (0) or a negative PSD_ERR_*.
+ *     Arguments are validated on the host before anything is enqueued; on error nothing
+ *     is launched and no output is written.  psd_last_error() gives a message.
+ *   - "device" pointers are HIP device memory owned by the caller (any allocator).
+ *     "host" pointers are ordinary host memory.  The library allocates device memory only
+ *     inside psd_create (a few KB of control state) and frees it in psd_destroy.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     enqueue asynchronously and do not synchronise, except psd_decode_block, which
+ *     returns host statistics and reads small counters back once per iteration.
+ *   - Layouts are row-major.  tokens int32 [B, N]; the active block is positions
+ *     block_start .. block_start+L-1 of every sequence (1 <= L <= 64).  Per-block tables
+ *     are top1 int32 [B, L] and conf float [B, L]: a masked position carries the
+ *     prediction, any other position the sentinel (its own token, -1.0f).
+ *   - Sequences of a batch are independent; batching never changes a sequence's result.
+ */
+#ifndef PSD_H
+#define PSD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PSD_OK               0
+#define PSD_ERR_INVALID_ARG -1
+#define PSD_ERR_SHAPE       -2
+#define PSD_ERR_WORKSPACE   -3
+#define PSD_ERR_DEVICE      -4
+#define PSD_ERR_UNSUPPORTED -5
+
+#define PSD_MAX_NODES 32   /* K, root included */
+#define PSD_MAX_BLOCK 64   /* L */
+
+#define PSD_DTYPE_FP32 0   /* debug path: fp32 storage and arithmetic, plain kernels */
+#define PSD_DTYPE_BF16 1   /* bf16 storage, MFMA contractions with fp32 accumulation */
+
+typedef struct psd_handle psd_handle;
+
+/* Model layout.  The paper only requires a bidirectional transformer that yields a
+ * distribution per position (Sec. 3.1); this is the pre-norm RMSNorm / rotary / SwiGLU
+ * decoder stack of the benchmarked 7-8B models, run without a causal mask. */
+typedef struct {
+    int32_t n_layers, d_model, n_heads, n_kv_heads, d_head, d_ffn, vocab;
+    int32_t mask_id;       /* id of [M]; it has an embedding row but is never predicted */
+    float   rms_eps;
+    int32_t qkv_bias;      /* 1: bq/bk/bv present */
+    int32_t dtype;         /* PSD_DTYPE_*: type of every weight matrix */
+    float   logit_scale;   /* logits = logit_scale * (y W_lm^T); 1.0 normally */
+    int32_t max_seq;       /* rows of the rotary tables */
+} psd_model_config;
+
+/* Device pointers, borrowed for the life of the handle.  Matrices are [out, in] in the
+ * model dtype; norm gains, biases and rotary tables are fp32.  The per-layer members are
+ * host arrays of n_layers device pointers (copied by psd_create). */
+typedef struct {
+    const void  *tok_emb;      /* [vocab, d_model] */
+    const float *final_norm;   /* [d_model] */
+    const void  *lm_head;      /* [vocab, d_model] */
+    const float *rope_cos;     /* [max_seq, d_head/2], cos(pos * theta^(-2j/d_head)) */
+    const float *rope_sin;     /* [max_seq, d_head/2]; pairs are (j, j + d_head/2) */
+    const float *const *attn_norm;   /* [d_model] */
+    const void  *const *wq;          /* [n_heads*d_head, d_model] */
+    const void  *const *wk;          /* [n_kv_heads*d_head, d_model] */
+    const void  *const *wv;          /* [n_kv_heads*d_head, d_model] */
+    const float *const *bq, *const *bk, *const *bv;   /* NULL arrays when qkv_bias == 0 */
+    const void  *const *wo;          /* [d_model, n_heads*d_head] */
+    const float *const *ffn_norm;    /* [d_model] */
+    const void  *const *w_gate;      /* [d_ffn, d_model] */
+    const void  *const *w_up;        /* [d_ffn, d_model] */
+    const void  *const *w_down;      /* [d_model, d_ffn] */
+} psd_weights;
+
+/* Transfer policy pi (Sec. 3.2 stage 1; App. B.2): over the masked positions of the block,
+ * ordered by confidence descending (ties: lower position first), commit every position
+ * with c > tau plus the k_min most confident; if k_max > 0 at most the k_max most
+ * confident of those.  Greedy decoding: tau = +inf, k_min = 1.  Confidence Parallel
+ * Decoding: tau = 0.9, k_min = 1.  The same rule is the acceptance criterion A_pi. */
+typedef struct {
+    float   tau;
+    int32_t k_min;
+    int32_t k_max;   /* 0 = unbounded */
+} psd_policy;
+
+/* Draft DAG (Sec. 3.2 stage 2).  Node k speculates on the ranks of the speculative
+ * ordering sigma whose bits are set in rank_set[k] (bit r <-> sigma_{r+1}); node 0 is the
+ * root with rank_set[0] = 0.  Edges are implied: (p, k) is an edge iff S_p is a strict
+ * subset of S_k.  Ranks >= m (the number of residual masks) are ignored. */
+typedef struct {
+    int32_t  K;
+    uint64_t rank_set[PSD_MAX_NODES];
+} psd_graph;
+
+/* Per-sequence counters of psd_decode_block.  TPF = tokens / invocations with
+ * tokens = tokens_policy + tokens_draft + tokens_postverify; a batched verification
+ * counts as one invocation (Sec. 4.1 "Metrics"). */
+typedef struct {
+    int64_t invocations;
+    int64_t tokens_policy;       /* committed by pi in stage 1 */
+    int64_t tokens_draft;        /* |S_k*| of the accepted drafts */
+    int64_t tokens_postverify;   /* committed by pi on k*'s verifier output */
+    int32_t depth_hist[PSD_MAX_NODES + PSD_MAX_BLOCK + 1];   /* histogram of |S_k*| */
+} psd_stats;
+
+const char *psd_status_string(int32_t status);
+/* Message of the last error raised on the calling thread ("" if none). */
+const char *psd_last_error(void);
+
+/* Creates a handle on the current HIP device.  Fails with PSD_ERR_DEVICE when no gfx950
+ * device is present, PSD_ERR_SHAPE / PSD_ERR_UNSUPPORTED on layouts the kernels do not
+ * cover (bf16 needs d_head in {64, 128} and d_model, d_ffn multiples of 64; fp32 takes
+ * any even d_head). */
+int32_t psd_create(const psd_model_config *cfg, const psd_weights *w, psd_handle **out);
+int32_t psd_destroy(psd_handle *h);
+
+/* Bytes of device workspace that a forward over up to max_seqs sequences of length N with
+ * block length L needs (psd_verify_accept and psd_decode_block run max_seqs = B*K).
+ * Negative status on bad arguments. */
+int64_t psd_workspace_bytes(const psd_model_config *cfg, int32_t max_seqs, int32_t N, int32_t L);
+
+/* Prefix chain: node k speculates on the k*width most confident residual positions. */
+int32_t psd_graph_chain(int32_t K, int32_t width, psd_graph *out);
+
+/* Model call (Sec. 3.1; Alg. 1 stage 1 and the batched pass of stage 3): forward S
+ * sequences over all N positions with bidirectional attention, then on the L block rows of
+ * each the top-1 token x_hat = argmax_v p(v) and confidence c = max_v p(v), p the softmax
+ * of the logits over the vocabulary without [M].  Ties go to the lowest token id.  The
+ * logits are reduced on the fly and never stored.
+ *   tokens device int32 [S, N] (read); top1 device int32 [S, L], conf device float [S, L]
+ *   (written); ws device, ws_bytes >= psd_workspace_bytes(cfg, S, N, L). */
+int32_t psd_forward_confidence(psd_handle *h, const int32_t *tokens, int32_t S, int32_t N,
+                               int32_t block_start, int32_t L, int32_t *top1, float *conf,
+                               void *ws, int64_t ws_bytes, void *stream);
+
+/* Debug companion of psd_forward_confidence: writes the raw block logits
+ * logit_scale * (y W_lm^T), [M] column included, as float [S*L, vocab] (device).  Only for
+ * numeric parity checks; the decode path never materialises logits. */
+int32_t psd_forward_logits(psd_handle *h, const int32_t *tokens, int32_t S, int32_t N,
+                           int32_t block_start, int32_t L, float *logits,
+                           void *ws, int64_t ws_bytes, void *stream);
+
+/* Debug switch for numeric cross-checks: bit 0 runs the layer contractions, bit 1 the
+ * attention, bit 2 the LM-head on the plain (non-MFMA) kernels.  0 (default) = MFMA path. */
+int32_t psd_debug_set_plain(psd_handle *h, int32_t mask);
+
+/* Stage 1 commit (Eq. 1): applies pi to every sequence in place.
+ *   tokens device int32 [B, N] (updated); top1/conf device [B, L] (read);
+ *   transfer_mask device uint8 [B, L] (1 where committed); n_selected device int32 [B]. */
+int32_t psd_select_unmask(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_t block_start,
+                          int32_t L, const int32_t *top1, const float *conf, const psd_policy *policy,
+                          uint8_t *transfer_mask, int32_t *n_selected, void *stream);
+
+/* Stage 2 (Eq. 2): from the post-commit tokens and the step-t (top1, conf): the
+ * speculative ordering sigma (block-local positions, confidence descending, ties lower
+ * position first, padded with -1), the residual count m, and the K drafts.
+ *   tokens device int32 [B, N] (read); sigma device int32 [B, L]; m device int32 [B];
+ *   drafts device int32 [B, K, N] (written). */
+int32_t psd_build_drafts(psd_handle *h, const int32_t *tokens, int32_t B, int32_t N, int32_t block_start,
+                         int32_t L, const int32_t *top1, const float *conf, const psd_graph *graph,
+                         int32_t *sigma, int32_t *m, int32_t *drafts, void *stream);
+
+/* Hierarchical acceptance and state advance on given verifier outputs (Alg. 1 stage 3
+ * without the model call).  Node k is accepted iff some accepted p with S_p a strict
+ * subset of S_k has, on every position i of S_k \ S_p, v_top1[p, i] equal to the drafted
+ * token and i committed by pi applied to p's verifier output.  k* is the accepted node
+ * with the largest S (ties: lowest index); tokens <- draft k*, then pi is applied once more
+ * on k*'s verifier output.  Sequences with m == 0 are left untouched (k_star = 0).
+ *   tokens device int32 [B, N] (written); drafts device int32 [B, K, N]; sigma device
+ *   [B, L]; m device [B]; v_top1 / v_conf device [B, K, L]; k_star device int32 [B];
+ *   accepted device uint8 [B, K]. */
+int32_t psd_accept(psd_handle *h, int32_t *tokens, const int32_t *drafts, int32_t B, int32_t N,
+                   int32_t block_start, int32_t L, const int32_t *sigma, const int32_t *m,
+                   const psd_graph *graph, const psd_policy *policy, const int32_t *v_top1,
+                   const float *v_conf, int32_t *k_star, uint8_t *accepted, void *stream);
+
+/* Stage 3 whole (Sec. 3.2): one batched forward over the B*K drafts (one invocation),
+ * then psd_accept on its outputs, which are also returned in v_top1 / v_conf [B, K, L].
+ * ws_bytes >= psd_workspace_bytes(cfg, B*K, N, L). */
+int32_t psd_verify_accept(psd_handle *h, int32_t *tokens, const int32_t *drafts, int32_t B, int32_t N,
+                          int32_t block_start, int32_t L, const int32_t *sigma, const int32_t *m,
+                          const psd_graph *graph, const psd_policy *policy, int32_t *k_star,
+                          uint8_t *accepted, int32_t *v_top1, float *v_conf,
+                          void *ws, int64_t ws_bytes, void *stream);
+
+/* Alg. 1 on the block [block_start, block_start+L) of B sequences, until none of them has
+ * a masked position left in it.  Sequences that finish early drop out of the model calls.
+ * Blocks until done.  tokens device int32 [B, N] (updated in place);
+ * stats host psd_stats [B], counters are ADDED to what it holds (zero it first);
+ * ws_bytes >= psd_workspace_bytes(cfg, B*K, N, L) + psd_decode_scratch_bytes(B, N, L, K). */
+int32_t psd_decode_block(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_t block_start,
+                         int32_t L, const psd_policy *policy, const psd_graph *graph, psd_stats *stats,
+                         void *ws, int64_t ws_bytes, void *stream);
+int64_t psd_decode_scratch_bytes(int32_t B, int32_t N, int32_t L, int32_t K);
+
+/* Per-handle timing of the last psd_decode_block / forward calls is not kept; callers time
+ * with HIP events on `stream`.  For roofline accounting the library reports the algorithmic
+ * work of one forward: FLOPs of the layer contractions, of attention, and of the LM-head,
+ * and the bytes the LM-head pass must move (weights once + hidden rows + outputs). */
+typedef struct {
+    double gemm_flops, attn_flops, head_flops, head_bytes, weight_bytes;
+} psd_work;
+int32_t psd_forward_work(const psd_model_config *cfg, int32_t S, int32_t N, int32_t L, psd_work *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PSD_H */

@@ -49,6 +49,10 @@ class Policy:
     k_min: int = 1
     k_max: int = 0        # 0 = unbounded
 
+    def __post_init__(self):
+        # confidences are fp32 values; the threshold is compared in that same precision
+        object.__setattr__(self, "tau", float(np.float32(self.tau)))
+
 
 @dataclass(frozen=True)
 class Graph:

@@ -1,0 +1,375 @@
+"""ctypes binding of libpsd.so: same call names as include/psd.h, torch tensors in and out.
+
+Nothing here computes: tensors are allocated with torch, their device pointers and the
+current HIP stream are handed to the library, and every step of the PSD path runs in its
+kernels.  Loading fails loudly when the library has not been built; there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+MAX_NODES = 32
+MAX_BLOCK = 64
+HIST = MAX_NODES + MAX_BLOCK + 1
+
+
+class PsdError(RuntimeError):
+    pass
+
+
+class _Config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("d_head", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32), ("mask_id", C.c_int32),
+                ("rms_eps", C.c_float), ("qkv_bias", C.c_int32), ("dtype", C.c_int32), ("logit_scale", C.c_float),
+                ("max_seq", C.c_int32)]
+
+
+_PP = C.POINTER(C.c_void_p)
+
+
+class _Weights(C.Structure):
+    _fields_ = [("tok_emb", C.c_void_p), ("final_norm", C.c_void_p), ("lm_head", C.c_void_p), ("rope_cos", C.c_void_p),
+                ("rope_sin", C.c_void_p), ("attn_norm", _PP), ("wq", _PP), ("wk", _PP), ("wv", _PP), ("bq", _PP),
+                ("bk", _PP), ("bv", _PP), ("wo", _PP), ("ffn_norm", _PP), ("w_gate", _PP), ("w_up", _PP), ("w_down", _PP)]
+
+
+class _Policy(C.Structure):
+    _fields_ = [("tau", C.c_float), ("k_min", C.c_int32), ("k_max", C.c_int32)]
+
+
+class _Graph(C.Structure):
+    _fields_ = [("K", C.c_int32), ("rank_set", C.c_uint64 * MAX_NODES)]
+
+
+class _Stats(C.Structure):
+    _fields_ = [("invocations", C.c_int64), ("tokens_policy", C.c_int64), ("tokens_draft", C.c_int64),
+                ("tokens_postverify", C.c_int64), ("depth_hist", C.c_int32 * HIST)]
+
+
+class _Work(C.Structure):
+    _fields_ = [("gemm_flops", C.c_double), ("attn_flops", C.c_double), ("head_flops", C.c_double),
+                ("head_bytes", C.c_double), ("weight_bytes", C.c_double)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "libpsd.so")
+
+
+def load_library():
+    """Loads libpsd.so (built by paper_2605_15609_amd/build.py).  Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise PsdError(f"{path} not found: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    lib = C.CDLL(path)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    sig = {
+        "psd_status_string": (C.c_char_p, [i32]),
+        "psd_last_error": (C.c_char_p, []),
+        "psd_create": (i32, [C.POINTER(_Config), C.POINTER(_Weights), C.POINTER(vp)]),
+        "psd_destroy": (i32, [vp]),
+        "psd_debug_set_plain": (i32, [vp, i32]),
+        "psd_workspace_bytes": (i64, [C.POINTER(_Config), i32, i32, i32]),
+        "psd_decode_scratch_bytes": (i64, [i32, i32, i32, i32]),
+        "psd_graph_chain": (i32, [i32, i32, C.POINTER(_Graph)]),
+        "psd_forward_confidence": (i32, [vp, vp, i32, i32, i32, i32, vp, vp, vp, i64, vp]),
+        "psd_forward_logits": (i32, [vp, vp, i32, i32, i32, i32, vp, vp, i64, vp]),
+        "psd_select_unmask": (i32, [vp, vp, i32, i32, i32, i32, vp, vp, C.POINTER(_Policy), vp, vp, vp]),
+        "psd_build_drafts": (i32, [vp, vp, i32, i32, i32, i32, vp, vp, C.POINTER(_Graph), vp, vp, vp, vp]),
+        "psd_accept": (i32, [vp, vp, vp, i32, i32, i32, i32, vp, vp, C.POINTER(_Graph), C.POINTER(_Policy), vp, vp, vp,
+                             vp, vp]),
+        "psd_verify_accept": (i32, [vp, vp, vp, i32, i32, i32, i32, vp, vp, C.POINTER(_Graph), C.POINTER(_Policy), vp,
+                                    vp, vp, vp, vp, i64, vp]),
+        "psd_decode_block": (i32, [vp, vp, i32, i32, i32, i32, C.POINTER(_Policy), C.POINTER(_Graph), C.POINTER(_Stats),
+                                   vp, i64, vp]),
+        "psd_forward_work": (i32, [C.POINTER(_Config), i32, i32, i32, C.POINTER(_Work)]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc < 0:
+        lib = load_library()
+        raise PsdError(f"{lib.psd_status_string(int(rc)).decode()} ({int(rc)}): {lib.psd_last_error().decode()}")
+    return rc
+
+
+@dataclass(frozen=True)
+class Policy:
+    tau: float = 0.9
+    k_min: int = 1
+    k_max: int = 0
+
+    def c(self) -> _Policy:
+        return _Policy(float(np.float32(self.tau)), int(self.k_min), int(self.k_max))
+
+
+@dataclass(frozen=True)
+class Graph:
+    rank_sets: tuple      # K ints, bit r set <-> rank r speculated; rank_sets[0] == 0
+
+    @property
+    def K(self) -> int:
+        return len(self.rank_sets)
+
+    def c(self) -> _Graph:
+        g = _Graph()
+        g.K = self.K
+        for k, bits in enumerate(self.rank_sets):
+            g.rank_set[k] = int(bits)
+        return g
+
+
+def chain_graph(K: int, width: int = 1) -> Graph:
+    g = _Graph()
+    _check(load_library().psd_graph_chain(K, width, C.byref(g)))
+    return Graph(tuple(int(g.rank_set[k]) for k in range(g.K)))
+
+
+@dataclass
+class Stats:
+    invocations: int = 0
+    tokens_policy: int = 0
+    tokens_draft: int = 0
+    tokens_postverify: int = 0
+    depth_hist: List[int] = field(default_factory=lambda: [0] * HIST)
+
+    @property
+    def tokens(self) -> int:
+        return self.tokens_policy + self.tokens_draft + self.tokens_postverify
+
+    @property
+    def tpf(self) -> float:
+        return self.tokens / max(1, self.invocations)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev_i32(t, device):
+    return torch.as_tensor(np.ascontiguousarray(t, dtype=np.int32) if not torch.is_tensor(t) else t, device=device) \
+        .to(torch.int32).contiguous()
+
+
+class Model:
+    """Device-resident weights plus the library handle.  ``Model.from_host(host_model)``
+    uploads a psd_inputs.HostModel; matrices go up in the model dtype, the rest as fp32."""
+
+    def __init__(self, shape, max_seq: int, tensors: dict, layer_tensors: list, device="cuda:0"):
+        self.lib = load_library()
+        self.shape = shape
+        self.max_seq = int(max_seq)
+        self.device = torch.device(device)
+        self._tensors = tensors            # keep alive: the handle borrows the pointers
+        self._layers = layer_tensors
+        self._ws = None
+        cfg = _Config(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.d_head, shape.d_ffn,
+                      shape.vocab, shape.mask_id, shape.rms_eps, int(shape.qkv_bias), 1 if shape.dtype == "bf16" else 0,
+                      float(shape.logit_scale), self.max_seq)
+        self.cfg = cfg
+        w = _Weights()
+        for name in ("tok_emb", "final_norm", "lm_head", "rope_cos", "rope_sin"):
+            setattr(w, name, tensors[name].data_ptr())
+        self._arrays = {}
+        for name in ("attn_norm", "wq", "wk", "wv", "bq", "bk", "bv", "wo", "ffn_norm", "w_gate", "w_up", "w_down"):
+            if layer_tensors[0].get(name) is None:
+                setattr(w, name, None)
+                continue
+            arr = (C.c_void_p * shape.n_layers)(*[lt[name].data_ptr() for lt in layer_tensors])
+            self._arrays[name] = arr
+            setattr(w, name, C.cast(arr, _PP))
+        handle = C.c_void_p()
+        with torch.cuda.device(self.device):
+            _check(self.lib.psd_create(C.byref(cfg), C.byref(w), C.byref(handle)))
+        self.handle = handle
+
+    @classmethod
+    def from_host(cls, host_model, device="cuda:0") -> "Model":
+        shape = host_model.shape
+        mat_dtype = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+        dev = torch.device(device)
+
+        def up(a, dtype):
+            return torch.from_numpy(np.ascontiguousarray(a)).to(device=dev, dtype=dtype).contiguous()
+
+        tensors = {"tok_emb": up(host_model.tok_emb, mat_dtype), "lm_head": up(host_model.lm_head, mat_dtype),
+                   "final_norm": up(host_model.final_norm, torch.float32),
+                   "rope_cos": up(host_model.rope_cos, torch.float32), "rope_sin": up(host_model.rope_sin, torch.float32)}
+        layers = []
+        for lw in host_model.layers:
+            lt = {}
+            for k, v in lw.items():
+                if v is None:
+                    lt[k] = None
+                else:
+                    lt[k] = up(v, mat_dtype if v.ndim == 2 else torch.float32)
+            layers.append(lt)
+        return cls(shape, host_model.max_seq, tensors, layers, device)
+
+    def close(self):
+        if getattr(self, "handle", None):
+            self.lib.psd_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_plain(self, mask: int):
+        _check(self.lib.psd_debug_set_plain(self.handle, int(mask)))
+
+    def workspace(self, n_bytes: int) -> torch.Tensor:
+        if self._ws is None or self._ws.numel() < n_bytes:
+            self._ws = None
+            self._ws = torch.empty(int(n_bytes) + 256, dtype=torch.uint8, device=self.device)
+        return self._ws
+
+    def forward_ws(self, S: int, N: int, L: int, extra: int = 0):
+        need = self.lib.psd_workspace_bytes(C.byref(self.cfg), S, N, L)
+        _check(need)
+        ws = self.workspace(need + extra)
+        return ws, need + extra
+
+
+def forward_work(model: Model, S: int, N: int, L: int) -> dict:
+    w = _Work()
+    _check(model.lib.psd_forward_work(C.byref(model.cfg), S, N, L, C.byref(w)))
+    return {k: getattr(w, k) for k, _ in _Work._fields_}
+
+
+# ------------------------------------------------------------------------------------------
+# the calls of include/psd.h
+# ------------------------------------------------------------------------------------------
+
+
+def psd_forward_confidence(model: Model, tokens: torch.Tensor, block_start: int, L: int):
+    """tokens int32 [S, N] on the device -> (top1 int32 [S, L], conf float32 [S, L])."""
+    assert tokens.dtype == torch.int32 and tokens.is_contiguous() and tokens.dim() == 2
+    S, N = tokens.shape
+    top1 = torch.empty((S, L), dtype=torch.int32, device=tokens.device)
+    conf = torch.empty((S, L), dtype=torch.float32, device=tokens.device)
+    ws, nb = model.forward_ws(S, N, L)
+    _check(model.lib.psd_forward_confidence(model.handle, _ptr(tokens), S, N, block_start, L, _ptr(top1), _ptr(conf),
+                                            _ptr(ws), nb, _stream()))
+    return top1, conf
+
+
+def psd_forward_logits(model: Model, tokens: torch.Tensor, block_start: int, L: int) -> torch.Tensor:
+    assert tokens.dtype == torch.int32 and tokens.is_contiguous() and tokens.dim() == 2
+    S, N = tokens.shape
+    logits = torch.empty((S * L, model.shape.vocab), dtype=torch.float32, device=tokens.device)
+    ws, nb = model.forward_ws(S, N, L)
+    _check(model.lib.psd_forward_logits(model.handle, _ptr(tokens), S, N, block_start, L, _ptr(logits), _ptr(ws), nb,
+                                        _stream()))
+    return logits
+
+
+def psd_select_unmask(model: Model, tokens: torch.Tensor, block_start: int, L: int, top1: torch.Tensor,
+                      conf: torch.Tensor, policy: Policy):
+    """In place on tokens [B, N]; returns (transfer_mask uint8 [B, L], n_selected int32 [B])."""
+    B, N = tokens.shape
+    tm = torch.empty((B, L), dtype=torch.uint8, device=tokens.device)
+    ns = torch.empty((B,), dtype=torch.int32, device=tokens.device)
+    pol = policy.c()
+    _check(model.lib.psd_select_unmask(model.handle, _ptr(tokens), B, N, block_start, L, _ptr(top1), _ptr(conf),
+                                       C.byref(pol), _ptr(tm), _ptr(ns), _stream()))
+    return tm, ns
+
+
+def psd_build_drafts(model: Model, tokens: torch.Tensor, block_start: int, L: int, top1: torch.Tensor,
+                     conf: torch.Tensor, graph: Graph):
+    """-> (sigma int32 [B, L], m int32 [B], drafts int32 [B, K, N])."""
+    B, N = tokens.shape
+    sigma = torch.empty((B, L), dtype=torch.int32, device=tokens.device)
+    m = torch.empty((B,), dtype=torch.int32, device=tokens.device)
+    drafts = torch.empty((B, graph.K, N), dtype=torch.int32, device=tokens.device)
+    g = graph.c()
+    _check(model.lib.psd_build_drafts(model.handle, _ptr(tokens), B, N, block_start, L, _ptr(top1), _ptr(conf),
+                                      C.byref(g), _ptr(sigma), _ptr(m), _ptr(drafts), _stream()))
+    return sigma, m, drafts
+
+
+def psd_accept(model: Model, tokens: torch.Tensor, drafts: torch.Tensor, block_start: int, L: int, sigma: torch.Tensor,
+               m: torch.Tensor, graph: Graph, policy: Policy, v_top1: torch.Tensor, v_conf: torch.Tensor):
+    """In place on tokens; returns (k_star int32 [B], accepted uint8 [B, K])."""
+    B, N = tokens.shape
+    k_star = torch.empty((B,), dtype=torch.int32, device=tokens.device)
+    accepted = torch.empty((B, graph.K), dtype=torch.uint8, device=tokens.device)
+    g, pol = graph.c(), policy.c()
+    _check(model.lib.psd_accept(model.handle, _ptr(tokens), _ptr(drafts), B, N, block_start, L, _ptr(sigma), _ptr(m),
+                                C.byref(g), C.byref(pol), _ptr(v_top1), _ptr(v_conf), _ptr(k_star), _ptr(accepted),
+                                _stream()))
+    return k_star, accepted
+
+
+def psd_verify_accept(model: Model, tokens: torch.Tensor, drafts: torch.Tensor, block_start: int, L: int,
+                      sigma: torch.Tensor, m: torch.Tensor, graph: Graph, policy: Policy):
+    """One batched forward over the drafts + acceptance; in place on tokens.
+    Returns (k_star, accepted, v_top1 [B, K, L], v_conf [B, K, L])."""
+    B, N = tokens.shape
+    K = graph.K
+    k_star = torch.empty((B,), dtype=torch.int32, device=tokens.device)
+    accepted = torch.empty((B, K), dtype=torch.uint8, device=tokens.device)
+    v_top1 = torch.empty((B, K, L), dtype=torch.int32, device=tokens.device)
+    v_conf = torch.empty((B, K, L), dtype=torch.float32, device=tokens.device)
+    g, pol = graph.c(), policy.c()
+    ws, nb = model.forward_ws(B * K, N, L)
+    _check(model.lib.psd_verify_accept(model.handle, _ptr(tokens), _ptr(drafts), B, N, block_start, L, _ptr(sigma),
+                                       _ptr(m), C.byref(g), C.byref(pol), _ptr(k_star), _ptr(accepted), _ptr(v_top1),
+                                       _ptr(v_conf), _ptr(ws), nb, _stream()))
+    return k_star, accepted, v_top1, v_conf
+
+
+def psd_decode_block(model: Model, tokens: torch.Tensor, block_start: int, L: int, policy: Policy, graph: Graph,
+                     stats: Optional[Sequence[Stats]] = None) -> List[Stats]:
+    """Alg. 1 on one block of every sequence of tokens [B, N], in place.  Blocks until done."""
+    B, N = tokens.shape
+    K = graph.K
+    extra = model.lib.psd_decode_scratch_bytes(B, N, L, K)
+    _check(extra)
+    ws, nb = model.forward_ws(B * K, N, L, extra=extra)
+    cstats = (_Stats * B)()
+    g, pol = graph.c(), policy.c()
+    _check(model.lib.psd_decode_block(model.handle, _ptr(tokens), B, N, block_start, L, C.byref(pol), C.byref(g), cstats,
+                                      _ptr(ws), nb, _stream()))
+    out = list(stats) if stats is not None else [Stats() for _ in range(B)]
+    for b in range(B):
+        out[b].invocations += cstats[b].invocations
+        out[b].tokens_policy += cstats[b].tokens_policy
+        out[b].tokens_draft += cstats[b].tokens_draft
+        out[b].tokens_postverify += cstats[b].tokens_postverify
+        for i in range(HIST):
+            out[b].depth_hist[i] += cstats[b].depth_hist[i]
+    return out
+
+
+def decode(model: Model, tokens: torch.Tensor, prompt_len: int, L: int, policy: Policy, graph: Graph) -> List[Stats]:
+    """Semi-autoregressive generation: psd_decode_block on each block, left to right."""
+    B, N = tokens.shape
+    stats = [Stats() for _ in range(B)]
+    for block_start in range(prompt_len, N, L):
+        stats = psd_decode_block(model, tokens, block_start, min(L, N - block_start), policy, graph, stats)
+    return stats

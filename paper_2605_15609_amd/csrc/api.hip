@@ -1,0 +1,406 @@
+// C ABI of libpsd: argument checks, handle management and the Alg. 1 block loop.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "psd_internal.h"
+
+static thread_local char g_err[512] = "";
+
+void psd_set_error(const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+namespace {
+
+__global__ void count_masks_kernel(const int32_t *__restrict__ tokens, int N, int block_start, int L, int32_t mask_id,
+                                   int32_t *__restrict__ n_left) {
+    const int b = blockIdx.x, j = threadIdx.x;
+    const bool live = j < L && tokens[(int64_t)b * N + block_start + j] == mask_id;
+    const int n = __popcll(__ballot(live));
+    if (j == 0) n_left[b] = n;
+}
+
+__global__ void fill_i32_kernel(int32_t *p, int64_t n, int32_t v) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+int32_t check_cfg(const psd_model_config *c) {
+    if (!c) PSD_FAIL(PSD_ERR_INVALID_ARG, "config is NULL");
+    if (c->n_layers < 1 || c->d_model < 1 || c->n_heads < 1 || c->n_kv_heads < 1 || c->d_head < 2 || c->d_ffn < 1 ||
+        c->vocab < 2 || c->max_seq < 1)
+        PSD_FAIL(PSD_ERR_SHAPE, "non-positive model dimension");
+    if (c->n_heads % c->n_kv_heads) PSD_FAIL(PSD_ERR_SHAPE, "n_heads must be a multiple of n_kv_heads");
+    if (c->d_head % 2) PSD_FAIL(PSD_ERR_SHAPE, "d_head must be even (rotary pairs)");
+    if (c->mask_id < 0 || c->mask_id >= c->vocab) PSD_FAIL(PSD_ERR_SHAPE, "mask_id outside the embedding table");
+    if (c->dtype != PSD_DTYPE_FP32 && c->dtype != PSD_DTYPE_BF16) PSD_FAIL(PSD_ERR_UNSUPPORTED, "dtype %d", c->dtype);
+    if (c->dtype == PSD_DTYPE_BF16) {
+        if (c->d_head != 64 && c->d_head != 128) PSD_FAIL(PSD_ERR_UNSUPPORTED, "bf16 path needs d_head 64 or 128");
+        if (c->d_model % 64 || c->d_ffn % 64) PSD_FAIL(PSD_ERR_UNSUPPORTED, "bf16 path needs d_model, d_ffn multiples of 64");
+    }
+    return PSD_OK;
+}
+
+int32_t check_block(const psd_handle *h, int B, int N, int block_start, int L) {
+    if (!h) PSD_FAIL(PSD_ERR_INVALID_ARG, "handle is NULL");
+    if (B < 1) PSD_FAIL(PSD_ERR_SHAPE, "batch %d", B);
+    if (N < 1 || N > h->cfg.max_seq) PSD_FAIL(PSD_ERR_SHAPE, "sequence length %d outside 1..max_seq=%d", N, h->cfg.max_seq);
+    if (L < 1 || L > PSD_MAX_BLOCK) PSD_FAIL(PSD_ERR_SHAPE, "block length %d outside 1..%d", L, PSD_MAX_BLOCK);
+    if (block_start < 0 || block_start + L > N) PSD_FAIL(PSD_ERR_SHAPE, "block [%d, %d) outside the sequence of %d", block_start,
+                                                         block_start + L, N);
+    return PSD_OK;
+}
+
+int32_t check_graph(const psd_graph *g, GraphArg *out) {
+    if (!g) PSD_FAIL(PSD_ERR_INVALID_ARG, "graph is NULL");
+    if (g->K < 1 || g->K > PSD_MAX_NODES) PSD_FAIL(PSD_ERR_SHAPE, "graph with %d nodes (1..%d)", g->K, PSD_MAX_NODES);
+    if (g->rank_set[0] != 0) PSD_FAIL(PSD_ERR_INVALID_ARG, "node 0 must be the root (empty rank set)");
+    out->K = g->K;
+    for (int k = 0; k < PSD_MAX_NODES; ++k) out->rank_set[k] = k < g->K ? g->rank_set[k] : 0;
+    return PSD_OK;
+}
+
+int32_t check_policy(const psd_policy *p) {
+    if (!p) PSD_FAIL(PSD_ERR_INVALID_ARG, "policy is NULL");
+    if (p->k_min < 0 || p->k_max < 0) PSD_FAIL(PSD_ERR_INVALID_ARG, "negative k_min / k_max");
+    if (p->tau != p->tau) PSD_FAIL(PSD_ERR_INVALID_ARG, "tau is NaN");
+    return PSD_OK;
+}
+
+#define CHECK(expr)                  \
+    do {                             \
+        int32_t rc_ = (expr);        \
+        if (rc_ != PSD_OK) return rc_; \
+    } while (0)
+
+struct DecodeScratch {
+    int64_t top1, conf, sigma, m, n_left, drafts, v_top1, v_conf, k_star, accepted, devstats, rows, total;
+};
+
+DecodeScratch plan_decode(int64_t B, int64_t N, int64_t L, int64_t K) {
+    DecodeScratch s;
+    int64_t off = 0;
+    auto take = [&](int64_t bytes) {
+        const int64_t o = off;
+        off += align_up(bytes, 256);
+        return o;
+    };
+    s.top1 = take(B * L * 4);
+    s.conf = take(B * L * 4);
+    s.sigma = take(B * L * 4);
+    s.m = take(B * 4);
+    s.n_left = take(B * 4);
+    s.drafts = take(B * K * N * 4);
+    s.v_top1 = take(B * K * L * 4);
+    s.v_conf = take(B * K * L * 4);
+    s.k_star = take(B * 4);
+    s.accepted = take(B * K);
+    s.devstats = take(B * PSD_DEVSTAT_WORDS * 4);
+    s.rows = take(B * K * 4);
+    s.total = off;
+    return s;
+}
+
+}   // namespace
+
+extern "C" {
+
+const char *psd_status_string(int32_t status) {
+    switch (status) {
+        case PSD_OK: return "ok";
+        case PSD_ERR_INVALID_ARG: return "invalid argument";
+        case PSD_ERR_SHAPE: return "shape out of range";
+        case PSD_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case PSD_ERR_DEVICE: return "HIP device error";
+        case PSD_ERR_UNSUPPORTED: return "unsupported configuration";
+        default: return "unknown status";
+    }
+}
+
+const char *psd_last_error(void) { return g_err; }
+
+int32_t psd_create(const psd_model_config *cfg, const psd_weights *w, psd_handle **out) {
+    if (!out) PSD_FAIL(PSD_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    CHECK(check_cfg(cfg));
+    if (!w) PSD_FAIL(PSD_ERR_INVALID_ARG, "weights is NULL");
+    if (!w->tok_emb || !w->final_norm || !w->lm_head || !w->rope_cos || !w->rope_sin || !w->attn_norm || !w->wq || !w->wk ||
+        !w->wv || !w->wo || !w->ffn_norm || !w->w_gate || !w->w_up || !w->w_down)
+        PSD_FAIL(PSD_ERR_INVALID_ARG, "a weight pointer is NULL");
+    if (cfg->qkv_bias && (!w->bq || !w->bk || !w->bv)) PSD_FAIL(PSD_ERR_INVALID_ARG, "qkv_bias set but a bias array is NULL");
+    int dev = 0;
+    PSD_HIP(hipGetDevice(&dev));
+    hipDeviceProp_t prop;
+    PSD_HIP(hipGetDeviceProperties(&prop, dev));
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+        PSD_FAIL(PSD_ERR_DEVICE, "device %d is %s; this library is built for gfx950 only", dev, prop.gcnArchName);
+    psd_handle *h = new (std::nothrow) psd_handle();
+    if (!h) PSD_FAIL(PSD_ERR_DEVICE, "out of host memory");
+    h->cfg = *cfg;
+    h->tok_emb = w->tok_emb;
+    h->lm_head = w->lm_head;
+    h->final_norm = w->final_norm;
+    h->rope_cos = w->rope_cos;
+    h->rope_sin = w->rope_sin;
+    h->device = dev;
+    h->plain_mask = 0;
+    h->layers.resize(cfg->n_layers);
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        psd_handle::Layer &L = h->layers[l];
+        L.attn_norm = w->attn_norm[l];
+        L.ffn_norm = w->ffn_norm[l];
+        L.wq = w->wq[l];
+        L.wk = w->wk[l];
+        L.wv = w->wv[l];
+        L.wo = w->wo[l];
+        L.w_gate = w->w_gate[l];
+        L.w_up = w->w_up[l];
+        L.w_down = w->w_down[l];
+        L.bq = cfg->qkv_bias ? w->bq[l] : nullptr;
+        L.bk = cfg->qkv_bias ? w->bk[l] : nullptr;
+        L.bv = cfg->qkv_bias ? w->bv[l] : nullptr;
+        if (!L.attn_norm || !L.ffn_norm || !L.wq || !L.wk || !L.wv || !L.wo || !L.w_gate || !L.w_up || !L.w_down ||
+            (cfg->qkv_bias && (!L.bq || !L.bk || !L.bv))) {
+            delete h;
+            PSD_FAIL(PSD_ERR_INVALID_ARG, "layer %d has a NULL weight pointer", l);
+        }
+    }
+    h->host_counts_cap = 1 << 16;
+    hipError_t e = hipHostMalloc((void **)&h->host_counts, sizeof(int32_t) * h->host_counts_cap, hipHostMallocDefault);
+    if (e != hipSuccess) {
+        delete h;
+        PSD_FAIL(PSD_ERR_DEVICE, "hipHostMalloc: %s", hipGetErrorString(e));
+    }
+    *out = h;
+    return PSD_OK;
+}
+
+int32_t psd_destroy(psd_handle *h) {
+    if (!h) return PSD_OK;
+    if (h->host_counts) (void)hipHostFree(h->host_counts);
+    delete h;
+    return PSD_OK;
+}
+
+int32_t psd_debug_set_plain(psd_handle *h, int32_t mask) {
+    if (!h) PSD_FAIL(PSD_ERR_INVALID_ARG, "handle is NULL");
+    h->plain_mask = mask;
+    return PSD_OK;
+}
+
+int64_t psd_workspace_bytes(const psd_model_config *cfg, int32_t max_seqs, int32_t N, int32_t L) {
+    int32_t rc = check_cfg(cfg);
+    if (rc != PSD_OK) return rc;
+    if (max_seqs < 1 || N < 1 || L < 1 || L > PSD_MAX_BLOCK || L > N) {
+        psd_set_error("psd_workspace_bytes: bad max_seqs/N/L %d/%d/%d", max_seqs, N, L);
+        return PSD_ERR_SHAPE;
+    }
+    return plan_forward(*cfg, max_seqs, N, L).total;
+}
+
+int64_t psd_decode_scratch_bytes(int32_t B, int32_t N, int32_t L, int32_t K) {
+    if (B < 1 || N < 1 || L < 1 || K < 1) {
+        psd_set_error("psd_decode_scratch_bytes: bad B/N/L/K");
+        return PSD_ERR_SHAPE;
+    }
+    return plan_decode(B, N, L, K).total;
+}
+
+int32_t psd_graph_chain(int32_t K, int32_t width, psd_graph *out) {
+    if (!out) PSD_FAIL(PSD_ERR_INVALID_ARG, "out is NULL");
+    if (K < 1 || K > PSD_MAX_NODES || width < 1) PSD_FAIL(PSD_ERR_SHAPE, "chain with K=%d width=%d", K, width);
+    if ((int64_t)(K - 1) * width > 64) PSD_FAIL(PSD_ERR_SHAPE, "chain deeper than 64 ranks");
+    memset(out, 0, sizeof(*out));
+    out->K = K;
+    for (int k = 0; k < K; ++k) {
+        const int n = k * width;
+        out->rank_set[k] = n >= 64 ? ~0ull : ((1ull << n) - 1ull);
+    }
+    return PSD_OK;
+}
+
+int32_t psd_forward_confidence(psd_handle *h, const int32_t *tokens, int32_t S, int32_t N, int32_t block_start, int32_t L,
+                               int32_t *top1, float *conf, void *ws, int64_t ws_bytes, void *stream) {
+    CHECK(check_block(h, S, N, block_start, L));
+    if (!tokens || !top1 || !conf) PSD_FAIL(PSD_ERR_INVALID_ARG, "NULL tokens/top1/conf");
+    hipStream_t st = (hipStream_t)stream;
+    CHECK(run_forward_hidden(h, tokens, nullptr, S, N, block_start, L, ws, ws_bytes, st));
+    return run_head_confidence(h, tokens, nullptr, S, N, block_start, L, top1, conf, nullptr, ws, st);
+}
+
+int32_t psd_forward_logits(psd_handle *h, const int32_t *tokens, int32_t S, int32_t N, int32_t block_start, int32_t L,
+                           float *logits, void *ws, int64_t ws_bytes, void *stream) {
+    CHECK(check_block(h, S, N, block_start, L));
+    if (!tokens || !logits) PSD_FAIL(PSD_ERR_INVALID_ARG, "NULL tokens/logits");
+    hipStream_t st = (hipStream_t)stream;
+    CHECK(run_forward_hidden(h, tokens, nullptr, S, N, block_start, L, ws, ws_bytes, st));
+    return run_head_logits(h, S, N, L, logits, ws, st);
+}
+
+int32_t psd_select_unmask(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_t block_start, int32_t L,
+                          const int32_t *top1, const float *conf, const psd_policy *policy, uint8_t *transfer_mask,
+                          int32_t *n_selected, void *stream) {
+    CHECK(check_block(h, B, N, block_start, L));
+    CHECK(check_policy(policy));
+    if (!tokens || !top1 || !conf) PSD_FAIL(PSD_ERR_INVALID_ARG, "NULL tokens/top1/conf");
+    launch_select_unmask(tokens, B, N, block_start, L, top1, conf, *policy, h->cfg.mask_id, transfer_mask, n_selected,
+                         nullptr, nullptr, (hipStream_t)stream);
+    PSD_HIP(hipGetLastError());
+    return PSD_OK;
+}
+
+int32_t psd_build_drafts(psd_handle *h, const int32_t *tokens, int32_t B, int32_t N, int32_t block_start, int32_t L,
+                         const int32_t *top1, const float *conf, const psd_graph *graph, int32_t *sigma, int32_t *m,
+                         int32_t *drafts, void *stream) {
+    CHECK(check_block(h, B, N, block_start, L));
+    GraphArg g;
+    CHECK(check_graph(graph, &g));
+    if (!tokens || !top1 || !conf || !sigma || !m || !drafts) PSD_FAIL(PSD_ERR_INVALID_ARG, "NULL argument");
+    launch_build_drafts(tokens, B, N, block_start, L, top1, conf, g, h->cfg.mask_id, sigma, m, drafts, (hipStream_t)stream);
+    PSD_HIP(hipGetLastError());
+    return PSD_OK;
+}
+
+int32_t psd_accept(psd_handle *h, int32_t *tokens, const int32_t *drafts, int32_t B, int32_t N, int32_t block_start,
+                   int32_t L, const int32_t *sigma, const int32_t *m, const psd_graph *graph, const psd_policy *policy,
+                   const int32_t *v_top1, const float *v_conf, int32_t *k_star, uint8_t *accepted, void *stream) {
+    CHECK(check_block(h, B, N, block_start, L));
+    GraphArg g;
+    CHECK(check_graph(graph, &g));
+    CHECK(check_policy(policy));
+    if (!tokens || !drafts || !sigma || !m || !v_top1 || !v_conf) PSD_FAIL(PSD_ERR_INVALID_ARG, "NULL argument");
+    launch_accept(tokens, drafts, B, N, block_start, L, sigma, m, g, *policy, h->cfg.mask_id, v_top1, v_conf, k_star,
+                  accepted, nullptr, nullptr, (hipStream_t)stream);
+    PSD_HIP(hipGetLastError());
+    return PSD_OK;
+}
+
+int32_t psd_verify_accept(psd_handle *h, int32_t *tokens, const int32_t *drafts, int32_t B, int32_t N, int32_t block_start,
+                          int32_t L, const int32_t *sigma, const int32_t *m, const psd_graph *graph,
+                          const psd_policy *policy, int32_t *k_star, uint8_t *accepted, int32_t *v_top1, float *v_conf,
+                          void *ws, int64_t ws_bytes, void *stream) {
+    CHECK(check_block(h, B, N, block_start, L));
+    GraphArg g;
+    CHECK(check_graph(graph, &g));
+    CHECK(check_policy(policy));
+    if (!tokens || !drafts || !sigma || !m || !v_top1 || !v_conf) PSD_FAIL(PSD_ERR_INVALID_ARG, "NULL argument");
+    hipStream_t st = (hipStream_t)stream;
+    const int S = B * g.K;
+    CHECK(run_forward_hidden(h, drafts, nullptr, S, N, block_start, L, ws, ws_bytes, st));
+    CHECK(run_head_confidence(h, drafts, nullptr, S, N, block_start, L, v_top1, v_conf, nullptr, ws, st));
+    launch_accept(tokens, drafts, B, N, block_start, L, sigma, m, g, *policy, h->cfg.mask_id, v_top1, v_conf, k_star,
+                  accepted, nullptr, nullptr, st);
+    PSD_HIP(hipGetLastError());
+    return PSD_OK;
+}
+
+int32_t psd_decode_block(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_t block_start, int32_t L,
+                         const psd_policy *policy, const psd_graph *graph, psd_stats *stats, void *ws, int64_t ws_bytes,
+                         void *stream) {
+    CHECK(check_block(h, B, N, block_start, L));
+    GraphArg g;
+    CHECK(check_graph(graph, &g));
+    CHECK(check_policy(policy));
+    if (!tokens || !stats) PSD_FAIL(PSD_ERR_INVALID_ARG, "NULL tokens/stats");
+    const int K = g.K;
+    const int64_t fwd_bytes = plan_forward(h->cfg, (int64_t)B * K, N, L).total;
+    const DecodeScratch sc = plan_decode(B, N, L, K);
+    if (!ws || ws_bytes < fwd_bytes + sc.total)
+        PSD_FAIL(PSD_ERR_WORKSPACE, "workspace of %lld bytes, psd_decode_block needs %lld", (long long)ws_bytes,
+                 (long long)(fwd_bytes + sc.total));
+    if ((reinterpret_cast<uintptr_t>(ws) & 255) != 0) PSD_FAIL(PSD_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    if ((int64_t)B * (K + 2 + PSD_DEVSTAT_WORDS) > h->host_counts_cap) PSD_FAIL(PSD_ERR_SHAPE, "batch too large for the control buffer");
+    hipStream_t st = (hipStream_t)stream;
+    char *base = (char *)ws + fwd_bytes;
+    int32_t *top1 = (int32_t *)(base + sc.top1), *sigma = (int32_t *)(base + sc.sigma), *m = (int32_t *)(base + sc.m);
+    int32_t *n_left = (int32_t *)(base + sc.n_left), *drafts = (int32_t *)(base + sc.drafts);
+    int32_t *v_top1 = (int32_t *)(base + sc.v_top1), *k_star = (int32_t *)(base + sc.k_star);
+    int32_t *devstats = (int32_t *)(base + sc.devstats), *rows = (int32_t *)(base + sc.rows);
+    float *conf = (float *)(base + sc.conf), *v_conf = (float *)(base + sc.v_conf);
+    uint8_t *accepted = (uint8_t *)(base + sc.accepted);
+    int32_t *hc = h->host_counts;        // [0, B): counts read back; [B, B + B*K): row lists uploaded
+    int32_t *hrows = hc + B;
+    const int32_t mask_id = h->cfg.mask_id;
+
+    {
+        const int64_t n = (int64_t)B * PSD_DEVSTAT_WORDS;
+        hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, devstats, n, 0);
+    }
+    hipLaunchKernelGGL(count_masks_kernel, dim3(B), dim3(64), 0, st, tokens, N, block_start, L, mask_id, n_left);
+    PSD_HIP(hipMemcpyAsync(hc, n_left, sizeof(int32_t) * B, hipMemcpyDeviceToHost, st));
+    PSD_HIP(hipStreamSynchronize(st));
+    std::vector<int> active;
+    for (int b = 0; b < B; ++b)
+        if (hc[b] > 0) active.push_back(b);
+    std::vector<int64_t> invocations(B, 0);
+
+    while (!active.empty()) {
+        // stage 1: one forward over the active sequences, policy commit, drafts
+        const int S1 = (int)active.size();
+        for (int s = 0; s < S1; ++s) hrows[s] = active[s];
+        PSD_HIP(hipMemcpyAsync(rows, hrows, sizeof(int32_t) * S1, hipMemcpyHostToDevice, st));
+        CHECK(run_forward_hidden(h, tokens, rows, S1, N, block_start, L, ws, fwd_bytes, st));
+        CHECK(run_head_confidence(h, tokens, rows, S1, N, block_start, L, top1, conf, rows, ws, st));
+        for (int b : active) invocations[b] += 1;
+        launch_select_unmask(tokens, B, N, block_start, L, top1, conf, *policy, mask_id, nullptr, nullptr, n_left, devstats, st);
+        launch_build_drafts(tokens, B, N, block_start, L, top1, conf, g, mask_id, sigma, m, drafts, st);
+        PSD_HIP(hipMemcpyAsync(hc, m, sizeof(int32_t) * B, hipMemcpyDeviceToHost, st));
+        PSD_HIP(hipStreamSynchronize(st));
+        std::vector<int> vset;
+        for (int b : active)
+            if (hc[b] > 0) vset.push_back(b);
+        if (vset.empty()) break;
+        // stage 3: one batched forward over the K drafts of every sequence that still has masks
+        const int S3 = (int)vset.size() * K;
+        for (size_t i = 0; i < vset.size(); ++i)
+            for (int k = 0; k < K; ++k) hrows[i * K + k] = vset[i] * K + k;
+        PSD_HIP(hipMemcpyAsync(rows, hrows, sizeof(int32_t) * S3, hipMemcpyHostToDevice, st));
+        CHECK(run_forward_hidden(h, drafts, rows, S3, N, block_start, L, ws, fwd_bytes, st));
+        CHECK(run_head_confidence(h, drafts, rows, S3, N, block_start, L, v_top1, v_conf, rows, ws, st));
+        for (int b : vset) invocations[b] += 1;
+        launch_accept(tokens, drafts, B, N, block_start, L, sigma, m, g, *policy, mask_id, v_top1, v_conf, k_star, accepted,
+                      n_left, devstats, st);
+        PSD_HIP(hipMemcpyAsync(hc, n_left, sizeof(int32_t) * B, hipMemcpyDeviceToHost, st));
+        PSD_HIP(hipStreamSynchronize(st));
+        active.clear();
+        for (int b : vset)
+            if (hc[b] > 0) active.push_back(b);
+    }
+
+    int32_t *hstats = hc + B + (int64_t)B * K;
+    PSD_HIP(hipMemcpyAsync(hstats, devstats, sizeof(int32_t) * B * PSD_DEVSTAT_WORDS, hipMemcpyDeviceToHost, st));
+    PSD_HIP(hipStreamSynchronize(st));
+    for (int b = 0; b < B; ++b) {
+        const int32_t *ds = hstats + (int64_t)b * PSD_DEVSTAT_WORDS;
+        stats[b].invocations += invocations[b];
+        stats[b].tokens_policy += ds[PSD_DEVSTAT_POLICY];
+        stats[b].tokens_draft += ds[PSD_DEVSTAT_DRAFT];
+        stats[b].tokens_postverify += ds[PSD_DEVSTAT_POST];
+        for (int i = 0; i <= PSD_MAX_BLOCK; ++i) stats[b].depth_hist[i] += ds[PSD_DEVSTAT_HIST + i];
+    }
+    PSD_HIP(hipGetLastError());
+    return PSD_OK;
+}
+
+int32_t psd_forward_work(const psd_model_config *c, int32_t S, int32_t N, int32_t L, psd_work *out) {
+    CHECK(check_cfg(c));
+    if (!out || S < 1 || N < 1 || L < 1) PSD_FAIL(PSD_ERR_INVALID_ARG, "bad arguments");
+    const double esz = c->dtype == PSD_DTYPE_BF16 ? 2.0 : 4.0;
+    const double d = c->d_model, hq = (double)c->n_heads * c->d_head, hkv = (double)c->n_kv_heads * c->d_head, f = c->d_ffn;
+    const double layer_params = d * hq + 2.0 * d * hkv + hq * d + 3.0 * d * f;
+    const double T = (double)S * N, rows = (double)S * L;
+    out->gemm_flops = 2.0 * T * layer_params * c->n_layers;
+    out->attn_flops = 4.0 * (double)N * N * hq * S * c->n_layers;
+    out->head_flops = 2.0 * rows * c->vocab * d;
+    out->head_bytes = (double)c->vocab * d * esz + rows * d * esz + rows * 8.0;
+    out->weight_bytes = layer_params * esz * c->n_layers;
+    return PSD_OK;
+}
+
+}   // extern "C"

@@ -1,0 +1,102 @@
+// Token-wise kernels of the forward pass: embedding gather, RMSNorm, rotary embedding.
+// All are HBM-bound streaming kernels: one workgroup per row, 16-byte accesses where the
+// layout allows, fp32 arithmetic, the residual stream h kept in fp32.
+#include "psd_internal.h"
+#include "device_types.h"
+
+namespace {
+
+template <typename T>
+__global__ __launch_bounds__(256) void embed_kernel(const int32_t *__restrict__ tokens,
+                                                    const int32_t *__restrict__ seq_rows, int N,
+                                                    const T *__restrict__ emb, int d, float *__restrict__ h) {
+    const int64_t t = blockIdx.x;   // slot-major token index s*N + i
+    const int s = (int)(t / N), i = (int)(t % N);
+    const int64_t src_row = seq_rows ? seq_rows[s] : s;
+    const int32_t tok = tokens[src_row * N + i];
+    const T *e = emb + (int64_t)tok * d;
+    float *o = h + t * d;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) o[c] = to_float(e[c]);
+}
+
+__device__ __forceinline__ float block_sum(float v, float *smem) {
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    if ((threadIdx.x & 63) == 0) smem[w] = v;
+    __syncthreads();
+    float tot = 0.f;
+    for (int i = 0; i < nw; ++i) tot += smem[i];
+    __syncthreads();
+    return tot;
+}
+
+// out[r, :] = h[src(r), :] * rsqrt(mean(h^2) + eps) * gain ; src(r) = r, or the block rows of each sequence
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ h, int d, const float *__restrict__ gain,
+                                                      float eps, T *__restrict__ out, int N, int block_start, int L) {
+    __shared__ float smem[4];
+    const int64_t r = blockIdx.x;
+    int64_t src = r;
+    if (L > 0) src = (r / L) * N + block_start + (r % L);
+    const float *x = h + src * d;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) {
+        const float v = x[c];
+        ss += v * v;
+    }
+    ss = block_sum(ss, smem);
+    const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+    T *o = out + r * d;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) o[c] = from_float<T>(x[c] * inv * gain[c]);
+}
+
+// rotate-half rotary embedding in place on the q and k heads of qkv [tokens, (H + 2 Hkv) * dh]
+template <typename T>
+__global__ __launch_bounds__(256) void rope_kernel(T *__restrict__ qkv, int N, int n_heads, int n_kv_heads, int d_head,
+                                                   const float *__restrict__ cos_t, const float *__restrict__ sin_t) {
+    const int64_t t = blockIdx.x;
+    const int pos = (int)(t % N);
+    const int half = d_head >> 1;
+    const int rot_heads = n_heads + n_kv_heads;
+    T *row = qkv + t * (int64_t)(n_heads + 2 * n_kv_heads) * d_head;
+    for (int idx = threadIdx.x; idx < rot_heads * half; idx += blockDim.x) {
+        const int hd = idx / half, j = idx % half;
+        T *p = row + hd * d_head;
+        const float c = cos_t[(int64_t)pos * half + j], s = sin_t[(int64_t)pos * half + j];
+        const float x1 = to_float(p[j]), x2 = to_float(p[j + half]);
+        p[j] = from_float<T>(x1 * c - x2 * s);
+        p[j + half] = from_float<T>(x2 * c + x1 * s);
+    }
+}
+
+}   // namespace
+
+template <typename T>
+void launch_embed(const int32_t *tokens, const int32_t *seq_rows, int S, int N, const T *emb, int d, float *h,
+                  hipStream_t st) {
+    hipLaunchKernelGGL(embed_kernel<T>, dim3((unsigned)((int64_t)S * N)), dim3(256), 0, st, tokens, seq_rows, N, emb, d, h);
+}
+template <typename T>
+void launch_rmsnorm(const float *h, int64_t rows, int d, const float *gain, float eps, T *out, hipStream_t st) {
+    hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out, 0, 0, 0);
+}
+template <typename T>
+void launch_rmsnorm_block(const float *h, int S, int N, int block_start, int L, int d, const float *gain, float eps,
+                          T *out, hipStream_t st) {
+    hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3((unsigned)(S * L)), dim3(256), 0, st, h, d, gain, eps, out, N, block_start, L);
+}
+template <typename T>
+void launch_rope(T *qkv, int64_t tokens, int N, int n_heads, int n_kv_heads, int d_head, const float *cos_t,
+                 const float *sin_t, hipStream_t st) {
+    hipLaunchKernelGGL(rope_kernel<T>, dim3((unsigned)tokens), dim3(256), 0, st, qkv, N, n_heads, n_kv_heads, d_head,
+                       cos_t, sin_t);
+}
+
+#define INSTANTIATE(T)                                                                                              \
+    template void launch_embed<T>(const int32_t *, const int32_t *, int, int, const T *, int, float *, hipStream_t); \
+    template void launch_rmsnorm<T>(const float *, int64_t, int, const float *, float, T *, hipStream_t);           \
+    template void launch_rmsnorm_block<T>(const float *, int, int, int, int, int, const float *, float, T *,        \
+                                          hipStream_t);                                                             \
+    template void launch_rope<T>(T *, int64_t, int, int, int, int, const float *, const float *, hipStream_t);
+INSTANTIATE(float)
+INSTANTIATE(bf16_t)

@@ -1,0 +1,168 @@
+// The model call of the PSD step (Sec. 3.1): bidirectional transformer forward over S
+// sequences of N tokens, then top-1 token and confidence on the L rows of the active block.
+// This file only sequences kernels on one stream; every operation runs in the kernels of
+// elementwise.hip, gemm_mfma.hip, attention_mfma.hip, lm_head.hip (plain_kernels.hip on the
+// debug path).
+#include "psd_internal.h"
+
+ForwardPlan plan_forward(const psd_model_config &cfg, int64_t S, int64_t N, int64_t L) {
+    const int64_t T = S * N, rows = S * L;
+    const int64_t esz = cfg.dtype == PSD_DTYPE_BF16 ? 2 : 4;
+    const int64_t qkv_w = (int64_t)(cfg.n_heads + 2 * cfg.n_kv_heads) * cfg.d_head;
+    ForwardPlan p;
+    int64_t off = 0;
+    auto take = [&](int64_t bytes) {
+        const int64_t o = off;
+        off += align_up(bytes, 256);
+        return o;
+    };
+    p.off_h = take(T * cfg.d_model * 4);
+    p.off_a = take(T * cfg.d_model * esz);
+    p.off_qkv = take(T * qkv_w * esz);
+    p.off_vt = take(T * (int64_t)cfg.n_kv_heads * cfg.d_head * esz);
+    p.off_o = take(T * (int64_t)cfg.n_heads * cfg.d_head * esz);
+    p.off_act = take(T * cfg.d_ffn * esz);
+    p.off_y = take(rows * cfg.d_model * esz);
+    p.off_rowsum = take(rows * 4);
+    p.off_rowarg = take(rows * 4);
+    // LM-head scratch: per-slab partial (max, sum, argmax) triples on the fused path; the
+    // debug path stores full logits here instead
+    int64_t part = rows * (int64_t)cfg.vocab * 4;
+    if (cfg.dtype == PSD_DTYPE_BF16) {
+        const int64_t fused = head_partial_bytes((int)rows, cfg.vocab);
+        if (fused > part) part = fused;
+    }
+    p.off_part = take(part);
+    p.total = off;
+    return p;
+}
+
+namespace {
+
+template <typename T>
+struct Dispatch;
+
+template <>
+struct Dispatch<float> {
+    static void gemm(psd_handle *, const float *A, const void *W, const void *W2, int64_t M, int Nout, int Kin, int epi,
+                     const float *bias, float *out, float *resid, int ldo, hipStream_t st) {
+        launch_plain_gemm<float, float>(A, (const float *)W, (const float *)W2, M, Nout, Kin, epi, bias, 1.0f, out, resid,
+                                        ldo, st);
+    }
+    static void attention(psd_handle *, float *qkv, float *, int S, int N, int H, int Hkv, int dh, float *out,
+                          hipStream_t st) {
+        launch_plain_attention<float>(qkv, S, N, H, Hkv, dh, out, st);
+    }
+};
+
+template <>
+struct Dispatch<bf16_t> {
+    static void gemm(psd_handle *h, const bf16_t *A, const void *W, const void *W2, int64_t M, int Nout, int Kin, int epi,
+                     const float *bias, bf16_t *out, float *resid, int ldo, hipStream_t st) {
+        if (h->plain_mask & 1)
+            launch_plain_gemm<bf16_t, bf16_t>(A, (const bf16_t *)W, (const bf16_t *)W2, M, Nout, Kin, epi, bias, 1.0f, out,
+                                              resid, ldo, st);
+        else
+            launch_gemm_bf16(A, (const bf16_t *)W, (const bf16_t *)W2, M, Nout, Kin, epi, bias, out, resid, ldo, st);
+    }
+    static void attention(psd_handle *h, bf16_t *qkv, bf16_t *vT, int S, int N, int H, int Hkv, int dh, bf16_t *out,
+                          hipStream_t st) {
+        if ((h->plain_mask & 2) || (N % 8) != 0) {
+            launch_plain_attention<bf16_t>(qkv, S, N, H, Hkv, dh, out, st);
+        } else {
+            launch_transpose_v(qkv, S, N, H, Hkv, dh, vT, st);
+            launch_attention_bf16(qkv, vT, S, N, H, Hkv, dh, out, st);
+        }
+    }
+};
+
+template <typename T>
+int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N, int block_start,
+                            int L, char *ws, hipStream_t st) {
+    const psd_model_config &c = h->cfg;
+    const ForwardPlan p = plan_forward(c, S, N, L);
+    const int64_t ntok = (int64_t)S * N;
+    const int d = c.d_model, H = c.n_heads, Hkv = c.n_kv_heads, dh = c.d_head, F = c.d_ffn;
+    const int qkv_w = (H + 2 * Hkv) * dh;
+    float *hbuf = (float *)(ws + p.off_h);
+    T *a = (T *)(ws + p.off_a), *qkv = (T *)(ws + p.off_qkv), *vT = (T *)(ws + p.off_vt), *o = (T *)(ws + p.off_o);
+    T *act = (T *)(ws + p.off_act), *y = (T *)(ws + p.off_y);
+
+    launch_embed<T>(tokens, seq_rows, S, N, (const T *)h->tok_emb, d, hbuf, st);
+    for (const psd_handle::Layer &lw : h->layers) {
+        launch_rmsnorm<T>(hbuf, ntok, d, lw.attn_norm, c.rms_eps, a, st);
+        const int epi_qkv = c.qkv_bias ? EPI_BIAS : EPI_STORE;
+        Dispatch<T>::gemm(h, a, lw.wq, nullptr, ntok, H * dh, d, epi_qkv, lw.bq, qkv, nullptr, qkv_w, st);
+        Dispatch<T>::gemm(h, a, lw.wk, nullptr, ntok, Hkv * dh, d, epi_qkv, lw.bk, qkv + H * dh, nullptr, qkv_w, st);
+        Dispatch<T>::gemm(h, a, lw.wv, nullptr, ntok, Hkv * dh, d, epi_qkv, lw.bv, qkv + (H + Hkv) * dh, nullptr, qkv_w, st);
+        launch_rope<T>(qkv, ntok, N, H, Hkv, dh, h->rope_cos, h->rope_sin, st);
+        Dispatch<T>::attention(h, qkv, vT, S, N, H, Hkv, dh, o, st);
+        Dispatch<T>::gemm(h, o, lw.wo, nullptr, ntok, d, H * dh, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, st);
+        launch_rmsnorm<T>(hbuf, ntok, d, lw.ffn_norm, c.rms_eps, a, st);
+        Dispatch<T>::gemm(h, a, lw.w_gate, lw.w_up, ntok, F, d, EPI_SWIGLU, nullptr, act, nullptr, F, st);
+        Dispatch<T>::gemm(h, act, lw.w_down, nullptr, ntok, d, F, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, st);
+    }
+    launch_rmsnorm_block<T>(hbuf, S, N, block_start, L, d, h->final_norm, c.rms_eps, y, st);
+    return PSD_OK;
+}
+
+}   // namespace
+
+int32_t run_forward_hidden(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N, int block_start,
+                           int L, void *ws, int64_t ws_bytes, hipStream_t st) {
+    const ForwardPlan p = plan_forward(h->cfg, S, N, L);
+    if (ws == nullptr || ws_bytes < p.total)
+        PSD_FAIL(PSD_ERR_WORKSPACE, "workspace of %lld bytes, forward over %d x %d tokens needs %lld", (long long)ws_bytes,
+                 S, N, (long long)p.total);
+    if ((reinterpret_cast<uintptr_t>(ws) & 255) != 0) PSD_FAIL(PSD_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    int32_t rc;
+    if (h->cfg.dtype == PSD_DTYPE_BF16)
+        rc = forward_hidden_impl<bf16_t>(h, tokens, seq_rows, S, N, block_start, L, (char *)ws, st);
+    else
+        rc = forward_hidden_impl<float>(h, tokens, seq_rows, S, N, block_start, L, (char *)ws, st);
+    if (rc != PSD_OK) return rc;
+    PSD_HIP(hipGetLastError());
+    return PSD_OK;
+}
+
+int32_t run_head_confidence(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N, int block_start,
+                            int L, int32_t *top1, float *conf, const int32_t *out_rows, void *ws_, hipStream_t st) {
+    const psd_model_config &c = h->cfg;
+    const ForwardPlan p = plan_forward(c, S, N, L);
+    char *ws = (char *)ws_;
+    const int rows = S * L;
+    float *row_sum = (float *)(ws + p.off_rowsum);
+    int32_t *row_arg = (int32_t *)(ws + p.off_rowarg);
+    if (c.dtype == PSD_DTYPE_BF16 && !(h->plain_mask & 4)) {
+        launch_head_confidence_bf16((const bf16_t *)(ws + p.off_y), (const bf16_t *)h->lm_head, rows, c.vocab, c.d_model,
+                                    c.logit_scale, c.mask_id, ws + p.off_part, row_sum, row_arg, st);
+    } else {
+        float *logits = (float *)(ws + p.off_part);
+        if (c.dtype == PSD_DTYPE_BF16)
+            launch_plain_gemm<bf16_t, float>((const bf16_t *)(ws + p.off_y), (const bf16_t *)h->lm_head, nullptr, rows,
+                                             c.vocab, c.d_model, EPI_STORE, nullptr, c.logit_scale, logits, nullptr, c.vocab,
+                                             st);
+        else
+            launch_plain_gemm<float, float>((const float *)(ws + p.off_y), (const float *)h->lm_head, nullptr, rows, c.vocab,
+                                            c.d_model, EPI_STORE, nullptr, c.logit_scale, logits, nullptr, c.vocab, st);
+        launch_logits_top1(logits, rows, c.vocab, c.mask_id, row_sum, row_arg, st);
+    }
+    launch_head_finish(row_sum, row_arg, tokens, seq_rows, out_rows, S, N, block_start, L, c.mask_id, top1, conf, st);
+    PSD_HIP(hipGetLastError());
+    return PSD_OK;
+}
+
+int32_t run_head_logits(psd_handle *h, int S, int N, int L, float *logits, void *ws_, hipStream_t st) {
+    const psd_model_config &c = h->cfg;
+    const ForwardPlan p = plan_forward(c, S, N, L);
+    char *ws = (char *)ws_;
+    const int rows = S * L;
+    if (c.dtype == PSD_DTYPE_BF16)
+        launch_plain_gemm<bf16_t, float>((const bf16_t *)(ws + p.off_y), (const bf16_t *)h->lm_head, nullptr, rows, c.vocab,
+                                         c.d_model, EPI_STORE, nullptr, c.logit_scale, logits, nullptr, c.vocab, st);
+    else
+        launch_plain_gemm<float, float>((const float *)(ws + p.off_y), (const float *)h->lm_head, nullptr, rows, c.vocab,
+                                        c.d_model, EPI_STORE, nullptr, c.logit_scale, logits, nullptr, c.vocab, st);
+    PSD_HIP(hipGetLastError());
+    return PSD_OK;
+}

@@ -1,0 +1,258 @@
+// bf16 contraction D[i, j] = sum_k X[i, k] * Y[j, k] on the gfx950 matrix cores
+// (v_mfma_f32_32x32x16_bf16, fp32 accumulation).  Both operands are K-contiguous ("NT"
+// form), the natural MFMA feed: every lane fetches 8 consecutive k (16 bytes) of one row.
+//
+// Tiling: a workgroup of 4 wavefronts owns a BM x BN tile; K advances 64 at a time through
+// a double-buffered LDS stage (global -> registers -> LDS, one barrier per step).  LDS rows
+// are 128 bytes; the 16-byte chunk c of row r sits at chunk slot c ^ (r & 7), so the 32
+// rows a wavefront touches per fetch spread over all banks.  Workgroup ids are remapped so
+// that each of the 8 XCDs (which receive consecutive ids round-robin) works on a compact
+// range of tiles and its private L2 sees the operand reuse.
+//
+// After the K loop a lane holds, for every 32x32 subtile, column j = lane % 32 and the 16
+// rows i = 8*(v/4) + 4*(lane/32) + v%4.  The epilogue is a template policy:
+//   EPI_STORE / EPI_BIAS   out = bf16(acc (+ bias[j]))                     QKV projection
+//   EPI_RESIDUAL           resid[i, j] += acc           (fp32 stream)       O and down projections
+//   EPI_SWIGLU             out = bf16(silu(X Yg^T) * (X Yu^T))              gate and up in one pass
+//   EPI_TOP1               per column j: running (max, argmax, sum-exp) over the rows i
+//                          (LM-head with X = W_lm, Y = hidden rows; logits never stored)
+#pragma once
+#include "psd_internal.h"
+#include "device_types.h"
+
+namespace mfma {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int EPI_TOP1 = 4;
+constexpr int BK = 64;                  // k extent per stage (bf16) = 128 bytes per row
+constexpr int ROW_BYTES = BK * 2;
+
+struct Top1Args {
+    float scale;        // logits = scale * acc
+    int mask_id;        // row (vocab id) that is never predicted
+    float *pmax;        // [slabs, cols] partial maxima
+    float *psum;        // [slabs, cols] partial sum exp(z - pmax)
+    int32_t *parg;      // [slabs, cols] partial argmax (lowest id on ties)
+    int cols_total;
+};
+
+__device__ __forceinline__ int swz(int row, int chunk) { return row * ROW_BYTES + ((chunk ^ (row & 7)) << 4); }
+
+// merge two (max, argmax, sum-exp) triples; ties go to the lower index
+__device__ __forceinline__ void top1_merge(float &b, int &a, float &s, float b2, int a2, float s2) {
+    const float bn = fmaxf(b, b2);
+    const float s_new = (bn == -INFINITY) ? 0.f : s * __expf(b - bn) + s2 * __expf(b2 - bn);
+    if (b2 > b || (b2 == b && a2 < a)) a = a2;
+    b = bn;
+    s = s_new;
+}
+
+template <int BM, int BN, int WGM, int WGN, int EPI>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Y,
+                                                        const bf16_t *__restrict__ Y2, int M, int Nout, int Kin,
+                                                        const float *__restrict__ bias, bf16_t *__restrict__ out,
+                                                        float *__restrict__ resid, int ldo, int tiles_n, int n_tiles,
+                                                        Top1Args t1) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    constexpr bool DUAL = EPI == EPI_SWIGLU;
+    constexpr int BN_OUT = DUAL ? BN / 2 : BN;            // output columns per tile
+    constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES, STAGE = A_BYTES + B_BYTES;
+    constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
+    constexpr int A_CH = BM * 8 / 256, B_CH = (BN * 8 + 255) / 256;
+    static_assert(WGM * WGN == 4 && TM >= 1 && TN >= 1 && (!DUAL || TN % 2 == 0), "tile shape");
+    static_assert(BM * 8 % 256 == 0, "tile rows");
+
+    // XCD-aware tile id: ids i, i+8, i+16 ... land on the same XCD; give that XCD a contiguous tile range
+    int pid = blockIdx.x;
+    if (n_tiles % 8 == 0) pid = (pid % 8) * (n_tiles / 8) + pid / 8;
+    const int tile_m = pid / tiles_n, tile_n = pid % tiles_n;
+    const int m0 = tile_m * BM, n0 = tile_n * BN_OUT;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WGN, wn = wave % WGN;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    uint4 ra[A_CH], rb[B_CH];
+    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+
+    auto load_global = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) {
+            const int q = i * 256 + tid, r = q >> 3, c = q & 7;
+            const int m = m0 + r;
+            ra[i] = (m < M) ? *reinterpret_cast<const uint4 *>(X + (int64_t)m * Kin + k0 + c * 8) : zero4;
+        }
+#pragma unroll
+        for (int i = 0; i < B_CH; ++i) {
+            const int q = i * 256 + tid, r = q >> 3, c = q & 7;
+            const bf16_t *src = Y;
+            int n = n0 + r;
+            if (DUAL && r >= BN / 2) {
+                src = Y2;
+                n = n0 + r - BN / 2;
+            }
+            rb[i] = (r < BN && n < Nout) ? *reinterpret_cast<const uint4 *>(src + (int64_t)n * Kin + k0 + c * 8) : zero4;
+        }
+    };
+    auto store_lds = [&](int stage) {
+        unsigned char *sa = lds + stage * STAGE, *sb = sa + A_BYTES;
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) {
+            const int q = i * 256 + tid, r = q >> 3, c = q & 7;
+            *reinterpret_cast<uint4 *>(sa + swz(r, c)) = ra[i];
+        }
+#pragma unroll
+        for (int i = 0; i < B_CH; ++i) {
+            const int q = i * 256 + tid, r = q >> 3, c = q & 7;
+            if (r < BN) *reinterpret_cast<uint4 *>(sb + swz(r, c)) = rb[i];
+        }
+    };
+
+    const int nk = Kin / BK;
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    for (int kt = 0; kt < nk; ++kt) {
+        const int stage = kt & 1;
+        if (kt + 1 < nk) load_global((kt + 1) * BK);
+        const unsigned char *sa = lds + stage * STAGE, *sb = sa + A_BYTES;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            bf16x8 fa[TM], fb[TN];
+            const int c = kk * 2 + lhalf;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int r = wm * WTM + i * 32 + lrow;
+                fa[i] = *reinterpret_cast<const bf16x8 *>(sa + swz(r, c));
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                int r;
+                if (DUAL) {   // first half of the subtiles: gate rows, second half: up rows of the same columns
+                    const int jj = j % (TN / 2);
+                    r = (j >= TN / 2 ? BN / 2 : 0) + wn * (WTN / 2) + jj * 32 + lrow;
+                } else {
+                    r = wn * WTN + j * 32 + lrow;
+                }
+                fb[j] = *reinterpret_cast<const bf16x8 *>(sb + swz(r, c));
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < nk) store_lds(stage ^ 1);
+        __syncthreads();
+    }
+
+    if constexpr (EPI == EPI_TOP1) {
+        // per column j: (max, lowest argmax, sum exp) over this tile's rows; rows ascend with (i, v)
+        // inside a lane, so a strict comparison keeps the lowest index on ties
+        __shared__ float s_b[WGM][BN];
+        __shared__ float s_s[WGM][BN];
+        __shared__ int s_a[WGM][BN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            float best = -INFINITY;
+            int arg = 0x7fffffff;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + wm * WTM + i * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
+                    float z = acc[i][j][v] * t1.scale;
+                    if (m >= M || m == t1.mask_id) z = -INFINITY;
+                    acc[i][j][v] = z;
+                    if (z > best) {
+                        best = z;
+                        arg = m;
+                    }
+                }
+            float sum = 0.f;
+            if (best > -INFINITY) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) sum += __expf(acc[i][j][v] - best);
+            }
+            const float b2 = __shfl_xor(best, 32, 64);
+            const int a2 = __shfl_xor(arg, 32, 64);
+            const float s2 = __shfl_xor(sum, 32, 64);
+            top1_merge(best, arg, sum, b2, a2, s2);
+            if (lhalf == 0) {
+                const int col = wn * WTN + j * 32 + lrow;
+                s_b[wm][col] = best;
+                s_a[wm][col] = arg;
+                s_s[wm][col] = sum;
+            }
+        }
+        __syncthreads();
+        if (tid < BN && n0 + tid < Nout) {
+            float best = s_b[0][tid], sum = s_s[0][tid];
+            int arg = s_a[0][tid];
+#pragma unroll
+            for (int w = 1; w < WGM; ++w) top1_merge(best, arg, sum, s_b[w][tid], s_a[w][tid], s_s[w][tid]);
+            const int64_t o = (int64_t)tile_m * t1.cols_total + n0 + tid;
+            t1.pmax[o] = best;
+            t1.psum[o] = sum;
+            t1.parg[o] = arg;
+        }
+    } else {
+        constexpr int TN_OUT = DUAL ? TN / 2 : TN;
+        constexpr int WTN_OUT = DUAL ? WTN / 2 : WTN;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN_OUT; ++j) {
+                const int n = n0 + wn * WTN_OUT + j * 32 + lrow;
+                if (n >= Nout) continue;
+                const float bn = (EPI == EPI_BIAS) ? bias[n] : 0.f;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + wm * WTM + i * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
+                    if (m >= M) continue;
+                    float x = acc[i][j][v];
+                    if (EPI == EPI_BIAS) x += bn;
+                    if (DUAL) {
+                        const float u = acc[i][j + TN / 2][v];
+                        x = x / (1.0f + __expf(-x)) * u;
+                    }
+                    if (EPI == EPI_RESIDUAL)
+                        resid[(int64_t)m * ldo + n] += x;
+                    else
+                        out[(int64_t)m * ldo + n] = from_float<bf16_t>(x);
+                }
+            }
+    }
+}
+
+template <int BM, int BN, int WGM, int WGN, int EPI>
+void launch_cfg(const bf16_t *X, const bf16_t *Y, const bf16_t *Y2, int M, int Nout, int Kin, const float *bias,
+                bf16_t *out, float *resid, int ldo, Top1Args t1, hipStream_t st) {
+    constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (Nout + BN_OUT - 1) / BN_OUT;
+    const int n_tiles = tiles_m * tiles_n;
+    constexpr int smem = 2 * (BM + BN) * ROW_BYTES;
+    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, EPI>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(n_tiles), dim3(256), smem, st, X, Y, Y2, M, Nout, Kin, bias, out, resid, ldo, tiles_n,
+                       n_tiles, t1);
+}
+
+}   // namespace mfma

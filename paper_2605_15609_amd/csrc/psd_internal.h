@@ -1,0 +1,125 @@
+// Internal declarations shared by the translation units of libpsd (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "psd.h"
+
+struct bf16_t {
+    uint16_t bits;
+};
+
+struct psd_handle {
+    psd_model_config cfg;
+    const void *tok_emb, *lm_head;
+    const float *final_norm, *rope_cos, *rope_sin;
+    struct Layer {
+        const float *attn_norm, *ffn_norm, *bq, *bk, *bv;
+        const void *wq, *wk, *wv, *wo, *w_gate, *w_up, *w_down;
+    };
+    std::vector<Layer> layers;
+    int device;
+    int plain_mask;          // debug: bit 0 plain GEMM, bit 1 plain attention, bit 2 plain LM-head
+    int32_t *host_counts;    // pinned host staging for psd_decode_block
+    int host_counts_cap;
+};
+
+void psd_set_error(const char *fmt, ...);
+
+#define PSD_FAIL(code, ...)         \
+    do {                            \
+        psd_set_error(__VA_ARGS__); \
+        return (code);              \
+    } while (0)
+
+#define PSD_HIP(expr)                                                                                  \
+    do {                                                                                               \
+        hipError_t e_ = (expr);                                                                        \
+        if (e_ != hipSuccess) PSD_FAIL(PSD_ERR_DEVICE, "%s: %s", #expr, hipGetErrorString(e_));        \
+    } while (0)
+
+static inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+// ---------------------------------------------------------------- decision kernels (decide.hip)
+#define PSD_DEVSTAT_POLICY 0
+#define PSD_DEVSTAT_DRAFT 1
+#define PSD_DEVSTAT_POST 2
+#define PSD_DEVSTAT_HIST 3
+#define PSD_DEVSTAT_WORDS (3 + PSD_MAX_NODES + PSD_MAX_BLOCK + 1)
+
+struct GraphArg {
+    int32_t K;
+    uint64_t rank_set[PSD_MAX_NODES];
+};
+
+void launch_select_unmask(int32_t *tokens, int B, int N, int block_start, int L, const int32_t *top1,
+                          const float *conf, psd_policy policy, int32_t mask_id, uint8_t *transfer_mask,
+                          int32_t *n_selected, int32_t *n_left, int32_t *devstats, hipStream_t st);
+void launch_build_drafts(const int32_t *tokens, int B, int N, int block_start, int L, const int32_t *top1,
+                         const float *conf, const GraphArg &g, int32_t mask_id, int32_t *sigma, int32_t *m,
+                         int32_t *drafts, hipStream_t st);
+void launch_accept(int32_t *tokens, const int32_t *drafts, int B, int N, int block_start, int L,
+                   const int32_t *sigma, const int32_t *m, const GraphArg &g, psd_policy policy, int32_t mask_id,
+                   const int32_t *v_top1, const float *v_conf, int32_t *k_star, uint8_t *accepted,
+                   int32_t *n_left, int32_t *devstats, hipStream_t st);
+
+// ---------------------------------------------------------------- forward (forward.hip)
+struct ForwardPlan {
+    int64_t off_h, off_a, off_qkv, off_vt, off_o, off_act, off_y, off_rowsum, off_rowarg, off_part, total;
+};
+ForwardPlan plan_forward(const psd_model_config &cfg, int64_t S, int64_t N, int64_t L);
+
+// Layer stack + final norm on the block rows; leaves y [S*L, d] in the workspace.
+// seq_rows (device, may be NULL) maps batch slot s -> row of `tokens` to read.
+int32_t run_forward_hidden(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N,
+                           int block_start, int L, void *ws, int64_t ws_bytes, hipStream_t st);
+// LM-head + top-1 confidence on y; out_rows (device, may be NULL) maps slot s -> row of top1/conf.
+int32_t run_head_confidence(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N,
+                            int block_start, int L, int32_t *top1, float *conf, const int32_t *out_rows,
+                            void *ws, hipStream_t st);
+int32_t run_head_logits(psd_handle *h, int S, int N, int L, float *logits, void *ws, hipStream_t st);
+
+// ---------------------------------------------------------------- kernel launchers
+// elementwise.hip
+template <typename T>
+void launch_embed(const int32_t *tokens, const int32_t *seq_rows, int S, int N, const T *emb, int d, float *h,
+                  hipStream_t st);
+template <typename T>
+void launch_rmsnorm(const float *h, int64_t rows, int d, const float *gain, float eps, T *out, hipStream_t st);
+template <typename T>
+void launch_rmsnorm_block(const float *h, int S, int N, int block_start, int L, int d, const float *gain,
+                          float eps, T *out, hipStream_t st);
+template <typename T>
+void launch_rope(T *qkv, int64_t tokens, int N, int n_heads, int n_kv_heads, int d_head, const float *cos_t,
+                 const float *sin_t, hipStream_t st);
+// vT[s][kvh][c][i] <- V part of qkv[s*N + i]; the MFMA attention reads values key-contiguous
+void launch_transpose_v(const bf16_t *qkv, int S, int N, int n_heads, int n_kv_heads, int d_head, bf16_t *vT,
+                        hipStream_t st);
+
+// plain_kernels.hip (debug path, any shape)
+enum Epilogue { EPI_STORE = 0, EPI_BIAS = 1, EPI_RESIDUAL = 2, EPI_SWIGLU = 3 };
+template <typename T, typename TO>
+void launch_plain_gemm(const T *A, const T *W, const T *W2, int64_t M, int Nout, int Kin, int epi, const float *bias,
+                       float scale, TO *out, float *resid, int ldo, hipStream_t st);
+template <typename T>
+void launch_plain_attention(const T *qkv, int S, int N, int n_heads, int n_kv_heads, int d_head, T *out,
+                            hipStream_t st);
+void launch_logits_top1(const float *logits, int rows, int V, int mask_id, float *row_sum, int32_t *row_arg,
+                        hipStream_t st);
+void launch_head_finish(const float *row_sum, const int32_t *row_arg, const int32_t *tokens, const int32_t *seq_rows,
+                        const int32_t *out_rows, int S, int N, int block_start, int L, int mask_id, int32_t *top1,
+                        float *conf, hipStream_t st);
+
+// gemm_mfma.hip (bf16; Nout, Kin multiples of 64)
+void launch_gemm_bf16(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int64_t M, int Nout, int Kin, int epi,
+                      const float *bias, bf16_t *out, float *resid, int ldo, hipStream_t st);
+// attention_mfma.hip (bf16, d_head 64 or 128): q, k from qkv (rotary applied), values from vT
+void launch_attention_bf16(const bf16_t *qkv, const bf16_t *vT, int S, int N, int n_heads, int n_kv_heads, int d_head,
+                           bf16_t *out, hipStream_t st);
+// lm_head.hip (bf16): LM-head fused with the online top-1 / sum-exp reduction
+int64_t head_partial_bytes(int rows, int V);
+void launch_head_confidence_bf16(const bf16_t *y, const bf16_t *W, int rows, int V, int d, float scale, int mask_id,
+                                 void *partials, float *row_sum, int32_t *row_arg, hipStream_t st);

@@ -1,0 +1,130 @@
+"""Numeric parity of the HIP forward + top-1 confidence with the fp64 oracle, through the C ABI.
+
+Tolerances (from the benchmark spec): logits within 1e-4 max-abs on the fp32 debug path and
+2e-2 on the bf16 MFMA path; top-1 tokens equal except where the oracle's own top-1 margin
+is below 1e-3 (logged and excluded).  Confidences are compared relatively: a logit error
+of e changes a softmax probability by at most a factor exp(2e).
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import psd_inputs as inp
+from oracle import psd_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+SMALL = inp.WORKLOADS[2].shape
+SHAPES = {
+    # d_head 64, MHA, ragged sequence length (200 = 128 + 72), ragged vocab tail vs 128/256 slabs
+    "small-2l": (inp.cut_down(SMALL, n_layers=2, vocab=5000, seed=21), 200, 96, 32),
+    # d_head 128, grouped KV heads + QKV bias (Dream layout), 136 tokens
+    "gqa-bias": (inp.cut_down(inp.WORKLOADS[4].shape, n_layers=2, d_model=512, n_heads=4, n_kv_heads=2, d_ffn=640,
+                              vocab=3001, seed=22), 136, 40, 64),
+    # full config-2 model (8 layers, vocab 32000)
+    "cfg2-full": (SMALL, 384, 128, 32),
+}
+
+
+def _state(shape, N, block_start, L, seed, n_committed):
+    rng = np.random.default_rng(seed)
+    t = np.full(N, shape.mask_id, dtype=np.int32)
+    t[:block_start] = inp.draw_prompt(shape.vocab, block_start, seed)
+    idx = rng.choice(L, size=n_committed, replace=False)
+    t[block_start + idx] = rng.integers(0, shape.vocab - 1, size=n_committed)
+    return t
+
+
+def _margins(z, mask_id):
+    z = z.copy()
+    z[:, mask_id] = -np.inf
+    part = np.partition(z, -2, axis=-1)
+    return part[:, -1] - part[:, -2]
+
+
+def _compare(model, host, tokens_list, block_start, L, tol_logits, label):
+    import paper_2605_15609_amd as psd
+    from tests.gpu_common import to_dev, say
+    shape = host.shape
+    tokens = np.stack(tokens_list)
+    d_tokens = to_dev(tokens)
+    logits = psd.psd_forward_logits(model, d_tokens, block_start, L).cpu().numpy().reshape(len(tokens_list), L, -1)
+    top1, conf = psd.psd_forward_confidence(model, d_tokens, block_start, L)
+    torch.cuda.synchronize()
+    top1, conf = top1.cpu().numpy(), conf.cpu().numpy()
+    worst, near_ties = 0.0, 0
+    for s, t in enumerate(tokens_list):
+        o_top1, o_conf, z = orc.forward_confidence(host, t, block_start, L, return_logits=True)
+        err = np.abs(logits[s] - z).max()
+        worst = max(worst, err)
+        assert err <= tol_logits, f"{label}: logits max-abs error {err:.3e} > {tol_logits}"
+        masked = t[block_start: block_start + L] == shape.mask_id
+        # sentinels
+        assert (top1[s][~masked] == t[block_start: block_start + L][~masked]).all()
+        assert (conf[s][~masked] == -1.0).all()
+        margin = _margins(z, shape.mask_id)
+        safe = masked & (margin >= 1e-3)
+        near_ties += int((masked & (margin < 1e-3)).sum())
+        assert (top1[s][safe] == o_top1[safe]).all(), f"{label}: top-1 mismatch away from near-ties"
+        assert (top1[s][masked] != shape.mask_id).all()
+        rel = np.abs(conf[s][safe] / o_conf[safe] - 1.0).max() if safe.any() else 0.0
+        assert rel <= np.expm1(2 * tol_logits) + 1e-5, f"{label}: confidence off by {rel:.3e}"
+    say(f"[forward] {label}: logits max-abs err {worst:.3e} (tol {tol_logits}), near-tie rows excluded: {near_ties}")
+    return worst
+
+
+def test_fp32_debug_path_config1():
+    from tests.gpu_common import make_models
+    w = inp.WORKLOADS[1]
+    host, model = make_models(w.shape, w.seq_len)
+    states = [inp.initial_state(w)[0], _state(w.shape, w.seq_len, 16, 32, 5, 11)]
+    _compare(model, host, states, 16, 32, 1e-4, "cfg1-fp32")
+
+
+@pytest.mark.parametrize("name", list(SHAPES))
+@pytest.mark.parametrize("plain", [7, 6, 5, 3, 0], ids=["all-plain", "mfma-gemm", "mfma-attn", "fused-head", "all-mfma"])
+def test_bf16_paths(name, plain):
+    from tests.gpu_common import make_models, say
+    shape, N, bs, L = SHAPES[name]
+    if name == "cfg2-full" and plain not in (7, 0):
+        pytest.skip("full config 2 is checked on the all-plain and all-MFMA paths only")
+    say(f"[forward] {name} plain_mask={plain}")
+    host, model = make_models(shape, N)
+    model.set_plain(plain)
+    states = [_state(shape, N, bs, L, 1, 0), _state(shape, N, bs, L, 2, L // 3)]
+    if name != "cfg2-full":
+        states.append(_state(shape, N, bs, L, 3, L - 1))
+    _compare(model, host, states, bs, L, 2e-2, f"{name}/mask{plain}")
+
+
+def test_batched_forward_equals_single(monkeypatch):
+    """Batching S sequences must not change any sequence's (top1, conf) by more than rounding
+    of the tile schedule; the decisions of the all-MFMA path must agree exactly here."""
+    import paper_2605_15609_amd as psd
+    from tests.gpu_common import make_models, to_dev
+    shape, N, bs, L = SHAPES["small-2l"]
+    host, model = make_models(shape, N)
+    states = np.stack([_state(shape, N, bs, L, s, s * 3) for s in range(5)])
+    t_all, c_all = psd.psd_forward_confidence(model, to_dev(states), bs, L)
+    for s in range(5):
+        t1, c1 = psd.psd_forward_confidence(model, to_dev(states[s: s + 1]), bs, L)
+        assert (t1[0] == t_all[s]).all()
+        assert torch.allclose(c1[0], c_all[s], rtol=1e-5, atol=0)
+
+
+def test_logit_scale_is_applied_inside_the_fused_head():
+    import paper_2605_15609_amd as psd
+    from tests.gpu_common import make_models, to_dev
+    shape, N, bs, L = SHAPES["small-2l"]
+    shape = dataclasses.replace(shape, logit_scale=6.0)
+    host, model = make_models(shape, N)
+    t = _state(shape, N, bs, L, 4, 5)
+    top1, conf = psd.psd_forward_confidence(model, to_dev(t[None]), bs, L)
+    o_top1, o_conf, z = orc.forward_confidence(host, t, bs, L, return_logits=True)
+    masked = t[bs: bs + L] == shape.mask_id
+    safe = masked & (_margins(z, shape.mask_id) >= 6e-3)
+    assert (top1[0].cpu().numpy()[safe] == o_top1[safe]).all()
+    rel = np.abs(conf[0].cpu().numpy()[safe] / o_conf[safe] - 1).max()
+    assert rel < np.expm1(2 * 6 * 2e-2)

@@ -1,0 +1,62 @@
+"""The C-ABI library loads and exports every symbol that include/psd.h declares (CPU only)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2605_15609_amd as psd
+    if not os.path.exists(psd.library_path()):
+        from paper_2605_15609_amd import build
+        build.build()
+    return psd.load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "psd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(psd_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert {"psd_forward_confidence", "psd_select_unmask", "psd_build_drafts", "psd_verify_accept",
+            "psd_decode_block"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_host_only_entry_points(lib):
+    import paper_2605_15609_amd as psd
+    assert lib.psd_status_string(0) == b"ok" and lib.psd_status_string(-3).startswith(b"workspace")
+    g = psd.chain_graph(4)
+    assert g.rank_sets == (0, 1, 3, 7)
+    assert psd.chain_graph(3, 2).rank_sets == (0, 3, 15)
+    with pytest.raises(psd.PsdError):
+        psd.chain_graph(40)
+    assert lib.psd_decode_scratch_bytes(1, 512, 32, 4) > 4 * 512 * 4
+    assert lib.psd_decode_scratch_bytes(0, 512, 32, 4) < 0
+
+
+def test_workspace_and_work_accounting(lib):
+    import psd_inputs as inp
+    from paper_2605_15609_amd.binding import _Config, _Work
+    s = inp.WORKLOADS[3].shape
+    cfg = _Config(s.n_layers, s.d_model, s.n_heads, s.n_kv_heads, s.d_head, s.d_ffn, s.vocab, s.mask_id, s.rms_eps, 0, 1,
+                  1.0, 512)
+    small = lib.psd_workspace_bytes(ctypes.byref(cfg), 1, 512, 32)
+    big = lib.psd_workspace_bytes(ctypes.byref(cfg), 4, 512, 32)
+    assert 0 < small < big < 2 ** 33
+    w = _Work()
+    assert lib.psd_forward_work(ctypes.byref(cfg), 4, 512, 32, ctypes.byref(w)) == 0
+    # config 3 verify call: ~28.6 TFLOP of layer contractions, 1.036 GB LM-head weights
+    assert abs(w.gemm_flops / 28.59e12 - 1) < 0.01
+    assert abs(w.attn_flops / 0.55e12 - 1) < 0.01
+    assert abs(w.head_bytes / 1.037e9 - 1) < 0.01
+    bad = _Config(2, 100, 4, 4, 25, 256, 300, 299, 1e-5, 0, 1, 1.0, 64)
+    assert lib.psd_workspace_bytes(ctypes.byref(bad), 1, 32, 8) < 0
