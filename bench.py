@@ -1,0 +1,163 @@
+#!/usr/bin/env python3
+"""Benchmark of the PSD hot path on one MI355X.
+
+A "step" is one whole decode of the workload: every block of every sequence run through
+Alg. 1 (stage-1 forward + top-1 confidence, policy commit, draft build, batched
+verification forward, hierarchical acceptance) by psd_decode_block, inputs and weights
+resident in HBM.  Prints ONE JSON line: decoded tokens/s (whole job), tokens per forward
+(TPF), the roofline figure of the dominant kernel measured live with HIP events, and the
+CPU oracle timed on a bounded sample.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--logit-scale 1.0]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16
+HBM_PEAK_GBS = 8000.0
+
+
+def cpu_baseline(workload, stats_tokens, n_stage1, n_verify, threads_hint):
+    """Times the oracle as it stands on a bounded sample: forward + confidence of one
+    sequence at the workload's N on 1-layer and 2-layer cuts of the model (same widths and
+    vocabulary).  Per-layer and per-call costs are extrapolated to the full depth and to
+    the call counts of the measured decode (the oracle runs each sequence of a batched
+    verification separately)."""
+    import numpy as np
+    import psd_inputs as inp
+    from oracle import psd_oracle as orc
+    shape, N, L = workload.shape, workload.seq_len, workload.block_len
+    tokens = inp.initial_state(workload)[0]
+    times = {}
+    for nl in (1, 2):
+        cut = inp.cut_down(shape, n_layers=nl)
+        host = inp.draw_model(cut, N)
+        t0 = time.perf_counter()
+        orc.forward_confidence(host, tokens, workload.prompt_len, L)
+        times[nl] = time.perf_counter() - t0
+        del host
+    per_layer = max(times[2] - times[1], 1e-9)
+    rest = max(times[1] - per_layer, 0.0)
+    t_seq = shape.n_layers * per_layer + rest
+    total = (n_stage1 + n_verify * workload.n_drafts) * t_seq
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = threads_hint
+    return {"value": stats_tokens / total, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"oracle forward+confidence of one {N}-token sequence on 1- and 2-layer cuts of the model "
+                      f"({times[1]:.2f}s, {times[2]:.2f}s), extrapolated to {shape.n_layers} layers and to the "
+                      f"{n_stage1} stage-1 + {n_verify}x{workload.n_drafts} verify sequence-forwards of one decode",
+            "seconds_per_sequence_forward": t_seq}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=3, help="BASELINE configuration index (1-5)")
+    ap.add_argument("--logit-scale", type=float, default=1.0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import dataclasses
+    import numpy as np
+    import torch
+    import psd_inputs as inp
+    import paper_2605_15609_amd as psd
+    from paper_2605_15609_amd.synthetic import synthetic_model
+
+    if not os.path.exists(psd.library_path()):
+        from paper_2605_15609_amd import build
+        build.build()
+    w = inp.WORKLOADS[args.config]
+    if args.logit_scale != 1.0:
+        w = dataclasses.replace(w, shape=dataclasses.replace(w.shape, logit_scale=args.logit_scale))
+    shape = w.shape
+    torch.cuda.set_device(0)
+    t0 = time.perf_counter()
+    model = synthetic_model(shape, w.seq_len, "cuda:0", threads=16)
+    torch.cuda.synchronize()
+    t_weights = time.perf_counter() - t0
+    tokens0 = torch.from_numpy(inp.initial_state(w)).to("cuda:0")
+    policy, graph = psd.Policy(w.tau, w.k_min, w.k_max), psd.chain_graph(w.n_drafts)
+
+    def one_decode():
+        toks = tokens0.clone()
+        stats = psd.decode(model, toks, w.prompt_len, w.block_len, policy, graph)
+        return toks, stats
+
+    for _ in range(args.warmup):
+        one_decode()
+    torch.cuda.synchronize()
+
+    # dominant kernel: the SwiGLU gate/up contraction of the verification forward
+    bf16 = shape.dtype == "bf16"
+    if bf16:
+        model.probe_begin(3, 1)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        toks, stats = one_decode()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    roofline = None
+    if bf16:
+        ms, launches, flops = model.probe_end()
+        if launches > 0 and ms > 0:
+            achieved = flops / (ms * 1e-3) / 1e12
+            roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                        "kernel": "gemm_bf16_kernel<256,256,2,2,SWIGLU>", "launches": int(launches),
+                        "avg_launch_us": ms * 1e3 / launches, "flops_per_launch": flops / launches}
+
+    assert not bool((toks == shape.mask_id).any()), "decode left masked positions"
+    n_tokens = w.batch * w.gen_len
+    invocations = sum(s.invocations for s in stats)
+    n_verify = sum(sum(s.depth_hist) for s in stats)
+    n_stage1 = invocations - n_verify
+    tpf = sum(s.tokens for s in stats) / max(1, invocations)
+    value = args.steps * n_tokens / elapsed
+
+    # whole-forward accounting for the verification pass (MFMA utilisation of the model call)
+    # (per-sequence call counts: a stage-1 call is one sequence-forward, a verify call K of them)
+    work_v = psd.forward_work(model, w.n_drafts, w.seq_len, w.block_len)
+    work_1 = psd.forward_work(model, 1, w.seq_len, w.block_len)
+    flops_decode = n_stage1 * (work_1["gemm_flops"] + work_1["attn_flops"] + work_1["head_flops"]) + \
+                   n_verify * (work_v["gemm_flops"] + work_v["attn_flops"] + work_v["head_flops"])
+    out = {
+        "metric": "decoded tokens/s (PSD, tokens per forward in config.tpf)", "value": value, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": f"config {w.index}: {shape.name}, B={w.batch}, prompt {w.prompt_len} Zipf tokens, "
+                               f"{w.gen_len} generated in blocks of {w.block_len}, K={w.n_drafts} chain, tau={w.tau}",
+                   "tpf": tpf, "invocations": int(invocations), "stage1_calls": int(n_stage1),
+                   "verify_calls": int(n_verify), "logit_scale": shape.logit_scale,
+                   "tokens_policy": int(sum(s.tokens_policy for s in stats)),
+                   "tokens_draft": int(sum(s.tokens_draft for s in stats)),
+                   "tokens_postverify": int(sum(s.tokens_postverify for s in stats)),
+                   "model_tflops_per_s_whole_decode": flops_decode / (elapsed / args.steps) / 1e12,
+                   "weights_setup_s": t_weights},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, n_tokens, n_stage1, n_verify, os.cpu_count() or 1)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -214,6 +214,33 @@ typedef struct {
 } psd_work;
 int32_t psd_forward_work(const psd_model_config *cfg, int32_t S, int32_t N, int32_t L, psd_work *out);
 
+/* Kernel-level hooks for parity tests and timing at full shapes without a model: the same
+ * launchers the forward uses, on caller-provided device buffers (bf16 = raw 16-bit).
+ *   gemm:  epilogue 0/1: out[m, n] = bf16(sum_k A[m,k] W[n,k] (+ bias[n]));
+ *          2: resid[m, n] += sum (fp32);  3: out = bf16(silu(A W^T) * (A W2^T)).
+ *          A [M, Kin], W / W2 [Nout, Kin]; Nout, Kin multiples of 64; ldo = row stride of out / resid.
+ *   attention: qkv [S*N, (n_heads + 2 n_kv_heads) * d_head] with rotary already applied;
+ *          vT is scratch of S*N*n_kv_heads*d_head bf16; out [S*N, n_heads*d_head].
+ *   head:  y [rows, d], W [vocab, d] -> row_sum[r] = sum_v exp(z_v - max_v z), row_arg[r] =
+ *          argmax_v z_v over v != mask_id, z = scale * y W^T; scratch from
+ *          psd_kernel_head_scratch_bytes. */
+int32_t psd_kernel_gemm_bf16(const void *A, const void *W, const void *W2, int64_t M, int32_t Nout, int32_t Kin,
+                             int32_t epilogue, const float *bias, void *out, float *resid, int32_t ldo, void *stream);
+int32_t psd_kernel_attention_bf16(const void *qkv, int32_t S, int32_t N, int32_t n_heads, int32_t n_kv_heads,
+                                  int32_t d_head, void *vT, void *out, void *stream);
+int64_t psd_kernel_head_scratch_bytes(int32_t rows, int32_t vocab);
+int32_t psd_kernel_head_confidence_bf16(const void *y, const void *W, int32_t rows, int32_t vocab, int32_t d, float scale,
+                                        int32_t mask_id, void *scratch, float *row_sum, int32_t *row_arg, void *stream);
+
+/* Kernel timing for roofline accounting.  Between psd_probe_begin and psd_probe_end every
+ * launch of the layer-contraction kernel with the given epilogue (0 store, 1 bias,
+ * 2 residual, 3 SwiGLU) and workgroup tile (0: 128x128, 1: 256x256) is bracketed by HIP
+ * events on the stream it is launched on (up to max_launches; later ones go untimed).
+ * psd_probe_end waits for those events and returns their summed duration, the number of
+ * timed launches and their algorithmic FLOPs (2*M*N*K, twice that for SwiGLU). */
+int32_t psd_probe_begin(psd_handle *h, int32_t epilogue, int32_t tile, int32_t max_launches);
+int32_t psd_probe_end(psd_handle *h, double *total_ms, int64_t *launches, double *flops);
+
 #ifdef __cplusplus
 }
 #endif

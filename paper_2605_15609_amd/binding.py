@@ -94,6 +94,12 @@ def load_library():
                                     vp, vp, vp, vp, i64, vp]),
         "psd_decode_block": (i32, [vp, vp, i32, i32, i32, i32, C.POINTER(_Policy), C.POINTER(_Graph), C.POINTER(_Stats),
                                    vp, i64, vp]),
+        "psd_kernel_gemm_bf16": (i32, [vp, vp, vp, i64, i32, i32, i32, vp, vp, vp, i32, vp]),
+        "psd_kernel_attention_bf16": (i32, [vp, i32, i32, i32, i32, i32, vp, vp, vp]),
+        "psd_kernel_head_scratch_bytes": (i64, [i32, i32]),
+        "psd_kernel_head_confidence_bf16": (i32, [vp, vp, i32, i32, i32, C.c_float, i32, vp, vp, vp, vp]),
+        "psd_probe_begin": (i32, [vp, i32, i32, i32]),
+        "psd_probe_end": (i32, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
         "psd_forward_work": (i32, [C.POINTER(_Config), i32, i32, i32, C.POINTER(_Work)]),
     }
     for name, (res, args) in sig.items():
@@ -241,6 +247,14 @@ class Model:
     def set_plain(self, mask: int):
         _check(self.lib.psd_debug_set_plain(self.handle, int(mask)))
 
+    def probe_begin(self, epilogue: int, tile: int, max_launches: int = 65536):
+        _check(self.lib.psd_probe_begin(self.handle, epilogue, tile, max_launches))
+
+    def probe_end(self):
+        ms, n, fl = C.c_double(), C.c_int64(), C.c_double()
+        _check(self.lib.psd_probe_end(self.handle, C.byref(ms), C.byref(n), C.byref(fl)))
+        return ms.value, n.value, fl.value
+
     def workspace(self, n_bytes: int) -> torch.Tensor:
         if self._ws is None or self._ws.numel() < n_bytes:
             self._ws = None
@@ -373,3 +387,54 @@ def decode(model: Model, tokens: torch.Tensor, prompt_len: int, L: int, policy: 
     for block_start in range(prompt_len, N, L):
         stats = psd_decode_block(model, tokens, block_start, min(L, N - block_start), policy, graph, stats)
     return stats
+
+
+# ------------------------------------------------------------------------------------------
+# kernel-level hooks (parity tests and timing at full shapes without a model)
+# ------------------------------------------------------------------------------------------
+
+EPI_STORE, EPI_BIAS, EPI_RESIDUAL, EPI_SWIGLU = 0, 1, 2, 3
+
+
+def kernel_gemm_bf16(A: torch.Tensor, W: torch.Tensor, epilogue: int = EPI_STORE, W2: Optional[torch.Tensor] = None,
+                     bias: Optional[torch.Tensor] = None, resid: Optional[torch.Tensor] = None,
+                     out: Optional[torch.Tensor] = None):
+    """A bf16 [M, K], W bf16 [N, K] -> out bf16 [M, N] (or resid fp32 [M, N] += for EPI_RESIDUAL)."""
+    lib = load_library()
+    M, K = A.shape
+    Nout = W.shape[0]
+    if epilogue == EPI_RESIDUAL:
+        assert resid is not None and resid.dtype == torch.float32
+        _check(lib.psd_kernel_gemm_bf16(_ptr(A), _ptr(W), None, M, Nout, K, epilogue, None, None, _ptr(resid),
+                                        resid.stride(0), _stream()))
+        return resid
+    if out is None:
+        out = torch.empty((M, Nout), dtype=torch.bfloat16, device=A.device)
+    _check(lib.psd_kernel_gemm_bf16(_ptr(A), _ptr(W), _ptr(W2), M, Nout, K, epilogue, _ptr(bias), _ptr(out), None,
+                                    out.stride(0), _stream()))
+    return out
+
+
+def kernel_attention_bf16(qkv: torch.Tensor, S: int, N: int, n_heads: int, n_kv_heads: int, d_head: int,
+                          out: Optional[torch.Tensor] = None, vT: Optional[torch.Tensor] = None):
+    lib = load_library()
+    if vT is None:
+        vT = torch.empty((S * N * n_kv_heads * d_head,), dtype=torch.bfloat16, device=qkv.device)
+    if out is None:
+        out = torch.empty((S * N, n_heads * d_head), dtype=torch.bfloat16, device=qkv.device)
+    _check(lib.psd_kernel_attention_bf16(_ptr(qkv), S, N, n_heads, n_kv_heads, d_head, _ptr(vT), _ptr(out), _stream()))
+    return out
+
+
+def kernel_head_confidence_bf16(y: torch.Tensor, W: torch.Tensor, scale: float, mask_id: int, scratch=None):
+    """y bf16 [rows, d], W bf16 [V, d] -> (row_sum fp32 [rows], row_arg int32 [rows])."""
+    lib = load_library()
+    rows, d = y.shape
+    V = W.shape[0]
+    if scratch is None:
+        scratch = torch.empty((int(lib.psd_kernel_head_scratch_bytes(rows, V)),), dtype=torch.uint8, device=y.device)
+    row_sum = torch.empty((rows,), dtype=torch.float32, device=y.device)
+    row_arg = torch.empty((rows,), dtype=torch.int32, device=y.device)
+    _check(lib.psd_kernel_head_confidence_bf16(_ptr(y), _ptr(W), rows, V, d, float(scale), int(mask_id), _ptr(scratch),
+                                               _ptr(row_sum), _ptr(row_arg), _stream()))
+    return row_sum, row_arg

@@ -184,6 +184,7 @@ int32_t psd_create(const psd_model_config *cfg, const psd_weights *w, psd_handle
 int32_t psd_destroy(psd_handle *h) {
     if (!h) return PSD_OK;
     if (h->host_counts) (void)hipHostFree(h->host_counts);
+    for (hipEvent_t e : h->probe.ev) (void)hipEventDestroy(e);
     delete h;
     return PSD_OK;
 }
@@ -191,6 +192,41 @@ int32_t psd_destroy(psd_handle *h) {
 int32_t psd_debug_set_plain(psd_handle *h, int32_t mask) {
     if (!h) PSD_FAIL(PSD_ERR_INVALID_ARG, "handle is NULL");
     h->plain_mask = mask;
+    return PSD_OK;
+}
+
+int32_t psd_probe_begin(psd_handle *h, int32_t epilogue, int32_t tile, int32_t max_launches) {
+    if (!h) PSD_FAIL(PSD_ERR_INVALID_ARG, "handle is NULL");
+    if (epilogue < 0 || epilogue > 3 || tile < 0 || tile > 1 || max_launches < 1 || max_launches > (1 << 20))
+        PSD_FAIL(PSD_ERR_INVALID_ARG, "bad probe arguments");
+    psd_handle::Probe &pr = h->probe;
+    while (pr.ev.size() < (size_t)max_launches * 2) {
+        hipEvent_t e;
+        PSD_HIP(hipEventCreate(&e));
+        pr.ev.push_back(e);
+    }
+    pr.enabled = 1;
+    pr.epi = epilogue;
+    pr.tile = tile;
+    pr.used = 0;
+    pr.flops = 0.0;
+    return PSD_OK;
+}
+
+int32_t psd_probe_end(psd_handle *h, double *total_ms, int64_t *launches, double *flops) {
+    if (!h || !total_ms || !launches || !flops) PSD_FAIL(PSD_ERR_INVALID_ARG, "NULL argument");
+    psd_handle::Probe &pr = h->probe;
+    pr.enabled = 0;
+    double ms = 0.0;
+    for (size_t i = 0; i + 1 < pr.used; i += 2) {
+        PSD_HIP(hipEventSynchronize(pr.ev[i + 1]));
+        float t = 0.f;
+        PSD_HIP(hipEventElapsedTime(&t, pr.ev[i], pr.ev[i + 1]));
+        ms += t;
+    }
+    *total_ms = ms;
+    *launches = (int64_t)(pr.used / 2);
+    *flops = pr.flops;
     return PSD_OK;
 }
 
@@ -384,6 +420,50 @@ int32_t psd_decode_block(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, i
         stats[b].tokens_postverify += ds[PSD_DEVSTAT_POST];
         for (int i = 0; i <= PSD_MAX_BLOCK; ++i) stats[b].depth_hist[i] += ds[PSD_DEVSTAT_HIST + i];
     }
+    PSD_HIP(hipGetLastError());
+    return PSD_OK;
+}
+
+// ---- kernel-level hooks: the same launchers the forward uses, on caller-provided buffers ----
+
+int32_t psd_kernel_gemm_bf16(const void *A, const void *W, const void *W2, int64_t M, int32_t Nout, int32_t Kin,
+                             int32_t epilogue, const float *bias, void *out, float *resid, int32_t ldo, void *stream) {
+    if (!A || !W || M < 1 || M > (1 << 30) || Nout < 1 || Kin < 1) PSD_FAIL(PSD_ERR_INVALID_ARG, "bad GEMM arguments");
+    if (Kin % 64 || Nout % 64) PSD_FAIL(PSD_ERR_SHAPE, "Nout and Kin must be multiples of 64");
+    if (epilogue < 0 || epilogue > 3) PSD_FAIL(PSD_ERR_INVALID_ARG, "epilogue %d", epilogue);
+    if (epilogue == EPI_SWIGLU && !W2) PSD_FAIL(PSD_ERR_INVALID_ARG, "SwiGLU needs the second weight");
+    if (epilogue == EPI_BIAS && !bias) PSD_FAIL(PSD_ERR_INVALID_ARG, "bias is NULL");
+    if (epilogue == EPI_RESIDUAL ? !resid : !out) PSD_FAIL(PSD_ERR_INVALID_ARG, "output is NULL");
+    if (ldo < Nout) PSD_FAIL(PSD_ERR_SHAPE, "ldo < Nout");
+    launch_gemm_bf16((const bf16_t *)A, (const bf16_t *)W, (const bf16_t *)W2, M, Nout, Kin, epilogue, bias, (bf16_t *)out,
+                     resid, ldo, (hipStream_t)stream);
+    PSD_HIP(hipGetLastError());
+    return PSD_OK;
+}
+
+int32_t psd_kernel_attention_bf16(const void *qkv, int32_t S, int32_t N, int32_t n_heads, int32_t n_kv_heads, int32_t d_head,
+                                  void *vT, void *out, void *stream) {
+    if (!qkv || !vT || !out || S < 1 || N < 1) PSD_FAIL(PSD_ERR_INVALID_ARG, "bad attention arguments");
+    if ((d_head != 64 && d_head != 128) || N % 8 || n_kv_heads < 1 || n_heads % n_kv_heads)
+        PSD_FAIL(PSD_ERR_SHAPE, "attention needs d_head 64/128, N a multiple of 8, n_heads a multiple of n_kv_heads");
+    launch_transpose_v((const bf16_t *)qkv, S, N, n_heads, n_kv_heads, d_head, (bf16_t *)vT, (hipStream_t)stream);
+    launch_attention_bf16((const bf16_t *)qkv, (const bf16_t *)vT, S, N, n_heads, n_kv_heads, d_head, (bf16_t *)out,
+                          (hipStream_t)stream);
+    PSD_HIP(hipGetLastError());
+    return PSD_OK;
+}
+
+int64_t psd_kernel_head_scratch_bytes(int32_t rows, int32_t vocab) {
+    if (rows < 1 || vocab < 2) return PSD_ERR_SHAPE;
+    return head_partial_bytes(rows, vocab);
+}
+
+int32_t psd_kernel_head_confidence_bf16(const void *y, const void *W, int32_t rows, int32_t vocab, int32_t d, float scale,
+                                        int32_t mask_id, void *scratch, float *row_sum, int32_t *row_arg, void *stream) {
+    if (!y || !W || !scratch || !row_sum || !row_arg || rows < 1 || vocab < 2) PSD_FAIL(PSD_ERR_INVALID_ARG, "bad arguments");
+    if (d % 64) PSD_FAIL(PSD_ERR_SHAPE, "d must be a multiple of 64");
+    launch_head_confidence_bf16((const bf16_t *)y, (const bf16_t *)W, rows, vocab, d, scale, mask_id, scratch, row_sum,
+                                row_arg, (hipStream_t)stream);
     PSD_HIP(hipGetLastError());
     return PSD_OK;
 }

@@ -27,10 +27,9 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int BQ = 128;    // queries per workgroup
 constexpr int BKV = 64;    // keys per stage
 
-union Frag {
-    uint4 u;
-    bf16x8 v;
-};
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 u) { return __builtin_bit_cast(bf16x8, u); }
 
 template <int DH>
 __global__ __launch_bounds__(256) void attention_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ vT, int N,
@@ -56,47 +55,54 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t *__restrict
     const uint4 zero4 = make_uint4(0, 0, 0, 0);
 
     // Q fragments: lane (q = lrow, half) holds Q[q][16*ks + 8*half .. +7]
-    Frag qf[KS];
+    bf16x8 qf[KS];
     {
         const int q = q0 + wave * 32 + lrow;
         const bf16_t *qp = seq + (int64_t)q * row_w + head * DH;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-            qf[ks].u = (q < N) ? *reinterpret_cast<const uint4 *>(qp + ks * 16 + lhalf * 8) : zero4;
+        for (int ks = 0; ks < KS; ++ks) {
+            u32x4 t = {0u, 0u, 0u, 0u};
+            if (q < N) t = *reinterpret_cast<const u32x4 *>(qp + ks * 16 + lhalf * 8);
+            qf[ks] = as_bf16x8(t);
+        }
     }
 
     uint4 rk[KCH], rv[VCH];
-    auto load_global = [&](int k0) {
-#pragma unroll
-        for (int i = 0; i < KCH; ++i) {
-            const int qd = i * 256 + tid, r = qd / (DH / 8), c = qd % (DH / 8);
-            const int key = k0 + r;
-            rk[i] = (key < N) ? *reinterpret_cast<const uint4 *>(seq + (int64_t)key * row_w + (n_heads + kvh) * DH + c * 8)
-                              : zero4;
-        }
-#pragma unroll
-        for (int i = 0; i < VCH; ++i) {
-            const int qd = i * 256 + tid, r = qd >> 3, c = qd & 7;
-            const int key = k0 + c * 8;
-            rv[i] = (key < N) ? *reinterpret_cast<const uint4 *>(vt_head + (int64_t)r * N + key) : zero4;
-        }
-    };
-    auto store_lds = [&](int stage) {
-        unsigned char *sk = lds + stage * STAGE, *sv = sk + K_BYTES;
-#pragma unroll
-        for (int i = 0; i < KCH; ++i) {
-            const int qd = i * 256 + tid, r = qd / (DH / 8), c = qd % (DH / 8);
-            *reinterpret_cast<uint4 *>(sk + r * KROW + ((c ^ (r & 7)) << 4)) = rk[i];
-        }
-#pragma unroll
-        for (int i = 0; i < VCH; ++i) {
-            const int qd = i * 256 + tid, r = qd >> 3, c = qd & 7;
-            const int kg = c >> 1, u = c & 1;   // 16-key group, which 8-key half of it this chunk is
-            // keys 4w..4w+3 of that half go to chunk (2*kg + w), at 8-byte slot u
-            *reinterpret_cast<uint2 *>(sv + r * VROW + (((kg * 2 + 0) ^ (r & 7)) << 4) + u * 8) = make_uint2(rv[i].x, rv[i].y);
-            *reinterpret_cast<uint2 *>(sv + r * VROW + (((kg * 2 + 1) ^ (r & 7)) << 4) + u * 8) = make_uint2(rv[i].z, rv[i].w);
-        }
-    };
+// global -> registers for the key tile starting at k0 (keys past the end read as zero)
+#define PSD_ATT_LOAD_GLOBAL(k0)                                                                                  \
+    {                                                                                                            \
+        _Pragma("unroll") for (int i = 0; i < KCH; ++i) {                                                        \
+            const int qd = i * 256 + tid, r = qd / (DH / 8), c = qd % (DH / 8);                                  \
+            const int key = (k0) + r;                                                                            \
+            rk[i] = zero4;                                                                                       \
+            if (key < N)                                                                                         \
+                rk[i] = *reinterpret_cast<const uint4 *>(seq + (int64_t)key * row_w + (n_heads + kvh) * DH + c * 8); \
+        }                                                                                                        \
+        _Pragma("unroll") for (int i = 0; i < VCH; ++i) {                                                        \
+            const int qd = i * 256 + tid, r = qd >> 3, c = qd & 7;                                               \
+            const int key = (k0) + c * 8;                                                                        \
+            rv[i] = zero4;                                                                                       \
+            if (key < N) rv[i] = *reinterpret_cast<const uint4 *>(vt_head + (int64_t)r * N + key);               \
+        }                                                                                                        \
+    }
+// registers -> LDS.  V^T chunk c holds keys 8c..8c+7 of a row; keys 4w..4w+3 of each 8-key half u of a
+// 16-key group kg go to chunk (2*kg + w), 8-byte slot u: the permuted key order of the second MFMA
+#define PSD_ATT_STORE_LDS(stage)                                                                                 \
+    {                                                                                                            \
+        unsigned char *sk_ = lds + (stage) * STAGE, *sv_ = sk_ + K_BYTES;                                        \
+        _Pragma("unroll") for (int i = 0; i < KCH; ++i) {                                                        \
+            const int qd = i * 256 + tid, r = qd / (DH / 8), c = qd % (DH / 8);                                  \
+            *reinterpret_cast<uint4 *>(sk_ + r * KROW + ((c ^ (r & 7)) << 4)) = rk[i];                           \
+        }                                                                                                        \
+        _Pragma("unroll") for (int i = 0; i < VCH; ++i) {                                                        \
+            const int qd = i * 256 + tid, r = qd >> 3, c = qd & 7;                                               \
+            const int kg = c >> 1, u = c & 1;                                                                    \
+            *reinterpret_cast<uint2 *>(sv_ + r * VROW + (((kg * 2 + 0) ^ (r & 7)) << 4) + u * 8) =               \
+                make_uint2(rv[i].x, rv[i].y);                                                                    \
+            *reinterpret_cast<uint2 *>(sv_ + r * VROW + (((kg * 2 + 1) ^ (r & 7)) << 4) + u * 8) =               \
+                make_uint2(rv[i].z, rv[i].w);                                                                    \
+        }                                                                                                        \
+    }
 
     floatx16 acc_o[CT];
 #pragma unroll
@@ -107,13 +113,13 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t *__restrict
     const float sl2 = 1.4426950408889634f / sqrtf((float)DH);   // softmax scale folded into exp2
 
     const int n_tiles = (N + BKV - 1) / BKV;
-    load_global(0);
-    store_lds(0);
+    PSD_ATT_LOAD_GLOBAL(0)
+    PSD_ATT_STORE_LDS(0)
     __syncthreads();
 
     for (int t = 0; t < n_tiles; ++t) {
         const int stage = t & 1, k0 = t * BKV;
-        if (t + 1 < n_tiles) load_global(k0 + BKV);
+        if (t + 1 < n_tiles) PSD_ATT_LOAD_GLOBAL(k0 + BKV)
         const unsigned char *sk = lds + stage * STAGE, *sv = sk + K_BYTES;
 
         // scores, transposed: acc_s[kt][v] <-> key 32*kt + 8*(v/4) + 4*half + v%4, query lrow
@@ -127,7 +133,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t *__restrict
             for (int ks = 0; ks < KS; ++ks) {
                 const int c = ks * 2 + lhalf;
                 const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(sk + r * KROW + ((c ^ (r & 7)) << 4));
-                acc_s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks].v, acc_s[kt], 0, 0, 0);
+                acc_s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc_s[kt], 0, 0, 0);
             }
         }
         // keys past the end of the sequence do not exist
@@ -150,7 +156,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t *__restrict
         const float m_new = fmaxf(m_run, mx);
         const float alpha = exp2f((m_run - m_new) * sl2);
         float psum = 0.f;
-        Frag pf[4];   // P^T as B operands, one per group of 16 keys
+        bf16x8 pf[4];   // P^T as B operands, one per group of 16 keys
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
             float p[16];
@@ -161,11 +167,12 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t *__restrict
             }
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
-                Frag &f = pf[kt * 2 + u];
-                f.u.x = pack_bf16x2(p[8 * u + 0], p[8 * u + 1]);
-                f.u.y = pack_bf16x2(p[8 * u + 2], p[8 * u + 3]);
-                f.u.z = pack_bf16x2(p[8 * u + 4], p[8 * u + 5]);
-                f.u.w = pack_bf16x2(p[8 * u + 6], p[8 * u + 7]);
+                u32x4 f;
+                f.x = pack_bf16x2(p[8 * u + 0], p[8 * u + 1]);
+                f.y = pack_bf16x2(p[8 * u + 2], p[8 * u + 3]);
+                f.z = pack_bf16x2(p[8 * u + 4], p[8 * u + 5]);
+                f.w = pack_bf16x2(p[8 * u + 6], p[8 * u + 7]);
+                pf[kt * 2 + u] = as_bf16x8(f);
             }
         }
         l_run = l_run * alpha + psum;
@@ -182,13 +189,15 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t *__restrict
                 const int r = ct * 32 + lrow;
                 const int c = kg * 2 + lhalf;
                 const bf16x8 vf = *reinterpret_cast<const bf16x8 *>(sv + r * VROW + ((c ^ (r & 7)) << 4));
-                acc_o[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kg].v, acc_o[ct], 0, 0, 0);
+                acc_o[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kg], acc_o[ct], 0, 0, 0);
             }
         }
-        if (t + 1 < n_tiles) store_lds(stage ^ 1);
+        if (t + 1 < n_tiles) PSD_ATT_STORE_LDS(stage ^ 1)
         __syncthreads();
     }
 
+#undef PSD_ATT_LOAD_GLOBAL
+#undef PSD_ATT_STORE_LDS
     // the two half-waves of a query hold disjoint key subsets of the sum
     l_run += __shfl_xor(l_run, 32, 64);
     const float inv = 1.0f / l_run;

@@ -62,8 +62,18 @@ struct Dispatch<bf16_t> {
         if (h->plain_mask & 1)
             launch_plain_gemm<bf16_t, bf16_t>(A, (const bf16_t *)W, (const bf16_t *)W2, M, Nout, Kin, epi, bias, 1.0f, out,
                                               resid, ldo, st);
-        else
+        else {
+            psd_handle::Probe &pr = h->probe;
+            const bool timed = pr.enabled && epi == pr.epi && gemm_bf16_tile(M, Nout, epi) == pr.tile &&
+                               pr.used + 2 <= pr.ev.size();
+            if (timed) (void)hipEventRecord(pr.ev[pr.used], st);
             launch_gemm_bf16(A, (const bf16_t *)W, (const bf16_t *)W2, M, Nout, Kin, epi, bias, out, resid, ldo, st);
+            if (timed) {
+                (void)hipEventRecord(pr.ev[pr.used + 1], st);
+                pr.used += 2;
+                pr.flops += 2.0 * (double)M * Nout * Kin * (epi == EPI_SWIGLU ? 2.0 : 1.0);
+            }
+        }
     }
     static void attention(psd_handle *h, bf16_t *qkv, bf16_t *vT, int S, int N, int H, int Hkv, int dh, bf16_t *out,
                           hipStream_t st) {

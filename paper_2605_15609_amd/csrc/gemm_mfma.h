@@ -84,48 +84,47 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
     uint4 ra[A_CH], rb[B_CH];
     const uint4 zero4 = make_uint4(0, 0, 0, 0);
 
-    auto load_global = [&](int k0) {
-#pragma unroll
-        for (int i = 0; i < A_CH; ++i) {
-            const int q = i * 256 + tid, r = q >> 3, c = q & 7;
-            const int m = m0 + r;
-            ra[i] = (m < M) ? *reinterpret_cast<const uint4 *>(X + (int64_t)m * Kin + k0 + c * 8) : zero4;
-        }
-#pragma unroll
-        for (int i = 0; i < B_CH; ++i) {
-            const int q = i * 256 + tid, r = q >> 3, c = q & 7;
-            const bf16_t *src = Y;
-            int n = n0 + r;
-            if (DUAL && r >= BN / 2) {
-                src = Y2;
-                n = n0 + r - BN / 2;
-            }
-            rb[i] = (r < BN && n < Nout) ? *reinterpret_cast<const uint4 *>(src + (int64_t)n * Kin + k0 + c * 8) : zero4;
-        }
-    };
-    auto store_lds = [&](int stage) {
-        unsigned char *sa = lds + stage * STAGE, *sb = sa + A_BYTES;
-#pragma unroll
-        for (int i = 0; i < A_CH; ++i) {
-            const int q = i * 256 + tid, r = q >> 3, c = q & 7;
-            *reinterpret_cast<uint4 *>(sa + swz(r, c)) = ra[i];
-        }
-#pragma unroll
-        for (int i = 0; i < B_CH; ++i) {
-            const int q = i * 256 + tid, r = q >> 3, c = q & 7;
-            if (r < BN) *reinterpret_cast<uint4 *>(sb + swz(r, c)) = rb[i];
-        }
-    };
+// global -> registers for the K-stage starting at k0 (rows past the matrix edge read as zero)
+#define PSD_GEMM_LOAD_GLOBAL(k0)                                                                              \
+    {                                                                                                         \
+        _Pragma("unroll") for (int i = 0; i < A_CH; ++i) {                                                    \
+            const int q = i * 256 + tid, r = q >> 3, c = q & 7;                                               \
+            const int m = m0 + r;                                                                             \
+            ra[i] = zero4;                                                                                    \
+            if (m < M) ra[i] = *reinterpret_cast<const uint4 *>(X + (int64_t)m * Kin + (k0) + c * 8);         \
+        }                                                                                                     \
+        _Pragma("unroll") for (int i = 0; i < B_CH; ++i) {                                                    \
+            const int q = i * 256 + tid, r = q >> 3, c = q & 7;                                               \
+            const bool second = DUAL && r >= BN / 2;                                                          \
+            const bf16_t *src = second ? Y2 : Y;                                                              \
+            const int n = second ? n0 + r - BN / 2 : n0 + r;                                                  \
+            rb[i] = zero4;                                                                                    \
+            if (r < BN && n < Nout) rb[i] = *reinterpret_cast<const uint4 *>(src + (int64_t)n * Kin + (k0) + c * 8); \
+        }                                                                                                     \
+    }
+// registers -> LDS stage
+#define PSD_GEMM_STORE_LDS(stage)                                                                             \
+    {                                                                                                         \
+        unsigned char *sa_ = lds + (stage) * STAGE, *sb_ = sa_ + A_BYTES;                                     \
+        _Pragma("unroll") for (int i = 0; i < A_CH; ++i) {                                                    \
+            const int q = i * 256 + tid, r = q >> 3, c = q & 7;                                               \
+            *reinterpret_cast<uint4 *>(sa_ + swz(r, c)) = ra[i];                                              \
+        }                                                                                                     \
+        _Pragma("unroll") for (int i = 0; i < B_CH; ++i) {                                                    \
+            const int q = i * 256 + tid, r = q >> 3, c = q & 7;                                               \
+            if (r < BN) *reinterpret_cast<uint4 *>(sb_ + swz(r, c)) = rb[i];                                  \
+        }                                                                                                     \
+    }
 
     const int nk = Kin / BK;
-    load_global(0);
-    store_lds(0);
+    PSD_GEMM_LOAD_GLOBAL(0)
+    PSD_GEMM_STORE_LDS(0)
     __syncthreads();
 
     const int lrow = lane & 31, lhalf = lane >> 5;
     for (int kt = 0; kt < nk; ++kt) {
         const int stage = kt & 1;
-        if (kt + 1 < nk) load_global((kt + 1) * BK);
+        if (kt + 1 < nk) PSD_GEMM_LOAD_GLOBAL((kt + 1) * BK)
         const unsigned char *sa = lds + stage * STAGE, *sb = sa + A_BYTES;
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
@@ -153,9 +152,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
         }
-        if (kt + 1 < nk) store_lds(stage ^ 1);
+        if (kt + 1 < nk) PSD_GEMM_STORE_LDS(stage ^ 1)
         __syncthreads();
     }
+
+#undef PSD_GEMM_LOAD_GLOBAL
+#undef PSD_GEMM_STORE_LDS
 
     if constexpr (EPI == EPI_TOP1) {
         // per column j: (max, lowest argmax, sum exp) over this tile's rows; rows ascend with (i, v)

@@ -25,6 +25,13 @@ struct psd_handle {
     int plain_mask;          // debug: bit 0 plain GEMM, bit 1 plain attention, bit 2 plain LM-head
     int32_t *host_counts;    // pinned host staging for psd_decode_block
     int host_counts_cap;
+    // optional HIP-event timing of one contraction kernel (epilogue kind + tile config)
+    struct Probe {
+        int enabled = 0, epi = -1, tile = -1;
+        std::vector<hipEvent_t> ev;     // pairs (start, stop)
+        size_t used = 0;                // events handed out
+        double flops = 0.0;             // algorithmic FLOPs of the timed launches
+    } probe;
 };
 
 void psd_set_error(const char *fmt, ...);
@@ -114,6 +121,8 @@ void launch_head_finish(const float *row_sum, const int32_t *row_arg, const int3
                         float *conf, hipStream_t st);
 
 // gemm_mfma.hip (bf16; Nout, Kin multiples of 64)
+// tile configuration the dispatcher picks for a shape (0: 128x128, 1: 256x256 workgroup tiles)
+int gemm_bf16_tile(int64_t M, int Nout, int epi);
 void launch_gemm_bf16(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int64_t M, int Nout, int Kin, int epi,
                       const float *bias, bf16_t *out, float *resid, int ldo, hipStream_t st);
 // attention_mfma.hip (bf16, d_head 64 or 128): q, k from qkv (rotary applied), values from vT
