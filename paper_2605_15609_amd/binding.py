@@ -62,7 +62,7 @@ _lib = None
 
 
 def library_path() -> str:
-    return os.path.join(_HERE, "libpsd.so")
+    return os.environ.get("PSD_LIBRARY", os.path.join(_HERE, "libpsd.so"))
 
 
 def load_library():

@@ -92,14 +92,14 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t *__restrict
         unsigned char *sk_ = lds + (stage) * STAGE, *sv_ = sk_ + K_BYTES;                                        \
         _Pragma("unroll") for (int i = 0; i < KCH; ++i) {                                                        \
             const int qd = i * 256 + tid, r = qd / (DH / 8), c = qd % (DH / 8);                                  \
-            *reinterpret_cast<uint4 *>(sk_ + r * KROW + ((c ^ (r & 7)) << 4)) = rk[i];                           \
+            *reinterpret_cast<uint4 *>(sk_ + r * KROW + ((c ^ ((r >> 1) & 7)) << 4)) = rk[i];                           \
         }                                                                                                        \
         _Pragma("unroll") for (int i = 0; i < VCH; ++i) {                                                        \
             const int qd = i * 256 + tid, r = qd >> 3, c = qd & 7;                                               \
             const int kg = c >> 1, u = c & 1;                                                                    \
-            *reinterpret_cast<uint2 *>(sv_ + r * VROW + (((kg * 2 + 0) ^ (r & 7)) << 4) + u * 8) =               \
+            *reinterpret_cast<uint2 *>(sv_ + r * VROW + (((kg * 2 + 0) ^ ((r >> 1) & 7)) << 4) + u * 8) =               \
                 make_uint2(rv[i].x, rv[i].y);                                                                    \
-            *reinterpret_cast<uint2 *>(sv_ + r * VROW + (((kg * 2 + 1) ^ (r & 7)) << 4) + u * 8) =               \
+            *reinterpret_cast<uint2 *>(sv_ + r * VROW + (((kg * 2 + 1) ^ ((r >> 1) & 7)) << 4) + u * 8) =               \
                 make_uint2(rv[i].z, rv[i].w);                                                                    \
         }                                                                                                        \
     }
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t *__restrict
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 const int c = ks * 2 + lhalf;
-                const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(sk + r * KROW + ((c ^ (r & 7)) << 4));
+                const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(sk + r * KROW + ((c ^ ((r >> 1) & 7)) << 4));
                 acc_s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc_s[kt], 0, 0, 0);
             }
         }
@@ -188,7 +188,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t *__restrict
             for (int ct = 0; ct < CT; ++ct) {
                 const int r = ct * 32 + lrow;
                 const int c = kg * 2 + lhalf;
-                const bf16x8 vf = *reinterpret_cast<const bf16x8 *>(sv + r * VROW + ((c ^ (r & 7)) << 4));
+                const bf16x8 vf = *reinterpret_cast<const bf16x8 *>(sv + r * VROW + ((c ^ ((r >> 1) & 7)) << 4));
                 acc_o[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kg], acc_o[ct], 0, 0, 0);
             }
         }

@@ -38,7 +38,9 @@ struct Top1Args {
     int cols_total;
 };
 
-__device__ __forceinline__ int swz(int row, int chunk) { return row * ROW_BYTES + ((chunk ^ (row & 7)) << 4); }
+// 64 LDS banks x 4 bytes: rows r and r+1 cover the two 128-byte halves, so the chunk slot is rotated by
+// (r >> 1): any 16 consecutive rows fetching the same logical chunk then hit 16 distinct bank groups
+__device__ __forceinline__ int swz(int row, int chunk) { return row * ROW_BYTES + ((chunk ^ ((row >> 1) & 7)) << 4); }
 
 // merge two (max, argmax, sum-exp) triples; ties go to the lower index
 __device__ __forceinline__ void top1_merge(float &b, int &a, float &s, float b2, int a2, float s2) {
@@ -47,6 +49,27 @@ __device__ __forceinline__ void top1_merge(float &b, int &a, float &s, float b2,
     if (b2 > b || (b2 == b && a2 < a)) a = a2;
     b = bn;
     s = s_new;
+}
+
+// Scheduling hint for one k-step: spread NR LDS reads (front-loaded over the first half, so they land
+// before the next k-step needs them), NW LDS writes and NV global loads evenly between NM MFMAs.
+template <int I, int NM, int NR, int NW, int NV>
+__device__ __forceinline__ void sched_mix() {
+    if constexpr (I < NM) {
+        // LDS writes cannot be reordered before LDS reads that precede them in program order, so the
+        // reads take the first half of the k-step and the writes (with the global loads that refill
+        // their registers) the second half
+        constexpr int half = (NM + 1) / 2, rest = NM - half;
+        constexpr int r = (I < half) ? ((I + 1) * NR / half - I * NR / half) : 0;
+        constexpr int J = I - half;
+        constexpr int w = (I >= half) ? ((J + 1) * NW / rest - J * NW / rest) : 0;
+        constexpr int v = (I >= half) ? ((J + 1) * NV / rest - J * NV / rest) : 0;
+        if constexpr (r > 0) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);
+        if constexpr (w > 0) __builtin_amdgcn_sched_group_barrier(0x200, w, 0);
+        if constexpr (v > 0) __builtin_amdgcn_sched_group_barrier(0x020, v, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        sched_mix<I + 1, NM, NR, NW, NV>();
+    }
 }
 
 template <int BM, int BN, int WGM, int WGN, int EPI>
@@ -60,9 +83,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
     constexpr int BN_OUT = DUAL ? BN / 2 : BN;            // output columns per tile
     constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES, STAGE = A_BYTES + B_BYTES;
     constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
-    constexpr int A_CH = BM * 8 / 256, B_CH = (BN * 8 + 255) / 256;
+    constexpr int A_CH = BM * 8 / 256, B_CH = BN * 8 / 256;
     static_assert(WGM * WGN == 4 && TM >= 1 && TN >= 1 && (!DUAL || TN % 2 == 0), "tile shape");
-    static_assert(BM * 8 % 256 == 0, "tile rows");
+    static_assert(BM % 32 == 0 && BN % 32 == 0, "tile rows come in groups of 32 (256 lanes x 16 bytes)");
 
     // XCD-aware tile id: ids i, i+8, i+16 ... land on the same XCD; give that XCD a contiguous tile range
     int pid = blockIdx.x;
@@ -81,25 +104,36 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    uint4 ra[A_CH], rb[B_CH];
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+    // Operand tiles are fetched with raw buffer loads: one per-lane byte offset (row within a 32-row
+    // group, 16-byte chunk) plus a wave-uniform offset (row group, K position) in a scalar register,
+    // so the loads need no per-load address registers, and rows past the matrix edge read as zero
+    // through the descriptor's range check instead of a branch.
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    u32x4 ra[A_CH], rb[B_CH];
+    const int rows_x = min(BM, M - m0), rows_y = min(BN_OUT, Nout - n0);
+    const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t *>(X) + (int64_t)m0 * Kin, 0, rows_x * Kin * 2, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_y = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t *>(Y) + (int64_t)n0 * Kin, 0, rows_y * Kin * 2, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc_y2 = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t *>(DUAL ? Y2 : Y) + (int64_t)n0 * Kin, 0, rows_y * Kin * 2, 0x00020000);
+    const int voff = (tid >> 3) * Kin * 2 + (tid & 7) * 16;
 
-// global -> registers for the K-stage starting at k0 (rows past the matrix edge read as zero)
-#define PSD_GEMM_LOAD_GLOBAL(k0)                                                                              \
+#ifdef PSD_EXPERIMENT_SAMEK
+#define PSD_K0(k0) 0
+#else
+#define PSD_K0(k0) (k0)
+#endif
+#define PSD_GEMM_LOAD_GLOBAL(k0_)                                                                             \
     {                                                                                                         \
-        _Pragma("unroll") for (int i = 0; i < A_CH; ++i) {                                                    \
-            const int q = i * 256 + tid, r = q >> 3, c = q & 7;                                               \
-            const int m = m0 + r;                                                                             \
-            ra[i] = zero4;                                                                                    \
-            if (m < M) ra[i] = *reinterpret_cast<const uint4 *>(X + (int64_t)m * Kin + (k0) + c * 8);         \
-        }                                                                                                     \
+        const int k0 = PSD_K0(k0_);                                                                           \
+        _Pragma("unroll") for (int i = 0; i < A_CH; ++i)                                                      \
+            ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, voff, (i * 32 * Kin + (k0)) * 2, 0);        \
         _Pragma("unroll") for (int i = 0; i < B_CH; ++i) {                                                    \
-            const int q = i * 256 + tid, r = q >> 3, c = q & 7;                                               \
-            const bool second = DUAL && r >= BN / 2;                                                          \
-            const bf16_t *src = second ? Y2 : Y;                                                              \
-            const int n = second ? n0 + r - BN / 2 : n0 + r;                                                  \
-            rb[i] = zero4;                                                                                    \
-            if (r < BN && n < Nout) rb[i] = *reinterpret_cast<const uint4 *>(src + (int64_t)n * Kin + (k0) + c * 8); \
+            if (DUAL && i * 32 >= BN / 2)                                                                     \
+                rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_y2, voff, ((i * 32 - BN / 2) * Kin + (k0)) * 2, 0); \
+            else                                                                                              \
+                rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_y, voff, (i * 32 * Kin + (k0)) * 2, 0);    \
         }                                                                                                     \
     }
 // registers -> LDS stage
@@ -108,54 +142,87 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
         unsigned char *sa_ = lds + (stage) * STAGE, *sb_ = sa_ + A_BYTES;                                     \
         _Pragma("unroll") for (int i = 0; i < A_CH; ++i) {                                                    \
             const int q = i * 256 + tid, r = q >> 3, c = q & 7;                                               \
-            *reinterpret_cast<uint4 *>(sa_ + swz(r, c)) = ra[i];                                              \
+            *reinterpret_cast<u32x4 *>(sa_ + swz(r, c)) = ra[i];                                              \
         }                                                                                                     \
         _Pragma("unroll") for (int i = 0; i < B_CH; ++i) {                                                    \
             const int q = i * 256 + tid, r = q >> 3, c = q & 7;                                               \
-            if (r < BN) *reinterpret_cast<uint4 *>(sb_ + swz(r, c)) = rb[i];                                  \
+            *reinterpret_cast<u32x4 *>(sb_ + swz(r, c)) = rb[i];                                  \
         }                                                                                                     \
     }
 
     const int nk = Kin / BK;
-    PSD_GEMM_LOAD_GLOBAL(0)
-    PSD_GEMM_STORE_LDS(0)
-    __syncthreads();
-
     const int lrow = lane & 31, lhalf = lane >> 5;
-    for (int kt = 0; kt < nk; ++kt) {
-        const int stage = kt & 1;
-        if (kt + 1 < nk) PSD_GEMM_LOAD_GLOBAL((kt + 1) * BK)
-        const unsigned char *sa = lds + stage * STAGE, *sb = sa + A_BYTES;
+
+    // LDS byte offsets of this lane's fragment rows (k-step 0); k-step kk flips the chunk index by 2*kk
+    int offa[TM], offb[TN];
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8 fa[TM], fb[TN];
-            const int c = kk * 2 + lhalf;
+    for (int i = 0; i < TM; ++i) offa[i] = (wm * WTM + i * 32 + lrow) * ROW_BYTES;
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int r = wm * WTM + i * 32 + lrow;
-                fa[i] = *reinterpret_cast<const bf16x8 *>(sa + swz(r, c));
-            }
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                int r;
-                if (DUAL) {   // first half of the subtiles: gate rows, second half: up rows of the same columns
-                    const int jj = j % (TN / 2);
-                    r = (j >= TN / 2 ? BN / 2 : 0) + wn * (WTN / 2) + jj * 32 + lrow;
-                } else {
-                    r = wn * WTN + j * 32 + lrow;
-                }
-                fb[j] = *reinterpret_cast<const bf16x8 *>(sb + swz(r, c));
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    for (int j = 0; j < TN; ++j) {
+        int r;
+        if (DUAL) {   // first half of the subtiles: gate rows, second half: up rows of the same columns
+            const int jj = j % (TN / 2);
+            r = (j >= TN / 2 ? BN / 2 : 0) + wn * (WTN / 2) + jj * 32 + lrow;
+        } else {
+            r = wn * WTN + j * 32 + lrow;
         }
-        if (kt + 1 < nk) PSD_GEMM_STORE_LDS(stage ^ 1)
-        __syncthreads();
+        offb[j] = A_BYTES + r * ROW_BYTES;
+    }
+    const int rsw = (lrow >> 1) & 7;   // swizzle key of every fragment row of this lane: rows differ by multiples of 32
+
+// fragments of k-step kk of an LDS stage into register set `set`
+#define PSD_GEMM_LOAD_FRAGS(stage, kk, set)                                                                   \
+    {                                                                                                         \
+        const unsigned char *s_ = lds + (stage) * STAGE;                                                      \
+        const int co_ = ((((kk) * 2 + lhalf) ^ rsw) << 4);                                                    \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                        \
+            fa[set][i] = *reinterpret_cast<const bf16x8 *>(s_ + offa[i] + co_);                               \
+        _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                        \
+            fb[set][j] = *reinterpret_cast<const bf16x8 *>(s_ + offb[j] + co_);                               \
+    }
+#define PSD_GEMM_MFMA(set)                                                                                    \
+    {                                                                                                         \
+        _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                        \
+            _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                    \
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0); \
     }
 
+    bf16x8 fa[2][TM], fb[2][TN];
+    constexpr int NFRAG = TM + TN, NMFMA = TM * TN;
+
+    constexpr int NLD = A_CH + B_CH;
+    PSD_GEMM_LOAD_GLOBAL(0)
+    PSD_GEMM_STORE_LDS(0)
+    PSD_GEMM_LOAD_GLOBAL(BK)
+    __syncthreads();
+    PSD_GEMM_LOAD_FRAGS(0, 0, 0)
+
+    // Per K-stage: k-steps 0 and 1 compute with the next k-step's fragments in flight; k-step 2 also
+    // parks the K-stage fetched one stage ago in the other LDS buffer and refills the staging
+    // registers with the stage after it (a global load has a whole stage to land); after the barrier
+    // k-step 3 computes while the first fragments of the next stage arrive.  The body is branch-free:
+    // the two fetches past the end of K stay inside the buffer range (or read as zero) and land in
+    // an LDS stage that is never consumed.
+    for (int kt = 0; kt < nk; ++kt) {
+        const int stage = kt & 1;
+        PSD_GEMM_LOAD_FRAGS(stage, 1, 1)
+        PSD_GEMM_MFMA(0)
+        sched_mix<0, NMFMA, NFRAG, 0, 0>();
+        PSD_GEMM_LOAD_FRAGS(stage, 2, 0)
+        PSD_GEMM_MFMA(1)
+        sched_mix<0, NMFMA, NFRAG, 0, 0>();
+        PSD_GEMM_LOAD_FRAGS(stage, 3, 1)
+        PSD_GEMM_STORE_LDS(stage ^ 1)
+        PSD_GEMM_LOAD_GLOBAL((kt + 2) * BK)
+        PSD_GEMM_MFMA(0)
+        sched_mix<0, NMFMA, NFRAG, NLD, NLD>();
+        __syncthreads();
+        PSD_GEMM_LOAD_FRAGS(stage ^ 1, 0, 0)
+        PSD_GEMM_MFMA(1)
+        sched_mix<0, NMFMA, NFRAG, 0, 0>();
+    }
+#undef PSD_GEMM_LOAD_FRAGS
+#undef PSD_GEMM_MFMA
 #undef PSD_GEMM_LOAD_GLOBAL
 #undef PSD_GEMM_STORE_LDS
 
