@@ -156,6 +156,10 @@ int32_t psd_forward_logits(psd_handle *h, const int32_t *tokens, int32_t S, int3
  * attention, bit 2 the LM-head on the plain (non-MFMA) kernels.  0 (default) = MFMA path. */
 int32_t psd_debug_set_plain(psd_handle *h, int32_t mask);
 
+/* Debug / tuning: forces the workgroup tile of the layer contractions (see psd_probe_begin
+ * for the numbering; -1 = pick per shape).  Process-wide. */
+int32_t psd_debug_force_gemm_tile(int32_t tile);
+
 /* Stage 1 commit (Eq. 1): applies pi to every sequence in place.
  *   tokens device int32 [B, N] (updated); top1/conf device [B, L] (read);
  *   transfer_mask device uint8 [B, L] (1 where committed); n_selected device int32 [B]. */
@@ -234,7 +238,7 @@ int32_t psd_kernel_head_confidence_bf16(const void *y, const void *W, int32_t ro
 
 /* Kernel timing for roofline accounting.  Between psd_probe_begin and psd_probe_end every
  * launch of the layer-contraction kernel with the given epilogue (0 store, 1 bias,
- * 2 residual, 3 SwiGLU) and workgroup tile (0: 128x128, 1: 256x256) is bracketed by HIP
+ * 2 residual, 3 SwiGLU) and workgroup tile (0: 128x128, 1: 256x256, 2: 256x128, 3: 128x64, 4: 128x192) is bracketed by HIP
  * events on the stream it is launched on (up to max_launches; later ones go untimed).
  * psd_probe_end waits for those events and returns their summed duration, the number of
  * timed launches and their algorithmic FLOPs (2*M*N*K, twice that for SwiGLU). */

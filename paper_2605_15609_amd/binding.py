@@ -98,6 +98,7 @@ def load_library():
         "psd_kernel_attention_bf16": (i32, [vp, i32, i32, i32, i32, i32, vp, vp, vp]),
         "psd_kernel_head_scratch_bytes": (i64, [i32, i32]),
         "psd_kernel_head_confidence_bf16": (i32, [vp, vp, i32, i32, i32, C.c_float, i32, vp, vp, vp, vp]),
+        "psd_debug_force_gemm_tile": (i32, [i32]),
         "psd_probe_begin": (i32, [vp, i32, i32, i32]),
         "psd_probe_end": (i32, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
         "psd_forward_work": (i32, [C.POINTER(_Config), i32, i32, i32, C.POINTER(_Work)]),
@@ -178,6 +179,17 @@ def _dev_i32(t, device):
         .to(torch.int32).contiguous()
 
 
+def pack_qkv(lt: dict) -> None:
+    """Re-homes wq | wk | wv (and bq | bk | bv) of one layer back to back in one allocation, so the
+    library can run the three projections as a single contraction.  Views keep the storage alive."""
+    w = torch.cat([lt["wq"], lt["wk"], lt["wv"]], dim=0).contiguous()
+    nq, nk = lt["wq"].shape[0], lt["wk"].shape[0]
+    lt["wq"], lt["wk"], lt["wv"] = w[:nq], w[nq:nq + nk], w[nq + nk:]
+    if lt.get("bq") is not None:
+        b = torch.cat([lt["bq"], lt["bk"], lt["bv"]]).contiguous()
+        lt["bq"], lt["bk"], lt["bv"] = b[:nq], b[nq:nq + nk], b[nq + nk:]
+
+
 class Model:
     """Device-resident weights plus the library handle.  ``Model.from_host(host_model)``
     uploads a psd_inputs.HostModel; matrices go up in the model dtype, the rest as fp32."""
@@ -230,6 +242,7 @@ class Model:
                     lt[k] = None
                 else:
                     lt[k] = up(v, mat_dtype if v.ndim == 2 else torch.float32)
+            pack_qkv(lt)
             layers.append(lt)
         return cls(shape, host_model.max_seq, tensors, layers, device)
 

@@ -102,9 +102,17 @@ int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t 
     for (const psd_handle::Layer &lw : h->layers) {
         launch_rmsnorm<T>(hbuf, ntok, d, lw.attn_norm, c.rms_eps, a, st);
         const int epi_qkv = c.qkv_bias ? EPI_BIAS : EPI_STORE;
-        Dispatch<T>::gemm(h, a, lw.wq, nullptr, ntok, H * dh, d, epi_qkv, lw.bq, qkv, nullptr, qkv_w, st);
-        Dispatch<T>::gemm(h, a, lw.wk, nullptr, ntok, Hkv * dh, d, epi_qkv, lw.bk, qkv + H * dh, nullptr, qkv_w, st);
-        Dispatch<T>::gemm(h, a, lw.wv, nullptr, ntok, Hkv * dh, d, epi_qkv, lw.bv, qkv + (H + Hkv) * dh, nullptr, qkv_w, st);
+        // one launch when wq | wk | wv (and the biases) sit back to back in memory, as one [qkv_w, d] matrix
+        const T *wq = (const T *)lw.wq, *wk = (const T *)lw.wk, *wv = (const T *)lw.wv;
+        const bool fused = wk == wq + (int64_t)H * dh * d && wv == wk + (int64_t)Hkv * dh * d &&
+                           (!c.qkv_bias || (lw.bk == lw.bq + H * dh && lw.bv == lw.bk + Hkv * dh));
+        if (fused) {
+            Dispatch<T>::gemm(h, a, wq, nullptr, ntok, qkv_w, d, epi_qkv, lw.bq, qkv, nullptr, qkv_w, st);
+        } else {
+            Dispatch<T>::gemm(h, a, wq, nullptr, ntok, H * dh, d, epi_qkv, lw.bq, qkv, nullptr, qkv_w, st);
+            Dispatch<T>::gemm(h, a, wk, nullptr, ntok, Hkv * dh, d, epi_qkv, lw.bk, qkv + H * dh, nullptr, qkv_w, st);
+            Dispatch<T>::gemm(h, a, wv, nullptr, ntok, Hkv * dh, d, epi_qkv, lw.bv, qkv + (H + Hkv) * dh, nullptr, qkv_w, st);
+        }
         launch_rope<T>(qkv, ntok, N, H, Hkv, dh, h->rope_cos, h->rope_sin, st);
         Dispatch<T>::attention(h, qkv, vT, S, N, H, Hkv, dh, o, st);
         Dispatch<T>::gemm(h, o, lw.wo, nullptr, ntok, d, H * dh, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, st);

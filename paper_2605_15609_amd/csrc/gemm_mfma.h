@@ -3,9 +3,9 @@
 // form), the natural MFMA feed: every lane fetches 8 consecutive k (16 bytes) of one row.
 //
 // Tiling: a workgroup of 4 wavefronts owns a BM x BN tile; K advances 64 at a time through
-// a double-buffered LDS stage (global -> registers -> LDS, one barrier per step).  LDS rows
-// are 128 bytes; the 16-byte chunk c of row r sits at chunk slot c ^ (r & 7), so the 32
-// rows a wavefront touches per fetch spread over all banks.  Workgroup ids are remapped so
+// a double-buffered LDS stage filled by direct global -> LDS loads, one barrier per stage.
+// LDS rows are 128 bytes; the 16-byte chunk c of row r sits at chunk slot c ^ ((r >> 1) & 7),
+// so the 32 rows a wavefront touches per fragment fetch spread over all 64 banks.  Workgroup ids are remapped so
 // that each of the 8 XCDs (which receive consecutive ids round-robin) works on a compact
 // range of tiles and its private L2 sees the operand reuse.
 //
@@ -83,7 +83,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
     constexpr int BN_OUT = DUAL ? BN / 2 : BN;            // output columns per tile
     constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES, STAGE = A_BYTES + B_BYTES;
     constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
-    constexpr int A_CH = BM * 8 / 256, B_CH = BN * 8 / 256;
     static_assert(WGM * WGN == 4 && TM >= 1 && TN >= 1 && (!DUAL || TN % 2 == 0), "tile shape");
     static_assert(BM % 32 == 0 && BN % 32 == 0, "tile rows come in groups of 32 (256 lanes x 16 bytes)");
 
@@ -104,12 +103,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // Operand tiles are fetched with raw buffer loads: one per-lane byte offset (row within a 32-row
-    // group, 16-byte chunk) plus a wave-uniform offset (row group, K position) in a scalar register,
-    // so the loads need no per-load address registers, and rows past the matrix edge read as zero
-    // through the descriptor's range check instead of a branch.
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    u32x4 ra[A_CH], rb[B_CH];
+    // Operand tiles go from global memory straight into LDS (buffer_load ... lds): no staging
+    // registers and no ds_write traffic on the wavefronts' issue ports.  One such instruction moves
+    // 64 lanes x 16 bytes = 8 tile rows x 128 bytes into 1 KB of consecutive LDS, lane l landing at
+    // offset 16*l, i.e. row l/8, chunk slot l%8.  The XOR swizzle therefore lives on the global
+    // side: the lane fetches logical chunk (l%8) ^ key(row), key(row) = (row >> 1) & 7.  Row groups
+    // are dealt to the 4 wavefronts round-robin (group g = 4*j + wave), which makes the key a
+    // per-lane constant: ((wave & 1) * 4 + l/16) & 7.  The per-lane byte offset is one VGPR; the
+    // group and K position are wave-uniform and ride in a scalar offset.  Rows past the matrix edge
+    // are rejected by the descriptor's range check (they only feed outputs that are never stored).
     const int rows_x = min(BM, M - m0), rows_y = min(BN_OUT, Nout - n0);
     const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<bf16_t *>(X) + (int64_t)m0 * Kin, 0, rows_x * Kin * 2, 0x00020000);
@@ -117,37 +119,35 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
         const_cast<bf16_t *>(Y) + (int64_t)n0 * Kin, 0, rows_y * Kin * 2, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrc_y2 = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<bf16_t *>(DUAL ? Y2 : Y) + (int64_t)n0 * Kin, 0, rows_y * Kin * 2, 0x00020000);
-    const int voff = (tid >> 3) * Kin * 2 + (tid & 7) * 16;
+    const int uwave = __builtin_amdgcn_readfirstlane(wave);
+    const int dma_key = (((uwave & 1) << 2) + (lane >> 4)) & 7;
+    const int voff = (lane >> 3) * Kin * 2 + (((lane & 7) ^ dma_key) << 4);
+    constexpr int GA = BM / 8 / 4, GB = BN / 8 / 4;   // row groups per wavefront, A and B tile
+    typedef __attribute__((address_space(3))) void lds_void;
 
-#ifdef PSD_EXPERIMENT_SAMEK
-#define PSD_K0(k0) 0
-#else
-#define PSD_K0(k0) (k0)
-#endif
-#define PSD_GEMM_LOAD_GLOBAL(k0_)                                                                             \
+// global -> LDS stage, K position k0
+#define PSD_GEMM_DMA(stage, k0)                                                                               \
     {                                                                                                         \
-        const int k0 = PSD_K0(k0_);                                                                           \
-        _Pragma("unroll") for (int i = 0; i < A_CH; ++i)                                                      \
-            ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, voff, (i * 32 * Kin + (k0)) * 2, 0);        \
-        _Pragma("unroll") for (int i = 0; i < B_CH; ++i) {                                                    \
-            if (DUAL && i * 32 >= BN / 2)                                                                     \
-                rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_y2, voff, ((i * 32 - BN / 2) * Kin + (k0)) * 2, 0); \
+        unsigned char *sa_ = lds + (stage) * STAGE + uwave * 1024, *sb_ = sa_ + A_BYTES;                      \
+        _Pragma("unroll") for (int j = 0; j < GA; ++j)                                                        \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, (lds_void *)(sa_ + j * 4096), 16, voff,          \
+                                                     ((j * 4 + uwave) * 8 * Kin + (k0)) * 2, 0, 0);           \
+        _Pragma("unroll") for (int j = 0; j < GB; ++j) {                                                      \
+            if (DUAL && j * 32 >= BN / 2)                                                                     \
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_y2, (lds_void *)(sb_ + j * 4096), 16, voff,     \
+                                                         (((j * 4 + uwave) * 8 - BN / 2) * Kin + (k0)) * 2, 0, 0); \
             else                                                                                              \
-                rb[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_y, voff, (i * 32 * Kin + (k0)) * 2, 0);    \
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_y, (lds_void *)(sb_ + j * 4096), 16, voff,      \
+                                                         ((j * 4 + uwave) * 8 * Kin + (k0)) * 2, 0, 0);       \
         }                                                                                                     \
     }
-// registers -> LDS stage
-#define PSD_GEMM_STORE_LDS(stage)                                                                             \
+// every DMA of this wavefront has landed; then all wavefronts agree (s_barrier), and the compiler must
+// not move LDS accesses across the point
+#define PSD_GEMM_STAGE_SYNC()                                                                                 \
     {                                                                                                         \
-        unsigned char *sa_ = lds + (stage) * STAGE, *sb_ = sa_ + A_BYTES;                                     \
-        _Pragma("unroll") for (int i = 0; i < A_CH; ++i) {                                                    \
-            const int q = i * 256 + tid, r = q >> 3, c = q & 7;                                               \
-            *reinterpret_cast<u32x4 *>(sa_ + swz(r, c)) = ra[i];                                              \
-        }                                                                                                     \
-        _Pragma("unroll") for (int i = 0; i < B_CH; ++i) {                                                    \
-            const int q = i * 256 + tid, r = q >> 3, c = q & 7;                                               \
-            *reinterpret_cast<u32x4 *>(sb_ + swz(r, c)) = rb[i];                                  \
-        }                                                                                                     \
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                                      \
+        __builtin_amdgcn_s_barrier();                                                                         \
+        asm volatile("" ::: "memory");                                                                        \
     }
 
     const int nk = Kin / BK;
@@ -190,41 +190,37 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
     bf16x8 fa[2][TM], fb[2][TN];
     constexpr int NFRAG = TM + TN, NMFMA = TM * TN;
 
-    constexpr int NLD = A_CH + B_CH;
-    PSD_GEMM_LOAD_GLOBAL(0)
-    PSD_GEMM_STORE_LDS(0)
-    PSD_GEMM_LOAD_GLOBAL(BK)
-    __syncthreads();
+    constexpr int NLD = GA + GB;
+    PSD_GEMM_DMA(0, 0)
+    PSD_GEMM_STAGE_SYNC()
     PSD_GEMM_LOAD_FRAGS(0, 0, 0)
 
-    // Per K-stage: k-steps 0 and 1 compute with the next k-step's fragments in flight; k-step 2 also
-    // parks the K-stage fetched one stage ago in the other LDS buffer and refills the staging
-    // registers with the stage after it (a global load has a whole stage to land); after the barrier
-    // k-step 3 computes while the first fragments of the next stage arrive.  The body is branch-free:
-    // the two fetches past the end of K stay inside the buffer range (or read as zero) and land in
-    // an LDS stage that is never consumed.
+    // Per K-stage: the DMA of the next stage goes out during k-step 0, into the buffer every wavefront
+    // left at the last barrier, and has the rest of the stage to land.  k-steps 0..2 compute with the
+    // next k-step's fragments in flight; after the stage barrier k-step 3 computes while the first
+    // fragments of the next stage arrive.  The body is branch-free: the fetch past the end of K stays
+    // inside the buffer range (or is rejected) and lands in a stage that is never consumed.
     for (int kt = 0; kt < nk; ++kt) {
         const int stage = kt & 1;
         PSD_GEMM_LOAD_FRAGS(stage, 1, 1)
+        PSD_GEMM_DMA(stage ^ 1, (kt + 1) * BK)
         PSD_GEMM_MFMA(0)
-        sched_mix<0, NMFMA, NFRAG, 0, 0>();
+        sched_mix<0, NMFMA, NFRAG, 0, NLD>();
         PSD_GEMM_LOAD_FRAGS(stage, 2, 0)
         PSD_GEMM_MFMA(1)
         sched_mix<0, NMFMA, NFRAG, 0, 0>();
         PSD_GEMM_LOAD_FRAGS(stage, 3, 1)
-        PSD_GEMM_STORE_LDS(stage ^ 1)
-        PSD_GEMM_LOAD_GLOBAL((kt + 2) * BK)
         PSD_GEMM_MFMA(0)
-        sched_mix<0, NMFMA, NFRAG, NLD, NLD>();
-        __syncthreads();
+        sched_mix<0, NMFMA, NFRAG, 0, 0>();
+        PSD_GEMM_STAGE_SYNC()
         PSD_GEMM_LOAD_FRAGS(stage ^ 1, 0, 0)
         PSD_GEMM_MFMA(1)
         sched_mix<0, NMFMA, NFRAG, 0, 0>();
     }
 #undef PSD_GEMM_LOAD_FRAGS
 #undef PSD_GEMM_MFMA
-#undef PSD_GEMM_LOAD_GLOBAL
-#undef PSD_GEMM_STORE_LDS
+#undef PSD_GEMM_DMA
+#undef PSD_GEMM_STAGE_SYNC
 
     if constexpr (EPI == EPI_TOP1) {
         // per column j: (max, lowest argmax, sum exp) over this tile's rows; rows ascend with (i, v)

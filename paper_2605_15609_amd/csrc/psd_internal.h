@@ -121,8 +121,10 @@ void launch_head_finish(const float *row_sum, const int32_t *row_arg, const int3
                         float *conf, hipStream_t st);
 
 // gemm_mfma.hip (bf16; Nout, Kin multiples of 64)
-// tile configuration the dispatcher picks for a shape (0: 128x128, 1: 256x256 workgroup tiles)
+// tile configuration the dispatcher picks for a shape (0: 128x128, 1: 256x256, 2: 256x128, 3: 128x64,
+// 4: 128x192 workgroup tiles)
 int gemm_bf16_tile(int64_t M, int Nout, int epi);
+void gemm_bf16_force_tile(int tile);   // debug: -1 = automatic
 void launch_gemm_bf16(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int64_t M, int Nout, int Kin, int epi,
                       const float *bias, bf16_t *out, float *resid, int ldo, hipStream_t st);
 // attention_mfma.hip (bf16, d_head 64 or 128): q, k from qkv (rotary applied), values from vT

@@ -8,7 +8,7 @@ import numpy as np
 import torch
 
 import psd_inputs as inp
-from .binding import Model
+from .binding import Model, pack_qkv
 
 
 def synthetic_model(shape: "inp.ModelShape", max_seq: int, device: str = "cuda:0", threads: int = 8) -> Model:
@@ -34,6 +34,8 @@ def synthetic_model(shape: "inp.ModelShape", max_seq: int, device: str = "cuda:0
                     tensors[name] = t
                 else:
                     layers[l][name] = t
+    for lt in layers:
+        pack_qkv(lt)
     cos, sin = inp.rope_tables(shape, max_seq)
     tensors["rope_cos"], tensors["rope_sin"] = up(cos), up(sin)
     return Model(shape, max_seq, tensors, layers, device)
