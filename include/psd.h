@@ -238,7 +238,8 @@ int32_t psd_kernel_head_confidence_bf16(const void *y, const void *W, int32_t ro
 
 /* Kernel timing for roofline accounting.  Between psd_probe_begin and psd_probe_end every
  * launch of the layer-contraction kernel with the given epilogue (0 store, 1 bias,
- * 2 residual, 3 SwiGLU) and workgroup tile (0: 128x128, 1: 256x256, 2: 256x128, 3: 128x64, 4: 128x192) is bracketed by HIP
+ * 2 residual, 3 SwiGLU) and workgroup tile (0: 128x128, 1: 256x256, 2: 256x128, 3: 128x64, 4: 128x192
+ * on a 2-stage LDS ring; 5: 128x64, 6: 128x128, 7: 64x64 on a 4-stage ring) is bracketed by HIP
  * events on the stream it is launched on (up to max_launches; later ones go untimed).
  * psd_probe_end waits for those events and returns their summed duration, the number of
  * timed launches and their algorithmic FLOPs (2*M*N*K, twice that for SwiGLU). */

@@ -202,7 +202,7 @@ int32_t psd_debug_force_gemm_tile(int32_t tile) {
 
 int32_t psd_probe_begin(psd_handle *h, int32_t epilogue, int32_t tile, int32_t max_launches) {
     if (!h) PSD_FAIL(PSD_ERR_INVALID_ARG, "handle is NULL");
-    if (epilogue < 0 || epilogue > 3 || tile < 0 || tile > 4 || max_launches < 1 || max_launches > (1 << 20))
+    if (epilogue < 0 || epilogue > 3 || tile < 0 || tile > 7 || max_launches < 1 || max_launches > (1 << 20))
         PSD_FAIL(PSD_ERR_INVALID_ARG, "bad probe arguments");
     psd_handle::Probe &pr = h->probe;
     while (pr.ev.size() < (size_t)max_launches * 2) {

@@ -3,7 +3,7 @@
 // form), the natural MFMA feed: every lane fetches 8 consecutive k (16 bytes) of one row.
 //
 // Tiling: a workgroup of 4 wavefronts owns a BM x BN tile; K advances 64 at a time through
-// a double-buffered LDS stage filled by direct global -> LDS loads, one barrier per stage.
+// a ring of NSTAGE LDS stages filled by direct global -> LDS loads, one barrier per stage.
 // LDS rows are 128 bytes; the 16-byte chunk c of row r sits at chunk slot c ^ ((r >> 1) & 7),
 // so the 32 rows a wavefront touches per fragment fetch spread over all 64 banks.  Workgroup ids are remapped so
 // that each of the 8 XCDs (which receive consecutive ids round-robin) works on a compact
@@ -72,7 +72,7 @@ __device__ __forceinline__ void sched_mix() {
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI>
+template <int BM, int BN, int WGM, int WGN, int EPI, int NSTAGE>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Y,
                                                         const bf16_t *__restrict__ Y2, int M, int Nout, int Kin,
                                                         const float *__restrict__ bias, bf16_t *__restrict__ out,
@@ -123,6 +123,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
     const int dma_key = (((uwave & 1) << 2) + (lane >> 4)) & 7;
     const int voff = (lane >> 3) * Kin * 2 + (((lane & 7) ^ dma_key) << 4);
     constexpr int GA = BM / 8 / 4, GB = BN / 8 / 4;   // row groups per wavefront, A and B tile
+    constexpr int NLD = GA + GB;                      // DMA instructions per wavefront per stage
     typedef __attribute__((address_space(3))) void lds_void;
 
 // global -> LDS stage, K position k0
@@ -141,11 +142,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
                                                          ((j * 4 + uwave) * 8 * Kin + (k0)) * 2, 0, 0);       \
         }                                                                                                     \
     }
-// every DMA of this wavefront has landed; then all wavefronts agree (s_barrier), and the compiler must
+// the oldest DMA stage of this wavefront has landed (the NSTAGE-2 younger ones may still fly); then all wavefronts agree (s_barrier), and the compiler must
 // not move LDS accesses across the point
 #define PSD_GEMM_STAGE_SYNC()                                                                                 \
     {                                                                                                         \
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                                      \
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 2) * NLD) : "memory");                             \
         __builtin_amdgcn_s_barrier();                                                                         \
         asm volatile("" ::: "memory");                                                                        \
     }
@@ -190,33 +191,38 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
     bf16x8 fa[2][TM], fb[2][TN];
     constexpr int NFRAG = TM + TN, NMFMA = TM * TN;
 
-    constexpr int NLD = GA + GB;
-    PSD_GEMM_DMA(0, 0)
+    static_assert(NSTAGE >= 2 && (NSTAGE - 2) * NLD <= 63, "DMA groups in flight must fit the vmcnt counter");
+#pragma unroll
+    for (int p = 0; p < NSTAGE - 1; ++p) PSD_GEMM_DMA(p, p * BK)
     PSD_GEMM_STAGE_SYNC()
     PSD_GEMM_LOAD_FRAGS(0, 0, 0)
 
-    // Per K-stage: the DMA of the next stage goes out during k-step 0, into the buffer every wavefront
-    // left at the last barrier, and has the rest of the stage to land.  k-steps 0..2 compute with the
-    // next k-step's fragments in flight; after the stage barrier k-step 3 computes while the first
-    // fragments of the next stage arrive.  The body is branch-free: the fetch past the end of K stays
-    // inside the buffer range (or is rejected) and lands in a stage that is never consumed.
+    // Per K-stage: the DMA of stage kt+NSTAGE-1 goes out during k-step 0, into the ring slot every
+    // wavefront left at the last barrier, and has NSTAGE-1 stages to land.  k-steps 0..2 compute with
+    // the next k-step's fragments in flight; after the stage barrier k-step 3 computes while the first
+    // fragments of the next stage arrive.  The body is branch-free: fetches past the end of K stay
+    // inside the buffer range (or are rejected) and land in ring slots that are never consumed.
+    int cur = 0;
     for (int kt = 0; kt < nk; ++kt) {
-        const int stage = kt & 1;
-        PSD_GEMM_LOAD_FRAGS(stage, 1, 1)
-        PSD_GEMM_DMA(stage ^ 1, (kt + 1) * BK)
+        const int nxt = (cur + 1 == NSTAGE) ? 0 : cur + 1;
+        const int fill = (cur == 0) ? NSTAGE - 1 : cur - 1;
+        PSD_GEMM_LOAD_FRAGS(cur, 1, 1)
+        PSD_GEMM_DMA(fill, (kt + NSTAGE - 1) * BK)
         PSD_GEMM_MFMA(0)
         sched_mix<0, NMFMA, NFRAG, 0, NLD>();
-        PSD_GEMM_LOAD_FRAGS(stage, 2, 0)
+        PSD_GEMM_LOAD_FRAGS(cur, 2, 0)
         PSD_GEMM_MFMA(1)
         sched_mix<0, NMFMA, NFRAG, 0, 0>();
-        PSD_GEMM_LOAD_FRAGS(stage, 3, 1)
+        PSD_GEMM_LOAD_FRAGS(cur, 3, 1)
         PSD_GEMM_MFMA(0)
         sched_mix<0, NMFMA, NFRAG, 0, 0>();
         PSD_GEMM_STAGE_SYNC()
-        PSD_GEMM_LOAD_FRAGS(stage ^ 1, 0, 0)
+        PSD_GEMM_LOAD_FRAGS(nxt, 0, 0)
         PSD_GEMM_MFMA(1)
         sched_mix<0, NMFMA, NFRAG, 0, 0>();
+        cur = nxt;
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no DMA may outlive the loop
 #undef PSD_GEMM_LOAD_FRAGS
 #undef PSD_GEMM_MFMA
 #undef PSD_GEMM_DMA
@@ -303,14 +309,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI>
+template <int BM, int BN, int WGM, int WGN, int EPI, int NSTAGE = 2>
 void launch_cfg(const bf16_t *X, const bf16_t *Y, const bf16_t *Y2, int M, int Nout, int Kin, const float *bias,
                 bf16_t *out, float *resid, int ldo, Top1Args t1, hipStream_t st) {
     constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (Nout + BN_OUT - 1) / BN_OUT;
     const int n_tiles = tiles_m * tiles_n;
-    constexpr int smem = 2 * (BM + BN) * ROW_BYTES;
-    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, EPI>;
+    constexpr int smem = NSTAGE * (BM + BN) * ROW_BYTES;
+    static_assert(smem <= 160 * 1024, "LDS ring exceeds the 160 KB of a CU");
+    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, EPI, NSTAGE>;
     static bool attr_done = false;
     if (!attr_done) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);

@@ -13,7 +13,7 @@ struct TileCfg {
     int bm, bn;
 };
 // index = value returned by gemm_bf16_tile
-constexpr TileCfg kTiles[] = {{128, 128}, {256, 256}, {256, 128}, {128, 64}, {128, 192}};
+constexpr TileCfg kTiles[] = {{128, 128}, {256, 256}, {256, 128}, {128, 64}, {128, 192}, {128, 64}, {128, 128}, {64, 64}};
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
 template <int EPI>
@@ -32,6 +32,19 @@ void dispatch(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int M, int Nou
         case 4:
             if constexpr (EPI != EPI_SWIGLU) {
                 launch_cfg<128, 192, 2, 2, EPI>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st);
+                break;
+            }
+            [[fallthrough]];
+        case 5:   // deep LDS ring: a lone workgroup per CU needs its fetches several stages ahead
+            if constexpr (EPI != EPI_SWIGLU) {
+                launch_cfg<128, 64, 2, 2, EPI, 4>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st);
+                break;
+            }
+            [[fallthrough]];
+        case 6: launch_cfg<128, 128, 2, 2, EPI, 4>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st); break;
+        case 7:
+            if constexpr (EPI != EPI_SWIGLU) {
+                launch_cfg<64, 64, 2, 2, EPI, 4>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st);
                 break;
             }
             [[fallthrough]];
@@ -60,7 +73,12 @@ int gemm_bf16_tile(int64_t M, int Nout, int epi) {
     if (dual) return t256 >= 128 ? 1 : 0;
     if (t256 >= 512 && epi != EPI_RESIDUAL) return 1;
     const int64_t t128 = ((M + 127) / 128) * ((cols + 127) / 128);
-    if (t128 <= 256 + 64 && Nout % 64 == 0) return 3;
+    const int64_t t12864 = ((M + 127) / 128) * ((cols + 63) / 64);
+    if (t128 <= 256) {   // at most one 128x128 workgroup per CU: latency-bound, use the deep LDS ring
+        if (t12864 <= 128) return 7;
+        return t12864 <= 256 ? 5 : 6;
+    }
+    if (t128 <= 320) return 3;
     if (epi != EPI_RESIDUAL && Nout % 192 == 0 && t128 >= 1024) return 4;
     return 0;
 }

@@ -122,7 +122,7 @@ void launch_head_finish(const float *row_sum, const int32_t *row_arg, const int3
 
 // gemm_mfma.hip (bf16; Nout, Kin multiples of 64)
 // tile configuration the dispatcher picks for a shape (0: 128x128, 1: 256x256, 2: 256x128, 3: 128x64,
-// 4: 128x192 workgroup tiles)
+// 4: 128x192 workgroup tiles on a 2-stage LDS ring; 5: 128x64, 6: 128x128, 7: 64x64 on a 4-stage ring)
 int gemm_bf16_tile(int64_t M, int Nout, int epi);
 void gemm_bf16_force_tile(int tile);   // debug: -1 = automatic
 void launch_gemm_bf16(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int64_t M, int Nout, int Kin, int epi,
