@@ -1,0 +1,154 @@
+"""Kernel-level parity at the full shapes of the benchmark configurations, on sampled outputs
+that the fp64 oracle computes one by one (the whole result at these sizes would take the CPU
+minutes).  Through the C ABI's kernel hooks, in the launch configuration the forward uses."""
+import numpy as np
+import pytest
+import torch
+
+import psd_inputs as inp
+from oracle import psd_oracle as orc
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def bf16_round_trip(a):
+    return inp.round_to_bf16(np.asarray(a, dtype=np.float32))
+
+
+def dev_bf16(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV).to(torch.bfloat16)
+
+
+def host_f64(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+GEMM_CASES = [
+    # label, M, N, K, epilogue           (config 3 verify / stage-1, config 4 verify, ragged M)
+    ("c3v-qkv", 2048, 12288, 4096, 0), ("c3v-o", 2048, 4096, 4096, 2), ("c3v-swiglu", 2048, 12288, 4096, 3),
+    ("c3v-down", 2048, 4096, 12288, 2), ("c3s-qkv", 512, 12288, 4096, 0), ("c3s-o", 512, 4096, 4096, 2),
+    ("c3s-down", 512, 4096, 12288, 2), ("c4v-qkv-bias", 6144, 4608, 3584, 1), ("c4v-swiglu", 6144, 18944, 3584, 3),
+    ("c4s-down", 1024, 3584, 18944, 2), ("ragged", 200, 1408, 512, 3), ("ragged-store", 333, 1536, 512, 0),
+    ("ragged-resid", 77, 512, 1408, 2),
+]
+
+
+@pytest.mark.parametrize("label,M,N,K,epi", GEMM_CASES, ids=[c[0] for c in GEMM_CASES])
+def test_gemm_sampled_rows(label, M, N, K, epi):
+    from paper_2605_15609_amd import binding as B
+    print(f"[kernels] gemm {label} M={M} N={N} K={K} epi={epi}", flush=True)
+    rng = np.random.default_rng(hash(label) % 2 ** 31)
+    A = bf16_round_trip(rng.standard_normal((M, K), dtype=np.float32))
+    W = bf16_round_trip(rng.standard_normal((N, K), dtype=np.float32) * 0.05)
+    W2 = bf16_round_trip(rng.standard_normal((N, K), dtype=np.float32) * 0.05) if epi == 3 else None
+    bias = rng.standard_normal(N).astype(np.float32) if epi == 1 else None
+    resid0 = rng.standard_normal((M, N)).astype(np.float32) if epi == 2 else None
+    dA, dW = dev_bf16(A), dev_bf16(W)
+    if epi == 2:
+        d_res = torch.from_numpy(resid0).to(DEV)
+        B.kernel_gemm_bf16(dA, dW, epi, resid=d_res)
+        got = d_res.cpu().numpy().astype(np.float64)
+    else:
+        out = B.kernel_gemm_bf16(dA, dW, epi, W2=None if W2 is None else dev_bf16(W2),
+                                 bias=None if bias is None else torch.from_numpy(bias).to(DEV))
+        got = host_f64(out)
+    torch.cuda.synchronize()
+    rows = sorted(set([0, M - 1, M // 2] + [int(r) for r in rng.integers(0, M, size=13)]))
+    a = A[rows].astype(np.float64)
+    ref = a @ W.astype(np.float64).T
+    if epi == 1:
+        ref = ref + bias
+    if epi == 3:
+        ref = orc.silu(ref) * (a @ W2.astype(np.float64).T)
+    if epi == 2:
+        ref = ref + resid0[rows]
+        tol = 1e-3 * np.sqrt(K / 4096) + 1e-6 * np.abs(ref)             # fp32 accumulation only
+    else:
+        tol = 2.0 ** -8 * np.abs(ref) + 2e-3 * np.sqrt(K / 4096)        # one bf16 rounding of the result
+    err = np.abs(got[rows] - ref)
+    assert (err <= tol).all(), f"{label}: max err {err.max():.3e} at {np.unravel_index(err.argmax(), err.shape)}"
+
+
+ATTN_CASES = [("c3v", 4, 512, 32, 32, 128), ("c4v-gqa", 6, 1024, 28, 4, 128), ("c2v", 4, 384, 8, 8, 64),
+              ("c5-len", 2, 1280, 32, 32, 128), ("ragged", 3, 200, 4, 2, 64)]
+
+
+@pytest.mark.parametrize("label,S,N,H,Hkv,dh", ATTN_CASES, ids=[c[0] for c in ATTN_CASES])
+def test_attention_sampled_queries(label, S, N, H, Hkv, dh):
+    from paper_2605_15609_amd import binding as B
+    print(f"[kernels] attention {label}", flush=True)
+    rng = np.random.default_rng(len(label) + N)
+    qkv = bf16_round_trip(rng.standard_normal((S * N, (H + 2 * Hkv) * dh), dtype=np.float32))
+    out = host_f64(B.kernel_attention_bf16(dev_bf16(qkv), S, N, H, Hkv, dh))
+    torch.cuda.synchronize()
+    group = H // Hkv
+    worst = 0.0
+    for _ in range(24):
+        s, hd, i = int(rng.integers(S)), int(rng.integers(H)), int(rng.integers(N))
+        if _ == 0:
+            s, hd, i = S - 1, H - 1, N - 1
+        seq = qkv[s * N: (s + 1) * N].astype(np.float64)
+        q = seq[i, hd * dh: (hd + 1) * dh]
+        k = seq[:, (H + hd // group) * dh: (H + hd // group + 1) * dh]
+        v = seq[:, (H + Hkv + hd // group) * dh: (H + Hkv + hd // group + 1) * dh]
+        ref = orc.attention(q[None, None, :], k[:, None, :], v[:, None, :])[0, 0]
+        got = out[s * N + i, hd * dh: (hd + 1) * dh]
+        worst = max(worst, np.abs(got - ref).max())
+    # probabilities and outputs are rounded to bf16 once each: relative 2^-8 on O(1) values
+    assert worst < 2e-2, f"{label}: max err {worst:.3e}"
+
+
+HEAD_CASES = [("c3-stage1", 32, 126464, 4096), ("c3-verify", 128, 126464, 4096), ("c4-verify", 192, 152064, 3584),
+              ("c2-verify", 128, 32000, 512), ("ragged", 77, 5000, 512), ("many-rows", 300, 3001, 512)]
+
+
+@pytest.mark.parametrize("label,rows,V,d", HEAD_CASES, ids=[c[0] for c in HEAD_CASES])
+def test_fused_head_sampled_rows(label, rows, V, d):
+    from paper_2605_15609_amd import binding as B
+    print(f"[kernels] head {label}", flush=True)
+    rng = np.random.default_rng(rows + V)
+    y = bf16_round_trip(rng.standard_normal((rows, d), dtype=np.float32))
+    W = bf16_round_trip(rng.standard_normal((V, d), dtype=np.float32) * 0.02)
+    mask_id = V - 1
+    scale = 1.7
+    row_sum, row_arg = B.kernel_head_confidence_bf16(dev_bf16(y), dev_bf16(W), scale, mask_id)
+    torch.cuda.synchronize()
+    row_sum, row_arg = row_sum.cpu().numpy().astype(np.float64), row_arg.cpu().numpy()
+    sample = sorted(set([0, rows - 1] + [int(r) for r in rng.integers(0, rows, size=6)]))
+    Wd = W.astype(np.float64)
+    for r in sample:
+        z = scale * (y[r].astype(np.float64) @ Wd.T)
+        x_hat, c = orc.top1_confidence(z[None], mask_id)
+        zz = z.copy()
+        zz[mask_id] = -np.inf
+        top2 = np.partition(zz, -2)[-2:]
+        if top2[1] - top2[0] >= 1e-3:
+            assert row_arg[r] == x_hat[0], f"{label}: row {r} argmax {row_arg[r]} vs {x_hat[0]}"
+        assert row_arg[r] != mask_id
+        assert abs((1.0 / row_sum[r]) / c[0] - 1.0) < 2e-3, f"{label}: row {r} confidence {1 / row_sum[r]} vs {c[0]}"
+
+
+def test_head_ties_go_to_the_lowest_token_id_and_mask_is_excluded():
+    from paper_2605_15609_amd import binding as B
+    d, V = 64, 1000
+    y = np.zeros((40, d), dtype=np.float32)
+    y[:, 0] = 1.0
+    W = np.zeros((V, d), dtype=np.float32)
+    W[[17, 300, 700, 999], 0] = 2.0            # exact ties across different vocabulary slabs; 999 is [M]
+    W[999, 0] = 8.0
+    row_sum, row_arg = B.kernel_head_confidence_bf16(dev_bf16(y), dev_bf16(W), 1.0, 999)
+    torch.cuda.synchronize()
+    assert (row_arg.cpu().numpy() == 17).all()
+    expect = 3 + (V - 4) * np.exp(-2.0)
+    np.testing.assert_allclose(row_sum.cpu().numpy(), expect, rtol=1e-5)
+
+
+def test_kernel_hooks_reject_bad_shapes():
+    from paper_2605_15609_amd import binding as B
+    a = torch.zeros((8, 100), dtype=torch.bfloat16, device=DEV)
+    w = torch.zeros((64, 100), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(B.PsdError, match="multiples of 64"):
+        B.kernel_gemm_bf16(a, w)
+    with pytest.raises(B.PsdError):
+        B.kernel_attention_bf16(torch.zeros((10, 3 * 64), dtype=torch.bfloat16, device=DEV), 1, 10, 1, 1, 64)
