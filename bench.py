@@ -106,7 +106,7 @@ def main():
     # dominant kernel: the SwiGLU gate/up contraction of the verification forward
     bf16 = shape.dtype == "bf16"
     if bf16:
-        model.probe_begin(3, 1)
+        model.probe_begin(3, 9)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         toks, stats = one_decode()
@@ -119,8 +119,15 @@ def main():
             achieved = flops / (ms * 1e-3) / 1e12
             roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                         "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                        "kernel": "gemm_bf16_kernel<256,256,2,2,SWIGLU>", "launches": int(launches),
+                        "kernel": "mfma::gemm_bf16_kernel<256, 256, 4, 2, 3, 2> (SwiGLU gate/up contraction)", "launches": int(launches),
                         "avg_launch_us": ms * 1e3 / launches, "flops_per_launch": flops / launches}
+
+    if roofline is not None:
+        # context for `frac`: what a loop of nothing but MFMAs sustains here on real (non-zero) operand data
+        from paper_2605_15609_amd.binding import kernel_mfma_rate
+        ops = (torch.randn(1 << 16, device="cuda:0") * 0.5).to(torch.bfloat16)
+        roofline["mfma_only_loop_random_operands_tflops"] = kernel_mfma_rate(ops)
+        roofline["mfma_only_loop_zero_operands_tflops"] = kernel_mfma_rate(torch.zeros_like(ops))
 
     assert not bool((toks == shape.mask_id).any()), "decode left masked positions"
     n_tokens = w.batch * w.gen_len

@@ -16,7 +16,8 @@
  *     is launched and no output is written.  psd_last_error() gives a message.
  *   - "device" pointers are HIP device memory owned by the caller (any allocator).
  *     "host" pointers are ordinary host memory.  The library allocates device memory only
- *     inside psd_create (a few KB of control state) and frees it in psd_destroy.
+ *     inside psd_create (for bf16 models a second copy of the LM-head matrix in MFMA-fragment
+ *     order, vocab*d_model*2 bytes) and frees it in psd_destroy.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     enqueue asynchronously and do not synchronise, except psd_decode_block, which
  *     returns host statistics and reads small counters back once per iteration.
@@ -233,13 +234,31 @@ int32_t psd_kernel_gemm_bf16(const void *A, const void *W, const void *W2, int64
 int32_t psd_kernel_attention_bf16(const void *qkv, int32_t S, int32_t N, int32_t n_heads, int32_t n_kv_heads,
                                   int32_t d_head, void *vT, void *out, void *stream);
 int64_t psd_kernel_head_scratch_bytes(int32_t rows, int32_t vocab);
+/*   streaming head (what the forward runs for <= 192 rows): both operands in MFMA-fragment order,
+ *          [ceil(R/32)][K/16][64 lanes][8 bf16]; psd_kernel_pack_rows builds that copy of a row-major
+ *          [R, K] matrix into dst of psd_kernel_packed_bytes(R, K) bytes.  Same outputs and scratch as
+ *          psd_kernel_head_confidence_bf16 (the tiled kernel, which the forward keeps for more rows). */
+int64_t psd_kernel_packed_bytes(int64_t R, int32_t K);
+int32_t psd_kernel_pack_rows(const void *src, int64_t R, int32_t K, void *dst, void *stream);
+int32_t psd_kernel_head_stream_bf16(const void *y_packed, const void *W_packed, int32_t rows, int32_t vocab, int32_t d,
+                                    float scale, int32_t mask_id, void *scratch, float *row_sum, int32_t *row_arg,
+                                    void *stream);
 int32_t psd_kernel_head_confidence_bf16(const void *y, const void *W, int32_t rows, int32_t vocab, int32_t d, float scale,
                                         int32_t mask_id, void *scratch, float *row_sum, int32_t *row_arg, void *stream);
+
+/* Calibration kernel: 256 workgroups of 4 wavefronts, each running `iters` rounds of 16 independent
+ * v_mfma_f32_32x32x16_bf16 on operand data read from `operands` (device, bf16 values, >= 16 bytes)
+ * and rotated between rounds; nothing else.  Returns in *flops the FLOPs of the launch; the
+ * caller times it with events on `stream`.  The MFMA clock is power-managed, so the rate on real
+ * data (not zeros) is the sustained ceiling for a contraction on this device.  sink: device, 4 MiB. */
+int32_t psd_kernel_mfma_rate(const void *operands, int64_t operand_bytes, int32_t iters, void *sink, int64_t sink_bytes,
+                             double *flops, void *stream);
 
 /* Kernel timing for roofline accounting.  Between psd_probe_begin and psd_probe_end every
  * launch of the layer-contraction kernel with the given epilogue (0 store, 1 bias,
  * 2 residual, 3 SwiGLU) and workgroup tile (0: 128x128, 1: 256x256, 2: 256x128, 3: 128x64, 4: 128x192
- * on a 2-stage LDS ring; 5: 128x64, 6: 128x128, 7: 64x64 on a 4-stage ring) is bracketed by HIP
+ * on a 2-stage LDS ring; 5: 128x64, 6: 128x128, 7: 64x64 on a 4-stage ring; 8, 9: 256x256 with 8
+ * wavefronts arranged 2x4 / 4x2) is bracketed by HIP
  * events on the stream it is launched on (up to max_launches; later ones go untimed).
  * psd_probe_end waits for those events and returns their summed duration, the number of
  * timed launches and their algorithmic FLOPs (2*M*N*K, twice that for SwiGLU). */

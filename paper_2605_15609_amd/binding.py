@@ -99,6 +99,10 @@ def load_library():
         "psd_kernel_head_scratch_bytes": (i64, [i32, i32]),
         "psd_kernel_head_confidence_bf16": (i32, [vp, vp, i32, i32, i32, C.c_float, i32, vp, vp, vp, vp]),
         "psd_debug_force_gemm_tile": (i32, [i32]),
+        "psd_kernel_packed_bytes": (i64, [i64, i32]),
+        "psd_kernel_pack_rows": (i32, [vp, i64, i32, vp, vp]),
+        "psd_kernel_head_stream_bf16": (i32, [vp, vp, i32, i32, i32, C.c_float, i32, vp, vp, vp, vp]),
+        "psd_kernel_mfma_rate": (i32, [vp, i64, i32, vp, i64, C.POINTER(C.c_double), vp]),
         "psd_probe_begin": (i32, [vp, i32, i32, i32]),
         "psd_probe_end": (i32, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
         "psd_forward_work": (i32, [C.POINTER(_Config), i32, i32, i32, C.POINTER(_Work)]),
@@ -450,4 +454,46 @@ def kernel_head_confidence_bf16(y: torch.Tensor, W: torch.Tensor, scale: float, 
     row_arg = torch.empty((rows,), dtype=torch.int32, device=y.device)
     _check(lib.psd_kernel_head_confidence_bf16(_ptr(y), _ptr(W), rows, V, d, float(scale), int(mask_id), _ptr(scratch),
                                                _ptr(row_sum), _ptr(row_arg), _stream()))
+    return row_sum, row_arg
+
+
+def kernel_mfma_rate(operands: torch.Tensor, iters: int = 4000) -> float:
+    """Sustained TFLOP/s of a pure-MFMA loop on the given bf16 operand data (see psd.h)."""
+    lib = load_library()
+    sink = torch.empty((4 << 20,), dtype=torch.uint8, device=operands.device)
+    fl = C.c_double()
+    nbytes = operands.numel() * operands.element_size()
+    _check(lib.psd_kernel_mfma_rate(_ptr(operands), nbytes, 50, _ptr(sink), sink.numel(), C.byref(fl), _stream()))
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    _check(lib.psd_kernel_mfma_rate(_ptr(operands), nbytes, iters, _ptr(sink), sink.numel(), C.byref(fl), _stream()))
+    e1.record()
+    torch.cuda.synchronize()
+    return fl.value / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
+def kernel_pack_rows(src: torch.Tensor) -> torch.Tensor:
+    """Row-major bf16 [R, K] -> its MFMA-fragment-order copy (flat bf16 tensor)."""
+    lib = load_library()
+    R, K = src.shape
+    n = int(lib.psd_kernel_packed_bytes(R, K))
+    _check(n)
+    dst = torch.empty((n // 2,), dtype=torch.bfloat16, device=src.device)
+    _check(lib.psd_kernel_pack_rows(_ptr(src), R, K, _ptr(dst), _stream()))
+    return dst
+
+
+def kernel_head_stream_bf16(y: torch.Tensor, W_packed: torch.Tensor, V: int, scale: float, mask_id: int, scratch=None,
+                            y_packed=None):
+    """Streaming LM-head on a pre-packed weight copy; y row-major bf16 [rows, d] is packed here."""
+    lib = load_library()
+    rows, d = y.shape
+    if y_packed is None:
+        y_packed = kernel_pack_rows(y)
+    if scratch is None:
+        scratch = torch.empty((int(lib.psd_kernel_head_scratch_bytes(rows, V)),), dtype=torch.uint8, device=y.device)
+    row_sum = torch.empty((rows,), dtype=torch.float32, device=y.device)
+    row_arg = torch.empty((rows,), dtype=torch.int32, device=y.device)
+    _check(lib.psd_kernel_head_stream_bf16(_ptr(y_packed), _ptr(W_packed), rows, V, d, float(scale), int(mask_id),
+                                           _ptr(scratch), _ptr(row_sum), _ptr(row_arg), _stream()))
     return row_sum, row_arg

@@ -171,6 +171,22 @@ int32_t psd_create(const psd_model_config *cfg, const psd_weights *w, psd_handle
             PSD_FAIL(PSD_ERR_INVALID_ARG, "layer %d has a NULL weight pointer", l);
         }
     }
+    h->lm_head_packed = nullptr;
+    if (cfg->dtype == PSD_DTYPE_BF16) {
+        // second copy of the LM-head in MFMA-fragment order for the streaming confidence pass
+        hipError_t pe = hipMalloc(&h->lm_head_packed, packed_rows_bytes(cfg->vocab, cfg->d_model));
+        if (pe != hipSuccess) {
+            delete h;
+            PSD_FAIL(PSD_ERR_DEVICE, "hipMalloc of the packed LM-head: %s", hipGetErrorString(pe));
+        }
+        launch_pack_rows((const bf16_t *)w->lm_head, cfg->vocab, cfg->d_model, (bf16_t *)h->lm_head_packed, nullptr);
+        pe = hipDeviceSynchronize();
+        if (pe != hipSuccess) {
+            (void)hipFree(h->lm_head_packed);
+            delete h;
+            PSD_FAIL(PSD_ERR_DEVICE, "packing the LM-head: %s", hipGetErrorString(pe));
+        }
+    }
     h->host_counts_cap = 1 << 16;
     hipError_t e = hipHostMalloc((void **)&h->host_counts, sizeof(int32_t) * h->host_counts_cap, hipHostMallocDefault);
     if (e != hipSuccess) {
@@ -184,6 +200,7 @@ int32_t psd_create(const psd_model_config *cfg, const psd_weights *w, psd_handle
 int32_t psd_destroy(psd_handle *h) {
     if (!h) return PSD_OK;
     if (h->host_counts) (void)hipHostFree(h->host_counts);
+    if (h->lm_head_packed) (void)hipFree(h->lm_head_packed);
     for (hipEvent_t e : h->probe.ev) (void)hipEventDestroy(e);
     delete h;
     return PSD_OK;
@@ -202,7 +219,7 @@ int32_t psd_debug_force_gemm_tile(int32_t tile) {
 
 int32_t psd_probe_begin(psd_handle *h, int32_t epilogue, int32_t tile, int32_t max_launches) {
     if (!h) PSD_FAIL(PSD_ERR_INVALID_ARG, "handle is NULL");
-    if (epilogue < 0 || epilogue > 3 || tile < 0 || tile > 7 || max_launches < 1 || max_launches > (1 << 20))
+    if (epilogue < 0 || epilogue > 3 || tile < 0 || tile > 9 || max_launches < 1 || max_launches > (1 << 20))
         PSD_FAIL(PSD_ERR_INVALID_ARG, "bad probe arguments");
     psd_handle::Probe &pr = h->probe;
     while (pr.ev.size() < (size_t)max_launches * 2) {
@@ -463,6 +480,30 @@ int64_t psd_kernel_head_scratch_bytes(int32_t rows, int32_t vocab) {
     return head_partial_bytes(rows, vocab);
 }
 
+int64_t psd_kernel_packed_bytes(int64_t R, int32_t K) {
+    if (R < 1 || K < 16 || K % 16) return PSD_ERR_SHAPE;
+    return packed_rows_bytes(R, K);
+}
+
+int32_t psd_kernel_pack_rows(const void *src, int64_t R, int32_t K, void *dst, void *stream) {
+    if (!src || !dst || R < 1 || K < 64 || K % 64) PSD_FAIL(PSD_ERR_INVALID_ARG, "bad pack arguments");
+    launch_pack_rows((const bf16_t *)src, R, K, (bf16_t *)dst, (hipStream_t)stream);
+    PSD_HIP(hipGetLastError());
+    return PSD_OK;
+}
+
+int32_t psd_kernel_head_stream_bf16(const void *y_packed, const void *W_packed, int32_t rows, int32_t vocab, int32_t d,
+                                    float scale, int32_t mask_id, void *scratch, float *row_sum, int32_t *row_arg,
+                                    void *stream) {
+    if (!y_packed || !W_packed || !scratch || !row_sum || !row_arg || rows < 1 || vocab < 2)
+        PSD_FAIL(PSD_ERR_INVALID_ARG, "bad arguments");
+    if (!head_stream_supported(rows, d)) PSD_FAIL(PSD_ERR_SHAPE, "streaming head takes at most 192 rows and d a multiple of 64");
+    launch_head_stream_bf16((const bf16_t *)y_packed, (const bf16_t *)W_packed, rows, vocab, d, scale, mask_id, scratch, row_sum,
+                            row_arg, (hipStream_t)stream);
+    PSD_HIP(hipGetLastError());
+    return PSD_OK;
+}
+
 int32_t psd_kernel_head_confidence_bf16(const void *y, const void *W, int32_t rows, int32_t vocab, int32_t d, float scale,
                                         int32_t mask_id, void *scratch, float *row_sum, int32_t *row_arg, void *stream) {
     if (!y || !W || !scratch || !row_sum || !row_arg || rows < 1 || vocab < 2) PSD_FAIL(PSD_ERR_INVALID_ARG, "bad arguments");
@@ -470,6 +511,17 @@ int32_t psd_kernel_head_confidence_bf16(const void *y, const void *W, int32_t ro
     launch_head_confidence_bf16((const bf16_t *)y, (const bf16_t *)W, rows, vocab, d, scale, mask_id, scratch, row_sum,
                                 row_arg, (hipStream_t)stream);
     PSD_HIP(hipGetLastError());
+    return PSD_OK;
+}
+
+int32_t psd_kernel_mfma_rate(const void *operands, int64_t operand_bytes, int32_t iters, void *sink, int64_t sink_bytes,
+                             double *flops, void *stream) {
+    if (!operands || !sink || !flops || operand_bytes < 16 || iters < 1) PSD_FAIL(PSD_ERR_INVALID_ARG, "bad arguments");
+    if (sink_bytes < (int64_t)256 * 256 * 64) PSD_FAIL(PSD_ERR_WORKSPACE, "sink needs 4 MiB");
+    launch_mfma_rate(operands, (int)(operand_bytes / 16 > (1 << 20) ? (1 << 20) : operand_bytes / 16), iters, sink,
+                     (hipStream_t)stream);
+    PSD_HIP(hipGetLastError());
+    *flops = 256.0 * 4.0 * iters * 16.0 * 32768.0;
     return PSD_OK;
 }
 

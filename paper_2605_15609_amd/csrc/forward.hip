@@ -23,6 +23,7 @@ ForwardPlan plan_forward(const psd_model_config &cfg, int64_t S, int64_t N, int6
     p.off_o = take(T * (int64_t)cfg.n_heads * cfg.d_head * esz);
     p.off_act = take(T * cfg.d_ffn * esz);
     p.off_y = take(rows * cfg.d_model * esz);
+    p.off_ypack = take(cfg.dtype == PSD_DTYPE_BF16 ? packed_rows_bytes(rows, cfg.d_model) : 0);
     p.off_rowsum = take(rows * 4);
     p.off_rowarg = take(rows * 4);
     // LM-head scratch: per-slab partial (max, sum, argmax) triples on the fused path; the
@@ -151,7 +152,11 @@ int32_t run_head_confidence(psd_handle *h, const int32_t *tokens, const int32_t 
     const int rows = S * L;
     float *row_sum = (float *)(ws + p.off_rowsum);
     int32_t *row_arg = (int32_t *)(ws + p.off_rowarg);
-    if (c.dtype == PSD_DTYPE_BF16 && !(h->plain_mask & 4)) {
+    if (c.dtype == PSD_DTYPE_BF16 && !(h->plain_mask & 4) && h->lm_head_packed && head_stream_supported(rows, c.d_model)) {
+        launch_pack_rows((const bf16_t *)(ws + p.off_y), rows, c.d_model, (bf16_t *)(ws + p.off_ypack), st);
+        launch_head_stream_bf16((const bf16_t *)(ws + p.off_ypack), (const bf16_t *)h->lm_head_packed, rows, c.vocab, c.d_model,
+                                c.logit_scale, c.mask_id, ws + p.off_part, row_sum, row_arg, st);
+    } else if (c.dtype == PSD_DTYPE_BF16 && !(h->plain_mask & 4)) {
         launch_head_confidence_bf16((const bf16_t *)(ws + p.off_y), (const bf16_t *)h->lm_head, rows, c.vocab, c.d_model,
                                     c.logit_scale, c.mask_id, ws + p.off_part, row_sum, row_arg, st);
     } else {

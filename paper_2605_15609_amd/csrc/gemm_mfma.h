@@ -73,7 +73,7 @@ __device__ __forceinline__ void sched_mix() {
 }
 
 template <int BM, int BN, int WGM, int WGN, int EPI, int NSTAGE>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Y,
+__global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Y,
                                                         const bf16_t *__restrict__ Y2, int M, int Nout, int Kin,
                                                         const float *__restrict__ bias, bf16_t *__restrict__ out,
                                                         float *__restrict__ resid, int ldo, int tiles_n, int n_tiles,
@@ -83,8 +83,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
     constexpr int BN_OUT = DUAL ? BN / 2 : BN;            // output columns per tile
     constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES, STAGE = A_BYTES + B_BYTES;
     constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
-    static_assert(WGM * WGN == 4 && TM >= 1 && TN >= 1 && (!DUAL || TN % 2 == 0), "tile shape");
-    static_assert(BM % 32 == 0 && BN % 32 == 0, "tile rows come in groups of 32 (256 lanes x 16 bytes)");
+    constexpr int NW = WGM * WGN;   // wavefronts per workgroup
+    static_assert((NW == 4 || NW == 8) && TM >= 1 && TN >= 1 && (!DUAL || TN % 2 == 0), "tile shape");
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "every wavefront moves whole 8-row groups of both tiles");
 
     // XCD-aware tile id: ids i, i+8, i+16 ... land on the same XCD; give that XCD a contiguous tile range
     int pid = blockIdx.x;
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
     // 64 lanes x 16 bytes = 8 tile rows x 128 bytes into 1 KB of consecutive LDS, lane l landing at
     // offset 16*l, i.e. row l/8, chunk slot l%8.  The XOR swizzle therefore lives on the global
     // side: the lane fetches logical chunk (l%8) ^ key(row), key(row) = (row >> 1) & 7.  Row groups
-    // are dealt to the 4 wavefronts round-robin (group g = 4*j + wave), which makes the key a
+    // are dealt to the NW wavefronts round-robin (group g = NW*j + wave), which makes the key a
     // per-lane constant: ((wave & 1) * 4 + l/16) & 7.  The per-lane byte offset is one VGPR; the
     // group and K position are wave-uniform and ride in a scalar offset.  Rows past the matrix edge
     // are rejected by the descriptor's range check (they only feed outputs that are never stored).
@@ -122,7 +123,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
     const int uwave = __builtin_amdgcn_readfirstlane(wave);
     const int dma_key = (((uwave & 1) << 2) + (lane >> 4)) & 7;
     const int voff = (lane >> 3) * Kin * 2 + (((lane & 7) ^ dma_key) << 4);
-    constexpr int GA = BM / 8 / 4, GB = BN / 8 / 4;   // row groups per wavefront, A and B tile
+    constexpr int GA = BM / 8 / NW, GB = BN / 8 / NW;   // row groups per wavefront, A and B tile
     constexpr int NLD = GA + GB;                      // DMA instructions per wavefront per stage
     typedef __attribute__((address_space(3))) void lds_void;
 
@@ -131,15 +132,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
     {                                                                                                         \
         unsigned char *sa_ = lds + (stage) * STAGE + uwave * 1024, *sb_ = sa_ + A_BYTES;                      \
         _Pragma("unroll") for (int j = 0; j < GA; ++j)                                                        \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, (lds_void *)(sa_ + j * 4096), 16, voff,          \
-                                                     ((j * 4 + uwave) * 8 * Kin + (k0)) * 2, 0, 0);           \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, (lds_void *)(sa_ + j * (NW * 1024)), 16, voff,   \
+                                                     ((j * NW + uwave) * 8 * Kin + (k0)) * 2, 0, 0);          \
         _Pragma("unroll") for (int j = 0; j < GB; ++j) {                                                      \
-            if (DUAL && j * 32 >= BN / 2)                                                                     \
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_y2, (lds_void *)(sb_ + j * 4096), 16, voff,     \
-                                                         (((j * 4 + uwave) * 8 - BN / 2) * Kin + (k0)) * 2, 0, 0); \
+            if (DUAL && j * (8 * NW) >= BN / 2)                                                               \
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_y2, (lds_void *)(sb_ + j * (NW * 1024)), 16, voff, \
+                                                         (((j * NW + uwave) * 8 - BN / 2) * Kin + (k0)) * 2, 0, 0); \
             else                                                                                              \
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_y, (lds_void *)(sb_ + j * 4096), 16, voff,      \
-                                                         ((j * 4 + uwave) * 8 * Kin + (k0)) * 2, 0, 0);       \
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_y, (lds_void *)(sb_ + j * (NW * 1024)), 16, voff, \
+                                                         ((j * NW + uwave) * 8 * Kin + (k0)) * 2, 0, 0);      \
         }                                                                                                     \
     }
 // the oldest DMA stage of this wavefront has landed (the NSTAGE-2 younger ones may still fly); then all wavefronts agree (s_barrier), and the compiler must
@@ -323,7 +324,7 @@ void launch_cfg(const bf16_t *X, const bf16_t *Y, const bf16_t *Y2, int M, int N
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(n_tiles), dim3(256), smem, st, X, Y, Y2, M, Nout, Kin, bias, out, resid, ldo, tiles_n,
+    hipLaunchKernelGGL(kern, dim3(n_tiles), dim3(WGM * WGN * 64), smem, st, X, Y, Y2, M, Nout, Kin, bias, out, resid, ldo, tiles_n,
                        n_tiles, t1);
 }
 

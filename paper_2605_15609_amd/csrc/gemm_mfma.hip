@@ -13,7 +13,7 @@ struct TileCfg {
     int bm, bn;
 };
 // index = value returned by gemm_bf16_tile
-constexpr TileCfg kTiles[] = {{128, 128}, {256, 256}, {256, 128}, {128, 64}, {128, 192}, {128, 64}, {128, 128}, {64, 64}};
+constexpr TileCfg kTiles[] = {{128, 128}, {256, 256}, {256, 128}, {128, 64}, {128, 192}, {128, 64}, {128, 128}, {64, 64}, {256, 256}, {256, 256}};
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
 template <int EPI>
@@ -48,6 +48,8 @@ void dispatch(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int M, int Nou
                 break;
             }
             [[fallthrough]];
+        case 8: launch_cfg<256, 256, 2, 4, EPI>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st); break;
+        case 9: launch_cfg<256, 256, 4, 2, EPI>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st); break;
         default: launch_cfg<128, 128, 2, 2, EPI>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st); break;
     }
 }
@@ -64,14 +66,17 @@ int gemm_bf16_tile(int64_t M, int Nout, int epi) {
     }
     // Rules read off a sweep of every tile over the layer shapes of the benchmark configurations
     // (MI355X): the 256x256 tile has the least LDS traffic per FLOP but runs one workgroup per CU, so
-    // it only pays with at least two full rounds of them (or for SwiGLU, whose two weight operands
-    // share the activation tile); short-M contractions with a narrow output need the small tile to
-    // reach every CU; otherwise 128x128 with two workgroups per CU hides latency best.
+    // it only pays with enough rounds of them (or for SwiGLU, whose two weight operands share the
+    // activation tile); short-M contractions with a narrow output need the small tile to reach every
+    // CU; otherwise 128x128 with two workgroups per CU hides latency best.
     const bool dual = epi == EPI_SWIGLU;
     const int64_t cols = dual ? 2 * (int64_t)Nout : Nout;
     const int64_t t256 = ((M + 255) / 256) * ((cols + 255) / 256);
-    if (dual) return t256 >= 128 ? 1 : 0;
-    if (t256 >= 512 && epi != EPI_RESIDUAL) return 1;
+    // the 256x256 tile runs as 8 wavefronts (two per SIMD, each 64x128): same LDS traffic per FLOP as four
+    // 128x128 wavefronts would need fewer fragment reads, but the second wavefront per SIMD hides the
+    // latencies that a lone one exposes
+    if (dual) return t256 >= 128 ? 9 : 0;
+    if (t256 >= 768 || (t256 >= 384 && Nout >= 8192)) return 9;
     const int64_t t128 = ((M + 127) / 128) * ((cols + 127) / 128);
     const int64_t t12864 = ((M + 127) / 128) * ((cols + 63) / 64);
     if (t128 <= 256) {   // at most one 128x128 workgroup per CU: latency-bound, use the deep LDS ring
@@ -92,4 +97,49 @@ void launch_gemm_bf16(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int64_
         case EPI_RESIDUAL: dispatch<EPI_RESIDUAL>(A, W, W2, m, Nout, Kin, bias, out, resid, ldo, st); break;
         default: dispatch<EPI_SWIGLU>(A, W, W2, m, Nout, Kin, bias, out, resid, ldo, st); break;
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Calibration: what a loop of nothing but v_mfma_f32_32x32x16_bf16 sustains on this device when
+// the operands are real data (16 independent accumulators per wavefront, 4 wavefronts per CU,
+// operand registers rotated every iteration).  The MFMA clock is power-managed, so this is well
+// below the rate the same loop reaches on all-zero operands; it is the ceiling a contraction
+// kernel can be judged against besides the published peak.
+namespace {
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void mfma_rate_kernel(const u32x4_t *__restrict__ src, int n_src, int iters,
+                                                        floatx16 *__restrict__ sink) {
+    bf16x8 a[4], b[4];
+    for (int i = 0; i < 4; ++i) {
+        a[i] = __builtin_bit_cast(bf16x8, src[(threadIdx.x * 8 + i) % n_src]);
+        b[i] = __builtin_bit_cast(bf16x8, src[(threadIdx.x * 8 + 4 + i) % n_src]);
+    }
+    floatx16 acc[4][4];
+    for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 4; ++j)
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        bf16x8 t = a[0];
+        a[0] = a[1]; a[1] = a[2]; a[2] = a[3]; a[3] = t;
+        t = b[0];
+        b[0] = b[1]; b[1] = b[2]; b[2] = b[3]; b[3] = t;
+    }
+    floatx16 s = acc[0][0];
+    for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 4; ++j)
+            if (i || j) s += acc[i][j];
+    sink[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+}   // namespace
+
+void launch_mfma_rate(const void *operands, int n_vec16, int iters, void *sink, hipStream_t st) {
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3(256), dim3(256), 0, st, (const u32x4_t *)operands, n_vec16, iters,
+                       (floatx16 *)sink);
 }

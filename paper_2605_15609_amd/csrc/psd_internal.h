@@ -23,6 +23,7 @@ struct psd_handle {
     std::vector<Layer> layers;
     int device;
     int plain_mask;          // debug: bit 0 plain GEMM, bit 1 plain attention, bit 2 plain LM-head
+    void *lm_head_packed;    // bf16 models: fragment-order copy of lm_head owned by the handle (streaming LM-head)
     int32_t *host_counts;    // pinned host staging for psd_decode_block
     int host_counts_cap;
     // optional HIP-event timing of one contraction kernel (epilogue kind + tile config)
@@ -75,7 +76,7 @@ void launch_accept(int32_t *tokens, const int32_t *drafts, int B, int N, int blo
 
 // ---------------------------------------------------------------- forward (forward.hip)
 struct ForwardPlan {
-    int64_t off_h, off_a, off_qkv, off_vt, off_o, off_act, off_y, off_rowsum, off_rowarg, off_part, total;
+    int64_t off_h, off_a, off_qkv, off_vt, off_o, off_act, off_y, off_ypack, off_rowsum, off_rowarg, off_part, total;
 };
 ForwardPlan plan_forward(const psd_model_config &cfg, int64_t S, int64_t N, int64_t L);
 
@@ -122,9 +123,12 @@ void launch_head_finish(const float *row_sum, const int32_t *row_arg, const int3
 
 // gemm_mfma.hip (bf16; Nout, Kin multiples of 64)
 // tile configuration the dispatcher picks for a shape (0: 128x128, 1: 256x256, 2: 256x128, 3: 128x64,
-// 4: 128x192 workgroup tiles on a 2-stage LDS ring; 5: 128x64, 6: 128x128, 7: 64x64 on a 4-stage ring)
+// 4: 128x192 workgroup tiles on a 2-stage LDS ring; 5: 128x64, 6: 128x128, 7: 64x64 on a 4-stage ring;
+// 8, 9: 256x256 with 8 wavefronts as 2x4 / 4x2)
 int gemm_bf16_tile(int64_t M, int Nout, int epi);
 void gemm_bf16_force_tile(int tile);   // debug: -1 = automatic
+// 256 workgroups x 4 wavefronts x iters x 16 MFMAs (32x32x16 bf16) on the given operand data; sink >= 4 MiB
+void launch_mfma_rate(const void *operands, int n_vec16, int iters, void *sink, hipStream_t st);
 void launch_gemm_bf16(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int64_t M, int Nout, int Kin, int epi,
                       const float *bias, bf16_t *out, float *resid, int ldo, hipStream_t st);
 // attention_mfma.hip (bf16, d_head 64 or 128): q, k from qkv (rotary applied), values from vT
@@ -132,5 +136,11 @@ void launch_attention_bf16(const bf16_t *qkv, const bf16_t *vT, int S, int N, in
                            bf16_t *out, hipStream_t st);
 // lm_head.hip (bf16): LM-head fused with the online top-1 / sum-exp reduction
 int64_t head_partial_bytes(int rows, int V);
+// fragment-order copies: [ceil(R/32)][K/16][64 lanes][8 bf16]
+int64_t packed_rows_bytes(int64_t R, int K);
+void launch_pack_rows(const bf16_t *src, int64_t R, int K, bf16_t *dst, hipStream_t st);
+bool head_stream_supported(int rows, int d);
+void launch_head_stream_bf16(const bf16_t *y_packed, const bf16_t *W_packed, int rows, int V, int d, float scale, int mask_id,
+                             void *partials, float *row_sum, int32_t *row_arg, hipStream_t st);
 void launch_head_confidence_bf16(const bf16_t *y, const bf16_t *W, int rows, int V, int d, float scale, int mask_id,
                                  void *partials, float *row_sum, int32_t *row_arg, hipStream_t st);

@@ -100,11 +100,13 @@ def test_attention_sampled_queries(label, S, N, H, Hkv, dh):
 
 
 HEAD_CASES = [("c3-stage1", 32, 126464, 4096), ("c3-verify", 128, 126464, 4096), ("c4-verify", 192, 152064, 3584),
-              ("c2-verify", 128, 32000, 512), ("ragged", 77, 5000, 512), ("many-rows", 300, 3001, 512)]
+              ("c2-verify", 128, 32000, 512), ("ragged", 77, 5000, 512), ("many-rows", 300, 3001, 512),
+              ("c5-block64", 64, 126464, 4096), ("rows-256", 250, 5000, 576), ("one-row", 1, 3001, 64)]
 
 
+@pytest.mark.parametrize("path", ["stream", "tiled"])
 @pytest.mark.parametrize("label,rows,V,d", HEAD_CASES, ids=[c[0] for c in HEAD_CASES])
-def test_fused_head_sampled_rows(label, rows, V, d):
+def test_fused_head_sampled_rows(label, rows, V, d, path):
     from paper_2605_15609_amd import binding as B
     print(f"[kernels] head {label}", flush=True)
     rng = np.random.default_rng(rows + V)
@@ -112,7 +114,13 @@ def test_fused_head_sampled_rows(label, rows, V, d):
     W = bf16_round_trip(rng.standard_normal((V, d), dtype=np.float32) * 0.02)
     mask_id = V - 1
     scale = 1.7
-    row_sum, row_arg = B.kernel_head_confidence_bf16(dev_bf16(y), dev_bf16(W), scale, mask_id)
+    dW, dy = dev_bf16(W), dev_bf16(y)
+    if path == "tiled":
+        row_sum, row_arg = B.kernel_head_confidence_bf16(dy, dW, scale, mask_id)
+    else:
+        if rows > 192:
+            pytest.skip("the streaming head takes at most 192 rows")
+        row_sum, row_arg = B.kernel_head_stream_bf16(dy, B.kernel_pack_rows(dW), V, scale, mask_id)
     torch.cuda.synchronize()
     row_sum, row_arg = row_sum.cpu().numpy().astype(np.float64), row_arg.cpu().numpy()
     sample = sorted(set([0, rows - 1] + [int(r) for r in rng.integers(0, rows, size=6)]))
@@ -137,11 +145,15 @@ def test_head_ties_go_to_the_lowest_token_id_and_mask_is_excluded():
     W = np.zeros((V, d), dtype=np.float32)
     W[[17, 300, 700, 999], 0] = 2.0            # exact ties across different vocabulary slabs; 999 is [M]
     W[999, 0] = 8.0
-    row_sum, row_arg = B.kernel_head_confidence_bf16(dev_bf16(y), dev_bf16(W), 1.0, 999)
-    torch.cuda.synchronize()
-    assert (row_arg.cpu().numpy() == 17).all()
-    expect = 3 + (V - 4) * np.exp(-2.0)
-    np.testing.assert_allclose(row_sum.cpu().numpy(), expect, rtol=1e-5)
+    for path in ("tiled", "stream"):
+        if path == "tiled":
+            row_sum, row_arg = B.kernel_head_confidence_bf16(dev_bf16(y), dev_bf16(W), 1.0, 999)
+        else:
+            row_sum, row_arg = B.kernel_head_stream_bf16(dev_bf16(y), B.kernel_pack_rows(dev_bf16(W)), V, 1.0, 999)
+        torch.cuda.synchronize()
+        assert (row_arg.cpu().numpy() == 17).all(), path
+        expect = 3 + (V - 4) * np.exp(-2.0)
+        np.testing.assert_allclose(row_sum.cpu().numpy(), expect, rtol=1e-5)
 
 
 def test_kernel_hooks_reject_bad_shapes():
