@@ -66,6 +66,11 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="BASELINE configuration index (1-5)")
     ap.add_argument("--logit-scale", type=float, default=1.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (a known-size reference for scaling rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--max-blocks", type=int, default=0,
+                    help="decode only the first blocks of the generation region (0 = all); tokens/s counts what was decoded")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1",
@@ -94,9 +99,16 @@ def main():
     tokens0 = torch.from_numpy(inp.initial_state(w)).to("cuda:0")
     policy, graph = psd.Policy(w.tau, w.k_min, w.k_max), psd.chain_graph(w.n_drafts)
 
+    n_blocks = w.gen_len // w.block_len
+    if args.max_blocks > 0:
+        n_blocks = min(n_blocks, args.max_blocks)
+    gen_end = w.prompt_len + n_blocks * w.block_len
+
     def one_decode():
         toks = tokens0.clone()
-        stats = psd.decode(model, toks, w.prompt_len, w.block_len, policy, graph)
+        stats = [psd.Stats() for _ in range(w.batch)]
+        for block_start in range(w.prompt_len, gen_end, w.block_len):
+            stats = psd.psd_decode_block(model, toks, block_start, w.block_len, policy, graph, stats)
         return toks, stats
 
     for _ in range(args.warmup):
@@ -122,6 +134,13 @@ def main():
                         "kernel": "mfma::gemm_bf16_kernel<256, 256, 4, 2, 3, 2> (SwiGLU gate/up contraction)", "launches": int(launches),
                         "avg_launch_us": ms * 1e3 / launches, "flops_per_launch": flops / launches}
 
+    if args.calibrate_copy:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     if roofline is not None:
         # context for `frac`: what a loop of nothing but MFMAs sustains here on real (non-zero) operand data
         from paper_2605_15609_amd.binding import kernel_mfma_rate
@@ -129,8 +148,8 @@ def main():
         roofline["mfma_only_loop_random_operands_tflops"] = kernel_mfma_rate(ops)
         roofline["mfma_only_loop_zero_operands_tflops"] = kernel_mfma_rate(torch.zeros_like(ops))
 
-    assert not bool((toks == shape.mask_id).any()), "decode left masked positions"
-    n_tokens = w.batch * w.gen_len
+    assert not bool((toks[:, :gen_end] == shape.mask_id).any()), "decode left masked positions"
+    n_tokens = w.batch * n_blocks * w.block_len
     invocations = sum(s.invocations for s in stats)
     n_verify = sum(sum(s.depth_hist) for s in stats)
     n_stage1 = invocations - n_verify
@@ -149,7 +168,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"config {w.index}: {shape.name}, B={w.batch}, prompt {w.prompt_len} Zipf tokens, "
-                               f"{w.gen_len} generated in blocks of {w.block_len}, K={w.n_drafts} chain, tau={w.tau}",
+                               f"{n_blocks * w.block_len} generated in blocks of {w.block_len}, K={w.n_drafts} chain, tau={w.tau}",
                    "tpf": tpf, "invocations": int(invocations), "stage1_calls": int(n_stage1),
                    "verify_calls": int(n_verify), "logit_scale": shape.logit_scale,
                    "tokens_policy": int(sum(s.tokens_policy for s in stats)),

@@ -25,7 +25,9 @@
  *     block_start .. block_start+L-1 of every sequence (1 <= L <= 64).  Per-block tables
  *     are top1 int32 [B, L] and conf float [B, L]: a masked position carries the
  *     prediction, any other position the sentinel (its own token, -1.0f).
- *   - Sequences of a batch are independent; batching never changes a sequence's result.
+ *   - Sequences of a batch are independent.  Batching never changes a sequence's logits or top-1
+ *     tokens; the confidence normaliser is summed in an order that depends on the number of rows
+ *     in the call, so confidences can differ in the last fp32 bit between batch shapes.
  */
 #ifndef PSD_H
 #define PSD_H

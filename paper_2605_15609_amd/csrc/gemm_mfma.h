@@ -90,7 +90,18 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
     // XCD-aware tile id: ids i, i+8, i+16 ... land on the same XCD; give that XCD a contiguous tile range
     int pid = blockIdx.x;
     if (n_tiles % 8 == 0) pid = (pid % 8) * (n_tiles / 8) + pid / 8;
-    const int tile_m = pid / tiles_n, tile_n = pid % tiles_n;
+    // Each XCD has its own L2, so its tile range should re-use what it fetches: the range is cut along the
+    // dimension of the LARGER operand (each XCD then reads an eighth of it, plus all of the small one), and
+    // inside the range the index of the small operand runs fastest.
+    const int tiles_m = n_tiles / tiles_n;
+    int tile_m, tile_n;
+    if (M <= Nout) {
+        tile_n = pid / tiles_m;
+        tile_m = pid % tiles_m;
+    } else {
+        tile_m = pid / tiles_n;
+        tile_n = pid % tiles_n;
+    }
     const int m0 = tile_m * BM, n0 = tile_n * BN_OUT;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;

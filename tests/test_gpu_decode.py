@@ -201,3 +201,44 @@ def test_config3_width_two_layers_lockstep():
     log = _lockstep(w, shape, n_blocks=1, max_iters=3)
     print(f"[decode] config 3 (2 layers) lock-step: {log}", flush=True)
     assert log["iters"] == 3
+
+
+def test_config4_shape_two_layers_lockstep():
+    """Config 4's layout (grouped KV heads 28/4, QKV bias, d = 3584, F = 18944, V = 152064, N = 1024, K = 6)
+    with the depth cut to 2 layers; two iterations against the oracle."""
+    w = inp.WORKLOADS[4]
+    shape = inp.cut_down(w.shape, n_layers=2)
+    log = _lockstep(w, shape, n_blocks=1, max_iters=2)
+    print(f"[decode] config 4 (2 layers) lock-step: {log}", flush=True)
+    assert log["iters"] == 2
+
+
+def test_config5_shape_batched_block_decode():
+    """Config 5's batch shape (16 sequences of 1280 tokens, L = 64, K = 8: a verify call of 128 x 1280
+    tokens) on a 2-layer cut of the model: one block through psd_decode_block and the loop invariants;
+    then the model call for two of the sequences alone against the batched call."""
+    import paper_2605_15609_amd as psd
+    from paper_2605_15609_amd.synthetic import synthetic_model
+    w = inp.WORKLOADS[5]
+    shape = inp.cut_down(w.shape, n_layers=2, logit_scale=9.0)
+    model = synthetic_model(shape, w.seq_len, DEV, threads=16)
+    policy, graph = psd.Policy(w.tau, w.k_min, w.k_max), psd.chain_graph(w.n_drafts)
+    tokens0 = inp.initial_state(w)
+    together = _dev(tokens0)
+    stats = psd.psd_decode_block(model, together, w.prompt_len, w.block_len, policy, graph)
+    torch.cuda.synchronize()
+    blk = together[:, w.prompt_len: w.prompt_len + w.block_len]
+    assert not bool((blk == shape.mask_id).any())
+    assert bool((together[:, w.prompt_len + w.block_len:] == shape.mask_id).all())      # later blocks untouched
+    assert (together[:, : w.prompt_len].cpu().numpy() == tokens0[:, : w.prompt_len]).all()
+    for s in stats:
+        assert s.tokens == w.block_len and 1 <= s.invocations <= w.block_len and s.tpf >= 1.0
+    print(f"[decode] config 5 shape: TPF per sequence {[round(s.tpf, 2) for s in stats]}", flush=True)
+    # Batching changes which LM-head kernel runs (1024 rows: tiled; 64 rows: streaming), i.e. the order in
+    # which the softmax normaliser is summed; confidences agree to fp32 rounding, tokens exactly.
+    state = _dev(tokens0)
+    t_all, c_all = psd.psd_forward_confidence(model, state, w.prompt_len, w.block_len)
+    for b in (0, 11):
+        t1, c1 = psd.psd_forward_confidence(model, _dev(tokens0[b: b + 1]), w.prompt_len, w.block_len)
+        assert (t1[0] == t_all[b]).all(), b
+        assert torch.allclose(c1[0], c_all[b], rtol=2e-6, atol=0), b
