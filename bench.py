@@ -117,21 +117,32 @@ def main():
 
     # dominant kernel: the SwiGLU gate/up contraction of the verification forward
     bf16 = shape.dtype == "bf16"
+    lib = psd.load_library()
+    tile_names = {0: "128, 128, 2, 2, 3, 2", 9: "256, 256, 4, 2, 3, 2"}
     if bf16:
-        model.probe_begin(3, 9)
+        # the tile the dispatcher picks for the verification pass's SwiGLU contraction
+        swiglu_tile = lib.psd_kernel_gemm_tile(w.batch * w.n_drafts * w.seq_len, shape.d_ffn, 3)
+        model.probe_begin(3, swiglu_tile)
+        model.probe_begin(4, 0)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         toks, stats = one_decode()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    roofline = None
+    roofline, lm_head = None, None
     if bf16:
-        ms, launches, flops = model.probe_end()
+        hms, hcalls, hbytes = model.probe_end(4)
+        if hcalls > 0 and hms > 0:
+            gbs = hbytes / (hms * 1e-3) / 1e9
+            lm_head = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                       "calls": int(hcalls), "avg_pass_us": hms * 1e3 / hcalls, "bytes_per_pass": hbytes / hcalls,
+                       "what": "LM-head confidence pass (weight stream + merge), stage-1 and verify calls together"}
+        ms, launches, flops = model.probe_end(3)
         if launches > 0 and ms > 0:
             achieved = flops / (ms * 1e-3) / 1e12
             roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                         "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                        "kernel": "mfma::gemm_bf16_kernel<256, 256, 4, 2, 3, 2> (SwiGLU gate/up contraction)", "launches": int(launches),
+                        "kernel": f"mfma::gemm_bf16_kernel<{tile_names.get(swiglu_tile, swiglu_tile)}> (SwiGLU gate/up contraction)", "launches": int(launches),
                         "avg_launch_us": ms * 1e3 / launches, "flops_per_launch": flops / launches}
 
     if args.calibrate_copy:
@@ -177,6 +188,7 @@ def main():
                    "model_tflops_per_s_whole_decode": flops_decode / (elapsed / args.steps) / 1e12,
                    "weights_setup_s": t_weights},
         "roofline": roofline,
+        "lm_head_roofline": lm_head,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, n_tokens, n_stage1, n_verify, os.cpu_count() or 1)

@@ -260,12 +260,16 @@ int32_t psd_kernel_mfma_rate(const void *operands, int64_t operand_bytes, int32_
  * launch of the layer-contraction kernel with the given epilogue (0 store, 1 bias,
  * 2 residual, 3 SwiGLU) and workgroup tile (0: 128x128, 1: 256x256, 2: 256x128, 3: 128x64, 4: 128x192
  * on a 2-stage LDS ring; 5: 128x64, 6: 128x128, 7: 64x64 on a 4-stage ring; 8, 9: 256x256 with 8
- * wavefronts arranged 2x4 / 4x2) is bracketed by HIP
- * events on the stream it is launched on (up to max_launches; later ones go untimed).
- * psd_probe_end waits for those events and returns their summed duration, the number of
- * timed launches and their algorithmic FLOPs (2*M*N*K, twice that for SwiGLU). */
+ * wavefronts arranged 2x4 / 4x2) is bracketed by HIP events on the stream it is launched on (up to
+ * max_launches; later ones go untimed).  Epilogue 4 selects the LM-head confidence pass instead
+ * (all its kernels, tile ignored); it can be timed together with one contraction kernel.
+ * psd_probe_end waits for those events and returns their summed duration, the number of timed
+ * launches and their algorithmic work: FLOPs (2*M*N*K, twice that for SwiGLU) for a contraction,
+ * bytes (vocab*d*2 + rows*d*2 + rows*8) for the LM-head pass.
+ * psd_kernel_gemm_tile tells which tile the dispatcher picks for a shape. */
 int32_t psd_probe_begin(psd_handle *h, int32_t epilogue, int32_t tile, int32_t max_launches);
-int32_t psd_probe_end(psd_handle *h, double *total_ms, int64_t *launches, double *flops);
+int32_t psd_probe_end(psd_handle *h, int32_t epilogue, double *total_ms, int64_t *launches, double *work);
+int32_t psd_kernel_gemm_tile(int64_t M, int32_t Nout, int32_t epilogue);
 
 #ifdef __cplusplus
 }

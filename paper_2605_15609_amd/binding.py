@@ -104,7 +104,8 @@ def load_library():
         "psd_kernel_head_stream_bf16": (i32, [vp, vp, i32, i32, i32, C.c_float, i32, vp, vp, vp, vp]),
         "psd_kernel_mfma_rate": (i32, [vp, i64, i32, vp, i64, C.POINTER(C.c_double), vp]),
         "psd_probe_begin": (i32, [vp, i32, i32, i32]),
-        "psd_probe_end": (i32, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
+        "psd_probe_end": (i32, [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
+        "psd_kernel_gemm_tile": (i32, [i64, i32, i32]),
         "psd_forward_work": (i32, [C.POINTER(_Config), i32, i32, i32, C.POINTER(_Work)]),
     }
     for name, (res, args) in sig.items():
@@ -267,9 +268,9 @@ class Model:
     def probe_begin(self, epilogue: int, tile: int, max_launches: int = 65536):
         _check(self.lib.psd_probe_begin(self.handle, epilogue, tile, max_launches))
 
-    def probe_end(self):
+    def probe_end(self, epilogue: int):
         ms, n, fl = C.c_double(), C.c_int64(), C.c_double()
-        _check(self.lib.psd_probe_end(self.handle, C.byref(ms), C.byref(n), C.byref(fl)))
+        _check(self.lib.psd_probe_end(self.handle, epilogue, C.byref(ms), C.byref(n), C.byref(fl)))
         return ms.value, n.value, fl.value
 
     def workspace(self, n_bytes: int) -> torch.Tensor:

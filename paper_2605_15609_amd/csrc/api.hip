@@ -202,6 +202,7 @@ int32_t psd_destroy(psd_handle *h) {
     if (h->host_counts) (void)hipHostFree(h->host_counts);
     if (h->lm_head_packed) (void)hipFree(h->lm_head_packed);
     for (hipEvent_t e : h->probe.ev) (void)hipEventDestroy(e);
+    for (hipEvent_t e : h->probe_head.ev) (void)hipEventDestroy(e);
     delete h;
     return PSD_OK;
 }
@@ -219,9 +220,9 @@ int32_t psd_debug_force_gemm_tile(int32_t tile) {
 
 int32_t psd_probe_begin(psd_handle *h, int32_t epilogue, int32_t tile, int32_t max_launches) {
     if (!h) PSD_FAIL(PSD_ERR_INVALID_ARG, "handle is NULL");
-    if (epilogue < 0 || epilogue > 3 || tile < 0 || tile > 9 || max_launches < 1 || max_launches > (1 << 20))
+    if (epilogue < 0 || epilogue > 4 || tile < 0 || tile > 9 || max_launches < 1 || max_launches > (1 << 20))
         PSD_FAIL(PSD_ERR_INVALID_ARG, "bad probe arguments");
-    psd_handle::Probe &pr = h->probe;
+    psd_handle::Probe &pr = epilogue == 4 ? h->probe_head : h->probe;
     while (pr.ev.size() < (size_t)max_launches * 2) {
         hipEvent_t e;
         PSD_HIP(hipEventCreate(&e));
@@ -235,9 +236,9 @@ int32_t psd_probe_begin(psd_handle *h, int32_t epilogue, int32_t tile, int32_t m
     return PSD_OK;
 }
 
-int32_t psd_probe_end(psd_handle *h, double *total_ms, int64_t *launches, double *flops) {
+int32_t psd_probe_end(psd_handle *h, int32_t epilogue, double *total_ms, int64_t *launches, double *flops) {
     if (!h || !total_ms || !launches || !flops) PSD_FAIL(PSD_ERR_INVALID_ARG, "NULL argument");
-    psd_handle::Probe &pr = h->probe;
+    psd_handle::Probe &pr = epilogue == 4 ? h->probe_head : h->probe;
     pr.enabled = 0;
     double ms = 0.0;
     for (size_t i = 0; i + 1 < pr.used; i += 2) {
@@ -523,6 +524,11 @@ int32_t psd_kernel_mfma_rate(const void *operands, int64_t operand_bytes, int32_
     PSD_HIP(hipGetLastError());
     *flops = 256.0 * 4.0 * iters * 16.0 * 32768.0;
     return PSD_OK;
+}
+
+int32_t psd_kernel_gemm_tile(int64_t M, int32_t Nout, int32_t epilogue) {
+    if (M < 1 || Nout < 1 || epilogue < 0 || epilogue > 3) PSD_FAIL(PSD_ERR_INVALID_ARG, "bad arguments");
+    return gemm_bf16_tile(M, Nout, epilogue);
 }
 
 int32_t psd_forward_work(const psd_model_config *c, int32_t S, int32_t N, int32_t L, psd_work *out) {

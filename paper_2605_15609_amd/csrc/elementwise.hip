@@ -33,7 +33,8 @@ __device__ __forceinline__ float block_sum(float v, float *smem) {
 // out[r, :] = h[src(r), :] * rsqrt(mean(h^2) + eps) * gain ; src(r) = r, or the block rows of each sequence
 template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ h, int d, const float *__restrict__ gain,
-                                                      float eps, T *__restrict__ out, int N, int block_start, int L) {
+                                                      float eps, T *__restrict__ out, int N, int block_start, int L,
+                                                      T *__restrict__ packed) {
     __shared__ float smem[4];
     const int64_t r = blockIdx.x;
     int64_t src = r;
@@ -47,7 +48,13 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ 
     ss = block_sum(ss, smem);
     const float inv = 1.0f / sqrtf(ss / (float)d + eps);
     T *o = out + r * d;
-    for (int c = threadIdx.x; c < d; c += blockDim.x) o[c] = from_float<T>(x[c] * inv * gain[c]);
+    const int nks = d / 16;
+    for (int c = threadIdx.x; c < d; c += blockDim.x) {
+        const T v = from_float<T>(x[c] * inv * gain[c]);
+        o[c] = v;
+        // second copy in MFMA-fragment order [row / 32][c / 16][64 lanes][8] for the streaming LM-head
+        if (packed) packed[(((r >> 5) * nks + (c >> 4)) * 64 + ((c >> 3) & 1) * 32 + (r & 31)) * 8 + (c & 7)] = v;
+    }
 }
 
 // rotate-half rotary embedding in place on the q and k heads of qkv [tokens, (H + 2 Hkv) * dh]
@@ -78,12 +85,13 @@ void launch_embed(const int32_t *tokens, const int32_t *seq_rows, int S, int N, 
 }
 template <typename T>
 void launch_rmsnorm(const float *h, int64_t rows, int d, const float *gain, float eps, T *out, hipStream_t st) {
-    hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out, 0, 0, 0);
+    hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out, 0, 0, 0, (T *)nullptr);
 }
 template <typename T>
 void launch_rmsnorm_block(const float *h, int S, int N, int block_start, int L, int d, const float *gain, float eps,
-                          T *out, hipStream_t st) {
-    hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3((unsigned)(S * L)), dim3(256), 0, st, h, d, gain, eps, out, N, block_start, L);
+                          T *out, T *packed, hipStream_t st) {
+    hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3((unsigned)(S * L)), dim3(256), 0, st, h, d, gain, eps, out, N, block_start, L,
+                       packed);
 }
 template <typename T>
 void launch_rope(T *qkv, int64_t tokens, int N, int n_heads, int n_kv_heads, int d_head, const float *cos_t,
@@ -95,7 +103,7 @@ void launch_rope(T *qkv, int64_t tokens, int N, int n_heads, int n_kv_heads, int
 #define INSTANTIATE(T)                                                                                              \
     template void launch_embed<T>(const int32_t *, const int32_t *, int, int, const T *, int, float *, hipStream_t); \
     template void launch_rmsnorm<T>(const float *, int64_t, int, const float *, float, T *, hipStream_t);           \
-    template void launch_rmsnorm_block<T>(const float *, int, int, int, int, int, const float *, float, T *,        \
+    template void launch_rmsnorm_block<T>(const float *, int, int, int, int, int, const float *, float, T *, T *,   \
                                           hipStream_t);                                                             \
     template void launch_rope<T>(T *, int64_t, int, int, int, int, const float *, const float *, hipStream_t);
 INSTANTIATE(float)

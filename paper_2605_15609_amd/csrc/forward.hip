@@ -121,7 +121,8 @@ int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t 
         Dispatch<T>::gemm(h, a, lw.w_gate, lw.w_up, ntok, F, d, EPI_SWIGLU, nullptr, act, nullptr, F, st);
         Dispatch<T>::gemm(h, act, lw.w_down, nullptr, ntok, d, F, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, st);
     }
-    launch_rmsnorm_block<T>(hbuf, S, N, block_start, L, d, h->final_norm, c.rms_eps, y, st);
+    T *ypack = (c.dtype == PSD_DTYPE_BF16 && h->lm_head_packed && head_stream_supported(S * L, d)) ? (T *)(ws + p.off_ypack) : nullptr;
+    launch_rmsnorm_block<T>(hbuf, S, N, block_start, L, d, h->final_norm, c.rms_eps, y, ypack, st);
     return PSD_OK;
 }
 
@@ -152,10 +153,29 @@ int32_t run_head_confidence(psd_handle *h, const int32_t *tokens, const int32_t 
     const int rows = S * L;
     float *row_sum = (float *)(ws + p.off_rowsum);
     int32_t *row_arg = (int32_t *)(ws + p.off_rowarg);
+    psd_handle::Probe &pr = h->probe_head;
+    const bool timed = pr.enabled && pr.used + 2 <= pr.ev.size();
+    struct StopOnExit {   // closes the timed bracket on every return path
+        psd_handle::Probe &pr;
+        bool on;
+        hipStream_t st;
+        double bytes;
+        ~StopOnExit() {
+            if (!on) return;
+            (void)hipEventRecord(pr.ev[pr.used + 1], st);
+            pr.used += 2;
+            pr.flops += bytes;
+        }
+    } stop{pr, timed, st, (double)c.vocab * c.d_model * (c.dtype == PSD_DTYPE_BF16 ? 2.0 : 4.0) +
+                              (double)rows * c.d_model * (c.dtype == PSD_DTYPE_BF16 ? 2.0 : 4.0) + rows * 8.0};
+    if (timed) (void)hipEventRecord(pr.ev[pr.used], st);
     if (c.dtype == PSD_DTYPE_BF16 && !(h->plain_mask & 4) && h->lm_head_packed && head_stream_supported(rows, c.d_model)) {
-        launch_pack_rows((const bf16_t *)(ws + p.off_y), rows, c.d_model, (bf16_t *)(ws + p.off_ypack), st);
-        launch_head_stream_bf16((const bf16_t *)(ws + p.off_ypack), (const bf16_t *)h->lm_head_packed, rows, c.vocab, c.d_model,
-                                c.logit_scale, c.mask_id, ws + p.off_part, row_sum, row_arg, st);
+        // y was already written in fragment order by the final norm; the merge writes (top1, conf) directly
+        HeadFinish fin = {tokens, seq_rows, out_rows, S, N, block_start, L, top1, conf};
+        launch_head_stream_finish_bf16((const bf16_t *)(ws + p.off_ypack), (const bf16_t *)h->lm_head_packed, rows, c.vocab,
+                                       c.d_model, c.logit_scale, c.mask_id, ws + p.off_part, fin, st);
+        PSD_HIP(hipGetLastError());
+        return PSD_OK;
     } else if (c.dtype == PSD_DTYPE_BF16 && !(h->plain_mask & 4)) {
         launch_head_confidence_bf16((const bf16_t *)(ws + p.off_y), (const bf16_t *)h->lm_head, rows, c.vocab, c.d_model,
                                     c.logit_scale, c.mask_id, ws + p.off_part, row_sum, row_arg, st);

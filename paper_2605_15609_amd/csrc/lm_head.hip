@@ -165,6 +165,44 @@ void launch_stream(const bf16_t *Wp, const bf16_t *Yp, int V, int rows, int d, T
                        t1);
 }
 
+// one workgroup per hidden row: merge the slab triples and write the block tables (prediction on masked
+// positions, sentinel (own token, -1) elsewhere)
+__global__ __launch_bounds__(256) void head_merge_finish_kernel(const float *__restrict__ pmax, const float *__restrict__ psum,
+                                                                const int32_t *__restrict__ parg, int slabs, int rows,
+                                                                HeadFinish fin, int mask_id) {
+    __shared__ float s_b[4], s_s[4];
+    __shared__ int s_a[4];
+    const int r = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    float best = -INFINITY, sum = 0.f;
+    int arg = 0x7fffffff;
+    for (int sl = tid; sl < slabs; sl += 256) {
+        const int64_t o = (int64_t)sl * rows + r;
+        top1_merge(best, arg, sum, pmax[o], parg[o], psum[o]);
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        const float b2 = __shfl_xor(best, off, 64);
+        const int a2 = __shfl_xor(arg, off, 64);
+        const float s2 = __shfl_xor(sum, off, 64);
+        top1_merge(best, arg, sum, b2, a2, s2);
+    }
+    if (lane == 0) {
+        s_b[w] = best;
+        s_a[w] = arg;
+        s_s[w] = sum;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        for (int i = 1; i < 4; ++i) top1_merge(best, arg, sum, s_b[i], s_a[i], s_s[i]);
+        const int s = r / fin.L, j = r % fin.L;
+        const int64_t src = fin.seq_rows ? fin.seq_rows[s] : s;
+        const int64_t dst = fin.out_rows ? fin.out_rows[s] : s;
+        const int32_t tok = fin.tokens[src * fin.N + fin.block_start + j];
+        const bool masked = tok == mask_id;
+        fin.top1[dst * fin.L + j] = masked ? arg : tok;
+        fin.conf[dst * fin.L + j] = masked ? 1.0f / sum : -1.0f;
+    }
+}
+
 }   // namespace
 
 int64_t head_partial_bytes(int rows, int V) {
@@ -182,10 +220,9 @@ void launch_pack_rows(const bf16_t *src, int64_t R, int K, bf16_t *dst, hipStrea
 
 bool head_stream_supported(int rows, int d) { return rows <= 192 && d % 64 == 0; }
 
-void launch_head_stream_bf16(const bf16_t *y_packed, const bf16_t *W_packed, int rows, int V, int d, float scale, int mask_id,
-                             void *partials, float *row_sum, int32_t *row_arg, hipStream_t st) {
+static int stream_partials(const bf16_t *y_packed, const bf16_t *W_packed, int rows, int V, int d, float scale, int mask_id,
+                           void *partials, Top1Args &t1, hipStream_t st) {
     const int64_t stride = align_up((int64_t)((V + 31) / 32) * rows * 4, 256);
-    Top1Args t1;
     t1.scale = scale;
     t1.mask_id = mask_id;
     t1.pmax = (float *)partials;
@@ -210,8 +247,23 @@ void launch_head_stream_bf16(const bf16_t *y_packed, const bf16_t *W_packed, int
         slabs = (V + 63) / 64;
         launch_stream<2, 6, 4>(W_packed, y_packed, V, rows, d, t1, st);
     }
+    return slabs;
+}
+
+void launch_head_stream_bf16(const bf16_t *y_packed, const bf16_t *W_packed, int rows, int V, int d, float scale, int mask_id,
+                             void *partials, float *row_sum, int32_t *row_arg, hipStream_t st) {
+    Top1Args t1;
+    const int slabs = stream_partials(y_packed, W_packed, rows, V, d, scale, mask_id, partials, t1, st);
     hipLaunchKernelGGL(head_merge_kernel, dim3(rows), dim3(64), 0, st, t1.pmax, t1.psum, t1.parg, slabs, rows, row_sum,
                        row_arg);
+}
+
+void launch_head_stream_finish_bf16(const bf16_t *y_packed, const bf16_t *W_packed, int rows, int V, int d, float scale,
+                                    int mask_id, void *partials, const HeadFinish &fin, hipStream_t st) {
+    Top1Args t1;
+    const int slabs = stream_partials(y_packed, W_packed, rows, V, d, scale, mask_id, partials, t1, st);
+    hipLaunchKernelGGL(head_merge_finish_kernel, dim3(rows), dim3(256), 0, st, t1.pmax, t1.psum, t1.parg, slabs, rows, fin,
+                       mask_id);
 }
 
 void launch_head_confidence_bf16(const bf16_t *y, const bf16_t *W, int rows, int V, int d, float scale, int mask_id,

@@ -31,8 +31,8 @@ struct psd_handle {
         int enabled = 0, epi = -1, tile = -1;
         std::vector<hipEvent_t> ev;     // pairs (start, stop)
         size_t used = 0;                // events handed out
-        double flops = 0.0;             // algorithmic FLOPs of the timed launches
-    } probe;
+        double flops = 0.0;             // algorithmic work of the timed launches (FLOPs; bytes for the LM-head pass)
+    } probe, probe_head;
 };
 
 void psd_set_error(const char *fmt, ...);
@@ -99,7 +99,7 @@ template <typename T>
 void launch_rmsnorm(const float *h, int64_t rows, int d, const float *gain, float eps, T *out, hipStream_t st);
 template <typename T>
 void launch_rmsnorm_block(const float *h, int S, int N, int block_start, int L, int d, const float *gain,
-                          float eps, T *out, hipStream_t st);
+                          float eps, T *out, T *packed /* fragment-order copy, may be NULL */, hipStream_t st);
 template <typename T>
 void launch_rope(T *qkv, int64_t tokens, int N, int n_heads, int n_kv_heads, int d_head, const float *cos_t,
                  const float *sin_t, hipStream_t st);
@@ -142,5 +142,14 @@ void launch_pack_rows(const bf16_t *src, int64_t R, int K, bf16_t *dst, hipStrea
 bool head_stream_supported(int rows, int d);
 void launch_head_stream_bf16(const bf16_t *y_packed, const bf16_t *W_packed, int rows, int V, int d, float scale, int mask_id,
                              void *partials, float *row_sum, int32_t *row_arg, hipStream_t st);
+// where the streamed head's result goes: (row_sum, row_arg) and/or the final (top1, conf) tables with sentinels
+struct HeadFinish {
+    const int32_t *tokens, *seq_rows, *out_rows;
+    int S, N, block_start, L;
+    int32_t *top1;
+    float *conf;
+};
+void launch_head_stream_finish_bf16(const bf16_t *y_packed, const bf16_t *W_packed, int rows, int V, int d, float scale,
+                                    int mask_id, void *partials, const HeadFinish &fin, hipStream_t st);
 void launch_head_confidence_bf16(const bf16_t *y, const bf16_t *W, int rows, int V, int d, float scale, int mask_id,
                                  void *partials, float *row_sum, int32_t *row_arg, hipStream_t st);
