@@ -57,6 +57,46 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ 
     }
 }
 
+// the layer norms of the bf16 path: one workgroup per row, the row (d <= 8192) held in registers between the
+// two passes, 32-byte loads and 16-byte stores
+__global__ __launch_bounds__(256) void rmsnorm_bf16_vec_kernel(const float *__restrict__ h, int d, const float *__restrict__ gain,
+                                                               float eps, bf16_t *__restrict__ out) {
+    __shared__ float smem[4];
+    const int64_t r = blockIdx.x;
+    const float4 *x = reinterpret_cast<const float4 *>(h + r * d);
+    const float4 *g = reinterpret_cast<const float4 *>(gain);
+    constexpr int MAXV = 4;                 // 8 floats per chunk, up to 4 chunks per thread: d <= 8192
+    float4 v[MAXV][2];
+    float ss = 0.f;
+    const int nchunk = d / 8;
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+        const int c = i * 256 + threadIdx.x;
+        if (c < nchunk) {
+            v[i][0] = x[2 * c];
+            v[i][1] = x[2 * c + 1];
+            ss += v[i][0].x * v[i][0].x + v[i][0].y * v[i][0].y + v[i][0].z * v[i][0].z + v[i][0].w * v[i][0].w;
+            ss += v[i][1].x * v[i][1].x + v[i][1].y * v[i][1].y + v[i][1].z * v[i][1].z + v[i][1].w * v[i][1].w;
+        }
+    }
+    ss = block_sum(ss, smem);
+    const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+    uint4 *o = reinterpret_cast<uint4 *>(out + r * d);
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i) {
+        const int c = i * 256 + threadIdx.x;
+        if (c < nchunk) {
+            const float4 g0 = g[2 * c], g1 = g[2 * c + 1];
+            uint4 w;
+            w.x = pack_bf16x2(v[i][0].x * inv * g0.x, v[i][0].y * inv * g0.y);
+            w.y = pack_bf16x2(v[i][0].z * inv * g0.z, v[i][0].w * inv * g0.w);
+            w.z = pack_bf16x2(v[i][1].x * inv * g1.x, v[i][1].y * inv * g1.y);
+            w.w = pack_bf16x2(v[i][1].z * inv * g1.z, v[i][1].w * inv * g1.w);
+            o[c] = w;
+        }
+    }
+}
+
 // rotate-half rotary embedding in place on the q and k heads of qkv [tokens, (H + 2 Hkv) * dh]
 template <typename T>
 __global__ __launch_bounds__(256) void rope_kernel(T *__restrict__ qkv, int N, int n_heads, int n_kv_heads, int d_head,
@@ -76,6 +116,40 @@ __global__ __launch_bounds__(256) void rope_kernel(T *__restrict__ qkv, int N, i
     }
 }
 
+// bf16 rotary: a thread owns 8 consecutive pair indices j of one head (two 16-byte accesses each way)
+__global__ __launch_bounds__(256) void rope_bf16_vec_kernel(bf16_t *__restrict__ qkv, int N, int n_heads, int n_kv_heads,
+                                                            int d_head, const float *__restrict__ cos_t,
+                                                            const float *__restrict__ sin_t) {
+    const int64_t t = blockIdx.x;
+    const int pos = (int)(t % N);
+    const int half = d_head >> 1, groups = half >> 3;
+    const int rot_heads = n_heads + n_kv_heads;
+    bf16_t *row = qkv + t * (int64_t)(n_heads + 2 * n_kv_heads) * d_head;
+    for (int idx = threadIdx.x; idx < rot_heads * groups; idx += blockDim.x) {
+        const int hd = idx / groups, j0 = (idx % groups) * 8;
+        uint4 *p1 = reinterpret_cast<uint4 *>(row + hd * d_head + j0);
+        uint4 *p2 = reinterpret_cast<uint4 *>(row + hd * d_head + j0 + half);
+        const uint4 a = *p1, b = *p2;
+        const float4 c0 = *reinterpret_cast<const float4 *>(cos_t + (int64_t)pos * half + j0);
+        const float4 c1 = *reinterpret_cast<const float4 *>(cos_t + (int64_t)pos * half + j0 + 4);
+        const float4 s0 = *reinterpret_cast<const float4 *>(sin_t + (int64_t)pos * half + j0);
+        const float4 s1 = *reinterpret_cast<const float4 *>(sin_t + (int64_t)pos * half + j0 + 4);
+        const float cs[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+        const float sn[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+        const uint32_t au[4] = {a.x, a.y, a.z, a.w}, bu[4] = {b.x, b.y, b.z, b.w};
+        uint32_t oa[4], ob[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float x1l = bf16_bits_to_float((uint16_t)(au[e] & 0xffff)), x1h = bf16_bits_to_float((uint16_t)(au[e] >> 16));
+            const float x2l = bf16_bits_to_float((uint16_t)(bu[e] & 0xffff)), x2h = bf16_bits_to_float((uint16_t)(bu[e] >> 16));
+            oa[e] = pack_bf16x2(x1l * cs[2 * e] - x2l * sn[2 * e], x1h * cs[2 * e + 1] - x2h * sn[2 * e + 1]);
+            ob[e] = pack_bf16x2(x2l * cs[2 * e] + x1l * sn[2 * e], x2h * cs[2 * e + 1] + x1h * sn[2 * e + 1]);
+        }
+        *p1 = make_uint4(oa[0], oa[1], oa[2], oa[3]);
+        *p2 = make_uint4(ob[0], ob[1], ob[2], ob[3]);
+    }
+}
+
 }   // namespace
 
 template <typename T>
@@ -86,6 +160,14 @@ void launch_embed(const int32_t *tokens, const int32_t *seq_rows, int S, int N, 
 template <typename T>
 void launch_rmsnorm(const float *h, int64_t rows, int d, const float *gain, float eps, T *out, hipStream_t st) {
     hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out, 0, 0, 0, (T *)nullptr);
+}
+template <>
+void launch_rmsnorm<bf16_t>(const float *h, int64_t rows, int d, const float *gain, float eps, bf16_t *out, hipStream_t st) {
+    if (d % 8 == 0 && d <= 8192)
+        hipLaunchKernelGGL(rmsnorm_bf16_vec_kernel, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out);
+    else
+        hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out, 0, 0, 0,
+                           (bf16_t *)nullptr);
 }
 template <typename T>
 void launch_rmsnorm_block(const float *h, int S, int N, int block_start, int L, int d, const float *gain, float eps,
@@ -99,6 +181,16 @@ void launch_rope(T *qkv, int64_t tokens, int N, int n_heads, int n_kv_heads, int
     hipLaunchKernelGGL(rope_kernel<T>, dim3((unsigned)tokens), dim3(256), 0, st, qkv, N, n_heads, n_kv_heads, d_head,
                        cos_t, sin_t);
 }
+template <>
+void launch_rope<bf16_t>(bf16_t *qkv, int64_t tokens, int N, int n_heads, int n_kv_heads, int d_head, const float *cos_t,
+                         const float *sin_t, hipStream_t st) {
+    if (d_head % 16 == 0)
+        hipLaunchKernelGGL(rope_bf16_vec_kernel, dim3((unsigned)tokens), dim3(256), 0, st, qkv, N, n_heads, n_kv_heads, d_head,
+                           cos_t, sin_t);
+    else
+        hipLaunchKernelGGL(rope_kernel<bf16_t>, dim3((unsigned)tokens), dim3(256), 0, st, qkv, N, n_heads, n_kv_heads, d_head,
+                           cos_t, sin_t);
+}
 
 #define INSTANTIATE(T)                                                                                              \
     template void launch_embed<T>(const int32_t *, const int32_t *, int, int, const T *, int, float *, hipStream_t); \
@@ -107,4 +199,6 @@ void launch_rope(T *qkv, int64_t tokens, int N, int n_heads, int n_kv_heads, int
                                           hipStream_t);                                                             \
     template void launch_rope<T>(T *, int64_t, int, int, int, int, const float *, const float *, hipStream_t);
 INSTANTIATE(float)
-INSTANTIATE(bf16_t)
+template void launch_embed<bf16_t>(const int32_t *, const int32_t *, int, int, const bf16_t *, int, float *, hipStream_t);
+template void launch_rmsnorm_block<bf16_t>(const float *, int, int, int, int, int, const float *, float, bf16_t *, bf16_t *,
+                                           hipStream_t);

@@ -53,7 +53,7 @@ __global__ __launch_bounds__(64) void head_merge_kernel(const float *__restrict_
 // reduction as the tiled kernel; one triple per (row, wavefront slab) goes to the merge kernel.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-template <int TMV, int TNR, int D>
+template <int TMV, int TNR, int D, int DB = D>
 __global__ __launch_bounds__(256) void head_stream_kernel(const bf16_t *__restrict__ Wp, const bf16_t *__restrict__ Yp, int V,
                                                           int rows, int Kin, int n_slabs, Top1Args t1) {
     const int slab = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6));
@@ -77,16 +77,24 @@ __global__ __launch_bounds__(256) void head_stream_kernel(const bf16_t *__restri
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    u32x4 ra[D][TMV], rb[D][TNR];
-#define PSD_HEAD_FETCH(u, ks)                                                                                  \
+    // operand rings: D k-steps of weight fragments (HBM latency) and DB <= D of hidden-row fragments (L2 latency)
+    static_assert(D % DB == 0, "the hidden-row ring must divide the weight ring");
+    u32x4 ra[D][TMV], rb[DB][TNR];
+#define PSD_HEAD_FETCH_A(u, ks)                                                                                \
     {                                                                                                         \
         _Pragma("unroll") for (int i = 0; i < TMV; ++i)                                                       \
             ra[u][i] = __builtin_amdgcn_raw_buffer_load_b128(rw, voff, (i * nks + (ks)) * 1024, 0);           \
+    }
+#define PSD_HEAD_FETCH_B(u, ks)                                                                                \
+    {                                                                                                         \
         _Pragma("unroll") for (int j = 0; j < TNR; ++j)                                                       \
             rb[u][j] = __builtin_amdgcn_raw_buffer_load_b128(ry, voff, (j * nks + (ks)) * 1024, 0);           \
     }
 #pragma unroll
-    for (int u = 0; u < D; ++u) PSD_HEAD_FETCH(u, u)
+    for (int u = 0; u < D; ++u) {
+        PSD_HEAD_FETCH_A(u, u)
+        if (u < DB) PSD_HEAD_FETCH_B(u, u)
+    }
     for (int ks0 = 0; ks0 < nks; ks0 += D) {
 #pragma unroll
         for (int u = 0; u < D; ++u) {
@@ -95,13 +103,15 @@ __global__ __launch_bounds__(256) void head_stream_kernel(const bf16_t *__restri
 #pragma unroll
                 for (int j = 0; j < TNR; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ra[u][i]),
-                                                                        __builtin_bit_cast(bf16x8, rb[u][j]), acc[i][j], 0, 0, 0);
-            // refill the slot for D k-steps ahead (past the end: the last k-step again, never consumed)
-            const int nx = min(ks0 + u + D, nks - 1);
-            PSD_HEAD_FETCH(u, nx)
+                                                                        __builtin_bit_cast(bf16x8, rb[u % DB][j]), acc[i][j], 0, 0,
+                                                                        0);
+            // refill the slots for D / DB k-steps ahead (past the end: the last k-step again, never consumed)
+            PSD_HEAD_FETCH_A(u, min(ks0 + u + D, nks - 1))
+            PSD_HEAD_FETCH_B(u % DB, min(ks0 + u + DB, nks - 1))
         }
     }
-#undef PSD_HEAD_FETCH
+#undef PSD_HEAD_FETCH_A
+#undef PSD_HEAD_FETCH_B
 
 #pragma unroll
     for (int j = 0; j < TNR; ++j) {
@@ -158,10 +168,10 @@ __global__ __launch_bounds__(256) void pack_rows_kernel(const bf16_t *__restrict
     dst[idx] = v;
 }
 
-template <int TMV, int TNR, int D>
+template <int TMV, int TNR, int D, int DB = D>
 void launch_stream(const bf16_t *Wp, const bf16_t *Yp, int V, int rows, int d, Top1Args t1, hipStream_t st) {
     const int n_slabs = (V + 32 * TMV - 1) / (32 * TMV);
-    hipLaunchKernelGGL((head_stream_kernel<TMV, TNR, D>), dim3((n_slabs + 3) / 4), dim3(256), 0, st, Wp, Yp, V, rows, d, n_slabs,
+    hipLaunchKernelGGL((head_stream_kernel<TMV, TNR, D, DB>), dim3((n_slabs + 3) / 4), dim3(256), 0, st, Wp, Yp, V, rows, d, n_slabs,
                        t1);
 }
 
