@@ -227,7 +227,7 @@ int32_t psd_forward_work(const psd_model_config *cfg, int32_t S, int32_t N, int3
  *          2: resid[m, n] += sum (fp32);  3: out = bf16(silu(A W^T) * (A W2^T)).
  *          A [M, Kin], W / W2 [Nout, Kin]; Nout, Kin multiples of 64; ldo = row stride of out / resid.
  *   attention: qkv [S*N, (n_heads + 2 n_kv_heads) * d_head] with rotary already applied;
- *          vT is scratch of S*N*n_kv_heads*d_head bf16; out [S*N, n_heads*d_head].
+ *          vT is scratch of S*ceil(N/64)*64*n_kv_heads*d_head bf16; out [S*N, n_heads*d_head].
  *   head:  y [rows, d], W [vocab, d] -> row_sum[r] = sum_v exp(z_v - max_v z), row_arg[r] =
  *          argmax_v z_v over v != mask_id, z = scale * y W^T; scratch from
  *          psd_kernel_head_scratch_bytes. */

@@ -437,7 +437,7 @@ def kernel_attention_bf16(qkv: torch.Tensor, S: int, N: int, n_heads: int, n_kv_
                           out: Optional[torch.Tensor] = None, vT: Optional[torch.Tensor] = None):
     lib = load_library()
     if vT is None:
-        vT = torch.empty((S * N * n_kv_heads * d_head,), dtype=torch.bfloat16, device=qkv.device)
+        vT = torch.empty((S * ((N + 63) // 64 * 64) * n_kv_heads * d_head,), dtype=torch.bfloat16, device=qkv.device)
     if out is None:
         out = torch.empty((S * N, n_heads * d_head), dtype=torch.bfloat16, device=qkv.device)
     _check(lib.psd_kernel_attention_bf16(_ptr(qkv), S, N, n_heads, n_kv_heads, d_head, _ptr(vT), _ptr(out), _stream()))

@@ -13,8 +13,8 @@
 // key 8*(e/4) + 4*half + e%4 of each group of 16); V^T tiles are stored in LDS in that same
 // permuted key order, so a lane's 8 values are one 16-byte read.
 //
-// One workgroup = 4 wavefronts = 128 queries of one (sequence, head); K and V^T tiles of
-// 64 keys are staged through double-buffered, XOR-swizzled LDS.  Grouped KV heads: the
+// One workgroup = 4 (or 2) wavefronts = 128 (64) queries of one (sequence, head); K and V^T tiles
+// of 64 keys go global -> LDS directly (buffer_load ... lds) into double-buffered, XOR-swizzled LDS.  Grouped KV heads: the
 // query heads of a group simply read the same K / V^T tiles (they hit L2).
 #include "psd_internal.h"
 #include "device_types.h"
@@ -24,35 +24,36 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int BQ = 128;    // queries per workgroup
 constexpr int BKV = 64;    // keys per stage
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 u) { return __builtin_bit_cast(bf16x8, u); }
 
-template <int DH>
-__global__ __launch_bounds__(256) void attention_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ vT, int N,
-                                                        int n_heads, int n_kv_heads, bf16_t *__restrict__ out) {
+typedef __attribute__((address_space(3))) void lds_void;
+
+// NW wavefronts (32 queries each) per workgroup; N_pad = row length of vT (N rounded up to 64, tail zero)
+template <int DH, int NW>
+__global__ __launch_bounds__(NW * 64) void attention_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ vT, int N,
+                                                            int N_pad, int n_heads, int n_kv_heads, bf16_t *__restrict__ out) {
     constexpr int KROW = DH * 2;                 // bytes per K row in LDS
     constexpr int K_BYTES = BKV * KROW;
     constexpr int VROW = BKV * 2;                // bytes per V^T row in LDS (128)
     constexpr int V_BYTES = DH * VROW;
     constexpr int STAGE = K_BYTES + V_BYTES;
-    constexpr int KCH = BKV * (DH / 8) / 256;    // 16-byte chunks per thread, K tile
-    constexpr int VCH = DH * 8 / 256;            // 16-byte chunks per thread, V^T tile
     constexpr int CT = DH / 32;                  // output subtiles along the head dimension
     constexpr int KS = DH / 16;                  // k-steps of the score contraction
-    __shared__ __align__(16) unsigned char lds[2 * STAGE];
+    constexpr int KRPI = 1024 / KROW;            // K rows moved by one DMA instruction (4 or 8)
+    constexpr int KG = BKV / KRPI / NW;          // K-tile DMA instructions per wavefront
+    constexpr int VG = DH / 8 / NW;              // V^T-tile DMA instructions per wavefront (8 rows each)
+    extern __shared__ __align__(16) unsigned char lds[];
 
-    const int q0 = blockIdx.x * BQ, head = blockIdx.y, s = blockIdx.z;
+    const int q0 = blockIdx.x * (32 * NW), head = blockIdx.y, s = blockIdx.z;
     const int kvh = head / (n_heads / n_kv_heads);
     const int row_w = (n_heads + 2 * n_kv_heads) * DH;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lrow = lane & 31, lhalf = lane >> 5;
     const bf16_t *seq = qkv + (int64_t)s * N * row_w;
-    const bf16_t *vt_head = vT + ((int64_t)s * n_kv_heads + kvh) * DH * (int64_t)N;
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
 
     // Q fragments: lane (q = lrow, half) holds Q[q][16*ks + 8*half .. +7]
     bf16x8 qf[KS];
@@ -67,41 +68,36 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t *__restrict
         }
     }
 
-    uint4 rk[KCH], rv[VCH];
-// global -> registers for the key tile starting at k0 (keys past the end read as zero)
-#define PSD_ATT_LOAD_GLOBAL(k0)                                                                                  \
+    // K and V^T tiles go global -> LDS directly (buffer_load ... lds), 1 KB per instruction, with the XOR
+    // swizzle applied on the global side: the lane that lands at (row, slot) fetches chunk slot ^ key(row),
+    // key(row) = (row >> 1) & 7.  Row groups are dealt round-robin to the wavefronts.  Keys past the end of
+    // the sequence are rejected by the descriptor (K) or read the zero padding of vT.
+    const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t *>(seq) + (n_heads + kvh) * DH, 0, (int)(((int64_t)N * row_w - (n_heads + kvh) * DH) * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t *>(vT) + ((int64_t)s * n_kv_heads + kvh) * DH * (int64_t)N_pad, 0, DH * N_pad * 2, 0x00020000);
+    constexpr int KLPR = 64 / KRPI;              // lanes per K row in one DMA instruction (16 or 8)
+#define PSD_ATT_DMA(stage, k0)                                                                                   \
     {                                                                                                            \
-        _Pragma("unroll") for (int i = 0; i < KCH; ++i) {                                                        \
-            const int qd = i * 256 + tid, r = qd / (DH / 8), c = qd % (DH / 8);                                  \
-            const int key = (k0) + r;                                                                            \
-            rk[i] = zero4;                                                                                       \
-            if (key < N)                                                                                         \
-                rk[i] = *reinterpret_cast<const uint4 *>(seq + (int64_t)key * row_w + (n_heads + kvh) * DH + c * 8); \
+        unsigned char *sk_ = lds + (stage) * STAGE + wave * 1024, *sv_ = lds + (stage) * STAGE + K_BYTES + wave * 1024; \
+        _Pragma("unroll") for (int j = 0; j < KG; ++j) {                                                         \
+            const int row = (j * NW + wave) * KRPI + lane / KLPR;                                                \
+            const int voff = (lane / KLPR) * row_w * 2 + (((lane % KLPR) ^ ((row >> 1) & 7)) << 4);              \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_void *)(sk_ + j * (NW * 1024)), 16, voff,          \
+                                                     (((k0) + (j * NW + wave) * KRPI) * row_w) * 2, 0, 0);        \
         }                                                                                                        \
-        _Pragma("unroll") for (int i = 0; i < VCH; ++i) {                                                        \
-            const int qd = i * 256 + tid, r = qd >> 3, c = qd & 7;                                               \
-            const int key = (k0) + c * 8;                                                                        \
-            rv[i] = zero4;                                                                                       \
-            if (key < N) rv[i] = *reinterpret_cast<const uint4 *>(vt_head + (int64_t)r * N + key);               \
+        _Pragma("unroll") for (int j = 0; j < VG; ++j) {                                                         \
+            const int row = (j * NW + wave) * 8 + (lane >> 3);                                                   \
+            const int voff = (lane >> 3) * N_pad * 2 + (((lane & 7) ^ ((row >> 1) & 7)) << 4);                   \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_void *)(sv_ + j * (NW * 1024)), 16, voff,          \
+                                                     ((j * NW + wave) * 8 * N_pad + (k0)) * 2, 0, 0);            \
         }                                                                                                        \
     }
-// registers -> LDS.  V^T chunk c holds keys 8c..8c+7 of a row; keys 4w..4w+3 of each 8-key half u of a
-// 16-key group kg go to chunk (2*kg + w), 8-byte slot u: the permuted key order of the second MFMA
-#define PSD_ATT_STORE_LDS(stage)                                                                                 \
+#define PSD_ATT_SYNC()                                                                                           \
     {                                                                                                            \
-        unsigned char *sk_ = lds + (stage) * STAGE, *sv_ = sk_ + K_BYTES;                                        \
-        _Pragma("unroll") for (int i = 0; i < KCH; ++i) {                                                        \
-            const int qd = i * 256 + tid, r = qd / (DH / 8), c = qd % (DH / 8);                                  \
-            *reinterpret_cast<uint4 *>(sk_ + r * KROW + ((c ^ ((r >> 1) & 7)) << 4)) = rk[i];                           \
-        }                                                                                                        \
-        _Pragma("unroll") for (int i = 0; i < VCH; ++i) {                                                        \
-            const int qd = i * 256 + tid, r = qd >> 3, c = qd & 7;                                               \
-            const int kg = c >> 1, u = c & 1;                                                                    \
-            *reinterpret_cast<uint2 *>(sv_ + r * VROW + (((kg * 2 + 0) ^ ((r >> 1) & 7)) << 4) + u * 8) =               \
-                make_uint2(rv[i].x, rv[i].y);                                                                    \
-            *reinterpret_cast<uint2 *>(sv_ + r * VROW + (((kg * 2 + 1) ^ ((r >> 1) & 7)) << 4) + u * 8) =               \
-                make_uint2(rv[i].z, rv[i].w);                                                                    \
-        }                                                                                                        \
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                                         \
+        __builtin_amdgcn_s_barrier();                                                                            \
+        asm volatile("" ::: "memory");                                                                           \
     }
 
     floatx16 acc_o[CT];
@@ -113,13 +109,14 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t *__restrict
     const float sl2 = 1.4426950408889634f / sqrtf((float)DH);   // softmax scale folded into exp2
 
     const int n_tiles = (N + BKV - 1) / BKV;
-    PSD_ATT_LOAD_GLOBAL(0)
-    PSD_ATT_STORE_LDS(0)
-    __syncthreads();
+    PSD_ATT_DMA(0, 0)
+    PSD_ATT_SYNC()
 
     for (int t = 0; t < n_tiles; ++t) {
         const int stage = t & 1, k0 = t * BKV;
-        if (t + 1 < n_tiles) PSD_ATT_LOAD_GLOBAL(k0 + BKV)
+        // next tile into the other buffer (every wavefront left it at the last barrier); past the last tile the
+        // fetch is rejected or reads padding and is never consumed
+        PSD_ATT_DMA(stage ^ 1, k0 + BKV)
         const unsigned char *sk = lds + stage * STAGE, *sv = sk + K_BYTES;
 
         // scores, transposed: acc_s[kt][v] <-> key 32*kt + 8*(v/4) + 4*half + v%4, query lrow
@@ -192,12 +189,11 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t *__restrict
                 acc_o[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kg], acc_o[ct], 0, 0, 0);
             }
         }
-        if (t + 1 < n_tiles) PSD_ATT_STORE_LDS(stage ^ 1)
-        __syncthreads();
+        PSD_ATT_SYNC()
     }
+#undef PSD_ATT_DMA
+#undef PSD_ATT_SYNC
 
-#undef PSD_ATT_LOAD_GLOBAL
-#undef PSD_ATT_STORE_LDS
     // the two half-waves of a query hold disjoint key subsets of the sum
     l_run += __shfl_xor(l_run, 32, 64);
     const float inv = 1.0f / l_run;
@@ -217,9 +213,11 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t *__restrict
     }
 }
 
-// vT[s][kvh][c][i] = qkv[s*N + i][(H + Hkv + kvh)*dh + c], 64x64 tiles through LDS
-__global__ __launch_bounds__(256) void transpose_v_kernel(const bf16_t *__restrict__ qkv, int N, int n_heads, int n_kv_heads,
-                                                          int d_head, bf16_t *__restrict__ vT) {
+// vT[s][kvh][c][pi(i)] = qkv[s*N + i][(H + Hkv + kvh)*dh + c], 64x64 tiles through LDS.  Rows of vT are N_pad long
+// (N rounded up to 64, the tail zero).  Inside every group of 16 keys the order is 0-3, 8-11, 4-7, 12-15: the
+// contraction-slot order of the second attention MFMA, so that a lane's 8 values are one 16-byte piece.
+__global__ __launch_bounds__(256) void transpose_v_kernel(const bf16_t *__restrict__ qkv, int N, int N_pad, int n_heads,
+                                                          int n_kv_heads, int d_head, bf16_t *__restrict__ vT) {
     __shared__ uint16_t tile[64][66];
     const int i0 = blockIdx.x * 64, cg = blockIdx.y, s = blockIdx.z;   // cg indexes 64-wide column groups of all KV heads
     const int row_w = (n_heads + 2 * n_kv_heads) * d_head;
@@ -230,10 +228,12 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const bf16_t *__restri
         tile[r][tx] = (i < N) ? qkv[((int64_t)s * N + i) * row_w + (n_heads + n_kv_heads) * d_head + col0 + tx].bits : 0;
     }
     __syncthreads();
+    // destination key slot tx holds source key: swap the middle two 4-key pieces of each 16-group
+    const int piece = (tx >> 2) & 3;
+    const int src_key = (tx & ~15) | ((((piece & 1) << 1) | (piece >> 1)) << 2) | (tx & 3);
     for (int r = ty; r < 64; r += 4) {
         const int c = col0 + r;   // = kvh * d_head + channel
-        const int i = i0 + tx;
-        if (i < N) vT[((int64_t)s * n_kv_heads * d_head + c) * N + i].bits = tile[tx][r];
+        vT[((int64_t)s * n_kv_heads * d_head + c) * N_pad + i0 + tx].bits = tile[src_key][r];
     }
 }
 
@@ -241,15 +241,36 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const bf16_t *__restri
 
 void launch_transpose_v(const bf16_t *qkv, int S, int N, int n_heads, int n_kv_heads, int d_head, bf16_t *vT,
                         hipStream_t st) {
-    hipLaunchKernelGGL(transpose_v_kernel, dim3((N + 63) / 64, n_kv_heads * d_head / 64, S), dim3(256), 0, st, qkv, N,
+    const int N_pad = (N + 63) / 64 * 64;
+    hipLaunchKernelGGL(transpose_v_kernel, dim3(N_pad / 64, n_kv_heads * d_head / 64, S), dim3(256), 0, st, qkv, N, N_pad,
                        n_heads, n_kv_heads, d_head, vT);
+}
+
+template <int DH, int NW>
+static void launch_att(const bf16_t *qkv, const bf16_t *vT, int S, int N, int n_heads, int n_kv_heads, bf16_t *out,
+                       hipStream_t st) {
+    const int N_pad = (N + 63) / 64 * 64;
+    constexpr int smem = 2 * (BKV * DH * 2 + DH * BKV * 2);
+    auto kern = attention_kernel<DH, NW>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        attr_done = true;
+    }
+    dim3 grid((N + 32 * NW - 1) / (32 * NW), n_heads, S);
+    hipLaunchKernelGGL(kern, grid, dim3(NW * 64), smem, st, qkv, vT, N, N_pad, n_heads, n_kv_heads, out);
 }
 
 void launch_attention_bf16(const bf16_t *qkv, const bf16_t *vT, int S, int N, int n_heads, int n_kv_heads, int d_head,
                            bf16_t *out, hipStream_t st) {
-    dim3 grid((N + BQ - 1) / BQ, n_heads, S);
-    if (d_head == 128)
-        hipLaunchKernelGGL(attention_kernel<128>, grid, dim3(256), 0, st, qkv, vT, N, n_heads, n_kv_heads, out);
-    else
-        hipLaunchKernelGGL(attention_kernel<64>, grid, dim3(256), 0, st, qkv, vT, N, n_heads, n_kv_heads, out);
+    // 128 queries per workgroup when that still gives two workgroups per CU, else 64
+    const int64_t blocks128 = (int64_t)((N + 127) / 128) * n_heads * S;
+    const bool small = blocks128 < 512;
+    if (d_head == 128) {
+        if (small) launch_att<128, 2>(qkv, vT, S, N, n_heads, n_kv_heads, out, st);
+        else launch_att<128, 4>(qkv, vT, S, N, n_heads, n_kv_heads, out, st);
+    } else {
+        if (small) launch_att<64, 2>(qkv, vT, S, N, n_heads, n_kv_heads, out, st);
+        else launch_att<64, 4>(qkv, vT, S, N, n_heads, n_kv_heads, out, st);
+    }
 }

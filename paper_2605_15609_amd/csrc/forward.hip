@@ -19,7 +19,7 @@ ForwardPlan plan_forward(const psd_model_config &cfg, int64_t S, int64_t N, int6
     p.off_h = take(T * cfg.d_model * 4);
     p.off_a = take(T * cfg.d_model * esz);
     p.off_qkv = take(T * qkv_w * esz);
-    p.off_vt = take(T * (int64_t)cfg.n_kv_heads * cfg.d_head * esz);
+    p.off_vt = take(S * ((N + 63) / 64 * 64) * (int64_t)cfg.n_kv_heads * cfg.d_head * esz);   // rows padded to 64 keys
     p.off_o = take(T * (int64_t)cfg.n_heads * cfg.d_head * esz);
     p.off_act = take(T * cfg.d_ffn * esz);
     p.off_y = take(rows * cfg.d_model * esz);
