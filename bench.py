@@ -118,7 +118,6 @@ def main():
     # dominant kernel: the SwiGLU gate/up contraction of the verification forward
     bf16 = shape.dtype == "bf16"
     lib = psd.load_library()
-    tile_names = {0: "128, 128, 2, 2, 3, 2", 9: "256, 256, 4, 2, 3, 2"}
     if bf16:
         # the tile the dispatcher picks for the verification pass's SwiGLU contraction
         swiglu_tile = lib.psd_kernel_gemm_tile(w.batch * w.n_drafts * w.seq_len, shape.d_ffn, 3)
@@ -142,7 +141,7 @@ def main():
             achieved = flops / (ms * 1e-3) / 1e12
             roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                         "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                        "kernel": f"mfma::gemm_bf16_kernel<{tile_names.get(swiglu_tile, swiglu_tile)}> (SwiGLU gate/up contraction)", "launches": int(launches),
+                        "kernel": f"mfma::gemm_bf16_kernel, SwiGLU gate/up contraction, tile {lib.psd_kernel_gemm_tile_name(swiglu_tile).decode()}", "launches": int(launches),
                         "avg_launch_us": ms * 1e3 / launches, "flops_per_launch": flops / launches}
 
     if args.calibrate_copy:

@@ -160,7 +160,8 @@ int32_t psd_forward_logits(psd_handle *h, const int32_t *tokens, int32_t S, int3
 int32_t psd_debug_set_plain(psd_handle *h, int32_t mask);
 
 /* Debug / tuning: forces the workgroup tile of the layer contractions (see psd_probe_begin
- * for the numbering; -1 = pick per shape).  Process-wide. */
+ * and psd_kernel_gemm_tile_name for the numbering; -1 = pick per shape; a tile that cannot run the
+ * epilogue asked for is ignored).  Process-wide. */
 int32_t psd_debug_force_gemm_tile(int32_t tile);
 
 /* Stage 1 commit (Eq. 1): applies pi to every sequence in place.
@@ -258,9 +259,9 @@ int32_t psd_kernel_mfma_rate(const void *operands, int64_t operand_bytes, int32_
 
 /* Kernel timing for roofline accounting.  Between psd_probe_begin and psd_probe_end every
  * launch of the layer-contraction kernel with the given epilogue (0 store, 1 bias,
- * 2 residual, 3 SwiGLU) and workgroup tile (0: 128x128, 1: 256x256, 2: 256x128, 3: 128x64, 4: 128x192
- * on a 2-stage LDS ring; 5: 128x64, 6: 128x128, 7: 64x64 on a 4-stage ring; 8, 9: 256x256 with 8
- * wavefronts arranged 2x4 / 4x2) is bracketed by HIP events on the stream it is launched on (up to
+ * 2 residual, 3 SwiGLU) and workgroup tile configuration (an index below
+ * psd_kernel_gemm_tile_count; psd_kernel_gemm_tile_name describes it: tile extent, wavefronts,
+ * depths of the two LDS rings) is bracketed by HIP events on the stream it is launched on (up to
  * max_launches; later ones go untimed).  Epilogue 4 selects the LM-head confidence pass instead
  * (all its kernels, tile ignored); it can be timed together with one contraction kernel.
  * psd_probe_end waits for those events and returns their summed duration, the number of timed
@@ -270,6 +271,9 @@ int32_t psd_kernel_mfma_rate(const void *operands, int64_t operand_bytes, int32_
 int32_t psd_probe_begin(psd_handle *h, int32_t epilogue, int32_t tile, int32_t max_launches);
 int32_t psd_probe_end(psd_handle *h, int32_t epilogue, double *total_ms, int64_t *launches, double *work);
 int32_t psd_kernel_gemm_tile(int64_t M, int32_t Nout, int32_t epilogue);
+/* Number of tile configurations (valid tile ids are 0 .. count-1) and a static description of one. */
+int32_t psd_kernel_gemm_tile_count(void);
+const char *psd_kernel_gemm_tile_name(int32_t tile);
 
 #ifdef __cplusplus
 }

@@ -106,6 +106,8 @@ def load_library():
         "psd_probe_begin": (i32, [vp, i32, i32, i32]),
         "psd_probe_end": (i32, [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
         "psd_kernel_gemm_tile": (i32, [i64, i32, i32]),
+        "psd_kernel_gemm_tile_count": (i32, []),
+        "psd_kernel_gemm_tile_name": (C.c_char_p, [i32]),
         "psd_forward_work": (i32, [C.POINTER(_Config), i32, i32, i32, C.POINTER(_Work)]),
     }
     for name, (res, args) in sig.items():

@@ -220,7 +220,7 @@ int32_t psd_debug_force_gemm_tile(int32_t tile) {
 
 int32_t psd_probe_begin(psd_handle *h, int32_t epilogue, int32_t tile, int32_t max_launches) {
     if (!h) PSD_FAIL(PSD_ERR_INVALID_ARG, "handle is NULL");
-    if (epilogue < 0 || epilogue > 4 || tile < 0 || tile > 9 || max_launches < 1 || max_launches > (1 << 20))
+    if (epilogue < 0 || epilogue > 4 || tile < 0 || tile >= gemm_bf16_tile_count() || max_launches < 1 || max_launches > (1 << 20))
         PSD_FAIL(PSD_ERR_INVALID_ARG, "bad probe arguments");
     psd_handle::Probe &pr = epilogue == 4 ? h->probe_head : h->probe;
     while (pr.ev.size() < (size_t)max_launches * 2) {
@@ -530,6 +530,9 @@ int32_t psd_kernel_gemm_tile(int64_t M, int32_t Nout, int32_t epilogue) {
     if (M < 1 || Nout < 1 || epilogue < 0 || epilogue > 3) PSD_FAIL(PSD_ERR_INVALID_ARG, "bad arguments");
     return gemm_bf16_tile(M, Nout, epilogue);
 }
+
+int32_t psd_kernel_gemm_tile_count(void) { return gemm_bf16_tile_count(); }
+const char *psd_kernel_gemm_tile_name(int32_t tile) { return gemm_bf16_tile_name(tile); }
 
 int32_t psd_forward_work(const psd_model_config *c, int32_t S, int32_t N, int32_t L, psd_work *out) {
     CHECK(check_cfg(c));

@@ -2,8 +2,11 @@
 // (v_mfma_f32_32x32x16_bf16, fp32 accumulation).  Both operands are K-contiguous ("NT"
 // form), the natural MFMA feed: every lane fetches 8 consecutive k (16 bytes) of one row.
 //
-// Tiling: a workgroup of 4 wavefronts owns a BM x BN tile; K advances 64 at a time through
-// a ring of NSTAGE LDS stages filled by direct global -> LDS loads, one barrier per stage.
+// Tiling: a workgroup of 4 or 8 wavefronts owns a BM x BN tile; K advances 64 at a time.  Each
+// operand tile has its own ring of LDS stages (NSA for X, NSB for Y) filled by direct global -> LDS
+// loads, one barrier per stage.  The rings differ in depth because the operands differ in where
+// they come from: activations were just written and sit in cache, weights arrive cold from HBM and
+// need their fetches several stages ahead.
 // LDS rows are 128 bytes; the 16-byte chunk c of row r sits at chunk slot c ^ ((r >> 1) & 7),
 // so the 32 rows a wavefront touches per fragment fetch spread over all 64 banks.  Workgroup ids are remapped so
 // that each of the 8 XCDs (which receive consecutive ids round-robin) works on a compact
@@ -72,7 +75,7 @@ __device__ __forceinline__ void sched_mix() {
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, int NSTAGE>
+template <int BM, int BN, int WGM, int WGN, int EPI, int NSA, int NSB>
 __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Y,
                                                         const bf16_t *__restrict__ Y2, int M, int Nout, int Kin,
                                                         const float *__restrict__ bias, bf16_t *__restrict__ out,
@@ -81,7 +84,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
     extern __shared__ __align__(16) unsigned char lds[];
     constexpr bool DUAL = EPI == EPI_SWIGLU;
     constexpr int BN_OUT = DUAL ? BN / 2 : BN;            // output columns per tile
-    constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES, STAGE = A_BYTES + B_BYTES;
+    constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES, B_RING = NSA * A_BYTES;   // X ring first, then the Y ring
     constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
     constexpr int NW = WGM * WGN;   // wavefronts per workgroup
     static_assert((NW == 4 || NW == 8) && TM >= 1 && TN >= 1 && (!DUAL || TN % 2 == 0), "tile shape");
@@ -138,13 +141,17 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
     constexpr int NLD = GA + GB;                      // DMA instructions per wavefront per stage
     typedef __attribute__((address_space(3))) void lds_void;
 
-// global -> LDS stage, K position k0
-#define PSD_GEMM_DMA(stage, k0)                                                                               \
+// global -> LDS: one stage of the X tile / of the Y tile, K position k0, into ring slot `slot`
+#define PSD_GEMM_DMA_A(slot, k0)                                                                              \
     {                                                                                                         \
-        unsigned char *sa_ = lds + (stage) * STAGE + uwave * 1024, *sb_ = sa_ + A_BYTES;                      \
+        unsigned char *sa_ = lds + (slot) * A_BYTES + uwave * 1024;                                           \
         _Pragma("unroll") for (int j = 0; j < GA; ++j)                                                        \
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, (lds_void *)(sa_ + j * (NW * 1024)), 16, voff,   \
                                                      ((j * NW + uwave) * 8 * Kin + (k0)) * 2, 0, 0);          \
+    }
+#define PSD_GEMM_DMA_B(slot, k0)                                                                              \
+    {                                                                                                         \
+        unsigned char *sb_ = lds + B_RING + (slot) * B_BYTES + uwave * 1024;                                  \
         _Pragma("unroll") for (int j = 0; j < GB; ++j) {                                                      \
             if (DUAL && j * (8 * NW) >= BN / 2)                                                               \
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_y2, (lds_void *)(sb_ + j * (NW * 1024)), 16, voff, \
@@ -154,11 +161,26 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
                                                          ((j * NW + uwave) * 8 * Kin + (k0)) * 2, 0, 0);      \
         }                                                                                                     \
     }
-// the oldest DMA stage of this wavefront has landed (the NSTAGE-2 younger ones may still fly); then all wavefronts agree (s_barrier), and the compiler must
-// not move LDS accesses across the point
-#define PSD_GEMM_STAGE_SYNC()                                                                                 \
+// Every iteration issues the fetch of the shallower ring first.  Memory returns in issue order, so
+// once the counter says that at most WAIT younger DMA instructions are in flight, both tiles of the
+// next stage have landed: with the X ring shallower, its stage kt+1 was issued NSA-2 iterations ago
+// and only that iteration's Y fetch plus NSA-2 whole iterations are younger (and mirrored).
+#define PSD_GEMM_ISSUE(sa, sb, kt_)                                                                           \
     {                                                                                                         \
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTAGE - 2) * NLD) : "memory");                             \
+        if constexpr (NSA <= NSB) {                                                                           \
+            PSD_GEMM_DMA_A(sa, ((kt_) + NSA - 1) * BK)                                                        \
+            PSD_GEMM_DMA_B(sb, ((kt_) + NSB - 1) * BK)                                                        \
+        } else {                                                                                              \
+            PSD_GEMM_DMA_B(sb, ((kt_) + NSB - 1) * BK)                                                        \
+            PSD_GEMM_DMA_A(sa, ((kt_) + NSA - 1) * BK)                                                        \
+        }                                                                                                     \
+    }
+    constexpr int WAIT = NSA < NSB ? (NSA - 2) * NLD + GB : NSA > NSB ? (NSB - 2) * NLD + GA : (NSA - 2) * NLD;
+// the DMAs of the next stage have landed; then all wavefronts agree (s_barrier), and the compiler must
+// not move LDS accesses across the point
+#define PSD_GEMM_STAGE_SYNC(n)                                                                                \
+    {                                                                                                         \
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory");                                              \
         __builtin_amdgcn_s_barrier();                                                                         \
         asm volatile("" ::: "memory");                                                                        \
     }
@@ -179,19 +201,19 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
         } else {
             r = wn * WTN + j * 32 + lrow;
         }
-        offb[j] = A_BYTES + r * ROW_BYTES;
+        offb[j] = B_RING + r * ROW_BYTES;
     }
     const int rsw = (lrow >> 1) & 7;   // swizzle key of every fragment row of this lane: rows differ by multiples of 32
 
 // fragments of k-step kk of an LDS stage into register set `set`
-#define PSD_GEMM_LOAD_FRAGS(stage, kk, set)                                                                   \
+#define PSD_GEMM_LOAD_FRAGS(sa, sb, kk, set)                                                                  \
     {                                                                                                         \
-        const unsigned char *s_ = lds + (stage) * STAGE;                                                      \
+        const unsigned char *a_ = lds + (sa) * A_BYTES, *b_ = lds + (sb) * B_BYTES;                           \
         const int co_ = ((((kk) * 2 + lhalf) ^ rsw) << 4);                                                    \
         _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                        \
-            fa[set][i] = *reinterpret_cast<const bf16x8 *>(s_ + offa[i] + co_);                               \
+            fa[set][i] = *reinterpret_cast<const bf16x8 *>(a_ + offa[i] + co_);                               \
         _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                        \
-            fb[set][j] = *reinterpret_cast<const bf16x8 *>(s_ + offb[j] + co_);                               \
+            fb[set][j] = *reinterpret_cast<const bf16x8 *>(b_ + offb[j] + co_);                               \
     }
 #define PSD_GEMM_MFMA(set)                                                                                    \
     {                                                                                                         \
@@ -203,41 +225,46 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
     bf16x8 fa[2][TM], fb[2][TN];
     constexpr int NFRAG = TM + TN, NMFMA = TM * TN;
 
-    static_assert(NSTAGE >= 2 && (NSTAGE - 2) * NLD <= 63, "DMA groups in flight must fit the vmcnt counter");
+    static_assert(NSA >= 2 && NSB >= 2 && (NSA - 1) * GA + (NSB - 1) * GB <= 63, "DMA groups in flight must fit the vmcnt counter");
 #pragma unroll
-    for (int p = 0; p < NSTAGE - 1; ++p) PSD_GEMM_DMA(p, p * BK)
-    PSD_GEMM_STAGE_SYNC()
-    PSD_GEMM_LOAD_FRAGS(0, 0, 0)
+    for (int p = 0; p < NSA - 1; ++p) PSD_GEMM_DMA_A(p, p * BK)
+#pragma unroll
+    for (int p = 0; p < NSB - 1; ++p) PSD_GEMM_DMA_B(p, p * BK)
+    PSD_GEMM_STAGE_SYNC(0)
+    PSD_GEMM_LOAD_FRAGS(0, 0, 0, 0)
 
-    // Per K-stage: the DMA of stage kt+NSTAGE-1 goes out during k-step 0, into the ring slot every
-    // wavefront left at the last barrier, and has NSTAGE-1 stages to land.  k-steps 0..2 compute with
+    // Per K-stage: the DMAs that refill the ring slots every wavefront left at the last barrier go
+    // out during k-step 0 (X stage kt+NSA-1, Y stage kt+NSB-1).  k-steps 0..2 compute with
     // the next k-step's fragments in flight; after the stage barrier k-step 3 computes while the first
     // fragments of the next stage arrive.  The body is branch-free: fetches past the end of K stay
     // inside the buffer range (or are rejected) and land in ring slots that are never consumed.
-    int cur = 0;
+    int ca = 0, cb = 0;
     for (int kt = 0; kt < nk; ++kt) {
-        const int nxt = (cur + 1 == NSTAGE) ? 0 : cur + 1;
-        const int fill = (cur == 0) ? NSTAGE - 1 : cur - 1;
-        PSD_GEMM_LOAD_FRAGS(cur, 1, 1)
-        PSD_GEMM_DMA(fill, (kt + NSTAGE - 1) * BK)
+        const int na = (ca + 1 == NSA) ? 0 : ca + 1, nb = (cb + 1 == NSB) ? 0 : cb + 1;
+        const int fill_a = (ca == 0) ? NSA - 1 : ca - 1, fill_b = (cb == 0) ? NSB - 1 : cb - 1;
+        PSD_GEMM_LOAD_FRAGS(ca, cb, 1, 1)
+        PSD_GEMM_ISSUE(fill_a, fill_b, kt)
         PSD_GEMM_MFMA(0)
         sched_mix<0, NMFMA, NFRAG, 0, NLD>();
-        PSD_GEMM_LOAD_FRAGS(cur, 2, 0)
+        PSD_GEMM_LOAD_FRAGS(ca, cb, 2, 0)
         PSD_GEMM_MFMA(1)
         sched_mix<0, NMFMA, NFRAG, 0, 0>();
-        PSD_GEMM_LOAD_FRAGS(cur, 3, 1)
+        PSD_GEMM_LOAD_FRAGS(ca, cb, 3, 1)
         PSD_GEMM_MFMA(0)
         sched_mix<0, NMFMA, NFRAG, 0, 0>();
-        PSD_GEMM_STAGE_SYNC()
-        PSD_GEMM_LOAD_FRAGS(nxt, 0, 0)
+        PSD_GEMM_STAGE_SYNC(WAIT)
+        PSD_GEMM_LOAD_FRAGS(na, nb, 0, 0)
         PSD_GEMM_MFMA(1)
         sched_mix<0, NMFMA, NFRAG, 0, 0>();
-        cur = nxt;
+        ca = na;
+        cb = nb;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no DMA may outlive the loop
 #undef PSD_GEMM_LOAD_FRAGS
 #undef PSD_GEMM_MFMA
-#undef PSD_GEMM_DMA
+#undef PSD_GEMM_DMA_A
+#undef PSD_GEMM_DMA_B
+#undef PSD_GEMM_ISSUE
 #undef PSD_GEMM_STAGE_SYNC
 
     if constexpr (EPI == EPI_TOP1) {
@@ -321,15 +348,15 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, int NSTAGE = 2>
+template <int BM, int BN, int WGM, int WGN, int EPI, int NSA = 2, int NSB = NSA>
 void launch_cfg(const bf16_t *X, const bf16_t *Y, const bf16_t *Y2, int M, int Nout, int Kin, const float *bias,
                 bf16_t *out, float *resid, int ldo, Top1Args t1, hipStream_t st) {
     constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (Nout + BN_OUT - 1) / BN_OUT;
     const int n_tiles = tiles_m * tiles_n;
-    constexpr int smem = NSTAGE * (BM + BN) * ROW_BYTES;
+    constexpr int smem = (NSA * BM + NSB * BN) * ROW_BYTES;
     static_assert(smem <= 160 * 1024, "LDS ring exceeds the 160 KB of a CU");
-    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, EPI, NSTAGE>;
+    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, EPI, NSA, NSB>;
     static bool attr_done = false;
     if (!attr_done) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);

@@ -1,7 +1,7 @@
 // Layer contractions of the forward pass (QKV, O, SwiGLU gate/up, down) on the MFMA kernel
 // template of gemm_mfma.h: activations are the row operand, weights [out, in] the column
 // operand.  The workgroup tile is picked per shape so that the grid fills the 256 CUs: big
-// square tiles (least LDS traffic per FLOP) when there are enough of them, smaller ones for
+// tiles (least LDS traffic per FLOP) when whole rounds of them come out, smaller ones for
 // the short-M stage-1 pass and the narrow O / down projections.
 #include "gemm_mfma.h"
 
@@ -11,81 +11,87 @@ using namespace mfma;
 
 struct TileCfg {
     int bm, bn;
+    const char *name;
 };
 // index = value returned by gemm_bf16_tile
-constexpr TileCfg kTiles[] = {{128, 128}, {256, 256}, {256, 128}, {128, 64}, {128, 192}, {128, 64}, {128, 128}, {64, 64}, {256, 256}, {256, 256}};
+constexpr TileCfg kTiles[] = {
+    {128, 128, "128x128, 4 wavefronts, LDS rings 2/3"},   // two workgroups per CU
+    {256, 256, "256x256, 8 wavefronts, LDS rings 2/3"},   // least LDS traffic per FLOP; fills the 160 KB
+    {256, 192, "256x192, 8 wavefronts, LDS rings 2/4"},
+    {128, 192, "128x192, 4 wavefronts, LDS rings 2/2"},   // two workgroups per CU
+    {128, 64, "128x64, 4 wavefronts, LDS rings 4/4"},     // lone workgroup per CU: fetches several stages ahead
+    {128, 128, "128x128, 4 wavefronts, LDS rings 4/4"},
+    {64, 64, "64x64, 4 wavefronts, LDS rings 4/4"},
+};
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
 template <int EPI>
 void dispatch(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int M, int Nout, int Kin, const float *bias,
               bf16_t *out, float *resid, int ldo, hipStream_t st) {
     Top1Args none = {};
-    switch (gemm_bf16_tile(M, Nout, EPI)) {
-        case 1: launch_cfg<256, 256, 2, 2, EPI>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st); break;
-        case 2: launch_cfg<256, 128, 2, 2, EPI>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st); break;
-        case 3:   // (never chosen for SwiGLU: the gate and up halves need whole subtiles per wave)
-            if constexpr (EPI != EPI_SWIGLU) {
-                launch_cfg<128, 64, 2, 2, EPI>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st);
-                break;
-            }
-            [[fallthrough]];
-        case 4:
-            if constexpr (EPI != EPI_SWIGLU) {
-                launch_cfg<128, 192, 2, 2, EPI>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st);
-                break;
-            }
-            [[fallthrough]];
-        case 5:   // deep LDS ring: a lone workgroup per CU needs its fetches several stages ahead
-            if constexpr (EPI != EPI_SWIGLU) {
-                launch_cfg<128, 64, 2, 2, EPI, 4>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st);
-                break;
-            }
-            [[fallthrough]];
-        case 6: launch_cfg<128, 128, 2, 2, EPI, 4>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st); break;
-        case 7:
-            if constexpr (EPI != EPI_SWIGLU) {
-                launch_cfg<64, 64, 2, 2, EPI, 4>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st);
-                break;
-            }
-            [[fallthrough]];
-        case 8: launch_cfg<256, 256, 2, 4, EPI>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st); break;
-        case 9: launch_cfg<256, 256, 4, 2, EPI>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st); break;
-        default: launch_cfg<128, 128, 2, 2, EPI>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st); break;
+    const int tile = gemm_bf16_tile(M, Nout, EPI);
+    // SwiGLU needs an even number of 32-column subtiles per wavefront (gate and up halves); gemm_bf16_tile
+    // never returns the others for it
+    if constexpr (EPI != EPI_SWIGLU) {
+        switch (tile) {
+            case 2: return launch_cfg<256, 192, 4, 2, EPI, 2, 4>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st);
+            case 3: return launch_cfg<128, 192, 2, 2, EPI, 2, 2>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st);
+            case 4: return launch_cfg<128, 64, 2, 2, EPI, 4, 4>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st);
+            case 6: return launch_cfg<64, 64, 2, 2, EPI, 4, 4>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st);
+            default: break;
+        }
+    }
+    switch (tile) {
+        case 1: return launch_cfg<256, 256, 4, 2, EPI, 2, 3>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st);
+        case 5: return launch_cfg<128, 128, 2, 2, EPI, 4, 4>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st);
+        default: return launch_cfg<128, 128, 2, 2, EPI, 2, 3>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st);
     }
 }
+
+bool tile_fits(int tile, int epi) { return epi != EPI_SWIGLU || tile == 0 || tile == 1 || tile == 5; }
 
 }   // namespace
 
 static int g_force_tile = -1;
 void gemm_bf16_force_tile(int tile) { g_force_tile = tile; }
+int gemm_bf16_tile_count() { return kNumTiles; }
+const char *gemm_bf16_tile_name(int tile) { return tile >= 0 && tile < kNumTiles ? kTiles[tile].name : "?"; }
 
 int gemm_bf16_tile(int64_t M, int Nout, int epi) {
-    if (g_force_tile >= 0 && g_force_tile < kNumTiles) {
-        const bool ok = epi != EPI_SWIGLU || (kTiles[g_force_tile].bn / 2) % 64 == 0;
-        if (ok) return g_force_tile;
-    }
-    // Rules read off a sweep of every tile over the layer shapes of the benchmark configurations
-    // (MI355X): the 256x256 tile has the least LDS traffic per FLOP but runs one workgroup per CU, so
-    // it only pays with enough rounds of them (or for SwiGLU, whose two weight operands share the
-    // activation tile); short-M contractions with a narrow output need the small tile to reach every
-    // CU; otherwise 128x128 with two workgroups per CU hides latency best.
+    if (g_force_tile >= 0 && g_force_tile < kNumTiles && tile_fits(g_force_tile, epi)) return g_force_tile;
     const bool dual = epi == EPI_SWIGLU;
     const int64_t cols = dual ? 2 * (int64_t)Nout : Nout;
-    const int64_t t256 = ((M + 255) / 256) * ((cols + 255) / 256);
-    // the 256x256 tile runs as 8 wavefronts (two per SIMD, each 64x128): same LDS traffic per FLOP as four
-    // 128x128 wavefronts would need fewer fragment reads, but the second wavefront per SIMD hides the
-    // latencies that a lone one exposes
-    if (dual) return t256 >= 128 ? 9 : 0;
-    if (t256 >= 768 || (t256 >= 384 && Nout >= 8192)) return 9;
-    const int64_t t128 = ((M + 127) / 128) * ((cols + 127) / 128);
-    const int64_t t12864 = ((M + 127) / 128) * ((cols + 63) / 64);
-    if (t128 <= 256) {   // at most one 128x128 workgroup per CU: latency-bound, use the deep LDS ring
-        if (t12864 <= 128) return 7;
-        return t12864 <= 256 ? 5 : 6;
+    auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((cols + bn - 1) / bn); };
+    // SwiGLU reads two weight operands against one activation tile: the big tile as soon as it
+    // reaches half of the CUs
+    if (dual) return tiles(256, 256) >= 128 ? 1 : 0;
+    // At most one 128x128 workgroup per CU: the contraction is bound by fetch latency, not by the
+    // matrix cores; small tiles reach every CU and the deep rings keep several stages in flight.
+    if (tiles(128, 128) <= 256) {
+        const int64_t t = tiles(128, 64);
+        return t <= 128 ? 6 : t <= 256 ? 4 : 5;
     }
-    if (t128 <= 320) return 3;
-    if (epi != EPI_RESIDUAL && Nout % 192 == 0 && t128 >= 1024) return 4;
-    return 0;
+    // Otherwise: rounds of workgroups over the 256 CUs times the work of one round, weighted by the
+    // rate each tile sustains on a full machine (PFLOP/s with weights streamed cold from HBM, from a
+    // sweep over the layer shapes of the benchmark configurations).  A tile that runs two workgroups per
+    // CU does a round of 512 in the time of two.
+    struct Cand {
+        int tile, per_round;
+        double rate;
+    };
+    const Cand cand[] = {{1, 256, 1.23}, {3, 512, 1.15}, {2, 256, 1.13}, {0, 512, 1.00}};
+    int best = 0;
+    double best_cost = 0;
+    for (const Cand &c : cand) {
+        const int64_t n = tiles(kTiles[c.tile].bm, kTiles[c.tile].bn);
+        const int64_t rounds = (n + c.per_round - 1) / c.per_round;
+        const double cost = (double)rounds * (c.per_round / 256) * kTiles[c.tile].bm * kTiles[c.tile].bn / c.rate;
+        if (best_cost == 0 || cost < best_cost) {
+            best_cost = cost;
+            best = c.tile;
+        }
+    }
+    return best;
 }
 
 void launch_gemm_bf16(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int64_t M, int Nout, int Kin, int epi,

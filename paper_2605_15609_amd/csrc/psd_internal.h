@@ -126,6 +126,8 @@ void launch_head_finish(const float *row_sum, const int32_t *row_arg, const int3
 // 4: 128x192 workgroup tiles on a 2-stage LDS ring; 5: 128x64, 6: 128x128, 7: 64x64 on a 4-stage ring;
 // 8, 9: 256x256 with 8 wavefronts as 2x4 / 4x2)
 int gemm_bf16_tile(int64_t M, int Nout, int epi);
+int gemm_bf16_tile_count();
+const char *gemm_bf16_tile_name(int tile);
 void gemm_bf16_force_tile(int tile);   // debug: -1 = automatic
 // 256 workgroups x 4 wavefronts x iters x 16 MFMAs (32x32x16 bf16) on the given operand data; sink >= 4 MiB
 void launch_mfma_rate(const void *operands, int n_vec16, int iters, void *sink, hipStream_t st);

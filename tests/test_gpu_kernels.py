@@ -70,6 +70,45 @@ def test_gemm_sampled_rows(label, M, N, K, epi):
     assert (err <= tol).all(), f"{label}: max err {err.max():.3e} at {np.unravel_index(err.argmax(), err.shape)}"
 
 
+@pytest.mark.parametrize("epi", [0, 2, 3], ids=["store", "residual", "swiglu"])
+def test_gemm_every_tile_configuration(epi):
+    """Each workgroup tile / LDS ring depth the dispatcher can pick, forced in turn on one ragged shape
+    (several tiles in both directions, K = 18 stages so every ring wraps) and checked in full."""
+    from paper_2605_15609_amd import binding as B
+    lib = B.load_library()
+    M, N, K = 333, 832, 1152
+    rng = np.random.default_rng(40 + epi)
+    A = bf16_round_trip(rng.standard_normal((M, K), dtype=np.float32))
+    W = bf16_round_trip(rng.standard_normal((N, K), dtype=np.float32) * 0.05)
+    W2 = bf16_round_trip(rng.standard_normal((N, K), dtype=np.float32) * 0.05) if epi == 3 else None
+    resid0 = rng.standard_normal((M, N)).astype(np.float32) if epi == 2 else None
+    a = A.astype(np.float64)
+    ref = a @ W.astype(np.float64).T
+    if epi == 3:
+        ref = orc.silu(ref) * (a @ W2.astype(np.float64).T)
+    if epi == 2:
+        ref = ref + resid0
+        tol = 1e-3 + 1e-6 * np.abs(ref)
+    else:
+        tol = 2.0 ** -8 * np.abs(ref) + 2e-3
+    dA, dW = dev_bf16(A), dev_bf16(W)
+    dW2 = None if W2 is None else dev_bf16(W2)
+    try:
+        for tile in range(lib.psd_kernel_gemm_tile_count()):
+            print(f"[kernels] gemm tile {tile} epi={epi}", flush=True)
+            lib.psd_debug_force_gemm_tile(tile)
+            if epi == 2:
+                d_res = torch.from_numpy(resid0).to(DEV)
+                B.kernel_gemm_bf16(dA, dW, epi, resid=d_res)
+                got = d_res.cpu().numpy().astype(np.float64)
+            else:
+                got = host_f64(B.kernel_gemm_bf16(dA, dW, epi, W2=dW2))
+            err = np.abs(got - ref)
+            assert (err <= tol).all(), f"tile {tile}: max err {err.max():.3e} at {np.unravel_index(err.argmax(), err.shape)}"
+    finally:
+        lib.psd_debug_force_gemm_tile(-1)
+
+
 ATTN_CASES = [("c3v", 4, 512, 32, 32, 128), ("c4v-gqa", 6, 1024, 28, 4, 128), ("c2v", 4, 384, 8, 8, 64),
               ("c5-len", 2, 1280, 32, 32, 128), ("ragged", 3, 200, 4, 2, 64)]
 
