@@ -22,6 +22,13 @@ sys.path.insert(0, ROOT)
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
 
+# HBM-side bytes per launch of the SwiGLU contraction at config 3, from two rocprofv3 --pmc runs (FETCH_SIZE,
+# WRITE_SIZE) scaled by what the same counters read for a plain 256 MiB copy (factors 2.00 and 1.00); commands
+# and tables in profiles/config3_hbm_traffic_pmc.md.  (fetched, written) MiB for the verification launch
+# (2048 tokens, 768 workgroups) and the stage-1 launch (512 tokens, 192 workgroups) of the 256x256 tile.
+SWIGLU_TRAFFIC_MIB = {"config": 3, "tile": "256x256, 8 wavefronts, LDS rings 2/3",
+                      "verify": (584.4, 49.3), "stage1": (230.7, 12.0)}
+
 
 def cpu_baseline(workload, stats_tokens, n_stage1, n_verify, threads_hint):
     """Times the oracle as it stands on a bounded sample: forward + confidence of one
@@ -163,6 +170,14 @@ def main():
     invocations = sum(s.invocations for s in stats)
     n_verify = sum(sum(s.depth_hist) for s in stats)
     n_stage1 = invocations - n_verify
+    if roofline is not None and w.index == SWIGLU_TRAFFIC_MIB["config"] and w.batch == 1 and \
+            lib.psd_kernel_gemm_tile_name(swiglu_tile).decode() == SWIGLU_TRAFFIC_MIB["tile"]:
+        # per launch, averaged over this decode's mix of verification and stage-1 launches like `achieved`
+        v, s1 = sum(SWIGLU_TRAFFIC_MIB["verify"]), sum(SWIGLU_TRAFFIC_MIB["stage1"])
+        roofline["traffic"] = (n_verify * v + n_stage1 * s1) / max(1, invocations) * 2 ** 20
+        roofline["traffic_unit"] = "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated; profiles/config3_hbm_traffic_pmc.md)"
+        roofline["algorithmic_bytes_per_launch"] = ((n_verify * w.n_drafts + n_stage1) * w.seq_len * (shape.d_model + shape.d_ffn) * 2
+                                                    / max(1, invocations) + 2 * shape.d_ffn * shape.d_model * 2)
     tpf = sum(s.tokens for s in stats) / max(1, invocations)
     value = args.steps * n_tokens / elapsed
 
