@@ -94,7 +94,7 @@ def load_library():
                                     vp, vp, vp, vp, i64, vp]),
         "psd_decode_block": (i32, [vp, vp, i32, i32, i32, i32, C.POINTER(_Policy), C.POINTER(_Graph), C.POINTER(_Stats),
                                    vp, i64, vp]),
-        "psd_kernel_gemm_bf16": (i32, [vp, vp, vp, i64, i32, i32, i32, vp, vp, vp, i32, vp]),
+        "psd_kernel_gemm_bf16": (i32, [vp, vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp, i32, vp]),
         "psd_kernel_attention_bf16": (i32, [vp, i32, i32, i32, i32, i32, vp, vp, vp]),
         "psd_kernel_head_scratch_bytes": (i64, [i32, i32]),
         "psd_kernel_head_confidence_bf16": (i32, [vp, vp, i32, i32, i32, C.c_float, i32, vp, vp, vp, vp]),
@@ -419,18 +419,21 @@ EPI_STORE, EPI_BIAS, EPI_RESIDUAL, EPI_SWIGLU = 0, 1, 2, 3
 def kernel_gemm_bf16(A: torch.Tensor, W: torch.Tensor, epilogue: int = EPI_STORE, W2: Optional[torch.Tensor] = None,
                      bias: Optional[torch.Tensor] = None, resid: Optional[torch.Tensor] = None,
                      out: Optional[torch.Tensor] = None):
-    """A bf16 [M, K], W bf16 [N, K] -> out bf16 [M, N] (or resid fp32 [M, N] += for EPI_RESIDUAL)."""
+    """A bf16 [M, K], W bf16 [N, K] -> out bf16 [M, N] (or resid fp32 [M, N] += for EPI_RESIDUAL).
+    A and W (W2 like W) may be row-strided views (unit stride along K)."""
     lib = load_library()
     M, K = A.shape
     Nout = W.shape[0]
+    assert A.stride(1) == 1 and W.stride(1) == 1 and (W2 is None or W2.stride() == W.stride())
+    lda, ldw = A.stride(0), W.stride(0)
     if epilogue == EPI_RESIDUAL:
         assert resid is not None and resid.dtype == torch.float32
-        _check(lib.psd_kernel_gemm_bf16(_ptr(A), _ptr(W), None, M, Nout, K, epilogue, None, None, _ptr(resid),
+        _check(lib.psd_kernel_gemm_bf16(_ptr(A), _ptr(W), None, M, Nout, K, lda, ldw, epilogue, None, None, _ptr(resid),
                                         resid.stride(0), _stream()))
         return resid
     if out is None:
         out = torch.empty((M, Nout), dtype=torch.bfloat16, device=A.device)
-    _check(lib.psd_kernel_gemm_bf16(_ptr(A), _ptr(W), _ptr(W2), M, Nout, K, epilogue, _ptr(bias), _ptr(out), None,
+    _check(lib.psd_kernel_gemm_bf16(_ptr(A), _ptr(W), _ptr(W2), M, Nout, K, lda, ldw, epilogue, _ptr(bias), _ptr(out), None,
                                     out.stride(0), _stream()))
     return out
 

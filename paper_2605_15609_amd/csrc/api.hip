@@ -450,15 +450,18 @@ int32_t psd_decode_block(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, i
 // ---- kernel-level hooks: the same launchers the forward uses, on caller-provided buffers ----
 
 int32_t psd_kernel_gemm_bf16(const void *A, const void *W, const void *W2, int64_t M, int32_t Nout, int32_t Kin,
-                             int32_t epilogue, const float *bias, void *out, float *resid, int32_t ldo, void *stream) {
+                             int32_t lda, int32_t ldw, int32_t epilogue, const float *bias, void *out, float *resid,
+                             int32_t ldo, void *stream) {
     if (!A || !W || M < 1 || M > (1 << 30) || Nout < 1 || Kin < 1) PSD_FAIL(PSD_ERR_INVALID_ARG, "bad GEMM arguments");
     if (Kin % 64 || Nout % 64) PSD_FAIL(PSD_ERR_SHAPE, "Nout and Kin must be multiples of 64");
+    if (lda < Kin || ldw < Kin || lda % 8 || ldw % 8 || lda > (1 << 20) || ldw > (1 << 20))
+        PSD_FAIL(PSD_ERR_SHAPE, "row strides must be multiples of 8 in [Kin, 2^20]");
     if (epilogue < 0 || epilogue > 3) PSD_FAIL(PSD_ERR_INVALID_ARG, "epilogue %d", epilogue);
     if (epilogue == EPI_SWIGLU && !W2) PSD_FAIL(PSD_ERR_INVALID_ARG, "SwiGLU needs the second weight");
     if (epilogue == EPI_BIAS && !bias) PSD_FAIL(PSD_ERR_INVALID_ARG, "bias is NULL");
     if (epilogue == EPI_RESIDUAL ? !resid : !out) PSD_FAIL(PSD_ERR_INVALID_ARG, "output is NULL");
     if (ldo < Nout) PSD_FAIL(PSD_ERR_SHAPE, "ldo < Nout");
-    launch_gemm_bf16((const bf16_t *)A, (const bf16_t *)W, (const bf16_t *)W2, M, Nout, Kin, epilogue, bias, (bf16_t *)out,
+    launch_gemm_bf16((const bf16_t *)A, (const bf16_t *)W, (const bf16_t *)W2, M, Nout, Kin, lda, ldw, epilogue, bias, (bf16_t *)out,
                      resid, ldo, (hipStream_t)stream);
     PSD_HIP(hipGetLastError());
     return PSD_OK;

@@ -1,6 +1,7 @@
 // bf16 contraction D[i, j] = sum_k X[i, k] * Y[j, k] on the gfx950 matrix cores
 // (v_mfma_f32_32x32x16_bf16, fp32 accumulation).  Both operands are K-contiguous ("NT"
-// form), the natural MFMA feed: every lane fetches 8 consecutive k (16 bytes) of one row.
+// form, row strides ldx / ldy elements), the natural MFMA feed: every lane fetches 8 consecutive k
+// (16 bytes) of one row.
 //
 // Tiling: a workgroup of 4 or 8 wavefronts owns a BM x BN tile; K advances 64 at a time.  Each
 // operand tile has its own ring of LDS stages (NSA for X, NSB for Y) filled by direct global -> LDS
@@ -77,7 +78,7 @@ __device__ __forceinline__ void sched_mix() {
 
 template <int BM, int BN, int WGM, int WGN, int EPI, int NSA, int NSB>
 __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Y,
-                                                        const bf16_t *__restrict__ Y2, int M, int Nout, int Kin,
+                                                        const bf16_t *__restrict__ Y2, int M, int Nout, int Kin, int ldx, int ldy,
                                                         const float *__restrict__ bias, bf16_t *__restrict__ out,
                                                         float *__restrict__ resid, int ldo, int tiles_n, int n_tiles,
                                                         Top1Args t1) {
@@ -129,14 +130,15 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
     // are rejected by the descriptor's range check (they only feed outputs that are never stored).
     const int rows_x = min(BM, M - m0), rows_y = min(BN_OUT, Nout - n0);
     const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<bf16_t *>(X) + (int64_t)m0 * Kin, 0, rows_x * Kin * 2, 0x00020000);
+        const_cast<bf16_t *>(X) + (int64_t)m0 * ldx, 0, ((rows_x - 1) * ldx + Kin) * 2, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrc_y = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<bf16_t *>(Y) + (int64_t)n0 * Kin, 0, rows_y * Kin * 2, 0x00020000);
+        const_cast<bf16_t *>(Y) + (int64_t)n0 * ldy, 0, ((rows_y - 1) * ldy + Kin) * 2, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrc_y2 = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<bf16_t *>(DUAL ? Y2 : Y) + (int64_t)n0 * Kin, 0, rows_y * Kin * 2, 0x00020000);
+        const_cast<bf16_t *>(DUAL ? Y2 : Y) + (int64_t)n0 * ldy, 0, ((rows_y - 1) * ldy + Kin) * 2, 0x00020000);
     const int uwave = __builtin_amdgcn_readfirstlane(wave);
     const int dma_key = (((uwave & 1) << 2) + (lane >> 4)) & 7;
-    const int voff = (lane >> 3) * Kin * 2 + (((lane & 7) ^ dma_key) << 4);
+    const int voff_x = (lane >> 3) * ldx * 2 + (((lane & 7) ^ dma_key) << 4);
+    const int voff_y = (lane >> 3) * ldy * 2 + (((lane & 7) ^ dma_key) << 4);
     constexpr int GA = BM / 8 / NW, GB = BN / 8 / NW;   // row groups per wavefront, A and B tile
     constexpr int NLD = GA + GB;                      // DMA instructions per wavefront per stage
     typedef __attribute__((address_space(3))) void lds_void;
@@ -146,19 +148,19 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
     {                                                                                                         \
         unsigned char *sa_ = lds + (slot) * A_BYTES + uwave * 1024;                                           \
         _Pragma("unroll") for (int j = 0; j < GA; ++j)                                                        \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, (lds_void *)(sa_ + j * (NW * 1024)), 16, voff,   \
-                                                     ((j * NW + uwave) * 8 * Kin + (k0)) * 2, 0, 0);          \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, (lds_void *)(sa_ + j * (NW * 1024)), 16, voff_x, \
+                                                     ((j * NW + uwave) * 8 * ldx + (k0)) * 2, 0, 0);          \
     }
 #define PSD_GEMM_DMA_B(slot, k0)                                                                              \
     {                                                                                                         \
         unsigned char *sb_ = lds + B_RING + (slot) * B_BYTES + uwave * 1024;                                  \
         _Pragma("unroll") for (int j = 0; j < GB; ++j) {                                                      \
             if (DUAL && j * (8 * NW) >= BN / 2)                                                               \
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_y2, (lds_void *)(sb_ + j * (NW * 1024)), 16, voff, \
-                                                         (((j * NW + uwave) * 8 - BN / 2) * Kin + (k0)) * 2, 0, 0); \
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_y2, (lds_void *)(sb_ + j * (NW * 1024)), 16, voff_y, \
+                                                         (((j * NW + uwave) * 8 - BN / 2) * ldy + (k0)) * 2, 0, 0); \
             else                                                                                              \
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_y, (lds_void *)(sb_ + j * (NW * 1024)), 16, voff, \
-                                                         ((j * NW + uwave) * 8 * Kin + (k0)) * 2, 0, 0);      \
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_y, (lds_void *)(sb_ + j * (NW * 1024)), 16, voff_y, \
+                                                         ((j * NW + uwave) * 8 * ldy + (k0)) * 2, 0, 0);      \
         }                                                                                                     \
     }
 // Every iteration issues the fetch of the shallower ring first.  Memory returns in issue order, so
@@ -349,7 +351,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
 }
 
 template <int BM, int BN, int WGM, int WGN, int EPI, int NSA = 2, int NSB = NSA>
-void launch_cfg(const bf16_t *X, const bf16_t *Y, const bf16_t *Y2, int M, int Nout, int Kin, const float *bias,
+void launch_cfg(const bf16_t *X, const bf16_t *Y, const bf16_t *Y2, int M, int Nout, int Kin, int ldx, int ldy, const float *bias,
                 bf16_t *out, float *resid, int ldo, Top1Args t1, hipStream_t st) {
     constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (Nout + BN_OUT - 1) / BN_OUT;
@@ -362,7 +364,7 @@ void launch_cfg(const bf16_t *X, const bf16_t *Y, const bf16_t *Y2, int M, int N
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(n_tiles), dim3(WGM * WGN * 64), smem, st, X, Y, Y2, M, Nout, Kin, bias, out, resid, ldo, tiles_n,
+    hipLaunchKernelGGL(kern, dim3(n_tiles), dim3(WGM * WGN * 64), smem, st, X, Y, Y2, M, Nout, Kin, ldx, ldy, bias, out, resid, ldo, tiles_n,
                        n_tiles, t1);
 }
 

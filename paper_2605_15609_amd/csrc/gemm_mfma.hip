@@ -26,7 +26,7 @@ constexpr TileCfg kTiles[] = {
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
 template <int EPI>
-void dispatch(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int M, int Nout, int Kin, const float *bias,
+void dispatch(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int M, int Nout, int Kin, int lda, int ldw, const float *bias,
               bf16_t *out, float *resid, int ldo, hipStream_t st) {
     Top1Args none = {};
     const int tile = gemm_bf16_tile(M, Nout, EPI);
@@ -34,17 +34,17 @@ void dispatch(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int M, int Nou
     // never returns the others for it
     if constexpr (EPI != EPI_SWIGLU) {
         switch (tile) {
-            case 2: return launch_cfg<256, 192, 4, 2, EPI, 2, 4>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st);
-            case 3: return launch_cfg<128, 192, 2, 2, EPI, 2, 2>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st);
-            case 4: return launch_cfg<128, 64, 2, 2, EPI, 4, 4>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st);
-            case 6: return launch_cfg<64, 64, 2, 2, EPI, 4, 4>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st);
+            case 2: return launch_cfg<256, 192, 4, 2, EPI, 2, 4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+            case 3: return launch_cfg<128, 192, 2, 2, EPI, 2, 2>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+            case 4: return launch_cfg<128, 64, 2, 2, EPI, 4, 4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+            case 6: return launch_cfg<64, 64, 2, 2, EPI, 4, 4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
             default: break;
         }
     }
     switch (tile) {
-        case 1: return launch_cfg<256, 256, 4, 2, EPI, 2, 3>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st);
-        case 5: return launch_cfg<128, 128, 2, 2, EPI, 4, 4>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st);
-        default: return launch_cfg<128, 128, 2, 2, EPI, 2, 3>(A, W, W2, M, Nout, Kin, bias, out, resid, ldo, none, st);
+        case 1: return launch_cfg<256, 256, 4, 2, EPI, 2, 3>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+        case 5: return launch_cfg<128, 128, 2, 2, EPI, 4, 4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+        default: return launch_cfg<128, 128, 2, 2, EPI, 2, 3>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
     }
 }
 
@@ -94,14 +94,14 @@ int gemm_bf16_tile(int64_t M, int Nout, int epi) {
     return best;
 }
 
-void launch_gemm_bf16(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int64_t M, int Nout, int Kin, int epi,
+void launch_gemm_bf16(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int64_t M, int Nout, int Kin, int lda, int ldw, int epi,
                       const float *bias, bf16_t *out, float *resid, int ldo, hipStream_t st) {
     const int m = (int)M;
     switch (epi) {
-        case EPI_STORE: dispatch<EPI_STORE>(A, W, W2, m, Nout, Kin, bias, out, resid, ldo, st); break;
-        case EPI_BIAS: dispatch<EPI_BIAS>(A, W, W2, m, Nout, Kin, bias, out, resid, ldo, st); break;
-        case EPI_RESIDUAL: dispatch<EPI_RESIDUAL>(A, W, W2, m, Nout, Kin, bias, out, resid, ldo, st); break;
-        default: dispatch<EPI_SWIGLU>(A, W, W2, m, Nout, Kin, bias, out, resid, ldo, st); break;
+        case EPI_STORE: dispatch<EPI_STORE>(A, W, W2, m, Nout, Kin, lda, ldw, bias, out, resid, ldo, st); break;
+        case EPI_BIAS: dispatch<EPI_BIAS>(A, W, W2, m, Nout, Kin, lda, ldw, bias, out, resid, ldo, st); break;
+        case EPI_RESIDUAL: dispatch<EPI_RESIDUAL>(A, W, W2, m, Nout, Kin, lda, ldw, bias, out, resid, ldo, st); break;
+        default: dispatch<EPI_SWIGLU>(A, W, W2, m, Nout, Kin, lda, ldw, bias, out, resid, ldo, st); break;
     }
 }
 

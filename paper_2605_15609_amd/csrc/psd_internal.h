@@ -110,7 +110,7 @@ void launch_transpose_v(const bf16_t *qkv, int S, int N, int n_heads, int n_kv_h
 // plain_kernels.hip (debug path, any shape)
 enum Epilogue { EPI_STORE = 0, EPI_BIAS = 1, EPI_RESIDUAL = 2, EPI_SWIGLU = 3 };
 template <typename T, typename TO>
-void launch_plain_gemm(const T *A, const T *W, const T *W2, int64_t M, int Nout, int Kin, int epi, const float *bias,
+void launch_plain_gemm(const T *A, const T *W, const T *W2, int64_t M, int Nout, int Kin, int lda, int epi, const float *bias,
                        float scale, TO *out, float *resid, int ldo, hipStream_t st);
 template <typename T>
 void launch_plain_attention(const T *qkv, int S, int N, int n_heads, int n_kv_heads, int d_head, T *out,
@@ -131,7 +131,8 @@ const char *gemm_bf16_tile_name(int tile);
 void gemm_bf16_force_tile(int tile);   // debug: -1 = automatic
 // 256 workgroups x 4 wavefronts x iters x 16 MFMAs (32x32x16 bf16) on the given operand data; sink >= 4 MiB
 void launch_mfma_rate(const void *operands, int n_vec16, int iters, void *sink, hipStream_t st);
-void launch_gemm_bf16(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int64_t M, int Nout, int Kin, int epi,
+// A [M, Kin] with row stride lda, W / W2 [Nout, Kin] with row stride ldw (elements)
+void launch_gemm_bf16(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int64_t M, int Nout, int Kin, int lda, int ldw, int epi,
                       const float *bias, bf16_t *out, float *resid, int ldo, hipStream_t st);
 // attention_mfma.hip (bf16, d_head 64 or 128): q, k from qkv (rotary applied), values from vT
 void launch_attention_bf16(const bf16_t *qkv, const bf16_t *vT, int S, int N, int n_heads, int n_kv_heads, int d_head,
