@@ -228,16 +228,18 @@ int32_t psd_forward_work(const psd_model_config *cfg, int32_t S, int32_t N, int3
  *          2: resid[m, n] += sum (fp32);  3: out = bf16(silu(A W^T) * (A W2^T)).
  *          A [M, Kin] with row stride lda, W / W2 [Nout, Kin] with row stride ldw (elements, multiples
  *          of 8); Nout, Kin multiples of 64; ldo = row stride of out / resid.
- *   attention: qkv [S*N, (n_heads + 2 n_kv_heads) * d_head] with rotary already applied;
- *          vT is scratch of S*ceil(N/64)*64*n_kv_heads*d_head bf16; out [S*N, n_heads*d_head].
+ *   attention: qkv [S*N, (n_heads + 2 n_kv_heads) * d_head] with row stride ld_qkv (elements, multiple of 8),
+ *          rotary already applied; vT is scratch of psd_kernel_attention_scratch_bytes; out
+ *          [S*N, n_heads*d_head] dense.
  *   head:  y [rows, d], W [vocab, d] -> row_sum[r] = sum_v exp(z_v - max_v z), row_arg[r] =
  *          argmax_v z_v over v != mask_id, z = scale * y W^T; scratch from
  *          psd_kernel_head_scratch_bytes. */
 int32_t psd_kernel_gemm_bf16(const void *A, const void *W, const void *W2, int64_t M, int32_t Nout, int32_t Kin,
                              int32_t lda, int32_t ldw, int32_t epilogue, const float *bias, void *out, float *resid,
                              int32_t ldo, void *stream);
-int32_t psd_kernel_attention_bf16(const void *qkv, int32_t S, int32_t N, int32_t n_heads, int32_t n_kv_heads,
-                                  int32_t d_head, void *vT, void *out, void *stream);
+int64_t psd_kernel_attention_scratch_bytes(int32_t S, int32_t N, int32_t n_kv_heads, int32_t d_head);
+int32_t psd_kernel_attention_bf16(const void *qkv, int32_t ld_qkv, int32_t S, int32_t N, int32_t n_heads,
+                                  int32_t n_kv_heads, int32_t d_head, void *vT, void *out, void *stream);
 int64_t psd_kernel_head_scratch_bytes(int32_t rows, int32_t vocab);
 /*   streaming head (what the forward runs for <= 192 rows): both operands in MFMA-fragment order,
  *          [ceil(R/32)][K/16][64 lanes][8 bf16]; psd_kernel_pack_rows builds that copy of a row-major

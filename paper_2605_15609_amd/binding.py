@@ -95,7 +95,8 @@ def load_library():
         "psd_decode_block": (i32, [vp, vp, i32, i32, i32, i32, C.POINTER(_Policy), C.POINTER(_Graph), C.POINTER(_Stats),
                                    vp, i64, vp]),
         "psd_kernel_gemm_bf16": (i32, [vp, vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp, i32, vp]),
-        "psd_kernel_attention_bf16": (i32, [vp, i32, i32, i32, i32, i32, vp, vp, vp]),
+        "psd_kernel_attention_scratch_bytes": (i64, [i32, i32, i32, i32]),
+        "psd_kernel_attention_bf16": (i32, [vp, i32, i32, i32, i32, i32, i32, vp, vp, vp]),
         "psd_kernel_head_scratch_bytes": (i64, [i32, i32]),
         "psd_kernel_head_confidence_bf16": (i32, [vp, vp, i32, i32, i32, C.c_float, i32, vp, vp, vp, vp]),
         "psd_debug_force_gemm_tile": (i32, [i32]),
@@ -440,12 +441,16 @@ def kernel_gemm_bf16(A: torch.Tensor, W: torch.Tensor, epilogue: int = EPI_STORE
 
 def kernel_attention_bf16(qkv: torch.Tensor, S: int, N: int, n_heads: int, n_kv_heads: int, d_head: int,
                           out: Optional[torch.Tensor] = None, vT: Optional[torch.Tensor] = None):
+    """qkv bf16 [S*N, (n_heads + 2 n_kv_heads) * d_head], possibly a row-strided view -> out bf16 [S*N, n_heads*d_head]."""
     lib = load_library()
+    assert qkv.stride(1) == 1
     if vT is None:
-        vT = torch.empty((S * ((N + 63) // 64 * 64) * n_kv_heads * d_head,), dtype=torch.bfloat16, device=qkv.device)
+        vT = torch.empty((lib.psd_kernel_attention_scratch_bytes(S, N, n_kv_heads, d_head) // 2,), dtype=torch.bfloat16,
+                         device=qkv.device)
     if out is None:
         out = torch.empty((S * N, n_heads * d_head), dtype=torch.bfloat16, device=qkv.device)
-    _check(lib.psd_kernel_attention_bf16(_ptr(qkv), S, N, n_heads, n_kv_heads, d_head, _ptr(vT), _ptr(out), _stream()))
+    _check(lib.psd_kernel_attention_bf16(_ptr(qkv), qkv.stride(0), S, N, n_heads, n_kv_heads, d_head, _ptr(vT), _ptr(out),
+                                         _stream()))
     return out
 
 

@@ -467,13 +467,20 @@ int32_t psd_kernel_gemm_bf16(const void *A, const void *W, const void *W2, int64
     return PSD_OK;
 }
 
-int32_t psd_kernel_attention_bf16(const void *qkv, int32_t S, int32_t N, int32_t n_heads, int32_t n_kv_heads, int32_t d_head,
-                                  void *vT, void *out, void *stream) {
+int64_t psd_kernel_attention_scratch_bytes(int32_t S, int32_t N, int32_t n_kv_heads, int32_t d_head) {
+    if (S < 1 || N < 1 || n_kv_heads < 1 || d_head < 1) return -1;
+    return (int64_t)S * vt_row_stride(N) * n_kv_heads * d_head * 2;
+}
+
+int32_t psd_kernel_attention_bf16(const void *qkv, int32_t ld_qkv, int32_t S, int32_t N, int32_t n_heads, int32_t n_kv_heads,
+                                  int32_t d_head, void *vT, void *out, void *stream) {
     if (!qkv || !vT || !out || S < 1 || N < 1) PSD_FAIL(PSD_ERR_INVALID_ARG, "bad attention arguments");
+    if (n_heads < 1 || n_kv_heads < 1 || ld_qkv < (n_heads + 2 * n_kv_heads) * d_head || ld_qkv % 8)
+        PSD_FAIL(PSD_ERR_SHAPE, "ld_qkv must be a multiple of 8 and at least the row width");
     if ((d_head != 64 && d_head != 128) || N % 8 || n_kv_heads < 1 || n_heads % n_kv_heads)
         PSD_FAIL(PSD_ERR_SHAPE, "attention needs d_head 64/128, N a multiple of 8, n_heads a multiple of n_kv_heads");
-    launch_transpose_v((const bf16_t *)qkv, S, N, n_heads, n_kv_heads, d_head, (bf16_t *)vT, (hipStream_t)stream);
-    launch_attention_bf16((const bf16_t *)qkv, (const bf16_t *)vT, S, N, n_heads, n_kv_heads, d_head, (bf16_t *)out,
+    launch_transpose_v((const bf16_t *)qkv, ld_qkv, S, N, n_heads, n_kv_heads, d_head, (bf16_t *)vT, (hipStream_t)stream);
+    launch_attention_bf16((const bf16_t *)qkv, ld_qkv, (const bf16_t *)vT, S, N, n_heads, n_kv_heads, d_head, (bf16_t *)out,
                           (hipStream_t)stream);
     PSD_HIP(hipGetLastError());
     return PSD_OK;

@@ -32,10 +32,12 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 u) { return __builtin_bit_cast
 
 typedef __attribute__((address_space(3))) void lds_void;
 
-// NW wavefronts (32 queries each) per workgroup; N_pad = row length of vT (N rounded up to 64, tail zero)
+// NW wavefronts (32 queries each) per workgroup; ld_qkv / ld_vt = row strides (elements) of qkv and of vT,
+// whose rows hold N rounded up to 64 keys (tail zero)
 template <int DH, int NW>
-__global__ __launch_bounds__(NW * 64) void attention_kernel(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ vT, int N,
-                                                            int N_pad, int n_heads, int n_kv_heads, bf16_t *__restrict__ out) {
+__global__ __launch_bounds__(NW * 64) void attention_kernel(const bf16_t *__restrict__ qkv, int ld_qkv,
+                                                            const bf16_t *__restrict__ vT, int ld_vt, int N, int n_heads,
+                                                            int n_kv_heads, bf16_t *__restrict__ out) {
     constexpr int KROW = DH * 2;                 // bytes per K row in LDS
     constexpr int K_BYTES = BKV * KROW;
     constexpr int VROW = BKV * 2;                // bytes per V^T row in LDS (128)
@@ -50,7 +52,7 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(const bf16_t *__rest
 
     const int q0 = blockIdx.x * (32 * NW), head = blockIdx.y, s = blockIdx.z;
     const int kvh = head / (n_heads / n_kv_heads);
-    const int row_w = (n_heads + 2 * n_kv_heads) * DH;
+    const int row_w = ld_qkv;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lrow = lane & 31, lhalf = lane >> 5;
     const bf16_t *seq = qkv + (int64_t)s * N * row_w;
@@ -75,7 +77,7 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(const bf16_t *__rest
     const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<bf16_t *>(seq) + (n_heads + kvh) * DH, 0, (int)(((int64_t)N * row_w - (n_heads + kvh) * DH) * 2), 0x00020000);
     const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<bf16_t *>(vT) + ((int64_t)s * n_kv_heads + kvh) * DH * (int64_t)N_pad, 0, DH * N_pad * 2, 0x00020000);
+        const_cast<bf16_t *>(vT) + ((int64_t)s * n_kv_heads + kvh) * DH * (int64_t)ld_vt, 0, DH * ld_vt * 2, 0x00020000);
     constexpr int KLPR = 64 / KRPI;              // lanes per K row in one DMA instruction (16 or 8)
 #define PSD_ATT_DMA(stage, k0)                                                                                   \
     {                                                                                                            \
@@ -88,9 +90,9 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(const bf16_t *__rest
         }                                                                                                        \
         _Pragma("unroll") for (int j = 0; j < VG; ++j) {                                                         \
             const int row = (j * NW + wave) * 8 + (lane >> 3);                                                   \
-            const int voff = (lane >> 3) * N_pad * 2 + (((lane & 7) ^ ((row >> 1) & 7)) << 4);                   \
+            const int voff = (lane >> 3) * ld_vt * 2 + (((lane & 7) ^ ((row >> 1) & 7)) << 4);                   \
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_void *)(sv_ + j * (NW * 1024)), 16, voff,          \
-                                                     ((j * NW + wave) * 8 * N_pad + (k0)) * 2, 0, 0);            \
+                                                     ((j * NW + wave) * 8 * ld_vt + (k0)) * 2, 0, 0);             \
         }                                                                                                        \
     }
 #define PSD_ATT_SYNC()                                                                                           \
@@ -213,14 +215,14 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(const bf16_t *__rest
     }
 }
 
-// vT[s][kvh][c][pi(i)] = qkv[s*N + i][(H + Hkv + kvh)*dh + c], 64x64 tiles through LDS.  Rows of vT are N_pad long
-// (N rounded up to 64, the tail zero).  Inside every group of 16 keys the order is 0-3, 8-11, 4-7, 12-15: the
+// vT[s][kvh][c][pi(i)] = qkv[s*N + i][(H + Hkv + kvh)*dh + c], 64x64 tiles through LDS.  Rows of vT (stride ld_vt)
+// hold N rounded up to 64 keys, the tail zero.  Inside every group of 16 keys the order is 0-3, 8-11, 4-7, 12-15: the
 // contraction-slot order of the second attention MFMA, so that a lane's 8 values are one 16-byte piece.
-__global__ __launch_bounds__(256) void transpose_v_kernel(const bf16_t *__restrict__ qkv, int N, int N_pad, int n_heads,
-                                                          int n_kv_heads, int d_head, bf16_t *__restrict__ vT) {
+__global__ __launch_bounds__(256) void transpose_v_kernel(const bf16_t *__restrict__ qkv, int ld_qkv, int N, int n_heads,
+                                                          int n_kv_heads, int d_head, bf16_t *__restrict__ vT, int ld_vt) {
     __shared__ uint16_t tile[64][66];
     const int i0 = blockIdx.x * 64, cg = blockIdx.y, s = blockIdx.z;   // cg indexes 64-wide column groups of all KV heads
-    const int row_w = (n_heads + 2 * n_kv_heads) * d_head;
+    const int row_w = ld_qkv;
     const int col0 = cg * 64;                                          // within the V part
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     for (int r = ty; r < 64; r += 4) {
@@ -233,23 +235,22 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const bf16_t *__restri
     const int src_key = (tx & ~15) | ((((piece & 1) << 1) | (piece >> 1)) << 2) | (tx & 3);
     for (int r = ty; r < 64; r += 4) {
         const int c = col0 + r;   // = kvh * d_head + channel
-        vT[((int64_t)s * n_kv_heads * d_head + c) * N_pad + i0 + tx].bits = tile[src_key][r];
+        vT[((int64_t)s * n_kv_heads * d_head + c) * ld_vt + i0 + tx].bits = tile[src_key][r];
     }
 }
 
 }   // namespace
 
-void launch_transpose_v(const bf16_t *qkv, int S, int N, int n_heads, int n_kv_heads, int d_head, bf16_t *vT,
+void launch_transpose_v(const bf16_t *qkv, int ld_qkv, int S, int N, int n_heads, int n_kv_heads, int d_head, bf16_t *vT,
                         hipStream_t st) {
     const int N_pad = (N + 63) / 64 * 64;
-    hipLaunchKernelGGL(transpose_v_kernel, dim3(N_pad / 64, n_kv_heads * d_head / 64, S), dim3(256), 0, st, qkv, N, N_pad,
-                       n_heads, n_kv_heads, d_head, vT);
+    hipLaunchKernelGGL(transpose_v_kernel, dim3(N_pad / 64, n_kv_heads * d_head / 64, S), dim3(256), 0, st, qkv, ld_qkv, N,
+                       n_heads, n_kv_heads, d_head, vT, (int)vt_row_stride(N));
 }
 
 template <int DH, int NW>
-static void launch_att(const bf16_t *qkv, const bf16_t *vT, int S, int N, int n_heads, int n_kv_heads, bf16_t *out,
+static void launch_att(const bf16_t *qkv, int ld_qkv, const bf16_t *vT, int S, int N, int n_heads, int n_kv_heads, bf16_t *out,
                        hipStream_t st) {
-    const int N_pad = (N + 63) / 64 * 64;
     constexpr int smem = 2 * (BKV * DH * 2 + DH * BKV * 2);
     auto kern = attention_kernel<DH, NW>;
     static bool attr_done = false;
@@ -258,19 +259,19 @@ static void launch_att(const bf16_t *qkv, const bf16_t *vT, int S, int N, int n_
         attr_done = true;
     }
     dim3 grid((N + 32 * NW - 1) / (32 * NW), n_heads, S);
-    hipLaunchKernelGGL(kern, grid, dim3(NW * 64), smem, st, qkv, vT, N, N_pad, n_heads, n_kv_heads, out);
+    hipLaunchKernelGGL(kern, grid, dim3(NW * 64), smem, st, qkv, ld_qkv, vT, (int)vt_row_stride(N), N, n_heads, n_kv_heads, out);
 }
 
-void launch_attention_bf16(const bf16_t *qkv, const bf16_t *vT, int S, int N, int n_heads, int n_kv_heads, int d_head,
+void launch_attention_bf16(const bf16_t *qkv, int ld_qkv, const bf16_t *vT, int S, int N, int n_heads, int n_kv_heads, int d_head,
                            bf16_t *out, hipStream_t st) {
     // 128 queries per workgroup when that still gives two workgroups per CU, else 64
     const int64_t blocks128 = (int64_t)((N + 127) / 128) * n_heads * S;
     const bool small = blocks128 < 512;
     if (d_head == 128) {
-        if (small) launch_att<128, 2>(qkv, vT, S, N, n_heads, n_kv_heads, out, st);
-        else launch_att<128, 4>(qkv, vT, S, N, n_heads, n_kv_heads, out, st);
+        if (small) launch_att<128, 2>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, st);
+        else launch_att<128, 4>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, st);
     } else {
-        if (small) launch_att<64, 2>(qkv, vT, S, N, n_heads, n_kv_heads, out, st);
-        else launch_att<64, 4>(qkv, vT, S, N, n_heads, n_kv_heads, out, st);
+        if (small) launch_att<64, 2>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, st);
+        else launch_att<64, 4>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, st);
     }
 }

@@ -97,15 +97,15 @@ __global__ __launch_bounds__(256) void rmsnorm_bf16_vec_kernel(const float *__re
     }
 }
 
-// rotate-half rotary embedding in place on the q and k heads of qkv [tokens, (H + 2 Hkv) * dh]
+// rotate-half rotary embedding in place on the q and k heads of qkv [tokens, (H + 2 Hkv) * dh], row stride ld
 template <typename T>
-__global__ __launch_bounds__(256) void rope_kernel(T *__restrict__ qkv, int N, int n_heads, int n_kv_heads, int d_head,
+__global__ __launch_bounds__(256) void rope_kernel(T *__restrict__ qkv, int ld, int N, int n_heads, int n_kv_heads, int d_head,
                                                    const float *__restrict__ cos_t, const float *__restrict__ sin_t) {
     const int64_t t = blockIdx.x;
     const int pos = (int)(t % N);
     const int half = d_head >> 1;
     const int rot_heads = n_heads + n_kv_heads;
-    T *row = qkv + t * (int64_t)(n_heads + 2 * n_kv_heads) * d_head;
+    T *row = qkv + t * (int64_t)ld;
     for (int idx = threadIdx.x; idx < rot_heads * half; idx += blockDim.x) {
         const int hd = idx / half, j = idx % half;
         T *p = row + hd * d_head;
@@ -117,14 +117,14 @@ __global__ __launch_bounds__(256) void rope_kernel(T *__restrict__ qkv, int N, i
 }
 
 // bf16 rotary: a thread owns 8 consecutive pair indices j of one head (two 16-byte accesses each way)
-__global__ __launch_bounds__(256) void rope_bf16_vec_kernel(bf16_t *__restrict__ qkv, int N, int n_heads, int n_kv_heads,
+__global__ __launch_bounds__(256) void rope_bf16_vec_kernel(bf16_t *__restrict__ qkv, int ld, int N, int n_heads, int n_kv_heads,
                                                             int d_head, const float *__restrict__ cos_t,
                                                             const float *__restrict__ sin_t) {
     const int64_t t = blockIdx.x;
     const int pos = (int)(t % N);
     const int half = d_head >> 1, groups = half >> 3;
     const int rot_heads = n_heads + n_kv_heads;
-    bf16_t *row = qkv + t * (int64_t)(n_heads + 2 * n_kv_heads) * d_head;
+    bf16_t *row = qkv + t * (int64_t)ld;
     for (int idx = threadIdx.x; idx < rot_heads * groups; idx += blockDim.x) {
         const int hd = idx / groups, j0 = (idx % groups) * 8;
         uint4 *p1 = reinterpret_cast<uint4 *>(row + hd * d_head + j0);
@@ -176,19 +176,19 @@ void launch_rmsnorm_block(const float *h, int S, int N, int block_start, int L, 
                        packed);
 }
 template <typename T>
-void launch_rope(T *qkv, int64_t tokens, int N, int n_heads, int n_kv_heads, int d_head, const float *cos_t,
+void launch_rope(T *qkv, int ld, int64_t tokens, int N, int n_heads, int n_kv_heads, int d_head, const float *cos_t,
                  const float *sin_t, hipStream_t st) {
-    hipLaunchKernelGGL(rope_kernel<T>, dim3((unsigned)tokens), dim3(256), 0, st, qkv, N, n_heads, n_kv_heads, d_head,
+    hipLaunchKernelGGL(rope_kernel<T>, dim3((unsigned)tokens), dim3(256), 0, st, qkv, ld, N, n_heads, n_kv_heads, d_head,
                        cos_t, sin_t);
 }
 template <>
-void launch_rope<bf16_t>(bf16_t *qkv, int64_t tokens, int N, int n_heads, int n_kv_heads, int d_head, const float *cos_t,
+void launch_rope<bf16_t>(bf16_t *qkv, int ld, int64_t tokens, int N, int n_heads, int n_kv_heads, int d_head, const float *cos_t,
                          const float *sin_t, hipStream_t st) {
     if (d_head % 16 == 0)
-        hipLaunchKernelGGL(rope_bf16_vec_kernel, dim3((unsigned)tokens), dim3(256), 0, st, qkv, N, n_heads, n_kv_heads, d_head,
+        hipLaunchKernelGGL(rope_bf16_vec_kernel, dim3((unsigned)tokens), dim3(256), 0, st, qkv, ld, N, n_heads, n_kv_heads, d_head,
                            cos_t, sin_t);
     else
-        hipLaunchKernelGGL(rope_kernel<bf16_t>, dim3((unsigned)tokens), dim3(256), 0, st, qkv, N, n_heads, n_kv_heads, d_head,
+        hipLaunchKernelGGL(rope_kernel<bf16_t>, dim3((unsigned)tokens), dim3(256), 0, st, qkv, ld, N, n_heads, n_kv_heads, d_head,
                            cos_t, sin_t);
 }
 
@@ -197,7 +197,7 @@ void launch_rope<bf16_t>(bf16_t *qkv, int64_t tokens, int N, int n_heads, int n_
     template void launch_rmsnorm<T>(const float *, int64_t, int, const float *, float, T *, hipStream_t);           \
     template void launch_rmsnorm_block<T>(const float *, int, int, int, int, int, const float *, float, T *, T *,   \
                                           hipStream_t);                                                             \
-    template void launch_rope<T>(T *, int64_t, int, int, int, int, const float *, const float *, hipStream_t);
+    template void launch_rope<T>(T *, int, int64_t, int, int, int, int, const float *, const float *, hipStream_t);
 INSTANTIATE(float)
 template void launch_embed<bf16_t>(const int32_t *, const int32_t *, int, int, const bf16_t *, int, float *, hipStream_t);
 template void launch_rmsnorm_block<bf16_t>(const float *, int, int, int, int, int, const float *, float, bf16_t *, bf16_t *,

@@ -9,7 +9,7 @@
 // (d_ffn = 12288) the row tiles of the down projection's activation operand all start in the same
 // cache channel and the fetches of a K-stage queue up behind each other (measured: 123 -> 93 us at
 // 512 tokens); other widths do not care.
-int64_t act_row_stride(const psd_model_config &cfg) { return cfg.d_ffn + 64; }
+int64_t act_row_stride(const psd_model_config &cfg) { return padded_row_stride(cfg.d_ffn); }
 
 ForwardPlan plan_forward(const psd_model_config &cfg, int64_t S, int64_t N, int64_t L) {
     const int64_t T = S * N, rows = S * L;
@@ -24,8 +24,8 @@ ForwardPlan plan_forward(const psd_model_config &cfg, int64_t S, int64_t N, int6
     };
     p.off_h = take(T * cfg.d_model * 4);
     p.off_a = take(T * cfg.d_model * esz);
-    p.off_qkv = take(T * qkv_w * esz);
-    p.off_vt = take(S * ((N + 63) / 64 * 64) * (int64_t)cfg.n_kv_heads * cfg.d_head * esz);   // rows padded to 64 keys
+    p.off_qkv = take(T * qkv_row_stride(qkv_w) * esz);
+    p.off_vt = take(S * vt_row_stride(N) * (int64_t)cfg.n_kv_heads * cfg.d_head * esz);
     p.off_o = take(T * (int64_t)cfg.n_heads * cfg.d_head * esz);
     p.off_act = take(T * act_row_stride(cfg) * esz);
     p.off_y = take(rows * cfg.d_model * esz);
@@ -57,9 +57,9 @@ struct Dispatch<float> {
         launch_plain_gemm<float, float>(A, (const float *)W, (const float *)W2, M, Nout, Kin, lda, epi, bias, 1.0f, out, resid,
                                         ldo, st);
     }
-    static void attention(psd_handle *, float *qkv, float *, int S, int N, int H, int Hkv, int dh, float *out,
+    static void attention(psd_handle *, float *qkv, int ld_qkv, float *, int S, int N, int H, int Hkv, int dh, float *out,
                           hipStream_t st) {
-        launch_plain_attention<float>(qkv, S, N, H, Hkv, dh, out, st);
+        launch_plain_attention<float>(qkv, ld_qkv, S, N, H, Hkv, dh, out, st);
     }
 };
 
@@ -83,13 +83,13 @@ struct Dispatch<bf16_t> {
             }
         }
     }
-    static void attention(psd_handle *h, bf16_t *qkv, bf16_t *vT, int S, int N, int H, int Hkv, int dh, bf16_t *out,
+    static void attention(psd_handle *h, bf16_t *qkv, int ld_qkv, bf16_t *vT, int S, int N, int H, int Hkv, int dh, bf16_t *out,
                           hipStream_t st) {
         if ((h->plain_mask & 2) || (N % 8) != 0) {
-            launch_plain_attention<bf16_t>(qkv, S, N, H, Hkv, dh, out, st);
+            launch_plain_attention<bf16_t>(qkv, ld_qkv, S, N, H, Hkv, dh, out, st);
         } else {
-            launch_transpose_v(qkv, S, N, H, Hkv, dh, vT, st);
-            launch_attention_bf16(qkv, vT, S, N, H, Hkv, dh, out, st);
+            launch_transpose_v(qkv, ld_qkv, S, N, H, Hkv, dh, vT, st);
+            launch_attention_bf16(qkv, ld_qkv, vT, S, N, H, Hkv, dh, out, st);
         }
     }
 };
@@ -105,7 +105,7 @@ int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t 
     float *hbuf = (float *)(ws + p.off_h);
     T *a = (T *)(ws + p.off_a), *qkv = (T *)(ws + p.off_qkv), *vT = (T *)(ws + p.off_vt), *o = (T *)(ws + p.off_o);
     T *act = (T *)(ws + p.off_act), *y = (T *)(ws + p.off_y);
-    const int ld_act = (int)act_row_stride(c);
+    const int ld_act = (int)act_row_stride(c), ld_qkv = (int)qkv_row_stride(qkv_w);
 
     launch_embed<T>(tokens, seq_rows, S, N, (const T *)h->tok_emb, d, hbuf, st);
     for (const psd_handle::Layer &lw : h->layers) {
@@ -116,14 +116,14 @@ int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t 
         const bool fused = wk == wq + (int64_t)H * dh * d && wv == wk + (int64_t)Hkv * dh * d &&
                            (!c.qkv_bias || (lw.bk == lw.bq + H * dh && lw.bv == lw.bk + Hkv * dh));
         if (fused) {
-            Dispatch<T>::gemm(h, a, d, wq, nullptr, ntok, qkv_w, d, epi_qkv, lw.bq, qkv, nullptr, qkv_w, st);
+            Dispatch<T>::gemm(h, a, d, wq, nullptr, ntok, qkv_w, d, epi_qkv, lw.bq, qkv, nullptr, ld_qkv, st);
         } else {
-            Dispatch<T>::gemm(h, a, d, wq, nullptr, ntok, H * dh, d, epi_qkv, lw.bq, qkv, nullptr, qkv_w, st);
-            Dispatch<T>::gemm(h, a, d, wk, nullptr, ntok, Hkv * dh, d, epi_qkv, lw.bk, qkv + H * dh, nullptr, qkv_w, st);
-            Dispatch<T>::gemm(h, a, d, wv, nullptr, ntok, Hkv * dh, d, epi_qkv, lw.bv, qkv + (H + Hkv) * dh, nullptr, qkv_w, st);
+            Dispatch<T>::gemm(h, a, d, wq, nullptr, ntok, H * dh, d, epi_qkv, lw.bq, qkv, nullptr, ld_qkv, st);
+            Dispatch<T>::gemm(h, a, d, wk, nullptr, ntok, Hkv * dh, d, epi_qkv, lw.bk, qkv + H * dh, nullptr, ld_qkv, st);
+            Dispatch<T>::gemm(h, a, d, wv, nullptr, ntok, Hkv * dh, d, epi_qkv, lw.bv, qkv + (H + Hkv) * dh, nullptr, ld_qkv, st);
         }
-        launch_rope<T>(qkv, ntok, N, H, Hkv, dh, h->rope_cos, h->rope_sin, st);
-        Dispatch<T>::attention(h, qkv, vT, S, N, H, Hkv, dh, o, st);
+        launch_rope<T>(qkv, ld_qkv, ntok, N, H, Hkv, dh, h->rope_cos, h->rope_sin, st);
+        Dispatch<T>::attention(h, qkv, ld_qkv, vT, S, N, H, Hkv, dh, o, st);
         Dispatch<T>::gemm(h, o, H * dh, lw.wo, nullptr, ntok, d, H * dh, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, st);
         launch_rmsnorm<T>(hbuf, ntok, d, lw.ffn_norm, c.rms_eps, a, st);
         Dispatch<T>::gemm(h, a, d, lw.w_gate, lw.w_up, ntok, F, d, EPI_SWIGLU, nullptr, act, nullptr, ld_act, st);

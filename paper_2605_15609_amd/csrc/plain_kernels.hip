@@ -69,14 +69,14 @@ __global__ __launch_bounds__(256) void plain_gemm_kernel(const T *__restrict__ A
 
 // one wavefront per (query, head, sequence); scores of all N keys kept in LDS
 template <typename T>
-__global__ __launch_bounds__(64) void plain_attention_kernel(const T *__restrict__ qkv, int N, int n_heads,
+__global__ __launch_bounds__(64) void plain_attention_kernel(const T *__restrict__ qkv, int ld, int N, int n_heads,
                                                              int n_kv_heads, int d_head, T *__restrict__ out) {
     extern __shared__ float smem[];
     float *qs = smem;            // [d_head]
     float *sc = smem + d_head;   // [N]
     const int i = blockIdx.x, hd = blockIdx.y, s = blockIdx.z;
     const int lane = threadIdx.x;
-    const int row_w = (n_heads + 2 * n_kv_heads) * d_head;
+    const int row_w = ld;
     const int kvh = hd / (n_heads / n_kv_heads);
     const T *base = qkv + (int64_t)s * N * row_w;
     const T *q = base + (int64_t)i * row_w + hd * d_head;
@@ -191,9 +191,9 @@ void launch_plain_gemm(const T *A, const T *W, const T *W2, int64_t M, int Nout,
 }
 
 template <typename T>
-void launch_plain_attention(const T *qkv, int S, int N, int n_heads, int n_kv_heads, int d_head, T *out, hipStream_t st) {
+void launch_plain_attention(const T *qkv, int ld, int S, int N, int n_heads, int n_kv_heads, int d_head, T *out, hipStream_t st) {
     const size_t smem = (size_t)(d_head + N) * sizeof(float);
-    hipLaunchKernelGGL(plain_attention_kernel<T>, dim3(N, n_heads, S), dim3(64), smem, st, qkv, N, n_heads, n_kv_heads,
+    hipLaunchKernelGGL(plain_attention_kernel<T>, dim3(N, n_heads, S), dim3(64), smem, st, qkv, ld, N, n_heads, n_kv_heads,
                        d_head, out);
 }
 
@@ -216,5 +216,5 @@ template void launch_plain_gemm<bf16_t, bf16_t>(const bf16_t *, const bf16_t *, 
                                                 const float *, float, bf16_t *, float *, int, hipStream_t);
 template void launch_plain_gemm<bf16_t, float>(const bf16_t *, const bf16_t *, const bf16_t *, int64_t, int, int, int, int,
                                                const float *, float, float *, float *, int, hipStream_t);
-template void launch_plain_attention<float>(const float *, int, int, int, int, int, float *, hipStream_t);
-template void launch_plain_attention<bf16_t>(const bf16_t *, int, int, int, int, int, bf16_t *, hipStream_t);
+template void launch_plain_attention<float>(const float *, int, int, int, int, int, int, float *, hipStream_t);
+template void launch_plain_attention<bf16_t>(const bf16_t *, int, int, int, int, int, int, bf16_t *, hipStream_t);

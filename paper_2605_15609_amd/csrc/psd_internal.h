@@ -101,10 +101,16 @@ template <typename T>
 void launch_rmsnorm_block(const float *h, int S, int N, int block_start, int L, int d, const float *gain,
                           float eps, T *out, T *packed /* fragment-order copy, may be NULL */, hipStream_t st);
 template <typename T>
-void launch_rope(T *qkv, int64_t tokens, int N, int n_heads, int n_kv_heads, int d_head, const float *cos_t,
+void launch_rope(T *qkv, int ld /* row stride */, int64_t tokens, int N, int n_heads, int n_kv_heads, int d_head, const float *cos_t,
                  const float *sin_t, hipStream_t st);
-// vT[s][kvh][c][i] <- V part of qkv[s*N + i]; the MFMA attention reads values key-contiguous
-void launch_transpose_v(const bf16_t *qkv, int S, int N, int n_heads, int n_kv_heads, int d_head, bf16_t *vT,
+// Row strides of the workspace matrices.  Padding rows by 64 elements keeps consecutive rows out of the same
+// cache channel; it pays for the SwiGLU output (24 KB rows feeding the down projection) and was measured
+// to make no difference for qkv and vT, which stay dense.
+inline int64_t padded_row_stride(int64_t width) { return width + 64; }
+inline int64_t qkv_row_stride(int64_t w) { return w; }
+inline int64_t vt_row_stride(int64_t N) { return (N + 63) / 64 * 64; }
+// vT[s][kvh][c][i] <- V part of qkv[s*N + i] (rows of vt_row_stride(N) elements); the MFMA attention reads values key-contiguous
+void launch_transpose_v(const bf16_t *qkv, int ld_qkv, int S, int N, int n_heads, int n_kv_heads, int d_head, bf16_t *vT,
                         hipStream_t st);
 
 // plain_kernels.hip (debug path, any shape)
@@ -113,7 +119,7 @@ template <typename T, typename TO>
 void launch_plain_gemm(const T *A, const T *W, const T *W2, int64_t M, int Nout, int Kin, int lda, int epi, const float *bias,
                        float scale, TO *out, float *resid, int ldo, hipStream_t st);
 template <typename T>
-void launch_plain_attention(const T *qkv, int S, int N, int n_heads, int n_kv_heads, int d_head, T *out,
+void launch_plain_attention(const T *qkv, int ld, int S, int N, int n_heads, int n_kv_heads, int d_head, T *out,
                             hipStream_t st);
 void launch_logits_top1(const float *logits, int rows, int V, int mask_id, float *row_sum, int32_t *row_arg,
                         hipStream_t st);
@@ -135,7 +141,7 @@ void launch_mfma_rate(const void *operands, int n_vec16, int iters, void *sink, 
 void launch_gemm_bf16(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int64_t M, int Nout, int Kin, int lda, int ldw, int epi,
                       const float *bias, bf16_t *out, float *resid, int ldo, hipStream_t st);
 // attention_mfma.hip (bf16, d_head 64 or 128): q, k from qkv (rotary applied), values from vT
-void launch_attention_bf16(const bf16_t *qkv, const bf16_t *vT, int S, int N, int n_heads, int n_kv_heads, int d_head,
+void launch_attention_bf16(const bf16_t *qkv, int ld_qkv, const bf16_t *vT, int S, int N, int n_heads, int n_kv_heads, int d_head,
                            bf16_t *out, hipStream_t st);
 // lm_head.hip (bf16): LM-head fused with the online top-1 / sum-exp reduction
 int64_t head_partial_bytes(int rows, int V);

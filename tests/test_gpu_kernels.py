@@ -119,7 +119,13 @@ def test_attention_sampled_queries(label, S, N, H, Hkv, dh):
     print(f"[kernels] attention {label}", flush=True)
     rng = np.random.default_rng(len(label) + N)
     qkv = bf16_round_trip(rng.standard_normal((S * N, (H + 2 * Hkv) * dh), dtype=np.float32))
-    out = host_f64(B.kernel_attention_bf16(dev_bf16(qkv), S, N, H, Hkv, dh))
+    d_qkv = dev_bf16(qkv)
+    out = host_f64(B.kernel_attention_bf16(d_qkv, S, N, H, Hkv, dh))
+    # the forward keeps qkv with padded rows: same result from a row-strided view
+    padded = torch.zeros((S * N, qkv.shape[1] + 64), dtype=torch.bfloat16, device=DEV)
+    padded[:, :qkv.shape[1]] = d_qkv
+    out_padded = B.kernel_attention_bf16(padded[:, :qkv.shape[1]], S, N, H, Hkv, dh)
+    assert torch.equal(out_padded.cpu(), torch.from_numpy(out).to(torch.bfloat16)), f"{label}: row-strided qkv changes the result"
     torch.cuda.synchronize()
     group = H // Hkv
     worst = 0.0
