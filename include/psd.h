@@ -84,7 +84,10 @@ typedef struct {
     const float *const *ffn_norm;    /* [d_model] */
     const void  *const *w_gate;      /* [d_ffn, d_model] */
     const void  *const *w_up;        /* [d_ffn, d_model] */
-    const void  *const *w_down;      /* [d_model, d_ffn] */
+    const void  *const *w_down;      /* [d_model, d_ffn], row stride w_down_stride */
+    int32_t w_down_stride;           /* elements between rows of w_down; 0 = d_ffn (dense).  A multiple of 8.
+                                      * Rows padded by 64 elements avoid cache-channel conflicts on MI355X
+                                      * when a dense row is a multiple of 8 KB (d_ffn = 12288). */
 } psd_weights;
 
 /* Transfer policy pi (Sec. 3.2 stage 1; App. B.2): over the masked positions of the block,

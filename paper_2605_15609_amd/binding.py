@@ -37,7 +37,8 @@ _PP = C.POINTER(C.c_void_p)
 class _Weights(C.Structure):
     _fields_ = [("tok_emb", C.c_void_p), ("final_norm", C.c_void_p), ("lm_head", C.c_void_p), ("rope_cos", C.c_void_p),
                 ("rope_sin", C.c_void_p), ("attn_norm", _PP), ("wq", _PP), ("wk", _PP), ("wv", _PP), ("bq", _PP),
-                ("bk", _PP), ("bv", _PP), ("wo", _PP), ("ffn_norm", _PP), ("w_gate", _PP), ("w_up", _PP), ("w_down", _PP)]
+                ("bk", _PP), ("bv", _PP), ("wo", _PP), ("ffn_norm", _PP), ("w_gate", _PP), ("w_up", _PP), ("w_down", _PP),
+                ("w_down_stride", C.c_int32)]
 
 
 class _Policy(C.Structure):
@@ -189,13 +190,21 @@ def _dev_i32(t, device):
 
 def pack_qkv(lt: dict) -> None:
     """Re-homes wq | wk | wv (and bq | bk | bv) of one layer back to back in one allocation, so the
-    library can run the three projections as a single contraction.  Views keep the storage alive."""
+    library can run the three projections as a single contraction, and w_down into padded rows.
+    Views keep the storage alive."""
     w = torch.cat([lt["wq"], lt["wk"], lt["wv"]], dim=0).contiguous()
     nq, nk = lt["wq"].shape[0], lt["wk"].shape[0]
     lt["wq"], lt["wk"], lt["wv"] = w[:nq], w[nq:nq + nk], w[nq + nk:]
     if lt.get("bq") is not None:
         b = torch.cat([lt["bq"], lt["bk"], lt["bv"]]).contiguous()
         lt["bq"], lt["bk"], lt["bv"] = b[:nq], b[nq:nq + nk], b[nq + nk:]
+    # w_down [d_model, d_ffn] with rows padded by 64 elements: dense rows of a multiple of 8 KB would all start
+    # in the same cache channel (see psd_weights.w_down_stride)
+    wd = lt["w_down"]
+    if wd.dtype == torch.bfloat16 and wd.stride(0) == wd.shape[1]:
+        padded = torch.zeros((wd.shape[0], wd.shape[1] + 64), dtype=wd.dtype, device=wd.device)
+        padded[:, :wd.shape[1]] = wd
+        lt["w_down"] = padded[:, :wd.shape[1]]
 
 
 class Model:
@@ -225,6 +234,9 @@ class Model:
             arr = (C.c_void_p * shape.n_layers)(*[lt[name].data_ptr() for lt in layer_tensors])
             self._arrays[name] = arr
             setattr(w, name, C.cast(arr, _PP))
+        strides = {lt["w_down"].stride(0) for lt in layer_tensors}
+        assert len(strides) == 1 and all(lt["w_down"].stride(1) == 1 for lt in layer_tensors)
+        w.w_down_stride = strides.pop()
         handle = C.c_void_p()
         with torch.cuda.device(self.device):
             _check(self.lib.psd_create(C.byref(cfg), C.byref(w), C.byref(handle)))

@@ -134,6 +134,8 @@ int32_t psd_create(const psd_model_config *cfg, const psd_weights *w, psd_handle
         !w->wv || !w->wo || !w->ffn_norm || !w->w_gate || !w->w_up || !w->w_down)
         PSD_FAIL(PSD_ERR_INVALID_ARG, "a weight pointer is NULL");
     if (cfg->qkv_bias && (!w->bq || !w->bk || !w->bv)) PSD_FAIL(PSD_ERR_INVALID_ARG, "qkv_bias set but a bias array is NULL");
+    if (w->w_down_stride != 0 && (w->w_down_stride < cfg->d_ffn || w->w_down_stride % 8 || w->w_down_stride > (1 << 20)))
+        PSD_FAIL(PSD_ERR_SHAPE, "w_down_stride %d: 0 or a multiple of 8 in [d_ffn, 2^20]", w->w_down_stride);
     int dev = 0;
     PSD_HIP(hipGetDevice(&dev));
     hipDeviceProp_t prop;
@@ -148,6 +150,7 @@ int32_t psd_create(const psd_model_config *cfg, const psd_weights *w, psd_handle
     h->final_norm = w->final_norm;
     h->rope_cos = w->rope_cos;
     h->rope_sin = w->rope_sin;
+    h->w_down_stride = w->w_down_stride ? w->w_down_stride : cfg->d_ffn;
     h->device = dev;
     h->plain_mask = 0;
     h->layers.resize(cfg->n_layers);

@@ -51,11 +51,11 @@ struct Dispatch;
 
 template <>
 struct Dispatch<float> {
-    // A [M, Kin] with row stride lda; weights dense [Nout, Kin]
-    static void gemm(psd_handle *, const float *A, int lda, const void *W, const void *W2, int64_t M, int Nout, int Kin, int epi,
-                     const float *bias, float *out, float *resid, int ldo, hipStream_t st) {
-        launch_plain_gemm<float, float>(A, (const float *)W, (const float *)W2, M, Nout, Kin, lda, epi, bias, 1.0f, out, resid,
-                                        ldo, st);
+    // A [M, Kin] with row stride lda; weights [Nout, Kin] with row stride ldw
+    static void gemm(psd_handle *, const float *A, int lda, const void *W, const void *W2, int ldw, int64_t M, int Nout, int Kin,
+                     int epi, const float *bias, float *out, float *resid, int ldo, hipStream_t st) {
+        launch_plain_gemm<float, float>(A, (const float *)W, (const float *)W2, M, Nout, Kin, lda, ldw, epi, bias, 1.0f, out,
+                                        resid, ldo, st);
     }
     static void attention(psd_handle *, float *qkv, int ld_qkv, float *, int S, int N, int H, int Hkv, int dh, float *out,
                           hipStream_t st) {
@@ -65,17 +65,17 @@ struct Dispatch<float> {
 
 template <>
 struct Dispatch<bf16_t> {
-    static void gemm(psd_handle *h, const bf16_t *A, int lda, const void *W, const void *W2, int64_t M, int Nout, int Kin, int epi,
-                     const float *bias, bf16_t *out, float *resid, int ldo, hipStream_t st) {
+    static void gemm(psd_handle *h, const bf16_t *A, int lda, const void *W, const void *W2, int ldw, int64_t M, int Nout, int Kin,
+                     int epi, const float *bias, bf16_t *out, float *resid, int ldo, hipStream_t st) {
         if (h->plain_mask & 1)
-            launch_plain_gemm<bf16_t, bf16_t>(A, (const bf16_t *)W, (const bf16_t *)W2, M, Nout, Kin, lda, epi, bias, 1.0f, out,
+            launch_plain_gemm<bf16_t, bf16_t>(A, (const bf16_t *)W, (const bf16_t *)W2, M, Nout, Kin, lda, ldw, epi, bias, 1.0f, out,
                                               resid, ldo, st);
         else {
             psd_handle::Probe &pr = h->probe;
             const bool timed = pr.enabled && epi == pr.epi && gemm_bf16_tile(M, Nout, epi) == pr.tile &&
                                pr.used + 2 <= pr.ev.size();
             if (timed) (void)hipEventRecord(pr.ev[pr.used], st);
-            launch_gemm_bf16(A, (const bf16_t *)W, (const bf16_t *)W2, M, Nout, Kin, lda, Kin, epi, bias, out, resid, ldo, st);
+            launch_gemm_bf16(A, (const bf16_t *)W, (const bf16_t *)W2, M, Nout, Kin, lda, ldw, epi, bias, out, resid, ldo, st);
             if (timed) {
                 (void)hipEventRecord(pr.ev[pr.used + 1], st);
                 pr.used += 2;
@@ -116,18 +116,18 @@ int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t 
         const bool fused = wk == wq + (int64_t)H * dh * d && wv == wk + (int64_t)Hkv * dh * d &&
                            (!c.qkv_bias || (lw.bk == lw.bq + H * dh && lw.bv == lw.bk + Hkv * dh));
         if (fused) {
-            Dispatch<T>::gemm(h, a, d, wq, nullptr, ntok, qkv_w, d, epi_qkv, lw.bq, qkv, nullptr, ld_qkv, st);
+            Dispatch<T>::gemm(h, a, d, wq, nullptr, d, ntok, qkv_w, d, epi_qkv, lw.bq, qkv, nullptr, ld_qkv, st);
         } else {
-            Dispatch<T>::gemm(h, a, d, wq, nullptr, ntok, H * dh, d, epi_qkv, lw.bq, qkv, nullptr, ld_qkv, st);
-            Dispatch<T>::gemm(h, a, d, wk, nullptr, ntok, Hkv * dh, d, epi_qkv, lw.bk, qkv + H * dh, nullptr, ld_qkv, st);
-            Dispatch<T>::gemm(h, a, d, wv, nullptr, ntok, Hkv * dh, d, epi_qkv, lw.bv, qkv + (H + Hkv) * dh, nullptr, ld_qkv, st);
+            Dispatch<T>::gemm(h, a, d, wq, nullptr, d, ntok, H * dh, d, epi_qkv, lw.bq, qkv, nullptr, ld_qkv, st);
+            Dispatch<T>::gemm(h, a, d, wk, nullptr, d, ntok, Hkv * dh, d, epi_qkv, lw.bk, qkv + H * dh, nullptr, ld_qkv, st);
+            Dispatch<T>::gemm(h, a, d, wv, nullptr, d, ntok, Hkv * dh, d, epi_qkv, lw.bv, qkv + (H + Hkv) * dh, nullptr, ld_qkv, st);
         }
         launch_rope<T>(qkv, ld_qkv, ntok, N, H, Hkv, dh, h->rope_cos, h->rope_sin, st);
         Dispatch<T>::attention(h, qkv, ld_qkv, vT, S, N, H, Hkv, dh, o, st);
-        Dispatch<T>::gemm(h, o, H * dh, lw.wo, nullptr, ntok, d, H * dh, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, st);
+        Dispatch<T>::gemm(h, o, H * dh, lw.wo, nullptr, H * dh, ntok, d, H * dh, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, st);
         launch_rmsnorm<T>(hbuf, ntok, d, lw.ffn_norm, c.rms_eps, a, st);
-        Dispatch<T>::gemm(h, a, d, lw.w_gate, lw.w_up, ntok, F, d, EPI_SWIGLU, nullptr, act, nullptr, ld_act, st);
-        Dispatch<T>::gemm(h, act, ld_act, lw.w_down, nullptr, ntok, d, F, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, st);
+        Dispatch<T>::gemm(h, a, d, lw.w_gate, lw.w_up, d, ntok, F, d, EPI_SWIGLU, nullptr, act, nullptr, ld_act, st);
+        Dispatch<T>::gemm(h, act, ld_act, lw.w_down, nullptr, h->w_down_stride, ntok, d, F, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, st);
     }
     T *ypack = (c.dtype == PSD_DTYPE_BF16 && h->lm_head_packed && head_stream_supported(S * L, d)) ? (T *)(ws + p.off_ypack) : nullptr;
     launch_rmsnorm_block<T>(hbuf, S, N, block_start, L, d, h->final_norm, c.rms_eps, y, ypack, st);
@@ -191,11 +191,11 @@ int32_t run_head_confidence(psd_handle *h, const int32_t *tokens, const int32_t 
         float *logits = (float *)(ws + p.off_part);
         if (c.dtype == PSD_DTYPE_BF16)
             launch_plain_gemm<bf16_t, float>((const bf16_t *)(ws + p.off_y), (const bf16_t *)h->lm_head, nullptr, rows,
-                                             c.vocab, c.d_model, c.d_model, EPI_STORE, nullptr, c.logit_scale, logits, nullptr, c.vocab,
+                                             c.vocab, c.d_model, c.d_model, c.d_model, EPI_STORE, nullptr, c.logit_scale, logits, nullptr, c.vocab,
                                              st);
         else
             launch_plain_gemm<float, float>((const float *)(ws + p.off_y), (const float *)h->lm_head, nullptr, rows, c.vocab,
-                                            c.d_model, c.d_model, EPI_STORE, nullptr, c.logit_scale, logits, nullptr, c.vocab, st);
+                                            c.d_model, c.d_model, c.d_model, EPI_STORE, nullptr, c.logit_scale, logits, nullptr, c.vocab, st);
         launch_logits_top1(logits, rows, c.vocab, c.mask_id, row_sum, row_arg, st);
     }
     launch_head_finish(row_sum, row_arg, tokens, seq_rows, out_rows, S, N, block_start, L, c.mask_id, top1, conf, st);
@@ -210,10 +210,10 @@ int32_t run_head_logits(psd_handle *h, int S, int N, int L, float *logits, void 
     const int rows = S * L;
     if (c.dtype == PSD_DTYPE_BF16)
         launch_plain_gemm<bf16_t, float>((const bf16_t *)(ws + p.off_y), (const bf16_t *)h->lm_head, nullptr, rows, c.vocab,
-                                         c.d_model, c.d_model, EPI_STORE, nullptr, c.logit_scale, logits, nullptr, c.vocab, st);
+                                         c.d_model, c.d_model, c.d_model, EPI_STORE, nullptr, c.logit_scale, logits, nullptr, c.vocab, st);
     else
         launch_plain_gemm<float, float>((const float *)(ws + p.off_y), (const float *)h->lm_head, nullptr, rows, c.vocab,
-                                        c.d_model, c.d_model, EPI_STORE, nullptr, c.logit_scale, logits, nullptr, c.vocab, st);
+                                        c.d_model, c.d_model, c.d_model, EPI_STORE, nullptr, c.logit_scale, logits, nullptr, c.vocab, st);
     PSD_HIP(hipGetLastError());
     return PSD_OK;
 }

@@ -11,7 +11,7 @@ constexpr int GK = 16;
 
 template <typename T, typename TO>
 __global__ __launch_bounds__(256) void plain_gemm_kernel(const T *__restrict__ A, const T *__restrict__ W,
-                                                         const T *__restrict__ W2, int64_t M, int Nout, int Kin, int lda, int epi,
+                                                         const T *__restrict__ W2, int64_t M, int Nout, int Kin, int lda, int ldw, int epi,
                                                          const float *__restrict__ bias, float scale,
                                                          TO *__restrict__ out, float *__restrict__ resid, int ldo) {
     __shared__ float As[GK][GT + 1];
@@ -27,8 +27,8 @@ __global__ __launch_bounds__(256) void plain_gemm_kernel(const T *__restrict__ A
             const int r = e / GK, c = e % GK;
             const int k = k0 + c;
             As[c][r] = (m0 + r < M && k < Kin) ? to_float(A[(m0 + r) * lda + k]) : 0.f;
-            Ws[c][r] = (n0 + r < Nout && k < Kin) ? to_float(W[(int64_t)(n0 + r) * Kin + k]) : 0.f;
-            if (dual) W2s[c][r] = (n0 + r < Nout && k < Kin) ? to_float(W2[(int64_t)(n0 + r) * Kin + k]) : 0.f;
+            Ws[c][r] = (n0 + r < Nout && k < Kin) ? to_float(W[(int64_t)(n0 + r) * ldw + k]) : 0.f;
+            if (dual) W2s[c][r] = (n0 + r < Nout && k < Kin) ? to_float(W2[(int64_t)(n0 + r) * ldw + k]) : 0.f;
         }
         __syncthreads();
 #pragma unroll
@@ -183,10 +183,10 @@ __global__ void head_finish_kernel(const float *__restrict__ row_sum, const int3
 }   // namespace
 
 template <typename T, typename TO>
-void launch_plain_gemm(const T *A, const T *W, const T *W2, int64_t M, int Nout, int Kin, int lda, int epi, const float *bias,
+void launch_plain_gemm(const T *A, const T *W, const T *W2, int64_t M, int Nout, int Kin, int lda, int ldw, int epi, const float *bias,
                        float scale, TO *out, float *resid, int ldo, hipStream_t st) {
     dim3 grid((Nout + GT - 1) / GT, (unsigned)((M + GT - 1) / GT));
-    hipLaunchKernelGGL((plain_gemm_kernel<T, TO>), grid, dim3(256), 0, st, A, W, W2, M, Nout, Kin, lda, epi, bias, scale, out,
+    hipLaunchKernelGGL((plain_gemm_kernel<T, TO>), grid, dim3(256), 0, st, A, W, W2, M, Nout, Kin, lda, ldw, epi, bias, scale, out,
                        resid, ldo);
 }
 
@@ -210,11 +210,11 @@ void launch_head_finish(const float *row_sum, const int32_t *row_arg, const int3
                        out_rows, S, N, block_start, L, mask_id, top1, conf);
 }
 
-template void launch_plain_gemm<float, float>(const float *, const float *, const float *, int64_t, int, int, int, int,
+template void launch_plain_gemm<float, float>(const float *, const float *, const float *, int64_t, int, int, int, int, int,
                                               const float *, float, float *, float *, int, hipStream_t);
-template void launch_plain_gemm<bf16_t, bf16_t>(const bf16_t *, const bf16_t *, const bf16_t *, int64_t, int, int, int, int,
+template void launch_plain_gemm<bf16_t, bf16_t>(const bf16_t *, const bf16_t *, const bf16_t *, int64_t, int, int, int, int, int,
                                                 const float *, float, bf16_t *, float *, int, hipStream_t);
-template void launch_plain_gemm<bf16_t, float>(const bf16_t *, const bf16_t *, const bf16_t *, int64_t, int, int, int, int,
+template void launch_plain_gemm<bf16_t, float>(const bf16_t *, const bf16_t *, const bf16_t *, int64_t, int, int, int, int, int,
                                                const float *, float, float *, float *, int, hipStream_t);
 template void launch_plain_attention<float>(const float *, int, int, int, int, int, int, float *, hipStream_t);
 template void launch_plain_attention<bf16_t>(const bf16_t *, int, int, int, int, int, int, bf16_t *, hipStream_t);

@@ -21,6 +21,7 @@ struct psd_handle {
         const void *wq, *wk, *wv, *wo, *w_gate, *w_up, *w_down;
     };
     std::vector<Layer> layers;
+    int w_down_stride;       // row stride of every w_down (elements)
     int device;
     int plain_mask;          // debug: bit 0 plain GEMM, bit 1 plain attention, bit 2 plain LM-head
     void *lm_head_packed;    // bf16 models: fragment-order copy of lm_head owned by the handle (streaming LM-head)
@@ -116,7 +117,7 @@ void launch_transpose_v(const bf16_t *qkv, int ld_qkv, int S, int N, int n_heads
 // plain_kernels.hip (debug path, any shape)
 enum Epilogue { EPI_STORE = 0, EPI_BIAS = 1, EPI_RESIDUAL = 2, EPI_SWIGLU = 3 };
 template <typename T, typename TO>
-void launch_plain_gemm(const T *A, const T *W, const T *W2, int64_t M, int Nout, int Kin, int lda, int epi, const float *bias,
+void launch_plain_gemm(const T *A, const T *W, const T *W2, int64_t M, int Nout, int Kin, int lda, int ldw, int epi, const float *bias,
                        float scale, TO *out, float *resid, int ldo, hipStream_t st);
 template <typename T>
 void launch_plain_attention(const T *qkv, int ld, int S, int N, int n_heads, int n_kv_heads, int d_head, T *out,
