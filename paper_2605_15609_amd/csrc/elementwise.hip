@@ -152,6 +152,25 @@ __global__ __launch_bounds__(256) void rope_bf16_vec_kernel(bf16_t *__restrict__
 
 }   // namespace
 
+namespace {
+// dst[r, :] = src[(r / L) * N + block_start + r % L, :]: the block rows of every sequence, packed
+template <typename T>
+__global__ __launch_bounds__(256) void gather_block_rows_kernel(const T *__restrict__ src, T *__restrict__ dst, int width, int N,
+                                                                int block_start, int L) {
+    const int64_t r = blockIdx.x;
+    const T *s = src + ((r / L) * N + block_start + (r % L)) * width;
+    T *d = dst + r * width;
+    for (int c = threadIdx.x; c < width; c += blockDim.x) d[c] = s[c];
+}
+}   // namespace
+
+template <typename T>
+void launch_gather_block_rows(const T *src, T *dst, int width, int S, int N, int block_start, int L, hipStream_t st) {
+    hipLaunchKernelGGL(gather_block_rows_kernel<T>, dim3((unsigned)(S * L)), dim3(256), 0, st, src, dst, width, N, block_start, L);
+}
+template void launch_gather_block_rows<float>(const float *, float *, int, int, int, int, int, hipStream_t);
+template void launch_gather_block_rows<bf16_t>(const bf16_t *, bf16_t *, int, int, int, int, int, hipStream_t);
+
 template <typename T>
 void launch_embed(const int32_t *tokens, const int32_t *seq_rows, int S, int N, const T *emb, int d, float *h,
                   hipStream_t st) {

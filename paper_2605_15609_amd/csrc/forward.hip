@@ -28,6 +28,8 @@ ForwardPlan plan_forward(const psd_model_config &cfg, int64_t S, int64_t N, int6
     p.off_vt = take(S * vt_row_stride(N) * (int64_t)cfg.n_kv_heads * cfg.d_head * esz);
     p.off_o = take(T * (int64_t)cfg.n_heads * cfg.d_head * esz);
     p.off_act = take(T * act_row_stride(cfg) * esz);
+    p.off_oc = take(rows * (int64_t)cfg.n_heads * cfg.d_head * esz);   // last layer: attention output and residual
+    p.off_hc = take(rows * cfg.d_model * 4);                           // stream of the block rows only
     p.off_y = take(rows * cfg.d_model * esz);
     p.off_ypack = take(cfg.dtype == PSD_DTYPE_BF16 ? packed_rows_bytes(rows, cfg.d_model) : 0);
     p.off_rowsum = take(rows * 4);
@@ -107,8 +109,10 @@ int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t 
     T *act = (T *)(ws + p.off_act), *y = (T *)(ws + p.off_y);
     const int ld_act = (int)act_row_stride(c), ld_qkv = (int)qkv_row_stride(qkv_w);
 
+    const float *final_in = hbuf;
     launch_embed<T>(tokens, seq_rows, S, N, (const T *)h->tok_emb, d, hbuf, st);
-    for (const psd_handle::Layer &lw : h->layers) {
+    for (size_t li = 0; li < h->layers.size(); ++li) {
+        const psd_handle::Layer &lw = h->layers[li];
         launch_rmsnorm<T>(hbuf, ntok, d, lw.attn_norm, c.rms_eps, a, st);
         const int epi_qkv = c.qkv_bias ? EPI_BIAS : EPI_STORE;
         // one launch when wq | wk | wv (and the biases) sit back to back in memory, as one [qkv_w, d] matrix
@@ -124,13 +128,29 @@ int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t 
         }
         launch_rope<T>(qkv, ld_qkv, ntok, N, H, Hkv, dh, h->rope_cos, h->rope_sin, st);
         Dispatch<T>::attention(h, qkv, ld_qkv, vT, S, N, H, Hkv, dh, o, st);
-        Dispatch<T>::gemm(h, o, H * dh, lw.wo, nullptr, H * dh, ntok, d, H * dh, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, st);
-        launch_rmsnorm<T>(hbuf, ntok, d, lw.ffn_norm, c.rms_eps, a, st);
-        Dispatch<T>::gemm(h, a, d, lw.w_gate, lw.w_up, d, ntok, F, d, EPI_SWIGLU, nullptr, act, nullptr, ld_act, st);
-        Dispatch<T>::gemm(h, act, ld_act, lw.w_down, nullptr, h->w_down_stride, ntok, d, F, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, st);
+        // After the last attention only the block rows feed the LM-head: the rest of that layer (output
+        // projection, FFN) and the final norm run on those S*L rows alone, gathered into a packed stream.
+        float *hs = hbuf;
+        T *os = o;
+        int64_t nrow = ntok;
+        if (li + 1 == h->layers.size() && L < N) {
+            hs = (float *)(ws + p.off_hc);
+            os = (T *)(ws + p.off_oc);
+            nrow = (int64_t)S * L;
+            launch_gather_block_rows<float>(hbuf, hs, d, S, N, block_start, L, st);
+            launch_gather_block_rows<T>(o, os, H * dh, S, N, block_start, L, st);
+            final_in = hs;
+        }
+        Dispatch<T>::gemm(h, os, H * dh, lw.wo, nullptr, H * dh, nrow, d, H * dh, EPI_RESIDUAL, nullptr, nullptr, hs, d, st);
+        launch_rmsnorm<T>(hs, nrow, d, lw.ffn_norm, c.rms_eps, a, st);
+        Dispatch<T>::gemm(h, a, d, lw.w_gate, lw.w_up, d, nrow, F, d, EPI_SWIGLU, nullptr, act, nullptr, ld_act, st);
+        Dispatch<T>::gemm(h, act, ld_act, lw.w_down, nullptr, h->w_down_stride, nrow, d, F, EPI_RESIDUAL, nullptr, nullptr, hs, d, st);
     }
     T *ypack = (c.dtype == PSD_DTYPE_BF16 && h->lm_head_packed && head_stream_supported(S * L, d)) ? (T *)(ws + p.off_ypack) : nullptr;
-    launch_rmsnorm_block<T>(hbuf, S, N, block_start, L, d, h->final_norm, c.rms_eps, y, ypack, st);
+    if (final_in != hbuf)   // already the packed block rows
+        launch_rmsnorm_block<T>(final_in, S, L, 0, L, d, h->final_norm, c.rms_eps, y, ypack, st);
+    else
+        launch_rmsnorm_block<T>(hbuf, S, N, block_start, L, d, h->final_norm, c.rms_eps, y, ypack, st);
     return PSD_OK;
 }
 

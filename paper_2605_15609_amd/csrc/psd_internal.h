@@ -77,7 +77,7 @@ void launch_accept(int32_t *tokens, const int32_t *drafts, int B, int N, int blo
 
 // ---------------------------------------------------------------- forward (forward.hip)
 struct ForwardPlan {
-    int64_t off_h, off_a, off_qkv, off_vt, off_o, off_act, off_y, off_ypack, off_rowsum, off_rowarg, off_part, total;
+    int64_t off_h, off_a, off_qkv, off_vt, off_o, off_act, off_oc, off_hc, off_y, off_ypack, off_rowsum, off_rowarg, off_part, total;
 };
 ForwardPlan plan_forward(const psd_model_config &cfg, int64_t S, int64_t N, int64_t L);
 
@@ -101,6 +101,9 @@ void launch_rmsnorm(const float *h, int64_t rows, int d, const float *gain, floa
 template <typename T>
 void launch_rmsnorm_block(const float *h, int S, int N, int block_start, int L, int d, const float *gain,
                           float eps, T *out, T *packed /* fragment-order copy, may be NULL */, hipStream_t st);
+// dst [S*L, width] <- the L block rows of each of the S sequences of src [S*N, width]
+template <typename T>
+void launch_gather_block_rows(const T *src, T *dst, int width, int S, int N, int block_start, int L, hipStream_t st);
 template <typename T>
 void launch_rope(T *qkv, int ld /* row stride */, int64_t tokens, int N, int n_heads, int n_kv_heads, int d_head, const float *cos_t,
                  const float *sin_t, hipStream_t st);
