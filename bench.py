@@ -140,9 +140,17 @@ def main():
         hms, hcalls, hbytes = model.probe_end(4)
         if hcalls > 0 and hms > 0:
             gbs = hbytes / (hms * 1e-3) / 1e9
+            # rows per pass from the byte count (V d 2 + rows (d 2 + 8)); above the ridge (315 FLOP/B) the pass is MFMA work
+            w_bytes = shape.vocab * shape.d_model * 2.0
+            avg_rows = (hbytes / hcalls - w_bytes) / (shape.d_model * 2.0 + 8.0)
             lm_head = {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
                        "calls": int(hcalls), "avg_pass_us": hms * 1e3 / hcalls, "bytes_per_pass": hbytes / hcalls,
-                       "what": "LM-head confidence pass (weight stream + merge), stage-1 and verify calls together"}
+                       "avg_rows": avg_rows,
+                       "what": "LM-head confidence pass (final norm, weight stream, merge), stage-1 and verify calls together"}
+            if avg_rows > 315:
+                tfl = 2.0 * avg_rows * shape.vocab * shape.d_model * hcalls / (hms * 1e-3) / 1e12
+                lm_head.update({"bound": "mfma", "achieved": tfl, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                "frac": tfl / MFMA_BF16_PEAK_TFLOPS})
         ms, launches, flops = model.probe_end(3)
         if launches > 0 and ms > 0:
             achieved = flops / (ms * 1e-3) / 1e12

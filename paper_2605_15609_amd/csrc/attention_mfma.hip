@@ -34,7 +34,7 @@ typedef __attribute__((address_space(3))) void lds_void;
 
 // NW wavefronts (32 queries each) per workgroup; ld_qkv / ld_vt = row strides (elements) of qkv and of vT,
 // whose rows hold N rounded up to 64 keys (tail zero)
-template <int DH, int NW>
+template <int DH, int NW, int NSTG>
 __global__ __launch_bounds__(NW * 64) void attention_kernel(const bf16_t *__restrict__ qkv, int ld_qkv,
                                                             const bf16_t *__restrict__ vT, int ld_vt, int N, int n_heads,
                                                             int n_kv_heads, bf16_t *__restrict__ out) {
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(const bf16_t *__rest
     }
 #define PSD_ATT_SYNC()                                                                                           \
     {                                                                                                            \
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                                         \
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTG - 2) * (KG + VG)) : "memory");                            \
         __builtin_amdgcn_s_barrier();                                                                            \
         asm volatile("" ::: "memory");                                                                           \
     }
@@ -110,15 +110,23 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(const bf16_t *__rest
     float m_run = -INFINITY, l_run = 0.f;
     const float sl2 = 1.4426950408889634f / sqrtf((float)DH);   // softmax scale folded into exp2
 
+    // Ring of NSTG tile stages: the fetch of tile t + NSTG - 1 goes out before tile t is computed, so a tile has
+    // NSTG - 1 tile times to arrive (one tile of MFMA work is shorter than a round trip to memory).  Memory
+    // returns in issue order: once at most (NSTG - 2) tiles' worth of this wavefront's fetches are in flight,
+    // the next tile has landed.
+    static_assert(NSTG >= 2 && (NSTG - 1) * (KG + VG) <= 63, "DMA groups in flight must fit the vmcnt counter");
     const int n_tiles = (N + BKV - 1) / BKV;
-    PSD_ATT_DMA(0, 0)
+#pragma unroll
+    for (int p = 0; p < NSTG - 1; ++p) PSD_ATT_DMA(p, p * BKV)
     PSD_ATT_SYNC()
 
+    int stage = 0;
     for (int t = 0; t < n_tiles; ++t) {
-        const int stage = t & 1, k0 = t * BKV;
-        // next tile into the other buffer (every wavefront left it at the last barrier); past the last tile the
-        // fetch is rejected or reads padding and is never consumed
-        PSD_ATT_DMA(stage ^ 1, k0 + BKV)
+        const int k0 = t * BKV;
+        // refill the slot every wavefront left at the last barrier; past the last tile the fetch is rejected or
+        // reads padding and is never consumed
+        const int fill = (stage == 0) ? NSTG - 1 : stage - 1;
+        PSD_ATT_DMA(fill, k0 + (NSTG - 1) * BKV)
         const unsigned char *sk = lds + stage * STAGE, *sv = sk + K_BYTES;
 
         // scores, transposed: acc_s[kt][v] <-> key 32*kt + 8*(v/4) + 4*half + v%4, query lrow
@@ -192,7 +200,9 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(const bf16_t *__rest
             }
         }
         PSD_ATT_SYNC()
+        stage = (stage + 1 == NSTG) ? 0 : stage + 1;
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no fetch may outlive the loop
 #undef PSD_ATT_DMA
 #undef PSD_ATT_SYNC
 
@@ -248,11 +258,12 @@ void launch_transpose_v(const bf16_t *qkv, int ld_qkv, int S, int N, int n_heads
                        n_heads, n_kv_heads, d_head, vT, (int)vt_row_stride(N));
 }
 
-template <int DH, int NW>
+template <int DH, int NW, int NSTG>
 static void launch_att(const bf16_t *qkv, int ld_qkv, const bf16_t *vT, int S, int N, int n_heads, int n_kv_heads, bf16_t *out,
                        hipStream_t st) {
-    constexpr int smem = 2 * (BKV * DH * 2 + DH * BKV * 2);
-    auto kern = attention_kernel<DH, NW>;
+    constexpr int smem = NSTG * (BKV * DH * 2 + DH * BKV * 2);
+    static_assert(smem <= 160 * 1024, "LDS ring exceeds the 160 KB of a CU");
+    auto kern = attention_kernel<DH, NW, NSTG>;
     static bool attr_done = false;
     if (!attr_done) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -262,16 +273,19 @@ static void launch_att(const bf16_t *qkv, int ld_qkv, const bf16_t *vT, int S, i
     hipLaunchKernelGGL(kern, grid, dim3(NW * 64), smem, st, qkv, ld_qkv, vT, (int)vt_row_stride(N), N, n_heads, n_kv_heads, out);
 }
 
+#ifndef PSD_ATT_NSTG
+#define PSD_ATT_NSTG 2   // deeper rings (3, 4 stages) were measured 3-7 % slower: the kernel is not bound by fetch latency
+#endif
 void launch_attention_bf16(const bf16_t *qkv, int ld_qkv, const bf16_t *vT, int S, int N, int n_heads, int n_kv_heads, int d_head,
                            bf16_t *out, hipStream_t st) {
     // 128 queries per workgroup when that still gives two workgroups per CU, else 64
     const int64_t blocks128 = (int64_t)((N + 127) / 128) * n_heads * S;
     const bool small = blocks128 < 512;
     if (d_head == 128) {
-        if (small) launch_att<128, 2>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, st);
-        else launch_att<128, 4>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, st);
+        if (small) launch_att<128, 2, PSD_ATT_NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, st);
+        else launch_att<128, 4, PSD_ATT_NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, st);
     } else {
-        if (small) launch_att<64, 2>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, st);
-        else launch_att<64, 4>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, st);
+        if (small) launch_att<64, 2, PSD_ATT_NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, st);
+        else launch_att<64, 4, PSD_ATT_NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, st);
     }
 }
