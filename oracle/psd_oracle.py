@@ -18,6 +18,14 @@ The transformer itself (RMSNorm, rotary embedding, bidirectional softmax attenti
 optional grouped KV heads, SwiGLU feed-forward) is not described by the paper beyond
 "bidirectional attention"; its layout comes from the benchmark configurations.
 
+Precision: everything is fp64.  The benchmark configurations other than the first are "bf16" models (bf16
+operands, wider accumulation): for those, `operands="bf16"` additionally rounds the INPUTS of every
+contraction (normed activations, rotated queries and keys, values, attention probabilities, attention output,
+SwiGLU output, final hidden rows) to bf16, nearest-even via fp32, while sums, the residual stream, softmax
+and the LM-head reduction stay fp64.  That is the computation a bf16 model defines; without the option the
+oracle is the same network in exact arithmetic, from which any bf16 evaluation of an 8B-parameter shape
+differs by a few 1e-2 in the logits whatever the kernels do.
+
 Pins: every function here is pinned by tests/test_oracle_*.py (closed forms, special cases
 that reduce to library routines, brute force on tiny inputs, the greedy and K=1
 reductions).  Two things the paper does not publish stay "parity unpinned" against the
@@ -79,6 +87,22 @@ def chain_graph(K: int, width: int = 1) -> Graph:
 # ----------------------------------------------------------------------------------------
 
 
+def to_bf16(x: np.ndarray) -> np.ndarray:
+    """Nearest-even rounding to bf16 (8 significant bits) of the fp32 image of x; returned as fp64."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    r = ((u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000).astype(np.uint32)
+    return r.view(np.float32).astype(F64)
+
+
+def _operand(x: np.ndarray, operands: Optional[str]) -> np.ndarray:
+    """x as it enters a contraction: unchanged, or rounded to bf16."""
+    if operands is None:
+        return x
+    if operands == "bf16":
+        return to_bf16(x)
+    raise ValueError(f"operands={operands!r}")
+
+
 def rmsnorm(x: np.ndarray, gain: np.ndarray, eps: float) -> np.ndarray:
     ms = np.mean(x * x, axis=-1, keepdims=True)
     return x / np.sqrt(ms + eps) * gain
@@ -97,18 +121,23 @@ def softmax_rows(s: np.ndarray) -> np.ndarray:
     return e / e.sum(axis=-1, keepdims=True)
 
 
-def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray) -> np.ndarray:
+def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, operands: Optional[str] = None) -> np.ndarray:
     """Bidirectional softmax attention, no mask. q: [N, H, dh]; k, v: [N, Hkv, dh] -> [N, H, dh].
 
-    Query head j reads KV head j // (H / Hkv).
+    Query head j reads KV head j // (H / Hkv).  With operands="bf16" the probabilities enter the second
+    contraction rounded (as exp(s - max), before the division by their exact sum).
     """
     N, H, dh = q.shape
     group = H // k.shape[1]
     out = np.empty_like(q)
     for j in range(H):
         kj, vj = k[:, j // group, :], v[:, j // group, :]
-        p = softmax_rows(q[:, j, :] @ kj.T / np.sqrt(F64(dh)))
-        out[:, j, :] = p @ vj
+        s = q[:, j, :] @ kj.T / np.sqrt(F64(dh))
+        if operands is None:
+            out[:, j, :] = softmax_rows(s) @ vj
+        else:
+            e = np.exp(s - s.max(axis=-1, keepdims=True))
+            out[:, j, :] = (_operand(e, operands) @ vj) / e.sum(axis=-1, keepdims=True)
     return out
 
 
@@ -120,26 +149,29 @@ def _w(a) -> np.ndarray:
     return np.asarray(a, dtype=F64)
 
 
-def layer_forward(h: np.ndarray, lw: dict, shape, cos: np.ndarray, sin: np.ndarray) -> np.ndarray:
+def layer_forward(h: np.ndarray, lw: dict, shape, cos: np.ndarray, sin: np.ndarray,
+                  operands: Optional[str] = None) -> np.ndarray:
     """One pre-norm transformer layer on the residual stream h [N, d]."""
     N = h.shape[0]
     H, Hkv, dh = shape.n_heads, shape.n_kv_heads, shape.d_head
-    a = rmsnorm(h, _w(lw["attn_norm"]), shape.rms_eps)
+    a = _operand(rmsnorm(h, _w(lw["attn_norm"]), shape.rms_eps), operands)
     q = a @ _w(lw["wq"]).T
     k = a @ _w(lw["wk"]).T
     v = a @ _w(lw["wv"]).T
     if lw.get("bq") is not None:
         q, k, v = q + _w(lw["bq"]), k + _w(lw["bk"]), v + _w(lw["bv"])
-    q = rope(q.reshape(N, H, dh), cos, sin)
-    k = rope(k.reshape(N, Hkv, dh), cos, sin)
-    o = attention(q, k, v.reshape(N, Hkv, dh)).reshape(N, H * dh)
+    q = _operand(rope(q.reshape(N, H, dh), cos, sin), operands)
+    k = _operand(rope(k.reshape(N, Hkv, dh), cos, sin), operands)
+    v = _operand(v.reshape(N, Hkv, dh), operands)
+    o = _operand(attention(q, k, v, operands).reshape(N, H * dh), operands)
     h = h + o @ _w(lw["wo"]).T
-    f = rmsnorm(h, _w(lw["ffn_norm"]), shape.rms_eps)
-    h = h + (silu(f @ _w(lw["w_gate"]).T) * (f @ _w(lw["w_up"]).T)) @ _w(lw["w_down"]).T
+    f = _operand(rmsnorm(h, _w(lw["ffn_norm"]), shape.rms_eps), operands)
+    g = _operand(silu(f @ _w(lw["w_gate"]).T) * (f @ _w(lw["w_up"]).T), operands)
+    h = h + g @ _w(lw["w_down"]).T
     return h
 
 
-def forward_hidden(model, tokens: np.ndarray) -> np.ndarray:
+def forward_hidden(model, tokens: np.ndarray, operands: Optional[str] = None) -> np.ndarray:
     """Final-normed hidden states y [N, d] for one sequence (mask positions hold mask_id,
     which has an ordinary embedding row).  Positions are 0..N-1."""
     tokens = np.asarray(tokens)
@@ -147,13 +179,13 @@ def forward_hidden(model, tokens: np.ndarray) -> np.ndarray:
     cos, sin = _w(model.rope_cos[:N]), _w(model.rope_sin[:N])
     h = _w(model.tok_emb[tokens])
     for lw in model.layers:
-        h = layer_forward(h, lw, model.shape, cos, sin)
-    return rmsnorm(h, _w(model.final_norm), model.shape.rms_eps)
+        h = layer_forward(h, lw, model.shape, cos, sin, operands)
+    return _operand(rmsnorm(h, _w(model.final_norm), model.shape.rms_eps), operands)
 
 
-def block_logits(model, tokens: np.ndarray, block_start: int, L: int) -> np.ndarray:
+def block_logits(model, tokens: np.ndarray, block_start: int, L: int, operands: Optional[str] = None) -> np.ndarray:
     """z = logit_scale * y W_lm^T on the block rows, [L, V] (mask column not yet excluded)."""
-    y = forward_hidden(model, tokens)[block_start: block_start + L]
+    y = forward_hidden(model, tokens, operands)[block_start: block_start + L]
     return model.shape.logit_scale * (y @ _w(model.lm_head).T)
 
 
@@ -175,7 +207,7 @@ def top1_confidence(z: np.ndarray, mask_id: int) -> Tuple[np.ndarray, np.ndarray
 
 
 def forward_confidence(model, tokens: np.ndarray, block_start: int, L: int,
-                       return_logits: bool = False):
+                       return_logits: bool = False, operands: Optional[str] = None):
     """(top1 int32 [L], conf fp32 [L]) for the active block of one sequence.
 
     Masked block positions carry the prediction; the others carry the sentinel
@@ -183,7 +215,7 @@ def forward_confidence(model, tokens: np.ndarray, block_start: int, L: int,
     sides take every later decision.
     """
     tokens = np.asarray(tokens)
-    z = block_logits(model, tokens, block_start, L)
+    z = block_logits(model, tokens, block_start, L, operands)
     x_hat, c = top1_confidence(z, model.shape.mask_id)
     blk = tokens[block_start: block_start + L]
     masked = blk == model.shape.mask_id
@@ -387,5 +419,5 @@ def decode(confidence_fn: ConfidenceFn, tokens: np.ndarray, prompt_len: int, L: 
     return x, stats
 
 
-def model_confidence_fn(model) -> ConfidenceFn:
-    return lambda tokens, block_start, L: forward_confidence(model, tokens, block_start, L)
+def model_confidence_fn(model, operands: Optional[str] = None) -> ConfidenceFn:
+    return lambda tokens, block_start, L: forward_confidence(model, tokens, block_start, L, operands=operands)

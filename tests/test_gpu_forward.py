@@ -44,7 +44,15 @@ def _margins(z, mask_id):
     return part[:, -1] - part[:, -2]
 
 
-def _compare(model, host, tokens_list, block_start, L, tol_logits, label):
+def _compare(model, host, tokens_list, block_start, L, tol_logits, label, check=None, calibrate=False):
+    """GPU forward over all of tokens_list in one batch; the oracle runs (and is compared) on the sequences
+    listed in `check` (default: all).
+
+    calibrate=True is for the 4096-wide configurations, where bf16 arithmetic itself cannot hold 2e-2: the
+    logits have a standard deviation of 1.3 there, and the fp64 evaluation of the network with bf16-rounded
+    contraction operands (the oracle's operands="bf16") already differs from exact arithmetic by 5e-2 (2 layers)
+    to 1.3e-1 (32 layers) max-abs.  The tolerance is then taken from the oracle alone: the HIP logits may be at
+    most 1.5x (max-abs) and 1.25x (rms) as far from the exact logits as that bf16-operand evaluation is."""
     import paper_2605_15609_amd as psd
     from tests.gpu_common import to_dev, say
     shape = host.shape
@@ -56,8 +64,18 @@ def _compare(model, host, tokens_list, block_start, L, tol_logits, label):
     top1, conf = top1.cpu().numpy(), conf.cpu().numpy()
     worst, near_ties, wide = 0.0, 0, 0
     for s, t in enumerate(tokens_list):
+        if check is not None and s not in check:
+            continue
         o_top1, o_conf, z = orc.forward_confidence(host, t, block_start, L, return_logits=True)
         err = np.abs(logits[s] - z).max()
+        if calibrate:
+            z_b = orc.block_logits(host, t, block_start, L, operands="bf16")
+            inherent, inherent_rms = np.abs(z_b - z).max(), np.sqrt(np.mean((z_b - z) ** 2))
+            rms = np.sqrt(np.mean((logits[s] - z) ** 2))
+            say(f"[forward] {label} seq {s}: HIP vs exact oracle max-abs {err:.3e} rms {rms:.3e}; bf16-operand oracle vs exact "
+                f"max-abs {inherent:.3e} rms {inherent_rms:.3e}; HIP vs bf16-operand oracle max-abs {np.abs(logits[s] - z_b).max():.3e}")
+            assert rms <= 1.25 * inherent_rms, f"{label}: logits rms error {rms:.3e} > 1.25 x {inherent_rms:.3e}"
+            tol_logits = 1.5 * inherent
         worst = max(worst, err)
         assert err <= tol_logits, f"{label}: logits max-abs error {err:.3e} > {tol_logits}"
         masked = t[block_start: block_start + L] == shape.mask_id
