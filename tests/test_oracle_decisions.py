@@ -401,6 +401,37 @@ def test_speculation_pays_when_predictions_are_stable():
     assert s4.depth_hist[3] == 3
 
 
+def test_hand_worked_chain_trace_fixture():
+    """tests/golden/chain_trace.txt: Alg. 1 worked by hand for a model whose predictions never change (every draft
+    is right).  The oracle's trace must reproduce it iteration by iteration."""
+    import os
+    rows = []
+    with open(os.path.join(os.path.dirname(__file__), "golden", "chain_trace.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                rows.append(line.split())
+    vocab, L = 30, 16
+    fn = pseudo_model(vocab, 3, conf_kind="low", sticky=1.0)
+    tokens = np.full(L, vocab - 1, dtype=np.int32)
+    trace = []
+    _, stats = orc.decode_block(fn, tokens, 0, L, orc.Policy(0.9, 1), orc.chain_graph(4), vocab - 1, trace=trace)
+    got, masks, i = [], L, 0
+    while i < len(trace):
+        assert trace[i][0] == "commit"
+        n1 = len(trace[i][1])
+        if i + 1 < len(trace) and trace[i + 1][0] == "verify":
+            _, _, depth, n_post, _ = trace[i + 1]
+            got.append([str(len(got) + 1), str(masks), str(n1), str(depth), str(n_post), "2"])
+            masks -= n1 + depth + n_post
+            i += 2
+        else:
+            got.append([str(len(got) + 1), str(masks), str(n1), "-", "-", "1"])
+            masks -= n1
+            i += 1
+    assert got == rows
+    assert masks == 0 and stats.tokens == 16 and stats.invocations == 7
+
+
 def test_blocks_decode_left_to_right_and_later_blocks_stay_masked():
     vocab, L = 30, 8
     seen = []

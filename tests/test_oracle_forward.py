@@ -252,3 +252,80 @@ def test_forward_confidence_sentinels_and_logit_scale():
     model2 = dataclasses.replace(model, shape=dataclasses.replace(shape, logit_scale=4.0))
     top1b, confb = orc.forward_confidence(model2, tokens, 16, 32)
     assert (top1b == top1).all() and (confb[live] > conf[live]).all()
+
+
+# ---------------------------------------------------------------- bf16-operand evaluation
+
+
+def test_to_bf16_is_the_library_rounding_including_ties():
+    rng = np.random.default_rng(5)
+    x = np.concatenate([rng.standard_normal(4096) * 10.0 ** rng.integers(-6, 6, size=4096),
+                        # exact halfway cases between neighbouring bf16 values (ties go to the even significand)
+                        np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -(2.0 + 2.0 ** -7), 0.5 + 2.0 ** -9, 0.0, -0.0])])
+    ref = torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    got = orc.to_bf16(x)
+    assert np.array_equal(got, ref)
+    assert np.array_equal(orc.to_bf16(got), got)   # idempotent
+
+
+def _torch_bf16_operand_layer(h, lw, shape, cos, sin):
+    """The same layer with torch: every contraction operand cast to bfloat16 by the library, products and sums
+    in float64."""
+    def op(t):
+        return t.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+
+    def w(name):
+        return torch.from_numpy(np.asarray(lw[name], dtype=np.float64))
+
+    N, H, Hkv, dh = h.shape[0], shape.n_heads, shape.n_kv_heads, shape.d_head
+    tcos, tsin = torch.from_numpy(cos)[:, None, :], torch.from_numpy(sin)[:, None, :]
+
+    def rot(x):
+        x1, x2 = x[..., : dh // 2], x[..., dh // 2:]
+        return torch.cat([x1 * tcos - x2 * tsin, x2 * tcos + x1 * tsin], dim=-1)
+
+    a = op(torch.nn.functional.rms_norm(h, (h.shape[1],), w("attn_norm"), eps=shape.rms_eps))
+    q, k, v = a @ w("wq").T, a @ w("wk").T, a @ w("wv").T
+    if lw.get("bq") is not None:
+        q, k, v = q + w("bq"), k + w("bk"), v + w("bv")
+    q, k, v = op(rot(q.reshape(N, H, dh))), op(rot(k.reshape(N, Hkv, dh))), op(v.reshape(N, Hkv, dh))
+    o = torch.empty(N, H, dh, dtype=torch.float64)
+    for j in range(H):
+        s = q[:, j] @ k[:, j // (H // Hkv)].T / np.sqrt(dh)
+        e = torch.exp(s - s.max(dim=-1, keepdim=True).values)
+        o[:, j] = (op(e) @ v[:, j // (H // Hkv)]) / e.sum(dim=-1, keepdim=True)
+    h = h + op(o.reshape(N, H * dh)) @ w("wo").T
+    f = op(torch.nn.functional.rms_norm(h, (h.shape[1],), w("ffn_norm"), eps=shape.rms_eps))
+    g = op(torch.nn.functional.silu(f @ w("w_gate").T) * (f @ w("w_up").T))
+    return h + g @ w("w_down").T
+
+
+@pytest.mark.parametrize("shape", [TINY, GQA], ids=["mha", "gqa-bias"])
+def test_bf16_operand_layer_rounds_exactly_the_contraction_inputs(shape):
+    """operands="bf16": each contraction input goes through the bf16 rounding and nothing else does (checked
+    against a torch evaluation that casts the same operands with the library's bfloat16)."""
+    N = 11
+    model = inp.draw_model(shape, N)
+    rng = np.random.default_rng(3)
+    h = rng.standard_normal((N, shape.d_model))
+    cos, sin = np.asarray(model.rope_cos[:N], dtype=np.float64), np.asarray(model.rope_sin[:N], dtype=np.float64)
+    got = orc.layer_forward(h, model.layers[0], shape, cos, sin, operands="bf16")
+    ref = _torch_bf16_operand_layer(torch.from_numpy(h), model.layers[0], shape, cos, sin).numpy()
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-12)
+    exact = orc.layer_forward(h, model.layers[0], shape, cos, sin)
+    dev = np.abs(got - exact).max()
+    assert 0 < dev < 2e-2 * np.abs(exact).max()   # it does round, and by about 2^-9 relative
+
+
+def test_bf16_operand_logits_round_the_final_hidden_rows_and_stay_close_to_exact():
+    shape = GQA
+    N, bs, L = 12, 4, 8
+    model = inp.draw_model(shape, N)
+    t = _tokens(shape, N, 8)
+    y_exact = orc.forward_hidden(model, t)
+    y_b = orc.forward_hidden(model, t, operands="bf16")
+    assert np.array_equal(orc.to_bf16(y_b), y_b)            # the LM-head operand is bf16
+    z, z_b = orc.block_logits(model, t, bs, L), orc.block_logits(model, t, bs, L, operands="bf16")
+    np.testing.assert_allclose(z_b, y_b[bs: bs + L] @ np.asarray(model.lm_head, dtype=np.float64).T, atol=1e-12)
+    rel = np.abs(z_b - z).max() / np.abs(z).max()
+    assert 0 < rel < 0.05 and np.abs(y_b - y_exact).max() < 0.05
