@@ -44,57 +44,80 @@ def _margins(z, mask_id):
     return part[:, -1] - part[:, -2]
 
 
-def _compare(model, host, tokens_list, block_start, L, tol_logits, label, check=None, calibrate=False):
-    """GPU forward over all of tokens_list in one batch; the oracle runs (and is compared) on the sequences
-    listed in `check` (default: all).
+def oracle_reference(host, t, block_start, L, calibrate=False):
+    """What the oracle says about one sequence: (top1, conf, exact logits, bf16-operand logits or None)."""
+    o_top1, o_conf, z = orc.forward_confidence(host, t, block_start, L, return_logits=True)
+    z_b = orc.block_logits(host, t, block_start, L, operands="bf16") if calibrate else None
+    return o_top1, o_conf, z, z_b
 
-    calibrate=True is for the 4096-wide configurations, where bf16 arithmetic itself cannot hold 2e-2: the
-    logits have a standard deviation of 1.3 there, and the fp64 evaluation of the network with bf16-rounded
-    contraction operands (the oracle's operands="bf16") already differs from exact arithmetic by 5e-2 (2 layers)
-    to 1.3e-1 (32 layers) max-abs.  The tolerance is then taken from the oracle alone: the HIP logits may be at
-    most 1.5x (max-abs) and 1.25x (rms) as far from the exact logits as that bf16-operand evaluation is."""
+
+def check_sequence(ref, logits, top1, conf, t, mask_id, block_start, L, tol_logits, label):
+    """One sequence's HIP outputs (logits [L, V], top1 [L], conf [L]) against oracle_reference's.  Returns
+    (max-abs logit error, tolerance used, near-tie rows, mismatches outside near-ties but inside the logit band).
+
+    With bf16-operand logits in `ref` the tolerance is calibrated by the oracle alone.  That is for the 4096-wide
+    configurations, where bf16 arithmetic itself cannot hold 2e-2: the logits have a standard deviation of 1.3
+    there, and the fp64 evaluation of the network with bf16-rounded contraction operands (the oracle's
+    operands="bf16") already differs from exact arithmetic by 5e-2 (2 layers) to 1.3e-1 (32 layers) max-abs.  The
+    HIP logits may then be at most 1.5x (max-abs) and 1.25x (rms) as far from the exact logits as that
+    bf16-operand evaluation is."""
+    from tests.gpu_common import say
+    o_top1, o_conf, z, z_b = ref
+    err = np.abs(logits - z).max()
+    if z_b is not None:
+        inherent, inherent_rms = np.abs(z_b - z).max(), np.sqrt(np.mean((z_b - z) ** 2))
+        rms = np.sqrt(np.mean((logits - z) ** 2))
+        say(f"[forward] {label}: HIP vs exact oracle max-abs {err:.3e} rms {rms:.3e}; bf16-operand oracle vs exact "
+            f"max-abs {inherent:.3e} rms {inherent_rms:.3e}; HIP vs bf16-operand oracle max-abs {np.abs(logits - z_b).max():.3e}")
+        assert rms <= 1.25 * inherent_rms, f"{label}: logits rms error {rms:.3e} > 1.25 x {inherent_rms:.3e}"
+        tol_logits = 1.5 * inherent
+    assert err <= tol_logits, f"{label}: logits max-abs error {err:.3e} > {tol_logits}"
+    blk = t[block_start: block_start + L]
+    masked = blk == mask_id
+    # sentinels
+    assert (top1[~masked] == blk[~masked]).all()
+    assert (conf[~masked] == -1.0).all()
+    margin = _margins(z, mask_id)
+    near_ties = int((masked & (margin < 1e-3)).sum())
+    # a mismatch must stay within the band that the logit tolerance implies (2 * tol below the top)
+    differ = masked & (top1 != o_top1)
+    wide = 0
+    for j in np.nonzero(differ)[0]:
+        gap = z[j, o_top1[j]] - z[j, top1[j]]
+        assert gap <= 2 * tol_logits, f"{label}: top-1 mismatch with oracle logit gap {gap:.3e}"
+        wide += int(margin[j] >= 1e-3)
+    safe = masked & ~differ
+    assert (top1[masked] != mask_id).all()
+    rel = np.abs(conf[safe] / o_conf[safe] - 1.0).max() if safe.any() else 0.0
+    assert rel <= np.expm1(2 * tol_logits) + 1e-5, f"{label}: confidence off by {rel:.3e}"
+    return err, tol_logits, near_ties, wide
+
+
+def hip_forward(model, tokens_list, block_start, L):
+    """(logits [S, L, V], top1 [S, L], conf [S, L]) of one batched HIP forward, on the host."""
     import paper_2605_15609_amd as psd
-    from tests.gpu_common import to_dev, say
-    shape = host.shape
-    tokens = np.stack(tokens_list)
-    d_tokens = to_dev(tokens)
+    from tests.gpu_common import to_dev
+    d_tokens = to_dev(np.stack(tokens_list))
     logits = psd.psd_forward_logits(model, d_tokens, block_start, L).cpu().numpy().reshape(len(tokens_list), L, -1)
     top1, conf = psd.psd_forward_confidence(model, d_tokens, block_start, L)
     torch.cuda.synchronize()
-    top1, conf = top1.cpu().numpy(), conf.cpu().numpy()
-    worst, near_ties, wide = 0.0, 0, 0
+    return logits, top1.cpu().numpy(), conf.cpu().numpy()
+
+
+def _compare(model, host, tokens_list, block_start, L, tol_logits, label, check=None, calibrate=False):
+    """GPU forward over all of tokens_list in one batch; the oracle runs (and is compared) on the sequences
+    listed in `check` (default: all)."""
+    from tests.gpu_common import say
+    logits, top1, conf = hip_forward(model, tokens_list, block_start, L)
+    worst, near_ties, wide, tol = 0.0, 0, 0, tol_logits
     for s, t in enumerate(tokens_list):
         if check is not None and s not in check:
             continue
-        o_top1, o_conf, z = orc.forward_confidence(host, t, block_start, L, return_logits=True)
-        err = np.abs(logits[s] - z).max()
-        if calibrate:
-            z_b = orc.block_logits(host, t, block_start, L, operands="bf16")
-            inherent, inherent_rms = np.abs(z_b - z).max(), np.sqrt(np.mean((z_b - z) ** 2))
-            rms = np.sqrt(np.mean((logits[s] - z) ** 2))
-            say(f"[forward] {label} seq {s}: HIP vs exact oracle max-abs {err:.3e} rms {rms:.3e}; bf16-operand oracle vs exact "
-                f"max-abs {inherent:.3e} rms {inherent_rms:.3e}; HIP vs bf16-operand oracle max-abs {np.abs(logits[s] - z_b).max():.3e}")
-            assert rms <= 1.25 * inherent_rms, f"{label}: logits rms error {rms:.3e} > 1.25 x {inherent_rms:.3e}"
-            tol_logits = 1.5 * inherent
-        worst = max(worst, err)
-        assert err <= tol_logits, f"{label}: logits max-abs error {err:.3e} > {tol_logits}"
-        masked = t[block_start: block_start + L] == shape.mask_id
-        # sentinels
-        assert (top1[s][~masked] == t[block_start: block_start + L][~masked]).all()
-        assert (conf[s][~masked] == -1.0).all()
-        margin = _margins(z, shape.mask_id)
-        near_ties += int((masked & (margin < 1e-3)).sum())
-        # a mismatch must stay within the band that the logit tolerance implies (2 * tol below the top)
-        differ = masked & (top1[s] != o_top1)
-        for j in np.nonzero(differ)[0]:
-            gap = z[j, o_top1[j]] - z[j, top1[s][j]]
-            assert gap <= 2 * tol_logits, f"{label}: top-1 mismatch with oracle logit gap {gap:.3e}"
-            wide += int(margin[j] >= 1e-3)
-        safe = masked & ~differ
-        assert (top1[s][masked] != shape.mask_id).all()
-        rel = np.abs(conf[s][safe] / o_conf[safe] - 1.0).max() if safe.any() else 0.0
-        assert rel <= np.expm1(2 * tol_logits) + 1e-5, f"{label}: confidence off by {rel:.3e}"
-    say(f"[forward] {label}: logits max-abs err {worst:.3e} (tol {tol_logits}), near-tie rows (margin < 1e-3): {near_ties}, "
+        ref = oracle_reference(host, t, block_start, L, calibrate)
+        err, tol, nt, wd = check_sequence(ref, logits[s], top1[s], conf[s], t, host.shape.mask_id, block_start, L, tol_logits,
+                                          f"{label} seq {s}")
+        worst, near_ties, wide = max(worst, err), near_ties + nt, wide + wd
+    say(f"[forward] {label}: logits max-abs err {worst:.3e} (tol {tol:.3e}), near-tie rows (margin < 1e-3): {near_ties}, "
         f"mismatches beyond that but inside the logit band: {wide}")
     return worst
 

@@ -1,14 +1,18 @@
-"""Config 3 at its full size (32 layers, d_model 4096, vocabulary 126 464), in the launch configuration the
-benchmark times: the stage-1 call (1 x 512 tokens) and the verification call (4 drafts x 512 tokens) against
-the fp64 oracle over the full depth.  At this width the logit tolerance is calibrated by the oracle itself
-(see _compare in test_gpu_forward.py): no bf16 evaluation of this network stays within 2e-2 of exact arithmetic.  The oracle needs about 12 s per
-sequence-forward on 16 host cores and the fp32 host copy of the weights about 32 GB, so the verification batch
-is compared on its first and last draft only (sampled outputs; every draft runs through the same kernels)."""
+"""The 7B/8B-parameter configurations at their full size, in the launch configurations the benchmark times,
+against the fp64 oracle over the full depth: config 3 (32 layers, d_model 4096, V 126 464; stage-1 call of
+1 x 512 tokens and verification call of 4 x 512), config 4 (28 layers, grouped KV heads with QKV bias,
+V 152 064; 1 x 1024 and 6 x 1024) and config 5 (config 3's model; 16 x 1280 and 128 x 1280 tokens, block 64).
+
+The oracle needs 12-35 s per sequence-forward on 16 host cores and the fp32 host copy of the weights about
+32 GB, so each batch is compared on sampled sequences only (every sequence runs through the same kernels), and
+the same sequence sits in both the stage-1-shaped and the verification-shaped batch, so that one oracle
+evaluation checks both launch configurations.  At these widths the logit tolerance is calibrated by the oracle
+itself (check_sequence in test_gpu_forward.py): no bf16 evaluation of these networks stays within 2e-2 of exact
+arithmetic."""
 import time
 
 import numpy as np
 import pytest
-import torch
 
 import psd_inputs as inp
 from oracle import psd_oracle as orc
@@ -16,10 +20,23 @@ from oracle import psd_oracle as orc
 pytestmark = pytest.mark.gpu
 
 
-def test_config3_full_depth_stage1_and_verify():
+def _state(shape, N, block_start, L, seed, n_committed):
+    rng = np.random.default_rng(seed)
+    t = np.full(N, shape.mask_id, dtype=np.int32)
+    t[:block_start] = inp.draw_prompt(shape.vocab, block_start, seed)
+    idx = rng.choice(L, size=n_committed, replace=False)
+    t[block_start + idx] = rng.integers(0, shape.vocab - 1, size=n_committed)
+    return t
+
+
+def _need_memory():
     import psutil
     if psutil.virtual_memory().available < 60 * 2 ** 30:
-        pytest.skip("needs about 40 GB of free host memory for the fp32 host copy of an 8B-parameter model")
+        pytest.skip("needs about 40 GB of free host memory for the fp32 host copy of a 7-8B-parameter model")
+
+
+def test_config3_full_depth_stage1_and_verify():
+    _need_memory()
     import paper_2605_15609_amd as psd
     from tests.gpu_common import say
     from tests.test_gpu_forward import _compare
@@ -27,9 +44,8 @@ def test_config3_full_depth_stage1_and_verify():
     shape, N, P, L, K = w.shape, w.seq_len, w.prompt_len, w.block_len, w.n_drafts
     t0 = time.perf_counter()
     host = inp.draw_model(shape, N, threads=16)
-    say(f"[full-size] host model drawn in {time.perf_counter() - t0:.0f} s")
     model = psd.Model.from_host(host)
-    say(f"[full-size] uploaded after {time.perf_counter() - t0:.0f} s")
+    say(f"[full-size] config 3 drawn and uploaded after {time.perf_counter() - t0:.0f} s")
     tokens = inp.initial_state(w)[0]
     _compare(model, host, [tokens], P, L, 2e-2, "cfg3-full/stage-1", calibrate=True)
     say(f"[full-size] stage-1 compared after {time.perf_counter() - t0:.0f} s")
@@ -40,7 +56,36 @@ def test_config3_full_depth_stage1_and_verify():
     sigma, m, drafts = orc.build_drafts(committed, P, L, top1, conf, graph, shape.mask_id)
     assert m >= K - 1, "the first block leaves enough masks for every draft to differ"
     say(f"[full-size] drafts built after {time.perf_counter() - t0:.0f} s")
-    _compare(model, host, [np.asarray(d, dtype=np.int32) for d in drafts], P, L, 2e-2, "cfg3-full/verify", check=(0, K - 1), calibrate=True)
+    _compare(model, host, [np.asarray(d, dtype=np.int32) for d in drafts], P, L, 2e-2, "cfg3-full/verify", check=(0, K - 1),
+             calibrate=True)
     say(f"[full-size] verification compared after {time.perf_counter() - t0:.0f} s")
     model.close()
-    del host
+
+
+@pytest.mark.parametrize("cfg", [4, 5])
+def test_full_depth_both_launch_shapes_on_a_shared_sequence(cfg):
+    _need_memory()
+    import paper_2605_15609_amd as psd
+    from tests.gpu_common import say
+    from tests.test_gpu_forward import check_sequence, hip_forward, oracle_reference
+    w = inp.WORKLOADS[cfg]
+    shape, N, L, K, B = w.shape, w.seq_len, w.block_len, w.n_drafts, w.batch
+    bs = w.prompt_len + L            # second block: one finished block precedes it
+    t0 = time.perf_counter()
+    host = inp.draw_model(shape, N, threads=16)
+    model = psd.Model.from_host(host)
+    say(f"[full-size] config {cfg} drawn and uploaded after {time.perf_counter() - t0:.0f} s")
+    # seeded states with the block partly committed; sequence 0 of both batches is the same
+    states = [_state(shape, N, bs, L, 100 + i, (7 * i + 5) % L) for i in range(B * K)]
+    for t in states:
+        t[w.prompt_len: bs] = inp.draw_prompt(shape.vocab, L, 999)     # the finished first block
+    ref = oracle_reference(host, states[0], bs, L, calibrate=True)
+    say(f"[full-size] oracle evaluated sequence 0 after {time.perf_counter() - t0:.0f} s")
+    for label, batch in ((f"cfg{cfg}-full/stage-1 shape ({B} x {N})", states[:B]),
+                         (f"cfg{cfg}-full/verify shape ({B * K} x {N})", states)):
+        logits, top1, conf = hip_forward(model, batch, bs, L)
+        err, tol, near, wide = check_sequence(ref, logits[0], top1[0], conf[0], states[0], shape.mask_id, bs, L, 2e-2, label)
+        say(f"[full-size] {label}: logits max-abs err {err:.3e} (tol {tol:.3e}), near-ties {near}, inside the band {wide}; "
+            f"{time.perf_counter() - t0:.0f} s")
+        del logits
+    model.close()
