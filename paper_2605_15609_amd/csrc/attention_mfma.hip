@@ -35,7 +35,7 @@ typedef __attribute__((address_space(3))) void lds_void;
 // NW wavefronts (32 queries each) per workgroup; ld_qkv / ld_vt = row strides (elements) of qkv and of vT,
 // whose rows hold N rounded up to 64 keys (tail zero)
 template <int DH, int NW, int NSTG>
-__global__ __launch_bounds__(NW * 64) void attention_kernel(const bf16_t *__restrict__ qkv, int ld_qkv,
+__global__ __launch_bounds__(NW * 64, 2) void attention_kernel(const bf16_t *__restrict__ qkv, int ld_qkv,
                                                             const bf16_t *__restrict__ vT, int ld_vt, int N, int n_heads,
                                                             int n_kv_heads, bf16_t *__restrict__ out) {
     constexpr int KROW = DH * 2;                 // bytes per K row in LDS
@@ -49,6 +49,10 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(const bf16_t *__rest
     constexpr int KG = BKV / KRPI / NW;          // K-tile DMA instructions per wavefront
     constexpr int VG = DH / 8 / NW;              // V^T-tile DMA instructions per wavefront (8 rows each)
     extern __shared__ __align__(16) unsigned char lds[];
+    // Swizzle key of a K row.  The 64 LDS banks span 256 bytes: 128-byte rows (d_head 64) alternate between the
+    // two halves, so rows r and r+1 may share a chunk slot and the key is (r >> 1) & 7 as in the GEMM tiles;
+    // 256-byte rows (d_head 128) all start at bank 0 and need 16 different slots for 16 consecutive rows.
+    auto kkey = [](int r) { return DH == 128 ? (r & 15) : ((r >> 1) & 7); };
 
     const int q0 = blockIdx.x * (32 * NW), head = blockIdx.y, s = blockIdx.z;
     const int kvh = head / (n_heads / n_kv_heads);
@@ -72,7 +76,7 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(const bf16_t *__rest
 
     // K and V^T tiles go global -> LDS directly (buffer_load ... lds), 1 KB per instruction, with the XOR
     // swizzle applied on the global side: the lane that lands at (row, slot) fetches chunk slot ^ key(row),
-    // key(row) = (row >> 1) & 7.  Row groups are dealt round-robin to the wavefronts.  Keys past the end of
+    // key(row) = kkey(row) for K rows and (row >> 1) & 7 for the 128-byte V^T rows.  Row groups are dealt round-robin to the wavefronts.  Keys past the end of
     // the sequence are rejected by the descriptor (K) or read the zero padding of vT.
     const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<bf16_t *>(seq) + (n_heads + kvh) * DH, 0, (int)(((int64_t)N * row_w - (n_heads + kvh) * DH) * 2), 0x00020000);
@@ -84,7 +88,7 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(const bf16_t *__rest
         unsigned char *sk_ = lds + (stage) * STAGE + wave * 1024, *sv_ = lds + (stage) * STAGE + K_BYTES + wave * 1024; \
         _Pragma("unroll") for (int j = 0; j < KG; ++j) {                                                         \
             const int row = (j * NW + wave) * KRPI + lane / KLPR;                                                \
-            const int voff = (lane / KLPR) * row_w * 2 + (((lane % KLPR) ^ ((row >> 1) & 7)) << 4);              \
+            const int voff = (lane / KLPR) * row_w * 2 + (((lane % KLPR) ^ kkey(row)) << 4);                         \
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_void *)(sk_ + j * (NW * 1024)), 16, voff,          \
                                                      (((k0) + (j * NW + wave) * KRPI) * row_w) * 2, 0, 0);        \
         }                                                                                                        \
@@ -139,7 +143,7 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(const bf16_t *__rest
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 const int c = ks * 2 + lhalf;
-                const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(sk + r * KROW + ((c ^ ((r >> 1) & 7)) << 4));
+                const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(sk + r * KROW + ((c ^ kkey(r)) << 4));
                 acc_s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc_s[kt], 0, 0, 0);
             }
         }
