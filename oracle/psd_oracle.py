@@ -16,7 +16,9 @@ procedure itself, step by step, in the paper's order and notation:
 
 The transformer itself (RMSNorm, rotary embedding, bidirectional softmax attention with
 optional grouped KV heads, SwiGLU feed-forward) is not described by the paper beyond
-"bidirectional attention"; its layout comes from the benchmark configurations.
+"bidirectional attention"; its layout comes from the benchmark configurations.  One model
+family of the paper (App. A) uses context-causal block attention instead -- full attention
+inside a block, causal across blocks -- which `block_causal` selects; PSD itself is unchanged.
 
 Precision: everything is fp64.  The benchmark configurations other than the first are "bf16" models (bf16
 operands, wider accumulation): for those, `operands="bf16"` additionally rounds the INPUTS of every
@@ -121,8 +123,18 @@ def softmax_rows(s: np.ndarray) -> np.ndarray:
     return e / e.sum(axis=-1, keepdims=True)
 
 
-def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, operands: Optional[str] = None) -> np.ndarray:
-    """Bidirectional softmax attention, no mask. q: [N, H, dh]; k, v: [N, Hkv, dh] -> [N, H, dh].
+def block_causal_visibility(N: int, L: int) -> np.ndarray:
+    """visible[i, j] for context-causal block attention (App. A, the block-diffusion model family): position i
+    sees every position of its own block of L (full attention inside the block) and of all earlier blocks
+    (causal across blocks), and nothing later.  Blocks are [0, L), [L, 2L), ... from the start of the sequence."""
+    blk = np.arange(N) // L
+    return blk[None, :] <= blk[:, None]
+
+
+def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, operands: Optional[str] = None,
+              visible: Optional[np.ndarray] = None) -> np.ndarray:
+    """Softmax attention. q: [N, H, dh]; k, v: [N, Hkv, dh] -> [N, H, dh].  Bidirectional (every query sees
+    every key) unless `visible` [N, N] says which keys j query i may see.
 
     Query head j reads KV head j // (H / Hkv).  With operands="bf16" the probabilities enter the second
     contraction rounded (as exp(s - max), before the division by their exact sum).
@@ -133,6 +145,8 @@ def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, operands: Optional[st
     for j in range(H):
         kj, vj = k[:, j // group, :], v[:, j // group, :]
         s = q[:, j, :] @ kj.T / np.sqrt(F64(dh))
+        if visible is not None:
+            s = np.where(visible, s, -np.inf)
         if operands is None:
             out[:, j, :] = softmax_rows(s) @ vj
         else:
@@ -150,7 +164,7 @@ def _w(a) -> np.ndarray:
 
 
 def layer_forward(h: np.ndarray, lw: dict, shape, cos: np.ndarray, sin: np.ndarray,
-                  operands: Optional[str] = None) -> np.ndarray:
+                  operands: Optional[str] = None, visible: Optional[np.ndarray] = None) -> np.ndarray:
     """One pre-norm transformer layer on the residual stream h [N, d]."""
     N = h.shape[0]
     H, Hkv, dh = shape.n_heads, shape.n_kv_heads, shape.d_head
@@ -163,7 +177,7 @@ def layer_forward(h: np.ndarray, lw: dict, shape, cos: np.ndarray, sin: np.ndarr
     q = _operand(rope(q.reshape(N, H, dh), cos, sin), operands)
     k = _operand(rope(k.reshape(N, Hkv, dh), cos, sin), operands)
     v = _operand(v.reshape(N, Hkv, dh), operands)
-    o = _operand(attention(q, k, v, operands).reshape(N, H * dh), operands)
+    o = _operand(attention(q, k, v, operands, visible).reshape(N, H * dh), operands)
     h = h + o @ _w(lw["wo"]).T
     f = _operand(rmsnorm(h, _w(lw["ffn_norm"]), shape.rms_eps), operands)
     g = _operand(silu(f @ _w(lw["w_gate"]).T) * (f @ _w(lw["w_up"]).T), operands)
@@ -171,21 +185,28 @@ def layer_forward(h: np.ndarray, lw: dict, shape, cos: np.ndarray, sin: np.ndarr
     return h
 
 
-def forward_hidden(model, tokens: np.ndarray, operands: Optional[str] = None) -> np.ndarray:
+def forward_hidden(model, tokens: np.ndarray, operands: Optional[str] = None,
+                   block_causal: Optional[int] = None) -> np.ndarray:
     """Final-normed hidden states y [N, d] for one sequence (mask positions hold mask_id,
-    which has an ordinary embedding row).  Positions are 0..N-1."""
+    which has an ordinary embedding row).  Positions are 0..N-1.  block_causal = L switches the
+    attention of every layer from bidirectional to context-causal blocks of L."""
     tokens = np.asarray(tokens)
     N = tokens.shape[0]
     cos, sin = _w(model.rope_cos[:N]), _w(model.rope_sin[:N])
     h = _w(model.tok_emb[tokens])
+    visible = None if block_causal is None else block_causal_visibility(N, block_causal)
     for lw in model.layers:
-        h = layer_forward(h, lw, model.shape, cos, sin, operands)
+        h = layer_forward(h, lw, model.shape, cos, sin, operands, visible)
     return _operand(rmsnorm(h, _w(model.final_norm), model.shape.rms_eps), operands)
 
 
-def block_logits(model, tokens: np.ndarray, block_start: int, L: int, operands: Optional[str] = None) -> np.ndarray:
-    """z = logit_scale * y W_lm^T on the block rows, [L, V] (mask column not yet excluded)."""
-    y = forward_hidden(model, tokens, operands)[block_start: block_start + L]
+def block_logits(model, tokens: np.ndarray, block_start: int, L: int, operands: Optional[str] = None,
+                 block_causal: bool = False) -> np.ndarray:
+    """z = logit_scale * y W_lm^T on the block rows, [L, V] (mask column not yet excluded).  block_causal:
+    context-causal block attention with the decoding block length L (block_start a multiple of L)."""
+    if block_causal and block_start % L:
+        raise ValueError("context-causal blocks are aligned to multiples of the block length")
+    y = forward_hidden(model, tokens, operands, L if block_causal else None)[block_start: block_start + L]
     return model.shape.logit_scale * (y @ _w(model.lm_head).T)
 
 
@@ -207,7 +228,7 @@ def top1_confidence(z: np.ndarray, mask_id: int) -> Tuple[np.ndarray, np.ndarray
 
 
 def forward_confidence(model, tokens: np.ndarray, block_start: int, L: int,
-                       return_logits: bool = False, operands: Optional[str] = None):
+                       return_logits: bool = False, operands: Optional[str] = None, block_causal: bool = False):
     """(top1 int32 [L], conf fp32 [L]) for the active block of one sequence.
 
     Masked block positions carry the prediction; the others carry the sentinel
@@ -215,7 +236,7 @@ def forward_confidence(model, tokens: np.ndarray, block_start: int, L: int,
     sides take every later decision.
     """
     tokens = np.asarray(tokens)
-    z = block_logits(model, tokens, block_start, L, operands)
+    z = block_logits(model, tokens, block_start, L, operands, block_causal)
     x_hat, c = top1_confidence(z, model.shape.mask_id)
     blk = tokens[block_start: block_start + L]
     masked = blk == model.shape.mask_id
@@ -419,5 +440,6 @@ def decode(confidence_fn: ConfidenceFn, tokens: np.ndarray, prompt_len: int, L: 
     return x, stats
 
 
-def model_confidence_fn(model, operands: Optional[str] = None) -> ConfidenceFn:
-    return lambda tokens, block_start, L: forward_confidence(model, tokens, block_start, L, operands=operands)
+def model_confidence_fn(model, operands: Optional[str] = None, block_causal: bool = False) -> ConfidenceFn:
+    return lambda tokens, block_start, L: forward_confidence(model, tokens, block_start, L, operands=operands,
+                                                             block_causal=block_causal)

@@ -329,3 +329,59 @@ def test_bf16_operand_logits_round_the_final_hidden_rows_and_stay_close_to_exact
     np.testing.assert_allclose(z_b, y_b[bs: bs + L] @ np.asarray(model.lm_head, dtype=np.float64).T, atol=1e-12)
     rel = np.abs(z_b - z).max() / np.abs(z).max()
     assert 0 < rel < 0.05 and np.abs(y_b - y_exact).max() < 0.05
+
+
+# ---------------------------------------------------------------- context-causal block attention (App. A)
+
+
+def test_block_causal_attention_special_cases_and_library_mask():
+    rng = np.random.default_rng(21)
+    N, H, Hkv, dh = 24, 4, 2, 16
+    q, k, v = rng.standard_normal((N, H, dh)), rng.standard_normal((N, Hkv, dh)), rng.standard_normal((N, Hkv, dh))
+    tq, tk, tv = (torch.from_numpy(a).permute(1, 0, 2)[None] for a in (q, k, v))
+    sdpa = torch.nn.functional.scaled_dot_product_attention
+    # blocks of one token: ordinary causal attention
+    ref = sdpa(tq, tk, tv, is_causal=True, enable_gqa=True)[0].permute(1, 0, 2).numpy()
+    np.testing.assert_allclose(orc.attention(q, k, v, visible=orc.block_causal_visibility(N, 1)), ref, atol=1e-12)
+    # one block covering everything: bidirectional
+    np.testing.assert_allclose(orc.attention(q, k, v, visible=orc.block_causal_visibility(N, N)), orc.attention(q, k, v),
+                               atol=1e-14)
+    # any block length: the library's attention under the mask written out from the definition
+    for L in (4, 8, 12):
+        vis = np.array([[(j // L) <= (i // L) for j in range(N)] for i in range(N)])
+        assert np.array_equal(orc.block_causal_visibility(N, L), vis)
+        ref = sdpa(tq, tk, tv, attn_mask=torch.from_numpy(vis), enable_gqa=True)[0].permute(1, 0, 2).numpy()
+        np.testing.assert_allclose(orc.attention(q, k, v, visible=vis), ref, atol=1e-12)
+
+
+@pytest.mark.parametrize("shape", [TINY, GQA], ids=["llama-mha", "qwen2-gqa-bias"])
+def test_block_causal_forward_matches_hf_stack_with_the_same_mask(shape):
+    N, L = 24, 8
+    model = inp.draw_model(shape, N)
+    hf = _hf_model(shape, model)
+    t = _tokens(shape, N, 17)
+    vis = orc.block_causal_visibility(N, L)
+    mask = torch.where(torch.from_numpy(vis), 0.0, float("-inf")).to(torch.float32)[None, None]
+    with torch.no_grad():
+        ref = hf(input_ids=torch.from_numpy(t.astype(np.int64))[None], attention_mask=mask).last_hidden_state[0].numpy()
+    np.testing.assert_allclose(orc.forward_hidden(model, t, block_causal=L), ref, rtol=0, atol=2e-5)
+
+
+def test_block_causal_prefix_is_independent_of_what_follows():
+    """What makes a prefix KV cache exact: the hidden states of finished blocks depend on nothing after them,
+    and the active block depends on later positions not at all."""
+    shape, N, L = GQA, 32, 8
+    model = inp.draw_model(shape, N)
+    t = _tokens(shape, N, 23)
+    y = orc.forward_hidden(model, t, block_causal=L)
+    t2 = t.copy()
+    t2[2 * L:] = (t2[2 * L:] + 7) % (shape.vocab - 1)            # rewrite blocks 2 and 3
+    y2 = orc.forward_hidden(model, t2, block_causal=L)
+    np.testing.assert_allclose(y2[: 2 * L], y[: 2 * L], atol=1e-13)
+    assert np.abs(y2[2 * L:] - y[2 * L:]).max() > 1e-3
+    # truncating the sequence after a block changes nothing before the cut
+    np.testing.assert_allclose(orc.forward_hidden(model, t[: 3 * L], block_causal=L), y[: 3 * L], atol=1e-13)
+    # and the bidirectional model does not have that property
+    assert np.abs(orc.forward_hidden(model, t2)[: 2 * L] - orc.forward_hidden(model, t)[: 2 * L]).max() > 1e-3
+    with pytest.raises(ValueError):
+        orc.block_logits(model, t, 4, L, block_causal=True)
