@@ -50,6 +50,8 @@ extern "C" {
 
 #define PSD_DTYPE_FP32 0   /* debug path: fp32 storage and arithmetic, plain kernels */
 #define PSD_DTYPE_BF16 1   /* bf16 storage, MFMA contractions with fp32 accumulation */
+#define PSD_ATTN_BIDIRECTIONAL 0
+#define PSD_ATTN_BLOCK_CAUSAL 1
 
 typedef struct psd_handle psd_handle;
 
@@ -64,6 +66,8 @@ typedef struct {
     int32_t dtype;         /* PSD_DTYPE_*: type of every weight matrix */
     float   logit_scale;   /* logits = logit_scale * (y W_lm^T); 1.0 normally */
     int32_t max_seq;       /* rows of the rotary tables */
+    int32_t attention;     /* PSD_ATTN_*: bidirectional (default 0), or context-causal blocks (App. A: full
+                            * attention inside a block of the decoding block length, causal across blocks) */
 } psd_model_config;
 
 /* Device pointers, borrowed for the life of the handle.  Matrices are [out, in] in the
@@ -215,6 +219,41 @@ int32_t psd_decode_block(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, i
                          int32_t L, const psd_policy *policy, const psd_graph *graph, psd_stats *stats,
                          void *ws, int64_t ws_bytes, void *stream);
 int64_t psd_decode_scratch_bytes(int32_t B, int32_t N, int32_t L, int32_t K);
+
+/* ---- Context-causal block attention with an exact prefix KV cache ------------------------------
+ * One model family of the paper (App. A, the continually pretrained block-diffusion model) attends
+ * fully inside a block and causally across blocks.  With config.attention = PSD_ATTN_BLOCK_CAUSAL
+ * (blocks = the decoding blocks, from position 0; prompt length a multiple of the block length):
+ *   - the calls above still work on whole sequences (masked attention on the plain kernels: the
+ *     on-device reference for this mode);
+ *   - the calls below run the model on the L rows of the active block only.  Everything before the
+ *     block is finished, so its keys and values are exact in a cache, and nothing after it is
+ *     visible.  The K drafts of a verification batch share their sequence's cache (the "KV-cache
+ *     sharing" of Sec. 3.2 stage 3, lossless here).
+ * The cache is caller-owned device memory, psd_kv_cache_bytes(cfg, capacity) bytes per sequence,
+ * sequences back to back, 256-byte aligned; per layer it holds the rotated keys
+ * [capacity, n_kv_heads*d_head] and the values transposed.  It must be zeroed (psd_kv_reset) before a
+ * sequence starts.  Its length is not stored: a call's block_start says how many positions it holds,
+ * and psd_kv_prefill / psd_decode_block_cached extend it block by block.  Block lengths must be
+ * multiples of 16.  Workspace: psd_workspace_bytes(cfg, sequences, L, L) (+ the decode scratch).
+ *   psd_kv_prefill: forwards positions [0, n_prompt) of tokens [B, N] block by block and fills the caches.
+ *   psd_forward_confidence_cached: tokens device int32 [S, N], only positions block_start .. +L are
+ *     read; sequence s uses cache s / seqs_per_cache; writes top1/conf [S, L] (both or neither) and,
+ *     if logits != NULL, the raw block logits [S*L, vocab] (debug).
+ *   psd_decode_block_cached: psd_decode_block with cached model calls; afterwards the finished block
+ *     is appended to the caches (one more forward over the B blocks, not counted as an invocation:
+ *     it decodes nothing). */
+int64_t psd_kv_cache_bytes(const psd_model_config *cfg, int32_t capacity);
+int32_t psd_kv_reset(psd_handle *h, void *cache, int32_t n_seqs, int32_t capacity, void *stream);
+int32_t psd_kv_prefill(psd_handle *h, const int32_t *tokens, int32_t B, int32_t N, int32_t n_prompt, int32_t L,
+                       void *cache, int32_t capacity, void *ws, int64_t ws_bytes, void *stream);
+int32_t psd_forward_confidence_cached(psd_handle *h, const int32_t *tokens, int32_t S, int32_t N, int32_t block_start,
+                                      int32_t L, int32_t seqs_per_cache, const void *cache, int32_t capacity,
+                                      int32_t *top1, float *conf, float *logits, void *ws, int64_t ws_bytes,
+                                      void *stream);
+int32_t psd_decode_block_cached(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_t block_start, int32_t L,
+                                const psd_policy *policy, const psd_graph *graph, psd_stats *stats, void *cache,
+                                int32_t capacity, void *ws, int64_t ws_bytes, void *stream);
 
 /* Per-handle timing of the last psd_decode_block / forward calls is not kept; callers time
  * with HIP events on `stream`.  For roofline accounting the library reports the algorithmic

@@ -28,7 +28,7 @@ class _Config(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("d_head", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32), ("mask_id", C.c_int32),
                 ("rms_eps", C.c_float), ("qkv_bias", C.c_int32), ("dtype", C.c_int32), ("logit_scale", C.c_float),
-                ("max_seq", C.c_int32)]
+                ("max_seq", C.c_int32), ("attention", C.c_int32)]
 
 
 _PP = C.POINTER(C.c_void_p)
@@ -93,6 +93,12 @@ def load_library():
                              vp, vp]),
         "psd_verify_accept": (i32, [vp, vp, vp, i32, i32, i32, i32, vp, vp, C.POINTER(_Graph), C.POINTER(_Policy), vp,
                                     vp, vp, vp, vp, i64, vp]),
+        "psd_kv_cache_bytes": (i64, [C.POINTER(_Config), i32]),
+        "psd_kv_reset": (i32, [vp, vp, i32, i32, vp]),
+        "psd_kv_prefill": (i32, [vp, vp, i32, i32, i32, i32, vp, i32, vp, i64, vp]),
+        "psd_forward_confidence_cached": (i32, [vp, vp, i32, i32, i32, i32, i32, vp, i32, vp, vp, vp, vp, i64, vp]),
+        "psd_decode_block_cached": (i32, [vp, vp, i32, i32, i32, i32, C.POINTER(_Policy), C.POINTER(_Graph), C.POINTER(_Stats),
+                                           vp, i32, vp, i64, vp]),
         "psd_decode_block": (i32, [vp, vp, i32, i32, i32, i32, C.POINTER(_Policy), C.POINTER(_Graph), C.POINTER(_Stats),
                                    vp, i64, vp]),
         "psd_kernel_gemm_bf16": (i32, [vp, vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp, i32, vp]),
@@ -221,7 +227,7 @@ class Model:
         self._ws = None
         cfg = _Config(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.d_head, shape.d_ffn,
                       shape.vocab, shape.mask_id, shape.rms_eps, int(shape.qkv_bias), 1 if shape.dtype == "bf16" else 0,
-                      float(shape.logit_scale), self.max_seq)
+                      float(shape.logit_scale), self.max_seq, 1 if getattr(shape, "attention", "bidirectional") == "block_causal" else 0)
         self.cfg = cfg
         w = _Weights()
         for name in ("tok_emb", "final_norm", "lm_head", "rope_cos", "rope_sin"):
@@ -402,6 +408,64 @@ def psd_decode_block(model: Model, tokens: torch.Tensor, block_start: int, L: in
     g, pol = graph.c(), policy.c()
     _check(model.lib.psd_decode_block(model.handle, _ptr(tokens), B, N, block_start, L, C.byref(pol), C.byref(g), cstats,
                                       _ptr(ws), nb, _stream()))
+    out = list(stats) if stats is not None else [Stats() for _ in range(B)]
+    for b in range(B):
+        out[b].invocations += cstats[b].invocations
+        out[b].tokens_policy += cstats[b].tokens_policy
+        out[b].tokens_draft += cstats[b].tokens_draft
+        out[b].tokens_postverify += cstats[b].tokens_postverify
+        for i in range(HIST):
+            out[b].depth_hist[i] += cstats[b].depth_hist[i]
+    return out
+
+
+class KvCache:
+    """Device memory for the prefix KV caches of n_seqs sequences of a context-causal block model (zeroed)."""
+
+    def __init__(self, model: Model, n_seqs: int, capacity: int):
+        per_seq = model.lib.psd_kv_cache_bytes(C.byref(model.cfg), capacity)
+        _check(per_seq)
+        self.model, self.n_seqs, self.capacity = model, n_seqs, capacity
+        self.mem = torch.empty(per_seq * n_seqs + 256, dtype=torch.uint8, device=model.device)
+        self.reset()
+
+    def reset(self):
+        _check(self.model.lib.psd_kv_reset(self.model.handle, _ptr(self.mem), self.n_seqs, self.capacity, _stream()))
+
+
+def psd_kv_prefill(model: Model, tokens: torch.Tensor, n_prompt: int, L: int, cache: KvCache) -> None:
+    B, N = tokens.shape
+    ws, nb = model.forward_ws(B, L, L)
+    _check(model.lib.psd_kv_prefill(model.handle, _ptr(tokens), B, N, n_prompt, L, _ptr(cache.mem), cache.capacity, _ptr(ws), nb,
+                                    _stream()))
+
+
+def psd_forward_confidence_cached(model: Model, tokens: torch.Tensor, block_start: int, L: int, cache: KvCache,
+                                  seqs_per_cache: int = 1, want_logits: bool = False):
+    """tokens int32 [S, N]; the block rows against the caches -> (top1 [S, L], conf [S, L][, logits [S*L, V]])."""
+    S, N = tokens.shape
+    top1 = torch.empty((S, L), dtype=torch.int32, device=tokens.device)
+    conf = torch.empty((S, L), dtype=torch.float32, device=tokens.device)
+    logits = torch.empty((S * L, model.shape.vocab), dtype=torch.float32, device=tokens.device) if want_logits else None
+    ws, nb = model.forward_ws(S, L, L)
+    _check(model.lib.psd_forward_confidence_cached(model.handle, _ptr(tokens), S, N, block_start, L, seqs_per_cache,
+                                                   _ptr(cache.mem), cache.capacity, _ptr(top1), _ptr(conf), _ptr(logits),
+                                                   _ptr(ws), nb, _stream()))
+    return (top1, conf, logits) if want_logits else (top1, conf)
+
+
+def psd_decode_block_cached(model: Model, tokens: torch.Tensor, block_start: int, L: int, policy: Policy, graph: Graph,
+                            cache: KvCache, stats: Optional[Sequence[Stats]] = None) -> List[Stats]:
+    """psd_decode_block with cached model calls; the finished block is appended to the caches."""
+    B, N = tokens.shape
+    K = graph.K
+    extra = model.lib.psd_decode_scratch_bytes(B, N, L, K)
+    _check(extra)
+    ws, nb = model.forward_ws(B * K, L, L, extra=extra)
+    cstats = (_Stats * B)()
+    g, pol = graph.c(), policy.c()
+    _check(model.lib.psd_decode_block_cached(model.handle, _ptr(tokens), B, N, block_start, L, C.byref(pol), C.byref(g), cstats,
+                                             _ptr(cache.mem), cache.capacity, _ptr(ws), nb, _stream()))
     out = list(stats) if stats is not None else [Stats() for _ in range(B)]
     for b in range(B):
         out[b].invocations += cstats[b].invocations

@@ -40,6 +40,8 @@ int32_t check_cfg(const psd_model_config *c) {
     if (c->d_head % 2) PSD_FAIL(PSD_ERR_SHAPE, "d_head must be even (rotary pairs)");
     if (c->mask_id < 0 || c->mask_id >= c->vocab) PSD_FAIL(PSD_ERR_SHAPE, "mask_id outside the embedding table");
     if (c->dtype != PSD_DTYPE_FP32 && c->dtype != PSD_DTYPE_BF16) PSD_FAIL(PSD_ERR_UNSUPPORTED, "dtype %d", c->dtype);
+    if (c->attention != PSD_ATTN_BIDIRECTIONAL && c->attention != PSD_ATTN_BLOCK_CAUSAL)
+        PSD_FAIL(PSD_ERR_UNSUPPORTED, "attention mode %d", c->attention);
     if (c->dtype == PSD_DTYPE_BF16) {
         if (c->d_head != 64 && c->d_head != 128) PSD_FAIL(PSD_ERR_UNSUPPORTED, "bf16 path needs d_head 64 or 128");
         if (c->d_model % 64 || c->d_ffn % 64) PSD_FAIL(PSD_ERR_UNSUPPORTED, "bf16 path needs d_model, d_ffn multiples of 64");
@@ -362,20 +364,38 @@ int32_t psd_verify_accept(psd_handle *h, int32_t *tokens, const int32_t *drafts,
     return PSD_OK;
 }
 
-int32_t psd_decode_block(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_t block_start, int32_t L,
-                         const psd_policy *policy, const psd_graph *graph, psd_stats *stats, void *ws, int64_t ws_bytes,
-                         void *stream) {
+namespace {
+
+// Alg. 1 on one block.  kv = NULL: every model call runs over the whole sequences; otherwise over the block rows
+// against the sequences' KV caches (context-causal block attention), and the finished block is appended to them.
+int32_t decode_block_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_t block_start, int32_t L,
+                          const psd_policy *policy, const psd_graph *graph, psd_stats *stats, void *ws, int64_t ws_bytes,
+                          void *stream, const KvCacheArg *kv) {
     CHECK(check_block(h, B, N, block_start, L));
     GraphArg g;
     CHECK(check_graph(graph, &g));
     CHECK(check_policy(policy));
     if (!tokens || !stats) PSD_FAIL(PSD_ERR_INVALID_ARG, "NULL tokens/stats");
     const int K = g.K;
-    const int64_t fwd_bytes = plan_forward(h->cfg, (int64_t)B * K, N, L).total;
+    const int plan_N = kv ? L : N;     // rows per sequence that a model call runs over
+    const int64_t fwd_bytes = plan_forward(h->cfg, (int64_t)B * K, plan_N, L).total;
     const DecodeScratch sc = plan_decode(B, N, L, K);
     if (!ws || ws_bytes < fwd_bytes + sc.total)
-        PSD_FAIL(PSD_ERR_WORKSPACE, "workspace of %lld bytes, psd_decode_block needs %lld", (long long)ws_bytes,
+        PSD_FAIL(PSD_ERR_WORKSPACE, "workspace of %lld bytes, decoding the block needs %lld", (long long)ws_bytes,
                  (long long)(fwd_bytes + sc.total));
+    // one model call: forward + top-1 confidence of the sequences listed in `rows` (device) out of src [*, N]
+    auto model_call = [&](const int32_t *src, const int32_t *rows_dev, int S, int seqs_per_cache, int32_t *t1, float *cf,
+                          hipStream_t st_) -> int32_t {
+        if (kv) {
+            KvCacheArg a = *kv;
+            a.seqs_per_cache = seqs_per_cache;
+            a.append = false;
+            CHECK(run_forward_cached(h, src, rows_dev, S, N, block_start, L, a, ws, fwd_bytes, st_));
+        } else {
+            CHECK(run_forward_hidden(h, src, rows_dev, S, N, block_start, L, ws, fwd_bytes, st_));
+        }
+        return run_head_confidence(h, src, rows_dev, S, N, block_start, L, t1, cf, rows_dev, ws, st_, plan_N);
+    };
     if ((reinterpret_cast<uintptr_t>(ws) & 255) != 0) PSD_FAIL(PSD_ERR_WORKSPACE, "workspace must be 256-byte aligned");
     if ((int64_t)B * (K + 2 + PSD_DEVSTAT_WORDS) > h->host_counts_cap) PSD_FAIL(PSD_ERR_SHAPE, "batch too large for the control buffer");
     hipStream_t st = (hipStream_t)stream;
@@ -407,8 +427,7 @@ int32_t psd_decode_block(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, i
         const int S1 = (int)active.size();
         for (int s = 0; s < S1; ++s) hrows[s] = active[s];
         PSD_HIP(hipMemcpyAsync(rows, hrows, sizeof(int32_t) * S1, hipMemcpyHostToDevice, st));
-        CHECK(run_forward_hidden(h, tokens, rows, S1, N, block_start, L, ws, fwd_bytes, st));
-        CHECK(run_head_confidence(h, tokens, rows, S1, N, block_start, L, top1, conf, rows, ws, st));
+        CHECK(model_call(tokens, rows, S1, 1, top1, conf, st));
         for (int b : active) invocations[b] += 1;
         launch_select_unmask(tokens, B, N, block_start, L, top1, conf, *policy, mask_id, nullptr, nullptr, n_left, devstats, st);
         launch_build_drafts(tokens, B, N, block_start, L, top1, conf, g, mask_id, sigma, m, drafts, st);
@@ -423,8 +442,7 @@ int32_t psd_decode_block(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, i
         for (size_t i = 0; i < vset.size(); ++i)
             for (int k = 0; k < K; ++k) hrows[i * K + k] = vset[i] * K + k;
         PSD_HIP(hipMemcpyAsync(rows, hrows, sizeof(int32_t) * S3, hipMemcpyHostToDevice, st));
-        CHECK(run_forward_hidden(h, drafts, rows, S3, N, block_start, L, ws, fwd_bytes, st));
-        CHECK(run_head_confidence(h, drafts, rows, S3, N, block_start, L, v_top1, v_conf, rows, ws, st));
+        CHECK(model_call(drafts, rows, S3, K, v_top1, v_conf, st));
         for (int b : vset) invocations[b] += 1;
         launch_accept(tokens, drafts, B, N, block_start, L, sigma, m, g, *policy, mask_id, v_top1, v_conf, k_star, accepted,
                       n_left, devstats, st);
@@ -446,8 +464,107 @@ int32_t psd_decode_block(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, i
         stats[b].tokens_postverify += ds[PSD_DEVSTAT_POST];
         for (int i = 0; i <= PSD_MAX_BLOCK; ++i) stats[b].depth_hist[i] += ds[PSD_DEVSTAT_HIST + i];
     }
+    if (kv) {   // the block is finished: its keys and values become context
+        KvCacheArg a = *kv;
+        a.seqs_per_cache = 1;
+        a.append = true;
+        CHECK(run_forward_cached(h, tokens, nullptr, B, N, block_start, L, a, ws, fwd_bytes, st));
+    }
     PSD_HIP(hipGetLastError());
     return PSD_OK;
+}
+
+int32_t check_kv(const psd_handle *h, const void *cache, int32_t capacity, int32_t block_start, int32_t L) {
+    if (!h) PSD_FAIL(PSD_ERR_INVALID_ARG, "handle is NULL");
+    if (h->cfg.attention != PSD_ATTN_BLOCK_CAUSAL)
+        PSD_FAIL(PSD_ERR_UNSUPPORTED, "a KV cache is exact only for context-causal block attention (config.attention)");
+    if (!cache) PSD_FAIL(PSD_ERR_INVALID_ARG, "cache is NULL");
+    if ((reinterpret_cast<uintptr_t>(cache) & 255) != 0) PSD_FAIL(PSD_ERR_WORKSPACE, "cache must be 256-byte aligned");
+    if (capacity < 1 || capacity > h->cfg.max_seq) PSD_FAIL(PSD_ERR_SHAPE, "cache capacity %d outside 1..max_seq", capacity);
+    if (L < 1 || block_start % L) PSD_FAIL(PSD_ERR_SHAPE, "blocks are aligned to multiples of the block length %d", L);
+    if (L % 16) PSD_FAIL(PSD_ERR_SHAPE, "a cached block length must be a multiple of 16 (value layout), not %d", L);
+    if (block_start + L > capacity) PSD_FAIL(PSD_ERR_SHAPE, "block [%d, %d) exceeds the cache capacity %d", block_start,
+                                             block_start + L, capacity);
+    return PSD_OK;
+}
+
+}   // namespace
+
+int32_t psd_decode_block(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_t block_start, int32_t L,
+                         const psd_policy *policy, const psd_graph *graph, psd_stats *stats, void *ws, int64_t ws_bytes,
+                         void *stream) {
+    return decode_block_impl(h, tokens, B, N, block_start, L, policy, graph, stats, ws, ws_bytes, stream, nullptr);
+}
+
+// ---- context-causal block attention with an exact prefix KV cache ----
+
+int64_t psd_kv_cache_bytes(const psd_model_config *cfg, int32_t capacity) {
+    int32_t rc = check_cfg(cfg);
+    if (rc != PSD_OK) return rc;
+    if (capacity < 1 || capacity > cfg->max_seq) {
+        psd_set_error("psd_kv_cache_bytes: capacity %d outside 1..max_seq", capacity);
+        return PSD_ERR_SHAPE;
+    }
+    return align_up(kv_layout(*cfg, capacity).per_seq * (cfg->dtype == PSD_DTYPE_BF16 ? 2 : 4), 256);
+}
+
+int32_t psd_kv_reset(psd_handle *h, void *cache, int32_t n_seqs, int32_t capacity, void *stream) {
+    CHECK(check_kv(h, cache, capacity, 0, 16));
+    if (n_seqs < 1) PSD_FAIL(PSD_ERR_SHAPE, "n_seqs %d", n_seqs);
+    const int64_t words = psd_kv_cache_bytes(&h->cfg, capacity) / 4 * n_seqs;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, (hipStream_t)stream, (int32_t *)cache,
+                       words, 0);
+    PSD_HIP(hipGetLastError());
+    return PSD_OK;
+}
+
+int32_t psd_kv_prefill(psd_handle *h, const int32_t *tokens, int32_t B, int32_t N, int32_t n_prompt, int32_t L, void *cache,
+                       int32_t capacity, void *ws, int64_t ws_bytes, void *stream) {
+    CHECK(check_block(h, B, N, 0, L));
+    CHECK(check_kv(h, cache, capacity, 0, L));
+    if (!tokens) PSD_FAIL(PSD_ERR_INVALID_ARG, "tokens is NULL");
+    if (n_prompt < 0 || n_prompt % L || n_prompt > N || n_prompt > capacity)
+        PSD_FAIL(PSD_ERR_SHAPE, "prompt length %d: a multiple of the block length within the sequence and the cache", n_prompt);
+    KvCacheArg a;
+    a.base = cache;
+    a.capacity = capacity;
+    a.seqs_per_cache = 1;
+    a.append = true;
+    for (int start = 0; start < n_prompt; start += L) {   // block by block: each sees the blocks before it
+        a.len = start;
+        CHECK(run_forward_cached(h, tokens, nullptr, B, N, start, L, a, ws, ws_bytes, (hipStream_t)stream));
+    }
+    return PSD_OK;
+}
+
+int32_t psd_forward_confidence_cached(psd_handle *h, const int32_t *tokens, int32_t S, int32_t N, int32_t block_start, int32_t L,
+                                      int32_t seqs_per_cache, const void *cache, int32_t capacity, int32_t *top1, float *conf,
+                                      float *logits, void *ws, int64_t ws_bytes, void *stream) {
+    CHECK(check_block(h, S, N, block_start, L));
+    CHECK(check_kv(h, cache, capacity, block_start, L));
+    if (!tokens || (!logits && (!top1 || !conf))) PSD_FAIL(PSD_ERR_INVALID_ARG, "NULL tokens/top1/conf");
+    if (seqs_per_cache < 1 || S % seqs_per_cache) PSD_FAIL(PSD_ERR_SHAPE, "S must be a multiple of seqs_per_cache");
+    KvCacheArg a;
+    a.base = const_cast<void *>(cache);
+    a.capacity = capacity;
+    a.len = block_start;
+    a.seqs_per_cache = seqs_per_cache;
+    hipStream_t st = (hipStream_t)stream;
+    CHECK(run_forward_cached(h, tokens, nullptr, S, N, block_start, L, a, ws, ws_bytes, st));
+    if (logits) CHECK(run_head_logits(h, S, L, L, logits, ws, st));
+    if (top1 && conf) return run_head_confidence(h, tokens, nullptr, S, N, block_start, L, top1, conf, nullptr, ws, st, L);
+    return PSD_OK;
+}
+
+int32_t psd_decode_block_cached(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_t block_start, int32_t L,
+                                const psd_policy *policy, const psd_graph *graph, psd_stats *stats, void *cache,
+                                int32_t capacity, void *ws, int64_t ws_bytes, void *stream) {
+    CHECK(check_kv(h, cache, capacity, block_start, L));
+    KvCacheArg a;
+    a.base = cache;
+    a.capacity = capacity;
+    a.len = block_start;
+    return decode_block_impl(h, tokens, B, N, block_start, L, policy, graph, stats, ws, ws_bytes, stream, &a);
 }
 
 // ---- kernel-level hooks: the same launchers the forward uses, on caller-provided buffers ----
@@ -484,7 +601,7 @@ int32_t psd_kernel_attention_bf16(const void *qkv, int32_t ld_qkv, int32_t S, in
         PSD_FAIL(PSD_ERR_SHAPE, "attention needs d_head 64/128, N a multiple of 8, n_heads a multiple of n_kv_heads");
     launch_transpose_v((const bf16_t *)qkv, ld_qkv, S, N, n_heads, n_kv_heads, d_head, (bf16_t *)vT, (hipStream_t)stream);
     launch_attention_bf16((const bf16_t *)qkv, ld_qkv, (const bf16_t *)vT, S, N, n_heads, n_kv_heads, d_head, (bf16_t *)out,
-                          (hipStream_t)stream);
+                          KvPrefix(), (hipStream_t)stream);
     PSD_HIP(hipGetLastError());
     return PSD_OK;
 }

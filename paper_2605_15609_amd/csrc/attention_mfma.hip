@@ -34,10 +34,14 @@ typedef __attribute__((address_space(3))) void lds_void;
 
 // NW wavefronts (32 queries each) per workgroup; ld_qkv / ld_vt = row strides (elements) of qkv and of vT,
 // whose rows hold N rounded up to 64 keys (tail zero)
+//
+// pre: keys and values that precede the sequence's own N rows (a KV cache of pre.len positions, shared by
+// pre.seqs_per_cache consecutive sequences).  Every query sees all of them and all N own keys: with the own rows
+// being one block, that is context-causal block attention.  pre.len = 0: plain bidirectional attention.
 template <int DH, int NW, int NSTG>
 __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(const bf16_t *__restrict__ qkv, int ld_qkv,
                                                             const bf16_t *__restrict__ vT, int ld_vt, int N, int n_heads,
-                                                            int n_kv_heads, bf16_t *__restrict__ out) {
+                                                            int n_kv_heads, bf16_t *__restrict__ out, KvPrefix pre) {
     constexpr int KROW = DH * 2;                 // bytes per K row in LDS
     constexpr int K_BYTES = BKV * KROW;
     constexpr int VROW = BKV * 2;                // bytes per V^T row in LDS (128)
@@ -82,22 +86,37 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(const bf16_t *__r
         const_cast<bf16_t *>(seq) + (n_heads + kvh) * DH, 0, (int)(((int64_t)N * row_w - (n_heads + kvh) * DH) * 2), 0x00020000);
     const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<bf16_t *>(vT) + ((int64_t)s * n_kv_heads + kvh) * DH * (int64_t)ld_vt, 0, DH * ld_vt * 2, 0x00020000);
+    // the prefix (cache) of this sequence; empty descriptors when there is none
+    const int n_pre = (pre.len + BKV - 1) / BKV;
+    const int64_t cache = n_pre ? (pre.seq_rows ? pre.seq_rows[s] : s) / pre.seqs_per_cache : 0;
+    const __amdgpu_buffer_rsrc_t rk_pre = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t *>((const bf16_t *)pre.k) + cache * pre.stride_k + kvh * DH, 0, n_pre ? (pre.len * pre.ld_k - kvh * DH) * 2 : 0,
+        0x00020000);
+    const __amdgpu_buffer_rsrc_t rv_pre = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t *>((const bf16_t *)pre.vt) + cache * pre.stride_vt + (int64_t)kvh * DH * pre.ld_vt, 0,
+        n_pre ? DH * pre.ld_vt * 2 : 0, 0x00020000);
     constexpr int KLPR = 64 / KRPI;              // lanes per K row in one DMA instruction (16 or 8)
-#define PSD_ATT_DMA(stage, k0)                                                                                   \
+#define PSD_ATT_DMA_FROM(stage, rk_, ldk_, rv_, ldv_, k0)                                                        \
     {                                                                                                            \
         unsigned char *sk_ = lds + (stage) * STAGE + wave * 1024, *sv_ = lds + (stage) * STAGE + K_BYTES + wave * 1024; \
         _Pragma("unroll") for (int j = 0; j < KG; ++j) {                                                         \
             const int row = (j * NW + wave) * KRPI + lane / KLPR;                                                \
-            const int voff = (lane / KLPR) * row_w * 2 + (((lane % KLPR) ^ kkey(row)) << 4);                         \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_void *)(sk_ + j * (NW * 1024)), 16, voff,          \
-                                                     (((k0) + (j * NW + wave) * KRPI) * row_w) * 2, 0, 0);        \
+            const int voff = (lane / KLPR) * (ldk_) * 2 + (((lane % KLPR) ^ kkey(row)) << 4);                     \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rk_, (lds_void *)(sk_ + j * (NW * 1024)), 16, voff,         \
+                                                     (((k0) + (j * NW + wave) * KRPI) * (ldk_)) * 2, 0, 0);       \
         }                                                                                                        \
         _Pragma("unroll") for (int j = 0; j < VG; ++j) {                                                         \
             const int row = (j * NW + wave) * 8 + (lane >> 3);                                                   \
-            const int voff = (lane >> 3) * ld_vt * 2 + (((lane & 7) ^ ((row >> 1) & 7)) << 4);                   \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lds_void *)(sv_ + j * (NW * 1024)), 16, voff,          \
-                                                     ((j * NW + wave) * 8 * ld_vt + (k0)) * 2, 0, 0);             \
+            const int voff = (lane >> 3) * (ldv_) * 2 + (((lane & 7) ^ ((row >> 1) & 7)) << 4);                  \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rv_, (lds_void *)(sv_ + j * (NW * 1024)), 16, voff,         \
+                                                     ((j * NW + wave) * 8 * (ldv_) + (k0)) * 2, 0, 0);            \
         }                                                                                                        \
+    }
+// tile tt of the key sequence: prefix tiles first, then the own rows
+#define PSD_ATT_DMA(stage, tt)                                                                                   \
+    {                                                                                                            \
+        if ((tt) < n_pre) PSD_ATT_DMA_FROM(stage, rk_pre, pre.ld_k, rv_pre, pre.ld_vt, (tt) * BKV)               \
+        else PSD_ATT_DMA_FROM(stage, rk, row_w, rv, ld_vt, ((tt) - n_pre) * BKV)                                 \
     }
 #define PSD_ATT_SYNC()                                                                                           \
     {                                                                                                            \
@@ -119,18 +138,19 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(const bf16_t *__r
     // returns in issue order: once at most (NSTG - 2) tiles' worth of this wavefront's fetches are in flight,
     // the next tile has landed.
     static_assert(NSTG >= 2 && (NSTG - 1) * (KG + VG) <= 63, "DMA groups in flight must fit the vmcnt counter");
-    const int n_tiles = (N + BKV - 1) / BKV;
+    const int n_tiles = n_pre + (N + BKV - 1) / BKV;
 #pragma unroll
-    for (int p = 0; p < NSTG - 1; ++p) PSD_ATT_DMA(p, p * BKV)
+    for (int p = 0; p < NSTG - 1; ++p) PSD_ATT_DMA(p, p)
     PSD_ATT_SYNC()
 
     int stage = 0;
     for (int t = 0; t < n_tiles; ++t) {
-        const int k0 = t * BKV;
+        // first key of the tile within its segment, and the number of keys that segment has
+        const int k0 = (t < n_pre ? t : t - n_pre) * BKV, limit = t < n_pre ? pre.len : N;
         // refill the slot every wavefront left at the last barrier; past the last tile the fetch is rejected or
         // reads padding and is never consumed
         const int fill = (stage == 0) ? NSTG - 1 : stage - 1;
-        PSD_ATT_DMA(fill, k0 + (NSTG - 1) * BKV)
+        PSD_ATT_DMA(fill, t + (NSTG - 1))
         const unsigned char *sk = lds + stage * STAGE, *sv = sk + K_BYTES;
 
         // scores, transposed: acc_s[kt][v] <-> key 32*kt + 8*(v/4) + 4*half + v%4, query lrow
@@ -147,14 +167,14 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(const bf16_t *__r
                 acc_s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], acc_s[kt], 0, 0, 0);
             }
         }
-        // keys past the end of the sequence do not exist
-        if (k0 + BKV > N) {
+        // keys past the end of the segment do not exist
+        if (k0 + BKV > limit) {
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int key = k0 + kt * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
-                    if (key >= N) acc_s[kt][v] = -INFINITY;
+                    if (key >= limit) acc_s[kt][v] = -INFINITY;
                 }
         }
         // online softmax for this lane's query
@@ -208,6 +228,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(const bf16_t *__r
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no fetch may outlive the loop
 #undef PSD_ATT_DMA
+#undef PSD_ATT_DMA_FROM
 #undef PSD_ATT_SYNC
 
     // the two half-waves of a query hold disjoint key subsets of the sum
@@ -264,7 +285,7 @@ void launch_transpose_v(const bf16_t *qkv, int ld_qkv, int S, int N, int n_heads
 
 template <int DH, int NW, int NSTG>
 static void launch_att(const bf16_t *qkv, int ld_qkv, const bf16_t *vT, int S, int N, int n_heads, int n_kv_heads, bf16_t *out,
-                       hipStream_t st) {
+                       const KvPrefix &pre, hipStream_t st) {
     constexpr int smem = NSTG * (BKV * DH * 2 + DH * BKV * 2);
     static_assert(smem <= 160 * 1024, "LDS ring exceeds the 160 KB of a CU");
     auto kern = attention_kernel<DH, NW, NSTG>;
@@ -274,22 +295,26 @@ static void launch_att(const bf16_t *qkv, int ld_qkv, const bf16_t *vT, int S, i
         attr_done = true;
     }
     dim3 grid((N + 32 * NW - 1) / (32 * NW), n_heads, S);
-    hipLaunchKernelGGL(kern, grid, dim3(NW * 64), smem, st, qkv, ld_qkv, vT, (int)vt_row_stride(N), N, n_heads, n_kv_heads, out);
+    hipLaunchKernelGGL(kern, grid, dim3(NW * 64), smem, st, qkv, ld_qkv, vT, (int)vt_row_stride(N), N, n_heads, n_kv_heads, out,
+                       pre);
 }
 
 #ifndef PSD_ATT_NSTG
 #define PSD_ATT_NSTG 2   // deeper rings (3, 4 stages) were measured 3-7 % slower: the kernel is not bound by fetch latency
 #endif
 void launch_attention_bf16(const bf16_t *qkv, int ld_qkv, const bf16_t *vT, int S, int N, int n_heads, int n_kv_heads, int d_head,
-                           bf16_t *out, hipStream_t st) {
-    // 128 queries per workgroup when that still gives two workgroups per CU, else 64
+                           bf16_t *out, const KvPrefix &pre, hipStream_t st) {
+    // 128 queries per workgroup when that still gives two workgroups per CU, else 64; one wavefront for a
+    // single block of 32 queries
     const int64_t blocks128 = (int64_t)((N + 127) / 128) * n_heads * S;
     const bool small = blocks128 < 512;
     if (d_head == 128) {
-        if (small) launch_att<128, 2, PSD_ATT_NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, st);
-        else launch_att<128, 4, PSD_ATT_NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, st);
+        if (N <= 32) launch_att<128, 1, PSD_ATT_NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
+        else if (small) launch_att<128, 2, PSD_ATT_NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
+        else launch_att<128, 4, PSD_ATT_NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
     } else {
-        if (small) launch_att<64, 2, PSD_ATT_NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, st);
-        else launch_att<64, 4, PSD_ATT_NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, st);
+        if (N <= 32) launch_att<64, 1, PSD_ATT_NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
+        else if (small) launch_att<64, 2, PSD_ATT_NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
+        else launch_att<64, 4, PSD_ATT_NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
     }
 }

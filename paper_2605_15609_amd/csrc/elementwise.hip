@@ -8,12 +8,12 @@ namespace {
 
 template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(const int32_t *__restrict__ tokens,
-                                                    const int32_t *__restrict__ seq_rows, int N,
+                                                    const int32_t *__restrict__ seq_rows, int N, int first, int count,
                                                     const T *__restrict__ emb, int d, float *__restrict__ h) {
-    const int64_t t = blockIdx.x;   // slot-major token index s*N + i
-    const int s = (int)(t / N), i = (int)(t % N);
+    const int64_t t = blockIdx.x;   // slot-major row index s*count + i: position first + i of sequence s
+    const int s = (int)(t / count), i = (int)(t % count);
     const int64_t src_row = seq_rows ? seq_rows[s] : s;
-    const int32_t tok = tokens[src_row * N + i];
+    const int32_t tok = tokens[src_row * N + first + i];
     const T *e = emb + (int64_t)tok * d;
     float *o = h + t * d;
     for (int c = threadIdx.x; c < d; c += blockDim.x) o[c] = to_float(e[c]);
@@ -99,10 +99,10 @@ __global__ __launch_bounds__(256) void rmsnorm_bf16_vec_kernel(const float *__re
 
 // rotate-half rotary embedding in place on the q and k heads of qkv [tokens, (H + 2 Hkv) * dh], row stride ld
 template <typename T>
-__global__ __launch_bounds__(256) void rope_kernel(T *__restrict__ qkv, int ld, int N, int n_heads, int n_kv_heads, int d_head,
+__global__ __launch_bounds__(256) void rope_kernel(T *__restrict__ qkv, int ld, int N, int pos0, int n_heads, int n_kv_heads, int d_head,
                                                    const float *__restrict__ cos_t, const float *__restrict__ sin_t) {
     const int64_t t = blockIdx.x;
-    const int pos = (int)(t % N);
+    const int pos = pos0 + (int)(t % N);
     const int half = d_head >> 1;
     const int rot_heads = n_heads + n_kv_heads;
     T *row = qkv + t * (int64_t)ld;
@@ -117,11 +117,11 @@ __global__ __launch_bounds__(256) void rope_kernel(T *__restrict__ qkv, int ld, 
 }
 
 // bf16 rotary: a thread owns 8 consecutive pair indices j of one head (two 16-byte accesses each way)
-__global__ __launch_bounds__(256) void rope_bf16_vec_kernel(bf16_t *__restrict__ qkv, int ld, int N, int n_heads, int n_kv_heads,
+__global__ __launch_bounds__(256) void rope_bf16_vec_kernel(bf16_t *__restrict__ qkv, int ld, int N, int pos0, int n_heads, int n_kv_heads,
                                                             int d_head, const float *__restrict__ cos_t,
                                                             const float *__restrict__ sin_t) {
     const int64_t t = blockIdx.x;
-    const int pos = (int)(t % N);
+    const int pos = pos0 + (int)(t % N);
     const int half = d_head >> 1, groups = half >> 3;
     const int rot_heads = n_heads + n_kv_heads;
     bf16_t *row = qkv + t * (int64_t)ld;
@@ -174,8 +174,45 @@ template void launch_gather_block_rows<bf16_t>(const bf16_t *, bf16_t *, int, in
 template <typename T>
 void launch_embed(const int32_t *tokens, const int32_t *seq_rows, int S, int N, const T *emb, int d, float *h,
                   hipStream_t st) {
-    hipLaunchKernelGGL(embed_kernel<T>, dim3((unsigned)((int64_t)S * N)), dim3(256), 0, st, tokens, seq_rows, N, emb, d, h);
+    hipLaunchKernelGGL(embed_kernel<T>, dim3((unsigned)((int64_t)S * N)), dim3(256), 0, st, tokens, seq_rows, N, 0, N, emb, d, h);
 }
+template <typename T>
+void launch_embed_block(const int32_t *tokens, const int32_t *seq_rows, int S, int N, int block_start, int L, const T *emb,
+                        int d, float *h, hipStream_t st) {
+    hipLaunchKernelGGL(embed_kernel<T>, dim3((unsigned)((int64_t)S * L)), dim3(256), 0, st, tokens, seq_rows, N, block_start, L,
+                       emb, d, h);
+}
+
+namespace {
+// one workgroup per row (s, j): the row's rotated keys go to K row len + j of its sequence's cache, its values into
+// column vt_key_slot(len + j) of the transposed value rows
+template <typename T>
+__global__ __launch_bounds__(256) void kv_append_kernel(const T *__restrict__ qkv, int ld_qkv, int L, int n_heads,
+                                                        int n_kv_heads, int d_head, T *__restrict__ k_cache,
+                                                        T *__restrict__ vt_cache, KvPrefix at) {
+    const int64_t r = blockIdx.x;
+    const int s = (int)(r / L), j = (int)(r % L);
+    const int64_t cache = (at.seq_rows ? at.seq_rows[s] : s) / at.seqs_per_cache;
+    const int w = n_kv_heads * d_head;
+    const T *krow = qkv + r * ld_qkv + n_heads * d_head, *vrow = krow + w;
+    T *kdst = k_cache + cache * at.stride_k + (int64_t)(at.len + j) * at.ld_k;
+    T *vdst = vt_cache + cache * at.stride_vt + vt_key_slot(at.len + j);
+    for (int c = threadIdx.x; c < w; c += blockDim.x) {
+        kdst[c] = krow[c];
+        vdst[(int64_t)c * at.ld_vt] = vrow[c];
+    }
+}
+}   // namespace
+
+template <typename T>
+void launch_kv_append(const T *qkv, int ld_qkv, int S, int L, int n_heads, int n_kv_heads, int d_head, T *k_cache, T *vt_cache,
+                      const KvPrefix &at, hipStream_t st) {
+    hipLaunchKernelGGL(kv_append_kernel<T>, dim3((unsigned)(S * L)), dim3(256), 0, st, qkv, ld_qkv, L, n_heads, n_kv_heads, d_head,
+                       k_cache, vt_cache, at);
+}
+template void launch_kv_append<float>(const float *, int, int, int, int, int, int, float *, float *, const KvPrefix &, hipStream_t);
+template void launch_kv_append<bf16_t>(const bf16_t *, int, int, int, int, int, int, bf16_t *, bf16_t *, const KvPrefix &,
+                                       hipStream_t);
 template <typename T>
 void launch_rmsnorm(const float *h, int64_t rows, int d, const float *gain, float eps, T *out, hipStream_t st) {
     hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out, 0, 0, 0, (T *)nullptr);
@@ -195,19 +232,19 @@ void launch_rmsnorm_block(const float *h, int S, int N, int block_start, int L, 
                        packed);
 }
 template <typename T>
-void launch_rope(T *qkv, int ld, int64_t tokens, int N, int n_heads, int n_kv_heads, int d_head, const float *cos_t,
+void launch_rope(T *qkv, int ld, int64_t tokens, int N, int pos0, int n_heads, int n_kv_heads, int d_head, const float *cos_t,
                  const float *sin_t, hipStream_t st) {
-    hipLaunchKernelGGL(rope_kernel<T>, dim3((unsigned)tokens), dim3(256), 0, st, qkv, ld, N, n_heads, n_kv_heads, d_head,
+    hipLaunchKernelGGL(rope_kernel<T>, dim3((unsigned)tokens), dim3(256), 0, st, qkv, ld, N, pos0, n_heads, n_kv_heads, d_head,
                        cos_t, sin_t);
 }
 template <>
-void launch_rope<bf16_t>(bf16_t *qkv, int ld, int64_t tokens, int N, int n_heads, int n_kv_heads, int d_head, const float *cos_t,
+void launch_rope<bf16_t>(bf16_t *qkv, int ld, int64_t tokens, int N, int pos0, int n_heads, int n_kv_heads, int d_head, const float *cos_t,
                          const float *sin_t, hipStream_t st) {
     if (d_head % 16 == 0)
-        hipLaunchKernelGGL(rope_bf16_vec_kernel, dim3((unsigned)tokens), dim3(256), 0, st, qkv, ld, N, n_heads, n_kv_heads, d_head,
+        hipLaunchKernelGGL(rope_bf16_vec_kernel, dim3((unsigned)tokens), dim3(256), 0, st, qkv, ld, N, pos0, n_heads, n_kv_heads, d_head,
                            cos_t, sin_t);
     else
-        hipLaunchKernelGGL(rope_kernel<bf16_t>, dim3((unsigned)tokens), dim3(256), 0, st, qkv, ld, N, n_heads, n_kv_heads, d_head,
+        hipLaunchKernelGGL(rope_kernel<bf16_t>, dim3((unsigned)tokens), dim3(256), 0, st, qkv, ld, N, pos0, n_heads, n_kv_heads, d_head,
                            cos_t, sin_t);
 }
 
@@ -216,8 +253,12 @@ void launch_rope<bf16_t>(bf16_t *qkv, int ld, int64_t tokens, int N, int n_heads
     template void launch_rmsnorm<T>(const float *, int64_t, int, const float *, float, T *, hipStream_t);           \
     template void launch_rmsnorm_block<T>(const float *, int, int, int, int, int, const float *, float, T *, T *,   \
                                           hipStream_t);                                                             \
-    template void launch_rope<T>(T *, int, int64_t, int, int, int, int, const float *, const float *, hipStream_t);
+    template void launch_rope<T>(T *, int, int64_t, int, int, int, int, int, const float *, const float *, hipStream_t);      \
+    template void launch_embed_block<T>(const int32_t *, const int32_t *, int, int, int, int, const T *, int, float *,     \
+                                        hipStream_t);
 INSTANTIATE(float)
 template void launch_embed<bf16_t>(const int32_t *, const int32_t *, int, int, const bf16_t *, int, float *, hipStream_t);
+template void launch_embed_block<bf16_t>(const int32_t *, const int32_t *, int, int, int, int, const bf16_t *, int, float *,
+                                         hipStream_t);
 template void launch_rmsnorm_block<bf16_t>(const float *, int, int, int, int, int, const float *, float, bf16_t *, bf16_t *,
                                            hipStream_t);

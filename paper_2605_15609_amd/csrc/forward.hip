@@ -60,8 +60,8 @@ struct Dispatch<float> {
                                         resid, ldo, st);
     }
     static void attention(psd_handle *, float *qkv, int ld_qkv, float *, int S, int N, int H, int Hkv, int dh, float *out,
-                          hipStream_t st) {
-        launch_plain_attention<float>(qkv, ld_qkv, S, N, H, Hkv, dh, out, st);
+                          const KvPrefix &pre, int block_len, hipStream_t st) {
+        launch_plain_attention<float>(qkv, ld_qkv, S, N, H, Hkv, dh, out, pre, block_len, st);
     }
 };
 
@@ -85,13 +85,15 @@ struct Dispatch<bf16_t> {
             }
         }
     }
+    // pre: KV prefix that every own row sees; block_len > 0: context-causal blocks among the own rows (only the
+    // plain kernel masks; the product path of that attention mode keeps finished blocks in the prefix instead)
     static void attention(psd_handle *h, bf16_t *qkv, int ld_qkv, bf16_t *vT, int S, int N, int H, int Hkv, int dh, bf16_t *out,
-                          hipStream_t st) {
-        if ((h->plain_mask & 2) || (N % 8) != 0) {
-            launch_plain_attention<bf16_t>(qkv, ld_qkv, S, N, H, Hkv, dh, out, st);
+                          const KvPrefix &pre, int block_len, hipStream_t st) {
+        if ((h->plain_mask & 2) || (N % 8) != 0 || (block_len > 0 && block_len < N)) {
+            launch_plain_attention<bf16_t>(qkv, ld_qkv, S, N, H, Hkv, dh, out, pre, block_len, st);
         } else {
             launch_transpose_v(qkv, ld_qkv, S, N, H, Hkv, dh, vT, st);
-            launch_attention_bf16(qkv, ld_qkv, vT, S, N, H, Hkv, dh, out, st);
+            launch_attention_bf16(qkv, ld_qkv, vT, S, N, H, Hkv, dh, out, pre, st);
         }
     }
 };
@@ -126,8 +128,8 @@ int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t 
             Dispatch<T>::gemm(h, a, d, wk, nullptr, d, ntok, Hkv * dh, d, epi_qkv, lw.bk, qkv + H * dh, nullptr, ld_qkv, st);
             Dispatch<T>::gemm(h, a, d, wv, nullptr, d, ntok, Hkv * dh, d, epi_qkv, lw.bv, qkv + (H + Hkv) * dh, nullptr, ld_qkv, st);
         }
-        launch_rope<T>(qkv, ld_qkv, ntok, N, H, Hkv, dh, h->rope_cos, h->rope_sin, st);
-        Dispatch<T>::attention(h, qkv, ld_qkv, vT, S, N, H, Hkv, dh, o, st);
+        launch_rope<T>(qkv, ld_qkv, ntok, N, 0, H, Hkv, dh, h->rope_cos, h->rope_sin, st);
+        Dispatch<T>::attention(h, qkv, ld_qkv, vT, S, N, H, Hkv, dh, o, KvPrefix(), c.attention == PSD_ATTN_BLOCK_CAUSAL ? L : 0, st);
         // After the last attention only the block rows feed the LM-head: the rest of that layer (output
         // projection, FFN) and the final norm run on those S*L rows alone, gathered into a packed stream.
         float *hs = hbuf;
@@ -154,7 +156,83 @@ int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t 
     return PSD_OK;
 }
 
+// The same model call on the L block rows alone, for context-causal block attention: everything before the block
+// is finished, its keys and values sit in the sequence's KV cache (kv.len = block_start positions), and nothing
+// after the block is visible.  S sequences of L rows; with kv.append the rows' keys and values are stored
+// behind the cache (the block is finished and becomes context).
+template <typename T>
+int32_t forward_cached_impl(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N, int block_start,
+                            int L, const KvCacheArg &kv, char *ws, hipStream_t st) {
+    const psd_model_config &c = h->cfg;
+    const ForwardPlan p = plan_forward(c, S, L, L);
+    const int64_t nrow = (int64_t)S * L;
+    const int d = c.d_model, H = c.n_heads, Hkv = c.n_kv_heads, dh = c.d_head, F = c.d_ffn;
+    const int qkv_w = (H + 2 * Hkv) * dh;
+    float *hbuf = (float *)(ws + p.off_h);
+    T *a = (T *)(ws + p.off_a), *qkv = (T *)(ws + p.off_qkv), *vT = (T *)(ws + p.off_vt), *o = (T *)(ws + p.off_o);
+    T *act = (T *)(ws + p.off_act), *y = (T *)(ws + p.off_y);
+    const int ld_act = (int)act_row_stride(c), ld_qkv = (int)qkv_row_stride(qkv_w);
+    const KvLayout lay = kv_layout(c, kv.capacity);
+    KvPrefix pre;
+    pre.len = kv.len;
+    pre.ld_k = (int)lay.ld_k;
+    pre.ld_vt = (int)lay.ld_vt;
+    pre.stride_k = pre.stride_vt = lay.per_seq;
+    pre.seq_rows = seq_rows;
+    pre.seqs_per_cache = kv.seqs_per_cache;
+
+    launch_embed_block<T>(tokens, seq_rows, S, N, block_start, L, (const T *)h->tok_emb, d, hbuf, st);
+    for (size_t li = 0; li < h->layers.size(); ++li) {
+        const psd_handle::Layer &lw = h->layers[li];
+        T *k_cache = (T *)kv.base + (int64_t)li * (lay.k_elems + lay.vt_elems), *vt_cache = k_cache + lay.k_elems;
+        pre.k = k_cache;
+        pre.vt = vt_cache;
+        launch_rmsnorm<T>(hbuf, nrow, d, lw.attn_norm, c.rms_eps, a, st);
+        const int epi_qkv = c.qkv_bias ? EPI_BIAS : EPI_STORE;
+        const T *wq = (const T *)lw.wq, *wk = (const T *)lw.wk, *wv = (const T *)lw.wv;
+        const bool fused = wk == wq + (int64_t)H * dh * d && wv == wk + (int64_t)Hkv * dh * d &&
+                           (!c.qkv_bias || (lw.bk == lw.bq + H * dh && lw.bv == lw.bk + Hkv * dh));
+        if (fused) {
+            Dispatch<T>::gemm(h, a, d, wq, nullptr, d, nrow, qkv_w, d, epi_qkv, lw.bq, qkv, nullptr, ld_qkv, st);
+        } else {
+            Dispatch<T>::gemm(h, a, d, wq, nullptr, d, nrow, H * dh, d, epi_qkv, lw.bq, qkv, nullptr, ld_qkv, st);
+            Dispatch<T>::gemm(h, a, d, wk, nullptr, d, nrow, Hkv * dh, d, epi_qkv, lw.bk, qkv + H * dh, nullptr, ld_qkv, st);
+            Dispatch<T>::gemm(h, a, d, wv, nullptr, d, nrow, Hkv * dh, d, epi_qkv, lw.bv, qkv + (H + Hkv) * dh, nullptr, ld_qkv, st);
+        }
+        launch_rope<T>(qkv, ld_qkv, nrow, L, block_start, H, Hkv, dh, h->rope_cos, h->rope_sin, st);
+        Dispatch<T>::attention(h, qkv, ld_qkv, vT, S, L, H, Hkv, dh, o, pre, 0, st);
+        if (kv.append) launch_kv_append<T>(qkv, ld_qkv, S, L, H, Hkv, dh, k_cache, vt_cache, pre, st);
+        Dispatch<T>::gemm(h, o, H * dh, lw.wo, nullptr, H * dh, nrow, d, H * dh, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, st);
+        launch_rmsnorm<T>(hbuf, nrow, d, lw.ffn_norm, c.rms_eps, a, st);
+        Dispatch<T>::gemm(h, a, d, lw.w_gate, lw.w_up, d, nrow, F, d, EPI_SWIGLU, nullptr, act, nullptr, ld_act, st);
+        Dispatch<T>::gemm(h, act, ld_act, lw.w_down, nullptr, h->w_down_stride, nrow, d, F, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, st);
+    }
+    T *ypack = (c.dtype == PSD_DTYPE_BF16 && h->lm_head_packed && head_stream_supported(S * L, d)) ? (T *)(ws + p.off_ypack) : nullptr;
+    launch_rmsnorm_block<T>(hbuf, S, L, 0, L, d, h->final_norm, c.rms_eps, y, ypack, st);
+    return PSD_OK;
+}
+
 }   // namespace
+
+int32_t run_forward_cached(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N, int block_start, int L,
+                           const KvCacheArg &kv, void *ws, int64_t ws_bytes, hipStream_t st) {
+    const ForwardPlan p = plan_forward(h->cfg, S, L, L);
+    if (ws == nullptr || ws_bytes < p.total)
+        PSD_FAIL(PSD_ERR_WORKSPACE, "workspace of %lld bytes, cached forward over %d x %d rows needs %lld", (long long)ws_bytes,
+                 S, L, (long long)p.total);
+    if ((reinterpret_cast<uintptr_t>(ws) & 255) != 0) PSD_FAIL(PSD_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    if (kv.len != block_start) PSD_FAIL(PSD_ERR_SHAPE, "the cache holds %d positions, the block starts at %d", kv.len, block_start);
+    if (kv.len + L > kv.capacity) PSD_FAIL(PSD_ERR_SHAPE, "cache of %d positions cannot take the block", kv.capacity);
+    if (kv.append && kv.seqs_per_cache != 1) PSD_FAIL(PSD_ERR_INVALID_ARG, "appending needs one sequence per cache");
+    int32_t rc;
+    if (h->cfg.dtype == PSD_DTYPE_BF16)
+        rc = forward_cached_impl<bf16_t>(h, tokens, seq_rows, S, N, block_start, L, kv, (char *)ws, st);
+    else
+        rc = forward_cached_impl<float>(h, tokens, seq_rows, S, N, block_start, L, kv, (char *)ws, st);
+    if (rc != PSD_OK) return rc;
+    PSD_HIP(hipGetLastError());
+    return PSD_OK;
+}
 
 int32_t run_forward_hidden(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N, int block_start,
                            int L, void *ws, int64_t ws_bytes, hipStream_t st) {
@@ -174,9 +252,9 @@ int32_t run_forward_hidden(psd_handle *h, const int32_t *tokens, const int32_t *
 }
 
 int32_t run_head_confidence(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N, int block_start,
-                            int L, int32_t *top1, float *conf, const int32_t *out_rows, void *ws_, hipStream_t st) {
+                            int L, int32_t *top1, float *conf, const int32_t *out_rows, void *ws_, hipStream_t st, int plan_N) {
     const psd_model_config &c = h->cfg;
-    const ForwardPlan p = plan_forward(c, S, N, L);
+    const ForwardPlan p = plan_forward(c, S, plan_N > 0 ? plan_N : N, L);
     char *ws = (char *)ws_;
     const int rows = S * L;
     float *row_sum = (float *)(ws + p.off_rowsum);

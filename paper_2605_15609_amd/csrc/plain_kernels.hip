@@ -67,34 +67,42 @@ __global__ __launch_bounds__(256) void plain_gemm_kernel(const T *__restrict__ A
     }
 }
 
-// one wavefront per (query, head, sequence); scores of all N keys kept in LDS
+// one wavefront per (query, head, sequence); scores of all keys kept in LDS.  Keys = the prefix (KV cache, all
+// visible) followed by the sequence's own N rows, among which block_len > 0 hides the blocks after the query's
 template <typename T>
 __global__ __launch_bounds__(64) void plain_attention_kernel(const T *__restrict__ qkv, int ld, int N, int n_heads,
-                                                             int n_kv_heads, int d_head, T *__restrict__ out) {
+                                                             int n_kv_heads, int d_head, T *__restrict__ out, KvPrefix pre,
+                                                             int block_len) {
     extern __shared__ float smem[];
     float *qs = smem;            // [d_head]
-    float *sc = smem + d_head;   // [N]
+    float *sc = smem + d_head;   // [pre.len + N]
     const int i = blockIdx.x, hd = blockIdx.y, s = blockIdx.z;
     const int lane = threadIdx.x;
     const int row_w = ld;
     const int kvh = hd / (n_heads / n_kv_heads);
     const T *base = qkv + (int64_t)s * N * row_w;
     const T *q = base + (int64_t)i * row_w + hd * d_head;
+    const int64_t cache = pre.len ? (pre.seq_rows ? pre.seq_rows[s] : s) / pre.seqs_per_cache : 0;
+    const T *kc = (const T *)pre.k + cache * pre.stride_k + kvh * d_head;
+    const T *vc = (const T *)pre.vt + cache * pre.stride_vt + (int64_t)kvh * d_head * pre.ld_vt;
+    const int n_keys = pre.len + N;
     for (int c = lane; c < d_head; c += 64) qs[c] = to_float(q[c]);
     __syncthreads();
     const float scale = 1.0f / sqrtf((float)d_head);
     float mx = -INFINITY;
-    for (int jj = lane; jj < N; jj += 64) {
-        const T *k = base + (int64_t)jj * row_w + (n_heads + kvh) * d_head;
+    for (int jj = lane; jj < n_keys; jj += 64) {
+        const int own = jj - pre.len;
+        const T *k = own < 0 ? kc + (int64_t)jj * pre.ld_k : base + (int64_t)own * row_w + (n_heads + kvh) * d_head;
         float dot = 0.f;
         for (int c = 0; c < d_head; ++c) dot = fmaf(qs[c], to_float(k[c]), dot);
         dot *= scale;
+        if (own >= 0 && block_len > 0 && own / block_len > i / block_len) dot = -INFINITY;
         sc[jj] = dot;
         mx = fmaxf(mx, dot);
     }
     for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
     float sum = 0.f;
-    for (int jj = lane; jj < N; jj += 64) {
+    for (int jj = lane; jj < n_keys; jj += 64) {
         const float e = expf(sc[jj] - mx);
         sc[jj] = e;
         sum += e;
@@ -105,9 +113,10 @@ __global__ __launch_bounds__(64) void plain_attention_kernel(const T *__restrict
     T *o = out + ((int64_t)s * N + i) * (n_heads * d_head) + hd * d_head;
     for (int c = lane; c < d_head; c += 64) {
         float acc = 0.f;
+        for (int jj = 0; jj < pre.len; ++jj) acc = fmaf(sc[jj], to_float(vc[(int64_t)c * pre.ld_vt + vt_key_slot(jj)]), acc);
         for (int jj = 0; jj < N; ++jj) {
             const T *v = base + (int64_t)jj * row_w + (n_heads + n_kv_heads + kvh) * d_head;
-            acc = fmaf(sc[jj], to_float(v[c]), acc);
+            acc = fmaf(sc[pre.len + jj], to_float(v[c]), acc);
         }
         o[c] = from_float<T>(acc * inv);
     }
@@ -191,10 +200,11 @@ void launch_plain_gemm(const T *A, const T *W, const T *W2, int64_t M, int Nout,
 }
 
 template <typename T>
-void launch_plain_attention(const T *qkv, int ld, int S, int N, int n_heads, int n_kv_heads, int d_head, T *out, hipStream_t st) {
-    const size_t smem = (size_t)(d_head + N) * sizeof(float);
+void launch_plain_attention(const T *qkv, int ld, int S, int N, int n_heads, int n_kv_heads, int d_head, T *out,
+                            const KvPrefix &pre, int block_len, hipStream_t st) {
+    const size_t smem = (size_t)(d_head + pre.len + N) * sizeof(float);
     hipLaunchKernelGGL(plain_attention_kernel<T>, dim3(N, n_heads, S), dim3(64), smem, st, qkv, ld, N, n_heads, n_kv_heads,
-                       d_head, out);
+                       d_head, out, pre, block_len);
 }
 
 void launch_logits_top1(const float *logits, int rows, int V, int mask_id, float *row_sum, int32_t *row_arg,
@@ -216,5 +226,7 @@ template void launch_plain_gemm<bf16_t, bf16_t>(const bf16_t *, const bf16_t *, 
                                                 const float *, float, bf16_t *, float *, int, hipStream_t);
 template void launch_plain_gemm<bf16_t, float>(const bf16_t *, const bf16_t *, const bf16_t *, int64_t, int, int, int, int, int,
                                                const float *, float, float *, float *, int, hipStream_t);
-template void launch_plain_attention<float>(const float *, int, int, int, int, int, int, float *, hipStream_t);
-template void launch_plain_attention<bf16_t>(const bf16_t *, int, int, int, int, int, int, bf16_t *, hipStream_t);
+template void launch_plain_attention<float>(const float *, int, int, int, int, int, int, float *, const KvPrefix &, int,
+                                            hipStream_t);
+template void launch_plain_attention<bf16_t>(const bf16_t *, int, int, int, int, int, int, bf16_t *, const KvPrefix &, int,
+                                             hipStream_t);

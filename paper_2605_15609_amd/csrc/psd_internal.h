@@ -88,14 +88,64 @@ int32_t run_forward_hidden(psd_handle *h, const int32_t *tokens, const int32_t *
 // LM-head + top-1 confidence on y; out_rows (device, may be NULL) maps slot s -> row of top1/conf.
 int32_t run_head_confidence(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N,
                             int block_start, int L, int32_t *top1, float *conf, const int32_t *out_rows,
-                            void *ws, hipStream_t st);
+                            void *ws, hipStream_t st, int plan_N = -1 /* sequence length the workspace was planned
+                            for, if not N (the cached forward plans for L rows per sequence) */);
+struct KvCacheArg;
+// forward over the L block rows of S sequences against their KV caches (context-causal block attention)
+int32_t run_forward_cached(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N, int block_start, int L,
+                           const KvCacheArg &kv, void *ws, int64_t ws_bytes, hipStream_t st);
 int32_t run_head_logits(psd_handle *h, int S, int N, int L, float *logits, void *ws, hipStream_t st);
+
+// Keys and values that precede a sequence's own rows in attention: a KV cache of `len` positions, shared by
+// seqs_per_cache consecutive sequences (the K drafts of one verification batch share their sequence's prefix).
+// K rows [len][n_kv_heads*d_head] with row stride ld_k; values transposed, [n_kv_heads*d_head][ld_vt] with the keys
+// of every group of 16 in the order 0-3, 8-11, 4-7, 12-15 (the contraction-slot order of the second attention
+// MFMA) and zeros behind position len.  Caches are stride_k / stride_vt elements apart.  len = 0: no prefix.
+struct KvPrefix {
+    const void *k = nullptr, *vt = nullptr;
+    int len = 0, ld_k = 0, ld_vt = 0;
+    int64_t stride_k = 0, stride_vt = 0;
+    const int32_t *seq_rows = nullptr;   // cache of sequence s = (seq_rows ? seq_rows[s] : s) / seqs_per_cache
+    int seqs_per_cache = 1;
+};
+// position of key i inside a transposed value row
+__host__ __device__ inline int vt_key_slot(int i) {
+    const int piece = (i >> 2) & 3;
+    return (i & ~15) | ((((piece & 1) << 1) | (piece >> 1)) << 2) | (i & 3);
+}
+// One sequence's KV cache of `capacity` positions: per layer the K rows, then the transposed values.
+struct KvLayout {
+    int64_t k_elems, vt_elems, ld_k, ld_vt, per_seq;   // elements
+};
+inline KvLayout kv_layout(const psd_model_config &c, int capacity) {
+    KvLayout l;
+    l.ld_k = (int64_t)c.n_kv_heads * c.d_head;
+    l.ld_vt = (capacity + 63) / 64 * 64;
+    l.k_elems = capacity * l.ld_k;
+    l.vt_elems = l.ld_k * l.ld_vt;
+    l.per_seq = c.n_layers * (l.k_elems + l.vt_elems);
+    return l;
+}
+// what a model call may attend to besides its own rows
+struct KvCacheArg {
+    void *base = nullptr;      // NULL: no cache (the call runs over whole sequences)
+    int capacity = 0, len = 0, seqs_per_cache = 1;
+    bool append = false;       // store the rows' keys and values behind position len (seqs_per_cache must be 1)
+};
 
 // ---------------------------------------------------------------- kernel launchers
 // elementwise.hip
 template <typename T>
 void launch_embed(const int32_t *tokens, const int32_t *seq_rows, int S, int N, const T *emb, int d, float *h,
                   hipStream_t st);
+// the same for the L block rows of each sequence only: h [S*L, d]
+template <typename T>
+void launch_embed_block(const int32_t *tokens, const int32_t *seq_rows, int S, int N, int block_start, int L, const T *emb,
+                        int d, float *h, hipStream_t st);
+// keys (rotated) and values of the rows of qkv [S*L, ...] into the caches of their sequences, positions len .. len+L-1
+template <typename T>
+void launch_kv_append(const T *qkv, int ld_qkv, int S, int L, int n_heads, int n_kv_heads, int d_head, T *k_cache, T *vt_cache,
+                      const KvPrefix &at, hipStream_t st);
 template <typename T>
 void launch_rmsnorm(const float *h, int64_t rows, int d, const float *gain, float eps, T *out, hipStream_t st);
 template <typename T>
@@ -105,7 +155,7 @@ void launch_rmsnorm_block(const float *h, int S, int N, int block_start, int L, 
 template <typename T>
 void launch_gather_block_rows(const T *src, T *dst, int width, int S, int N, int block_start, int L, hipStream_t st);
 template <typename T>
-void launch_rope(T *qkv, int ld /* row stride */, int64_t tokens, int N, int n_heads, int n_kv_heads, int d_head, const float *cos_t,
+void launch_rope(T *qkv, int ld /* row stride */, int64_t tokens, int N, int pos0 /* position of row 0 of each sequence */, int n_heads, int n_kv_heads, int d_head, const float *cos_t,
                  const float *sin_t, hipStream_t st);
 // Row strides of the workspace matrices.  Padding rows by 64 elements keeps consecutive rows out of the same
 // cache channel; it pays for the SwiGLU output (24 KB rows feeding the down projection) and was measured
@@ -122,8 +172,10 @@ enum Epilogue { EPI_STORE = 0, EPI_BIAS = 1, EPI_RESIDUAL = 2, EPI_SWIGLU = 3 };
 template <typename T, typename TO>
 void launch_plain_gemm(const T *A, const T *W, const T *W2, int64_t M, int Nout, int Kin, int lda, int ldw, int epi, const float *bias,
                        float scale, TO *out, float *resid, int ldo, hipStream_t st);
+// block_len > 0: context-causal blocks among the own rows (key j visible to query i iff j / block_len <= i / block_len)
 template <typename T>
 void launch_plain_attention(const T *qkv, int ld, int S, int N, int n_heads, int n_kv_heads, int d_head, T *out,
+                            const KvPrefix &pre, int block_len,
                             hipStream_t st);
 void launch_logits_top1(const float *logits, int rows, int V, int mask_id, float *row_sum, int32_t *row_arg,
                         hipStream_t st);
@@ -146,7 +198,7 @@ void launch_gemm_bf16(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int64_
                       const float *bias, bf16_t *out, float *resid, int ldo, hipStream_t st);
 // attention_mfma.hip (bf16, d_head 64 or 128): q, k from qkv (rotary applied), values from vT
 void launch_attention_bf16(const bf16_t *qkv, int ld_qkv, const bf16_t *vT, int S, int N, int n_heads, int n_kv_heads, int d_head,
-                           bf16_t *out, hipStream_t st);
+                           bf16_t *out, const KvPrefix &pre, hipStream_t st);
 // lm_head.hip (bf16): LM-head fused with the online top-1 / sum-exp reduction
 int64_t head_partial_bytes(int rows, int V);
 // fragment-order copies: [ceil(R/32)][K/16][64 lanes][8 bf16]

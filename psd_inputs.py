@@ -53,6 +53,7 @@ class ModelShape:
     qkv_bias: bool
     seed: int
     logit_scale: float = 1.0
+    attention: str = "bidirectional"     # or "block_causal": full attention inside a decoding block, causal across blocks
 
     @property
     def mask_id(self) -> int:

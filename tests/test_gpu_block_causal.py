@@ -1,0 +1,177 @@
+"""Context-causal block attention (one model family of the paper, App. A) with an exact prefix KV cache.
+
+The oracle defines the mode as one masked forward over the whole sequence; the HIP product path runs the block
+rows alone against cached keys and values.  Checked here: (1) the masked whole-sequence forward on the plain
+kernels, (2) prefill + cached forward (stage-1 shape and a verification batch whose drafts share one cache)
+against the oracle's masked forward, fp32 within 1e-4 and bf16 within 2e-2, (3) the cached path equals the
+masked whole-sequence path on the device, (4) a free-running fp32 decode with the cache reproduces the oracle's
+decode token for token, (5) a batched cached decode equals the sequences decoded alone."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import psd_inputs as inp
+from oracle import psd_oracle as orc
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def _bc(shape, **kw):
+    return dataclasses.replace(shape, attention="block_causal", **kw)
+
+
+FP32 = _bc(inp.cut_down(inp.WORKLOADS[4].shape, name="bc-fp32", dtype="fp32", n_layers=2, d_model=96, n_heads=6, n_kv_heads=2,
+                        d_head=16, d_ffn=160, vocab=211, seed=41))
+BF16 = {
+    "mha-dh64": _bc(inp.cut_down(inp.WORKLOADS[2].shape, n_layers=2, vocab=5000, seed=42)),
+    "gqa-bias-dh128": _bc(inp.cut_down(inp.WORKLOADS[4].shape, n_layers=2, d_model=512, n_heads=4, n_kv_heads=2, d_ffn=640,
+                                       vocab=3001, seed=43)),
+}
+
+
+def _state(shape, N, P, L, block, seed, n_committed):
+    """prompt, `block` finished generation blocks, an active block with n_committed tokens, masks behind."""
+    rng = np.random.default_rng(seed)
+    t = np.full(N, shape.mask_id, dtype=np.int32)
+    start = P + block * L
+    t[:start] = inp.draw_prompt(shape.vocab, start, seed)
+    idx = rng.choice(L, size=n_committed, replace=False)
+    t[start + idx] = rng.integers(0, shape.vocab - 1, size=n_committed)
+    return t, start
+
+
+def _check(shape, host, logits, top1, conf, t, start, L, tol, label):
+    from tests.test_gpu_forward import check_sequence
+    o_top1, o_conf, z = orc.forward_confidence(host, t, start, L, return_logits=True, block_causal=True)
+    return check_sequence((o_top1, o_conf, z, None), logits, top1, conf, t, shape.mask_id, start, L, tol, label)
+
+
+@pytest.mark.parametrize("L", [16, 32, 64])
+def test_fp32_cached_and_masked_paths_match_the_oracle(L):
+    import paper_2605_15609_amd as psd
+    from tests.gpu_common import say
+    shape = FP32
+    P, N = 2 * L, 5 * L
+    host = inp.draw_model(shape, N)
+    model = psd.Model.from_host(host, DEV)
+    cache = psd.KvCache(model, 1, N)
+    for block in (0, 2):
+        t, start = _state(shape, N, P, L, block, 7 + block, L // 3)
+        d = _dev(t[None])
+        # masked attention over the whole sequence (plain kernels)
+        logits = psd.psd_forward_logits(model, d, start, L).cpu().numpy()
+        top1, conf = psd.psd_forward_confidence(model, d, start, L)
+        e1 = _check(shape, host, logits, top1[0].cpu().numpy(), conf[0].cpu().numpy(), t, start, L, 1e-4, f"fp32 masked L={L}")[0]
+        # the block rows against the prefix cache
+        cache.reset()
+        psd.psd_kv_prefill(model, d, start, L, cache)
+        c_top1, c_conf, c_logits = psd.psd_forward_confidence_cached(model, d, start, L, cache, want_logits=True)
+        e2 = _check(shape, host, c_logits.cpu().numpy(), c_top1[0].cpu().numpy(), c_conf[0].cpu().numpy(), t, start, L, 1e-4,
+                    f"fp32 cached L={L}")[0]
+        say(f"[block-causal] fp32 L={L} block {block}: logits max-abs err masked {e1:.2e}, cached {e2:.2e}")
+
+
+@pytest.mark.parametrize("name", list(BF16))
+@pytest.mark.parametrize("plain", [0, 7], ids=["mfma", "plain"])
+def test_bf16_cached_forward_matches_the_oracle_and_the_masked_device_path(name, plain):
+    import paper_2605_15609_amd as psd
+    from tests.gpu_common import say
+    shape = BF16[name]
+    L, K = 32, 4
+    P, N = 3 * L, 6 * L
+    host = inp.draw_model(shape, N)
+    model = psd.Model.from_host(host, DEV)
+    model.set_plain(plain)
+    cache = psd.KvCache(model, 2, N)
+    # two sequences with their own prompts and one finished generation block each
+    seqs = [_state(shape, N, P, L, 1, 20 + b, 5 + 3 * b) for b in range(2)]
+    start = seqs[0][1]
+    d = _dev(np.stack([t for t, _ in seqs]))
+    psd.psd_kv_prefill(model, d, start, L, cache)
+    top1, conf, logits = psd.psd_forward_confidence_cached(model, d, start, L, cache, want_logits=True)
+    logits = logits.cpu().numpy().reshape(2, L, -1)
+    for b, (t, _) in enumerate(seqs):
+        err = _check(shape, host, logits[b], top1[b].cpu().numpy(), conf[b].cpu().numpy(), t, start, L, 2e-2,
+                     f"{name} cached stage-1 seq {b}")[0]
+        say(f"[block-causal] {name} plain={plain} stage-1 seq {b}: logits max-abs err {err:.3e}")
+    # a verification batch: K drafts per sequence sharing that sequence's cache
+    rng = np.random.default_rng(5)
+    drafts = []
+    for b, (t, _) in enumerate(seqs):
+        for k in range(K):
+            dft = t.copy()
+            masked = np.nonzero(dft[start: start + L] == shape.mask_id)[0]
+            fill = masked[: 2 * k]
+            dft[start + fill] = rng.integers(0, shape.vocab - 1, size=len(fill))
+            drafts.append(dft)
+    dd = _dev(np.stack(drafts))
+    v_top1, v_conf, v_logits = psd.psd_forward_confidence_cached(model, dd, start, L, cache, seqs_per_cache=K, want_logits=True)
+    v_logits = v_logits.cpu().numpy().reshape(2 * K, L, -1)
+    for i in (1, K - 1, K + 2, 2 * K - 1):
+        err = _check(shape, host, v_logits[i], v_top1[i].cpu().numpy(), v_conf[i].cpu().numpy(), drafts[i], start, L, 2e-2,
+                     f"{name} cached verify draft {i}")[0]
+        say(f"[block-causal] {name} plain={plain} verify draft {i}: logits max-abs err {err:.3e}")
+    # the masked whole-sequence forward on the device agrees with the cached one to rounding
+    m_logits = psd.psd_forward_logits(model, dd, start, L).cpu().numpy().reshape(2 * K, L, -1)
+    assert np.abs(m_logits - v_logits).max() < 2e-2
+
+
+def test_fp32_free_running_cached_decode_matches_the_oracle_decode():
+    import paper_2605_15609_amd as psd
+    shape = FP32
+    L, P, G = 16, 32, 48
+    N = P + G
+    host = inp.draw_model(shape, N)
+    model = psd.Model.from_host(host, DEV)
+    for K, tau in ((3, 0.9), (4, 0.05), (1, 0.9)):
+        tokens0 = np.full((1, N), shape.mask_id, dtype=np.int32)
+        tokens0[0, :P] = inp.draw_prompt(shape.vocab, P, 61)
+        d = _dev(tokens0)
+        cache = psd.KvCache(model, 1, N)
+        psd.psd_kv_prefill(model, d, P, L, cache)
+        stats = [psd.Stats()]
+        for start in range(P, N, L):
+            stats = psd.psd_decode_block_cached(model, d, start, L, psd.Policy(tau, 1, 0), psd.chain_graph(K), cache, stats)
+        ref, ostats = orc.decode(orc.model_confidence_fn(host, block_causal=True), tokens0[0], P, L, orc.Policy(tau, 1, 0),
+                                 orc.chain_graph(K), shape.mask_id)
+        assert (d.cpu().numpy()[0] == ref).all(), (K, tau)
+        s = stats[0]
+        assert (s.invocations, s.tokens_policy, s.tokens_draft, s.tokens_postverify) == \
+               (ostats.invocations, ostats.tokens_policy, ostats.tokens_draft, ostats.tokens_postverify)
+        assert s.depth_hist[:32] == ostats.depth_hist
+
+
+def test_bf16_batched_cached_decode_equals_sequences_alone_and_the_masked_decode():
+    import paper_2605_15609_amd as psd
+    shape = dataclasses.replace(BF16["mha-dh64"], logit_scale=14.0)
+    L, P, G, K, B = 32, 64, 64, 3, 3
+    N = P + G
+    host = inp.draw_model(shape, N)
+    model = psd.Model.from_host(host, DEV)
+    policy, graph = psd.Policy(0.9, 1, 0), psd.chain_graph(K)
+    tokens = np.full((B, N), shape.mask_id, dtype=np.int32)
+    for b in range(B):
+        tokens[b, :P] = inp.draw_prompt(shape.vocab, P, 70 + b)
+
+    def run(batch):
+        d = _dev(batch)
+        cache = psd.KvCache(model, batch.shape[0], N)
+        psd.psd_kv_prefill(model, d, P, L, cache)
+        stats = [psd.Stats() for _ in range(batch.shape[0])]
+        for start in range(P, N, L):
+            stats = psd.psd_decode_block_cached(model, d, start, L, policy, graph, cache, stats)
+        return d.cpu().numpy(), stats
+
+    together, st_all = run(tokens)
+    assert not (together == shape.mask_id).any()
+    for b in range(B):
+        alone, st = run(tokens[b: b + 1])
+        assert (alone[0] == together[b]).all()
+        assert st[0].invocations == st_all[b].invocations and st[0].tokens == st_all[b].tokens == G
