@@ -76,6 +76,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (a known-size reference for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--attention", choices=["bidirectional", "block-causal"], default="bidirectional",
+                    help="block-causal: the same shapes as a context-causal block model (App. A) decoded on the block rows "
+                         "against an exact prefix KV cache (prefill included in the step)")
     ap.add_argument("--max-blocks", type=int, default=0,
                     help="decode only the first blocks of the generation region (0 = all); tokens/s counts what was decoded")
     args = ap.parse_args()
@@ -97,6 +100,9 @@ def main():
     w = inp.WORKLOADS[args.config]
     if args.logit_scale != 1.0:
         w = dataclasses.replace(w, shape=dataclasses.replace(w.shape, logit_scale=args.logit_scale))
+    cached = args.attention == "block-causal"
+    if cached:
+        w = dataclasses.replace(w, shape=dataclasses.replace(w.shape, attention="block_causal"))
     shape = w.shape
     torch.cuda.set_device(0)
     t0 = time.perf_counter()
@@ -111,11 +117,24 @@ def main():
         n_blocks = min(n_blocks, args.max_blocks)
     gen_end = w.prompt_len + n_blocks * w.block_len
 
+    cache = psd.KvCache(model, w.batch, w.seq_len) if cached else None
+    prefill_ms = []
+
     def one_decode():
         toks = tokens0.clone()
         stats = [psd.Stats() for _ in range(w.batch)]
+        if cached:
+            cache.reset()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            psd.psd_kv_prefill(model, toks, w.prompt_len, w.block_len, cache)
+            e1.record()
+            prefill_ms.append((e0, e1))
         for block_start in range(w.prompt_len, gen_end, w.block_len):
-            stats = psd.psd_decode_block(model, toks, block_start, w.block_len, policy, graph, stats)
+            if cached:
+                stats = psd.psd_decode_block_cached(model, toks, block_start, w.block_len, policy, graph, cache, stats)
+            else:
+                stats = psd.psd_decode_block(model, toks, block_start, w.block_len, policy, graph, stats)
         return toks, stats
 
     for _ in range(args.warmup):
@@ -127,7 +146,8 @@ def main():
     lib = psd.load_library()
     if bf16:
         # the tile the dispatcher picks for the verification pass's SwiGLU contraction
-        swiglu_tile = lib.psd_kernel_gemm_tile(w.batch * w.n_drafts * w.seq_len, shape.d_ffn, 3)
+        rows_per_seq = w.block_len if cached else w.seq_len        # rows a model call runs over
+        swiglu_tile = lib.psd_kernel_gemm_tile(w.batch * w.n_drafts * rows_per_seq, shape.d_ffn, 3)
         model.probe_begin(3, swiglu_tile)
         model.probe_begin(4, 0)
     t0 = time.perf_counter()
@@ -158,6 +178,14 @@ def main():
                         "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
                         "kernel": f"mfma::gemm_bf16_kernel, SwiGLU gate/up contraction, tile {lib.psd_kernel_gemm_tile_name(swiglu_tile).decode()}", "launches": int(launches),
                         "avg_launch_us": ms * 1e3 / launches, "flops_per_launch": flops / launches}
+            # rows per launch from the FLOP count (4 d F per row); below the ridge (315 FLOP/B) the launch is a
+            # weight stream: algorithmic bytes = both weight matrices once + activations in + out
+            rows_total = flops / (4.0 * shape.d_model * shape.d_ffn)
+            by = launches * 2.0 * shape.d_ffn * shape.d_model * 2 + rows_total * (shape.d_model + shape.d_ffn) * 2
+            if flops / by < 315:
+                gbs = by / (ms * 1e-3) / 1e9
+                roofline.update({"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                                 "bytes_per_launch": by / launches, "tflops": achieved})
 
     if args.calibrate_copy:
         src = torch.ones(64 << 20, dtype=torch.float32, device="cuda:0")
@@ -191,8 +219,8 @@ def main():
 
     # whole-forward accounting for the verification pass (MFMA utilisation of the model call)
     # (per-sequence call counts: a stage-1 call is one sequence-forward, a verify call K of them)
-    work_v = psd.forward_work(model, w.n_drafts, w.seq_len, w.block_len)
-    work_1 = psd.forward_work(model, 1, w.seq_len, w.block_len)
+    work_v = psd.forward_work(model, w.n_drafts, w.block_len if cached else w.seq_len, w.block_len)
+    work_1 = psd.forward_work(model, 1, w.block_len if cached else w.seq_len, w.block_len)
     flops_decode = n_stage1 * (work_1["gemm_flops"] + work_1["attn_flops"] + work_1["head_flops"]) + \
                    n_verify * (work_v["gemm_flops"] + work_v["attn_flops"] + work_v["head_flops"])
     out = {
@@ -208,10 +236,14 @@ def main():
                    "tokens_draft": int(sum(s.tokens_draft for s in stats)),
                    "tokens_postverify": int(sum(s.tokens_postverify for s in stats)),
                    "model_tflops_per_s_whole_decode": flops_decode / (elapsed / args.steps) / 1e12,
-                   "weights_setup_s": t_weights},
+                   "weights_setup_s": t_weights, "attention": args.attention},
         "roofline": roofline,
         "lm_head_roofline": lm_head,
     }
+    if cached:
+        torch.cuda.synchronize()
+        out["config"]["prefill_ms"] = float(np.mean([a.elapsed_time(b) for a, b in prefill_ms[-args.steps:]]))
+        out["config"]["workload"] += ", context-causal block attention with prefix KV cache (prefill inside the step)"
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, n_tokens, n_stage1, n_verify, os.cpu_count() or 1)
     else:

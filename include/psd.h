@@ -279,6 +279,14 @@ int32_t psd_forward_work(const psd_model_config *cfg, int32_t S, int32_t N, int3
 int32_t psd_kernel_gemm_bf16(const void *A, const void *W, const void *W2, int64_t M, int32_t Nout, int32_t Kin,
                              int32_t lda, int32_t ldw, int32_t epilogue, const float *bias, void *out, float *resid,
                              int32_t ldo, void *stream);
+/* The residual contraction (epilogue 2, dense A, W and resid) cut into k_splits parts along K (0 = the choice
+ * the forward makes for this shape, possibly 1; otherwise 1..8 with Kin a multiple of 64*k_splits): part 0
+ * adds into resid, the others go to `partial` (device, (k_splits-1)*M*Nout floats) and are then added
+ * to resid in order by a second kernel, so that resid ends as resid + A W^T.  *used_splits (host, may be
+ * NULL) receives the number of parts. */
+int32_t psd_kernel_gemm_residual_splitk(const void *A, const void *W, int64_t M, int32_t Nout, int32_t Kin,
+                                        float *resid, float *partial, int64_t partial_bytes, int32_t k_splits,
+                                        int32_t *used_splits, void *stream);
 int64_t psd_kernel_attention_scratch_bytes(int32_t S, int32_t N, int32_t n_kv_heads, int32_t d_head);
 int32_t psd_kernel_attention_bf16(const void *qkv, int32_t ld_qkv, int32_t S, int32_t N, int32_t n_heads,
                                   int32_t n_kv_heads, int32_t d_head, void *vT, void *out, void *stream);

@@ -102,6 +102,7 @@ def load_library():
         "psd_decode_block": (i32, [vp, vp, i32, i32, i32, i32, C.POINTER(_Policy), C.POINTER(_Graph), C.POINTER(_Stats),
                                    vp, i64, vp]),
         "psd_kernel_gemm_bf16": (i32, [vp, vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp, i32, vp]),
+        "psd_kernel_gemm_residual_splitk": (i32, [vp, vp, i64, i32, i32, vp, vp, i64, i32, vp, vp]),
         "psd_kernel_attention_scratch_bytes": (i64, [i32, i32, i32, i32]),
         "psd_kernel_attention_bf16": (i32, [vp, i32, i32, i32, i32, i32, i32, vp, vp, vp]),
         "psd_kernel_head_scratch_bytes": (i64, [i32, i32]),
@@ -513,6 +514,23 @@ def kernel_gemm_bf16(A: torch.Tensor, W: torch.Tensor, epilogue: int = EPI_STORE
     _check(lib.psd_kernel_gemm_bf16(_ptr(A), _ptr(W), _ptr(W2), M, Nout, K, lda, ldw, epilogue, _ptr(bias), _ptr(out), None,
                                     out.stride(0), _stream()))
     return out
+
+
+def kernel_gemm_residual_splitk(A: torch.Tensor, W: torch.Tensor, resid: torch.Tensor, k_splits: int = 0,
+                                partial: Optional[torch.Tensor] = None) -> int:
+    """resid fp32 [M, N] += A W^T with the K range cut into k_splits parts (0 = the forward's choice);
+    returns the number of parts used."""
+    lib = load_library()
+    M, K = A.shape
+    Nout = W.shape[0]
+    assert A.is_contiguous() and W.is_contiguous()
+    assert resid.dtype == torch.float32 and resid.is_contiguous() and resid.shape == (M, Nout)
+    if partial is None:
+        partial = torch.empty((7 * M * Nout,), dtype=torch.float32, device=A.device)
+    used = C.c_int32(0)
+    _check(lib.psd_kernel_gemm_residual_splitk(_ptr(A), _ptr(W), M, Nout, K, _ptr(resid), _ptr(partial),
+                                               partial.numel() * 4, k_splits, C.byref(used), _stream()))
+    return used.value
 
 
 def kernel_attention_bf16(qkv: torch.Tensor, S: int, N: int, n_heads: int, n_kv_heads: int, d_head: int,

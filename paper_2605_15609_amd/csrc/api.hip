@@ -587,6 +587,24 @@ int32_t psd_kernel_gemm_bf16(const void *A, const void *W, const void *W2, int64
     return PSD_OK;
 }
 
+int32_t psd_kernel_gemm_residual_splitk(const void *A, const void *W, int64_t M, int32_t Nout, int32_t Kin, float *resid,
+                                        float *partial, int64_t partial_bytes, int32_t k_splits, int32_t *used_splits,
+                                        void *stream) {
+    if (!A || !W || !resid || M < 1 || M > (1 << 30) || Nout < 1 || Kin < 1) PSD_FAIL(PSD_ERR_INVALID_ARG, "bad GEMM arguments");
+    if (Kin % 64 || Nout % 64) PSD_FAIL(PSD_ERR_SHAPE, "Nout and Kin must be multiples of 64");
+    if (k_splits < 0 || k_splits > 8) PSD_FAIL(PSD_ERR_INVALID_ARG, "k_splits %d", k_splits);
+    const int splits = k_splits == 0 ? gemm_bf16_splits(M, Nout, Kin) : k_splits;
+    if (Kin % (64 * splits)) PSD_FAIL(PSD_ERR_SHAPE, "Kin must be a multiple of 64 * k_splits");
+    if (splits > 1 && (!partial || partial_bytes < (int64_t)(splits - 1) * M * Nout * 4))
+        PSD_FAIL(PSD_ERR_WORKSPACE, "partial sums need %lld bytes", (long long)((int64_t)(splits - 1) * M * Nout * 4));
+    launch_gemm_bf16_split((const bf16_t *)A, (const bf16_t *)W, M, Nout, Kin, Kin, Kin, resid, Nout, partial, splits,
+                           (hipStream_t)stream);
+    launch_fold_partials(resid, M, Nout, Nout, partial, splits - 1, (hipStream_t)stream);
+    PSD_HIP(hipGetLastError());
+    if (used_splits) *used_splits = splits;
+    return PSD_OK;
+}
+
 int64_t psd_kernel_attention_scratch_bytes(int32_t S, int32_t N, int32_t n_kv_heads, int32_t d_head) {
     if (S < 1 || N < 1 || n_kv_heads < 1 || d_head < 1) return -1;
     return (int64_t)S * vt_row_stride(N) * n_kv_heads * d_head * 2;

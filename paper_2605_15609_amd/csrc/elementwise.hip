@@ -30,19 +30,25 @@ __device__ __forceinline__ float block_sum(float v, float *smem) {
     return tot;
 }
 
-// out[r, :] = h[src(r), :] * rsqrt(mean(h^2) + eps) * gain ; src(r) = r, or the block rows of each sequence
+// out[r, :] = h[src(r), :] * rsqrt(mean(h^2) + eps) * gain ; src(r) = r, or the block rows of each sequence.
+// Pending K-split partial sums of the contraction that wrote h last are added first, in order, and the row of
+// h is brought up to date.
 template <typename T>
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ h, int d, const float *__restrict__ gain,
+__global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ h, int d, const float *__restrict__ gain,
                                                       float eps, T *__restrict__ out, int N, int block_start, int L,
-                                                      T *__restrict__ packed) {
+                                                      T *__restrict__ packed, PendingSums pend) {
     __shared__ float smem[4];
     const int64_t r = blockIdx.x;
     int64_t src = r;
     if (L > 0) src = (r / L) * N + block_start + (r % L);
-    const float *x = h + src * d;
+    float *x = h + src * d;
     float ss = 0.f;
     for (int c = threadIdx.x; c < d; c += blockDim.x) {
-        const float v = x[c];
+        float v = x[c];
+        if (pend.n > 0) {
+            for (int s = 0; s < pend.n; ++s) v += pend.partial[s * pend.stride + src * d + c];
+            x[c] = v;
+        }
         ss += v * v;
     }
     ss = block_sum(ss, smem);
@@ -59,11 +65,11 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *__restrict__ 
 
 // the layer norms of the bf16 path: one workgroup per row, the row (d <= 8192) held in registers between the
 // two passes, 32-byte loads and 16-byte stores
-__global__ __launch_bounds__(256) void rmsnorm_bf16_vec_kernel(const float *__restrict__ h, int d, const float *__restrict__ gain,
-                                                               float eps, bf16_t *__restrict__ out) {
+__global__ __launch_bounds__(256) void rmsnorm_bf16_vec_kernel(float *__restrict__ h, int d, const float *__restrict__ gain,
+                                                               float eps, bf16_t *__restrict__ out, PendingSums pend) {
     __shared__ float smem[4];
     const int64_t r = blockIdx.x;
-    const float4 *x = reinterpret_cast<const float4 *>(h + r * d);
+    float4 *x = reinterpret_cast<float4 *>(h + r * d);
     const float4 *g = reinterpret_cast<const float4 *>(gain);
     constexpr int MAXV = 4;                 // 8 floats per chunk, up to 4 chunks per thread: d <= 8192
     float4 v[MAXV][2];
@@ -75,6 +81,16 @@ __global__ __launch_bounds__(256) void rmsnorm_bf16_vec_kernel(const float *__re
         if (c < nchunk) {
             v[i][0] = x[2 * c];
             v[i][1] = x[2 * c + 1];
+            if (pend.n > 0) {
+                for (int s = 0; s < pend.n; ++s) {
+                    const float4 *q = reinterpret_cast<const float4 *>(pend.partial + s * pend.stride + r * d);
+                    const float4 q0 = q[2 * c], q1 = q[2 * c + 1];
+                    v[i][0].x += q0.x; v[i][0].y += q0.y; v[i][0].z += q0.z; v[i][0].w += q0.w;
+                    v[i][1].x += q1.x; v[i][1].y += q1.y; v[i][1].z += q1.z; v[i][1].w += q1.w;
+                }
+                x[2 * c] = v[i][0];
+                x[2 * c + 1] = v[i][1];
+            }
             ss += v[i][0].x * v[i][0].x + v[i][0].y * v[i][0].y + v[i][0].z * v[i][0].z + v[i][0].w * v[i][0].w;
             ss += v[i][1].x * v[i][1].x + v[i][1].y * v[i][1].y + v[i][1].z * v[i][1].z + v[i][1].w * v[i][1].w;
         }
@@ -214,22 +230,42 @@ template void launch_kv_append<float>(const float *, int, int, int, int, int, in
 template void launch_kv_append<bf16_t>(const bf16_t *, int, int, int, int, int, int, bf16_t *, bf16_t *, const KvPrefix &,
                                        hipStream_t);
 template <typename T>
-void launch_rmsnorm(const float *h, int64_t rows, int d, const float *gain, float eps, T *out, hipStream_t st) {
-    hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out, 0, 0, 0, (T *)nullptr);
+void launch_rmsnorm(float *h, int64_t rows, int d, const float *gain, float eps, T *out, PendingSums pend, hipStream_t st) {
+    hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out, 0, 0, 0, (T *)nullptr,
+                       pend);
 }
 template <>
-void launch_rmsnorm<bf16_t>(const float *h, int64_t rows, int d, const float *gain, float eps, bf16_t *out, hipStream_t st) {
+void launch_rmsnorm<bf16_t>(float *h, int64_t rows, int d, const float *gain, float eps, bf16_t *out, PendingSums pend,
+                            hipStream_t st) {
     if (d % 8 == 0 && d <= 8192)
-        hipLaunchKernelGGL(rmsnorm_bf16_vec_kernel, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out);
+        hipLaunchKernelGGL(rmsnorm_bf16_vec_kernel, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out, pend);
     else
         hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out, 0, 0, 0,
-                           (bf16_t *)nullptr);
+                           (bf16_t *)nullptr, pend);
 }
 template <typename T>
-void launch_rmsnorm_block(const float *h, int S, int N, int block_start, int L, int d, const float *gain, float eps,
-                          T *out, T *packed, hipStream_t st) {
+void launch_rmsnorm_block(float *h, int S, int N, int block_start, int L, int d, const float *gain, float eps,
+                          T *out, T *packed, PendingSums pend, hipStream_t st) {
     hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3((unsigned)(S * L)), dim3(256), 0, st, h, d, gain, eps, out, N, block_start, L,
-                       packed);
+                       packed, pend);
+}
+
+namespace {
+__global__ __launch_bounds__(256) void fold_partials_kernel(float *__restrict__ resid, int cols, int ldo,
+                                                            const float *__restrict__ partial, int n_partial, int64_t stride) {
+    const int64_t r = blockIdx.x;
+    for (int c = threadIdx.x; c < cols; c += blockDim.x) {
+        float v = resid[r * ldo + c];
+        for (int s = 0; s < n_partial; ++s) v += partial[s * stride + r * cols + c];
+        resid[r * ldo + c] = v;
+    }
+}
+}   // namespace
+
+void launch_fold_partials(float *resid, int64_t rows, int cols, int ldo, const float *partial, int n_partial, hipStream_t st) {
+    if (n_partial > 0)
+        hipLaunchKernelGGL(fold_partials_kernel, dim3((unsigned)rows), dim3(256), 0, st, resid, cols, ldo, partial, n_partial,
+                           rows * (int64_t)cols);
 }
 template <typename T>
 void launch_rope(T *qkv, int ld, int64_t tokens, int N, int pos0, int n_heads, int n_kv_heads, int d_head, const float *cos_t,
@@ -250,9 +286,9 @@ void launch_rope<bf16_t>(bf16_t *qkv, int ld, int64_t tokens, int N, int pos0, i
 
 #define INSTANTIATE(T)                                                                                              \
     template void launch_embed<T>(const int32_t *, const int32_t *, int, int, const T *, int, float *, hipStream_t); \
-    template void launch_rmsnorm<T>(const float *, int64_t, int, const float *, float, T *, hipStream_t);           \
-    template void launch_rmsnorm_block<T>(const float *, int, int, int, int, int, const float *, float, T *, T *,   \
-                                          hipStream_t);                                                             \
+    template void launch_rmsnorm<T>(float *, int64_t, int, const float *, float, T *, PendingSums, hipStream_t);    \
+    template void launch_rmsnorm_block<T>(float *, int, int, int, int, int, const float *, float, T *, T *,         \
+                                          PendingSums, hipStream_t);                                                \
     template void launch_rope<T>(T *, int, int64_t, int, int, int, int, int, const float *, const float *, hipStream_t);      \
     template void launch_embed_block<T>(const int32_t *, const int32_t *, int, int, int, int, const T *, int, float *,     \
                                         hipStream_t);
@@ -260,5 +296,5 @@ INSTANTIATE(float)
 template void launch_embed<bf16_t>(const int32_t *, const int32_t *, int, int, const bf16_t *, int, float *, hipStream_t);
 template void launch_embed_block<bf16_t>(const int32_t *, const int32_t *, int, int, int, int, const bf16_t *, int, float *,
                                          hipStream_t);
-template void launch_rmsnorm_block<bf16_t>(const float *, int, int, int, int, int, const float *, float, bf16_t *, bf16_t *,
-                                           hipStream_t);
+template void launch_rmsnorm_block<bf16_t>(float *, int, int, int, int, int, const float *, float, bf16_t *, bf16_t *,
+                                           PendingSums, hipStream_t);

@@ -28,6 +28,7 @@ ForwardPlan plan_forward(const psd_model_config &cfg, int64_t S, int64_t N, int6
     p.off_vt = take(S * vt_row_stride(N) * (int64_t)cfg.n_kv_heads * cfg.d_head * esz);
     p.off_o = take(T * (int64_t)cfg.n_heads * cfg.d_head * esz);
     p.off_act = take(T * act_row_stride(cfg) * esz);
+    p.off_ksplit = take(cfg.dtype == PSD_DTYPE_BF16 ? ksplit_bytes(cfg) : 0);
     p.off_oc = take(rows * (int64_t)cfg.n_heads * cfg.d_head * esz);   // last layer: attention output and residual
     p.off_hc = take(rows * cfg.d_model * 4);                           // stream of the block rows only
     p.off_y = take(rows * cfg.d_model * esz);
@@ -54,10 +55,11 @@ struct Dispatch;
 template <>
 struct Dispatch<float> {
     // A [M, Kin] with row stride lda; weights [Nout, Kin] with row stride ldw
-    static void gemm(psd_handle *, const float *A, int lda, const void *W, const void *W2, int ldw, int64_t M, int Nout, int Kin,
-                     int epi, const float *bias, float *out, float *resid, int ldo, hipStream_t st) {
+    static PendingSums gemm(psd_handle *, const float *A, int lda, const void *W, const void *W2, int ldw, int64_t M, int Nout,
+                            int Kin, int epi, const float *bias, float *out, float *resid, int ldo, float *, hipStream_t st) {
         launch_plain_gemm<float, float>(A, (const float *)W, (const float *)W2, M, Nout, Kin, lda, ldw, epi, bias, 1.0f, out,
                                         resid, ldo, st);
+        return PendingSums();
     }
     static void attention(psd_handle *, float *qkv, int ld_qkv, float *, int S, int N, int H, int Hkv, int dh, float *out,
                           const KvPrefix &pre, int block_len, hipStream_t st) {
@@ -67,12 +69,21 @@ struct Dispatch<float> {
 
 template <>
 struct Dispatch<bf16_t> {
-    static void gemm(psd_handle *h, const bf16_t *A, int lda, const void *W, const void *W2, int ldw, int64_t M, int Nout, int Kin,
-                     int epi, const float *bias, bf16_t *out, float *resid, int ldo, hipStream_t st) {
+    // returns the K-split partial sums (left in `ksplit`) that the next reader of resid has to add
+    static PendingSums gemm(psd_handle *h, const bf16_t *A, int lda, const void *W, const void *W2, int ldw, int64_t M, int Nout,
+                            int Kin, int epi, const float *bias, bf16_t *out, float *resid, int ldo, float *ksplit,
+                            hipStream_t st) {
+        PendingSums pend;
         if (h->plain_mask & 1)
             launch_plain_gemm<bf16_t, bf16_t>(A, (const bf16_t *)W, (const bf16_t *)W2, M, Nout, Kin, lda, ldw, epi, bias, 1.0f, out,
                                               resid, ldo, st);
-        else {
+        else if (const int splits = (epi == EPI_RESIDUAL && ksplit && ldo == Nout) ? gemm_bf16_splits(M, Nout, Kin) : 1;
+                 splits > 1 && (splits - 1) * M * Nout * 4 <= ksplit_bytes(h->cfg)) {
+            launch_gemm_bf16_split(A, (const bf16_t *)W, M, Nout, Kin, lda, ldw, resid, ldo, ksplit, splits, st);
+            pend.partial = ksplit;
+            pend.n = splits - 1;
+            pend.stride = M * Nout;
+        } else {
             psd_handle::Probe &pr = h->probe;
             const bool timed = pr.enabled && epi == pr.epi && gemm_bf16_tile(M, Nout, epi) == pr.tile &&
                                pr.used + 2 <= pr.ev.size();
@@ -84,6 +95,7 @@ struct Dispatch<bf16_t> {
                 pr.flops += 2.0 * (double)M * Nout * Kin * (epi == EPI_SWIGLU ? 2.0 : 1.0);
             }
         }
+        return pend;
     }
     // pre: KV prefix that every own row sees; block_len > 0: context-causal blocks among the own rows (only the
     // plain kernel masks; the product path of that attention mode keeps finished blocks in the prefix instead)
@@ -111,22 +123,27 @@ int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t 
     T *act = (T *)(ws + p.off_act), *y = (T *)(ws + p.off_y);
     const int ld_act = (int)act_row_stride(c), ld_qkv = (int)qkv_row_stride(qkv_w);
 
-    const float *final_in = hbuf;
+    float *final_in = hbuf;
+    // No K-split on this path: the sums of a sequence's rows must not depend on how many sequences share the
+    // call (whole-sequence results are bit-identical across batch sizes; only the block-row path trades that for
+    // bandwidth at small row counts).
+    float *ksplit = nullptr;
+    PendingSums pend;   // stays empty here; the norms take it for the block-row path
     launch_embed<T>(tokens, seq_rows, S, N, (const T *)h->tok_emb, d, hbuf, st);
     for (size_t li = 0; li < h->layers.size(); ++li) {
         const psd_handle::Layer &lw = h->layers[li];
-        launch_rmsnorm<T>(hbuf, ntok, d, lw.attn_norm, c.rms_eps, a, st);
+        launch_rmsnorm<T>(hbuf, ntok, d, lw.attn_norm, c.rms_eps, a, pend, st);
         const int epi_qkv = c.qkv_bias ? EPI_BIAS : EPI_STORE;
         // one launch when wq | wk | wv (and the biases) sit back to back in memory, as one [qkv_w, d] matrix
         const T *wq = (const T *)lw.wq, *wk = (const T *)lw.wk, *wv = (const T *)lw.wv;
         const bool fused = wk == wq + (int64_t)H * dh * d && wv == wk + (int64_t)Hkv * dh * d &&
                            (!c.qkv_bias || (lw.bk == lw.bq + H * dh && lw.bv == lw.bk + Hkv * dh));
         if (fused) {
-            Dispatch<T>::gemm(h, a, d, wq, nullptr, d, ntok, qkv_w, d, epi_qkv, lw.bq, qkv, nullptr, ld_qkv, st);
+            Dispatch<T>::gemm(h, a, d, wq, nullptr, d, ntok, qkv_w, d, epi_qkv, lw.bq, qkv, nullptr, ld_qkv, nullptr, st);
         } else {
-            Dispatch<T>::gemm(h, a, d, wq, nullptr, d, ntok, H * dh, d, epi_qkv, lw.bq, qkv, nullptr, ld_qkv, st);
-            Dispatch<T>::gemm(h, a, d, wk, nullptr, d, ntok, Hkv * dh, d, epi_qkv, lw.bk, qkv + H * dh, nullptr, ld_qkv, st);
-            Dispatch<T>::gemm(h, a, d, wv, nullptr, d, ntok, Hkv * dh, d, epi_qkv, lw.bv, qkv + (H + Hkv) * dh, nullptr, ld_qkv, st);
+            Dispatch<T>::gemm(h, a, d, wq, nullptr, d, ntok, H * dh, d, epi_qkv, lw.bq, qkv, nullptr, ld_qkv, nullptr, st);
+            Dispatch<T>::gemm(h, a, d, wk, nullptr, d, ntok, Hkv * dh, d, epi_qkv, lw.bk, qkv + H * dh, nullptr, ld_qkv, nullptr, st);
+            Dispatch<T>::gemm(h, a, d, wv, nullptr, d, ntok, Hkv * dh, d, epi_qkv, lw.bv, qkv + (H + Hkv) * dh, nullptr, ld_qkv, nullptr, st);
         }
         launch_rope<T>(qkv, ld_qkv, ntok, N, 0, H, Hkv, dh, h->rope_cos, h->rope_sin, st);
         Dispatch<T>::attention(h, qkv, ld_qkv, vT, S, N, H, Hkv, dh, o, KvPrefix(), c.attention == PSD_ATTN_BLOCK_CAUSAL ? L : 0, st);
@@ -143,16 +160,16 @@ int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t 
             launch_gather_block_rows<T>(o, os, H * dh, S, N, block_start, L, st);
             final_in = hs;
         }
-        Dispatch<T>::gemm(h, os, H * dh, lw.wo, nullptr, H * dh, nrow, d, H * dh, EPI_RESIDUAL, nullptr, nullptr, hs, d, st);
-        launch_rmsnorm<T>(hs, nrow, d, lw.ffn_norm, c.rms_eps, a, st);
-        Dispatch<T>::gemm(h, a, d, lw.w_gate, lw.w_up, d, nrow, F, d, EPI_SWIGLU, nullptr, act, nullptr, ld_act, st);
-        Dispatch<T>::gemm(h, act, ld_act, lw.w_down, nullptr, h->w_down_stride, nrow, d, F, EPI_RESIDUAL, nullptr, nullptr, hs, d, st);
+        pend = Dispatch<T>::gemm(h, os, H * dh, lw.wo, nullptr, H * dh, nrow, d, H * dh, EPI_RESIDUAL, nullptr, nullptr, hs, d, ksplit, st);
+        launch_rmsnorm<T>(hs, nrow, d, lw.ffn_norm, c.rms_eps, a, pend, st);
+        Dispatch<T>::gemm(h, a, d, lw.w_gate, lw.w_up, d, nrow, F, d, EPI_SWIGLU, nullptr, act, nullptr, ld_act, nullptr, st);
+        pend = Dispatch<T>::gemm(h, act, ld_act, lw.w_down, nullptr, h->w_down_stride, nrow, d, F, EPI_RESIDUAL, nullptr, nullptr, hs, d, ksplit, st);
     }
     T *ypack = (c.dtype == PSD_DTYPE_BF16 && h->lm_head_packed && head_stream_supported(S * L, d)) ? (T *)(ws + p.off_ypack) : nullptr;
     if (final_in != hbuf)   // already the packed block rows
-        launch_rmsnorm_block<T>(final_in, S, L, 0, L, d, h->final_norm, c.rms_eps, y, ypack, st);
+        launch_rmsnorm_block<T>(final_in, S, L, 0, L, d, h->final_norm, c.rms_eps, y, ypack, pend, st);
     else
-        launch_rmsnorm_block<T>(hbuf, S, N, block_start, L, d, h->final_norm, c.rms_eps, y, ypack, st);
+        launch_rmsnorm_block<T>(hbuf, S, N, block_start, L, d, h->final_norm, c.rms_eps, y, ypack, pend, st);
     return PSD_OK;
 }
 
@@ -181,34 +198,36 @@ int32_t forward_cached_impl(psd_handle *h, const int32_t *tokens, const int32_t 
     pre.seq_rows = seq_rows;
     pre.seqs_per_cache = kv.seqs_per_cache;
 
+    float *ksplit = c.dtype == PSD_DTYPE_BF16 ? (float *)(ws + p.off_ksplit) : nullptr;
+    PendingSums pend;
     launch_embed_block<T>(tokens, seq_rows, S, N, block_start, L, (const T *)h->tok_emb, d, hbuf, st);
     for (size_t li = 0; li < h->layers.size(); ++li) {
         const psd_handle::Layer &lw = h->layers[li];
         T *k_cache = (T *)kv.base + (int64_t)li * (lay.k_elems + lay.vt_elems), *vt_cache = k_cache + lay.k_elems;
         pre.k = k_cache;
         pre.vt = vt_cache;
-        launch_rmsnorm<T>(hbuf, nrow, d, lw.attn_norm, c.rms_eps, a, st);
+        launch_rmsnorm<T>(hbuf, nrow, d, lw.attn_norm, c.rms_eps, a, pend, st);
         const int epi_qkv = c.qkv_bias ? EPI_BIAS : EPI_STORE;
         const T *wq = (const T *)lw.wq, *wk = (const T *)lw.wk, *wv = (const T *)lw.wv;
         const bool fused = wk == wq + (int64_t)H * dh * d && wv == wk + (int64_t)Hkv * dh * d &&
                            (!c.qkv_bias || (lw.bk == lw.bq + H * dh && lw.bv == lw.bk + Hkv * dh));
         if (fused) {
-            Dispatch<T>::gemm(h, a, d, wq, nullptr, d, nrow, qkv_w, d, epi_qkv, lw.bq, qkv, nullptr, ld_qkv, st);
+            Dispatch<T>::gemm(h, a, d, wq, nullptr, d, nrow, qkv_w, d, epi_qkv, lw.bq, qkv, nullptr, ld_qkv, nullptr, st);
         } else {
-            Dispatch<T>::gemm(h, a, d, wq, nullptr, d, nrow, H * dh, d, epi_qkv, lw.bq, qkv, nullptr, ld_qkv, st);
-            Dispatch<T>::gemm(h, a, d, wk, nullptr, d, nrow, Hkv * dh, d, epi_qkv, lw.bk, qkv + H * dh, nullptr, ld_qkv, st);
-            Dispatch<T>::gemm(h, a, d, wv, nullptr, d, nrow, Hkv * dh, d, epi_qkv, lw.bv, qkv + (H + Hkv) * dh, nullptr, ld_qkv, st);
+            Dispatch<T>::gemm(h, a, d, wq, nullptr, d, nrow, H * dh, d, epi_qkv, lw.bq, qkv, nullptr, ld_qkv, nullptr, st);
+            Dispatch<T>::gemm(h, a, d, wk, nullptr, d, nrow, Hkv * dh, d, epi_qkv, lw.bk, qkv + H * dh, nullptr, ld_qkv, nullptr, st);
+            Dispatch<T>::gemm(h, a, d, wv, nullptr, d, nrow, Hkv * dh, d, epi_qkv, lw.bv, qkv + (H + Hkv) * dh, nullptr, ld_qkv, nullptr, st);
         }
         launch_rope<T>(qkv, ld_qkv, nrow, L, block_start, H, Hkv, dh, h->rope_cos, h->rope_sin, st);
         Dispatch<T>::attention(h, qkv, ld_qkv, vT, S, L, H, Hkv, dh, o, pre, 0, st);
         if (kv.append) launch_kv_append<T>(qkv, ld_qkv, S, L, H, Hkv, dh, k_cache, vt_cache, pre, st);
-        Dispatch<T>::gemm(h, o, H * dh, lw.wo, nullptr, H * dh, nrow, d, H * dh, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, st);
-        launch_rmsnorm<T>(hbuf, nrow, d, lw.ffn_norm, c.rms_eps, a, st);
-        Dispatch<T>::gemm(h, a, d, lw.w_gate, lw.w_up, d, nrow, F, d, EPI_SWIGLU, nullptr, act, nullptr, ld_act, st);
-        Dispatch<T>::gemm(h, act, ld_act, lw.w_down, nullptr, h->w_down_stride, nrow, d, F, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, st);
+        pend = Dispatch<T>::gemm(h, o, H * dh, lw.wo, nullptr, H * dh, nrow, d, H * dh, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, ksplit, st);
+        launch_rmsnorm<T>(hbuf, nrow, d, lw.ffn_norm, c.rms_eps, a, pend, st);
+        Dispatch<T>::gemm(h, a, d, lw.w_gate, lw.w_up, d, nrow, F, d, EPI_SWIGLU, nullptr, act, nullptr, ld_act, nullptr, st);
+        pend = Dispatch<T>::gemm(h, act, ld_act, lw.w_down, nullptr, h->w_down_stride, nrow, d, F, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, ksplit, st);
     }
     T *ypack = (c.dtype == PSD_DTYPE_BF16 && h->lm_head_packed && head_stream_supported(S * L, d)) ? (T *)(ws + p.off_ypack) : nullptr;
-    launch_rmsnorm_block<T>(hbuf, S, L, 0, L, d, h->final_norm, c.rms_eps, y, ypack, st);
+    launch_rmsnorm_block<T>(hbuf, S, L, 0, L, d, h->final_norm, c.rms_eps, y, ypack, pend, st);
     return PSD_OK;
 }
 

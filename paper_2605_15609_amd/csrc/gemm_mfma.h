@@ -17,6 +17,9 @@
 // rows i = 8*(v/4) + 4*(lane/32) + v%4.  The epilogue is a template policy:
 //   EPI_STORE / EPI_BIAS   out = bf16(acc (+ bias[j]))                     QKV projection
 //   EPI_RESIDUAL           resid[i, j] += acc           (fp32 stream)       O and down projections
+//                          With k_splits > 1 the K range is cut into equal parts, one workgroup per (tile,
+//                          part): part 0 adds into resid, part s > 0 stores its sum to partial[s - 1] (same
+//                          shape, dense rows), and whoever reads the stream next adds the partials in order.
 //   EPI_SWIGLU             out = bf16(silu(X Yg^T) * (X Yu^T))              gate and up in one pass
 //   EPI_TOP1               per column j: running (max, argmax, sum-exp) over the rows i
 //                          (LM-head with X = W_lm, Y = hidden rows; logits never stored)
@@ -81,7 +84,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
                                                         const bf16_t *__restrict__ Y2, int M, int Nout, int Kin, int ldx, int ldy,
                                                         const float *__restrict__ bias, bf16_t *__restrict__ out,
                                                         float *__restrict__ resid, int ldo, int tiles_n, int n_tiles,
-                                                        Top1Args t1) {
+                                                        Top1Args t1, int k_splits, float *__restrict__ partial) {
     extern __shared__ __align__(16) unsigned char lds[];
     constexpr bool DUAL = EPI == EPI_SWIGLU;
     constexpr int BN_OUT = DUAL ? BN / 2 : BN;            // output columns per tile
@@ -92,7 +95,12 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
     static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "every wavefront moves whole 8-row groups of both tiles");
 
     // XCD-aware tile id: ids i, i+8, i+16 ... land on the same XCD; give that XCD a contiguous tile range
-    int pid = blockIdx.x;
+    int pid = blockIdx.x, split = 0;
+    if (EPI == EPI_RESIDUAL && k_splits > 1) {
+        split = pid / n_tiles;
+        pid -= split * n_tiles;
+    }
+    const int k_len = Kin / k_splits, k_beg = split * k_len;   // this workgroup's K range
     if (n_tiles % 8 == 0) pid = (pid % 8) * (n_tiles / 8) + pid / 8;
     // Each XCD has its own L2, so its tile range should re-use what it fetches: the range is cut along the
     // dimension of the LARGER operand (each XCD then reads an eighth of it, plus all of the small one), and
@@ -130,11 +138,11 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
     // are rejected by the descriptor's range check (they only feed outputs that are never stored).
     const int rows_x = min(BM, M - m0), rows_y = min(BN_OUT, Nout - n0);
     const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<bf16_t *>(X) + (int64_t)m0 * ldx, 0, ((rows_x - 1) * ldx + Kin) * 2, 0x00020000);
+        const_cast<bf16_t *>(X) + (int64_t)m0 * ldx + k_beg, 0, ((rows_x - 1) * ldx + Kin - k_beg) * 2, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrc_y = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<bf16_t *>(Y) + (int64_t)n0 * ldy, 0, ((rows_y - 1) * ldy + Kin) * 2, 0x00020000);
+        const_cast<bf16_t *>(Y) + (int64_t)n0 * ldy + k_beg, 0, ((rows_y - 1) * ldy + Kin - k_beg) * 2, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrc_y2 = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<bf16_t *>(DUAL ? Y2 : Y) + (int64_t)n0 * ldy, 0, ((rows_y - 1) * ldy + Kin) * 2, 0x00020000);
+        const_cast<bf16_t *>(DUAL ? Y2 : Y) + (int64_t)n0 * ldy + k_beg, 0, ((rows_y - 1) * ldy + Kin - k_beg) * 2, 0x00020000);
     const int uwave = __builtin_amdgcn_readfirstlane(wave);
     const int dma_key = (((uwave & 1) << 2) + (lane >> 4)) & 7;
     const int voff_x = (lane >> 3) * ldx * 2 + (((lane & 7) ^ dma_key) << 4);
@@ -187,7 +195,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
         asm volatile("" ::: "memory");                                                                        \
     }
 
-    const int nk = Kin / BK;
+    const int nk = k_len / BK;
     const int lrow = lane & 31, lhalf = lane >> 5;
 
     // LDS byte offsets of this lane's fragment rows (k-step 0); k-step kk flips the chunk index by 2*kk
@@ -341,9 +349,12 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
                         const float u = acc[i][j + TN / 2][v];
                         x = x / (1.0f + __expf(-x)) * u;
                     }
-                    if (EPI == EPI_RESIDUAL)
-                        resid[(int64_t)m * ldo + n] += x;
-                    else
+                    if (EPI == EPI_RESIDUAL) {
+                        if (split == 0)
+                            resid[(int64_t)m * ldo + n] += x;
+                        else
+                            partial[((int64_t)(split - 1) * M + m) * Nout + n] = x;
+                    } else
                         out[(int64_t)m * ldo + n] = from_float<bf16_t>(x);
                 }
             }
@@ -352,7 +363,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
 
 template <int BM, int BN, int WGM, int WGN, int EPI, int NSA = 2, int NSB = NSA>
 void launch_cfg(const bf16_t *X, const bf16_t *Y, const bf16_t *Y2, int M, int Nout, int Kin, int ldx, int ldy, const float *bias,
-                bf16_t *out, float *resid, int ldo, Top1Args t1, hipStream_t st) {
+                bf16_t *out, float *resid, int ldo, Top1Args t1, hipStream_t st, int k_splits = 1, float *partial = nullptr) {
     constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (Nout + BN_OUT - 1) / BN_OUT;
     const int n_tiles = tiles_m * tiles_n;
@@ -364,8 +375,9 @@ void launch_cfg(const bf16_t *X, const bf16_t *Y, const bf16_t *Y2, int M, int N
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(n_tiles), dim3(WGM * WGN * 64), smem, st, X, Y, Y2, M, Nout, Kin, ldx, ldy, bias, out, resid, ldo, tiles_n,
-                       n_tiles, t1);
+    if (EPI != EPI_RESIDUAL) k_splits = 1;
+    hipLaunchKernelGGL(kern, dim3(n_tiles * k_splits), dim3(WGM * WGN * 64), smem, st, X, Y, Y2, M, Nout, Kin, ldx, ldy, bias, out, resid,
+                       ldo, tiles_n, n_tiles, t1, k_splits, partial);
 }
 
 }   // namespace mfma

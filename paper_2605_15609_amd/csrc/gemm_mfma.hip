@@ -52,8 +52,11 @@ bool tile_fits(int tile, int epi) { return epi != EPI_SWIGLU || tile == 0 || til
 
 }   // namespace
 
-static int g_force_tile = -1;
-void gemm_bf16_force_tile(int tile) { g_force_tile = tile; }
+static int g_force_tile = -1, g_force_splits = 0;
+void gemm_bf16_force_tile(int tile) {
+    g_force_tile = tile < 0 ? -1 : (tile & 0xff);
+    g_force_splits = tile < 0 ? 0 : (tile >> 8);
+}
 int gemm_bf16_tile_count() { return kNumTiles; }
 const char *gemm_bf16_tile_name(int tile) { return tile >= 0 && tile < kNumTiles ? kTiles[tile].name : "?"; }
 
@@ -64,7 +67,8 @@ int gemm_bf16_tile(int64_t M, int Nout, int epi) {
     auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((cols + bn - 1) / bn); };
     // SwiGLU reads two weight operands against one activation tile: the big tile as soon as it
     // reaches half of the CUs
-    if (dual) return tiles(256, 256) >= 128 ? 1 : 0;
+    // (a single row tile is a pure weight stream: the deep equal rings keep more of it in flight)
+    if (dual) return tiles(256, 256) >= 128 ? 1 : (M <= 128 ? 5 : 0);
     // At most one 128x128 workgroup per CU: the contraction is bound by fetch latency, not by the
     // matrix cores; small tiles reach every CU and the deep rings keep several stages in flight.
     if (tiles(128, 128) <= 256) {
@@ -92,6 +96,34 @@ int gemm_bf16_tile(int64_t M, int Nout, int epi) {
         }
     }
     return best;
+}
+
+// A residual contraction over at most 128 rows is a weight stream with one row tile and few column tiles: far too
+// few workgroups to keep HBM busy.  It is cut along K instead, one 128x128 workgroup (rings 4/4) per (column tile,
+// K part), up to 256 workgroups; every part keeps at least 8 K stages.  Part 0 adds into resid, the others store
+// partial sums that the next reader of resid adds in order (at most 7 * 128 rows: cheap at this size; for taller
+// contractions the extra pass costs more than the split gains, measured).
+int gemm_bf16_splits(int64_t M, int Nout, int Kin) {
+    int splits = 1;
+    if (g_force_splits > 0) {
+        splits = g_force_splits;
+    } else if (g_force_tile < 0 && M <= 128) {
+        const int64_t tiles = (Nout + 127) / 128;
+        for (int s = 8; s >= 2; s >>= 1)
+            if (tiles * s <= 256 && Kin / s >= 8 * BK && Kin % (s * BK) == 0) {
+                splits = s;
+                break;
+            }
+    }
+    if (splits > 8 || splits < 1 || Kin % (splits * BK) != 0) splits = 1;
+    return splits;
+}
+
+void launch_gemm_bf16_split(const bf16_t *A, const bf16_t *W, int64_t M, int Nout, int Kin, int lda, int ldw, float *resid, int ldo,
+                            float *partial, int splits, hipStream_t st) {
+    Top1Args none = {};
+    launch_cfg<128, 128, 2, 2, EPI_RESIDUAL, 4, 4>(A, W, nullptr, (int)M, Nout, Kin, lda, ldw, nullptr, nullptr, resid, ldo, none, st,
+                                                     splits, partial);
 }
 
 void launch_gemm_bf16(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int64_t M, int Nout, int Kin, int lda, int ldw, int epi,

@@ -76,8 +76,10 @@ void launch_accept(int32_t *tokens, const int32_t *drafts, int B, int N, int blo
                    int32_t *n_left, int32_t *devstats, hipStream_t st);
 
 // ---------------------------------------------------------------- forward (forward.hip)
+// workspace for the K-split partial sums of a residual contraction: at most 7 parts of at most 128 rows
+inline int64_t ksplit_bytes(const psd_model_config &c) { return 7ll * 128 * c.d_model * 4; }
 struct ForwardPlan {
-    int64_t off_h, off_a, off_qkv, off_vt, off_o, off_act, off_oc, off_hc, off_y, off_ypack, off_rowsum, off_rowarg, off_part, total;
+    int64_t off_h, off_a, off_qkv, off_vt, off_o, off_act, off_ksplit, off_oc, off_hc, off_y, off_ypack, off_rowsum, off_rowarg, off_part, total;
 };
 ForwardPlan plan_forward(const psd_model_config &cfg, int64_t S, int64_t N, int64_t L);
 
@@ -146,11 +148,19 @@ void launch_embed_block(const int32_t *tokens, const int32_t *seq_rows, int S, i
 template <typename T>
 void launch_kv_append(const T *qkv, int ld_qkv, int S, int L, int n_heads, int n_kv_heads, int d_head, T *k_cache, T *vt_cache,
                       const KvPrefix &at, hipStream_t st);
+// K-split partial sums that still have to be added to the residual stream h [rows, d]: partial[s] has the
+// same shape, s = 0 .. n-1, `stride` floats apart.  The norm that reads h next adds them (and stores h).
+struct PendingSums {
+    const float *partial = nullptr;
+    int n = 0;
+    int64_t stride = 0;
+};
 template <typename T>
-void launch_rmsnorm(const float *h, int64_t rows, int d, const float *gain, float eps, T *out, hipStream_t st);
+void launch_rmsnorm(float *h, int64_t rows, int d, const float *gain, float eps, T *out, PendingSums pend, hipStream_t st);
 template <typename T>
-void launch_rmsnorm_block(const float *h, int S, int N, int block_start, int L, int d, const float *gain,
-                          float eps, T *out, T *packed /* fragment-order copy, may be NULL */, hipStream_t st);
+void launch_rmsnorm_block(float *h, int S, int N, int block_start, int L, int d, const float *gain,
+                          float eps, T *out, T *packed /* fragment-order copy, may be NULL */, PendingSums pend,
+                          hipStream_t st);
 // dst [S*L, width] <- the L block rows of each of the S sequences of src [S*N, width]
 template <typename T>
 void launch_gather_block_rows(const T *src, T *dst, int width, int S, int N, int block_start, int L, hipStream_t st);
@@ -189,6 +199,12 @@ void launch_head_finish(const float *row_sum, const int32_t *row_arg, const int3
 // 8, 9: 256x256 with 8 wavefronts as 2x4 / 4x2)
 int gemm_bf16_tile(int64_t M, int Nout, int epi);
 int gemm_bf16_tile_count();
+// K-split of a residual contraction (1 = none).  With s > 1 parts, launch_gemm_bf16_split adds part 0 into
+// resid and stores parts 1..s-1 to partial [s-1][M][Nout] fp32; the next reader of resid adds them in order.
+int gemm_bf16_splits(int64_t M, int Nout, int Kin);
+void launch_gemm_bf16_split(const bf16_t *A, const bf16_t *W, int64_t M, int Nout, int Kin, int lda, int ldw, float *resid, int ldo,
+                            float *partial, int splits, hipStream_t st);
+void launch_fold_partials(float *resid, int64_t rows, int cols, int ldo, const float *partial, int n_partial, hipStream_t st);
 const char *gemm_bf16_tile_name(int tile);
 void gemm_bf16_force_tile(int tile);   // debug: -1 = automatic
 // 256 workgroups x 4 wavefronts x iters x 16 MFMAs (32x32x16 bf16) on the given operand data; sink >= 4 MiB

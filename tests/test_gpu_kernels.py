@@ -109,6 +109,37 @@ def test_gemm_every_tile_configuration(epi):
         lib.psd_debug_force_gemm_tile(-1)
 
 
+SPLITK_CASES = [("c3-block-down", 128, 4096, 12288, (0, 8)), ("c3-block-o", 128, 4096, 4096, (0, 8)),
+                ("c3-stage1-block-down", 32, 4096, 12288, (0, 4)), ("c4-block-down", 192, 3584, 18944, (0, 2, 4)),
+                ("c4-block-o", 96, 3584, 3584, (0,)), ("ragged", 77, 832, 1536, (1, 2, 3, 4, 6, 8))]
+
+
+@pytest.mark.parametrize("label,M,N,K,splits", SPLITK_CASES, ids=[c[0] for c in SPLITK_CASES])
+def test_gemm_residual_split_along_k(label, M, N, K, splits):
+    """Residual contraction over few rows cut along K (one workgroup per column tile and K part, partial sums
+    added in order afterwards): every row against the fp64 product, and bit-for-bit repeatable."""
+    from paper_2605_15609_amd import binding as B
+    rng = np.random.default_rng(len(label) * 1000 + M)
+    A = bf16_round_trip(rng.standard_normal((M, K), dtype=np.float32))
+    W = bf16_round_trip(rng.standard_normal((N, K), dtype=np.float32) * 0.05)
+    resid0 = rng.standard_normal((M, N)).astype(np.float32)
+    dA, dW = dev_bf16(A), dev_bf16(W)
+    ref = A.astype(np.float64) @ W.astype(np.float64).T + resid0
+    tol = 1e-3 * np.sqrt(K / 4096) + 1e-6 * np.abs(ref)
+    for s in splits:
+        print(f"[kernels] split-K gemm {label} k_splits={s}", flush=True)
+        outs = []
+        for _ in range(2):
+            d_res = torch.from_numpy(resid0).to(DEV)
+            used = B.kernel_gemm_residual_splitk(dA, dW, d_res, s)
+            outs.append(d_res.cpu().numpy())
+        assert s == 0 or used == s
+        assert not (s == 0 and M <= 128 and K >= 4096) or used > 1, "few rows and a long K must be split"
+        err = np.abs(outs[0].astype(np.float64) - ref)
+        assert (err <= tol).all(), f"{label} k_splits={s} (used {used}): max err {err.max():.3e}"
+        assert np.array_equal(outs[0], outs[1]), f"{label} k_splits={s}: two runs differ"
+
+
 ATTN_CASES = [("c3v", 4, 512, 32, 32, 128), ("c4v-gqa", 6, 1024, 28, 4, 128), ("c2v", 4, 384, 8, 8, 64),
               ("c5-len", 2, 1280, 32, 32, 128), ("ragged", 3, 200, 4, 2, 64)]
 
