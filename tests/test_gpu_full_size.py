@@ -89,3 +89,42 @@ def test_full_depth_both_launch_shapes_on_a_shared_sequence(cfg):
             f"{time.perf_counter() - t0:.0f} s")
         del logits
     model.close()
+
+
+def test_config3_full_depth_block_causal_with_kv_cache():
+    """The same 8B-parameter shape as a context-causal block model: prefill of the prompt and one finished block
+    into the KV cache, then the block-row model call in both launch shapes (1 x 32 rows; 4 drafts x 32 rows sharing
+    the cache) against the oracle's masked whole-sequence forward."""
+    _need_memory()
+    import dataclasses
+    import torch
+    import paper_2605_15609_amd as psd
+    from tests.gpu_common import say, to_dev
+    from tests.test_gpu_forward import check_sequence
+    w = inp.WORKLOADS[3]
+    shape = dataclasses.replace(w.shape, attention="block_causal")
+    N, L, K = w.seq_len, w.block_len, w.n_drafts
+    start = w.prompt_len + L
+    t0 = time.perf_counter()
+    host = inp.draw_model(shape, N, threads=16)
+    model = psd.Model.from_host(host)
+    say(f"[full-size] block-causal config 3 drawn and uploaded after {time.perf_counter() - t0:.0f} s")
+    states = [_state(shape, N, start, L, 300 + i, 3 + 5 * i) for i in range(K)]
+    for t in states:
+        t[:start] = states[0][:start]                     # the drafts of one sequence share everything before the block
+    cache = psd.KvCache(model, 1, N)
+    psd.psd_kv_prefill(model, to_dev(states[0][None]), start, L, cache)
+    o_top1, o_conf, z = orc.forward_confidence(host, states[0], start, L, return_logits=True, block_causal=True)
+    z_b = orc.block_logits(host, states[0], start, L, operands="bf16", block_causal=True)
+    say(f"[full-size] oracle evaluated draft 0 after {time.perf_counter() - t0:.0f} s")
+    for label, batch in (("cfg3-block-causal/stage-1 shape (1 x 32 rows)", states[:1]),
+                         (f"cfg3-block-causal/verify shape ({K} x 32 rows, shared cache)", states)):
+        top1, conf, logits = psd.psd_forward_confidence_cached(model, to_dev(np.stack(batch)), start, L, cache,
+                                                               seqs_per_cache=len(batch), want_logits=True)
+        torch.cuda.synchronize()
+        logits = logits.cpu().numpy().reshape(len(batch), L, -1)
+        err, tol, near, wide = check_sequence((o_top1, o_conf, z, z_b), logits[0], top1[0].cpu().numpy(), conf[0].cpu().numpy(),
+                                              states[0], shape.mask_id, start, L, 2e-2, label)
+        say(f"[full-size] {label}: logits max-abs err {err:.3e} (tol {tol:.3e}), near-ties {near}, inside the band {wide}; "
+            f"{time.perf_counter() - t0:.0f} s")
+    model.close()
