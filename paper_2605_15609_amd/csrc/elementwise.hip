@@ -63,12 +63,15 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ h, int
     }
 }
 
-// the layer norms of the bf16 path: one workgroup per row, the row (d <= 8192) held in registers between the
-// two passes, 32-byte loads and 16-byte stores
+// the norms of the bf16 path: one workgroup per row, the row (d <= 8192) held in registers between the
+// two passes, 32-byte loads and 16-byte stores.  L > 0: output row r is block row r % L of sequence r / L;
+// packed: second copy in MFMA-fragment order (a thread's 8 values are one 16-byte operand slot there too)
 __global__ __launch_bounds__(256) void rmsnorm_bf16_vec_kernel(float *__restrict__ h, int d, const float *__restrict__ gain,
-                                                               float eps, bf16_t *__restrict__ out, PendingSums pend) {
+                                                               float eps, bf16_t *__restrict__ out, PendingSums pend, int N,
+                                                               int block_start, int L, bf16_t *__restrict__ packed) {
     __shared__ float smem[4];
-    const int64_t r = blockIdx.x;
+    const int64_t r_out = blockIdx.x;
+    const int64_t r = L > 0 ? (r_out / L) * N + block_start + (r_out % L) : r_out;
     float4 *x = reinterpret_cast<float4 *>(h + r * d);
     const float4 *g = reinterpret_cast<const float4 *>(gain);
     constexpr int MAXV = 4;                 // 8 floats per chunk, up to 4 chunks per thread: d <= 8192
@@ -97,7 +100,9 @@ __global__ __launch_bounds__(256) void rmsnorm_bf16_vec_kernel(float *__restrict
     }
     ss = block_sum(ss, smem);
     const float inv = 1.0f / sqrtf(ss / (float)d + eps);
-    uint4 *o = reinterpret_cast<uint4 *>(out + r * d);
+    uint4 *o = reinterpret_cast<uint4 *>(out + r_out * d);
+    uint4 *op = reinterpret_cast<uint4 *>(packed);
+    const int64_t nks = d / 16;
 #pragma unroll
     for (int i = 0; i < MAXV; ++i) {
         const int c = i * 256 + threadIdx.x;
@@ -109,6 +114,8 @@ __global__ __launch_bounds__(256) void rmsnorm_bf16_vec_kernel(float *__restrict
             w.z = pack_bf16x2(v[i][1].x * inv * g1.x, v[i][1].y * inv * g1.y);
             w.w = pack_bf16x2(v[i][1].z * inv * g1.z, v[i][1].w * inv * g1.w);
             o[c] = w;
+            // fragment order [row / 32][k / 16][64 lanes][8]: lane = (k / 8 % 2) * 32 + row % 32, chunk c = k / 8
+            if (packed) op[((r_out >> 5) * nks + (c >> 1)) * 64 + (c & 1) * 32 + (r_out & 31)] = w;
         }
     }
 }
@@ -238,7 +245,8 @@ template <>
 void launch_rmsnorm<bf16_t>(float *h, int64_t rows, int d, const float *gain, float eps, bf16_t *out, PendingSums pend,
                             hipStream_t st) {
     if (d % 8 == 0 && d <= 8192)
-        hipLaunchKernelGGL(rmsnorm_bf16_vec_kernel, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out, pend);
+        hipLaunchKernelGGL(rmsnorm_bf16_vec_kernel, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out, pend, 0, 0, 0,
+                           (bf16_t *)nullptr);
     else
         hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out, 0, 0, 0,
                            (bf16_t *)nullptr, pend);
@@ -248,6 +256,16 @@ void launch_rmsnorm_block(float *h, int S, int N, int block_start, int L, int d,
                           T *out, T *packed, PendingSums pend, hipStream_t st) {
     hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3((unsigned)(S * L)), dim3(256), 0, st, h, d, gain, eps, out, N, block_start, L,
                        packed, pend);
+}
+template <>
+void launch_rmsnorm_block<bf16_t>(float *h, int S, int N, int block_start, int L, int d, const float *gain, float eps,
+                                  bf16_t *out, bf16_t *packed, PendingSums pend, hipStream_t st) {
+    if (d % 16 == 0 && d <= 8192)
+        hipLaunchKernelGGL(rmsnorm_bf16_vec_kernel, dim3((unsigned)(S * L)), dim3(256), 0, st, h, d, gain, eps, out, pend, N,
+                           block_start, L, packed);
+    else
+        hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3((unsigned)(S * L)), dim3(256), 0, st, h, d, gain, eps, out, N, block_start,
+                           L, packed, pend);
 }
 
 namespace {
@@ -296,5 +314,4 @@ INSTANTIATE(float)
 template void launch_embed<bf16_t>(const int32_t *, const int32_t *, int, int, const bf16_t *, int, float *, hipStream_t);
 template void launch_embed_block<bf16_t>(const int32_t *, const int32_t *, int, int, int, int, const bf16_t *, int, float *,
                                          hipStream_t);
-template void launch_rmsnorm_block<bf16_t>(float *, int, int, int, int, int, const float *, float, bf16_t *, bf16_t *,
-                                           PendingSums, hipStream_t);
+
