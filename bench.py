@@ -73,6 +73,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="BASELINE configuration index (1-5)")
     ap.add_argument("--logit-scale", type=float, default=1.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-also", action="store_true",
+                    help="skip the short extra measurement of config 2 (the small launch-latency-bound model) that a default run appends")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (a known-size reference for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -248,6 +250,31 @@ def main():
         out["cpu_baseline"] = cpu_baseline(w, n_tokens, n_stage1, n_verify, os.cpu_count() or 1)
     else:
         out["cpu_baseline"] = None
+    if args.config == 3 and not cached and not args.no_also and args.max_blocks == 0:
+        # context: the small configuration (8 layers, d_model 512), whose model call is ~90 launches of a few
+        # microseconds each -- launch-latency-bound, no roofline claim
+        del model
+        w2 = inp.WORKLOADS[2]
+        m2 = synthetic_model(w2.shape, w2.seq_len, "cuda:0", threads=16)
+        t2 = torch.from_numpy(inp.initial_state(w2)).to("cuda:0")
+        pol2, g2 = psd.Policy(w2.tau, w2.k_min, w2.k_max), psd.chain_graph(w2.n_drafts)
+
+        def decode2():
+            toks = t2.clone()
+            return psd.decode(m2, toks, w2.prompt_len, w2.block_len, pol2, g2)
+
+        decode2()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        reps = 5
+        for _ in range(reps):
+            st2 = decode2()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / reps
+        out["also"] = {"config 2 (small-bf16, B=1, 128-token prompt, 256 generated, L=32, K=4)": {
+            "tokens_per_s": w2.batch * w2.gen_len / dt, "ms_per_decode": dt * 1e3,
+            "tpf": sum(s.tokens for s in st2) / max(1, sum(s.invocations for s in st2)),
+            "invocations": int(sum(s.invocations for s in st2)), "bound": "launch latency"}}
     print(json.dumps(out))
 
 
