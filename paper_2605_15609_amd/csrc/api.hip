@@ -195,6 +195,7 @@ int32_t psd_create(const psd_model_config *cfg, const psd_weights *w, psd_handle
     h->host_counts_cap = 1 << 16;
     hipError_t e = hipHostMalloc((void **)&h->host_counts, sizeof(int32_t) * h->host_counts_cap, hipHostMallocDefault);
     if (e != hipSuccess) {
+        if (h->lm_head_packed) (void)hipFree(h->lm_head_packed);
         delete h;
         PSD_FAIL(PSD_ERR_DEVICE, "hipHostMalloc: %s", hipGetErrorString(e));
     }
