@@ -27,6 +27,16 @@
 #include "psd_internal.h"
 #include "device_types.h"
 
+// With two wavefronts per SIMD in one workgroup (the 8-wavefront tiles) the one inside an MFMA cluster gets issue
+// priority over its sibling's loads and address arithmetic (measured: SwiGLU 362 -> 352 us at 2048 tokens; the
+// 4-wavefront tiles, whose SIMD siblings belong to another workgroup, lose 4 % with it).
+#ifndef PSD_NO_SETPRIO
+#define PSD_PRIO_HI if constexpr (NW == 8) __builtin_amdgcn_s_setprio(1);
+#define PSD_PRIO_LO if constexpr (NW == 8) __builtin_amdgcn_s_setprio(0);
+#else
+#define PSD_PRIO_HI
+#define PSD_PRIO_LO
+#endif
 namespace mfma {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -227,9 +237,11 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
     }
 #define PSD_GEMM_MFMA(set)                                                                                    \
     {                                                                                                         \
+        PSD_PRIO_HI                                                                                           \
         _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                        \
             _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                    \
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0); \
+        PSD_PRIO_LO                                                                                           \
     }
 
     bf16x8 fa[2][TM], fb[2][TN];

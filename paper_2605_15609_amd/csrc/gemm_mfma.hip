@@ -83,7 +83,7 @@ int gemm_bf16_tile(int64_t M, int Nout, int epi) {
         int tile, per_round;
         double rate;
     };
-    const Cand cand[] = {{1, 256, 1.23}, {3, 512, 1.15}, {2, 256, 1.13}, {0, 512, 1.00}};
+    const Cand cand[] = {{1, 256, 1.25}, {2, 256, 1.16}, {3, 512, 1.15}, {0, 512, 1.00}};
     int best = 0;
     double best_cost = 0;
     for (const Cand &c : cand) {
