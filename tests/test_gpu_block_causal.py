@@ -175,3 +175,40 @@ def test_bf16_batched_cached_decode_equals_sequences_alone_and_the_masked_decode
         alone, st = run(tokens[b: b + 1])
         assert (alone[0] == together[b]).all()
         assert st[0].invocations == st_all[b].invocations and st[0].tokens == st_all[b].tokens == G
+
+
+def test_empty_prefix_full_cache_and_argument_errors():
+    import paper_2605_15609_amd as psd
+    shape = FP32
+    L = 16
+    N = 3 * L
+    host = inp.draw_model(shape, N)
+    model = psd.Model.from_host(host, DEV)
+    cache = psd.KvCache(model, 1, N)
+    # no prompt at all: the first block sees only itself
+    t = np.full(N, shape.mask_id, dtype=np.int32)
+    t[3] = 5
+    d = _dev(t[None])
+    psd.psd_kv_prefill(model, d, 0, L, cache)
+    top1, conf, logits = psd.psd_forward_confidence_cached(model, d, 0, L, cache, want_logits=True)
+    _check(shape, host, logits.cpu().numpy(), top1[0].cpu().numpy(), conf[0].cpu().numpy(), t, 0, L, 1e-4, "empty prefix")
+    # the last block of a cache filled to capacity
+    t2, start = _state(shape, N, 2 * L, L, 0, 9, 4)
+    d2 = _dev(t2[None])
+    cache.reset()
+    psd.psd_kv_prefill(model, d2, start, L, cache)
+    top1, conf, logits = psd.psd_forward_confidence_cached(model, d2, start, L, cache, want_logits=True)
+    _check(shape, host, logits.cpu().numpy(), top1[0].cpu().numpy(), conf[0].cpu().numpy(), t2, start, L, 1e-4, "cache at capacity")
+    # errors are reported, nothing is launched
+    with pytest.raises(psd.PsdError):
+        psd.psd_forward_confidence_cached(model, d2, start + 4, L, cache)            # block not aligned
+    with pytest.raises(psd.PsdError):
+        psd.psd_kv_prefill(model, d2, L + 3, L, cache)                               # prompt not a multiple of L
+    with pytest.raises(psd.PsdError):
+        psd.psd_forward_confidence_cached(model, d2, start, 8, cache)                # block length not a multiple of 16
+    small = psd.KvCache(model, 1, 2 * L)
+    with pytest.raises(psd.PsdError):
+        psd.psd_forward_confidence_cached(model, d2, start, L, small)                # block beyond the cache capacity
+    bidir = psd.Model.from_host(inp.draw_model(dataclasses.replace(shape, attention="bidirectional"), N), DEV)
+    with pytest.raises(psd.PsdError):
+        psd.KvCache(bidir, 1, N)                                                     # a cache is exact only for block-causal models
