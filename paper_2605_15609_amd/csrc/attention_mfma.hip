@@ -299,9 +299,9 @@ static void launch_att(const bf16_t *qkv, int ld_qkv, const bf16_t *vT, int S, i
                        pre);
 }
 
-#ifndef PSD_ATT_NSTG
-#define PSD_ATT_NSTG 2   // deeper rings (3, 4 stages) were measured 3-7 % slower: the kernel is not bound by fetch latency
-#endif
+// LDS ring depth of the K / V^T tiles; deeper rings (3, 4 stages) were measured 3-7 % slower: the kernel is not
+// bound by fetch latency
+constexpr int NSTG = 2;
 void launch_attention_bf16(const bf16_t *qkv, int ld_qkv, const bf16_t *vT, int S, int N, int n_heads, int n_kv_heads, int d_head,
                            bf16_t *out, const KvPrefix &pre, hipStream_t st) {
     // 128 queries per workgroup when that still gives two workgroups per CU, else 64; one wavefront for a
@@ -309,12 +309,12 @@ void launch_attention_bf16(const bf16_t *qkv, int ld_qkv, const bf16_t *vT, int 
     const int64_t blocks128 = (int64_t)((N + 127) / 128) * n_heads * S;
     const bool small = blocks128 < 512;
     if (d_head == 128) {
-        if (N <= 32) launch_att<128, 1, PSD_ATT_NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
-        else if (small) launch_att<128, 2, PSD_ATT_NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
-        else launch_att<128, 4, PSD_ATT_NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
+        if (N <= 32) launch_att<128, 1, NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
+        else if (small) launch_att<128, 2, NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
+        else launch_att<128, 4, NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
     } else {
-        if (N <= 32) launch_att<64, 1, PSD_ATT_NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
-        else if (small) launch_att<64, 2, PSD_ATT_NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
-        else launch_att<64, 4, PSD_ATT_NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
+        if (N <= 32) launch_att<64, 1, NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
+        else if (small) launch_att<64, 2, NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
+        else launch_att<64, 4, NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
     }
 }

@@ -289,18 +289,12 @@ void launch_head_confidence_bf16(const bf16_t *y, const bf16_t *W, int rows, int
     t1.parg = (int32_t *)((char *)partials + 2 * stride);
     t1.cols_total = rows;
     // row operand = W_lm (M := V), column operand = y (Nout := rows)
-#ifndef PSD_HEAD_NSTAGE
-#define PSD_HEAD_NSTAGE 2
-#endif
-#ifndef PSD_HEAD_NSTAGE_BIG
-#define PSD_HEAD_NSTAGE_BIG 2
-#endif
     if (rows <= 32)
-        launch_cfg<SLAB_SMALL, 32, 4, 1, EPI_TOP1, PSD_HEAD_NSTAGE>(W, y, nullptr, V, rows, d, d, d, nullptr, nullptr, nullptr, 0, t1, st);
+        launch_cfg<SLAB_SMALL, 32, 4, 1, EPI_TOP1, 2>(W, y, nullptr, V, rows, d, d, d, nullptr, nullptr, nullptr, 0, t1, st);
     else if (rows <= 64)
-        launch_cfg<SLAB_BIG, 64, 4, 1, EPI_TOP1, PSD_HEAD_NSTAGE_BIG>(W, y, nullptr, V, rows, d, d, d, nullptr, nullptr, nullptr, 0, t1, st);
+        launch_cfg<SLAB_BIG, 64, 4, 1, EPI_TOP1, 2>(W, y, nullptr, V, rows, d, d, d, nullptr, nullptr, nullptr, 0, t1, st);
     else
-        launch_cfg<SLAB_BIG, 128, 2, 2, EPI_TOP1, PSD_HEAD_NSTAGE_BIG>(W, y, nullptr, V, rows, d, d, d, nullptr, nullptr, nullptr, 0, t1, st);
+        launch_cfg<SLAB_BIG, 128, 2, 2, EPI_TOP1, 2>(W, y, nullptr, V, rows, d, d, d, nullptr, nullptr, nullptr, 0, t1, st);
     hipLaunchKernelGGL(head_merge_kernel, dim3(rows), dim3(64), 0, st, t1.pmax, t1.psum, t1.parg, slabs, rows, row_sum,
                        row_arg);
 }
