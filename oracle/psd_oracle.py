@@ -19,6 +19,8 @@ optional grouped KV heads, SwiGLU feed-forward) is not described by the paper be
 "bidirectional attention"; its layout comes from the benchmark configurations.  One model
 family of the paper (App. A) uses context-causal block attention instead -- full attention
 inside a block, causal across blocks -- which `block_causal` selects; PSD itself is unchanged.
+The evaluation protocol's EOS early stopping with truncated token statistics (App. B.1) is an
+option of the decode loop (`eos_id`).
 
 Precision: everything is fp64.  The benchmark configurations other than the first are "bf16" models (bf16
 operands, wider accumulation): for those, `operands="bf16"` additionally rounds the INPUTS of every
@@ -381,6 +383,9 @@ class Stats:
     tokens_draft: int = 0
     tokens_postverify: int = 0
     depth_hist: List[int] = field(default_factory=lambda: [0] * 32)
+    tokens_counted: int = 0     # resolved positions at or before the EOS position (all of them without an EOS)
+    stopped: bool = False       # an EOS token was produced and early stopping was on
+    eos_pos: int = -1           # position of the first EOS token in the sequence when stopped
 
     @property
     def tokens(self) -> int:
@@ -390,17 +395,51 @@ class Stats:
     def tpf(self) -> float:
         return self.tokens / max(1, self.invocations)
 
+    @property
+    def tpf_counted(self) -> float:
+        """Tokens per forward over the tokens up to and including the EOS position (App. B.1)."""
+        return self.tokens_counted / max(1, self.invocations)
+
 
 ConfidenceFn = Callable[[np.ndarray, int, int], Tuple[np.ndarray, np.ndarray]]
 
 
+def first_eos(tokens: np.ndarray, block_start: int, L: int, eos_id: Optional[int]) -> Optional[int]:
+    """Position of the first EOS token inside the block, None without one (or without early stopping)."""
+    if eos_id is None:
+        return None
+    hits = [i for i in range(block_start, block_start + L) if tokens[i] == eos_id]
+    return hits[0] if hits else None
+
+
 def decode_block(confidence_fn: ConfidenceFn, tokens: np.ndarray, block_start: int, L: int, policy: Policy,
-                 graph: Graph, mask_id: int, stats: Optional[Stats] = None, trace: Optional[list] = None):
+                 graph: Graph, mask_id: int, stats: Optional[Stats] = None, trace: Optional[list] = None,
+                 eos_id: Optional[int] = None):
     """Alg. 1 on one block of one sequence.  ``confidence_fn(tokens, block_start, L)`` is the
     model call (forward + top-1 confidence); a batched verification is K such calls counted
-    as one invocation."""
+    as one invocation.
+
+    EOS early stopping (App. B.1), when ``eos_id`` is given: decoding ends as soon as an EOS token
+    has been produced -- read as: after every update of the state (the stage-1 commit, and the
+    advance with its post-verification commit) the block is searched for ``eos_id`` and the loop
+    ends if it is there, whatever is still masked.  ``tokens_counted`` is the number of positions this call
+    resolved at or before the first EOS position (tokens unmasked beyond it are discarded from
+    the statistic, in whichever iteration they were unmasked); without an EOS every resolved
+    position counts."""
     stats = stats if stats is not None else Stats()
     x = np.array(tokens, dtype=np.int32, copy=True)
+    if eos_id is not None and eos_id == mask_id:
+        raise ValueError("the EOS token cannot be the mask token")
+    masked_on_entry = [block_start + j for j in masked_in_block(x, block_start, L, mask_id)]
+
+    def finish(x):
+        eos = first_eos(x, block_start, L, eos_id)
+        if eos is not None:
+            stats.stopped, stats.eos_pos = True, eos
+        limit = eos if eos is not None else block_start + L - 1
+        stats.tokens_counted += sum(1 for i in masked_on_entry if i <= limit and x[i] != mask_id)
+        return x, stats
+
     while masked_in_block(x, block_start, L, mask_id):
         top1, conf = confidence_fn(x, block_start, L)                       # stage 1
         stats.invocations += 1
@@ -408,6 +447,8 @@ def decode_block(confidence_fn: ConfidenceFn, tokens: np.ndarray, block_start: i
         stats.tokens_policy += int(transfer.sum())
         if trace is not None:
             trace.append(("commit", [block_start + j for j in range(L) if transfer[j]]))
+        if first_eos(x, block_start, L, eos_id) is not None:
+            break
         if not masked_in_block(x, block_start, L, mask_id):
             break
         sigma, m, drafts = build_drafts(x, block_start, L, top1, conf, graph, mask_id)   # stage 2
@@ -424,19 +465,25 @@ def decode_block(confidence_fn: ConfidenceFn, tokens: np.ndarray, block_start: i
         stats.depth_hist[depth] += 1
         if trace is not None:
             trace.append(("verify", k_star, depth, n_post, accepted.copy()))
-    return x, stats
+        if first_eos(x, block_start, L, eos_id) is not None:
+            break
+    return finish(x)
 
 
 def decode(confidence_fn: ConfidenceFn, tokens: np.ndarray, prompt_len: int, L: int, policy: Policy,
-           graph: Graph, mask_id: int, stats: Optional[Stats] = None, trace: Optional[list] = None):
+           graph: Graph, mask_id: int, stats: Optional[Stats] = None, trace: Optional[list] = None,
+           eos_id: Optional[int] = None):
     """Semi-autoregressive generation: blocks left to right, the next block starts only once
-    the current one is fully resolved (App. B.1).  Later blocks stay masked meanwhile."""
+    the current one is fully resolved (App. B.1).  Later blocks stay masked meanwhile.  With
+    ``eos_id`` the generation ends with the block that produced an EOS token."""
     stats = stats if stats is not None else Stats()
     x = np.array(tokens, dtype=np.int32, copy=True)
     N = x.shape[0]
     for block_start in range(prompt_len, N, L):
         x, stats = decode_block(confidence_fn, x, block_start, min(L, N - block_start), policy, graph,
-                                mask_id, stats, trace)
+                                mask_id, stats, trace, eos_id)
+        if stats.stopped:
+            break
     return x, stats
 
 

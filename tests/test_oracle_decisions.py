@@ -446,3 +446,116 @@ def test_blocks_decode_left_to_right_and_later_blocks_stay_masked():
     assert not (out == vocab - 1).any() and stats.tokens == 3 * L
     starts = [s for s, _ in seen]
     assert starts == sorted(starts) and set(starts) == {4, 12, 20} and all(flag for _, flag in seen)
+
+
+# ---------------------------------------------------------------- EOS early stopping (App. B.1)
+
+
+def scripted_model(top1, conf, mask_id):
+    """Predictions that never depend on the state (every draft is right)."""
+    top1, conf = np.asarray(top1, dtype=np.int32), np.asarray(conf, dtype=np.float32)
+
+    def fn(tokens, block_start, L):
+        blk = np.asarray(tokens[block_start: block_start + L])
+        masked = blk == mask_id
+        return np.where(masked, top1, blk).astype(np.int32), np.where(masked, conf, np.float32(-1)).astype(np.float32)
+
+    return fn
+
+
+def test_eos_stop_hand_worked():
+    """L = 8, chain K = 3 (depths 0, 1, 2), tau = 0.9, k_min = 1, all confidences below tau.
+    Iteration 1 by hand: stage 1 commits position 3 (0.8).  sigma = 1 (0.5), 2 (0.3), 4 (0.2), ...; drafts fill
+    {}, {1}, {1, 2}.  The predictions never change, so on the root's output the policy commits position 1 and on
+    the depth-1 draft's output position 2: both edges pass, k* is the depth-2 draft.  The post-verification
+    commit on its output takes position 4 (0.2).  State after the iteration: positions 1, 2, 3, 4 resolved."""
+    mask, eos, L = 99, 9, 8
+    conf = [0.1, 0.5, 0.3, 0.8, 0.2, 0.05, 0.04, 0.03]
+    P = 4                                        # a resolved prompt in front: positions below are block-local
+    tokens = np.full(P + L, mask, dtype=np.int32)
+    tokens[:P] = 7
+    policy, graph = orc.Policy(0.9, 1), orc.chain_graph(3)
+    # EOS predicted at position 2: it is produced by the accepted draft of iteration 1 -> stop after 2 invocations;
+    # positions at or before it that were resolved: 1 and 2 (0 is still masked; 3 and 4 lie beyond and are discarded)
+    fn = Counting(scripted_model([5, 5, eos, 5, 5, 5, 5, 5], conf, mask))
+    out, st = orc.decode_block(fn, tokens, P, L, policy, graph, mask, eos_id=eos)
+    assert out.tolist() == [7] * P + [mask, 5, eos, 5, 5, mask, mask, mask]
+    assert (st.stopped, st.eos_pos, st.invocations, st.tokens_counted) == (True, P + 2, 2, 2)
+    assert (st.tokens_policy, st.tokens_draft, st.tokens_postverify) == (1, 2, 1) and st.tpf_counted == 1.0
+    assert fn.calls == 1 + 3
+    # EOS predicted at position 3: the stage-1 commit produces it -> stop before any verification call
+    fn = Counting(scripted_model([5, 5, 5, eos, 5, 5, 5, 5], conf, mask))
+    out, st = orc.decode_block(fn, tokens, P, L, policy, graph, mask, eos_id=eos)
+    assert out.tolist() == [7] * P + [mask, mask, mask, eos, mask, mask, mask, mask]
+    assert (st.stopped, st.eos_pos, st.invocations, st.tokens_counted, fn.calls) == (True, P + 3, 1, 1, 1)
+    # EOS predicted at position 4: produced by the post-verification commit; resolved at or before it: 1, 2, 3, 4
+    fn = scripted_model([5, 5, 5, 5, eos, 5, 5, 5], conf, mask)
+    out, st = orc.decode_block(fn, tokens, P, L, policy, graph, mask, eos_id=eos)
+    assert (st.stopped, st.eos_pos, st.invocations, st.tokens_counted) == (True, P + 4, 2, 4)
+    # the same model without early stopping resolves the block and counts every token
+    out, st = orc.decode_block(fn, tokens, P, L, policy, graph, mask)
+    assert not (out == mask).any() and (st.stopped, st.eos_pos, st.tokens_counted) == (False, -1, L) and st.tokens == L
+    with pytest.raises(ValueError):
+        orc.decode_block(fn, tokens, P, L, policy, graph, mask, eos_id=mask)
+
+
+def test_eos_that_never_appears_changes_nothing():
+    vocab, L = 200, 32
+    for seed in range(6):
+        fn = pseudo_model(vocab, seed, sticky=0.7)
+        tokens = np.full(48, vocab - 1, dtype=np.int32)
+        tokens[:16] = 1
+        a, sa = orc.decode_block(fn, tokens, 16, L, orc.Policy(0.9, 1), orc.chain_graph(4), vocab - 1)
+        b, sb = orc.decode_block(fn, tokens, 16, L, orc.Policy(0.9, 1), orc.chain_graph(4), vocab - 1, eos_id=vocab + 7)
+        assert (a == b).all() and not sb.stopped and sb.tokens_counted == sb.tokens == L
+        assert (sa.invocations, sa.tokens_policy, sa.tokens_draft, sa.tokens_postverify) == \
+               (sb.invocations, sb.tokens_policy, sb.tokens_draft, sb.tokens_postverify)
+
+
+def test_eos_stop_is_the_first_state_with_an_eos_on_the_free_trajectory():
+    """The stopped run must walk the free run's trajectory (same commits, same values) and end at the first state
+    update after which the block holds the EOS token: no earlier state that the model was called on -- the input
+    of a stage-1 call, or the root draft of a verification batch, which is the state after the stage-1 commit --
+    may contain it, and the final state must."""
+    vocab, L, K, start = 200, 32, 4, 16
+    mask = vocab - 1
+    stopped_midway = 0
+    for seed in range(12):
+        base = pseudo_model(vocab, seed, sticky=0.7)
+        tokens = np.full(48, mask, dtype=np.int32)
+        tokens[:16] = 1
+        free, sf = orc.decode_block(base, tokens, start, L, orc.Policy(0.9, 1), orc.chain_graph(K), mask)
+        eos = int(free[start + 5 + seed])          # a token the free run does produce
+        calls = []
+
+        def fn(t, bs, Lb):
+            calls.append(np.array(t, copy=True))
+            return base(t, bs, Lb)
+
+        out, st = orc.decode_block(fn, tokens, start, L, orc.Policy(0.9, 1), orc.chain_graph(K), mask, eos_id=eos)
+        blk = out[start:start + L]
+        assert st.stopped and eos in blk.tolist() and st.eos_pos == start + blk.tolist().index(eos)
+        resolved = blk != mask
+        assert (blk[resolved] == free[start:start + L][resolved]).all()
+        assert st.invocations <= sf.invocations
+        for i, state in enumerate(calls):           # calls come in groups: stage 1, then the K drafts (root first)
+            if i % (K + 1) in (0, 1):
+                assert eos not in state[start:start + L].tolist()
+        assert st.tokens_counted == int(resolved[: st.eos_pos - start + 1].sum())
+        assert 1 <= st.tokens_counted <= st.tokens
+        stopped_midway += int((blk == mask).any())
+    assert stopped_midway >= 6                      # the stop does cut decoding short
+
+
+def test_eos_ends_the_generation_after_its_block():
+    vocab, L, mask = 30, 8, 29
+    base = pseudo_model(vocab, 5)
+    tokens = np.full(4 + 3 * L, mask, dtype=np.int32)
+    tokens[:4] = 2
+    free, _ = orc.decode(base, tokens, 4, L, orc.Policy(0.9, 1), orc.chain_graph(2), mask)
+    eos = int(free[4 + L + 3])                       # first produced in the second block (checked below)
+    assert eos not in free[4:4 + L].tolist()
+    out, st = orc.decode(base, tokens, 4, L, orc.Policy(0.9, 1), orc.chain_graph(2), mask, eos_id=eos)
+    assert (out[4:4 + L] == free[4:4 + L]).all() and st.stopped and 4 + L <= st.eos_pos < 4 + 2 * L
+    assert (out[4 + 2 * L:] == mask).all()
+    assert st.tokens_counted == L + int((out[4 + L: st.eos_pos + 1] != mask).sum())
