@@ -103,6 +103,13 @@ typedef struct {
     float   tau;
     int32_t k_min;
     int32_t k_max;   /* 0 = unbounded */
+    /* EOS early stopping of psd_decode_block / psd_decode_block_cached (evaluation protocol of
+     * App. B.1; the other calls ignore both fields).  eos_stop = 0: off.  eos_stop = 1: a sequence
+     * stops as soon as an EOS token has been produced: after every update of its state (the stage-1
+     * commit; the advance with its post-verification commit) its block is searched for eos_id, and
+     * if it is there the sequence takes part in no further model call, whatever is still masked. */
+    int32_t eos_stop;
+    int32_t eos_id;  /* 0 <= eos_id < vocab, not the mask token (checked when eos_stop = 1) */
 } psd_policy;
 
 /* Draft DAG (Sec. 3.2 stage 2).  Node k speculates on the ranks of the speculative
@@ -123,6 +130,14 @@ typedef struct {
     int64_t tokens_draft;        /* |S_k*| of the accepted drafts */
     int64_t tokens_postverify;   /* committed by pi on k*'s verifier output */
     int32_t depth_hist[PSD_MAX_NODES + PSD_MAX_BLOCK + 1];   /* histogram of |S_k*| */
+    /* App. B.1: tokens up to and including the EOS position.  tokens_counted grows by the number of
+     * block positions the call resolved at or before the first EOS token of the block (tokens
+     * unmasked beyond it are discarded, whenever they were unmasked); by all it resolved when the
+     * call did not stop on an EOS.  stopped is set to 1 and eos_pos to the sequence position of that
+     * first EOS token when it did; both are left alone otherwise. */
+    int64_t tokens_counted;
+    int32_t stopped;
+    int32_t eos_pos;
 } psd_stats;
 
 const char *psd_status_string(int32_t status);

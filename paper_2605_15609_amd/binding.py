@@ -42,7 +42,8 @@ class _Weights(C.Structure):
 
 
 class _Policy(C.Structure):
-    _fields_ = [("tau", C.c_float), ("k_min", C.c_int32), ("k_max", C.c_int32)]
+    _fields_ = [("tau", C.c_float), ("k_min", C.c_int32), ("k_max", C.c_int32), ("eos_stop", C.c_int32),
+                ("eos_id", C.c_int32)]
 
 
 class _Graph(C.Structure):
@@ -51,7 +52,8 @@ class _Graph(C.Structure):
 
 class _Stats(C.Structure):
     _fields_ = [("invocations", C.c_int64), ("tokens_policy", C.c_int64), ("tokens_draft", C.c_int64),
-                ("tokens_postverify", C.c_int64), ("depth_hist", C.c_int32 * HIST)]
+                ("tokens_postverify", C.c_int64), ("depth_hist", C.c_int32 * HIST), ("tokens_counted", C.c_int64),
+                ("stopped", C.c_int32), ("eos_pos", C.c_int32)]
 
 
 class _Work(C.Structure):
@@ -138,9 +140,11 @@ class Policy:
     tau: float = 0.9
     k_min: int = 1
     k_max: int = 0
+    eos_id: Optional[int] = None     # EOS early stopping of the block loop (App. B.1); None = off
 
     def c(self) -> _Policy:
-        return _Policy(float(np.float32(self.tau)), int(self.k_min), int(self.k_max))
+        return _Policy(float(np.float32(self.tau)), int(self.k_min), int(self.k_max),
+                       0 if self.eos_id is None else 1, 0 if self.eos_id is None else int(self.eos_id))
 
 
 @dataclass(frozen=True)
@@ -172,6 +176,9 @@ class Stats:
     tokens_draft: int = 0
     tokens_postverify: int = 0
     depth_hist: List[int] = field(default_factory=lambda: [0] * HIST)
+    tokens_counted: int = 0      # resolved positions at or before the EOS position (App. B.1)
+    stopped: bool = False
+    eos_pos: int = -1
 
     @property
     def tokens(self) -> int:
@@ -180,6 +187,10 @@ class Stats:
     @property
     def tpf(self) -> float:
         return self.tokens / max(1, self.invocations)
+
+    @property
+    def tpf_counted(self) -> float:
+        return self.tokens_counted / max(1, self.invocations)
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -397,6 +408,21 @@ def psd_verify_accept(model: Model, tokens: torch.Tensor, drafts: torch.Tensor, 
     return k_star, accepted, v_top1, v_conf
 
 
+def _add_stats(stats, cstats, B) -> List[Stats]:
+    out = list(stats) if stats is not None else [Stats() for _ in range(B)]
+    for b in range(B):
+        out[b].invocations += cstats[b].invocations
+        out[b].tokens_policy += cstats[b].tokens_policy
+        out[b].tokens_draft += cstats[b].tokens_draft
+        out[b].tokens_postverify += cstats[b].tokens_postverify
+        out[b].tokens_counted += cstats[b].tokens_counted
+        if cstats[b].stopped:
+            out[b].stopped, out[b].eos_pos = True, int(cstats[b].eos_pos)
+        for i in range(HIST):
+            out[b].depth_hist[i] += cstats[b].depth_hist[i]
+    return out
+
+
 def psd_decode_block(model: Model, tokens: torch.Tensor, block_start: int, L: int, policy: Policy, graph: Graph,
                      stats: Optional[Sequence[Stats]] = None) -> List[Stats]:
     """Alg. 1 on one block of every sequence of tokens [B, N], in place.  Blocks until done."""
@@ -409,15 +435,7 @@ def psd_decode_block(model: Model, tokens: torch.Tensor, block_start: int, L: in
     g, pol = graph.c(), policy.c()
     _check(model.lib.psd_decode_block(model.handle, _ptr(tokens), B, N, block_start, L, C.byref(pol), C.byref(g), cstats,
                                       _ptr(ws), nb, _stream()))
-    out = list(stats) if stats is not None else [Stats() for _ in range(B)]
-    for b in range(B):
-        out[b].invocations += cstats[b].invocations
-        out[b].tokens_policy += cstats[b].tokens_policy
-        out[b].tokens_draft += cstats[b].tokens_draft
-        out[b].tokens_postverify += cstats[b].tokens_postverify
-        for i in range(HIST):
-            out[b].depth_hist[i] += cstats[b].depth_hist[i]
-    return out
+    return _add_stats(stats, cstats, B)
 
 
 class KvCache:
@@ -467,23 +485,28 @@ def psd_decode_block_cached(model: Model, tokens: torch.Tensor, block_start: int
     g, pol = graph.c(), policy.c()
     _check(model.lib.psd_decode_block_cached(model.handle, _ptr(tokens), B, N, block_start, L, C.byref(pol), C.byref(g), cstats,
                                              _ptr(cache.mem), cache.capacity, _ptr(ws), nb, _stream()))
-    out = list(stats) if stats is not None else [Stats() for _ in range(B)]
-    for b in range(B):
-        out[b].invocations += cstats[b].invocations
-        out[b].tokens_policy += cstats[b].tokens_policy
-        out[b].tokens_draft += cstats[b].tokens_draft
-        out[b].tokens_postverify += cstats[b].tokens_postverify
-        for i in range(HIST):
-            out[b].depth_hist[i] += cstats[b].depth_hist[i]
-    return out
+    return _add_stats(stats, cstats, B)
 
 
 def decode(model: Model, tokens: torch.Tensor, prompt_len: int, L: int, policy: Policy, graph: Graph) -> List[Stats]:
-    """Semi-autoregressive generation: psd_decode_block on each block, left to right."""
+    """Semi-autoregressive generation: psd_decode_block on each block, left to right.  With EOS early stopping
+    (policy.eos_id) a sequence that produced an EOS token is left out of the later blocks."""
     B, N = tokens.shape
     stats = [Stats() for _ in range(B)]
     for block_start in range(prompt_len, N, L):
-        stats = psd_decode_block(model, tokens, block_start, min(L, N - block_start), policy, graph, stats)
+        going = [b for b in range(B) if not stats[b].stopped]
+        if not going:
+            break
+        Lb = min(L, N - block_start)
+        if len(going) == B:
+            stats = psd_decode_block(model, tokens, block_start, Lb, policy, graph, stats)
+        else:
+            idx = torch.as_tensor(going, device=tokens.device)
+            part = tokens.index_select(0, idx).contiguous()
+            sub = psd_decode_block(model, part, block_start, Lb, policy, graph, [stats[b] for b in going])
+            tokens.index_copy_(0, idx, part)
+            for b, st in zip(going, sub):
+                stats[b] = st
     return stats
 
 

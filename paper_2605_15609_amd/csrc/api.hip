@@ -18,12 +18,17 @@ void psd_set_error(const char *fmt, ...) {
 
 namespace {
 
+// masks of every sequence's block on entry: their number, and which positions (a 64-bit set in the counters)
 __global__ void count_masks_kernel(const int32_t *__restrict__ tokens, int N, int block_start, int L, int32_t mask_id,
-                                   int32_t *__restrict__ n_left) {
+                                   int32_t *__restrict__ n_left, int32_t *__restrict__ devstats) {
     const int b = blockIdx.x, j = threadIdx.x;
     const bool live = j < L && tokens[(int64_t)b * N + block_start + j] == mask_id;
-    const int n = __popcll(__ballot(live));
-    if (j == 0) n_left[b] = n;
+    const uint64_t set = __ballot(live);
+    if (j == 0) {
+        n_left[b] = __popcll(set);
+        devstats[(int64_t)b * PSD_DEVSTAT_WORDS + PSD_DEVSTAT_ENTRY] = (int32_t)(uint32_t)set;
+        devstats[(int64_t)b * PSD_DEVSTAT_WORDS + PSD_DEVSTAT_ENTRY + 1] = (int32_t)(uint32_t)(set >> 32);
+    }
 }
 
 __global__ void fill_i32_kernel(int32_t *p, int64_t n, int32_t v) {
@@ -376,6 +381,10 @@ int32_t decode_block_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, 
     GraphArg g;
     CHECK(check_graph(graph, &g));
     CHECK(check_policy(policy));
+    const bool eos_stop = policy->eos_stop != 0;
+    if (eos_stop && (policy->eos_id < 0 || policy->eos_id >= h->cfg.vocab || policy->eos_id == h->cfg.mask_id))
+        PSD_FAIL(PSD_ERR_INVALID_ARG, "eos_id %d: a token id below the vocabulary size %d other than the mask token",
+                 policy->eos_id, h->cfg.vocab);
     if (!tokens || !stats) PSD_FAIL(PSD_ERR_INVALID_ARG, "NULL tokens/stats");
     const int K = g.K;
     const int plan_N = kv ? L : N;     // rows per sequence that a model call runs over
@@ -415,7 +424,7 @@ int32_t decode_block_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, 
         const int64_t n = (int64_t)B * PSD_DEVSTAT_WORDS;
         hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, devstats, n, 0);
     }
-    hipLaunchKernelGGL(count_masks_kernel, dim3(B), dim3(64), 0, st, tokens, N, block_start, L, mask_id, n_left);
+    hipLaunchKernelGGL(count_masks_kernel, dim3(B), dim3(64), 0, st, tokens, N, block_start, L, mask_id, n_left, devstats);
     PSD_HIP(hipMemcpyAsync(hc, n_left, sizeof(int32_t) * B, hipMemcpyDeviceToHost, st));
     PSD_HIP(hipStreamSynchronize(st));
     std::vector<int> active;
@@ -432,6 +441,7 @@ int32_t decode_block_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, 
         for (int b : active) invocations[b] += 1;
         launch_select_unmask(tokens, B, N, block_start, L, top1, conf, *policy, mask_id, nullptr, nullptr, n_left, devstats, st);
         launch_build_drafts(tokens, B, N, block_start, L, top1, conf, g, mask_id, sigma, m, drafts, st);
+        if (eos_stop) launch_eos_stop(tokens, B, N, block_start, L, policy->eos_id, n_left, m, devstats, st);
         PSD_HIP(hipMemcpyAsync(hc, m, sizeof(int32_t) * B, hipMemcpyDeviceToHost, st));
         PSD_HIP(hipStreamSynchronize(st));
         std::vector<int> vset;
@@ -447,6 +457,7 @@ int32_t decode_block_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, 
         for (int b : vset) invocations[b] += 1;
         launch_accept(tokens, drafts, B, N, block_start, L, sigma, m, g, *policy, mask_id, v_top1, v_conf, k_star, accepted,
                       n_left, devstats, st);
+        if (eos_stop) launch_eos_stop(tokens, B, N, block_start, L, policy->eos_id, n_left, nullptr, devstats, st);
         PSD_HIP(hipMemcpyAsync(hc, n_left, sizeof(int32_t) * B, hipMemcpyDeviceToHost, st));
         PSD_HIP(hipStreamSynchronize(st));
         active.clear();
@@ -454,6 +465,7 @@ int32_t decode_block_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, 
             if (hc[b] > 0) active.push_back(b);
     }
 
+    launch_finish_counts(tokens, B, N, block_start, L, mask_id, policy->eos_stop, policy->eos_id, devstats, st);
     int32_t *hstats = hc + B + (int64_t)B * K;
     PSD_HIP(hipMemcpyAsync(hstats, devstats, sizeof(int32_t) * B * PSD_DEVSTAT_WORDS, hipMemcpyDeviceToHost, st));
     PSD_HIP(hipStreamSynchronize(st));
@@ -463,6 +475,11 @@ int32_t decode_block_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, 
         stats[b].tokens_policy += ds[PSD_DEVSTAT_POLICY];
         stats[b].tokens_draft += ds[PSD_DEVSTAT_DRAFT];
         stats[b].tokens_postverify += ds[PSD_DEVSTAT_POST];
+        stats[b].tokens_counted += ds[PSD_DEVSTAT_COUNTED];
+        if (ds[PSD_DEVSTAT_EOS] > 0) {
+            stats[b].stopped = 1;
+            stats[b].eos_pos = block_start + ds[PSD_DEVSTAT_EOS] - 1;
+        }
         for (int i = 0; i <= PSD_MAX_BLOCK; ++i) stats[b].depth_hist[i] += ds[PSD_DEVSTAT_HIST + i];
     }
     if (kv) {   // the block is finished: its keys and values become context

@@ -1,5 +1,6 @@
 // Decision kernels of the PSD step: transfer policy (Eq. 1), speculative ordering and
-// draft assembly (Eq. 2), hierarchical acceptance and state advance (Alg. 1, stage 3).
+// draft assembly (Eq. 2), hierarchical acceptance and state advance (Alg. 1, stage 3);
+// EOS early stopping and the truncated token count of the evaluation protocol (App. B.1).
 //
 // One 64-lane wavefront owns one sequence's block (L <= 64): lane j is block position j.
 // Rankings are rank-by-counting with wavefront shuffles -- position j's rank among the
@@ -45,7 +46,9 @@ __global__ __launch_bounds__(WAVE) void select_unmask_kernel(int32_t *__restrict
     const int j = threadIdx.x;
     int32_t *row = tokens + (int64_t)b * N + block_start;
     const bool in = j < L;
-    const bool live = in && row[j] == mask_id;
+    // a sequence that stopped on an EOS token keeps its masks: its predictions are stale, nothing is committed
+    const bool stopped = devstats && devstats[(int64_t)b * PSD_DEVSTAT_WORDS + PSD_DEVSTAT_EOS] > 0;
+    const bool live = in && !stopped && row[j] == mask_id;
     const float c = in ? conf[(int64_t)b * L + j] : -2.0f;
     const int rank = rank_by_confidence(live, c);
     const bool take = policy_commits(live, rank, c, policy);
@@ -215,7 +218,56 @@ __global__ __launch_bounds__(WAVE) void accept_kernel(int32_t *__restrict__ toke
     }
 }
 
+// ------------------------------------------------------------------ EOS early stopping (App. B.1)
+// After a state update: a sequence whose block holds the EOS token is finished, whatever is still masked.
+// Its mask counts are zeroed, which is what takes it out of the following model calls, and the position is
+// flagged in its counters, which is what keeps the stage-1 commit from touching it again.
+__global__ __launch_bounds__(WAVE) void eos_stop_kernel(const int32_t *__restrict__ tokens, int N, int block_start, int L,
+                                                        int32_t eos_id, int32_t *__restrict__ n_left,
+                                                        int32_t *__restrict__ m, int32_t *__restrict__ devstats) {
+    const int b = blockIdx.x, j = threadIdx.x;
+    const bool hit = j < L && tokens[(int64_t)b * N + block_start + j] == eos_id;
+    const uint64_t hits = __ballot(hit);
+    if (hits != 0ull && j == 0) {
+        if (n_left) n_left[b] = 0;
+        if (m) m[b] = 0;
+        devstats[(int64_t)b * PSD_DEVSTAT_WORDS + PSD_DEVSTAT_EOS] = __ffsll((unsigned long long)hits);
+    }
+}
+
+// End of the block loop: the first EOS position of the block (when stopping on EOS is on) and the number of
+// positions resolved by this call at or before it -- all resolved positions without an EOS.  The positions
+// masked on entry are in the sequence's counters as a 64-bit set.
+__global__ __launch_bounds__(WAVE) void finish_counts_kernel(const int32_t *__restrict__ tokens, int N, int block_start, int L,
+                                                             int32_t mask_id, int32_t eos_stop, int32_t eos_id,
+                                                             int32_t *__restrict__ devstats) {
+    const int b = blockIdx.x, j = threadIdx.x;
+    const int32_t tok = j < L ? tokens[(int64_t)b * N + block_start + j] : mask_id;
+    const uint64_t hits = __ballot(eos_stop && j < L && tok == eos_id);
+    const uint64_t resolved = __ballot(j < L && tok != mask_id);
+    if (j == 0) {
+        int32_t *ds = devstats + (int64_t)b * PSD_DEVSTAT_WORDS;
+        const int eos = hits ? __ffsll((unsigned long long)hits) - 1 : -1;
+        const int limit = eos >= 0 ? eos : L - 1;
+        const uint64_t upto = limit >= 63 ? ~0ull : ((1ull << (limit + 1)) - 1ull);
+        const uint64_t entry = (uint64_t)(uint32_t)ds[PSD_DEVSTAT_ENTRY] | ((uint64_t)(uint32_t)ds[PSD_DEVSTAT_ENTRY + 1] << 32);
+        ds[PSD_DEVSTAT_EOS] = eos + 1;
+        ds[PSD_DEVSTAT_COUNTED] = __popcll(entry & resolved & upto);
+    }
+}
+
 }   // namespace
+
+void launch_eos_stop(const int32_t *tokens, int B, int N, int block_start, int L, int32_t eos_id, int32_t *n_left, int32_t *m,
+                     int32_t *devstats, hipStream_t st) {
+    hipLaunchKernelGGL(eos_stop_kernel, dim3(B), dim3(WAVE), 0, st, tokens, N, block_start, L, eos_id, n_left, m, devstats);
+}
+
+void launch_finish_counts(const int32_t *tokens, int B, int N, int block_start, int L, int32_t mask_id, int32_t eos_stop,
+                          int32_t eos_id, int32_t *devstats, hipStream_t st) {
+    hipLaunchKernelGGL(finish_counts_kernel, dim3(B), dim3(WAVE), 0, st, tokens, N, block_start, L, mask_id, eos_stop, eos_id,
+                       devstats);
+}
 
 void launch_select_unmask(int32_t *tokens, int B, int N, int block_start, int L, const int32_t *top1, const float *conf,
                           psd_policy policy, int32_t mask_id, uint8_t *transfer_mask, int32_t *n_selected,

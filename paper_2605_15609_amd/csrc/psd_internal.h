@@ -56,14 +56,21 @@ static inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * 
 #define PSD_DEVSTAT_POLICY 0
 #define PSD_DEVSTAT_DRAFT 1
 #define PSD_DEVSTAT_POST 2
-#define PSD_DEVSTAT_HIST 3
-#define PSD_DEVSTAT_WORDS (3 + PSD_MAX_NODES + PSD_MAX_BLOCK + 1)
+#define PSD_DEVSTAT_EOS 3        // 1 + block position of the first EOS token once the sequence stopped on it, else 0
+#define PSD_DEVSTAT_ENTRY 4      // two words: which block positions were masked on entry (bit j = position j)
+#define PSD_DEVSTAT_COUNTED 6    // positions resolved at or before the EOS position (all resolved ones without an EOS)
+#define PSD_DEVSTAT_HIST 7
+#define PSD_DEVSTAT_WORDS (7 + PSD_MAX_NODES + PSD_MAX_BLOCK + 1)
 
 struct GraphArg {
     int32_t K;
     uint64_t rank_set[PSD_MAX_NODES];
 };
 
+void launch_eos_stop(const int32_t *tokens, int B, int N, int block_start, int L, int32_t eos_id, int32_t *n_left, int32_t *m,
+                     int32_t *devstats, hipStream_t st);
+void launch_finish_counts(const int32_t *tokens, int B, int N, int block_start, int L, int32_t mask_id, int32_t eos_stop,
+                          int32_t eos_id, int32_t *devstats, hipStream_t st);
 void launch_select_unmask(int32_t *tokens, int B, int N, int block_start, int L, const int32_t *top1,
                           const float *conf, psd_policy policy, int32_t mask_id, uint8_t *transfer_mask,
                           int32_t *n_selected, int32_t *n_left, int32_t *devstats, hipStream_t st);

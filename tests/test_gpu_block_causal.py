@@ -146,6 +146,23 @@ def test_fp32_free_running_cached_decode_matches_the_oracle_decode():
         assert (s.invocations, s.tokens_policy, s.tokens_draft, s.tokens_postverify) == \
                (ostats.invocations, ostats.tokens_policy, ostats.tokens_draft, ostats.tokens_postverify)
         assert s.depth_hist[:32] == ostats.depth_hist
+        # EOS early stopping (App. B.1) on the cached path: an EOS id the free run produces in its second block
+        eos = int(ref[P + L + 5])
+        d = _dev(tokens0)
+        cache.reset()
+        psd.psd_kv_prefill(model, d, P, L, cache)
+        stats = [psd.Stats()]
+        for start in range(P, N, L):
+            if stats[0].stopped:
+                break
+            stats = psd.psd_decode_block_cached(model, d, start, L, psd.Policy(tau, 1, 0, eos_id=eos), psd.chain_graph(K), cache,
+                                                stats)
+        ref2, o2 = orc.decode(orc.model_confidence_fn(host, block_causal=True), tokens0[0], P, L, orc.Policy(tau, 1, 0),
+                              orc.chain_graph(K), shape.mask_id, eos_id=eos)
+        s = stats[0]
+        assert (d.cpu().numpy()[0] == ref2).all() and o2.stopped, (K, tau)
+        assert (s.invocations, s.tokens, s.tokens_counted, bool(s.stopped), s.eos_pos) == \
+               (o2.invocations, o2.tokens, o2.tokens_counted, o2.stopped, o2.eos_pos)
 
 
 def test_bf16_batched_cached_decode_equals_sequences_alone_and_the_masked_decode():

@@ -129,3 +129,7 @@ def test_argument_errors_are_reported_not_launched(env):
         psd.psd_build_drafts(model, tokens, 0, 16, top1, conf, psd.Graph((1, 3)))
     with pytest.raises(psd.PsdError):
         psd.psd_select_unmask(model, tokens, 0, 16, top1, conf, psd.Policy(tau=float("nan")))
+    # EOS early stopping needs a token id other than the mask token
+    for bad in (model.cfg.mask_id, model.cfg.vocab, -3):
+        with pytest.raises(psd.PsdError, match="eos_id"):
+            psd.psd_decode_block(model, tokens, 0, 16, psd.Policy(eos_id=bad), psd.chain_graph(2))

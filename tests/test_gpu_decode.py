@@ -89,6 +89,82 @@ def test_batched_decode_equals_sequences_decoded_alone():
     assert all(s.tpf >= 1.0 for s in stats)
 
 
+def _counters(s):
+    return (s.invocations, s.tokens_policy, s.tokens_draft, s.tokens_postverify, s.tokens_counted, bool(s.stopped), s.eos_pos)
+
+
+def test_config1_eos_early_stop_matches_oracle_exactly():
+    """App. B.1: stop as soon as an EOS token is produced, count the tokens up to and including its position.
+    The EOS ids are tokens the oracle's free run produces at chosen positions, so the stop falls early, in the
+    middle and late in the block; three sequences share a batch, so the others go on while one has stopped."""
+    import paper_2605_15609_amd as psd
+    w = inp.WORKLOADS[1]
+    shape, P, L = w.shape, w.prompt_len, w.block_len
+    host = inp.draw_model(shape, w.seq_len)
+    model = psd.Model.from_host(host, DEV)
+    fn = orc.model_confidence_fn(host)
+    B = 3
+    tokens0 = np.full((B, w.seq_len), shape.mask_id, dtype=np.int32)
+    for b in range(B):
+        tokens0[b, :P] = inp.draw_prompt(shape.vocab, P, 300 + b)
+    cut_short = 0
+    for K, tau in ((2, 0.9), (4, 0.02)):
+        free = [orc.decode(fn, tokens0[b], P, L, orc.Policy(tau, 1, 0), orc.chain_graph(K), shape.mask_id)[0] for b in range(B)]
+        for pick in (1, 13, 30):
+            eos = int(free[0][P + pick])
+            d_tokens = _dev(tokens0)
+            stats = psd.decode(model, d_tokens, P, L, psd.Policy(tau, 1, 0, eos_id=eos), psd.chain_graph(K))
+            got = d_tokens.cpu().numpy()
+            for b in range(B):
+                ref, ost = orc.decode(fn, tokens0[b], P, L, orc.Policy(tau, 1, 0), orc.chain_graph(K), shape.mask_id, eos_id=eos)
+                assert (got[b] == ref).all(), (K, tau, pick, b)
+                assert _counters(stats[b]) == _counters(ost), (K, tau, pick, b)
+                cut_short += int(ost.stopped and (ref == shape.mask_id).any())
+            assert stats[0].stopped
+        # an EOS id that is never produced: nothing changes, every token counts
+        unused = next(t for t in range(shape.vocab) if t != shape.mask_id and all(t not in f.tolist() for f in free))
+        d_tokens = _dev(tokens0)
+        stats = psd.decode(model, d_tokens, P, L, psd.Policy(tau, 1, 0, eos_id=unused), psd.chain_graph(K))
+        for b in range(B):
+            assert (d_tokens.cpu().numpy()[b] == free[b]).all() and not stats[b].stopped
+            assert stats[b].tokens_counted == stats[b].tokens == L
+    assert cut_short >= 3
+
+
+def test_eos_stop_in_a_batch_over_several_blocks_equals_sequences_alone():
+    import paper_2605_15609_amd as psd
+    shape = inp.cut_down(inp.WORKLOADS[2].shape, n_layers=2, vocab=4000, seed=32, logit_scale=14.0)
+    N, P, L, K, B = 136, 40, 32, 3, 5
+    host = inp.draw_model(shape, N)
+    model = psd.Model.from_host(host, DEV)
+    graph = psd.chain_graph(K)
+    tokens = np.full((B, N), shape.mask_id, dtype=np.int32)
+    for b in range(B):
+        tokens[b, :P] = inp.draw_prompt(shape.vocab, P, 50 + b)
+    free = _dev(tokens)
+    psd.decode(model, free, P, L, psd.Policy(0.9, 1, 0), graph)
+    eos = int(free[1, P + L + 9])               # produced by sequence 1 in its second block (if not before)
+    policy = psd.Policy(0.9, 1, 0, eos_id=eos)
+    together = _dev(tokens)
+    stats = psd.decode(model, together, P, L, policy, graph)
+    for b in range(B):
+        alone = _dev(tokens[b: b + 1])
+        s = psd.decode(model, alone, P, L, policy, graph)
+        assert (alone[0] == together[b]).all(), b
+        assert _counters(s[0]) == _counters(stats[b]), b
+        row = together[b].cpu().numpy()
+        if stats[b].stopped:
+            assert row[stats[b].eos_pos] == eos and eos not in row[P:stats[b].eos_pos].tolist()
+            nxt = P + ((stats[b].eos_pos - P) // L + 1) * L
+            assert (row[nxt:] == shape.mask_id).all()           # no block after the one with the EOS was started
+            assert stats[b].tokens_counted <= stats[b].tokens
+        else:
+            assert eos not in row[P:].tolist() and not (row == shape.mask_id).any()
+            assert stats[b].tokens_counted == stats[b].tokens == N - P
+    assert stats[1].stopped and stats[1].eos_pos < P + 2 * L
+    assert any(not s.stopped for s in stats)
+
+
 def _lockstep(workload, shape, n_blocks, guard=1e-3, max_iters=10 ** 9):
     import paper_2605_15609_amd as psd
     from tests.gpu_common import gpu_graph
