@@ -83,6 +83,9 @@ def main():
                          "against an exact prefix KV cache (prefill included in the step)")
     ap.add_argument("--max-blocks", type=int, default=0,
                     help="decode only the first blocks of the generation region (0 = all); tokens/s counts what was decoded")
+    ap.add_argument("--calibrate-graph", action="store_true",
+                    help="instead of the benchmark: decode the workload once per candidate draft graph (chains of depth 1-8, "
+                         "wider steps, subset lattices) and print tokens/s and TPF of each, and the winner")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1",
@@ -113,6 +116,22 @@ def main():
     t_weights = time.perf_counter() - t0
     tokens0 = torch.from_numpy(inp.initial_state(w)).to("cuda:0")
     policy, graph = psd.Policy(w.tau, w.k_min, w.k_max), psd.chain_graph(w.n_drafts)
+
+    if args.calibrate_graph:
+        names = [f"chain K={k}" for k in range(1, 9)] + ["chain K=3 width=2", "chain K=4 width=2", "lattice depth=2",
+                                                         "lattice depth=3"]
+        cands = [psd.chain_graph(k) for k in range(1, 9)] + [psd.chain_graph(3, 2), psd.chain_graph(4, 2),
+                                                             psd.lattice_graph(2), psd.lattice_graph(3)]
+        kv = psd.KvCache(model, w.batch, w.seq_len) if cached else None
+        psd.psd_calibrate_graph(model, tokens0, w.prompt_len, w.block_len, policy, cands[:1], kv)     # warm-up
+        best, scores = psd.psd_calibrate_graph(model, tokens0, w.prompt_len, w.block_len, policy, cands, kv)
+        print(json.dumps({"mode": "calibrate_graph", "config": {"workload": f"config {w.index}: {shape.name}, B={w.batch}, prompt {w.prompt_len}, {w.gen_len} generated, L={w.block_len}",
+                                                                "attention": args.attention, "tau": w.tau},
+                          "best": names[best],
+                          "candidates": [{"graph": n, "K": g.K, "tokens_per_s": round(sc["tokens_per_s"], 2),
+                                          "tpf": round(sc["tpf"], 4), "seconds": round(sc["seconds"], 4)}
+                                         for n, g, sc in zip(names, cands, scores)]}))
+        return
 
     n_blocks = w.gen_len // w.block_len
     if args.max_blocks > 0:

@@ -158,6 +158,10 @@ int64_t psd_workspace_bytes(const psd_model_config *cfg, int32_t max_seqs, int32
 
 /* Prefix chain: node k speculates on the k*width most confident residual positions. */
 int32_t psd_graph_chain(int32_t K, int32_t width, psd_graph *out);
+/* Subset lattice: one node for every subset of the `depth` most confident residual positions
+ * (2^depth nodes, ordered by size): the densest multi-parent DAG over those positions -- a
+ * deeper draft can be reached through every order of unmasking (Sec. 3.2 stage 2).  depth 0..5. */
+int32_t psd_graph_lattice(int32_t depth, psd_graph *out);
 
 /* Model call (Sec. 3.1; Alg. 1 stage 1 and the batched pass of stage 3): forward S
  * sequences over all N positions with bidirectional attention, then on the L block rows of
@@ -269,6 +273,25 @@ int32_t psd_forward_confidence_cached(psd_handle *h, const int32_t *tokens, int3
 int32_t psd_decode_block_cached(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_t block_start, int32_t L,
                                 const psd_policy *policy, const psd_graph *graph, psd_stats *stats, void *cache,
                                 int32_t capacity, void *ws, int64_t ws_bytes, void *stream);
+
+/* Offline calibration of the draft graph (Sec. 3.2 stage 2: the topology is fixed before inference so
+ * as to maximise empirical throughput).  The calibration batch -- tokens device int32 [B, N], the first
+ * n_prompt positions of every row resolved, the rest [M] -- is decoded block by block once per candidate
+ * (on a copy in work_tokens, device int32 [B, N]; tokens itself is only read), timed with HIP events on
+ * `stream`; scores[c] (host) receives the candidate's decode time, decoded tokens per second, TPF, tokens
+ * and invocations summed over the batch, and *best the index with the highest tokens per second (lowest
+ * index on ties).  cache = NULL: whole-sequence model calls; otherwise the block-causal cached path
+ * (cache as for psd_decode_block_cached, for B sequences; it is reset and prefilled from the prompt before
+ * every candidate, outside the timed region).  ws as for psd_decode_block with the largest K among the
+ * candidates.  EOS early stopping is not applied (policy->eos_stop is ignored).  Blocks until done. */
+typedef struct {
+    double  seconds, tokens_per_s, tpf;
+    int64_t tokens, invocations;
+} psd_graph_score;
+int32_t psd_calibrate_graph(psd_handle *h, const int32_t *tokens, int32_t *work_tokens, int32_t B, int32_t N,
+                            int32_t n_prompt, int32_t L, const psd_policy *policy, const psd_graph *candidates,
+                            int32_t n_candidates, psd_graph_score *scores, int32_t *best, void *cache,
+                            int32_t capacity, void *ws, int64_t ws_bytes, void *stream);
 
 /* Per-handle timing of the last psd_decode_block / forward calls is not kept; callers time
  * with HIP events on `stream`.  For roofline accounting the library reports the algorithmic

@@ -56,6 +56,11 @@ class _Stats(C.Structure):
                 ("stopped", C.c_int32), ("eos_pos", C.c_int32)]
 
 
+class _GraphScore(C.Structure):
+    _fields_ = [("seconds", C.c_double), ("tokens_per_s", C.c_double), ("tpf", C.c_double), ("tokens", C.c_int64),
+                ("invocations", C.c_int64)]
+
+
 class _Work(C.Structure):
     _fields_ = [("gemm_flops", C.c_double), ("attn_flops", C.c_double), ("head_flops", C.c_double),
                 ("head_bytes", C.c_double), ("weight_bytes", C.c_double)]
@@ -87,6 +92,9 @@ def load_library():
         "psd_workspace_bytes": (i64, [C.POINTER(_Config), i32, i32, i32]),
         "psd_decode_scratch_bytes": (i64, [i32, i32, i32, i32]),
         "psd_graph_chain": (i32, [i32, i32, C.POINTER(_Graph)]),
+        "psd_graph_lattice": (i32, [i32, C.POINTER(_Graph)]),
+        "psd_calibrate_graph": (i32, [vp, vp, vp, i32, i32, i32, i32, C.POINTER(_Policy), C.POINTER(_Graph), i32,
+                                      C.POINTER(_GraphScore), C.POINTER(i32), vp, i32, vp, i64, vp]),
         "psd_forward_confidence": (i32, [vp, vp, i32, i32, i32, i32, vp, vp, vp, i64, vp]),
         "psd_forward_logits": (i32, [vp, vp, i32, i32, i32, i32, vp, vp, i64, vp]),
         "psd_select_unmask": (i32, [vp, vp, i32, i32, i32, i32, vp, vp, C.POINTER(_Policy), vp, vp, vp]),
@@ -166,6 +174,12 @@ class Graph:
 def chain_graph(K: int, width: int = 1) -> Graph:
     g = _Graph()
     _check(load_library().psd_graph_chain(K, width, C.byref(g)))
+    return Graph(tuple(int(g.rank_set[k]) for k in range(g.K)))
+
+
+def lattice_graph(depth: int) -> Graph:
+    g = _Graph()
+    _check(load_library().psd_graph_lattice(depth, C.byref(g)))
     return Graph(tuple(int(g.rank_set[k]) for k in range(g.K)))
 
 
@@ -486,6 +500,26 @@ def psd_decode_block_cached(model: Model, tokens: torch.Tensor, block_start: int
     _check(model.lib.psd_decode_block_cached(model.handle, _ptr(tokens), B, N, block_start, L, C.byref(pol), C.byref(g), cstats,
                                              _ptr(cache.mem), cache.capacity, _ptr(ws), nb, _stream()))
     return _add_stats(stats, cstats, B)
+
+
+def psd_calibrate_graph(model: Model, tokens: torch.Tensor, prompt_len: int, L: int, policy: Policy,
+                        candidates: Sequence[Graph], cache: Optional[KvCache] = None):
+    """Offline choice of the draft graph: decodes the calibration batch tokens [B, N] (left untouched) once per
+    candidate and returns (index of the candidate with the highest tokens/s, list of score dicts)."""
+    B, N = tokens.shape
+    K = max(g.K for g in candidates)
+    extra = model.lib.psd_decode_scratch_bytes(B, N, L, K)
+    _check(extra)
+    ws, nb = model.forward_ws(B * K, N, L, extra=extra)
+    work = torch.empty_like(tokens)
+    cg = (_Graph * len(candidates))(*[g.c() for g in candidates])
+    scores = (_GraphScore * len(candidates))()
+    best = C.c_int32(-1)
+    pol = policy.c()
+    _check(model.lib.psd_calibrate_graph(model.handle, _ptr(tokens), _ptr(work), B, N, prompt_len, L, C.byref(pol), cg,
+                                         len(candidates), scores, C.byref(best), None if cache is None else _ptr(cache.mem),
+                                         0 if cache is None else cache.capacity, _ptr(ws), nb, _stream()))
+    return int(best.value), [{k: getattr(sc, k) for k, _ in _GraphScore._fields_} for sc in scores]
 
 
 def decode(model: Model, tokens: torch.Tensor, prompt_len: int, L: int, policy: Policy, graph: Graph) -> List[Stats]:

@@ -295,6 +295,18 @@ int32_t psd_graph_chain(int32_t K, int32_t width, psd_graph *out) {
     return PSD_OK;
 }
 
+int32_t psd_graph_lattice(int32_t depth, psd_graph *out) {
+    if (!out) PSD_FAIL(PSD_ERR_INVALID_ARG, "out is NULL");
+    if (depth < 0 || (1 << depth) > PSD_MAX_NODES) PSD_FAIL(PSD_ERR_SHAPE, "lattice over %d ranks (0..5)", depth);
+    memset(out, 0, sizeof(*out));
+    out->K = 1 << depth;
+    int k = 0;
+    for (int size = 0; size <= depth; ++size)            // by subset size, then by value: the root comes first
+        for (uint64_t set = 0; set < (1ull << depth); ++set)
+            if (__builtin_popcountll(set) == size) out->rank_set[k++] = set;
+    return PSD_OK;
+}
+
 int32_t psd_forward_confidence(psd_handle *h, const int32_t *tokens, int32_t S, int32_t N, int32_t block_start, int32_t L,
                                int32_t *top1, float *conf, void *ws, int64_t ws_bytes, void *stream) {
     CHECK(check_block(h, S, N, block_start, L));
@@ -583,6 +595,75 @@ int32_t psd_decode_block_cached(psd_handle *h, int32_t *tokens, int32_t B, int32
     a.capacity = capacity;
     a.len = block_start;
     return decode_block_impl(h, tokens, B, N, block_start, L, policy, graph, stats, ws, ws_bytes, stream, &a);
+}
+
+// ---- offline calibration of the draft graph ----
+
+int32_t psd_calibrate_graph(psd_handle *h, const int32_t *tokens, int32_t *work_tokens, int32_t B, int32_t N, int32_t n_prompt,
+                            int32_t L, const psd_policy *policy, const psd_graph *candidates, int32_t n_candidates,
+                            psd_graph_score *scores, int32_t *best, void *cache, int32_t capacity, void *ws, int64_t ws_bytes,
+                            void *stream) {
+    CHECK(check_block(h, B, N, 0, L));
+    CHECK(check_policy(policy));
+    if (!tokens || !work_tokens || !candidates || !scores || !best) PSD_FAIL(PSD_ERR_INVALID_ARG, "NULL argument");
+    if (n_candidates < 1) PSD_FAIL(PSD_ERR_INVALID_ARG, "no candidate graph");
+    if (n_prompt < 0 || n_prompt >= N || (N - n_prompt) % L) PSD_FAIL(PSD_ERR_SHAPE, "the generated part must be whole blocks of %d", L);
+    if (cache && n_prompt % L) PSD_FAIL(PSD_ERR_SHAPE, "cached decoding needs a prompt of whole blocks");
+    GraphArg g;
+    for (int c = 0; c < n_candidates; ++c) CHECK(check_graph(candidates + c, &g));   // all checked before anything runs
+    psd_policy pol = *policy;
+    pol.eos_stop = 0;
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t e0, e1;
+    PSD_HIP(hipEventCreate(&e0));
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        PSD_FAIL(PSD_ERR_DEVICE, "hipEventCreate failed");
+    }
+    int32_t rc = PSD_OK;
+    std::vector<psd_stats> stats(B);
+    for (int c = 0; c < n_candidates && rc == PSD_OK; ++c) {
+        memset(stats.data(), 0, sizeof(psd_stats) * B);
+        if (hipMemcpyAsync(work_tokens, tokens, sizeof(int32_t) * (size_t)B * N, hipMemcpyDeviceToDevice, st) != hipSuccess) {
+            rc = PSD_ERR_DEVICE;
+            psd_set_error("psd_calibrate_graph: copy of the calibration batch failed");
+            break;
+        }
+        if (cache) {
+            rc = psd_kv_reset(h, cache, B, capacity, stream);
+            if (rc == PSD_OK) rc = psd_kv_prefill(h, work_tokens, B, N, n_prompt, L, cache, capacity, ws, ws_bytes, stream);
+            if (rc != PSD_OK) break;
+        }
+        (void)hipEventRecord(e0, st);
+        for (int start = n_prompt; start < N && rc == PSD_OK; start += L)
+            rc = cache ? psd_decode_block_cached(h, work_tokens, B, N, start, L, &pol, candidates + c, stats.data(), cache, capacity,
+                                                 ws, ws_bytes, stream)
+                       : psd_decode_block(h, work_tokens, B, N, start, L, &pol, candidates + c, stats.data(), ws, ws_bytes, stream);
+        if (rc != PSD_OK) break;
+        (void)hipEventRecord(e1, st);
+        float ms = 0.f;
+        if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess) {
+            rc = PSD_ERR_DEVICE;
+            psd_set_error("psd_calibrate_graph: timing failed");
+            break;
+        }
+        psd_graph_score &sc = scores[c];
+        sc.tokens = sc.invocations = 0;
+        for (int b = 0; b < B; ++b) {
+            sc.tokens += stats[b].tokens_policy + stats[b].tokens_draft + stats[b].tokens_postverify;
+            sc.invocations += stats[b].invocations;
+        }
+        sc.seconds = ms * 1e-3;
+        sc.tokens_per_s = sc.seconds > 0 ? sc.tokens / sc.seconds : 0.0;
+        sc.tpf = sc.invocations > 0 ? (double)sc.tokens / (double)sc.invocations : 0.0;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != PSD_OK) return rc;
+    *best = 0;
+    for (int c = 1; c < n_candidates; ++c)
+        if (scores[c].tokens_per_s > scores[*best].tokens_per_s) *best = c;
+    return PSD_OK;
 }
 
 // ---- kernel-level hooks: the same launchers the forward uses, on caller-provided buffers ----

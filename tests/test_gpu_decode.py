@@ -165,6 +165,39 @@ def test_eos_stop_in_a_batch_over_several_blocks_equals_sequences_alone():
     assert any(not s.stopped for s in stats)
 
 
+def test_graph_calibration_scores_every_candidate_like_the_oracle():
+    """Offline choice of the draft graph (Sec. 3.2 stage 2): every candidate's tokens, invocations and TPF on the
+    calibration batch must be the oracle's for that graph (fp32 model, exact); the winner is the candidate with the
+    highest measured tokens per second; the batch itself is left untouched."""
+    import paper_2605_15609_amd as psd
+    w = inp.WORKLOADS[1]
+    shape, P, L = w.shape, w.prompt_len, w.block_len
+    host = inp.draw_model(shape, w.seq_len)
+    model = psd.Model.from_host(host, DEV)
+    fn = orc.model_confidence_fn(host)
+    B = 2
+    tokens0 = np.full((B, w.seq_len), shape.mask_id, dtype=np.int32)
+    for b in range(B):
+        tokens0[b, :P] = inp.draw_prompt(shape.vocab, P, 400 + b)
+    cands = [psd.chain_graph(1), psd.chain_graph(2), psd.chain_graph(4), psd.chain_graph(3, 2), psd.lattice_graph(2),
+             psd.lattice_graph(3), psd.Graph((0, 1, 2, 3, 6))]
+    d = _dev(tokens0)
+    best, scores = psd.psd_calibrate_graph(model, d, P, L, psd.Policy(0.05, 1, 0), cands)
+    assert (d.cpu().numpy() == tokens0).all()
+    for g, sc in zip(cands, scores):
+        og = orc.Graph(tuple(frozenset(r for r in range(64) if (rs >> r) & 1) for rs in g.rank_sets))
+        tok = inv = 0
+        for b in range(B):
+            _, st = orc.decode(fn, tokens0[b], P, L, orc.Policy(0.05, 1, 0), og, shape.mask_id)
+            tok, inv = tok + st.tokens, inv + st.invocations
+        assert (sc["tokens"], sc["invocations"]) == (tok, inv) and tok == B * (w.seq_len - P), g.rank_sets
+        assert sc["tpf"] == pytest.approx(tok / inv) and sc["seconds"] > 0
+        assert sc["tokens_per_s"] == pytest.approx(tok / sc["seconds"])
+    assert best == max(range(len(cands)), key=lambda c: (scores[c]["tokens_per_s"], -c))
+    with pytest.raises(psd.PsdError):
+        psd.psd_calibrate_graph(model, d, P + 1, L, psd.Policy(), cands)        # generated part not whole blocks
+
+
 def _lockstep(workload, shape, n_blocks, guard=1e-3, max_iters=10 ** 9):
     import paper_2605_15609_amd as psd
     from tests.gpu_common import gpu_graph

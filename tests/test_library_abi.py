@@ -39,6 +39,15 @@ def test_host_only_entry_points(lib):
     assert psd.chain_graph(3, 2).rank_sets == (0, 3, 15)
     with pytest.raises(psd.PsdError):
         psd.chain_graph(40)
+    # subset lattice: every subset of the top ranks exactly once, root first, by size
+    import itertools
+    for depth in range(0, 6):
+        sets = psd.lattice_graph(depth).rank_sets
+        want = [sum(1 << r for r in c) for n in range(depth + 1) for c in itertools.combinations(range(depth), n)]
+        assert sorted(sets) == sorted(want) and len(sets) == 2 ** depth and sets[0] == 0
+        assert [bin(x).count("1") for x in sets] == sorted(bin(x).count("1") for x in sets)
+    with pytest.raises(psd.PsdError):
+        psd.lattice_graph(6)
     assert lib.psd_decode_scratch_bytes(1, 512, 32, 4) > 4 * 512 * 4
     assert lib.psd_decode_scratch_bytes(0, 512, 32, 4) < 0
 
