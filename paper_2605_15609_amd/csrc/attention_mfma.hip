@@ -18,6 +18,7 @@
 // query heads of a group simply read the same K / V^T tiles (they hit L2).
 #include "psd_internal.h"
 #include "device_types.h"
+#include "rope_device.h"
 
 namespace {
 
@@ -253,12 +254,11 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(const bf16_t *__r
 // vT[s][kvh][c][pi(i)] = qkv[s*N + i][(H + Hkv + kvh)*dh + c], 64x64 tiles through LDS.  Rows of vT (stride ld_vt)
 // hold N rounded up to 64 keys, the tail zero.  Inside every group of 16 keys the order is 0-3, 8-11, 4-7, 12-15: the
 // contraction-slot order of the second attention MFMA, so that a lane's 8 values are one 16-byte piece.
-__global__ __launch_bounds__(256) void transpose_v_kernel(const bf16_t *__restrict__ qkv, int ld_qkv, int N, int n_heads,
-                                                          int n_kv_heads, int d_head, bf16_t *__restrict__ vT, int ld_vt) {
+__device__ __forceinline__ void transpose_v_tile(const bf16_t *__restrict__ qkv, int ld_qkv, int N, int n_heads, int n_kv_heads,
+                                                 int d_head, bf16_t *__restrict__ vT, int ld_vt, int i0, int cg, int s) {
     __shared__ uint16_t tile[64][66];
-    const int i0 = blockIdx.x * 64, cg = blockIdx.y, s = blockIdx.z;   // cg indexes 64-wide column groups of all KV heads
     const int row_w = ld_qkv;
-    const int col0 = cg * 64;                                          // within the V part
+    const int col0 = cg * 64;                                          // within the V part; cg indexes 64-wide column groups of all KV heads
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     for (int r = ty; r < 64; r += 4) {
         const int i = i0 + r;
@@ -274,6 +274,28 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const bf16_t *__restri
     }
 }
 
+__global__ __launch_bounds__(256) void transpose_v_kernel(const bf16_t *__restrict__ qkv, int ld_qkv, int N, int n_heads,
+                                                          int n_kv_heads, int d_head, bf16_t *__restrict__ vT, int ld_vt) {
+    transpose_v_tile(qkv, ld_qkv, N, n_heads, n_kv_heads, d_head, vT, ld_vt, blockIdx.x * 64, blockIdx.y, blockIdx.z);
+}
+
+// Rotary on the q and k heads and the transpose of V touch disjoint columns of the same qkv rows: one launch does
+// both.  Workgroups [0, tokens) rotate one token each, the rest move one 64x64 tile of V (tile index: key tile
+// fastest, then column group, then sequence).
+__global__ __launch_bounds__(256) void rope_transpose_v_kernel(bf16_t *__restrict__ qkv, int ld_qkv, int N, int pos0, int n_heads,
+                                                               int n_kv_heads, int d_head, const float *__restrict__ cos_t,
+                                                               const float *__restrict__ sin_t, bf16_t *__restrict__ vT, int ld_vt,
+                                                               int tokens, int tiles_i, int tiles_c) {
+    if ((int)blockIdx.x < tokens) {
+        const int64_t t = blockIdx.x;
+        rope_bf16_vec_token(qkv + t * (int64_t)ld_qkv, pos0 + (int)(t % N), n_heads, n_kv_heads, d_head, cos_t, sin_t);
+    } else {
+        const int idx = (int)blockIdx.x - tokens;
+        transpose_v_tile(qkv, ld_qkv, N, n_heads, n_kv_heads, d_head, vT, ld_vt, (idx % tiles_i) * 64, (idx / tiles_i) % tiles_c,
+                         idx / (tiles_i * tiles_c));
+    }
+}
+
 }   // namespace
 
 void launch_transpose_v(const bf16_t *qkv, int ld_qkv, int S, int N, int n_heads, int n_kv_heads, int d_head, bf16_t *vT,
@@ -281,6 +303,13 @@ void launch_transpose_v(const bf16_t *qkv, int ld_qkv, int S, int N, int n_heads
     const int N_pad = (N + 63) / 64 * 64;
     hipLaunchKernelGGL(transpose_v_kernel, dim3(N_pad / 64, n_kv_heads * d_head / 64, S), dim3(256), 0, st, qkv, ld_qkv, N,
                        n_heads, n_kv_heads, d_head, vT, (int)vt_row_stride(N));
+}
+
+void launch_rope_transpose_v(bf16_t *qkv, int ld_qkv, int S, int N, int pos0, int n_heads, int n_kv_heads, int d_head,
+                             const float *cos_t, const float *sin_t, bf16_t *vT, hipStream_t st) {
+    const int tiles_i = (N + 63) / 64, tiles_c = n_kv_heads * d_head / 64, tokens = S * N;
+    hipLaunchKernelGGL(rope_transpose_v_kernel, dim3((unsigned)(tokens + tiles_i * tiles_c * S)), dim3(256), 0, st, qkv, ld_qkv, N,
+                       pos0, n_heads, n_kv_heads, d_head, cos_t, sin_t, vT, (int)vt_row_stride(N), tokens, tiles_i, tiles_c);
 }
 
 template <int DH, int NW, int NSTG>

@@ -61,8 +61,9 @@ struct Dispatch<float> {
                                         resid, ldo, st);
         return PendingSums();
     }
-    static void attention(psd_handle *, float *qkv, int ld_qkv, float *, int S, int N, int H, int Hkv, int dh, float *out,
-                          const KvPrefix &pre, int block_len, hipStream_t st) {
+    static void rope_attention(psd_handle *h, float *qkv, int ld_qkv, float *, int S, int N, int pos0, int H, int Hkv, int dh,
+                               float *out, const KvPrefix &pre, int block_len, hipStream_t st) {
+        launch_rope<float>(qkv, ld_qkv, (int64_t)S * N, N, pos0, H, Hkv, dh, h->rope_cos, h->rope_sin, st);
         launch_plain_attention<float>(qkv, ld_qkv, S, N, H, Hkv, dh, out, pre, block_len, st);
     }
 };
@@ -97,14 +98,17 @@ struct Dispatch<bf16_t> {
         }
         return pend;
     }
+    // Rotary on q and k (row i of a sequence sits at position pos0 + i), then attention.
     // pre: KV prefix that every own row sees; block_len > 0: context-causal blocks among the own rows (only the
     // plain kernel masks; the product path of that attention mode keeps finished blocks in the prefix instead)
-    static void attention(psd_handle *h, bf16_t *qkv, int ld_qkv, bf16_t *vT, int S, int N, int H, int Hkv, int dh, bf16_t *out,
-                          const KvPrefix &pre, int block_len, hipStream_t st) {
+    static void rope_attention(psd_handle *h, bf16_t *qkv, int ld_qkv, bf16_t *vT, int S, int N, int pos0, int H, int Hkv, int dh,
+                               bf16_t *out, const KvPrefix &pre, int block_len, hipStream_t st) {
         if ((h->plain_mask & 2) || (N % 8) != 0 || (block_len > 0 && block_len < N)) {
+            launch_rope<bf16_t>(qkv, ld_qkv, (int64_t)S * N, N, pos0, H, Hkv, dh, h->rope_cos, h->rope_sin, st);
             launch_plain_attention<bf16_t>(qkv, ld_qkv, S, N, H, Hkv, dh, out, pre, block_len, st);
         } else {
-            launch_transpose_v(qkv, ld_qkv, S, N, H, Hkv, dh, vT, st);
+            // the matrix-core kernel reads V transposed; rotary and that transpose share one launch
+            launch_rope_transpose_v(qkv, ld_qkv, S, N, pos0, H, Hkv, dh, h->rope_cos, h->rope_sin, vT, st);
             launch_attention_bf16(qkv, ld_qkv, vT, S, N, H, Hkv, dh, out, pre, st);
         }
     }
@@ -145,8 +149,8 @@ int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t 
             Dispatch<T>::gemm(h, a, d, wk, nullptr, d, ntok, Hkv * dh, d, epi_qkv, lw.bk, qkv + H * dh, nullptr, ld_qkv, nullptr, st);
             Dispatch<T>::gemm(h, a, d, wv, nullptr, d, ntok, Hkv * dh, d, epi_qkv, lw.bv, qkv + (H + Hkv) * dh, nullptr, ld_qkv, nullptr, st);
         }
-        launch_rope<T>(qkv, ld_qkv, ntok, N, 0, H, Hkv, dh, h->rope_cos, h->rope_sin, st);
-        Dispatch<T>::attention(h, qkv, ld_qkv, vT, S, N, H, Hkv, dh, o, KvPrefix(), c.attention == PSD_ATTN_BLOCK_CAUSAL ? L : 0, st);
+        Dispatch<T>::rope_attention(h, qkv, ld_qkv, vT, S, N, 0, H, Hkv, dh, o, KvPrefix(),
+                                    c.attention == PSD_ATTN_BLOCK_CAUSAL ? L : 0, st);
         // After the last attention only the block rows feed the LM-head: the rest of that layer (output
         // projection, FFN) and the final norm run on those S*L rows alone, gathered into a packed stream.
         float *hs = hbuf;
@@ -218,8 +222,7 @@ int32_t forward_cached_impl(psd_handle *h, const int32_t *tokens, const int32_t 
             Dispatch<T>::gemm(h, a, d, wk, nullptr, d, nrow, Hkv * dh, d, epi_qkv, lw.bk, qkv + H * dh, nullptr, ld_qkv, nullptr, st);
             Dispatch<T>::gemm(h, a, d, wv, nullptr, d, nrow, Hkv * dh, d, epi_qkv, lw.bv, qkv + (H + Hkv) * dh, nullptr, ld_qkv, nullptr, st);
         }
-        launch_rope<T>(qkv, ld_qkv, nrow, L, block_start, H, Hkv, dh, h->rope_cos, h->rope_sin, st);
-        Dispatch<T>::attention(h, qkv, ld_qkv, vT, S, L, H, Hkv, dh, o, pre, 0, st);
+        Dispatch<T>::rope_attention(h, qkv, ld_qkv, vT, S, L, block_start, H, Hkv, dh, o, pre, 0, st);
         if (kv.append) launch_kv_append<T>(qkv, ld_qkv, S, L, H, Hkv, dh, k_cache, vt_cache, pre, st);
         pend = Dispatch<T>::gemm(h, o, H * dh, lw.wo, nullptr, H * dh, nrow, d, H * dh, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, ksplit, st);
         launch_rmsnorm<T>(hbuf, nrow, d, lw.ffn_norm, c.rms_eps, a, pend, st);

@@ -181,6 +181,10 @@ inline int64_t padded_row_stride(int64_t width) { return width + 64; }
 inline int64_t qkv_row_stride(int64_t w) { return w; }
 inline int64_t vt_row_stride(int64_t N) { return (N + 63) / 64 * 64; }
 // vT[s][kvh][c][i] <- V part of qkv[s*N + i] (rows of vt_row_stride(N) elements); the MFMA attention reads values key-contiguous
+// rotary in place on q and k (position pos0 + row index inside the sequence) and V transposed into vT, one launch;
+// d_head % 16 == 0
+void launch_rope_transpose_v(bf16_t *qkv, int ld_qkv, int S, int N, int pos0, int n_heads, int n_kv_heads, int d_head,
+                             const float *cos_t, const float *sin_t, bf16_t *vT, hipStream_t st);
 void launch_transpose_v(const bf16_t *qkv, int ld_qkv, int S, int N, int n_heads, int n_kv_heads, int d_head, bf16_t *vT,
                         hipStream_t st);
 
