@@ -39,7 +39,13 @@ typedef __attribute__((address_space(3))) void lds_void;
 // pre: keys and values that precede the sequence's own N rows (a KV cache of pre.len positions, shared by
 // pre.seqs_per_cache consecutive sequences).  Every query sees all of them and all N own keys: with the own rows
 // being one block, that is context-causal block attention.  pre.len = 0: plain bidirectional attention.
-template <int DH, int NW, int NSTG>
+//
+// KSP > 1 (= NW): key-split mode for a single block of 32 queries.  The NW wavefronts all take the same queries
+// and deal the key tiles round-robin; each runs the tile loop on its own, with a ring of its own in LDS (no
+// barrier inside the loop), and the partial (max, sum, O^T) are merged in wavefront order at the end.  A lone
+// wavefront per (sequence, head) walks its tiles as one serial chain of fetch, MFMA, softmax, MFMA; the split
+// shortens that chain, which is all the time there is on the block-row path.
+template <int DH, int NW, int NSTG, int KSP = 1>
 __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(const bf16_t *__restrict__ qkv, int ld_qkv,
                                                             const bf16_t *__restrict__ vT, int ld_vt, int N, int n_heads,
                                                             int n_kv_heads, bf16_t *__restrict__ out, KvPrefix pre) {
@@ -51,25 +57,31 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(const bf16_t *__r
     constexpr int CT = DH / 32;                  // output subtiles along the head dimension
     constexpr int KS = DH / 16;                  // k-steps of the score contraction
     constexpr int KRPI = 1024 / KROW;            // K rows moved by one DMA instruction (4 or 8)
-    constexpr int KG = BKV / KRPI / NW;          // K-tile DMA instructions per wavefront
-    constexpr int VG = DH / 8 / NW;              // V^T-tile DMA instructions per wavefront (8 rows each)
-    extern __shared__ __align__(16) unsigned char lds[];
+    static_assert(KSP == 1 || KSP == NW, "key-split mode: every wavefront of the workgroup takes part");
+    constexpr int NWD = KSP > 1 ? 1 : NW;        // wavefronts that share the fetch of one tile
+    constexpr int KG = BKV / KRPI / NWD;         // K-tile DMA instructions per wavefront
+    constexpr int VG = DH / 8 / NWD;             // V^T-tile DMA instructions per wavefront (8 rows each)
+    extern __shared__ __align__(16) unsigned char lds_all[];
     // Swizzle key of a K row.  The 64 LDS banks span 256 bytes: 128-byte rows (d_head 64) alternate between the
     // two halves, so rows r and r+1 may share a chunk slot and the key is (r >> 1) & 7 as in the GEMM tiles;
     // 256-byte rows (d_head 128) all start at bank 0 and need 16 different slots for 16 consecutive rows.
     auto kkey = [](int r) { return DH == 128 ? (r & 15) : ((r >> 1) & 7); };
 
-    const int q0 = blockIdx.x * (32 * NW), head = blockIdx.y, s = blockIdx.z;
+    const int head = blockIdx.y, s = blockIdx.z;
     const int kvh = head / (n_heads / n_kv_heads);
     const int row_w = ld_qkv;
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tid = threadIdx.x, lane = tid & 63, wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // key-split: one query block per workgroup, a private ring per wavefront, every wavefront fetches whole tiles
+    const int q_base = KSP > 1 ? blockIdx.x * 32 : blockIdx.x * (32 * NW) + wave_id * 32;   // this wavefront's first query
+    const int wave = KSP > 1 ? 0 : wave_id;      // index among the wavefronts that share a tile's fetch
+    unsigned char *lds = lds_all + (KSP > 1 ? wave_id * (NSTG * STAGE) : 0);
     const int lrow = lane & 31, lhalf = lane >> 5;
     const bf16_t *seq = qkv + (int64_t)s * N * row_w;
 
     // Q fragments: lane (q = lrow, half) holds Q[q][16*ks + 8*half .. +7]
     bf16x8 qf[KS];
     {
-        const int q = q0 + wave * 32 + lrow;
+        const int q = q_base + lrow;
         const bf16_t *qp = seq + (int64_t)q * row_w + head * DH;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -101,16 +113,16 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(const bf16_t *__r
     {                                                                                                            \
         unsigned char *sk_ = lds + (stage) * STAGE + wave * 1024, *sv_ = lds + (stage) * STAGE + K_BYTES + wave * 1024; \
         _Pragma("unroll") for (int j = 0; j < KG; ++j) {                                                         \
-            const int row = (j * NW + wave) * KRPI + lane / KLPR;                                                \
+            const int row = (j * NWD + wave) * KRPI + lane / KLPR;                                                \
             const int voff = (lane / KLPR) * (ldk_) * 2 + (((lane % KLPR) ^ kkey(row)) << 4);                     \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rk_, (lds_void *)(sk_ + j * (NW * 1024)), 16, voff,         \
-                                                     (((k0) + (j * NW + wave) * KRPI) * (ldk_)) * 2, 0, 0);       \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rk_, (lds_void *)(sk_ + j * (NWD * 1024)), 16, voff,         \
+                                                     (((k0) + (j * NWD + wave) * KRPI) * (ldk_)) * 2, 0, 0);       \
         }                                                                                                        \
         _Pragma("unroll") for (int j = 0; j < VG; ++j) {                                                         \
-            const int row = (j * NW + wave) * 8 + (lane >> 3);                                                   \
+            const int row = (j * NWD + wave) * 8 + (lane >> 3);                                                   \
             const int voff = (lane >> 3) * (ldv_) * 2 + (((lane & 7) ^ ((row >> 1) & 7)) << 4);                  \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rv_, (lds_void *)(sv_ + j * (NW * 1024)), 16, voff,         \
-                                                     ((j * NW + wave) * 8 * (ldv_) + (k0)) * 2, 0, 0);            \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rv_, (lds_void *)(sv_ + j * (NWD * 1024)), 16, voff,         \
+                                                     ((j * NWD + wave) * 8 * (ldv_) + (k0)) * 2, 0, 0);            \
         }                                                                                                        \
     }
 // tile tt of the key sequence: prefix tiles first, then the own rows
@@ -122,7 +134,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(const bf16_t *__r
 #define PSD_ATT_SYNC()                                                                                           \
     {                                                                                                            \
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NSTG - 2) * (KG + VG)) : "memory");                            \
-        __builtin_amdgcn_s_barrier();                                                                            \
+        if constexpr (KSP == 1) __builtin_amdgcn_s_barrier();   /* a private ring needs no agreement */          \
         asm volatile("" ::: "memory");                                                                           \
     }
 
@@ -140,18 +152,21 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(const bf16_t *__r
     // the next tile has landed.
     static_assert(NSTG >= 2 && (NSTG - 1) * (KG + VG) <= 63, "DMA groups in flight must fit the vmcnt counter");
     const int n_tiles = n_pre + (N + BKV - 1) / BKV;
+    // this wavefront's tiles: all of them, or every KSP-th one
+    constexpr int TSTEP = KSP;
+    const int t_first = KSP > 1 ? wave_id : 0;
 #pragma unroll
-    for (int p = 0; p < NSTG - 1; ++p) PSD_ATT_DMA(p, p)
+    for (int p = 0; p < NSTG - 1; ++p) PSD_ATT_DMA(p, t_first + p * TSTEP)
     PSD_ATT_SYNC()
 
     int stage = 0;
-    for (int t = 0; t < n_tiles; ++t) {
+    for (int t = t_first; t < n_tiles; t += TSTEP) {
         // first key of the tile within its segment, and the number of keys that segment has
         const int k0 = (t < n_pre ? t : t - n_pre) * BKV, limit = t < n_pre ? pre.len : N;
         // refill the slot every wavefront left at the last barrier; past the last tile the fetch is rejected or
         // reads padding and is never consumed
         const int fill = (stage == 0) ? NSTG - 1 : stage - 1;
-        PSD_ATT_DMA(fill, t + (NSTG - 1))
+        PSD_ATT_DMA(fill, t + (NSTG - 1) * TSTEP)
         const unsigned char *sk = lds + stage * STAGE, *sv = sk + K_BYTES;
 
         // scores, transposed: acc_s[kt][v] <-> key 32*kt + 8*(v/4) + 4*half + v%4, query lrow
@@ -234,8 +249,36 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(const bf16_t *__r
 
     // the two half-waves of a query hold disjoint key subsets of the sum
     l_run += __shfl_xor(l_run, 32, 64);
+    if constexpr (KSP > 1) {
+        // merge the wavefronts' partial results in wavefront order: the others leave (max, sum, O^T) in their own
+        // ring, wavefront 0 rescales everything to the common maximum and stores.  Field f of lane l sits at
+        // word f * 64 + l.  A wavefront without tiles contributes max = -inf, sum = 0.
+        float *mine = reinterpret_cast<float *>(lds);
+        if (wave_id > 0) {
+            mine[lane] = m_run;
+            mine[64 + lane] = l_run;
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mine[(2 + ct * 16 + v) * 64 + lane] = acc_o[ct][v];
+        }
+        __syncthreads();
+        if (wave_id > 0) return;
+        for (int w = 1; w < KSP; ++w) {
+            const float *other = reinterpret_cast<const float *>(lds_all + w * (NSTG * STAGE));
+            const float m_o = other[lane], l_o = other[64 + lane];
+            const float m_new = fmaxf(m_run, m_o);
+            const float a_me = exp2f((m_run - m_new) * sl2), a_o = exp2f((m_o - m_new) * sl2);
+            l_run = l_run * a_me + l_o * a_o;
+            m_run = m_new;
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc_o[ct][v] = acc_o[ct][v] * a_me + other[(2 + ct * 16 + v) * 64 + lane] * a_o;
+        }
+    }
     const float inv = 1.0f / l_run;
-    const int q = q0 + wave * 32 + lrow;
+    const int q = q_base + lrow;
     if (q < N) {
         bf16_t *op = out + ((int64_t)s * N + q) * (n_heads * DH) + head * DH;
 #pragma unroll
@@ -312,18 +355,20 @@ void launch_rope_transpose_v(bf16_t *qkv, int ld_qkv, int S, int N, int pos0, in
                        pos0, n_heads, n_kv_heads, d_head, cos_t, sin_t, vT, (int)vt_row_stride(N), tokens, tiles_i, tiles_c);
 }
 
-template <int DH, int NW, int NSTG>
+template <int DH, int NW, int NSTG, int KSP = 1>
 static void launch_att(const bf16_t *qkv, int ld_qkv, const bf16_t *vT, int S, int N, int n_heads, int n_kv_heads, bf16_t *out,
                        const KvPrefix &pre, hipStream_t st) {
-    constexpr int smem = NSTG * (BKV * DH * 2 + DH * BKV * 2);
-    static_assert(smem <= 160 * 1024, "LDS ring exceeds the 160 KB of a CU");
-    auto kern = attention_kernel<DH, NW, NSTG>;
+    constexpr int smem = KSP * NSTG * (BKV * DH * 2 + DH * BKV * 2);
+    static_assert(smem <= 160 * 1024, "LDS rings exceed the 160 KB of a CU");
+    static_assert(KSP == 1 || (2 + DH / 32 * 16) * 64 * 4 <= NSTG * (BKV * DH * 2 + DH * BKV * 2), "merge data fit a ring");
+    auto kern = attention_kernel<DH, NW, NSTG, KSP>;
     static bool attr_done = false;
     if (!attr_done) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         attr_done = true;
     }
-    dim3 grid((N + 32 * NW - 1) / (32 * NW), n_heads, S);
+    constexpr int q_per_wg = KSP > 1 ? 32 : 32 * NW;
+    dim3 grid((N + q_per_wg - 1) / q_per_wg, n_heads, S);
     hipLaunchKernelGGL(kern, grid, dim3(NW * 64), smem, st, qkv, ld_qkv, vT, (int)vt_row_stride(N), N, n_heads, n_kv_heads, out,
                        pre);
 }
@@ -333,16 +378,16 @@ static void launch_att(const bf16_t *qkv, int ld_qkv, const bf16_t *vT, int S, i
 constexpr int NSTG = 2;
 void launch_attention_bf16(const bf16_t *qkv, int ld_qkv, const bf16_t *vT, int S, int N, int n_heads, int n_kv_heads, int d_head,
                            bf16_t *out, const KvPrefix &pre, hipStream_t st) {
-    // 128 queries per workgroup when that still gives two workgroups per CU, else 64; one wavefront for a
-    // single block of 32 queries
+    // 128 queries per workgroup when that still gives two workgroups per CU, else 64; a single block of 32
+    // queries (block-row path) is split along the keys over as many wavefronts as have room for a ring each
     const int64_t blocks128 = (int64_t)((N + 127) / 128) * n_heads * S;
     const bool small = blocks128 < 512;
     if (d_head == 128) {
-        if (N <= 32) launch_att<128, 1, NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
+        if (N <= 32) launch_att<128, 2, NSTG, 2>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
         else if (small) launch_att<128, 2, NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
         else launch_att<128, 4, NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
     } else {
-        if (N <= 32) launch_att<64, 1, NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
+        if (N <= 32) launch_att<64, 4, NSTG, 4>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
         else if (small) launch_att<64, 2, NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
         else launch_att<64, 4, NSTG>(qkv, ld_qkv, vT, S, N, n_heads, n_kv_heads, out, pre, st);
     }
