@@ -200,8 +200,11 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(const bf16_t *__r
 #pragma unroll
             for (int v = 0; v < 16; ++v) mx = fmaxf(mx, acc_s[kt][v]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        // exp(x - m) as the bare v_exp_f32 of (x * sl2 - m * sl2): one fused multiply-add per score, no
+        // denormal handling (a probability below 2^-126 is zero)
         const float m_new = fmaxf(m_run, mx);
-        const float alpha = exp2f((m_run - m_new) * sl2);
+        const float m_s = m_new * sl2;
+        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sl2);
         float psum = 0.f;
         bf16x8 pf[4];   // P^T as B operands, one per group of 16 keys
 #pragma unroll
@@ -209,7 +212,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(const bf16_t *__r
             float p[16];
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                p[v] = exp2f((acc_s[kt][v] - m_new) * sl2);
+                p[v] = __builtin_amdgcn_exp2f(__builtin_fmaf(acc_s[kt][v], sl2, -m_s));
                 psum += p[v];
             }
 #pragma unroll
@@ -268,7 +271,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(const bf16_t *__r
             const float *other = reinterpret_cast<const float *>(lds_all + w * (NSTG * STAGE));
             const float m_o = other[lane], l_o = other[64 + lane];
             const float m_new = fmaxf(m_run, m_o);
-            const float a_me = exp2f((m_run - m_new) * sl2), a_o = exp2f((m_o - m_new) * sl2);
+            const float a_me = __builtin_amdgcn_exp2f((m_run - m_new) * sl2), a_o = __builtin_amdgcn_exp2f((m_o - m_new) * sl2);
             l_run = l_run * a_me + l_o * a_o;
             m_run = m_new;
 #pragma unroll
