@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 # and tables in profiles/config3_hbm_traffic_pmc.md.  (fetched, written) MiB for the verification launch
 # (2048 tokens, 768 workgroups) and the stage-1 launch (512 tokens, 192 workgroups) of the 256x256 tile.
 SWIGLU_TRAFFIC_MIB = {"config": 3, "tile": "256x256, 8 wavefronts, LDS rings 2/3",
-                      "verify": (584.3, 48.5), "stage1": (230.7, 12.0)}
+                      "verify": (584.2, 48.6), "stage1": (230.6, 12.0)}
 
 
 def cpu_baseline(workload, stats_tokens, n_stage1, n_verify, threads_hint):
