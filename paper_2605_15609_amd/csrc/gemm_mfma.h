@@ -359,7 +359,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
                     if (EPI == EPI_BIAS) x += bn;
                     if (DUAL) {
                         const float u = acc[i][j + TN / 2][v];
-                        x = x / (1.0f + __expf(-x)) * u;
+                        x = x * __builtin_amdgcn_rcpf(1.0f + __expf(-x)) * u;   // silu(x) * u; v_rcp_f32 (1 ulp) instead of a full division
                     }
                     if (EPI == EPI_RESIDUAL) {
                         if (split == 0)
