@@ -20,7 +20,8 @@ optional grouped KV heads, SwiGLU feed-forward) is not described by the paper be
 family of the paper (App. A) uses context-causal block attention instead -- full attention
 inside a block, causal across blocks -- which `block_causal` selects; PSD itself is unchanged.
 The evaluation protocol's EOS early stopping with truncated token statistics (App. B.1) is an
-option of the decode loop (`eos_id`).
+option of the decode loop (`eos_id`).  `ApproximateCache` is a second model call for
+bidirectional models: block rows recomputed against per-layer keys / values frozen at block entry.
 
 Precision: everything is fp64.  The benchmark configurations other than the first are "bf16" models (bf16
 operands, wider accumulation): for those, `operands="bf16"` additionally rounds the INPUTS of every
@@ -135,8 +136,8 @@ def block_causal_visibility(N: int, L: int) -> np.ndarray:
 
 def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, operands: Optional[str] = None,
               visible: Optional[np.ndarray] = None) -> np.ndarray:
-    """Softmax attention. q: [N, H, dh]; k, v: [N, Hkv, dh] -> [N, H, dh].  Bidirectional (every query sees
-    every key) unless `visible` [N, N] says which keys j query i may see.
+    """Softmax attention. q: [Nq, H, dh]; k, v: [Nk, Hkv, dh] -> [Nq, H, dh].  Bidirectional (every query sees
+    every key) unless `visible` [Nq, Nk] says which keys j query i may see.
 
     Query head j reads KV head j // (H / Hkv).  With operands="bf16" the probabilities enter the second
     contraction rounded (as exp(s - max), before the division by their exact sum).
@@ -166,8 +167,12 @@ def _w(a) -> np.ndarray:
 
 
 def layer_forward(h: np.ndarray, lw: dict, shape, cos: np.ndarray, sin: np.ndarray,
-                  operands: Optional[str] = None, visible: Optional[np.ndarray] = None) -> np.ndarray:
-    """One pre-norm transformer layer on the residual stream h [N, d]."""
+                  operands: Optional[str] = None, visible: Optional[np.ndarray] = None,
+                  kv_out: Optional[list] = None, kv_frozen: Optional[tuple] = None) -> np.ndarray:
+    """One pre-norm transformer layer on the residual stream h [N, d] (cos / sin: the rotary rows of these N
+    positions).  kv_out: a list that receives this layer's (rotated keys, values), each [N, Hkv, dh], as the
+    attention uses them.  kv_frozen = (k, v): further keys and values, from positions that are not among the
+    rows of h, which every query also sees (the approximate cache)."""
     N = h.shape[0]
     H, Hkv, dh = shape.n_heads, shape.n_kv_heads, shape.d_head
     a = _operand(rmsnorm(h, _w(lw["attn_norm"]), shape.rms_eps), operands)
@@ -179,6 +184,10 @@ def layer_forward(h: np.ndarray, lw: dict, shape, cos: np.ndarray, sin: np.ndarr
     q = _operand(rope(q.reshape(N, H, dh), cos, sin), operands)
     k = _operand(rope(k.reshape(N, Hkv, dh), cos, sin), operands)
     v = _operand(v.reshape(N, Hkv, dh), operands)
+    if kv_out is not None:
+        kv_out.append((k, v))
+    if kv_frozen is not None:
+        k, v = np.concatenate([kv_frozen[0], k]), np.concatenate([kv_frozen[1], v])
     o = _operand(attention(q, k, v, operands, visible).reshape(N, H * dh), operands)
     h = h + o @ _w(lw["wo"]).T
     f = _operand(rmsnorm(h, _w(lw["ffn_norm"]), shape.rms_eps), operands)
@@ -188,7 +197,7 @@ def layer_forward(h: np.ndarray, lw: dict, shape, cos: np.ndarray, sin: np.ndarr
 
 
 def forward_hidden(model, tokens: np.ndarray, operands: Optional[str] = None,
-                   block_causal: Optional[int] = None) -> np.ndarray:
+                   block_causal: Optional[int] = None, kv_out: Optional[list] = None) -> np.ndarray:
     """Final-normed hidden states y [N, d] for one sequence (mask positions hold mask_id,
     which has an ordinary embedding row).  Positions are 0..N-1.  block_causal = L switches the
     attention of every layer from bidirectional to context-causal blocks of L."""
@@ -198,8 +207,65 @@ def forward_hidden(model, tokens: np.ndarray, operands: Optional[str] = None,
     h = _w(model.tok_emb[tokens])
     visible = None if block_causal is None else block_causal_visibility(N, block_causal)
     for lw in model.layers:
-        h = layer_forward(h, lw, model.shape, cos, sin, operands, visible)
+        h = layer_forward(h, lw, model.shape, cos, sin, operands, visible, kv_out)
     return _operand(rmsnorm(h, _w(model.final_norm), model.shape.rms_eps), operands)
+
+
+def forward_hidden_frozen(model, tokens: np.ndarray, block_start: int, L: int, frozen: list,
+                          operands: Optional[str] = None) -> np.ndarray:
+    """Final-normed hidden states of the block rows only, [L, d], with every layer's keys and values of the
+    positions OUTSIDE the block taken from `frozen` (one (k, v) pair per layer, [N - L, Hkv, dh]) instead of
+    being recomputed: the forward of a bidirectional model under an approximate KV cache.  The block rows keep
+    their positions block_start .. block_start + L - 1."""
+    blk = slice(block_start, block_start + L)
+    cos, sin = _w(model.rope_cos[blk]), _w(model.rope_sin[blk])
+    h = _w(model.tok_emb[np.asarray(tokens)[blk]])
+    for lw, kv in zip(model.layers, frozen):
+        h = layer_forward(h, lw, model.shape, cos, sin, operands, None, None, kv)
+    return _operand(rmsnorm(h, _w(model.final_norm), model.shape.rms_eps), operands)
+
+
+class ApproximateCache:
+    """Model call of a fully bidirectional model under an approximate KV cache over prefix and suffix.
+
+    The paper notes that KV-cache sharing can cut redundant computation (Sec. 3.2 stage 3) without fixing a
+    scheme; for bidirectional models any cache is an approximation.  The scheme here is the published
+    "dual cache" idea for block-wise diffusion decoding, restated: the first model call on a block (Alg. 1's
+    stage-1 call on the state the block is entered with) is an exact forward over the whole sequence, and it
+    freezes, per layer, the rotated keys and the values of every position outside the block.  Every later
+    call on that block (verification batches, later iterations) recomputes the block rows only and attends
+    to the frozen keys / values for the rest, which by then are stale: they were computed from the block's
+    earlier content.  Entering another block refreshes.  Calls are (tokens, block_start, L) ->
+    (top1, conf) like any model call of the loop; `logits` keeps the last call's block logits."""
+
+    def __init__(self, model, operands: Optional[str] = None):
+        self.model, self.operands = model, operands
+        self.block, self.outside, self.frozen, self.logits = None, None, None, None
+        self.refreshes = 0
+
+    def _outside(self, tokens, block_start, L):
+        return np.concatenate([tokens[:block_start], tokens[block_start + L:]])
+
+    def __call__(self, tokens: np.ndarray, block_start: int, L: int):
+        tokens = np.asarray(tokens)
+        m = self.model
+        if self.block != (block_start, L):
+            kv = []
+            y = forward_hidden(m, tokens, self.operands, None, kv)[block_start: block_start + L]
+            keep = np.r_[0:block_start, block_start + L:tokens.shape[0]]
+            self.frozen = [(k[keep], v[keep]) for k, v in kv]
+            self.block, self.outside = (block_start, L), self._outside(tokens, block_start, L).copy()
+            self.refreshes += 1
+        else:
+            if not np.array_equal(self._outside(tokens, block_start, L), self.outside):
+                raise ValueError("the cache holds keys and values of other tokens outside the block")
+            y = forward_hidden_frozen(m, tokens, block_start, L, self.frozen, self.operands)
+        z = m.shape.logit_scale * (y @ _w(m.lm_head).T)
+        self.logits = z
+        x_hat, c = top1_confidence(z, m.shape.mask_id)
+        blk = tokens[block_start: block_start + L]
+        masked = blk == m.shape.mask_id
+        return np.where(masked, x_hat, blk).astype(np.int32), np.where(masked, c, -1.0).astype(np.float32)
 
 
 def block_logits(model, tokens: np.ndarray, block_start: int, L: int, operands: Optional[str] = None,

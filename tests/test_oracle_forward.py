@@ -385,3 +385,103 @@ def test_block_causal_prefix_is_independent_of_what_follows():
     assert np.abs(orc.forward_hidden(model, t2)[: 2 * L] - orc.forward_hidden(model, t)[: 2 * L]).max() > 1e-3
     with pytest.raises(ValueError):
         orc.block_logits(model, t, 4, L, block_causal=True)
+
+
+# ---------------------------------------------------------------- approximate KV cache for bidirectional models
+
+
+def _torch_stack(model, tokens, override=None, keep_rows=None):
+    """The whole layer stack over ALL N rows with torch (float64).  Returns (final-normed hidden states [N, d], list of
+    per-layer (rotated keys, values)).  override: per-layer (k, v) whose rows `keep_rows` replace the freshly computed
+    ones before the attention -- i.e. those positions' keys and values are frozen."""
+    shape = model.shape
+    N, H, Hkv, dh = len(tokens), shape.n_heads, shape.n_kv_heads, shape.d_head
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    tcos, tsin = t(model.rope_cos[:N])[:, None, :], t(model.rope_sin[:N])[:, None, :]
+
+    def rot(x):
+        x1, x2 = x[..., : dh // 2], x[..., dh // 2:]
+        return torch.cat([x1 * tcos - x2 * tsin, x2 * tcos + x1 * tsin], dim=-1)
+
+    h = t(model.tok_emb[np.asarray(tokens)])
+    kvs = []
+    for li, lw in enumerate(model.layers):
+        a = torch.nn.functional.rms_norm(h, (h.shape[1],), t(lw["attn_norm"]), eps=shape.rms_eps)
+        q, k, v = a @ t(lw["wq"]).T, a @ t(lw["wk"]).T, a @ t(lw["wv"]).T
+        if lw.get("bq") is not None:
+            q, k, v = q + t(lw["bq"]), k + t(lw["bk"]), v + t(lw["bv"])
+        q, k, v = rot(q.reshape(N, H, dh)), rot(k.reshape(N, Hkv, dh)), v.reshape(N, Hkv, dh)
+        if override is not None:
+            k, v = k.clone(), v.clone()
+            k[keep_rows], v[keep_rows] = override[li][0][keep_rows], override[li][1][keep_rows]
+        kvs.append((k, v))
+        rep = H // Hkv
+        o = torch.nn.functional.scaled_dot_product_attention(q.transpose(0, 1), k.repeat_interleave(rep, 1).transpose(0, 1),
+                                                             v.repeat_interleave(rep, 1).transpose(0, 1)).transpose(0, 1)
+        h = h + o.reshape(N, H * dh) @ t(lw["wo"]).T
+        f = torch.nn.functional.rms_norm(h, (h.shape[1],), t(lw["ffn_norm"]), eps=shape.rms_eps)
+        h = h + (torch.nn.functional.silu(f @ t(lw["w_gate"]).T) * (f @ t(lw["w_up"]).T)) @ t(lw["w_down"]).T
+    return torch.nn.functional.rms_norm(h, (h.shape[1],), t(model.final_norm), eps=shape.rms_eps), kvs
+
+
+@pytest.mark.parametrize("shape", [TINY, GQA], ids=["mha", "gqa-bias"])
+def test_approximate_cache_first_call_exact_then_block_rows_against_frozen_keys_and_values(shape):
+    """The approximate cache is pinned by an independent torch evaluation over all N rows: the first call on a block is
+    the exact forward; a later call equals the full stack in which, at every layer, the keys and values of the
+    positions outside the block are overwritten by those of the first call (so the block rows see stale context, and
+    nothing else differs).  Unchanged block content reproduces the exact forward; changed content does not."""
+    N, L, start = 40, 8, 16
+    model = inp.draw_model(shape, N)
+    t0 = _tokens(shape, N, 5)
+    t0[start:start + L] = shape.mask_id
+    cache = orc.ApproximateCache(model)
+    top1, conf = cache(t0, start, L)
+    ex_top1, ex_conf, ex_z = orc.forward_confidence(model, t0, start, L, return_logits=True)
+    assert (top1 == ex_top1).all() and (conf == ex_conf).all() and cache.refreshes == 1
+    np.testing.assert_allclose(cache.logits, ex_z, rtol=0, atol=1e-12)
+    y0, kv0 = _torch_stack(model, t0)
+    np.testing.assert_allclose(y0[start:start + L].numpy() @ np.asarray(model.lm_head, dtype=np.float64).T * shape.logit_scale,
+                               ex_z, rtol=0, atol=1e-9)
+    # same content again: the frozen keys / values are exact, so is the result
+    cache(t0, start, L)
+    np.testing.assert_allclose(cache.logits, ex_z, rtol=0, atol=1e-10)
+    assert cache.refreshes == 1
+    # three block positions committed: block rows recomputed, the rest of the sequence frozen
+    t1 = t0.copy()
+    t1[[start + 1, start + 4, start + 7]] = [3, 9, 27]
+    top1, conf = cache(t1, start, L)
+    outside = np.r_[0:start, start + L:N]
+    y1, _ = _torch_stack(model, t1, override=kv0, keep_rows=torch.from_numpy(outside))
+    z_ref = y1[start:start + L].numpy() @ np.asarray(model.lm_head, dtype=np.float64).T * shape.logit_scale
+    np.testing.assert_allclose(cache.logits, z_ref, rtol=0, atol=1e-9)
+    z_exact = orc.forward_confidence(model, t1, start, L, return_logits=True)[2]
+    gap = np.abs(cache.logits - z_exact).max()
+    assert 1e-6 < gap < 0.5 * np.abs(z_exact).max()           # an approximation, and a mild one
+    assert (top1[[1, 4, 7]] == [3, 9, 27]).all() and (conf[[1, 4, 7]] == -1).all()
+    # another block refreshes; tokens changed outside the cached block are refused
+    cache(t1, start + L, L)
+    assert cache.refreshes == 2
+    bad = t1.copy()
+    bad[2] = (bad[2] + 1) % (shape.vocab - 1)
+    with pytest.raises(ValueError):
+        cache(bad, start + L, L)
+
+
+def test_approximate_cache_is_exact_when_the_block_is_the_whole_sequence_and_decodes_to_completion():
+    shape = TINY
+    N = 24
+    model = inp.draw_model(shape, N)
+    t = np.full(N, shape.mask_id, dtype=np.int32)
+    cache = orc.ApproximateCache(model)
+    cache(t, 0, N)
+    t2 = t.copy()
+    t2[5] = 17
+    cache(t2, 0, N)                                                # nothing outside the block: no stale context
+    np.testing.assert_allclose(cache.logits, orc.forward_confidence(model, t2, 0, N, return_logits=True)[2], rtol=0, atol=1e-10)
+    # the decode loop runs on it like on any model call: one refresh per block, every token resolved, TPF >= 1
+    P, L = 8, 8
+    x = np.full(P + 2 * L, shape.mask_id, dtype=np.int32)
+    x[:P] = inp.draw_prompt(shape.vocab, P, 3)
+    cache = orc.ApproximateCache(model)
+    out, st = orc.decode(cache, x, P, L, orc.Policy(0.9, 1), orc.chain_graph(3), shape.mask_id)
+    assert not (out == shape.mask_id).any() and cache.refreshes == 2 and st.tokens == 2 * L and st.tpf >= 1.0
