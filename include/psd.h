@@ -274,6 +274,31 @@ int32_t psd_decode_block_cached(psd_handle *h, int32_t *tokens, int32_t B, int32
                                 const psd_policy *policy, const psd_graph *graph, psd_stats *stats, void *cache,
                                 int32_t capacity, void *ws, int64_t ws_bytes, void *stream);
 
+/* ---- Approximate KV cache for fully bidirectional models -----------------------------------------
+ * Sec. 3.2 stage 3 notes that KV-cache sharing can cut redundant computation; with bidirectional
+ * attention any cache is an approximation, and the paper fixes no scheme.  The one offered here is the
+ * published prefix + suffix ("dual") cache of block-wise diffusion decoding: the model call that enters a
+ * block runs over the whole sequences (exact) and freezes, per layer, the rotated keys and the values of the
+ * N - L positions outside the block; every later call on that block runs on the L block rows alone and
+ * attends to the frozen entries, which are stale by then.  Results differ from the exact calls above (they
+ * are those of the same procedure under this approximation; the test oracle has the same mode).
+ * config.attention must be PSD_ATTN_BIDIRECTIONAL, L a multiple of 16.  The cache is laid out like the exact
+ * one (psd_kv_cache_bytes(cfg, capacity) per sequence, capacity >= N - L, zeroed once with psd_kv_reset).
+ *   psd_forward_confidence_approx: refresh = 1: exact call over the S whole sequences, fills cache s for
+ *     sequence s (seqs_per_cache must be 1); refresh = 0: block rows against the caches, sequence s using
+ *     cache s / seqs_per_cache (the K drafts of a verification batch share their sequence's cache).
+ *     Outputs as psd_forward_confidence_cached; ws as psd_workspace_bytes(cfg, S, refresh ? N : L, L).
+ *   psd_decode_block_approx: Alg. 1 on the block; the first stage-1 call refreshes, all other calls use the
+ *     caches.  cache for B sequences; ws_bytes >= max(psd_workspace_bytes(cfg, B, N, L),
+ *     psd_workspace_bytes(cfg, B*K, L, L)) + psd_decode_scratch_bytes(B, N, L, K). */
+int32_t psd_forward_confidence_approx(psd_handle *h, const int32_t *tokens, int32_t S, int32_t N, int32_t block_start,
+                                      int32_t L, int32_t refresh, int32_t seqs_per_cache, void *cache, int32_t capacity,
+                                      int32_t *top1, float *conf, float *logits, void *ws, int64_t ws_bytes,
+                                      void *stream);
+int32_t psd_decode_block_approx(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_t block_start, int32_t L,
+                                const psd_policy *policy, const psd_graph *graph, psd_stats *stats, void *cache,
+                                int32_t capacity, void *ws, int64_t ws_bytes, void *stream);
+
 /* Offline calibration of the draft graph (Sec. 3.2 stage 2: the topology is fixed before inference so
  * as to maximise empirical throughput).  The calibration batch -- tokens device int32 [B, N], the first
  * n_prompt positions of every row resolved, the rest [M] -- is decoded block by block once per candidate

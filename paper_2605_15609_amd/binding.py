@@ -111,6 +111,9 @@ def load_library():
                                            vp, i32, vp, i64, vp]),
         "psd_decode_block": (i32, [vp, vp, i32, i32, i32, i32, C.POINTER(_Policy), C.POINTER(_Graph), C.POINTER(_Stats),
                                    vp, i64, vp]),
+        "psd_forward_confidence_approx": (i32, [vp, vp, i32, i32, i32, i32, i32, i32, vp, i32, vp, vp, vp, vp, i64, vp]),
+        "psd_decode_block_approx": (i32, [vp, vp, i32, i32, i32, i32, C.POINTER(_Policy), C.POINTER(_Graph), C.POINTER(_Stats),
+                                          vp, i32, vp, i64, vp]),
         "psd_kernel_gemm_bf16": (i32, [vp, vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp, i32, vp]),
         "psd_kernel_gemm_residual_splitk": (i32, [vp, vp, i64, i32, i32, vp, vp, i64, i32, vp, vp]),
         "psd_kernel_attention_scratch_bytes": (i64, [i32, i32, i32, i32]),
@@ -498,6 +501,43 @@ def psd_decode_block_cached(model: Model, tokens: torch.Tensor, block_start: int
     cstats = (_Stats * B)()
     g, pol = graph.c(), policy.c()
     _check(model.lib.psd_decode_block_cached(model.handle, _ptr(tokens), B, N, block_start, L, C.byref(pol), C.byref(g), cstats,
+                                             _ptr(cache.mem), cache.capacity, _ptr(ws), nb, _stream()))
+    return _add_stats(stats, cstats, B)
+
+
+def psd_forward_confidence_approx(model: Model, tokens: torch.Tensor, block_start: int, L: int, cache: KvCache, refresh: bool,
+                                  seqs_per_cache: int = 1, want_logits: bool = False):
+    """Model call of a bidirectional model under the approximate prefix + suffix cache: refresh = exact call over the whole
+    sequences that fills the caches; otherwise the block rows against them.  Returns (top1, conf[, logits])."""
+    S, N = tokens.shape
+    ws, nb = model.forward_ws(S, N if refresh else L, L)
+    top1 = torch.empty((S, L), dtype=torch.int32, device=tokens.device)
+    conf = torch.empty((S, L), dtype=torch.float32, device=tokens.device)
+    logits = torch.empty((S * L, model.cfg.vocab), dtype=torch.float32, device=tokens.device) if want_logits else None
+    _check(model.lib.psd_forward_confidence_approx(model.handle, _ptr(tokens), S, N, block_start, L, 1 if refresh else 0,
+                                                   seqs_per_cache, _ptr(cache.mem), cache.capacity, _ptr(top1), _ptr(conf),
+                                                   _ptr(logits), _ptr(ws), nb, _stream()))
+    return (top1, conf, logits) if want_logits else (top1, conf)
+
+
+def psd_decode_block_approx(model: Model, tokens: torch.Tensor, block_start: int, L: int, policy: Policy, graph: Graph,
+                            cache: KvCache, stats: Optional[Sequence[Stats]] = None) -> List[Stats]:
+    """psd_decode_block under the approximate cache: the first model call on the block is exact and fills the caches."""
+    B, N = tokens.shape
+    K = graph.K
+    extra = model.lib.psd_decode_scratch_bytes(B, N, L, K)
+    _check(extra)
+    full = model.lib.psd_workspace_bytes(C.byref(model.cfg), B, N, L)
+    rows = model.lib.psd_workspace_bytes(C.byref(model.cfg), B * K, L, L)
+    _check(full)
+    _check(rows)
+    if full >= rows:
+        ws, nb = model.forward_ws(B, N, L, extra=extra)
+    else:
+        ws, nb = model.forward_ws(B * K, L, L, extra=extra)
+    cstats = (_Stats * B)()
+    g, pol = graph.c(), policy.c()
+    _check(model.lib.psd_decode_block_approx(model.handle, _ptr(tokens), B, N, block_start, L, C.byref(pol), C.byref(g), cstats,
                                              _ptr(cache.mem), cache.capacity, _ptr(ws), nb, _stream()))
     return _add_stats(stats, cstats, B)
 

@@ -3,6 +3,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
 
 #include "psd_internal.h"
@@ -399,15 +400,23 @@ int32_t decode_block_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, 
                  policy->eos_id, h->cfg.vocab);
     if (!tokens || !stats) PSD_FAIL(PSD_ERR_INVALID_ARG, "NULL tokens/stats");
     const int K = g.K;
+    const bool dual = kv && kv->dual;  // approximate cache: the first model call runs over whole sequences and fills it
     const int plan_N = kv ? L : N;     // rows per sequence that a model call runs over
-    const int64_t fwd_bytes = plan_forward(h->cfg, (int64_t)B * K, plan_N, L).total;
+    int64_t fwd_bytes = plan_forward(h->cfg, (int64_t)B * K, plan_N, L).total;
+    if (dual) fwd_bytes = std::max(fwd_bytes, plan_forward(h->cfg, B, N, L).total);
     const DecodeScratch sc = plan_decode(B, N, L, K);
     if (!ws || ws_bytes < fwd_bytes + sc.total)
         PSD_FAIL(PSD_ERR_WORKSPACE, "workspace of %lld bytes, decoding the block needs %lld", (long long)ws_bytes,
                  (long long)(fwd_bytes + sc.total));
     // one model call: forward + top-1 confidence of the sequences listed in `rows` (device) out of src [*, N]
+    bool refreshed = false;
     auto model_call = [&](const int32_t *src, const int32_t *rows_dev, int S, int seqs_per_cache, int32_t *t1, float *cf,
                           hipStream_t st_) -> int32_t {
+        if (dual && !refreshed) {   // the stage-1 call that enters the block: exact, and it freezes the context
+            refreshed = true;
+            CHECK(run_forward_hidden(h, src, rows_dev, S, N, block_start, L, ws, fwd_bytes, st_, kv));
+            return run_head_confidence(h, src, rows_dev, S, N, block_start, L, t1, cf, rows_dev, ws, st_, N);
+        }
         if (kv) {
             KvCacheArg a = *kv;
             a.seqs_per_cache = seqs_per_cache;
@@ -494,7 +503,7 @@ int32_t decode_block_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, 
         }
         for (int i = 0; i <= PSD_MAX_BLOCK; ++i) stats[b].depth_hist[i] += ds[PSD_DEVSTAT_HIST + i];
     }
-    if (kv) {   // the block is finished: its keys and values become context
+    if (kv && !dual) {   // the block is finished: its keys and values become context
         KvCacheArg a = *kv;
         a.seqs_per_cache = 1;
         a.append = true;
@@ -515,6 +524,20 @@ int32_t check_kv(const psd_handle *h, const void *cache, int32_t capacity, int32
     if (L % 16) PSD_FAIL(PSD_ERR_SHAPE, "a cached block length must be a multiple of 16 (value layout), not %d", L);
     if (block_start + L > capacity) PSD_FAIL(PSD_ERR_SHAPE, "block [%d, %d) exceeds the cache capacity %d", block_start,
                                              block_start + L, capacity);
+    return PSD_OK;
+}
+
+// the approximate cache of a bidirectional model: room for the N - L positions outside a block
+int32_t check_kv_approx(const psd_handle *h, const void *cache, int32_t capacity, int32_t N, int32_t L) {
+    if (!h) PSD_FAIL(PSD_ERR_INVALID_ARG, "handle is NULL");
+    if (h->cfg.attention != PSD_ATTN_BIDIRECTIONAL)
+        PSD_FAIL(PSD_ERR_UNSUPPORTED, "the approximate cache is for bidirectional models; a block-causal model has an exact one");
+    if (!cache) PSD_FAIL(PSD_ERR_INVALID_ARG, "cache is NULL");
+    if ((reinterpret_cast<uintptr_t>(cache) & 255) != 0) PSD_FAIL(PSD_ERR_WORKSPACE, "cache must be 256-byte aligned");
+    if (capacity < 1 || capacity > h->cfg.max_seq) PSD_FAIL(PSD_ERR_SHAPE, "cache capacity %d outside 1..max_seq", capacity);
+    if (L < 1 || L % 16) PSD_FAIL(PSD_ERR_SHAPE, "a cached block length must be a multiple of 16 (value layout), not %d", L);
+    if (N - L < 1 || N - L > capacity) PSD_FAIL(PSD_ERR_SHAPE, "the %d positions outside the block need a cache of that capacity, not %d",
+                                                N - L, capacity);
     return PSD_OK;
 }
 
@@ -539,7 +562,9 @@ int64_t psd_kv_cache_bytes(const psd_model_config *cfg, int32_t capacity) {
 }
 
 int32_t psd_kv_reset(psd_handle *h, void *cache, int32_t n_seqs, int32_t capacity, void *stream) {
-    CHECK(check_kv(h, cache, capacity, 0, 16));
+    if (!h || !cache) PSD_FAIL(PSD_ERR_INVALID_ARG, "NULL handle / cache");
+    if ((reinterpret_cast<uintptr_t>(cache) & 255) != 0) PSD_FAIL(PSD_ERR_WORKSPACE, "cache must be 256-byte aligned");
+    if (capacity < 1 || capacity > h->cfg.max_seq) PSD_FAIL(PSD_ERR_SHAPE, "cache capacity %d outside 1..max_seq", capacity);
     if (n_seqs < 1) PSD_FAIL(PSD_ERR_SHAPE, "n_seqs %d", n_seqs);
     const int64_t words = psd_kv_cache_bytes(&h->cfg, capacity) / 4 * n_seqs;
     hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, (hipStream_t)stream, (int32_t *)cache,
@@ -594,6 +619,45 @@ int32_t psd_decode_block_cached(psd_handle *h, int32_t *tokens, int32_t B, int32
     a.base = cache;
     a.capacity = capacity;
     a.len = block_start;
+    return decode_block_impl(h, tokens, B, N, block_start, L, policy, graph, stats, ws, ws_bytes, stream, &a);
+}
+
+// ---- approximate prefix + suffix KV cache for bidirectional models ----
+
+int32_t psd_forward_confidence_approx(psd_handle *h, const int32_t *tokens, int32_t S, int32_t N, int32_t block_start, int32_t L,
+                                      int32_t refresh, int32_t seqs_per_cache, void *cache, int32_t capacity, int32_t *top1,
+                                      float *conf, float *logits, void *ws, int64_t ws_bytes, void *stream) {
+    CHECK(check_block(h, S, N, block_start, L));
+    CHECK(check_kv_approx(h, cache, capacity, N, L));
+    if (!tokens || (!logits && (!top1 || !conf))) PSD_FAIL(PSD_ERR_INVALID_ARG, "NULL tokens/top1/conf");
+    if (seqs_per_cache < 1 || S % seqs_per_cache) PSD_FAIL(PSD_ERR_SHAPE, "S must be a multiple of seqs_per_cache");
+    if (refresh && seqs_per_cache != 1) PSD_FAIL(PSD_ERR_INVALID_ARG, "a refreshing call fills one cache per sequence");
+    KvCacheArg a;
+    a.base = cache;
+    a.capacity = capacity;
+    a.len = N - L;
+    a.seqs_per_cache = seqs_per_cache;
+    a.dual = true;
+    hipStream_t st = (hipStream_t)stream;
+    const int plan_N = refresh ? N : L;
+    if (refresh)
+        CHECK(run_forward_hidden(h, tokens, nullptr, S, N, block_start, L, ws, ws_bytes, st, &a));
+    else
+        CHECK(run_forward_cached(h, tokens, nullptr, S, N, block_start, L, a, ws, ws_bytes, st));
+    if (logits) CHECK(run_head_logits(h, S, plan_N, L, logits, ws, st));
+    if (top1 && conf) return run_head_confidence(h, tokens, nullptr, S, N, block_start, L, top1, conf, nullptr, ws, st, plan_N);
+    return PSD_OK;
+}
+
+int32_t psd_decode_block_approx(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_t block_start, int32_t L,
+                                const psd_policy *policy, const psd_graph *graph, psd_stats *stats, void *cache,
+                                int32_t capacity, void *ws, int64_t ws_bytes, void *stream) {
+    CHECK(check_kv_approx(h, cache, capacity, N, L));
+    KvCacheArg a;
+    a.base = cache;
+    a.capacity = capacity;
+    a.len = N - L;
+    a.dual = true;
     return decode_block_impl(h, tokens, B, N, block_start, L, policy, graph, stats, ws, ws_bytes, stream, &a);
 }
 

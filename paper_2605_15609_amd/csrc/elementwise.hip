@@ -182,17 +182,17 @@ void launch_embed_block(const int32_t *tokens, const int32_t *seq_rows, int S, i
 }
 
 namespace {
-// one workgroup per row (s, j): the row's rotated keys go to K row len + j of its sequence's cache, its values into
-// column vt_key_slot(len + j) of the transposed value rows
+// one workgroup per stored row (s, j): the rotated keys of row row_first + j of sequence s go to K row len + j of the
+// sequence's cache, its values into column vt_key_slot(len + j) of the transposed value rows
 template <typename T>
-__global__ __launch_bounds__(256) void kv_append_kernel(const T *__restrict__ qkv, int ld_qkv, int L, int n_heads,
-                                                        int n_kv_heads, int d_head, T *__restrict__ k_cache,
-                                                        T *__restrict__ vt_cache, KvPrefix at) {
+__global__ __launch_bounds__(256) void kv_store_kernel(const T *__restrict__ qkv, int ld_qkv, int rows_per_seq, int row_first,
+                                                       int count, int n_heads, int n_kv_heads, int d_head,
+                                                       T *__restrict__ k_cache, T *__restrict__ vt_cache, KvPrefix at) {
     const int64_t r = blockIdx.x;
-    const int s = (int)(r / L), j = (int)(r % L);
+    const int s = (int)(r / count), j = (int)(r % count);
     const int64_t cache = (at.seq_rows ? at.seq_rows[s] : s) / at.seqs_per_cache;
     const int w = n_kv_heads * d_head;
-    const T *krow = qkv + r * ld_qkv + n_heads * d_head, *vrow = krow + w;
+    const T *krow = qkv + ((int64_t)s * rows_per_seq + row_first + j) * ld_qkv + n_heads * d_head, *vrow = krow + w;
     T *kdst = k_cache + cache * at.stride_k + (int64_t)(at.len + j) * at.ld_k;
     T *vdst = vt_cache + cache * at.stride_vt + vt_key_slot(at.len + j);
     for (int c = threadIdx.x; c < w; c += blockDim.x) {
@@ -203,14 +203,16 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const T *__restrict__ qk
 }   // namespace
 
 template <typename T>
-void launch_kv_append(const T *qkv, int ld_qkv, int S, int L, int n_heads, int n_kv_heads, int d_head, T *k_cache, T *vt_cache,
-                      const KvPrefix &at, hipStream_t st) {
-    hipLaunchKernelGGL(kv_append_kernel<T>, dim3((unsigned)(S * L)), dim3(256), 0, st, qkv, ld_qkv, L, n_heads, n_kv_heads, d_head,
-                       k_cache, vt_cache, at);
+void launch_kv_store(const T *qkv, int ld_qkv, int S, int rows_per_seq, int row_first, int count, int n_heads, int n_kv_heads,
+                     int d_head, T *k_cache, T *vt_cache, const KvPrefix &at, hipStream_t st) {
+    if (count <= 0 || S <= 0) return;
+    hipLaunchKernelGGL(kv_store_kernel<T>, dim3((unsigned)(S * count)), dim3(256), 0, st, qkv, ld_qkv, rows_per_seq, row_first,
+                       count, n_heads, n_kv_heads, d_head, k_cache, vt_cache, at);
 }
-template void launch_kv_append<float>(const float *, int, int, int, int, int, int, float *, float *, const KvPrefix &, hipStream_t);
-template void launch_kv_append<bf16_t>(const bf16_t *, int, int, int, int, int, int, bf16_t *, bf16_t *, const KvPrefix &,
-                                       hipStream_t);
+template void launch_kv_store<float>(const float *, int, int, int, int, int, int, int, int, float *, float *, const KvPrefix &,
+                                     hipStream_t);
+template void launch_kv_store<bf16_t>(const bf16_t *, int, int, int, int, int, int, int, int, bf16_t *, bf16_t *, const KvPrefix &,
+                                      hipStream_t);
 template <typename T>
 void launch_rmsnorm(float *h, int64_t rows, int d, const float *gain, float eps, T *out, PendingSums pend, hipStream_t st) {
     hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out, 0, 0, 0, (T *)nullptr,

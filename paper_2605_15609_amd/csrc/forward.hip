@@ -116,7 +116,7 @@ struct Dispatch<bf16_t> {
 
 template <typename T>
 int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N, int block_start,
-                            int L, char *ws, hipStream_t st) {
+                            int L, char *ws, hipStream_t st, const KvCacheArg *store) {
     const psd_model_config &c = h->cfg;
     const ForwardPlan p = plan_forward(c, S, N, L);
     const int64_t ntok = (int64_t)S * N;
@@ -151,6 +151,20 @@ int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t 
         }
         Dispatch<T>::rope_attention(h, qkv, ld_qkv, vT, S, N, 0, H, Hkv, dh, o, KvPrefix(),
                                     c.attention == PSD_ATTN_BLOCK_CAUSAL ? L : 0, st);
+        if (store) {
+            // approximate cache: freeze this layer's keys / values of every position outside the block, prefix first
+            const KvLayout lay = kv_layout(c, store->capacity);
+            T *k_cache = (T *)store->base + (int64_t)li * (lay.k_elems + lay.vt_elems), *vt_cache = k_cache + lay.k_elems;
+            KvPrefix at;
+            at.ld_k = (int)lay.ld_k;
+            at.ld_vt = (int)lay.ld_vt;
+            at.stride_k = at.stride_vt = lay.per_seq;
+            at.seq_rows = seq_rows;
+            at.len = 0;
+            launch_kv_store<T>(qkv, ld_qkv, S, N, 0, block_start, H, Hkv, dh, k_cache, vt_cache, at, st);
+            at.len = block_start;
+            launch_kv_store<T>(qkv, ld_qkv, S, N, block_start + L, N - block_start - L, H, Hkv, dh, k_cache, vt_cache, at, st);
+        }
         // After the last attention only the block rows feed the LM-head: the rest of that layer (output
         // projection, FFN) and the final norm run on those S*L rows alone, gathered into a packed stream.
         float *hs = hbuf;
@@ -223,7 +237,7 @@ int32_t forward_cached_impl(psd_handle *h, const int32_t *tokens, const int32_t 
             Dispatch<T>::gemm(h, a, d, wv, nullptr, d, nrow, Hkv * dh, d, epi_qkv, lw.bv, qkv + (H + Hkv) * dh, nullptr, ld_qkv, nullptr, st);
         }
         Dispatch<T>::rope_attention(h, qkv, ld_qkv, vT, S, L, block_start, H, Hkv, dh, o, pre, 0, st);
-        if (kv.append) launch_kv_append<T>(qkv, ld_qkv, S, L, H, Hkv, dh, k_cache, vt_cache, pre, st);
+        if (kv.append) launch_kv_store<T>(qkv, ld_qkv, S, L, 0, L, H, Hkv, dh, k_cache, vt_cache, pre, st);
         pend = Dispatch<T>::gemm(h, o, H * dh, lw.wo, nullptr, H * dh, nrow, d, H * dh, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, ksplit, st);
         launch_rmsnorm<T>(hbuf, nrow, d, lw.ffn_norm, c.rms_eps, a, pend, st);
         Dispatch<T>::gemm(h, a, d, lw.w_gate, lw.w_up, d, nrow, F, d, EPI_SWIGLU, nullptr, act, nullptr, ld_act, nullptr, st);
@@ -243,8 +257,10 @@ int32_t run_forward_cached(psd_handle *h, const int32_t *tokens, const int32_t *
         PSD_FAIL(PSD_ERR_WORKSPACE, "workspace of %lld bytes, cached forward over %d x %d rows needs %lld", (long long)ws_bytes,
                  S, L, (long long)p.total);
     if ((reinterpret_cast<uintptr_t>(ws) & 255) != 0) PSD_FAIL(PSD_ERR_WORKSPACE, "workspace must be 256-byte aligned");
-    if (kv.len != block_start) PSD_FAIL(PSD_ERR_SHAPE, "the cache holds %d positions, the block starts at %d", kv.len, block_start);
-    if (kv.len + L > kv.capacity) PSD_FAIL(PSD_ERR_SHAPE, "cache of %d positions cannot take the block", kv.capacity);
+    if (!kv.dual && kv.len != block_start)
+        PSD_FAIL(PSD_ERR_SHAPE, "the cache holds %d positions, the block starts at %d", kv.len, block_start);
+    if (kv.dual && (kv.len != N - L || kv.append)) PSD_FAIL(PSD_ERR_SHAPE, "a cache of the %d positions outside the block", N - L);
+    if (kv.len + (kv.dual ? 0 : L) > kv.capacity) PSD_FAIL(PSD_ERR_SHAPE, "cache of %d positions is too small", kv.capacity);
     if (kv.append && kv.seqs_per_cache != 1) PSD_FAIL(PSD_ERR_INVALID_ARG, "appending needs one sequence per cache");
     int32_t rc;
     if (h->cfg.dtype == PSD_DTYPE_BF16)
@@ -257,17 +273,19 @@ int32_t run_forward_cached(psd_handle *h, const int32_t *tokens, const int32_t *
 }
 
 int32_t run_forward_hidden(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N, int block_start,
-                           int L, void *ws, int64_t ws_bytes, hipStream_t st) {
+                           int L, void *ws, int64_t ws_bytes, hipStream_t st, const KvCacheArg *store) {
     const ForwardPlan p = plan_forward(h->cfg, S, N, L);
     if (ws == nullptr || ws_bytes < p.total)
         PSD_FAIL(PSD_ERR_WORKSPACE, "workspace of %lld bytes, forward over %d x %d tokens needs %lld", (long long)ws_bytes,
                  S, N, (long long)p.total);
     if ((reinterpret_cast<uintptr_t>(ws) & 255) != 0) PSD_FAIL(PSD_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    if (store && (!store->base || !store->dual || store->capacity < N - L))
+        PSD_FAIL(PSD_ERR_SHAPE, "storing the keys and values outside the block needs a cache of %d positions", N - L);
     int32_t rc;
     if (h->cfg.dtype == PSD_DTYPE_BF16)
-        rc = forward_hidden_impl<bf16_t>(h, tokens, seq_rows, S, N, block_start, L, (char *)ws, st);
+        rc = forward_hidden_impl<bf16_t>(h, tokens, seq_rows, S, N, block_start, L, (char *)ws, st, store);
     else
-        rc = forward_hidden_impl<float>(h, tokens, seq_rows, S, N, block_start, L, (char *)ws, st);
+        rc = forward_hidden_impl<float>(h, tokens, seq_rows, S, N, block_start, L, (char *)ws, st, store);
     if (rc != PSD_OK) return rc;
     PSD_HIP(hipGetLastError());
     return PSD_OK;

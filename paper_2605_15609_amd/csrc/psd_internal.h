@@ -92,14 +92,17 @@ ForwardPlan plan_forward(const psd_model_config &cfg, int64_t S, int64_t N, int6
 
 // Layer stack + final norm on the block rows; leaves y [S*L, d] in the workspace.
 // seq_rows (device, may be NULL) maps batch slot s -> row of `tokens` to read.
+// store (may be NULL): also leave every layer's rotated keys and values of the positions outside the block in the
+// sequences' caches (store->dual), compacted: prefix positions first, then the suffix.
+struct KvCacheArg;
 int32_t run_forward_hidden(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N,
-                           int block_start, int L, void *ws, int64_t ws_bytes, hipStream_t st);
+                           int block_start, int L, void *ws, int64_t ws_bytes, hipStream_t st,
+                           const KvCacheArg *store = nullptr);
 // LM-head + top-1 confidence on y; out_rows (device, may be NULL) maps slot s -> row of top1/conf.
 int32_t run_head_confidence(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N,
                             int block_start, int L, int32_t *top1, float *conf, const int32_t *out_rows,
                             void *ws, hipStream_t st, int plan_N = -1 /* sequence length the workspace was planned
                             for, if not N (the cached forward plans for L rows per sequence) */);
-struct KvCacheArg;
 // forward over the L block rows of S sequences against their KV caches (context-causal block attention)
 int32_t run_forward_cached(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N, int block_start, int L,
                            const KvCacheArg &kv, void *ws, int64_t ws_bytes, hipStream_t st);
@@ -140,6 +143,9 @@ struct KvCacheArg {
     void *base = nullptr;      // NULL: no cache (the call runs over whole sequences)
     int capacity = 0, len = 0, seqs_per_cache = 1;
     bool append = false;       // store the rows' keys and values behind position len (seqs_per_cache must be 1)
+    bool dual = false;         // approximate cache of a bidirectional model: the len = N - L entries are the positions
+                               // OUTSIDE the block (prefix, then suffix), frozen by the whole-sequence call that
+                               // entered the block; the block rows keep their positions block_start ..
 };
 
 // ---------------------------------------------------------------- kernel launchers
@@ -151,10 +157,11 @@ void launch_embed(const int32_t *tokens, const int32_t *seq_rows, int S, int N, 
 template <typename T>
 void launch_embed_block(const int32_t *tokens, const int32_t *seq_rows, int S, int N, int block_start, int L, const T *emb,
                         int d, float *h, hipStream_t st);
-// keys (rotated) and values of the rows of qkv [S*L, ...] into the caches of their sequences, positions len .. len+L-1
+// keys (rotated) and values of rows row_first .. row_first+count-1 of every sequence of qkv [S*rows_per_seq, ...] into the
+// caches of their sequences, cache positions at.len .. at.len+count-1
 template <typename T>
-void launch_kv_append(const T *qkv, int ld_qkv, int S, int L, int n_heads, int n_kv_heads, int d_head, T *k_cache, T *vt_cache,
-                      const KvPrefix &at, hipStream_t st);
+void launch_kv_store(const T *qkv, int ld_qkv, int S, int rows_per_seq, int row_first, int count, int n_heads, int n_kv_heads,
+                     int d_head, T *k_cache, T *vt_cache, const KvPrefix &at, hipStream_t st);
 // K-split partial sums that still have to be added to the residual stream h [rows, d]: partial[s] has the
 // same shape, s = 0 .. n-1, `stride` floats apart.  The norm that reads h next adds them (and stores h).
 struct PendingSums {

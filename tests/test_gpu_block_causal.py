@@ -228,4 +228,4 @@ def test_empty_prefix_full_cache_and_argument_errors():
         psd.psd_forward_confidence_cached(model, d2, start, L, small)                # block beyond the cache capacity
     bidir = psd.Model.from_host(inp.draw_model(dataclasses.replace(shape, attention="bidirectional"), N), DEV)
     with pytest.raises(psd.PsdError):
-        psd.KvCache(bidir, 1, N)                                                     # a cache is exact only for block-causal models
+        psd.psd_forward_confidence_cached(bidir, d2, start, L, psd.KvCache(bidir, 1, N))   # exact only for block-causal models
