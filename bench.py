@@ -78,9 +78,11 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (a known-size reference for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
-    ap.add_argument("--attention", choices=["bidirectional", "block-causal"], default="bidirectional",
+    ap.add_argument("--attention", choices=["bidirectional", "block-causal", "approx-cache"], default="bidirectional",
                     help="block-causal: the same shapes as a context-causal block model (App. A) decoded on the block rows "
-                         "against an exact prefix KV cache (prefill included in the step)")
+                         "against an exact prefix KV cache (prefill included in the step); approx-cache: the bidirectional model "
+                         "under the approximate prefix + suffix cache (one exact call per block, block rows otherwise; results "
+                         "differ from the exact decode)")
     ap.add_argument("--max-blocks", type=int, default=0,
                     help="decode only the first blocks of the generation region (0 = all); tokens/s counts what was decoded")
     ap.add_argument("--calibrate-graph", action="store_true",
@@ -105,6 +107,7 @@ def main():
     w = inp.WORKLOADS[args.config]
     if args.logit_scale != 1.0:
         w = dataclasses.replace(w, shape=dataclasses.replace(w.shape, logit_scale=args.logit_scale))
+    approx = args.attention == "approx-cache"
     cached = args.attention == "block-causal"
     if cached:
         w = dataclasses.replace(w, shape=dataclasses.replace(w.shape, attention="block_causal"))
@@ -122,6 +125,8 @@ def main():
                                                          "lattice depth=3"]
         cands = [psd.chain_graph(k) for k in range(1, 9)] + [psd.chain_graph(3, 2), psd.chain_graph(4, 2),
                                                              psd.lattice_graph(2), psd.lattice_graph(3)]
+        if approx:
+            sys.exit("bench.py: --calibrate-graph runs the exact decode or the block-causal cached one")
         kv = psd.KvCache(model, w.batch, w.seq_len) if cached else None
         psd.psd_calibrate_graph(model, tokens0, w.prompt_len, w.block_len, policy, cands[:1], kv)     # warm-up
         best, scores = psd.psd_calibrate_graph(model, tokens0, w.prompt_len, w.block_len, policy, cands, kv)
@@ -138,7 +143,7 @@ def main():
         n_blocks = min(n_blocks, args.max_blocks)
     gen_end = w.prompt_len + n_blocks * w.block_len
 
-    cache = psd.KvCache(model, w.batch, w.seq_len) if cached else None
+    cache = psd.KvCache(model, w.batch, w.seq_len) if cached else psd.KvCache(model, w.batch, w.seq_len - w.block_len) if approx else None
     prefill_ms = []
 
     def one_decode():
@@ -154,6 +159,8 @@ def main():
         for block_start in range(w.prompt_len, gen_end, w.block_len):
             if cached:
                 stats = psd.psd_decode_block_cached(model, toks, block_start, w.block_len, policy, graph, cache, stats)
+            elif approx:
+                stats = psd.psd_decode_block_approx(model, toks, block_start, w.block_len, policy, graph, cache, stats)
             else:
                 stats = psd.psd_decode_block(model, toks, block_start, w.block_len, policy, graph, stats)
         return toks, stats
@@ -167,7 +174,7 @@ def main():
     lib = psd.load_library()
     if bf16:
         # the tile the dispatcher picks for the verification pass's SwiGLU contraction
-        rows_per_seq = w.block_len if cached else w.seq_len        # rows a model call runs over
+        rows_per_seq = w.block_len if (cached or approx) else w.seq_len        # rows a model call runs over
         swiglu_tile = lib.psd_kernel_gemm_tile(w.batch * w.n_drafts * rows_per_seq, shape.d_ffn, 3)
         model.probe_begin(3, swiglu_tile)
         model.probe_begin(4, 0)
@@ -240,10 +247,13 @@ def main():
 
     # whole-forward accounting for the verification pass (MFMA utilisation of the model call)
     # (per-sequence call counts: a stage-1 call is one sequence-forward, a verify call K of them)
-    work_v = psd.forward_work(model, w.n_drafts, w.block_len if cached else w.seq_len, w.block_len)
-    work_1 = psd.forward_work(model, 1, w.block_len if cached else w.seq_len, w.block_len)
-    flops_decode = n_stage1 * (work_1["gemm_flops"] + work_1["attn_flops"] + work_1["head_flops"]) + \
-                   n_verify * (work_v["gemm_flops"] + work_v["attn_flops"] + work_v["head_flops"])
+    rows_call = w.block_len if (cached or approx) else w.seq_len
+    work_v = psd.forward_work(model, w.n_drafts, rows_call, w.block_len)
+    work_1 = psd.forward_work(model, 1, rows_call, w.block_len)
+    total = lambda wk: wk["gemm_flops"] + wk["attn_flops"] + wk["head_flops"]
+    flops_decode = n_stage1 * total(work_1) + n_verify * total(work_v)
+    if approx:   # the call that enters a block runs over the whole sequence
+        flops_decode += n_blocks * w.batch * (total(psd.forward_work(model, 1, w.seq_len, w.block_len)) - total(work_1))
     out = {
         "metric": "decoded tokens/s (PSD, tokens per forward in config.tpf)", "value": value, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
@@ -265,11 +275,14 @@ def main():
         torch.cuda.synchronize()
         out["config"]["prefill_ms"] = float(np.mean([a.elapsed_time(b) for a, b in prefill_ms[-args.steps:]]))
         out["config"]["workload"] += ", context-causal block attention with prefix KV cache (prefill inside the step)"
+    if approx:
+        out["config"]["workload"] += (", approximate prefix + suffix KV cache (one exact whole-sequence call per block, block rows "
+                                      "against frozen keys / values otherwise; results differ from the exact decode)")
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, n_tokens, n_stage1, n_verify, os.cpu_count() or 1)
     else:
         out["cpu_baseline"] = None
-    if args.config == 3 and not cached and not args.no_also and args.max_blocks == 0:
+    if args.config == 3 and not cached and not approx and not args.no_also and args.max_blocks == 0:
         # context: the small configuration (8 layers, d_model 512), whose model call is ~90 kernels of a few
         # microseconds each -- bound by kernel granularity, no roofline claim
         del model

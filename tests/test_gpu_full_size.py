@@ -128,3 +128,62 @@ def test_config3_full_depth_block_causal_with_kv_cache():
         say(f"[full-size] {label}: logits max-abs err {err:.3e} (tol {tol:.3e}), near-ties {near}, inside the band {wide}; "
             f"{time.perf_counter() - t0:.0f} s")
     model.close()
+
+
+def test_config3_full_depth_approximate_cache():
+    """Config 3 itself (bidirectional) under the approximate prefix + suffix cache: the exact call that enters a block
+    fills the cache; then the block-row call in both launch shapes (1 x 32 rows; 4 drafts x 32 rows sharing the cache)
+    after five commits, against the oracle's ApproximateCache in exact arithmetic, with the tolerance calibrated by
+    the same oracle mode on bf16 operands."""
+    _need_memory()
+    import torch
+    import paper_2605_15609_amd as psd
+    from tests.gpu_common import say, to_dev
+    from tests.test_gpu_forward import check_sequence
+    w = inp.WORKLOADS[3]
+    shape = w.shape
+    N, L, K = w.seq_len, w.block_len, w.n_drafts
+    start = w.prompt_len + L
+    t0 = time.perf_counter()
+    host = inp.draw_model(shape, N, threads=16)
+    model = psd.Model.from_host(host)
+    say(f"[full-size] config 3 drawn and uploaded after {time.perf_counter() - t0:.0f} s")
+    entry = np.full(N, shape.mask_id, dtype=np.int32)
+    entry[:start] = inp.draw_prompt(shape.vocab, start, 300)
+    exact, rounded = orc.ApproximateCache(host), orc.ApproximateCache(host, operands="bf16")
+    ref0 = exact(entry, start, L)
+    z0 = exact.logits.copy()
+    rounded(entry, start, L)
+    zb0 = rounded.logits.copy()
+    say(f"[full-size] oracle refresh calls done after {time.perf_counter() - t0:.0f} s")
+    cache = psd.KvCache(model, 1, N - L)
+    top1, conf, logits = psd.psd_forward_confidence_approx(model, to_dev(entry[None]), start, L, cache, refresh=True,
+                                                           want_logits=True)
+    torch.cuda.synchronize()
+    err, tol, near, wide = check_sequence((ref0[0], ref0[1], z0, zb0), logits.cpu().numpy(), top1[0].cpu().numpy(),
+                                          conf[0].cpu().numpy(), entry, shape.mask_id, start, L, 2e-2, "cfg3-approx/refresh")
+    say(f"[full-size] cfg3-approx/refresh: logits max-abs err {err:.3e} (tol {tol:.3e}), near-ties {near}, inside the band {wide}")
+    rng = np.random.default_rng(5)
+    t1 = entry.copy()
+    idx = rng.choice(L, size=5, replace=False)
+    t1[start + idx] = ref0[0][idx]
+    drafts = np.repeat(t1[None], K, axis=0)
+    order = [j for j in range(L) if t1[start + j] == shape.mask_id]
+    for k in range(1, K):
+        for j in order[:k]:
+            drafts[k, start + j] = ref0[0][j]
+    ref1 = exact(drafts[K - 1], start, L)          # the deepest draft: it differs most from the state the cache was filled on
+    z1 = exact.logits.copy()
+    rounded(drafts[K - 1], start, L)
+    zb1 = rounded.logits.copy()
+    for label, batch, row in ((f"cfg3-approx/stage-1 shape (1 x {L} rows)", drafts[K - 1:], 0),
+                              (f"cfg3-approx/verify shape ({K} x {L} rows, shared cache)", drafts, K - 1)):
+        top1, conf, logits = psd.psd_forward_confidence_approx(model, to_dev(batch), start, L, cache, refresh=False,
+                                                               seqs_per_cache=len(batch), want_logits=True)
+        torch.cuda.synchronize()
+        logits = logits.cpu().numpy().reshape(len(batch), L, -1)
+        err, tol, near, wide = check_sequence((ref1[0], ref1[1], z1, zb1), logits[row], top1[row].cpu().numpy(),
+                                              conf[row].cpu().numpy(), drafts[K - 1], shape.mask_id, start, L, 2e-2, label)
+        say(f"[full-size] {label}: logits max-abs err {err:.3e} (tol {tol:.3e}), near-ties {near}, inside the band {wide}; "
+            f"{time.perf_counter() - t0:.0f} s")
+    model.close()
