@@ -86,12 +86,24 @@ __global__ __launch_bounds__(256) void rmsnorm_bf16_vec_kernel(float *__restrict
             v[i][0] = x[2 * c];
             v[i][1] = x[2 * c + 1];
             if (pend.n > 0) {
-                for (int s = 0; s < pend.n; ++s) {
-                    const float4 *q = reinterpret_cast<const float4 *>(pend.partial + s * pend.stride + r * d);
-                    const float4 q0 = q[2 * c], q1 = q[2 * c + 1];
-                    v[i][0].x += q0.x; v[i][0].y += q0.y; v[i][0].z += q0.z; v[i][0].w += q0.w;
-                    v[i][1].x += q1.x; v[i][1].y += q1.y; v[i][1].z += q1.z; v[i][1].w += q1.w;
-                }
+                // all partial sums are fetched before the first is added (one round trip to memory instead of one
+                // per part: these launches have a few dozen rows and nothing else to hide the latency); the adds
+                // keep the order of the parts
+                constexpr int MAXP = 7;     // a contraction is cut into at most 8 parts
+                float4 q[MAXP][2];
+#pragma unroll
+                for (int s = 0; s < MAXP; ++s)
+                    if (s < pend.n) {
+                        const float4 *qp = reinterpret_cast<const float4 *>(pend.partial + s * pend.stride + r * d);
+                        q[s][0] = qp[2 * c];
+                        q[s][1] = qp[2 * c + 1];
+                    }
+#pragma unroll
+                for (int s = 0; s < MAXP; ++s)
+                    if (s < pend.n) {
+                        v[i][0].x += q[s][0].x; v[i][0].y += q[s][0].y; v[i][0].z += q[s][0].z; v[i][0].w += q[s][0].w;
+                        v[i][1].x += q[s][1].x; v[i][1].y += q[s][1].y; v[i][1].z += q[s][1].z; v[i][1].w += q[s][1].w;
+                    }
                 x[2 * c] = v[i][0];
                 x[2 * c + 1] = v[i][1];
             }
