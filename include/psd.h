@@ -141,6 +141,10 @@ typedef struct {
 } psd_stats;
 
 const char *psd_status_string(int32_t status);
+/* sizeof of the structures above as this library was built, in the order psd_model_config, psd_weights,
+ * psd_policy, psd_graph, psd_stats, psd_work, psd_graph_score (the first n of them into out; returns how many
+ * there are): lets a foreign-language binding check its own declarations. */
+int32_t psd_struct_sizes(int32_t *out, int32_t n);
 /* Message of the last error raised on the calling thread ("" if none). */
 const char *psd_last_error(void);
 

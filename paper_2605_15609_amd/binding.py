@@ -91,6 +91,7 @@ def load_library():
         "psd_debug_set_plain": (i32, [vp, i32]),
         "psd_workspace_bytes": (i64, [C.POINTER(_Config), i32, i32, i32]),
         "psd_decode_scratch_bytes": (i64, [i32, i32, i32, i32]),
+        "psd_struct_sizes": (i32, [C.POINTER(i32), i32]),
         "psd_graph_chain": (i32, [i32, i32, C.POINTER(_Graph)]),
         "psd_graph_lattice": (i32, [i32, C.POINTER(_Graph)]),
         "psd_calibrate_graph": (i32, [vp, vp, vp, i32, i32, i32, i32, C.POINTER(_Policy), C.POINTER(_Graph), i32,
@@ -135,6 +136,11 @@ def load_library():
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
         fn.restype, fn.argtypes = res, args
+    # the structures declared here must be the ones the library was built with
+    mine = [C.sizeof(t) for t in (_Config, _Weights, _Policy, _Graph, _Stats, _Work, _GraphScore)]
+    theirs = (i32 * len(mine))()
+    if lib.psd_struct_sizes(theirs, len(mine)) != len(mine) or list(theirs) != mine:
+        raise PsdError(f"binding and libpsd.so disagree on the structure layouts: {mine} vs {list(theirs)} (rebuild the library)")
     _lib = lib
     return lib
 

@@ -283,6 +283,15 @@ int64_t psd_decode_scratch_bytes(int32_t B, int32_t N, int32_t L, int32_t K) {
     return plan_decode(B, N, L, K).total;
 }
 
+int32_t psd_struct_sizes(int32_t *out, int32_t n) {
+    const int32_t sizes[] = {(int32_t)sizeof(psd_model_config), (int32_t)sizeof(psd_weights), (int32_t)sizeof(psd_policy),
+                             (int32_t)sizeof(psd_graph),        (int32_t)sizeof(psd_stats),   (int32_t)sizeof(psd_work),
+                             (int32_t)sizeof(psd_graph_score)};
+    const int32_t count = (int32_t)(sizeof(sizes) / sizeof(sizes[0]));
+    for (int32_t i = 0; out && i < n && i < count; ++i) out[i] = sizes[i];
+    return count;
+}
+
 int32_t psd_graph_chain(int32_t K, int32_t width, psd_graph *out) {
     if (!out) PSD_FAIL(PSD_ERR_INVALID_ARG, "out is NULL");
     if (K < 1 || K > PSD_MAX_NODES || width < 1) PSD_FAIL(PSD_ERR_SHAPE, "chain with K=%d width=%d", K, width);
