@@ -229,3 +229,29 @@ def test_empty_prefix_full_cache_and_argument_errors():
     bidir = psd.Model.from_host(inp.draw_model(dataclasses.replace(shape, attention="bidirectional"), N), DEV)
     with pytest.raises(psd.PsdError):
         psd.psd_forward_confidence_cached(bidir, d2, start, L, psd.KvCache(bidir, 1, N))   # exact only for block-causal models
+
+
+def test_graph_calibration_on_the_cached_path_scores_like_the_oracle():
+    import paper_2605_15609_amd as psd
+    shape = FP32
+    L, P, G, B = 16, 32, 32, 2
+    N = P + G
+    host = inp.draw_model(shape, N)
+    model = psd.Model.from_host(host, DEV)
+    tokens0 = np.full((B, N), shape.mask_id, dtype=np.int32)
+    for b in range(B):
+        tokens0[b, :P] = inp.draw_prompt(shape.vocab, P, 90 + b)
+    cands = [psd.chain_graph(1), psd.chain_graph(3), psd.lattice_graph(2)]
+    d = _dev(tokens0)
+    cache = psd.KvCache(model, B, N)
+    best, scores = psd.psd_calibrate_graph(model, d, P, L, psd.Policy(0.05, 1, 0), cands, cache)
+    assert (d.cpu().numpy() == tokens0).all()
+    fn = orc.model_confidence_fn(host, block_causal=True)
+    for g, sc in zip(cands, scores):
+        og = orc.Graph(tuple(frozenset(r for r in range(64) if (rs >> r) & 1) for rs in g.rank_sets))
+        tok = inv = 0
+        for b in range(B):
+            _, st = orc.decode(fn, tokens0[b], P, L, orc.Policy(0.05, 1, 0), og, shape.mask_id)
+            tok, inv = tok + st.tokens, inv + st.invocations
+        assert (sc["tokens"], sc["invocations"]) == (tok, inv) and sc["seconds"] > 0
+    assert best == max(range(len(cands)), key=lambda c: (scores[c]["tokens_per_s"], -c))
