@@ -264,6 +264,7 @@ class Model:
                       shape.vocab, shape.mask_id, shape.rms_eps, int(shape.qkv_bias), 1 if shape.dtype == "bf16" else 0,
                       float(shape.logit_scale), self.max_seq, 1 if getattr(shape, "attention", "bidirectional") == "block_causal" else 0)
         self.cfg = cfg
+        self._check_tensors(shape, mat_dtype=torch.bfloat16 if shape.dtype == "bf16" else torch.float32)
         w = _Weights()
         for name in ("tok_emb", "final_norm", "lm_head", "rope_cos", "rope_sin"):
             setattr(w, name, tensors[name].data_ptr())
@@ -282,6 +283,33 @@ class Model:
         with torch.cuda.device(self.device):
             _check(self.lib.psd_create(C.byref(cfg), C.byref(w), C.byref(handle)))
         self.handle = handle
+
+    def _check_tensors(self, shape, mat_dtype):
+        """The library takes raw pointers: a tensor of the wrong dtype or extent would be read as garbage or past its
+        end.  Matrices [out, in] in the model dtype; norm gains, biases and rotary tables fp32."""
+        d, hq, hkv, f, v = shape.d_model, shape.n_heads * shape.d_head, shape.n_kv_heads * shape.d_head, shape.d_ffn, shape.vocab
+        want = {"tok_emb": ((v, d), mat_dtype), "lm_head": ((v, d), mat_dtype), "final_norm": ((d,), torch.float32),
+                "rope_cos": ((self.max_seq, shape.d_head // 2), torch.float32),
+                "rope_sin": ((self.max_seq, shape.d_head // 2), torch.float32)}
+        per_layer = {"attn_norm": ((d,), torch.float32), "ffn_norm": ((d,), torch.float32), "wq": ((hq, d), mat_dtype),
+                     "wk": ((hkv, d), mat_dtype), "wv": ((hkv, d), mat_dtype), "wo": ((d, hq), mat_dtype),
+                     "w_gate": ((f, d), mat_dtype), "w_up": ((f, d), mat_dtype), "w_down": ((d, f), mat_dtype),
+                     "bq": ((hq,), torch.float32), "bk": ((hkv,), torch.float32), "bv": ((hkv,), torch.float32)}
+
+        def check(name, t, dims, dtype, dense=True):
+            if tuple(t.shape) != tuple(dims) or t.dtype != dtype or t.device.type != self.device.type or t.stride(-1) != 1 \
+                    or (dense and not t.is_contiguous()):
+                raise PsdError(f"{name}: expected a {'dense ' if dense else ''}{dtype} tensor of shape {tuple(dims)} on {self.device}, "
+                               f"got {t.dtype} {tuple(t.shape)} strides {t.stride()} on {t.device}")
+        for name, (dims, dtype) in want.items():
+            check(name, self._tensors[name], dims, dtype)
+        for l, lt in enumerate(self._layers):
+            for name, (dims, dtype) in per_layer.items():
+                if lt.get(name) is None:
+                    if name in ("bq", "bk", "bv") and not shape.qkv_bias:
+                        continue
+                    raise PsdError(f"layer {l}: {name} is missing")
+                check(f"layer {l} {name}", lt[name], dims, dtype, dense=(name != "w_down"))
 
     @classmethod
     def from_host(cls, host_model, device="cuda:0") -> "Model":
@@ -705,3 +733,4 @@ def kernel_head_stream_bf16(y: torch.Tensor, W_packed: torch.Tensor, V: int, sca
     _check(lib.psd_kernel_head_stream_bf16(_ptr(y_packed), _ptr(W_packed), rows, V, d, float(scale), int(mask_id),
                                            _ptr(scratch), _ptr(row_sum), _ptr(row_arg), _stream()))
     return row_sum, row_arg
+

@@ -462,7 +462,13 @@ int32_t decode_block_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, 
         if (hc[b] > 0) active.push_back(b);
     std::vector<int64_t> invocations(B, 0);
 
+    // every model call commits at least one token of every sequence it runs (k_min >= 1), so a block of L positions
+    // is resolved after at most L iterations; anything beyond that means the model returned no usable predictions
+    int iterations = 0;
     while (!active.empty()) {
+        if (++iterations > L + 1)
+            PSD_FAIL(PSD_ERR_DEVICE, "the block [%d, %d) is not resolved after %d iterations: the model calls make no progress "
+                     "(k_min = %d; non-finite logits?)", block_start, block_start + L, L + 1, policy->k_min);
         // stage 1: one forward over the active sequences, policy commit, drafts
         const int S1 = (int)active.size();
         for (int s = 0; s < S1; ++s) hrows[s] = active[s];

@@ -10,14 +10,17 @@ namespace {
 template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(const int32_t *__restrict__ tokens,
                                                     const int32_t *__restrict__ seq_rows, int N, int first, int count,
-                                                    const T *__restrict__ emb, int d, float *__restrict__ h) {
+                                                    const T *__restrict__ emb, int vocab, int d, float *__restrict__ h) {
     const int64_t t = blockIdx.x;   // slot-major row index s*count + i: position first + i of sequence s
     const int s = (int)(t / count), i = (int)(t % count);
     const int64_t src_row = seq_rows ? seq_rows[s] : s;
     const int32_t tok = tokens[src_row * N + first + i];
-    const T *e = emb + (int64_t)tok * d;
+    // an id outside the embedding table (invalid input, e.g. a prediction taken from a model call that produced
+    // non-finite logits) reads nothing: its row of the stream is zero
+    const bool known = (uint32_t)tok < (uint32_t)vocab;
+    const T *e = emb + (int64_t)(known ? tok : 0) * d;
     float *o = h + t * d;
-    for (int c = threadIdx.x; c < d; c += blockDim.x) o[c] = to_float(e[c]);
+    for (int c = threadIdx.x; c < d; c += blockDim.x) o[c] = known ? to_float(e[c]) : 0.f;
 }
 
 __device__ __forceinline__ float block_sum(float v, float *smem) {
@@ -182,15 +185,16 @@ template void launch_gather_block_rows<float>(const float *, float *, int, int, 
 template void launch_gather_block_rows<bf16_t>(const bf16_t *, bf16_t *, int, int, int, int, int, hipStream_t);
 
 template <typename T>
-void launch_embed(const int32_t *tokens, const int32_t *seq_rows, int S, int N, const T *emb, int d, float *h,
+void launch_embed(const int32_t *tokens, const int32_t *seq_rows, int S, int N, const T *emb, int vocab, int d, float *h,
                   hipStream_t st) {
-    hipLaunchKernelGGL(embed_kernel<T>, dim3((unsigned)((int64_t)S * N)), dim3(256), 0, st, tokens, seq_rows, N, 0, N, emb, d, h);
+    hipLaunchKernelGGL(embed_kernel<T>, dim3((unsigned)((int64_t)S * N)), dim3(256), 0, st, tokens, seq_rows, N, 0, N, emb, vocab, d,
+                       h);
 }
 template <typename T>
 void launch_embed_block(const int32_t *tokens, const int32_t *seq_rows, int S, int N, int block_start, int L, const T *emb,
-                        int d, float *h, hipStream_t st) {
+                        int vocab, int d, float *h, hipStream_t st) {
     hipLaunchKernelGGL(embed_kernel<T>, dim3((unsigned)((int64_t)S * L)), dim3(256), 0, st, tokens, seq_rows, N, block_start, L,
-                       emb, d, h);
+                       emb, vocab, d, h);
 }
 
 namespace {
@@ -292,15 +296,15 @@ void launch_rope<bf16_t>(bf16_t *qkv, int ld, int64_t tokens, int N, int pos0, i
 }
 
 #define INSTANTIATE(T)                                                                                              \
-    template void launch_embed<T>(const int32_t *, const int32_t *, int, int, const T *, int, float *, hipStream_t); \
+    template void launch_embed<T>(const int32_t *, const int32_t *, int, int, const T *, int, int, float *, hipStream_t); \
     template void launch_rmsnorm<T>(float *, int64_t, int, const float *, float, T *, PendingSums, hipStream_t);    \
     template void launch_rmsnorm_block<T>(float *, int, int, int, int, int, const float *, float, T *, T *,         \
                                           PendingSums, hipStream_t);                                                \
     template void launch_rope<T>(T *, int, int64_t, int, int, int, int, int, const float *, const float *, hipStream_t);      \
-    template void launch_embed_block<T>(const int32_t *, const int32_t *, int, int, int, int, const T *, int, float *,     \
+    template void launch_embed_block<T>(const int32_t *, const int32_t *, int, int, int, int, const T *, int, int, float *, \
                                         hipStream_t);
 INSTANTIATE(float)
-template void launch_embed<bf16_t>(const int32_t *, const int32_t *, int, int, const bf16_t *, int, float *, hipStream_t);
-template void launch_embed_block<bf16_t>(const int32_t *, const int32_t *, int, int, int, int, const bf16_t *, int, float *,
+template void launch_embed<bf16_t>(const int32_t *, const int32_t *, int, int, const bf16_t *, int, int, float *, hipStream_t);
+template void launch_embed_block<bf16_t>(const int32_t *, const int32_t *, int, int, int, int, const bf16_t *, int, int, float *,
                                          hipStream_t);
 

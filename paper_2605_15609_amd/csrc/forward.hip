@@ -133,7 +133,7 @@ int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t 
     // bandwidth at small row counts).
     float *ksplit = nullptr;
     PendingSums pend;   // stays empty here; the norms take it for the block-row path
-    launch_embed<T>(tokens, seq_rows, S, N, (const T *)h->tok_emb, d, hbuf, st);
+    launch_embed<T>(tokens, seq_rows, S, N, (const T *)h->tok_emb, c.vocab, d, hbuf, st);
     for (size_t li = 0; li < h->layers.size(); ++li) {
         const psd_handle::Layer &lw = h->layers[li];
         launch_rmsnorm<T>(hbuf, ntok, d, lw.attn_norm, c.rms_eps, a, pend, st);
@@ -218,7 +218,7 @@ int32_t forward_cached_impl(psd_handle *h, const int32_t *tokens, const int32_t 
 
     float *ksplit = c.dtype == PSD_DTYPE_BF16 ? (float *)(ws + p.off_ksplit) : nullptr;
     PendingSums pend;
-    launch_embed_block<T>(tokens, seq_rows, S, N, block_start, L, (const T *)h->tok_emb, d, hbuf, st);
+    launch_embed_block<T>(tokens, seq_rows, S, N, block_start, L, (const T *)h->tok_emb, c.vocab, d, hbuf, st);
     for (size_t li = 0; li < h->layers.size(); ++li) {
         const psd_handle::Layer &lw = h->layers[li];
         T *k_cache = (T *)kv.base + (int64_t)li * (lay.k_elems + lay.vt_elems), *vt_cache = k_cache + lay.k_elems;
@@ -336,7 +336,7 @@ int32_t run_head_confidence(psd_handle *h, const int32_t *tokens, const int32_t 
                                             c.d_model, c.d_model, c.d_model, EPI_STORE, nullptr, c.logit_scale, logits, nullptr, c.vocab, st);
         launch_logits_top1(logits, rows, c.vocab, c.mask_id, row_sum, row_arg, st);
     }
-    launch_head_finish(row_sum, row_arg, tokens, seq_rows, out_rows, S, N, block_start, L, c.mask_id, top1, conf, st);
+    launch_head_finish(row_sum, row_arg, tokens, seq_rows, out_rows, S, N, block_start, L, c.mask_id, c.vocab, top1, conf, st);
     PSD_HIP(hipGetLastError());
     return PSD_OK;
 }

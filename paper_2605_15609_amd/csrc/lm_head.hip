@@ -179,7 +179,7 @@ void launch_stream(const bf16_t *Wp, const bf16_t *Yp, int V, int rows, int d, T
 // positions, sentinel (own token, -1) elsewhere)
 __global__ __launch_bounds__(256) void head_merge_finish_kernel(const float *__restrict__ pmax, const float *__restrict__ psum,
                                                                 const int32_t *__restrict__ parg, int slabs, int rows,
-                                                                HeadFinish fin, int mask_id) {
+                                                                HeadFinish fin, int mask_id, int vocab) {
     __shared__ float s_b[4], s_s[4];
     __shared__ int s_a[4];
     const int r = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -208,8 +208,10 @@ __global__ __launch_bounds__(256) void head_merge_finish_kernel(const float *__r
         const int64_t dst = fin.out_rows ? fin.out_rows[s] : s;
         const int32_t tok = fin.tokens[src * fin.N + fin.block_start + j];
         const bool masked = tok == mask_id;
-        fin.top1[dst * fin.L + j] = masked ? arg : tok;
-        fin.conf[dst * fin.L + j] = masked ? 1.0f / sum : -1.0f;
+        // a row without one finite logit (a model call on invalid input) has no prediction: token 0, confidence 0
+        const bool valid = (uint32_t)arg < (uint32_t)vocab && sum >= 1.0f;
+        fin.top1[dst * fin.L + j] = masked ? (valid ? arg : 0) : tok;
+        fin.conf[dst * fin.L + j] = masked ? (valid ? 1.0f / sum : 0.0f) : -1.0f;
     }
 }
 
@@ -273,7 +275,7 @@ void launch_head_stream_finish_bf16(const bf16_t *y_packed, const bf16_t *W_pack
     Top1Args t1;
     const int slabs = stream_partials(y_packed, W_packed, rows, V, d, scale, mask_id, partials, t1, st);
     hipLaunchKernelGGL(head_merge_finish_kernel, dim3(rows), dim3(256), 0, st, t1.pmax, t1.psum, t1.parg, slabs, rows, fin,
-                       mask_id);
+                       mask_id, V);
 }
 
 void launch_head_confidence_bf16(const bf16_t *y, const bf16_t *W, int rows, int V, int d, float scale, int mask_id,

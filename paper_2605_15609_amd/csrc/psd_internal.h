@@ -151,12 +151,12 @@ struct KvCacheArg {
 // ---------------------------------------------------------------- kernel launchers
 // elementwise.hip
 template <typename T>
-void launch_embed(const int32_t *tokens, const int32_t *seq_rows, int S, int N, const T *emb, int d, float *h,
+void launch_embed(const int32_t *tokens, const int32_t *seq_rows, int S, int N, const T *emb, int vocab, int d, float *h,
                   hipStream_t st);
 // the same for the L block rows of each sequence only: h [S*L, d]
 template <typename T>
 void launch_embed_block(const int32_t *tokens, const int32_t *seq_rows, int S, int N, int block_start, int L, const T *emb,
-                        int d, float *h, hipStream_t st);
+                        int vocab, int d, float *h, hipStream_t st);
 // keys (rotated) and values of rows row_first .. row_first+count-1 of every sequence of qkv [S*rows_per_seq, ...] into the
 // caches of their sequences, cache positions at.len .. at.len+count-1
 template <typename T>
@@ -208,7 +208,7 @@ void launch_plain_attention(const T *qkv, int ld, int S, int N, int n_heads, int
 void launch_logits_top1(const float *logits, int rows, int V, int mask_id, float *row_sum, int32_t *row_arg,
                         hipStream_t st);
 void launch_head_finish(const float *row_sum, const int32_t *row_arg, const int32_t *tokens, const int32_t *seq_rows,
-                        const int32_t *out_rows, int S, int N, int block_start, int L, int mask_id, int32_t *top1,
+                        const int32_t *out_rows, int S, int N, int block_start, int L, int mask_id, int vocab, int32_t *top1,
                         float *conf, hipStream_t st);
 
 // gemm_mfma.hip (bf16; Nout, Kin multiples of 64)

@@ -15,8 +15,9 @@ def synthetic_model(shape: "inp.ModelShape", max_seq: int, device: str = "cuda:0
     dev = torch.device(device)
     mat_dtype = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
 
-    def up(a):
-        dtype = mat_dtype if a.ndim == 2 else torch.float32
+    def up(a, matrix=None):
+        # weight matrices go up in the model dtype; norm gains, biases and the rotary tables stay fp32
+        dtype = mat_dtype if (a.ndim == 2 if matrix is None else matrix) else torch.float32
         return torch.from_numpy(a).to(device=dev, dtype=dtype).contiguous()
 
     jobs = [("tok_emb", -1), ("lm_head", -1), ("final_norm", -1)]
@@ -37,5 +38,5 @@ def synthetic_model(shape: "inp.ModelShape", max_seq: int, device: str = "cuda:0
     for lt in layers:
         pack_qkv(lt)
     cos, sin = inp.rope_tables(shape, max_seq)
-    tensors["rope_cos"], tensors["rope_sin"] = up(cos), up(sin)
+    tensors["rope_cos"], tensors["rope_sin"] = up(cos, matrix=False), up(sin, matrix=False)
     return Model(shape, max_seq, tensors, layers, device)

@@ -13,6 +13,7 @@ import torch
 
 import psd_inputs as inp
 from oracle import psd_oracle as orc
+from tests import parity_guard as G
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -198,6 +199,40 @@ def test_graph_calibration_scores_every_candidate_like_the_oracle():
         psd.psd_calibrate_graph(model, d, P + 1, L, psd.Policy(), cands)        # generated part not whole blocks
 
 
+def _check_tables(host, tokens_rows, bs, L, g_top1, g_conf, log, guard, eps):
+    """GPU model output vs oracle model output on the same states (one oracle forward per row of tokens_rows);
+    returns per row (oracle top1, oracle conf, near-tie flags, oracle top-1 margins)."""
+    shape = host.shape
+    mask_id = shape.mask_id
+    out = []
+    for r, t in enumerate(tokens_rows):
+        o_top1, o_conf, z = orc.forward_confidence(host, t, bs, L, return_logits=True)
+        masked = t[bs: bs + L] == mask_id
+        zz = z.copy()
+        zz[:, mask_id] = -np.inf
+        part = np.partition(zz, -2, axis=-1)
+        margin = part[:, -1] - part[:, -2]
+        tie = masked & (margin < guard)
+        log["near_tie_top1"] += int(tie.sum())
+        # A logit error of eps on either side lets the argmax land on any token whose oracle logit
+        # is within 2*eps of the top one.  Positions with margin < 1e-3 are the logged near-ties;
+        # a mismatch beyond that must still stay inside the band the logit tolerance implies.
+        differ = masked & (g_top1[r] != o_top1)
+        for j in np.nonzero(differ)[0]:
+            gap = zz[j, o_top1[j]] - zz[j, g_top1[r][j]]
+            assert gap <= 2 * eps, f"top-1 mismatch with oracle logit gap {gap:.3e} > 2 * {eps}"
+            if margin[j] >= guard:
+                log["top1_within_logit_tol"] = log.get("top1_within_logit_tol", 0) + 1
+        ok = masked & ~differ
+        assert (g_top1[r][~masked] == o_top1[~masked]).all() and (g_conf[r][~masked] == -1).all()
+        if ok.any():
+            rel = np.abs(g_conf[r][ok] / o_conf[ok] - 1).max()
+            log["max_conf_rel"] = max(log["max_conf_rel"], float(rel))
+            assert rel < np.expm1(2 * eps), f"confidence off by {rel}"
+        out.append((o_top1, o_conf, tie, margin))
+    return out
+
+
 def _lockstep(workload, shape, n_blocks, guard=1e-3, max_iters=10 ** 9):
     import paper_2605_15609_amd as psd
     from tests.gpu_common import gpu_graph
@@ -208,38 +243,14 @@ def _lockstep(workload, shape, n_blocks, guard=1e-3, max_iters=10 ** 9):
     gpol, ggraph = psd.Policy(workload.tau, workload.k_min, workload.k_max), gpu_graph(ograph)
     mask_id = shape.mask_id
     x = inp.initial_state(workload)[0]
-    log = {"iters": 0, "near_tie_top1": 0, "near_tie_rank": 0, "near_tau": 0, "resync": 0, "max_conf_rel": 0.0}
+    log = {"iters": 0, "near_tie_top1": 0, "commit_sets_differ": 0, "rank_pairs_inverted": 0, "verdicts_differ": 0,
+           "resync": 0, "unexplained": 0, "max_conf_rel": 0.0}
+    eps_logit = 2e-2 * max(1.0, shape.logit_scale)
+    r_conf = float(np.expm1(2 * eps_logit))       # relative confidence error that a logit error of eps_logit allows
+    n_ranks = max(max(rs) + 1 if rs else 0 for rs in ograph.rank_sets)     # ranks of sigma that feed the drafts
 
     def check_tables(tokens_rows, g_top1, g_conf):
-        """GPU model output vs oracle model output on the same states; returns per-row 'safe' flags."""
-        safe_all = []
-        for r, t in enumerate(tokens_rows):
-            o_top1, o_conf, z = orc.forward_confidence(host, t, bs, L, return_logits=True)
-            masked = t[bs: bs + L] == mask_id
-            zz = z.copy()
-            zz[:, mask_id] = -np.inf
-            part = np.partition(zz, -2, axis=-1)
-            margin = part[:, -1] - part[:, -2]
-            tie = masked & (margin < guard)
-            log["near_tie_top1"] += int(tie.sum())
-            # A logit error of eps on either side lets the argmax land on any token whose oracle logit
-            # is within 2*eps of the top one.  Positions with margin < 1e-3 are the logged near-ties;
-            # a mismatch beyond that must still stay inside the band the 2e-2 logit tolerance implies.
-            eps = 2e-2 * max(1.0, shape.logit_scale)
-            differ = masked & (g_top1[r] != o_top1)
-            for j in np.nonzero(differ)[0]:
-                gap = zz[j, o_top1[j]] - zz[j, g_top1[r][j]]
-                assert gap <= 2 * eps, f"top-1 mismatch with oracle logit gap {gap:.3e} > 2 * {eps}"
-                if margin[j] >= guard:
-                    log["top1_within_logit_tol"] = log.get("top1_within_logit_tol", 0) + 1
-            ok = masked & ~differ
-            assert (g_top1[r][~masked] == o_top1[~masked]).all() and (g_conf[r][~masked] == -1).all()
-            if ok.any():
-                rel = np.abs(g_conf[r][ok] / o_conf[ok] - 1).max()
-                log["max_conf_rel"] = max(log["max_conf_rel"], float(rel))
-                assert rel < np.expm1(2 * eps), f"confidence off by {rel}"
-            safe_all.append((o_top1, o_conf, tie))
-        return safe_all
+        return _check_tables(host, tokens_rows, bs, L, g_top1, g_conf, log, guard, eps_logit)
 
     for blk in range(n_blocks):
         bs = P + blk * L
@@ -248,7 +259,7 @@ def _lockstep(workload, shape, n_blocks, guard=1e-3, max_iters=10 ** 9):
             d_x = _dev(x[None])
             g_top1, g_conf = psd.psd_forward_confidence(model, d_x, bs, L)
             g_top1_h, g_conf_h = g_top1.cpu().numpy(), g_conf.cpu().numpy()
-            (o_top1, o_conf, _), = check_tables([x], g_top1_h, g_conf_h)
+            (o_top1, o_conf, _, _), = check_tables([x], g_top1_h, g_conf_h)
             # decisions: same tables in -> identical decisions out (no exclusions)
             tm, ns = psd.psd_select_unmask(model, d_x, bs, L, g_top1, g_conf, gpol)
             sigma, m, drafts = psd.psd_build_drafts(model, d_x, bs, L, g_top1, g_conf, ggraph)
@@ -257,29 +268,57 @@ def _lockstep(workload, shape, n_blocks, guard=1e-3, max_iters=10 ** 9):
             o_sigma, o_m, o_drafts = orc.build_drafts(x1, bs, L, g_top1_h[0], g_conf_h[0], ograph, mask_id)
             assert int(m[0]) == o_m and (sigma.cpu().numpy()[0] == o_sigma).all()
             assert (drafts.cpu().numpy()[0] == o_drafts).all()
-            # would the oracle, on its own tables, have decided the same?  (guards: rank gaps, tau)
+            # would the oracle, on its own tables, have decided the same?  Only the pairs whose order actually
+            # differs (and threshold crossings) may be blamed, and only when they are near-ties.
             x1_o, _ = orc.select_unmask(x, bs, L, o_top1, o_conf, opol, mask_id)
             s_o, m_o, d_o = orc.build_drafts(x1_o, bs, L, o_top1, o_conf, ograph, mask_id)
-            same = (x1_o == x1).all() and (d_o == o_drafts).all()
-            if not same:
-                live = o_conf[o_conf >= 0]
-                gaps = np.abs(np.diff(np.sort(live))) / np.maximum(np.sort(live)[1:], 1e-30)
-                near_rank = (gaps < 8e-2).any()
-                near_tau = (np.abs(live - opol.tau) < guard).any()
-                assert near_rank or near_tau, "decision differs from the oracle's without a near-tie to blame"
-                log["near_tie_rank"] += int(near_rank)
-                log["near_tau"] += int(near_tau)
+            T_g = [j for j in range(L) if x1[bs + j] != x[bs + j]]
+            T_o = [j for j in range(L) if x1_o[bs + j] != x[bs + j]]
+            bad = G.unexplained_commit_differences(o_conf, T_o, T_g, opol.tau, r_conf)
+            log["commit_sets_differ"] += int(set(T_o) != set(T_g))
+            # a committed position whose top-1 differs is the top-1 rule's business (checked in check_tables)
+            if set(T_o) == set(T_g):
+                inv = G.inverted_pairs(list(s_o[:m_o]), list(o_sigma[:o_m]), n_ranks)
+                log["rank_pairs_inverted"] += len(inv)
+                bad += [("rank", p) for p in G.unexplained_rank_differences(o_conf, s_o[:m_o], o_sigma[:o_m], n_ranks, r_conf)]
+            log["unexplained"] += len(bad)
+            assert not bad, f"decision differs from the oracle's without a near-tie on the pairs involved: {bad}"
+            if not ((x1_o == x1).all() and (d_o == o_drafts).all()):
                 log["resync"] += 1      # both sides continue from the common state reached with the GPU's tables
             if o_m == 0:
                 x = x1
                 continue
             k_star, accepted, v_top1, v_conf = psd.psd_verify_accept(model, d_x, drafts, bs, L, sigma, m, ggraph, gpol)
             v_top1_h, v_conf_h = v_top1.cpu().numpy()[0], v_conf.cpu().numpy()[0]
-            check_tables(list(o_drafts), v_top1_h, v_conf_h)
+            o_tabs = check_tables(list(o_drafts), v_top1_h, v_conf_h)
             o_acc, o_k = orc.hierarchical_accept(o_drafts, bs, L, o_sigma, o_m, ograph, opol, v_top1_h, v_conf_h, mask_id)
             x2, _ = orc.advance(o_drafts, o_k, bs, L, v_top1_h, v_conf_h, opol, mask_id)
             assert int(k_star[0]) == o_k and (accepted.cpu().numpy()[0] == o_acc).all()
             assert (d_x.cpu().numpy()[0] == x2).all()
+            # the same acceptance on the oracle's own verifier tables: every per-position verdict that differs must
+            # sit on a top-1 near-tie of that row or on a near pair of the parent's confidence ranking
+            ov_top1, ov_conf = np.stack([t[0] for t in o_tabs]), np.stack([t[1] for t in o_tabs])
+            spec = sorted({int(j) for j in o_sigma[:min(o_m, n_ranks)]})
+
+            def committed(tabs_conf):
+                return lambda p: set(orc.policy_select(orc.masked_in_block(o_drafts[p], bs, L, mask_id), tabs_conf[p], opol))
+
+            v_g = G.edge_verdicts(v_top1_h, g_top1_h[0], spec, committed(v_conf_h))
+            v_o = G.edge_verdicts(ov_top1, g_top1_h[0], spec, committed(ov_conf))
+            for p, a in zip(*np.nonzero(v_g != v_o)):
+                j = spec[a]
+                if o_drafts[p][bs + j] != mask_id:
+                    continue                      # p itself already holds position j: not an edge test
+                tie_top1 = o_tabs[p][3][j] < 2 * eps_logit
+                T_go, T_oo = committed(v_conf_h)(p), committed(ov_conf)(p)
+                swapped = not G.unexplained_commit_differences(ov_conf[p], sorted(T_oo), sorted(T_go), opol.tau, r_conf)
+                log["verdicts_differ"] += 1
+                if not (tie_top1 or (T_go != T_oo and swapped)):
+                    log["unexplained"] += 1
+                    raise AssertionError(f"acceptance verdict of parent {p} at position {j} differs from the oracle's without a near-tie")
+            if (v_g == v_o).all():
+                o_acc2, o_k2 = orc.hierarchical_accept(o_drafts, bs, L, o_sigma, o_m, ograph, opol, ov_top1, ov_conf, mask_id)
+                assert o_k2 == o_k and (o_acc2 == o_acc).all(), "same verdicts, different acceptance"
             x = x2
     return log
 
@@ -351,3 +390,57 @@ def test_config5_shape_batched_block_decode():
         t1, c1 = psd.psd_forward_confidence(model, _dev(tokens0[b: b + 1]), w.prompt_len, w.block_len)
         assert (t1[0] == t_all[b]).all(), b
         assert torch.allclose(c1[0], c_all[b], rtol=2e-6, atol=0), b
+
+
+def test_config5_shape_two_layers_lockstep_inside_the_batch():
+    """Config 5's launch shapes (16 x 1280 stage-1, 128 x 1280 verification, L = 64, K = 8) on a 2-layer cut: one
+    iteration through the batched step calls.  The oracle's forward runs on sequences of the batch (one for the
+    stage-1 tables; the root, one middle and the deepest draft of it for the verification tables); the decisions of
+    all 16 sequences are replayed through the oracle's decision functions on the GPU's tables, bit for bit."""
+    import paper_2605_15609_amd as psd
+    from tests.gpu_common import gpu_graph
+    w = inp.WORKLOADS[5]
+    shape = inp.cut_down(w.shape, n_layers=2)
+    N, bs, L, K, B = w.seq_len, w.prompt_len, w.block_len, w.n_drafts, w.batch
+    host = inp.draw_model(shape, N, threads=16)
+    model = psd.Model.from_host(host, DEV)
+    opol, ograph = orc.Policy(w.tau, w.k_min, w.k_max), orc.chain_graph(K)
+    gpol, ggraph = psd.Policy(w.tau, w.k_min, w.k_max), gpu_graph(ograph)
+    mask_id = shape.mask_id
+    x = inp.initial_state(w)
+    log = {"near_tie_top1": 0, "max_conf_rel": 0.0, "unexplained": 0}
+    eps_logit = 2e-2
+    r_conf = float(np.expm1(2 * eps_logit))
+    pick = 5
+    d_x = _dev(x)
+    g_top1, g_conf = psd.psd_forward_confidence(model, d_x, bs, L)
+    t1, cf = g_top1.cpu().numpy(), g_conf.cpu().numpy()
+    (o_top1, o_conf, _, _), = _check_tables(host, [x[pick]], bs, L, t1[pick:pick + 1], cf[pick:pick + 1], log, 1e-3, eps_logit)
+    tm, ns = psd.psd_select_unmask(model, d_x, bs, L, g_top1, g_conf, gpol)
+    sigma, m, drafts = psd.psd_build_drafts(model, d_x, bs, L, g_top1, g_conf, ggraph)
+    after, sigma_h, m_h, drafts_h = d_x.cpu().numpy(), sigma.cpu().numpy(), m.cpu().numpy(), drafts.cpu().numpy()
+    o_sig, o_m, o_dr = [None] * B, [0] * B, [None] * B
+    for b in range(B):
+        x1, _ = orc.select_unmask(x[b], bs, L, t1[b], cf[b], opol, mask_id)
+        assert (after[b] == x1).all(), b
+        o_sig[b], o_m[b], o_dr[b] = orc.build_drafts(x1, bs, L, t1[b], cf[b], ograph, mask_id)
+        assert int(m_h[b]) == o_m[b] and (sigma_h[b] == o_sig[b]).all() and (drafts_h[b] == o_dr[b]).all(), b
+    # the oracle on its own stage-1 tables of the picked sequence: only near pairs may differ
+    x1_o, _ = orc.select_unmask(x[pick], bs, L, o_top1, o_conf, opol, mask_id)
+    T_g = [j for j in range(L) if after[pick][bs + j] != mask_id]
+    T_o = [j for j in range(L) if x1_o[bs + j] != mask_id]
+    bad = G.unexplained_commit_differences(o_conf, T_o, T_g, opol.tau, r_conf)
+    if set(T_o) == set(T_g):
+        s_o, m_o, _ = orc.build_drafts(x1_o, bs, L, o_top1, o_conf, ograph, mask_id)
+        bad += G.unexplained_rank_differences(o_conf, s_o[:m_o], o_sig[pick][:o_m[pick]], K - 1, r_conf)
+    assert not bad, bad
+    k_star, accepted, v_top1, v_conf = psd.psd_verify_accept(model, d_x, drafts, bs, L, sigma, m, ggraph, gpol)
+    vt, vc = v_top1.cpu().numpy(), v_conf.cpu().numpy()
+    nodes = [0, K // 2, K - 1]
+    _check_tables(host, [o_dr[pick][k] for k in nodes], bs, L, vt[pick][nodes], vc[pick][nodes], log, 1e-3, eps_logit)
+    final, ks_h, acc_h = d_x.cpu().numpy(), k_star.cpu().numpy(), accepted.cpu().numpy()
+    for b in range(B):
+        o_acc, o_k = orc.hierarchical_accept(o_dr[b], bs, L, o_sig[b], o_m[b], ograph, opol, vt[b], vc[b], mask_id)
+        x2, _ = orc.advance(o_dr[b], o_k, bs, L, vt[b], vc[b], opol, mask_id)
+        assert int(ks_h[b]) == o_k and (acc_h[b] == o_acc).all() and (final[b] == x2).all(), b
+    print(f"[decode] config 5 shape (2 layers) lock-step inside the batch: {log}", flush=True)

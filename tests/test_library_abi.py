@@ -78,3 +78,34 @@ def test_workspace_and_work_accounting(lib):
     assert abs(w.head_bytes / 1.037e9 - 1) < 0.01
     bad = _Config(2, 100, 4, 4, 25, 256, 300, 299, 1e-5, 0, 1, 1.0, 64)
     assert lib.psd_workspace_bytes(ctypes.byref(bad), 1, 32, 8) < 0
+
+
+def test_the_binding_rejects_tensors_the_library_would_misread(lib):
+    """The library reads raw pointers: rotary tables handed over as bf16 would be read as fp32 (garbage, and past
+    the end of the tensor).  Model checks dtype and extent of every tensor before psd_create."""
+    import numpy as np
+    import torch
+    import psd_inputs as inp
+    from paper_2605_15609_amd import binding as B
+    shape = inp.cut_down(inp.WORKLOADS[2].shape, n_layers=1, vocab=512)
+    host = inp.draw_model(shape, 64)
+
+    def tensors(rope_dtype=torch.float32, max_seq=64):
+        mat = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(torch.bfloat16)
+        vec = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(torch.float32)
+        t = {"tok_emb": mat(host.tok_emb), "lm_head": mat(host.lm_head), "final_norm": vec(host.final_norm),
+             "rope_cos": torch.from_numpy(host.rope_cos[:max_seq]).to(rope_dtype), "rope_sin": torch.from_numpy(host.rope_sin[:max_seq]).to(rope_dtype)}
+        lt = {k: (None if v is None else (mat(v) if v.ndim == 2 else vec(v))) for k, v in host.layers[0].items()}
+        B.pack_qkv(lt)
+        return t, [lt]
+
+    t, layers = tensors(rope_dtype=torch.bfloat16)
+    with pytest.raises(B.PsdError, match="rope_cos"):
+        B.Model(shape, 64, t, layers, device="cpu")
+    t, layers = tensors(max_seq=32)                 # tables shorter than max_seq
+    with pytest.raises(B.PsdError, match="rope_cos"):
+        B.Model(shape, 64, t, layers, device="cpu")
+    t, layers = tensors()
+    layers[0]["wo"] = layers[0]["wo"].float()        # a matrix in the wrong dtype
+    with pytest.raises(B.PsdError, match="layer 0 wo"):
+        B.Model(shape, 64, t, layers, device="cpu")
