@@ -142,7 +142,7 @@ typedef struct {
 
 const char *psd_status_string(int32_t status);
 /* sizeof of the structures above as this library was built, in the order psd_model_config, psd_weights,
- * psd_policy, psd_graph, psd_stats, psd_work, psd_graph_score (the first n of them into out; returns how many
+ * psd_policy, psd_graph, psd_stats, psd_work, psd_graph_score, psd_debug_layout (the first n of them into out; returns how many
  * there are): lets a foreign-language binding check its own declarations. */
 int32_t psd_struct_sizes(int32_t *out, int32_t n);
 /* Message of the last error raised on the calling thread ("" if none). */
@@ -188,6 +188,24 @@ int32_t psd_forward_logits(psd_handle *h, const int32_t *tokens, int32_t S, int3
 /* Debug switch for numeric cross-checks: bit 0 runs the layer contractions, bit 1 the
  * attention, bit 2 the LM-head on the plain (non-MFMA) kernels.  0 (default) = MFMA path. */
 int32_t psd_debug_set_plain(psd_handle *h, int32_t mask);
+
+/* Debug hook for parity checks of one layer at full width: runs layer `layer` of the model alone on a residual
+ * stream supplied by the caller -- hidden, device float [S*N, d_model], updated in place as one layer of the forward
+ * would (Sec. 3.1 only asks for a bidirectional transformer; the layer is RMSNorm, QKV, rotary, attention over the
+ * sequence's N rows, output projection, RMSNorm, SwiGLU, down projection, with the kernels and tiles the forward picks
+ * for S*N rows).  stop_after = 1 stops once the attention output is written and leaves hidden untouched.  The
+ * intermediates stay in the workspace, where psd_debug_workspace_layout says (byte offsets; row strides in elements
+ * of the model dtype): a = output of the last norm that ran [S*N, d_model]; qkv = projections with rotary applied
+ * [S*N, ld_qkv]; vT = values transposed, [S, n_kv_heads*d_head, ld_vt] with the keys of every group of 16 in the
+ * order 0-3, 8-11, 4-7, 12-15; o = attention output [S*N, n_heads*d_head]; act = SwiGLU output [S*N, ld_act].
+ * ws as for psd_forward_confidence(S, N, L).  Honours psd_debug_set_plain. */
+typedef struct {
+    int64_t off_a, off_qkv, off_vt, off_o, off_act;
+    int32_t ld_qkv, ld_act, ld_vt, reserved;
+} psd_debug_layout;
+int32_t psd_debug_workspace_layout(const psd_model_config *cfg, int32_t S, int32_t N, int32_t L, psd_debug_layout *out);
+int32_t psd_debug_layer(psd_handle *h, int32_t layer, float *hidden, int32_t S, int32_t N, int32_t L, int32_t stop_after,
+                        void *ws, int64_t ws_bytes, void *stream);
 
 /* Debug / tuning: forces the workgroup tile of the layer contractions (see psd_probe_begin
  * and psd_kernel_gemm_tile_name for the numbering; -1 = pick per shape; a tile that cannot run the

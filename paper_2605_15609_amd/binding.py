@@ -66,6 +66,12 @@ class _Work(C.Structure):
                 ("head_bytes", C.c_double), ("weight_bytes", C.c_double)]
 
 
+class _DebugLayout(C.Structure):
+    _fields_ = [("off_a", C.c_int64), ("off_qkv", C.c_int64), ("off_vt", C.c_int64), ("off_o", C.c_int64),
+                ("off_act", C.c_int64), ("ld_qkv", C.c_int32), ("ld_act", C.c_int32), ("ld_vt", C.c_int32),
+                ("reserved", C.c_int32)]
+
+
 _lib = None
 
 
@@ -89,6 +95,8 @@ def load_library():
         "psd_create": (i32, [C.POINTER(_Config), C.POINTER(_Weights), C.POINTER(vp)]),
         "psd_destroy": (i32, [vp]),
         "psd_debug_set_plain": (i32, [vp, i32]),
+        "psd_debug_workspace_layout": (i32, [C.POINTER(_Config), i32, i32, i32, C.POINTER(_DebugLayout)]),
+        "psd_debug_layer": (i32, [vp, i32, vp, i32, i32, i32, i32, vp, i64, vp]),
         "psd_workspace_bytes": (i64, [C.POINTER(_Config), i32, i32, i32]),
         "psd_decode_scratch_bytes": (i64, [i32, i32, i32, i32]),
         "psd_struct_sizes": (i32, [C.POINTER(i32), i32]),
@@ -137,7 +145,7 @@ def load_library():
         fn = getattr(lib, name)
         fn.restype, fn.argtypes = res, args
     # the structures declared here must be the ones the library was built with
-    mine = [C.sizeof(t) for t in (_Config, _Weights, _Policy, _Graph, _Stats, _Work, _GraphScore)]
+    mine = [C.sizeof(t) for t in (_Config, _Weights, _Policy, _Graph, _Stats, _Work, _GraphScore, _DebugLayout)]
     theirs = (i32 * len(mine))()
     if lib.psd_struct_sizes(theirs, len(mine)) != len(mine) or list(theirs) != mine:
         raise PsdError(f"binding and libpsd.so disagree on the structure layouts: {mine} vs {list(theirs)} (rebuild the library)")
@@ -616,6 +624,31 @@ def decode(model: Model, tokens: torch.Tensor, prompt_len: int, L: int, policy: 
             for b, st in zip(going, sub):
                 stats[b] = st
     return stats
+
+
+def debug_layer(model: Model, layer: int, hidden: torch.Tensor, S: int, N: int, L: int, stop_after: int = 0) -> dict:
+    """psd_debug_layer: one layer of the model on the caller's residual stream hidden fp32 [S*N, d_model] (in place).
+    Returns views of the intermediates the layer left in the workspace (valid until the next call on this model):
+    a [S*N, d], qkv [S*N, qkv_w] (rotary applied), o [S*N, H*dh], act [S*N, d_ffn] (stop_after = 0 only)."""
+    assert hidden.dtype == torch.float32 and hidden.is_contiguous() and hidden.shape == (S * N, model.shape.d_model)
+    ws, nb = model.forward_ws(S, N, L)
+    lay = _DebugLayout()
+    _check(model.lib.psd_debug_workspace_layout(C.byref(model.cfg), S, N, L, C.byref(lay)))
+    _check(model.lib.psd_debug_layer(model.handle, layer, _ptr(hidden), S, N, L, stop_after, _ptr(ws), nb, _stream()))
+    sh = model.shape
+    dt = torch.bfloat16 if sh.dtype == "bf16" else torch.float32
+    esz = 2 if sh.dtype == "bf16" else 4
+    T = S * N
+    qkv_w = (sh.n_heads + 2 * sh.n_kv_heads) * sh.d_head
+
+    def view(off, rows, ld, width):
+        return ws[off: off + rows * ld * esz].view(dt).view(rows, ld)[:, :width]
+
+    out = {"a": view(lay.off_a, T, sh.d_model, sh.d_model), "qkv": view(lay.off_qkv, T, lay.ld_qkv, qkv_w),
+           "o": view(lay.off_o, T, sh.n_heads * sh.d_head, sh.n_heads * sh.d_head)}
+    if stop_after == 0:
+        out["act"] = view(lay.off_act, T, lay.ld_act, sh.d_ffn)
+    return out
 
 
 # ------------------------------------------------------------------------------------------

@@ -286,7 +286,7 @@ int64_t psd_decode_scratch_bytes(int32_t B, int32_t N, int32_t L, int32_t K) {
 int32_t psd_struct_sizes(int32_t *out, int32_t n) {
     const int32_t sizes[] = {(int32_t)sizeof(psd_model_config), (int32_t)sizeof(psd_weights), (int32_t)sizeof(psd_policy),
                              (int32_t)sizeof(psd_graph),        (int32_t)sizeof(psd_stats),   (int32_t)sizeof(psd_work),
-                             (int32_t)sizeof(psd_graph_score)};
+                             (int32_t)sizeof(psd_graph_score), (int32_t)sizeof(psd_debug_layout)};
     const int32_t count = (int32_t)(sizeof(sizes) / sizeof(sizes[0]));
     for (int32_t i = 0; out && i < n && i < count; ++i) out[i] = sizes[i];
     return count;
@@ -333,6 +333,30 @@ int32_t psd_forward_logits(psd_handle *h, const int32_t *tokens, int32_t S, int3
     hipStream_t st = (hipStream_t)stream;
     CHECK(run_forward_hidden(h, tokens, nullptr, S, N, block_start, L, ws, ws_bytes, st));
     return run_head_logits(h, S, N, L, logits, ws, st);
+}
+
+int32_t psd_debug_workspace_layout(const psd_model_config *cfg, int32_t S, int32_t N, int32_t L, psd_debug_layout *out) {
+    CHECK(check_cfg(cfg));
+    if (!out || S < 1 || N < 1 || L < 1 || L > PSD_MAX_BLOCK || L > N) PSD_FAIL(PSD_ERR_INVALID_ARG, "bad arguments");
+    const ForwardPlan p = plan_forward(*cfg, S, N, L);
+    out->off_a = p.off_a;
+    out->off_qkv = p.off_qkv;
+    out->off_vt = p.off_vt;
+    out->off_o = p.off_o;
+    out->off_act = p.off_act;
+    out->ld_qkv = (int32_t)qkv_row_stride((int64_t)(cfg->n_heads + 2 * cfg->n_kv_heads) * cfg->d_head);
+    out->ld_act = (int32_t)act_row_stride(*cfg);
+    out->ld_vt = (int32_t)vt_row_stride(N);
+    return PSD_OK;
+}
+
+int32_t psd_debug_layer(psd_handle *h, int32_t layer, float *hidden, int32_t S, int32_t N, int32_t L, int32_t stop_after, void *ws,
+                        int64_t ws_bytes, void *stream) {
+    CHECK(check_block(h, S, N, 0, L));
+    if (!hidden) PSD_FAIL(PSD_ERR_INVALID_ARG, "hidden is NULL");
+    if (layer < 0 || layer >= h->cfg.n_layers) PSD_FAIL(PSD_ERR_SHAPE, "layer %d outside 0..%d", layer, h->cfg.n_layers - 1);
+    if (stop_after != 0 && stop_after != 1) PSD_FAIL(PSD_ERR_INVALID_ARG, "stop_after %d", stop_after);
+    return run_debug_layer(h, layer, hidden, S, N, L, stop_after, ws, ws_bytes, (hipStream_t)stream);
 }
 
 int32_t psd_select_unmask(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_t block_start, int32_t L,

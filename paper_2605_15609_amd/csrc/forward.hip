@@ -248,7 +248,52 @@ int32_t forward_cached_impl(psd_handle *h, const int32_t *tokens, const int32_t 
     return PSD_OK;
 }
 
+// One layer of the stack on a residual stream handed in by the caller (all S*N rows, no block-row shortcut), with
+// the tile choices and kernels the forward makes for S*N rows.  stop_after = 1 returns once the attention output
+// is in the workspace (the stream is then untouched, and `a` still holds the first norm's output).
+template <typename T>
+int32_t debug_layer_impl(psd_handle *h, int li, float *hbuf, int S, int N, int L, int stop_after, char *ws, hipStream_t st) {
+    const psd_model_config &c = h->cfg;
+    const ForwardPlan p = plan_forward(c, S, N, L);
+    const int64_t ntok = (int64_t)S * N;
+    const int d = c.d_model, H = c.n_heads, Hkv = c.n_kv_heads, dh = c.d_head, F = c.d_ffn;
+    const int qkv_w = (H + 2 * Hkv) * dh;
+    T *a = (T *)(ws + p.off_a), *qkv = (T *)(ws + p.off_qkv), *vT = (T *)(ws + p.off_vt), *o = (T *)(ws + p.off_o);
+    T *act = (T *)(ws + p.off_act);
+    const int ld_act = (int)act_row_stride(c), ld_qkv = (int)qkv_row_stride(qkv_w);
+    const psd_handle::Layer &lw = h->layers[li];
+    launch_rmsnorm<T>(hbuf, ntok, d, lw.attn_norm, c.rms_eps, a, PendingSums(), st);
+    const int epi_qkv = c.qkv_bias ? EPI_BIAS : EPI_STORE;
+    Dispatch<T>::gemm(h, a, d, lw.wq, nullptr, d, ntok, H * dh, d, epi_qkv, lw.bq, qkv, nullptr, ld_qkv, nullptr, st);
+    Dispatch<T>::gemm(h, a, d, lw.wk, nullptr, d, ntok, Hkv * dh, d, epi_qkv, lw.bk, qkv + H * dh, nullptr, ld_qkv, nullptr, st);
+    Dispatch<T>::gemm(h, a, d, lw.wv, nullptr, d, ntok, Hkv * dh, d, epi_qkv, lw.bv, qkv + (H + Hkv) * dh, nullptr, ld_qkv, nullptr, st);
+    Dispatch<T>::rope_attention(h, qkv, ld_qkv, vT, S, N, 0, H, Hkv, dh, o, KvPrefix(), c.attention == PSD_ATTN_BLOCK_CAUSAL ? L : 0, st);
+    if (stop_after == 1) return PSD_OK;
+    Dispatch<T>::gemm(h, o, H * dh, lw.wo, nullptr, H * dh, ntok, d, H * dh, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, nullptr, st);
+    launch_rmsnorm<T>(hbuf, ntok, d, lw.ffn_norm, c.rms_eps, a, PendingSums(), st);
+    Dispatch<T>::gemm(h, a, d, lw.w_gate, lw.w_up, d, ntok, F, d, EPI_SWIGLU, nullptr, act, nullptr, ld_act, nullptr, st);
+    Dispatch<T>::gemm(h, act, ld_act, lw.w_down, nullptr, h->w_down_stride, ntok, d, F, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, nullptr, st);
+    return PSD_OK;
+}
+
 }   // namespace
+
+int32_t run_debug_layer(psd_handle *h, int layer, float *hidden, int S, int N, int L, int stop_after, void *ws, int64_t ws_bytes,
+                        hipStream_t st) {
+    const ForwardPlan p = plan_forward(h->cfg, S, N, L);
+    if (ws == nullptr || ws_bytes < p.total)
+        PSD_FAIL(PSD_ERR_WORKSPACE, "workspace of %lld bytes, one layer over %d x %d tokens needs %lld", (long long)ws_bytes, S, N,
+                 (long long)p.total);
+    if ((reinterpret_cast<uintptr_t>(ws) & 255) != 0) PSD_FAIL(PSD_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    int32_t rc;
+    if (h->cfg.dtype == PSD_DTYPE_BF16)
+        rc = debug_layer_impl<bf16_t>(h, layer, hidden, S, N, L, stop_after, (char *)ws, st);
+    else
+        rc = debug_layer_impl<float>(h, layer, hidden, S, N, L, stop_after, (char *)ws, st);
+    if (rc != PSD_OK) return rc;
+    PSD_HIP(hipGetLastError());
+    return PSD_OK;
+}
 
 int32_t run_forward_cached(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N, int block_start, int L,
                            const KvCacheArg &kv, void *ws, int64_t ws_bytes, hipStream_t st) {

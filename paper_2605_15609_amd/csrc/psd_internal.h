@@ -107,6 +107,10 @@ int32_t run_head_confidence(psd_handle *h, const int32_t *tokens, const int32_t 
 int32_t run_forward_cached(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N, int block_start, int L,
                            const KvCacheArg &kv, void *ws, int64_t ws_bytes, hipStream_t st);
 int32_t run_head_logits(psd_handle *h, int S, int N, int L, float *logits, void *ws, hipStream_t st);
+// debug: layer `layer` alone on the caller's residual stream [S*N, d_model] (in place); see psd_debug_layer
+int32_t run_debug_layer(psd_handle *h, int layer, float *hidden, int S, int N, int L, int stop_after, void *ws, int64_t ws_bytes,
+                        hipStream_t st);
+int64_t act_row_stride(const psd_model_config &cfg);
 
 // Keys and values that precede a sequence's own rows in attention: a KV cache of `len` positions, shared by
 // seqs_per_cache consecutive sequences (the K drafts of one verification batch share their sequence's prefix).

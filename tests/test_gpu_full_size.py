@@ -187,3 +187,145 @@ def test_config3_full_depth_approximate_cache():
         say(f"[full-size] {label}: logits max-abs err {err:.3e} (tol {tol:.3e}), near-ties {near}, inside the band {wide}; "
             f"{time.perf_counter() - t0:.0f} s")
     model.close()
+
+
+# ------------------------------------------------------------------------------------------------------------
+# One layer at a time, stage by stage, at full width: the check that an end-to-end tolerance of 0.2 logits cannot give.
+# The HIP layer runs alone (psd_debug_layer) on the ORACLE's exact residual stream at the input of an early, a middle
+# and the last layer of the 32-layer model; every stage's output is then compared with the exact (fp64) evaluation
+# of that stage on the HIP path's own input of the stage.  So each comparison sees exactly one bf16 rounding of the
+# stage's result (unit round-off u = 2^-8, relative) plus fp32 accumulation, and the bounds below are those:
+#   a    = bf16(rmsnorm(h))                         |err| <= u |ref|
+#   q, k = bf16(rope(bf16(a Wq^T)))                 |err| <= u (|x1 c| + |x2 s|) + u |ref|     (the projection is stored in
+#                                                    bf16 before the rotation: two roundings)
+#   v    = bf16(a Wv^T)                             |err| <= u |ref|
+#   o    = bf16(sum_j bf16(p_j) v_j / sum_j p_j)    |err| <= u sum_j p_j |v_j| / sum_j p_j + u |ref|
+#   a2   = bf16(rmsnorm(h + o Wo^T))                |err| <= u |ref|
+#   act  = bf16(silu(a2 Wg^T) * (a2 Wu^T))          |err| <= u |ref|
+#   h'   = h + o Wo^T + act Wd^T  (fp32)            |err| <= fp32 accumulation only
+# each plus the fp32 accumulation term g(K) sum_k |x_k w_k| with g(K) = 4 sqrt(K) 2^-24.
+LAYERS_CHECKED = (0, 15, 31)
+U = 2.0 ** -8
+
+
+def _acc(K):
+    return 4.0 * np.sqrt(K) * 2.0 ** -24
+
+
+def _stage_check(name, got, ref, bound, stats):
+    err = np.abs(got - ref)
+    worst = float((err / np.maximum(bound, 1e-300)).max())
+    stats[name] = round(worst, 3)
+    assert (err <= bound).all(), f"{name}: error {err.max():.3e} exceeds its bound by a factor {worst:.2f} at {np.unravel_index((err / np.maximum(bound, 1e-300)).argmax(), err.shape)}"
+
+
+def test_config3_single_layers_stage_by_stage_against_unit_roundoff_bounds():
+    _need_memory()
+    import torch
+    import paper_2605_15609_amd as psd
+    from paper_2605_15609_amd import binding as B
+    from tests.gpu_common import say, to_dev
+    w = inp.WORKLOADS[3]
+    shape, N, P, L = w.shape, w.seq_len, w.prompt_len, w.block_len
+    H, Hkv, dh, d, F = shape.n_heads, shape.n_kv_heads, shape.d_head, shape.d_model, shape.d_ffn
+    t0 = time.perf_counter()
+    host = inp.draw_model(shape, N, threads=16)
+    model = psd.Model.from_host(host)
+    say(f"[layer] config 3 drawn and uploaded after {time.perf_counter() - t0:.0f} s")
+    tokens = _state(shape, N, P, L, 77, 9)
+    cos, sin = host.rope_cos[:N].astype(np.float64), host.rope_sin[:N].astype(np.float64)
+    h = host.tok_emb[tokens].astype(np.float64)
+    inputs = {}
+    for l, lw in enumerate(host.layers):
+        if l in LAYERS_CHECKED:
+            inputs[l] = h.astype(np.float32)        # the stream crosses the boundary as fp32
+        if l == max(LAYERS_CHECKED):
+            break
+        h = orc.layer_forward(h, lw, shape, cos, sin)
+    say(f"[layer] oracle residual streams at the inputs of layers {LAYERS_CHECKED} after {time.perf_counter() - t0:.0f} s")
+    f64 = lambda t: t.float().cpu().numpy().astype(np.float64)
+    for l in LAYERS_CHECKED:
+        lw = host.layers[l]
+        W = lambda k: lw[k].astype(np.float64)
+        h_in = inputs[l].astype(np.float64)
+        stats = {}
+        # ---- first half: norm, projections, rotary, attention
+        d_h = to_dev(inputs[l])
+        out = B.debug_layer(model, l, d_h, 1, N, L, stop_after=1)
+        torch.cuda.synchronize()
+        assert torch.equal(d_h.cpu(), torch.from_numpy(inputs[l])), "stop_after = 1 must leave the stream untouched"
+        a1, qkv, o = f64(out["a"]), f64(out["qkv"]), f64(out["o"])
+        ref = orc.rmsnorm(h_in, W("attn_norm"), shape.rms_eps)
+        _stage_check("a", a1, ref, U * np.abs(ref) * 1.001 + 1e-12, stats)
+        Wqkv = np.concatenate([W("wq"), W("wk"), W("wv")])
+        pre = a1 @ Wqkv.T
+        accb = _acc(d) * (np.abs(a1) @ np.abs(Wqkv).T)
+        nq, nk = H * dh, Hkv * dh
+        qk_room = np.zeros((N, nq + nk))          # |x1 c| + |x2 s| + |result| of every rotated element
+        qk_acc = np.zeros((N, nq + nk))           # fp32 accumulation room of every rotated element
+        for name, lo, nh in (("q", 0, H), ("k", nq, Hkv)):
+            x = pre[:, lo: lo + nh * dh].reshape(N, nh, dh)
+            ab = accb[:, lo: lo + nh * dh].reshape(N, nh, dh)
+            half = dh // 2
+            x1, x2, c, s_ = x[..., :half], x[..., half:], cos[:, None, :], sin[:, None, :]
+            ref = orc.rope(x, cos, sin)
+            spread = np.concatenate([np.abs(x1 * c) + np.abs(x2 * s_), np.abs(x2 * c) + np.abs(x1 * s_)], axis=-1)
+            acc_r = np.concatenate([ab[..., :half] + ab[..., half:]] * 2, axis=-1)
+            _stage_check(name, qkv[:, lo: lo + nh * dh].reshape(N, nh, dh), ref, U * (spread + np.abs(ref)) * 1.001 + acc_r + 1e-12, stats)
+            qk_room[:, lo: lo + nh * dh] = (spread + np.abs(ref)).reshape(N, nh * dh)
+            qk_acc[:, lo: lo + nh * dh] = acc_r.reshape(N, nh * dh)
+        ref = pre[:, nq + nk:]
+        _stage_check("v", qkv[:, nq + nk:], ref, U * np.abs(ref) * 1.001 + accb[:, nq + nk:] + 1e-12, stats)
+        q, k, v = qkv[:, :nq].reshape(N, H, dh), qkv[:, nq: nq + nk].reshape(N, Hkv, dh), qkv[:, nq + nk:].reshape(N, Hkv, dh)
+        ref = orc.attention(q, k, v).reshape(N, H * dh)
+        spread = orc.attention(q, k, np.abs(v)).reshape(N, H * dh)        # sum_j p_j |v_j| / sum_j p_j
+        _stage_check("o", o, ref, U * (spread + np.abs(ref)) * 1.001 + 1e-4 * spread + 1e-12, stats)
+        # ---- whole layer: same first half (deterministic), then output projection, norm, SwiGLU, down projection
+        d_h = to_dev(inputs[l])
+        out = B.debug_layer(model, l, d_h, 1, N, L, stop_after=0)
+        torch.cuda.synchronize()
+        assert torch.equal(out["o"].cpu(), torch.from_numpy(o.astype(np.float32)).to(torch.bfloat16)), "the first half is not repeatable"
+        a2, act, h_out = f64(out["a"]), f64(out["act"]), d_h.cpu().numpy().astype(np.float64)
+        upd_o = o @ W("wo").T
+        h_mid = h_in + upd_o
+        acc_o = _acc(H * dh) * (np.abs(o) @ np.abs(W("wo")).T) + 2.0 ** -23 * np.abs(h_mid)
+        ref = orc.rmsnorm(h_mid, W("ffn_norm"), shape.rms_eps)
+        rms = np.sqrt(np.mean(h_mid ** 2, axis=-1, keepdims=True))
+        _stage_check("a2", a2, ref, U * np.abs(ref) * 1.001 + 2.0 * acc_o / rms + 1e-12, stats)
+        g, u_ = a2 @ W("w_gate").T, a2 @ W("w_up").T
+        ref = orc.silu(g) * u_
+        ag, au = _acc(d) * (np.abs(a2) @ np.abs(W("w_gate")).T), _acc(d) * (np.abs(a2) @ np.abs(W("w_up")).T)
+        _stage_check("act", act, ref, U * np.abs(ref) * 1.001 + 1.2 * ag * np.abs(u_) + au * np.abs(orc.silu(g)) + 1e-12, stats)
+        ref = h_mid + act @ W("w_down").T
+        acc_d = _acc(F) * (np.abs(act) @ np.abs(W("w_down")).T)
+        _stage_check("h_out", h_out, ref, acc_o + acc_d + 2.0 ** -22 * np.abs(ref) + 1e-12, stats)
+        # ---- the same layer on the plain fp32-accumulating debug kernels: the two paths round at the same points, so
+        # they may differ by the last bit of a bf16 result here and there, nothing more
+        model.set_plain(7)
+        d_p = to_dev(inputs[l])
+        outp = B.debug_layer(model, l, d_p, 1, N, L, stop_after=0)
+        torch.cuda.synchronize()
+        model.set_plain(0)
+        qkv_p, o_p, act_p = f64(outp["qkv"]), f64(outp["o"]), f64(outp["act"])
+        ulp = lambda x, y: 2.0 ** -7 * np.maximum(np.abs(x), np.abs(y))
+        # (a result that cancels to almost nothing is smaller than the accumulation error of its sum: both paths get that room)
+        pairs = (("v", qkv[:, nq + nk:], qkv_p[:, nq + nk:], 1.01 * ulp(qkv[:, nq + nk:], qkv_p[:, nq + nk:]) + 2 * accb[:, nq + nk:]),
+                 ("qk", qkv[:, :nq + nk], qkv_p[:, :nq + nk], 1.5 * 2.0 ** -7 * qk_room + 2 * qk_acc),   # a flip before the rotation is rotated too
+                 ("o", o, o_p, 3.01 * ulp(o, o_p) + 2e-3 * spread),
+                 ("act", act, act_p, None))      # downstream of the differences above: compared in the mean only
+        for name, mine, theirs, room in pairs:
+            diff = np.abs(mine - theirs)
+            frac = float((diff > 0).mean())
+            rel_rms = float(np.sqrt((diff ** 2).mean() / (mine ** 2).mean()))
+            stats[f"plain_{name}"] = (round(frac, 4), float(f"{rel_rms:.2e}"))
+            if room is not None:
+                assert (diff <= room + 1e-9).all(), f"layer {l} {name}: MFMA and plain kernels differ by more than rounding ({(diff / (room + 1e-9)).max():.2f} x)"
+            # if every element differed by one unit in the last place of bf16 the relative rms difference would be about 3e-3
+            assert rel_rms <= 4e-3, f"layer {l} {name}: MFMA and plain kernels differ by {rel_rms:.2e} relative rms"
+        dh_ = h_out - d_p.cpu().numpy().astype(np.float64)
+        rel = float(np.sqrt((dh_ ** 2).mean() / ((h_out - h_in) ** 2).mean()))
+        stats["plain_h_out"] = float(f"{rel:.2e}")
+        assert rel <= 4e-3, f"layer {l}: the layer's update differs between MFMA and plain kernels by {rel:.2e} relative rms"
+        say(f"[layer] config 3 layer {l}: worst error / bound per stage {stats}; |h| rms {np.sqrt((h_out ** 2).mean()):.3f}; "
+            f"{time.perf_counter() - t0:.0f} s")
+    model.close()

@@ -35,8 +35,9 @@ def test_structure_layouts_agree_with_the_binding(lib):
     from paper_2605_15609_amd import binding as B
     n = lib.psd_struct_sizes(None, 0)
     got = (ctypes.c_int32 * n)()
-    assert lib.psd_struct_sizes(got, n) == n == 7
-    assert list(got) == [ctypes.sizeof(t) for t in (B._Config, B._Weights, B._Policy, B._Graph, B._Stats, B._Work, B._GraphScore)]
+    assert lib.psd_struct_sizes(got, n) == n == 8
+    assert list(got) == [ctypes.sizeof(t) for t in (B._Config, B._Weights, B._Policy, B._Graph, B._Stats, B._Work, B._GraphScore,
+                                                    B._DebugLayout)]
     assert got[2] == 20 and got[6] == 40           # psd_policy: float + 4 x int32; psd_graph_score: 3 doubles + 2 x int64
 
 
