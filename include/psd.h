@@ -387,6 +387,15 @@ int32_t psd_kernel_head_stream_bf16(const void *y_packed, const void *W_packed, 
                                     void *stream);
 int32_t psd_kernel_head_confidence_bf16(const void *y, const void *W, int32_t rows, int32_t vocab, int32_t d, float scale,
                                         int32_t mask_id, void *scratch, float *row_sum, int32_t *row_arg, void *stream);
+/* psd_kernel_head_stream_bf16 for callers that cannot allocate device memory or size a scratch buffer: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs and kernels; the
+ * per-slab partial results go to a static device array inside the library (11 796 480 bytes, held by every GPU the
+ * library runs on until the process ends) instead of `scratch`.  Limits: rows <= 192, vocab <= 163 840
+ * (PSD_ERR_WORKSPACE beyond them; nothing is launched).  Allocates nothing and frees nothing.  All calls on one GPU
+ * share that array: calls that overlap on one GPU (different streams or threads) race; calls on one stream do not. */
+int32_t psd_kernel_head_stream_static_bf16(const void *y_packed, const void *W_packed, int32_t rows, int32_t vocab,
+                                           int32_t d, float scale, int32_t mask_id, float *row_sum, int32_t *row_arg,
+                                           void *stream);
 
 /* Calibration kernel: 256 workgroups of 4 wavefronts, each running `iters` rounds of 16 independent
  * v_mfma_f32_32x32x16_bf16 on operand data read from `operands` (device, bf16 values, >= 16 bytes)

@@ -133,6 +133,7 @@ def load_library():
         "psd_kernel_packed_bytes": (i64, [i64, i32]),
         "psd_kernel_pack_rows": (i32, [vp, i64, i32, vp, vp]),
         "psd_kernel_head_stream_bf16": (i32, [vp, vp, i32, i32, i32, C.c_float, i32, vp, vp, vp, vp]),
+        "psd_kernel_head_stream_static_bf16": (i32, [vp, vp, i32, i32, i32, C.c_float, i32, vp, vp, vp]),
         "psd_kernel_mfma_rate": (i32, [vp, i64, i32, vp, i64, C.POINTER(C.c_double), vp]),
         "psd_probe_begin": (i32, [vp, i32, i32, i32]),
         "psd_probe_end": (i32, [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
@@ -767,3 +768,10 @@ def kernel_head_stream_bf16(y: torch.Tensor, W_packed: torch.Tensor, V: int, sca
                                            _ptr(scratch), _ptr(row_sum), _ptr(row_arg), _stream()))
     return row_sum, row_arg
 
+
+def kernel_head_stream_static_bf16(y_packed: torch.Tensor, W_packed: torch.Tensor, rows: int, V: int, d: int, scale: float,
+                                   mask_id: int, row_sum: torch.Tensor, row_arg: torch.Tensor) -> None:
+    """psd_kernel_head_stream_static_bf16: every buffer comes from the caller, the library's static array serves as
+    scratch; nothing is allocated here or in the library."""
+    _check(load_library().psd_kernel_head_stream_static_bf16(_ptr(y_packed), _ptr(W_packed), rows, V, d, float(scale),
+                                                             int(mask_id), _ptr(row_sum), _ptr(row_arg), _stream()))

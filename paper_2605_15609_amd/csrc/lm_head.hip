@@ -7,6 +7,8 @@
 // triple per row; a second tiny kernel merges the slabs in ascending id order, so ties keep
 // the lowest token id and the result does not depend on scheduling.  Full logits never
 // reach HBM.  The [M] column is excluded from both the max and the normaliser.
+#include <mutex>
+
 #include "gemm_mfma.h"
 
 namespace {
@@ -299,4 +301,57 @@ void launch_head_confidence_bf16(const bf16_t *y, const bf16_t *W, int rows, int
         launch_cfg<SLAB_BIG, 128, 2, 2, EPI_TOP1, 2>(W, y, nullptr, V, rows, d, d, d, nullptr, nullptr, nullptr, 0, t1, st);
     hipLaunchKernelGGL(head_merge_kernel, dim3(rows), dim3(64), 0, st, t1.pmax, t1.psum, t1.parg, slabs, rows, row_sum,
                        row_arg);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The streaming head for callers that cannot allocate (HIP graph capture, tight serving loops): the per-slab
+// (max, sum-exp, argmax) triples go to a file-scope device array instead of a caller-provided scratch buffer.
+// Every GPU holds its own copy of the array at its own address; the address is looked up once per device and
+// that pointer, never the array's name, is what host code hands to the kernels.
+namespace {
+
+constexpr int kStaticMaxRows = 192;         // the streaming kernel's own limit
+constexpr int kStaticMaxVocab = 163840;     // 5120 slabs of 32 ids
+constexpr size_t kStaticScratchBytes = 3ull * (kStaticMaxVocab / 32) * kStaticMaxRows * 4;   // 11 796 480 bytes
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device (looked up on the first call there)
+int32_t static_scratch(void **out) {
+    int dev = -1;
+    PSD_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) PSD_FAIL(PSD_ERR_DEVICE, "device index %d outside 0..%d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        PSD_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) PSD_FAIL(PSD_ERR_DEVICE, "hipGetSymbolAddress returned a NULL address for the static scratch array");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return PSD_OK;
+}
+
+}   // namespace
+
+extern "C" int32_t psd_kernel_head_stream_static_bf16(const void *y_packed, const void *W_packed, int32_t rows, int32_t vocab,
+                                                      int32_t d, float scale, int32_t mask_id, float *row_sum, int32_t *row_arg,
+                                                      void *stream) {
+    if (!y_packed || !W_packed || !row_sum || !row_arg || rows < 1 || vocab < 2) PSD_FAIL(PSD_ERR_INVALID_ARG, "bad arguments");
+    if (!head_stream_supported(rows, d)) PSD_FAIL(PSD_ERR_SHAPE, "streaming head takes at most 192 rows and d a multiple of 64");
+    if (rows > kStaticMaxRows || vocab > kStaticMaxVocab)
+        PSD_FAIL(PSD_ERR_WORKSPACE, "the static scratch array holds the partial results of at most %d rows x %d vocabulary ids, not %d x %d",
+                 kStaticMaxRows, kStaticMaxVocab, rows, vocab);
+    void *ptr = nullptr;
+    const int32_t rc = static_scratch(&ptr);
+    if (rc != PSD_OK) return rc;
+    // every (row, slab) triple the merge reads is written by the stream kernel of this same call: nothing to clear
+    launch_head_stream_bf16((const bf16_t *)y_packed, (const bf16_t *)W_packed, rows, vocab, d, scale, mask_id, ptr, row_sum,
+                            row_arg, (hipStream_t)stream);
+    PSD_HIP(hipGetLastError());
+    return PSD_OK;
 }
