@@ -22,12 +22,18 @@
  *     enqueue asynchronously and do not synchronise, except psd_decode_block, which
  *     returns host statistics and reads small counters back once per iteration.
  *   - Layouts are row-major.  tokens int32 [B, N]; the active block is positions
- *     block_start .. block_start+L-1 of every sequence (1 <= L <= 64).  Per-block tables
+ *     block_start .. block_start+L-1 of every sequence (1 <= L <= 64; the step calls take one block_start for
+ *     the batch, psd_decode_block and psd_decode one per sequence).  Per-block tables
  *     are top1 int32 [B, L] and conf float [B, L]: a masked position carries the
  *     prediction, any other position the sentinel (its own token, -1.0f).
- *   - Sequences of a batch are independent.  Batching never changes a sequence's logits or top-1
- *     tokens; the confidence normaliser is summed in an order that depends on the number of rows
- *     in the call, so confidences can differ in the last fp32 bit between batch shapes.
+ *   - Sequences of a batch are independent.  In the whole-sequence calls batching never changes a sequence's
+ *     logits or top-1 tokens; the confidence normaliser is summed in an order that depends on the number of rows
+ *     in the call, so confidences can differ in the last fp32 bit between batch shapes.  The block-row calls
+ *     (psd_*_cached, psd_*_approx) cut the output and down projections along K when a call has at most 128 rows,
+ *     so there a sequence's fp32 sums, and with near-tied confidences its decisions, can depend on how many
+ *     sequences or drafts share the call; results agree to fp32 rounding of those sums.
+ *   - Token ids outside [0, vocab) are invalid input: they read a zero embedding row (no fault).  A block row
+ *     whose logits are all non-finite has no prediction: it yields (token 0, confidence 0).
  */
 #ifndef PSD_H
 #define PSD_H
@@ -251,14 +257,30 @@ int32_t psd_verify_accept(psd_handle *h, int32_t *tokens, const int32_t *drafts,
                           uint8_t *accepted, int32_t *v_top1, float *v_conf,
                           void *ws, int64_t ws_bytes, void *stream);
 
-/* Alg. 1 on the block [block_start, block_start+L) of B sequences, until none of them has
- * a masked position left in it.  Sequences that finish early drop out of the model calls.
+/* Alg. 1 on one block of each of B sequences: sequence b decodes the block [block_start[b], block_start[b]+L) until
+ * it has no masked position left (block_start: host int32 [B]; the sequences need not be on the same block).  An
+ * iteration is one stage-1 model call over the sequences still running and one batched verification call over the K
+ * drafts of those that keep masks after the stage-1 commit; sequences that finish early drop out of the model calls.
  * Blocks until done.  tokens device int32 [B, N] (updated in place);
  * stats host psd_stats [B], counters are ADDED to what it holds (zero it first);
  * ws_bytes >= psd_workspace_bytes(cfg, B*K, N, L) + psd_decode_scratch_bytes(B, N, L, K). */
-int32_t psd_decode_block(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_t block_start,
+int32_t psd_decode_block(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, const int32_t *block_start,
                          int32_t L, const psd_policy *policy, const psd_graph *graph, psd_stats *stats,
                          void *ws, int64_t ws_bytes, void *stream);
+/* The whole semi-autoregressive generation (Alg. 1 per block; App. B.1: blocks left to right, the next block of a
+ * sequence starts once its current one is fully resolved; with policy->eos_stop a sequence ends with the block in
+ * which an EOS token was produced).  block_start: host int32 [B], in and out: the first position of every sequence's
+ * current block on entry (N - block_start[b] a multiple of L; block_start[b] >= N: nothing left to do), and where
+ * the sequence stands on return (>= N when it reached the end).  Every sequence advances through its own blocks: a
+ * sequence that resolves its block moves on in the next iteration while the others continue, so the model calls
+ * keep all running sequences in one batch.  max_iterations > 0 returns after that many iterations of the batch
+ * (0: until every sequence is done); *iterations_done (host, may be NULL) receives the number run.  A later call
+ * continues from tokens and block_start as they stand.  Workspace and stats as for psd_decode_block; with
+ * max_iterations > 0 and EOS stopping, tokens_counted of a call counts what that call resolved at or before the
+ * first EOS its block holds by the end of the call. */
+int32_t psd_decode(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_t *block_start, int32_t L,
+                   const psd_policy *policy, const psd_graph *graph, psd_stats *stats, int32_t max_iterations,
+                   int32_t *iterations_done, void *ws, int64_t ws_bytes, void *stream);
 int64_t psd_decode_scratch_bytes(int32_t B, int32_t N, int32_t L, int32_t K);
 
 /* ---- Context-causal block attention with an exact prefix KV cache ------------------------------
@@ -410,14 +432,19 @@ int32_t psd_kernel_mfma_rate(const void *operands, int64_t operand_bytes, int32_
  * 2 residual, 3 SwiGLU) and workgroup tile configuration (an index below
  * psd_kernel_gemm_tile_count; psd_kernel_gemm_tile_name describes it: tile extent, wavefronts,
  * depths of the two LDS rings) is bracketed by HIP events on the stream it is launched on (up to
- * max_launches; later ones go untimed).  Epilogue 4 selects the LM-head confidence pass instead
- * (all its kernels, tile ignored); it can be timed together with one contraction kernel.
+ * max_launches; later ones go untimed).  Kind 4 selects the LM-head confidence pass instead
+ * (all its kernels, tile ignored), kind 5 every model call (forward + confidence pass) made by
+ * psd_decode_block / psd_decode; both can be timed together with one contraction kernel.
  * psd_probe_end waits for those events and returns their summed duration, the number of timed
  * launches and their algorithmic work: FLOPs (2*M*N*K, twice that for SwiGLU) for a contraction,
- * bytes (vocab*d*2 + rows*d*2 + rows*8) for the LM-head pass.
+ * bytes (vocab*d*2 + rows*d*2 + rows*8) for the LM-head pass, 0 for model calls (psd_forward_work gives it).
+ * psd_probe_read (after psd_probe_end) copies the first max_n timed launches one by one: ms[i] their duration and
+ * (a[i], b[i]) = (rows, output columns) of a contraction, (rows, 0) of an LM-head pass, (sequences, drafts per
+ * sequence: 1 for a stage-1 call, K for a verification call) of a model call; returns how many it wrote.
  * psd_kernel_gemm_tile tells which tile the dispatcher picks for a shape. */
 int32_t psd_probe_begin(psd_handle *h, int32_t epilogue, int32_t tile, int32_t max_launches);
 int32_t psd_probe_end(psd_handle *h, int32_t epilogue, double *total_ms, int64_t *launches, double *work);
+int32_t psd_probe_read(psd_handle *h, int32_t epilogue, int32_t max_n, float *ms, int64_t *a, int64_t *b);
 int32_t psd_kernel_gemm_tile(int64_t M, int32_t Nout, int32_t epilogue);
 /* Number of tile configurations (valid tile ids are 0 .. count-1) and a static description of one. */
 int32_t psd_kernel_gemm_tile_count(void);

@@ -118,8 +118,10 @@ def load_library():
         "psd_forward_confidence_cached": (i32, [vp, vp, i32, i32, i32, i32, i32, vp, i32, vp, vp, vp, vp, i64, vp]),
         "psd_decode_block_cached": (i32, [vp, vp, i32, i32, i32, i32, C.POINTER(_Policy), C.POINTER(_Graph), C.POINTER(_Stats),
                                            vp, i32, vp, i64, vp]),
-        "psd_decode_block": (i32, [vp, vp, i32, i32, i32, i32, C.POINTER(_Policy), C.POINTER(_Graph), C.POINTER(_Stats),
+        "psd_decode_block": (i32, [vp, vp, i32, i32, C.POINTER(i32), i32, C.POINTER(_Policy), C.POINTER(_Graph), C.POINTER(_Stats),
                                    vp, i64, vp]),
+        "psd_decode": (i32, [vp, vp, i32, i32, C.POINTER(i32), i32, C.POINTER(_Policy), C.POINTER(_Graph), C.POINTER(_Stats),
+                             i32, C.POINTER(i32), vp, i64, vp]),
         "psd_forward_confidence_approx": (i32, [vp, vp, i32, i32, i32, i32, i32, i32, vp, i32, vp, vp, vp, vp, i64, vp]),
         "psd_decode_block_approx": (i32, [vp, vp, i32, i32, i32, i32, C.POINTER(_Policy), C.POINTER(_Graph), C.POINTER(_Stats),
                                           vp, i32, vp, i64, vp]),
@@ -137,6 +139,7 @@ def load_library():
         "psd_kernel_mfma_rate": (i32, [vp, i64, i32, vp, i64, C.POINTER(C.c_double), vp]),
         "psd_probe_begin": (i32, [vp, i32, i32, i32]),
         "psd_probe_end": (i32, [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
+        "psd_probe_read": (i32, [vp, i32, i32, C.POINTER(C.c_float), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]),
         "psd_kernel_gemm_tile": (i32, [i64, i32, i32]),
         "psd_kernel_gemm_tile_count": (i32, []),
         "psd_kernel_gemm_tile_name": (C.c_char_p, [i32]),
@@ -366,6 +369,13 @@ class Model:
         _check(self.lib.psd_probe_end(self.handle, epilogue, C.byref(ms), C.byref(n), C.byref(fl)))
         return ms.value, n.value, fl.value
 
+    def probe_read(self, epilogue: int, max_n: int = 1 << 16):
+        """Per timed launch of the last probe of this kind: (milliseconds, a, b) -- see psd_probe_read."""
+        ms, a, b = (C.c_float * max_n)(), (C.c_int64 * max_n)(), (C.c_int64 * max_n)()
+        n = self.lib.psd_probe_read(self.handle, epilogue, max_n, ms, a, b)
+        _check(n)
+        return [(float(ms[i]), int(a[i]), int(b[i])) for i in range(n)]
+
     def workspace(self, n_bytes: int) -> torch.Tensor:
         if self._ws is None or self._ws.numel() < n_bytes:
             self._ws = None
@@ -483,9 +493,18 @@ def _add_stats(stats, cstats, B) -> List[Stats]:
     return out
 
 
-def psd_decode_block(model: Model, tokens: torch.Tensor, block_start: int, L: int, policy: Policy, graph: Graph,
+def _starts(block_start, B: int):
+    """One block start for the whole batch, or one per sequence -> int32[B] for the C call."""
+    vals = [int(block_start)] * B if np.isscalar(block_start) else [int(v) for v in block_start]
+    if len(vals) != B:
+        raise PsdError(f"{len(vals)} block starts for a batch of {B}")
+    return (C.c_int32 * B)(*vals)
+
+
+def psd_decode_block(model: Model, tokens: torch.Tensor, block_start, L: int, policy: Policy, graph: Graph,
                      stats: Optional[Sequence[Stats]] = None) -> List[Stats]:
-    """Alg. 1 on one block of every sequence of tokens [B, N], in place.  Blocks until done."""
+    """Alg. 1 on one block of every sequence of tokens [B, N], in place; block_start is one position for the batch or one
+    per sequence.  Blocks until done."""
     B, N = tokens.shape
     K = graph.K
     extra = model.lib.psd_decode_scratch_bytes(B, N, L, K)
@@ -493,9 +512,28 @@ def psd_decode_block(model: Model, tokens: torch.Tensor, block_start: int, L: in
     ws, nb = model.forward_ws(B * K, N, L, extra=extra)
     cstats = (_Stats * B)()
     g, pol = graph.c(), policy.c()
-    _check(model.lib.psd_decode_block(model.handle, _ptr(tokens), B, N, block_start, L, C.byref(pol), C.byref(g), cstats,
-                                      _ptr(ws), nb, _stream()))
+    _check(model.lib.psd_decode_block(model.handle, _ptr(tokens), B, N, _starts(block_start, B), L, C.byref(pol), C.byref(g),
+                                      cstats, _ptr(ws), nb, _stream()))
     return _add_stats(stats, cstats, B)
+
+
+def psd_decode(model: Model, tokens: torch.Tensor, block_start, L: int, policy: Policy, graph: Graph,
+               stats: Optional[Sequence[Stats]] = None, max_iterations: int = 0):
+    """The whole generation behind one call: every sequence walks through its own blocks (see psd.h).  block_start as for
+    psd_decode_block.  Returns (stats, block starts on return, iterations run); with max_iterations > 0 the call returns
+    after that many iterations and can be continued from the returned block starts."""
+    B, N = tokens.shape
+    K = graph.K
+    extra = model.lib.psd_decode_scratch_bytes(B, N, L, K)
+    _check(extra)
+    ws, nb = model.forward_ws(B * K, N, L, extra=extra)
+    cstats = (_Stats * B)()
+    g, pol = graph.c(), policy.c()
+    starts = _starts(block_start, B)
+    done = C.c_int32(0)
+    _check(model.lib.psd_decode(model.handle, _ptr(tokens), B, N, starts, L, C.byref(pol), C.byref(g), cstats,
+                                int(max_iterations), C.byref(done), _ptr(ws), nb, _stream()))
+    return _add_stats(stats, cstats, B), [int(v) for v in starts], int(done.value)
 
 
 class KvCache:
@@ -606,50 +644,20 @@ def psd_calibrate_graph(model: Model, tokens: torch.Tensor, prompt_len: int, L: 
 
 
 def decode(model: Model, tokens: torch.Tensor, prompt_len: int, L: int, policy: Policy, graph: Graph) -> List[Stats]:
-    """Semi-autoregressive generation: psd_decode_block on each block, left to right.  With EOS early stopping
-    (policy.eos_id) a sequence that produced an EOS token is left out of the later blocks."""
+    """Semi-autoregressive generation of everything behind the prompt: one psd_decode call (every sequence walks through
+    its own blocks; with EOS early stopping a sequence ends with the block that produced the EOS token).  A generated
+    part that is not whole blocks is decoded block by block with a shorter last block."""
     B, N = tokens.shape
+    if (N - prompt_len) % L == 0:
+        return psd_decode(model, tokens, prompt_len, L, policy, graph)[0]
     stats = [Stats() for _ in range(B)]
     for block_start in range(prompt_len, N, L):
-        going = [b for b in range(B) if not stats[b].stopped]
-        if not going:
+        if all(s.stopped for s in stats):
             break
-        Lb = min(L, N - block_start)
-        if len(going) == B:
-            stats = psd_decode_block(model, tokens, block_start, Lb, policy, graph, stats)
-        else:
-            idx = torch.as_tensor(going, device=tokens.device)
-            part = tokens.index_select(0, idx).contiguous()
-            sub = psd_decode_block(model, part, block_start, Lb, policy, graph, [stats[b] for b in going])
-            tokens.index_copy_(0, idx, part)
-            for b, st in zip(going, sub):
-                stats[b] = st
+        if any(s.stopped for s in stats):
+            raise PsdError("a ragged last block after an EOS stop of part of the batch: decode those sequences separately")
+        stats = psd_decode_block(model, tokens, block_start, min(L, N - block_start), policy, graph, stats)
     return stats
-
-
-def debug_layer(model: Model, layer: int, hidden: torch.Tensor, S: int, N: int, L: int, stop_after: int = 0) -> dict:
-    """psd_debug_layer: one layer of the model on the caller's residual stream hidden fp32 [S*N, d_model] (in place).
-    Returns views of the intermediates the layer left in the workspace (valid until the next call on this model):
-    a [S*N, d], qkv [S*N, qkv_w] (rotary applied), o [S*N, H*dh], act [S*N, d_ffn] (stop_after = 0 only)."""
-    assert hidden.dtype == torch.float32 and hidden.is_contiguous() and hidden.shape == (S * N, model.shape.d_model)
-    ws, nb = model.forward_ws(S, N, L)
-    lay = _DebugLayout()
-    _check(model.lib.psd_debug_workspace_layout(C.byref(model.cfg), S, N, L, C.byref(lay)))
-    _check(model.lib.psd_debug_layer(model.handle, layer, _ptr(hidden), S, N, L, stop_after, _ptr(ws), nb, _stream()))
-    sh = model.shape
-    dt = torch.bfloat16 if sh.dtype == "bf16" else torch.float32
-    esz = 2 if sh.dtype == "bf16" else 4
-    T = S * N
-    qkv_w = (sh.n_heads + 2 * sh.n_kv_heads) * sh.d_head
-
-    def view(off, rows, ld, width):
-        return ws[off: off + rows * ld * esz].view(dt).view(rows, ld)[:, :width]
-
-    out = {"a": view(lay.off_a, T, sh.d_model, sh.d_model), "qkv": view(lay.off_qkv, T, lay.ld_qkv, qkv_w),
-           "o": view(lay.off_o, T, sh.n_heads * sh.d_head, sh.n_heads * sh.d_head)}
-    if stop_after == 0:
-        out["act"] = view(lay.off_act, T, lay.ld_act, sh.d_ffn)
-    return out
 
 
 # ------------------------------------------------------------------------------------------

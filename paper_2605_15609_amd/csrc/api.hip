@@ -19,16 +19,20 @@ void psd_set_error(const char *fmt, ...) {
 
 namespace {
 
-// masks of every sequence's block on entry: their number, and which positions (a 64-bit set in the counters)
-__global__ void count_masks_kernel(const int32_t *__restrict__ tokens, int N, int block_start, int L, int32_t mask_id,
-                                   int32_t *__restrict__ n_left, int32_t *__restrict__ devstats) {
+// A sequence enters a block: the number of masks in it, and which positions they are (a 64-bit set in the
+// sequence's counters).  only != NULL: just the sequences b with only[b] != 0.
+__global__ void count_masks_kernel(const int32_t *__restrict__ tokens, int N, BlockStart bs, int L, int32_t mask_id,
+                                   int32_t *__restrict__ n_left, int32_t *__restrict__ devstats,
+                                   const int32_t *__restrict__ only) {
     const int b = blockIdx.x, j = threadIdx.x;
-    const bool live = j < L && tokens[(int64_t)b * N + block_start + j] == mask_id;
+    if (only && only[b] == 0) return;
+    const bool live = j < L && tokens[(int64_t)b * N + bs.of_row(b) + j] == mask_id;
     const uint64_t set = __ballot(live);
     if (j == 0) {
         n_left[b] = __popcll(set);
         devstats[(int64_t)b * PSD_DEVSTAT_WORDS + PSD_DEVSTAT_ENTRY] = (int32_t)(uint32_t)set;
         devstats[(int64_t)b * PSD_DEVSTAT_WORDS + PSD_DEVSTAT_ENTRY + 1] = (int32_t)(uint32_t)(set >> 32);
+        devstats[(int64_t)b * PSD_DEVSTAT_WORDS + PSD_DEVSTAT_EOS] = 0;
     }
 }
 
@@ -88,7 +92,7 @@ int32_t check_policy(const psd_policy *p) {
     } while (0)
 
 struct DecodeScratch {
-    int64_t top1, conf, sigma, m, n_left, drafts, v_top1, v_conf, k_star, accepted, devstats, rows, total;
+    int64_t top1, conf, sigma, m, n_left, drafts, v_top1, v_conf, k_star, accepted, devstats, rows, starts, flags, total;
 };
 
 DecodeScratch plan_decode(int64_t B, int64_t N, int64_t L, int64_t K) {
@@ -111,6 +115,8 @@ DecodeScratch plan_decode(int64_t B, int64_t N, int64_t L, int64_t K) {
     s.accepted = take(B * K);
     s.devstats = take(B * PSD_DEVSTAT_WORDS * 4);
     s.rows = take(B * K * 4);
+    s.starts = take(B * 4);
+    s.flags = take(B * 4);
     s.total = off;
     return s;
 }
@@ -215,6 +221,7 @@ int32_t psd_destroy(psd_handle *h) {
     if (h->lm_head_packed) (void)hipFree(h->lm_head_packed);
     for (hipEvent_t e : h->probe.ev) (void)hipEventDestroy(e);
     for (hipEvent_t e : h->probe_head.ev) (void)hipEventDestroy(e);
+    for (hipEvent_t e : h->probe_call.ev) (void)hipEventDestroy(e);
     delete h;
     return PSD_OK;
 }
@@ -230,11 +237,15 @@ int32_t psd_debug_force_gemm_tile(int32_t tile) {
     return PSD_OK;
 }
 
+namespace {
+psd_handle::Probe &probe_of(psd_handle *h, int32_t kind) { return kind == 4 ? h->probe_head : kind == 5 ? h->probe_call : h->probe; }
+}   // namespace
+
 int32_t psd_probe_begin(psd_handle *h, int32_t epilogue, int32_t tile, int32_t max_launches) {
     if (!h) PSD_FAIL(PSD_ERR_INVALID_ARG, "handle is NULL");
-    if (epilogue < 0 || epilogue > 4 || tile < 0 || tile >= gemm_bf16_tile_count() || max_launches < 1 || max_launches > (1 << 20))
+    if (epilogue < 0 || epilogue > 5 || tile < 0 || tile >= gemm_bf16_tile_count() || max_launches < 1 || max_launches > (1 << 20))
         PSD_FAIL(PSD_ERR_INVALID_ARG, "bad probe arguments");
-    psd_handle::Probe &pr = epilogue == 4 ? h->probe_head : h->probe;
+    psd_handle::Probe &pr = probe_of(h, epilogue);
     while (pr.ev.size() < (size_t)max_launches * 2) {
         hipEvent_t e;
         PSD_HIP(hipEventCreate(&e));
@@ -245,12 +256,15 @@ int32_t psd_probe_begin(psd_handle *h, int32_t epilogue, int32_t tile, int32_t m
     pr.tile = tile;
     pr.used = 0;
     pr.flops = 0.0;
+    pr.a.clear();
+    pr.b.clear();
     return PSD_OK;
 }
 
 int32_t psd_probe_end(psd_handle *h, int32_t epilogue, double *total_ms, int64_t *launches, double *flops) {
     if (!h || !total_ms || !launches || !flops) PSD_FAIL(PSD_ERR_INVALID_ARG, "NULL argument");
-    psd_handle::Probe &pr = epilogue == 4 ? h->probe_head : h->probe;
+    if (epilogue < 0 || epilogue > 5) PSD_FAIL(PSD_ERR_INVALID_ARG, "probe kind %d", epilogue);
+    psd_handle::Probe &pr = probe_of(h, epilogue);
     pr.enabled = 0;
     double ms = 0.0;
     for (size_t i = 0; i + 1 < pr.used; i += 2) {
@@ -263,6 +277,22 @@ int32_t psd_probe_end(psd_handle *h, int32_t epilogue, double *total_ms, int64_t
     *launches = (int64_t)(pr.used / 2);
     *flops = pr.flops;
     return PSD_OK;
+}
+
+int32_t psd_probe_read(psd_handle *h, int32_t epilogue, int32_t max_n, float *ms, int64_t *a, int64_t *b) {
+    if (!h || !ms || !a || !b || max_n < 0) PSD_FAIL(PSD_ERR_INVALID_ARG, "bad arguments");
+    if (epilogue < 0 || epilogue > 5) PSD_FAIL(PSD_ERR_INVALID_ARG, "probe kind %d", epilogue);
+    psd_handle::Probe &pr = probe_of(h, epilogue);
+    if (pr.enabled) PSD_FAIL(PSD_ERR_INVALID_ARG, "the probe is still running: call psd_probe_end first");
+    const size_t n = std::min<size_t>(pr.used / 2, (size_t)max_n);
+    for (size_t i = 0; i < n; ++i) {
+        float t = 0.f;
+        PSD_HIP(hipEventElapsedTime(&t, pr.ev[2 * i], pr.ev[2 * i + 1]));
+        ms[i] = t;
+        a[i] = i < pr.a.size() ? pr.a[i] : 0;
+        b[i] = i < pr.b.size() ? pr.b[i] : 0;
+    }
+    return (int32_t)n;
 }
 
 int64_t psd_workspace_bytes(const psd_model_config *cfg, int32_t max_seqs, int32_t N, int32_t L) {
@@ -418,12 +448,26 @@ int32_t psd_verify_accept(psd_handle *h, int32_t *tokens, const int32_t *drafts,
 
 namespace {
 
-// Alg. 1 on one block.  kv = NULL: every model call runs over the whole sequences; otherwise over the block rows
-// against the sequences' KV caches (context-causal block attention), and the finished block is appended to them.
-int32_t decode_block_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_t block_start, int32_t L,
-                          const psd_policy *policy, const psd_graph *graph, psd_stats *stats, void *ws, int64_t ws_bytes,
-                          void *stream, const KvCacheArg *kv) {
-    CHECK(check_block(h, B, N, block_start, L));
+// Alg. 1 over B sequences, each on its own block (Alg. 1; App. B.1 for the outer loop over blocks and EOS stopping).
+// starts [B] (host, in/out): first position of every sequence's current block.  advance = false: every sequence
+// decodes that one block and is done; advance = true: a sequence whose block is resolved moves on to the next one
+// (start + L) in the following iteration, until the end of the sequence -- the semi-autoregressive outer loop.  An
+// iteration is one stage-1 call over all running sequences plus one batched verification call over those that still
+// have masks after the stage-1 commit.  max_iterations > 0 ends the call after that many iterations (starts then says
+// where every sequence stands).  kv != NULL: model calls on the block rows against the sequences' KV caches; all
+// sequences must then share one block and advance must be false.
+int32_t decode_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_t *starts, int32_t L, const psd_policy *policy,
+                    const psd_graph *graph, psd_stats *stats, bool advance, int32_t max_iterations, int32_t *iterations_done,
+                    void *ws, int64_t ws_bytes, void *stream, const KvCacheArg *kv) {
+    if (!h) PSD_FAIL(PSD_ERR_INVALID_ARG, "handle is NULL");
+    if (!starts) PSD_FAIL(PSD_ERR_INVALID_ARG, "block starts are NULL");
+    if (B < 1) PSD_FAIL(PSD_ERR_SHAPE, "batch %d", B);
+    for (int b = 0; b < B; ++b) {
+        if (advance && starts[b] >= N) continue;          // a sequence that is already at its end
+        CHECK(check_block(h, 1, N, starts[b], L));
+        if (kv && starts[b] != starts[0]) PSD_FAIL(PSD_ERR_UNSUPPORTED, "cached model calls need one block start for the whole batch");
+    }
+    if (kv && advance) PSD_FAIL(PSD_ERR_UNSUPPORTED, "cached model calls decode one block per call");
     GraphArg g;
     CHECK(check_graph(graph, &g));
     CHECK(check_policy(policy));
@@ -432,6 +476,7 @@ int32_t decode_block_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, 
         PSD_FAIL(PSD_ERR_INVALID_ARG, "eos_id %d: a token id below the vocabulary size %d other than the mask token",
                  policy->eos_id, h->cfg.vocab);
     if (!tokens || !stats) PSD_FAIL(PSD_ERR_INVALID_ARG, "NULL tokens/stats");
+    if (max_iterations < 0) PSD_FAIL(PSD_ERR_INVALID_ARG, "max_iterations %d", max_iterations);
     const int K = g.K;
     const bool dual = kv && kv->dual;  // approximate cache: the first model call runs over whole sequences and fills it
     const int plan_N = kv ? L : N;     // rows per sequence that a model call runs over
@@ -439,94 +484,192 @@ int32_t decode_block_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, 
     if (dual) fwd_bytes = std::max(fwd_bytes, plan_forward(h->cfg, B, N, L).total);
     const DecodeScratch sc = plan_decode(B, N, L, K);
     if (!ws || ws_bytes < fwd_bytes + sc.total)
-        PSD_FAIL(PSD_ERR_WORKSPACE, "workspace of %lld bytes, decoding the block needs %lld", (long long)ws_bytes,
+        PSD_FAIL(PSD_ERR_WORKSPACE, "workspace of %lld bytes, decoding needs %lld", (long long)ws_bytes,
                  (long long)(fwd_bytes + sc.total));
-    // one model call: forward + top-1 confidence of the sequences listed in `rows` (device) out of src [*, N]
-    bool refreshed = false;
-    auto model_call = [&](const int32_t *src, const int32_t *rows_dev, int S, int seqs_per_cache, int32_t *t1, float *cf,
-                          hipStream_t st_) -> int32_t {
-        if (dual && !refreshed) {   // the stage-1 call that enters the block: exact, and it freezes the context
-            refreshed = true;
-            CHECK(run_forward_hidden(h, src, rows_dev, S, N, block_start, L, ws, fwd_bytes, st_, kv));
-            return run_head_confidence(h, src, rows_dev, S, N, block_start, L, t1, cf, rows_dev, ws, st_, N);
-        }
-        if (kv) {
-            KvCacheArg a = *kv;
-            a.seqs_per_cache = seqs_per_cache;
-            a.append = false;
-            CHECK(run_forward_cached(h, src, rows_dev, S, N, block_start, L, a, ws, fwd_bytes, st_));
-        } else {
-            CHECK(run_forward_hidden(h, src, rows_dev, S, N, block_start, L, ws, fwd_bytes, st_));
-        }
-        return run_head_confidence(h, src, rows_dev, S, N, block_start, L, t1, cf, rows_dev, ws, st_, plan_N);
-    };
     if ((reinterpret_cast<uintptr_t>(ws) & 255) != 0) PSD_FAIL(PSD_ERR_WORKSPACE, "workspace must be 256-byte aligned");
-    if ((int64_t)B * (K + 2 + PSD_DEVSTAT_WORDS) > h->host_counts_cap) PSD_FAIL(PSD_ERR_SHAPE, "batch too large for the control buffer");
+    if ((int64_t)B * (K + 4 + PSD_DEVSTAT_WORDS) > h->host_counts_cap) PSD_FAIL(PSD_ERR_SHAPE, "batch too large for the control buffer");
     hipStream_t st = (hipStream_t)stream;
     char *base = (char *)ws + fwd_bytes;
     int32_t *top1 = (int32_t *)(base + sc.top1), *sigma = (int32_t *)(base + sc.sigma), *m = (int32_t *)(base + sc.m);
     int32_t *n_left = (int32_t *)(base + sc.n_left), *drafts = (int32_t *)(base + sc.drafts);
     int32_t *v_top1 = (int32_t *)(base + sc.v_top1), *k_star = (int32_t *)(base + sc.k_star);
     int32_t *devstats = (int32_t *)(base + sc.devstats), *rows = (int32_t *)(base + sc.rows);
+    int32_t *d_starts = (int32_t *)(base + sc.starts), *d_flags = (int32_t *)(base + sc.flags);
     float *conf = (float *)(base + sc.conf), *v_conf = (float *)(base + sc.v_conf);
     uint8_t *accepted = (uint8_t *)(base + sc.accepted);
-    int32_t *hc = h->host_counts;        // [0, B): counts read back; [B, B + B*K): row lists uploaded
-    int32_t *hrows = hc + B;
+    // pinned staging: [0, B) counts read back; [B, B + B*K) row lists; then block starts, flags, final counters
+    int32_t *hc = h->host_counts;
+    int32_t *hrows = hc + B, *hstarts = hrows + (int64_t)B * K, *hflags = hstarts + B, *hstats = hflags + B;
     const int32_t mask_id = h->cfg.mask_id;
+    // whole-sequence model calls take the block start of every sequence from the device array; the cached calls use the
+    // common one (their KV lengths and rotary positions are per call)
+    const BlockStart bs_seq = kv ? BlockStart(starts[0]) : BlockStart(d_starts, 1);
+    const BlockStart bs_draft = kv ? BlockStart(starts[0]) : BlockStart(d_starts, K);
+
+    // one model call: forward + top-1 confidence of the sequences listed in `rows` (device) out of src [*, N]
+    bool refreshed = false;
+    auto model_call_untimed = [&](const int32_t *src, const int32_t *rows_dev, int S, int seqs_per_cache, const BlockStart &bs,
+                                  int32_t *t1, float *cf, hipStream_t st_) -> int32_t {
+        if (dual && !refreshed) {   // the stage-1 call that enters the block: exact, and it freezes the context
+            refreshed = true;
+            CHECK(run_forward_hidden(h, src, rows_dev, S, N, bs, L, ws, fwd_bytes, st_, kv));
+            return run_head_confidence(h, src, rows_dev, S, N, bs, L, t1, cf, rows_dev, ws, st_, N);
+        }
+        if (kv) {
+            KvCacheArg a = *kv;
+            a.seqs_per_cache = seqs_per_cache;
+            a.append = false;
+            CHECK(run_forward_cached(h, src, rows_dev, S, N, bs.common, L, a, ws, fwd_bytes, st_));
+        } else {
+            CHECK(run_forward_hidden(h, src, rows_dev, S, N, bs, L, ws, fwd_bytes, st_));
+        }
+        return run_head_confidence(h, src, rows_dev, S, N, bs, L, t1, cf, rows_dev, ws, st_, plan_N);
+    };
+    // the same between two HIP events when model calls are being timed (psd_probe_begin kind 5)
+    auto model_call = [&](const int32_t *src, const int32_t *rows_dev, int S, int seqs_per_cache, const BlockStart &bs, int32_t *t1,
+                          float *cf, hipStream_t st_) -> int32_t {
+        psd_handle::Probe &pr = h->probe_call;
+        const bool timed = pr.enabled && pr.used + 2 <= pr.ev.size();
+        if (timed) (void)hipEventRecord(pr.ev[pr.used], st_);
+        const int32_t rc = model_call_untimed(src, rows_dev, S, seqs_per_cache, bs, t1, cf, st_);
+        if (timed) {
+            (void)hipEventRecord(pr.ev[pr.used + 1], st_);
+            pr.used += 2;
+            pr.note(S, seqs_per_cache);
+        }
+        return rc;
+    };
 
     {
         const int64_t n = (int64_t)B * PSD_DEVSTAT_WORDS;
         hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, devstats, n, 0);
     }
-    hipLaunchKernelGGL(count_masks_kernel, dim3(B), dim3(64), 0, st, tokens, N, block_start, L, mask_id, n_left, devstats);
-    PSD_HIP(hipMemcpyAsync(hc, n_left, sizeof(int32_t) * B, hipMemcpyDeviceToHost, st));
-    PSD_HIP(hipStreamSynchronize(st));
-    std::vector<int> active;
-    for (int b = 0; b < B; ++b)
-        if (hc[b] > 0) active.push_back(b);
+    enum { ENTER, RUN, DONE };
+    std::vector<int> state(B, ENTER);
     std::vector<int64_t> invocations(B, 0);
+    std::vector<int32_t> eos_pos(B, -1);
+    std::vector<char> stopped(B, 0);
+    for (int b = 0; b < B; ++b)
+        if (advance && starts[b] >= N) state[b] = DONE;
+    auto upload_starts = [&]() -> int32_t {
+        for (int b = 0; b < B; ++b) hstarts[b] = std::min(starts[b], N - L);    // a finished sequence keeps its last block
+        PSD_HIP(hipMemcpyAsync(d_starts, hstarts, sizeof(int32_t) * B, hipMemcpyHostToDevice, st));
+        return PSD_OK;
+    };
+    auto upload_flags = [&](auto pred) -> int32_t {
+        for (int b = 0; b < B; ++b) hflags[b] = pred(b) ? 1 : 0;
+        PSD_HIP(hipMemcpyAsync(d_flags, hflags, sizeof(int32_t) * B, hipMemcpyHostToDevice, st));
+        return PSD_OK;
+    };
+    // the sequences that leave their block: close its token count, then move on (or finish)
+    auto leave_blocks = [&](const std::vector<int> &who, std::vector<char> &stopped) -> int32_t {
+        if (who.empty()) return PSD_OK;
+        std::vector<char> mark(B, 0);
+        for (int b : who) mark[b] = 1;
+        CHECK(upload_flags([&](int b) { return mark[b] != 0; }));
+        launch_finish_counts(tokens, B, N, bs_seq, L, mask_id, policy->eos_stop, policy->eos_id, devstats, d_flags, st);
+        if (eos_stop) PSD_HIP(hipMemcpyAsync(hstats, devstats, sizeof(int32_t) * B * PSD_DEVSTAT_WORDS, hipMemcpyDeviceToHost, st));
+        // (the staging buffer may be rewritten by the next upload: the copy of the flags must have been consumed)
+        PSD_HIP(hipStreamSynchronize(st));
+        for (int b : who) {
+            // an EOS token in the block it leaves ends the sequence (App. B.1), whatever is still masked in it
+            const int32_t eos = eos_stop ? hstats[(int64_t)b * PSD_DEVSTAT_WORDS + PSD_DEVSTAT_EOS] : 0;
+            if (eos > 0) {
+                stopped[b] = 1;
+                eos_pos[b] = std::min(starts[b], N - L) + eos - 1;
+            }
+            if (stopped[b] || !advance) {
+                state[b] = DONE;
+                if (advance && !stopped[b]) starts[b] += L;
+            } else {
+                starts[b] += L;
+                state[b] = starts[b] + L <= N ? ENTER : DONE;
+            }
+        }
+        return PSD_OK;
+    };
 
-    // every model call commits at least one token of every sequence it runs (k_min >= 1), so a block of L positions
-    // is resolved after at most L iterations; anything beyond that means the model returned no usable predictions
-    int iterations = 0;
-    while (!active.empty()) {
-        if (++iterations > L + 1)
-            PSD_FAIL(PSD_ERR_DEVICE, "the block [%d, %d) is not resolved after %d iterations: the model calls make no progress "
-                     "(k_min = %d; non-finite logits?)", block_start, block_start + L, L + 1, policy->k_min);
-        // stage 1: one forward over the active sequences, policy commit, drafts
+    CHECK(upload_starts());
+    int iterations = 0, stalled = 0;
+    while (true) {
+        // sequences entering a block: count its masks; a block without masks is left at once
+        bool entering = false;
+        for (int b = 0; b < B; ++b) entering = entering || state[b] == ENTER;
+        while (entering) {
+            CHECK(upload_starts());
+            CHECK(upload_flags([&](int b) { return state[b] == ENTER; }));
+            hipLaunchKernelGGL(count_masks_kernel, dim3(B), dim3(64), 0, st, tokens, N, bs_seq, L, mask_id, n_left, devstats, d_flags);
+            PSD_HIP(hipMemcpyAsync(hc, n_left, sizeof(int32_t) * B, hipMemcpyDeviceToHost, st));
+            PSD_HIP(hipStreamSynchronize(st));
+            std::vector<int> empty;
+            for (int b = 0; b < B; ++b) {
+                if (state[b] != ENTER) continue;
+                if (hc[b] > 0) state[b] = RUN;
+                else empty.push_back(b);
+            }
+            CHECK(leave_blocks(empty, stopped));
+            entering = false;
+            for (int b = 0; b < B; ++b) entering = entering || state[b] == ENTER;
+        }
+        std::vector<int> active;
+        for (int b = 0; b < B; ++b)
+            if (state[b] == RUN) active.push_back(b);
+        if (active.empty()) break;
+        if (max_iterations > 0 && iterations >= max_iterations) break;
+        // every model call commits at least one token of every sequence it runs (k_min >= 1), so a block of L positions
+        // is resolved after at most L iterations; a batch in which no sequence leaves a block for longer has a model
+        // that returns no usable predictions
+        if (++stalled > L + 1)
+            PSD_FAIL(PSD_ERR_DEVICE, "no block resolved in %d iterations: the model calls make no progress (k_min = %d; non-finite "
+                     "logits?)", L + 1, policy->k_min);
+        ++iterations;
+        // stage 1: one forward over the running sequences, policy commit, drafts
         const int S1 = (int)active.size();
         for (int s = 0; s < S1; ++s) hrows[s] = active[s];
         PSD_HIP(hipMemcpyAsync(rows, hrows, sizeof(int32_t) * S1, hipMemcpyHostToDevice, st));
-        CHECK(model_call(tokens, rows, S1, 1, top1, conf, st));
+        CHECK(model_call(tokens, rows, S1, 1, bs_seq, top1, conf, st));
         for (int b : active) invocations[b] += 1;
-        launch_select_unmask(tokens, B, N, block_start, L, top1, conf, *policy, mask_id, nullptr, nullptr, n_left, devstats, st);
-        launch_build_drafts(tokens, B, N, block_start, L, top1, conf, g, mask_id, sigma, m, drafts, st);
-        if (eos_stop) launch_eos_stop(tokens, B, N, block_start, L, policy->eos_id, n_left, m, devstats, st);
+        launch_select_unmask(tokens, B, N, bs_seq, L, top1, conf, *policy, mask_id, nullptr, nullptr, n_left, devstats, st);
+        launch_build_drafts(tokens, B, N, bs_seq, L, top1, conf, g, mask_id, sigma, m, drafts, st);
+        if (eos_stop) launch_eos_stop(tokens, B, N, bs_seq, L, policy->eos_id, n_left, m, devstats, st);
         PSD_HIP(hipMemcpyAsync(hc, m, sizeof(int32_t) * B, hipMemcpyDeviceToHost, st));
         PSD_HIP(hipStreamSynchronize(st));
         std::vector<int> vset;
         for (int b : active)
             if (hc[b] > 0) vset.push_back(b);
-        if (vset.empty()) break;
-        // stage 3: one batched forward over the K drafts of every sequence that still has masks
-        const int S3 = (int)vset.size() * K;
-        for (size_t i = 0; i < vset.size(); ++i)
-            for (int k = 0; k < K; ++k) hrows[i * K + k] = vset[i] * K + k;
-        PSD_HIP(hipMemcpyAsync(rows, hrows, sizeof(int32_t) * S3, hipMemcpyHostToDevice, st));
-        CHECK(model_call(drafts, rows, S3, K, v_top1, v_conf, st));
-        for (int b : vset) invocations[b] += 1;
-        launch_accept(tokens, drafts, B, N, block_start, L, sigma, m, g, *policy, mask_id, v_top1, v_conf, k_star, accepted,
-                      n_left, devstats, st);
-        if (eos_stop) launch_eos_stop(tokens, B, N, block_start, L, policy->eos_id, n_left, nullptr, devstats, st);
+        if (!vset.empty()) {
+            // stage 3: one batched forward over the K drafts of every sequence that still has masks
+            const int S3 = (int)vset.size() * K;
+            for (size_t i = 0; i < vset.size(); ++i)
+                for (int k = 0; k < K; ++k) hrows[i * K + k] = vset[i] * K + k;
+            PSD_HIP(hipMemcpyAsync(rows, hrows, sizeof(int32_t) * S3, hipMemcpyHostToDevice, st));
+            CHECK(model_call(drafts, rows, S3, K, bs_draft, v_top1, v_conf, st));
+            for (int b : vset) invocations[b] += 1;
+            launch_accept(tokens, drafts, B, N, bs_seq, L, sigma, m, g, *policy, mask_id, v_top1, v_conf, k_star, accepted,
+                          n_left, devstats, st);
+            if (eos_stop) launch_eos_stop(tokens, B, N, bs_seq, L, policy->eos_id, n_left, nullptr, devstats, st);
+        }
+        // who is done with the block: no masks left, or stopped on an EOS token (its mask counts were zeroed)
         PSD_HIP(hipMemcpyAsync(hc, n_left, sizeof(int32_t) * B, hipMemcpyDeviceToHost, st));
         PSD_HIP(hipStreamSynchronize(st));
-        active.clear();
-        for (int b : vset)
-            if (hc[b] > 0) active.push_back(b);
+        std::vector<int> leaving;
+        for (int b : active)
+            if (hc[b] == 0) leaving.push_back(b);
+        if (!leaving.empty()) stalled = 0;
+        CHECK(leave_blocks(leaving, stopped));
     }
-
-    launch_finish_counts(tokens, B, N, block_start, L, mask_id, policy->eos_stop, policy->eos_id, devstats, st);
-    int32_t *hstats = hc + B + (int64_t)B * K;
+    // sequences still inside a block when the call ends (max_iterations): what they resolved so far counts for this call
+    {
+        std::vector<int> open;
+        for (int b = 0; b < B; ++b)
+            if (state[b] == RUN) open.push_back(b);
+        if (!open.empty()) {
+            std::vector<char> mark(B, 0);
+            for (int b : open) mark[b] = 1;
+            CHECK(upload_flags([&](int b) { return mark[b] != 0; }));
+            launch_finish_counts(tokens, B, N, bs_seq, L, mask_id, policy->eos_stop, policy->eos_id, devstats, d_flags, st);
+        }
+    }
     PSD_HIP(hipMemcpyAsync(hstats, devstats, sizeof(int32_t) * B * PSD_DEVSTAT_WORDS, hipMemcpyDeviceToHost, st));
     PSD_HIP(hipStreamSynchronize(st));
     for (int b = 0; b < B; ++b) {
@@ -536,20 +679,30 @@ int32_t decode_block_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, 
         stats[b].tokens_draft += ds[PSD_DEVSTAT_DRAFT];
         stats[b].tokens_postverify += ds[PSD_DEVSTAT_POST];
         stats[b].tokens_counted += ds[PSD_DEVSTAT_COUNTED];
-        if (ds[PSD_DEVSTAT_EOS] > 0) {
+        if (stopped[b]) {
             stats[b].stopped = 1;
-            stats[b].eos_pos = block_start + ds[PSD_DEVSTAT_EOS] - 1;
+            stats[b].eos_pos = eos_pos[b];
         }
         for (int i = 0; i <= PSD_MAX_BLOCK; ++i) stats[b].depth_hist[i] += ds[PSD_DEVSTAT_HIST + i];
     }
+    if (iterations_done) *iterations_done = iterations;
     if (kv && !dual) {   // the block is finished: its keys and values become context
         KvCacheArg a = *kv;
         a.seqs_per_cache = 1;
         a.append = true;
-        CHECK(run_forward_cached(h, tokens, nullptr, B, N, block_start, L, a, ws, fwd_bytes, st));
+        CHECK(run_forward_cached(h, tokens, nullptr, B, N, starts[0], L, a, ws, fwd_bytes, st));
     }
     PSD_HIP(hipGetLastError());
     return PSD_OK;
+}
+
+// one block, the same for every sequence of the batch (the cached model calls)
+int32_t decode_block_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_t block_start, int32_t L,
+                          const psd_policy *policy, const psd_graph *graph, psd_stats *stats, void *ws, int64_t ws_bytes,
+                          void *stream, const KvCacheArg *kv) {
+    if (B < 1) PSD_FAIL(PSD_ERR_SHAPE, "batch %d", B);
+    std::vector<int32_t> starts(B, block_start);
+    return decode_impl(h, tokens, B, N, starts.data(), L, policy, graph, stats, false, 0, nullptr, ws, ws_bytes, stream, kv);
 }
 
 int32_t check_kv(const psd_handle *h, const void *cache, int32_t capacity, int32_t block_start, int32_t L) {
@@ -582,10 +735,26 @@ int32_t check_kv_approx(const psd_handle *h, const void *cache, int32_t capacity
 
 }   // namespace
 
-int32_t psd_decode_block(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_t block_start, int32_t L,
+int32_t psd_decode_block(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, const int32_t *block_start, int32_t L,
                          const psd_policy *policy, const psd_graph *graph, psd_stats *stats, void *ws, int64_t ws_bytes,
                          void *stream) {
-    return decode_block_impl(h, tokens, B, N, block_start, L, policy, graph, stats, ws, ws_bytes, stream, nullptr);
+    if (!block_start) PSD_FAIL(PSD_ERR_INVALID_ARG, "block_start is NULL");
+    if (B < 1) PSD_FAIL(PSD_ERR_SHAPE, "batch %d", B);
+    std::vector<int32_t> starts(block_start, block_start + B);
+    return decode_impl(h, tokens, B, N, starts.data(), L, policy, graph, stats, false, 0, nullptr, ws, ws_bytes, stream, nullptr);
+}
+
+int32_t psd_decode(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_t *block_start, int32_t L, const psd_policy *policy,
+                   const psd_graph *graph, psd_stats *stats, int32_t max_iterations, int32_t *iterations_done, void *ws,
+                   int64_t ws_bytes, void *stream) {
+    if (!block_start) PSD_FAIL(PSD_ERR_INVALID_ARG, "block_start is NULL");
+    if (!h) PSD_FAIL(PSD_ERR_INVALID_ARG, "handle is NULL");
+    for (int b = 0; b < B; ++b)
+        if (block_start[b] < N && (N - block_start[b]) % L)
+            PSD_FAIL(PSD_ERR_SHAPE, "sequence %d: the %d positions from its block start %d on are not whole blocks of %d", b,
+                     N - block_start[b], block_start[b], L);
+    return decode_impl(h, tokens, B, N, block_start, L, policy, graph, stats, true, max_iterations, iterations_done, ws, ws_bytes,
+                       stream, nullptr);
 }
 
 // ---- context-causal block attention with an exact prefix KV cache ----
@@ -741,7 +910,8 @@ int32_t psd_calibrate_graph(psd_handle *h, const int32_t *tokens, int32_t *work_
         for (int start = n_prompt; start < N && rc == PSD_OK; start += L)
             rc = cache ? psd_decode_block_cached(h, work_tokens, B, N, start, L, &pol, candidates + c, stats.data(), cache, capacity,
                                                  ws, ws_bytes, stream)
-                       : psd_decode_block(h, work_tokens, B, N, start, L, &pol, candidates + c, stats.data(), ws, ws_bytes, stream);
+                       : decode_block_impl(h, work_tokens, B, N, start, L, &pol, candidates + c, stats.data(), ws, ws_bytes, stream,
+                                           nullptr);
         if (rc != PSD_OK) break;
         (void)hipEventRecord(e1, st);
         float ms = 0.f;

@@ -35,7 +35,7 @@ __device__ __forceinline__ bool policy_commits(bool live, int rank, float c, con
 }
 
 // ------------------------------------------------------------------ stage 1 commit (Eq. 1)
-__global__ __launch_bounds__(WAVE) void select_unmask_kernel(int32_t *__restrict__ tokens, int N, int block_start, int L,
+__global__ __launch_bounds__(WAVE) void select_unmask_kernel(int32_t *__restrict__ tokens, int N, BlockStart bs, int L,
                                                              const int32_t *__restrict__ top1,
                                                              const float *__restrict__ conf, psd_policy policy,
                                                              int32_t mask_id, uint8_t *__restrict__ transfer_mask,
@@ -44,6 +44,7 @@ __global__ __launch_bounds__(WAVE) void select_unmask_kernel(int32_t *__restrict
                                                              int32_t *__restrict__ devstats) {
     const int b = blockIdx.x;
     const int j = threadIdx.x;
+    const int block_start = bs.of_row(b);
     int32_t *row = tokens + (int64_t)b * N + block_start;
     const bool in = j < L;
     // a sequence that stopped on an EOS token keeps its masks: its predictions are stale, nothing is committed
@@ -66,7 +67,7 @@ __global__ __launch_bounds__(WAVE) void select_unmask_kernel(int32_t *__restrict
 // ------------------------------------------------------------------ stage 2 drafts (Eq. 2)
 // grid (K, B): every (sequence, node) pair recomputes the ranking (64 shuffles) and writes
 // its own draft row with coalesced 4-byte stores.
-__global__ __launch_bounds__(WAVE) void build_drafts_kernel(const int32_t *__restrict__ tokens, int N, int block_start,
+__global__ __launch_bounds__(WAVE) void build_drafts_kernel(const int32_t *__restrict__ tokens, int N, BlockStart bs,
                                                             int L, const int32_t *__restrict__ top1,
                                                             const float *__restrict__ conf, GraphArg g, int32_t mask_id,
                                                             int32_t *__restrict__ sigma, int32_t *__restrict__ m_out,
@@ -74,6 +75,7 @@ __global__ __launch_bounds__(WAVE) void build_drafts_kernel(const int32_t *__res
     const int k = blockIdx.x;
     const int b = blockIdx.y;
     const int j = threadIdx.x;
+    const int block_start = bs.of_row(b);
     const int32_t *row = tokens + (int64_t)b * N;
     int32_t *out = drafts + ((int64_t)b * g.K + k) * N;
     const bool in = j < L;
@@ -100,7 +102,7 @@ __global__ __launch_bounds__(WAVE) void build_drafts_kernel(const int32_t *__res
 
 // ------------------------------------------------------------------ stage 3 acceptance + advance
 __global__ __launch_bounds__(WAVE) void accept_kernel(int32_t *__restrict__ tokens, const int32_t *__restrict__ drafts,
-                                                      int N, int block_start, int L, const int32_t *__restrict__ sigma,
+                                                      int N, BlockStart bs, int L, const int32_t *__restrict__ sigma,
                                                       const int32_t *__restrict__ m_in, GraphArg g, psd_policy policy,
                                                       int32_t mask_id, const int32_t *__restrict__ v_top1,
                                                       const float *__restrict__ v_conf, int32_t *__restrict__ k_star_out,
@@ -115,6 +117,7 @@ __global__ __launch_bounds__(WAVE) void accept_kernel(int32_t *__restrict__ toke
 
     const int b = blockIdx.x;
     const int j = threadIdx.x;
+    const int block_start = bs.of_row(b);
     const int K = g.K;
     const int m = m_in[b];
     const bool in = j < L;
@@ -222,10 +225,11 @@ __global__ __launch_bounds__(WAVE) void accept_kernel(int32_t *__restrict__ toke
 // After a state update: a sequence whose block holds the EOS token is finished, whatever is still masked.
 // Its mask counts are zeroed, which is what takes it out of the following model calls, and the position is
 // flagged in its counters, which is what keeps the stage-1 commit from touching it again.
-__global__ __launch_bounds__(WAVE) void eos_stop_kernel(const int32_t *__restrict__ tokens, int N, int block_start, int L,
+__global__ __launch_bounds__(WAVE) void eos_stop_kernel(const int32_t *__restrict__ tokens, int N, BlockStart bs, int L,
                                                         int32_t eos_id, int32_t *__restrict__ n_left,
                                                         int32_t *__restrict__ m, int32_t *__restrict__ devstats) {
     const int b = blockIdx.x, j = threadIdx.x;
+    const int block_start = bs.of_row(b);
     const bool hit = j < L && tokens[(int64_t)b * N + block_start + j] == eos_id;
     const uint64_t hits = __ballot(hit);
     if (hits != 0ull && j == 0) {
@@ -235,13 +239,16 @@ __global__ __launch_bounds__(WAVE) void eos_stop_kernel(const int32_t *__restric
     }
 }
 
-// End of the block loop: the first EOS position of the block (when stopping on EOS is on) and the number of
-// positions resolved by this call at or before it -- all resolved positions without an EOS.  The positions
-// masked on entry are in the sequence's counters as a 64-bit set.
-__global__ __launch_bounds__(WAVE) void finish_counts_kernel(const int32_t *__restrict__ tokens, int N, int block_start, int L,
+// A sequence leaves its block (resolved, stopped on an EOS token, or the call ends): the first EOS position of the
+// block (when stopping on EOS is on) and the number of positions resolved since the block was entered at or before
+// it -- all resolved positions without an EOS -- are added to the sequence's counters.  The positions masked on
+// entry are in the counters as a 64-bit set.  only != NULL: just the sequences b with only[b] != 0.
+__global__ __launch_bounds__(WAVE) void finish_counts_kernel(const int32_t *__restrict__ tokens, int N, BlockStart bs, int L,
                                                              int32_t mask_id, int32_t eos_stop, int32_t eos_id,
-                                                             int32_t *__restrict__ devstats) {
+                                                             int32_t *__restrict__ devstats, const int32_t *__restrict__ only) {
     const int b = blockIdx.x, j = threadIdx.x;
+    if (only && only[b] == 0) return;
+    const int block_start = bs.of_row(b);
     const int32_t tok = j < L ? tokens[(int64_t)b * N + block_start + j] : mask_id;
     const uint64_t hits = __ballot(eos_stop && j < L && tok == eos_id);
     const uint64_t resolved = __ballot(j < L && tok != mask_id);
@@ -252,38 +259,38 @@ __global__ __launch_bounds__(WAVE) void finish_counts_kernel(const int32_t *__re
         const uint64_t upto = limit >= 63 ? ~0ull : ((1ull << (limit + 1)) - 1ull);
         const uint64_t entry = (uint64_t)(uint32_t)ds[PSD_DEVSTAT_ENTRY] | ((uint64_t)(uint32_t)ds[PSD_DEVSTAT_ENTRY + 1] << 32);
         ds[PSD_DEVSTAT_EOS] = eos + 1;
-        ds[PSD_DEVSTAT_COUNTED] = __popcll(entry & resolved & upto);
+        ds[PSD_DEVSTAT_COUNTED] += __popcll(entry & resolved & upto);
     }
 }
 
 }   // namespace
 
-void launch_eos_stop(const int32_t *tokens, int B, int N, int block_start, int L, int32_t eos_id, int32_t *n_left, int32_t *m,
+void launch_eos_stop(const int32_t *tokens, int B, int N, BlockStart block_start, int L, int32_t eos_id, int32_t *n_left, int32_t *m,
                      int32_t *devstats, hipStream_t st) {
     hipLaunchKernelGGL(eos_stop_kernel, dim3(B), dim3(WAVE), 0, st, tokens, N, block_start, L, eos_id, n_left, m, devstats);
 }
 
-void launch_finish_counts(const int32_t *tokens, int B, int N, int block_start, int L, int32_t mask_id, int32_t eos_stop,
-                          int32_t eos_id, int32_t *devstats, hipStream_t st) {
+void launch_finish_counts(const int32_t *tokens, int B, int N, BlockStart block_start, int L, int32_t mask_id, int32_t eos_stop,
+                          int32_t eos_id, int32_t *devstats, const int32_t *only, hipStream_t st) {
     hipLaunchKernelGGL(finish_counts_kernel, dim3(B), dim3(WAVE), 0, st, tokens, N, block_start, L, mask_id, eos_stop, eos_id,
-                       devstats);
+                       devstats, only);
 }
 
-void launch_select_unmask(int32_t *tokens, int B, int N, int block_start, int L, const int32_t *top1, const float *conf,
+void launch_select_unmask(int32_t *tokens, int B, int N, BlockStart block_start, int L, const int32_t *top1, const float *conf,
                           psd_policy policy, int32_t mask_id, uint8_t *transfer_mask, int32_t *n_selected,
                           int32_t *n_left, int32_t *devstats, hipStream_t st) {
     hipLaunchKernelGGL(select_unmask_kernel, dim3(B), dim3(WAVE), 0, st, tokens, N, block_start, L, top1, conf, policy,
                        mask_id, transfer_mask, n_selected, n_left, devstats);
 }
 
-void launch_build_drafts(const int32_t *tokens, int B, int N, int block_start, int L, const int32_t *top1,
+void launch_build_drafts(const int32_t *tokens, int B, int N, BlockStart block_start, int L, const int32_t *top1,
                          const float *conf, const GraphArg &g, int32_t mask_id, int32_t *sigma, int32_t *m,
                          int32_t *drafts, hipStream_t st) {
     hipLaunchKernelGGL(build_drafts_kernel, dim3(g.K, B), dim3(WAVE), 0, st, tokens, N, block_start, L, top1, conf, g,
                        mask_id, sigma, m, drafts);
 }
 
-void launch_accept(int32_t *tokens, const int32_t *drafts, int B, int N, int block_start, int L, const int32_t *sigma,
+void launch_accept(int32_t *tokens, const int32_t *drafts, int B, int N, BlockStart block_start, int L, const int32_t *sigma,
                    const int32_t *m, const GraphArg &g, psd_policy policy, int32_t mask_id, const int32_t *v_top1,
                    const float *v_conf, int32_t *k_star, uint8_t *accepted, int32_t *n_left, int32_t *devstats,
                    hipStream_t st) {

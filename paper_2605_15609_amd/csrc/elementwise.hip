@@ -39,12 +39,13 @@ __device__ __forceinline__ float block_sum(float v, float *smem) {
 // h is brought up to date.
 template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ h, int d, const float *__restrict__ gain,
-                                                      float eps, T *__restrict__ out, int N, int block_start, int L,
-                                                      T *__restrict__ packed, PendingSums pend) {
+                                                      float eps, T *__restrict__ out, int N, BlockStart block_start, int L,
+                                                      T *__restrict__ packed, PendingSums pend,
+                                                      const int32_t *__restrict__ seq_rows) {
     __shared__ float smem[4];
     const int64_t r = blockIdx.x;
     int64_t src = r;
-    if (L > 0) src = (r / L) * N + block_start + (r % L);
+    if (L > 0) src = (r / L) * N + block_start.of_row(seq_rows ? seq_rows[r / L] : r / L) + (r % L);
     float *x = h + src * d;
     float ss = 0.f;
     for (int c = threadIdx.x; c < d; c += blockDim.x) {
@@ -72,10 +73,11 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ h, int
 // packed: second copy in MFMA-fragment order (a thread's 8 values are one 16-byte operand slot there too)
 __global__ __launch_bounds__(256) void rmsnorm_bf16_vec_kernel(float *__restrict__ h, int d, const float *__restrict__ gain,
                                                                float eps, bf16_t *__restrict__ out, PendingSums pend, int N,
-                                                               int block_start, int L, bf16_t *__restrict__ packed) {
+                                                               BlockStart block_start, int L, bf16_t *__restrict__ packed,
+                                                               const int32_t *__restrict__ seq_rows) {
     __shared__ float smem[4];
     const int64_t r_out = blockIdx.x;
-    const int64_t r = L > 0 ? (r_out / L) * N + block_start + (r_out % L) : r_out;
+    const int64_t r = L > 0 ? (r_out / L) * N + block_start.of_row(seq_rows ? seq_rows[r_out / L] : r_out / L) + (r_out % L) : r_out;
     float4 *x = reinterpret_cast<float4 *>(h + r * d);
     const float4 *g = reinterpret_cast<const float4 *>(gain);
     constexpr int MAXV = 4;                 // 8 floats per chunk, up to 4 chunks per thread: d <= 8192
@@ -169,20 +171,23 @@ namespace {
 // dst[r, :] = src[(r / L) * N + block_start + r % L, :]: the block rows of every sequence, packed
 template <typename T>
 __global__ __launch_bounds__(256) void gather_block_rows_kernel(const T *__restrict__ src, T *__restrict__ dst, int width, int N,
-                                                                int block_start, int L) {
+                                                                BlockStart block_start, int L,
+                                                                const int32_t *__restrict__ seq_rows) {
     const int64_t r = blockIdx.x;
-    const T *s = src + ((r / L) * N + block_start + (r % L)) * width;
+    const T *s = src + ((r / L) * N + block_start.of_row(seq_rows ? seq_rows[r / L] : r / L) + (r % L)) * width;
     T *d = dst + r * width;
     for (int c = threadIdx.x; c < width; c += blockDim.x) d[c] = s[c];
 }
 }   // namespace
 
 template <typename T>
-void launch_gather_block_rows(const T *src, T *dst, int width, int S, int N, int block_start, int L, hipStream_t st) {
-    hipLaunchKernelGGL(gather_block_rows_kernel<T>, dim3((unsigned)(S * L)), dim3(256), 0, st, src, dst, width, N, block_start, L);
+void launch_gather_block_rows(const T *src, T *dst, int width, const int32_t *seq_rows, int S, int N, BlockStart block_start, int L,
+                              hipStream_t st) {
+    hipLaunchKernelGGL(gather_block_rows_kernel<T>, dim3((unsigned)(S * L)), dim3(256), 0, st, src, dst, width, N, block_start, L,
+                       seq_rows);
 }
-template void launch_gather_block_rows<float>(const float *, float *, int, int, int, int, int, hipStream_t);
-template void launch_gather_block_rows<bf16_t>(const bf16_t *, bf16_t *, int, int, int, int, int, hipStream_t);
+template void launch_gather_block_rows<float>(const float *, float *, int, const int32_t *, int, int, BlockStart, int, hipStream_t);
+template void launch_gather_block_rows<bf16_t>(const bf16_t *, bf16_t *, int, const int32_t *, int, int, BlockStart, int, hipStream_t);
 
 template <typename T>
 void launch_embed(const int32_t *tokens, const int32_t *seq_rows, int S, int N, const T *emb, int vocab, int d, float *h,
@@ -231,34 +236,34 @@ template void launch_kv_store<bf16_t>(const bf16_t *, int, int, int, int, int, i
                                       hipStream_t);
 template <typename T>
 void launch_rmsnorm(float *h, int64_t rows, int d, const float *gain, float eps, T *out, PendingSums pend, hipStream_t st) {
-    hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out, 0, 0, 0, (T *)nullptr,
-                       pend);
+    hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out, 0, BlockStart(), 0, (T *)nullptr,
+                       pend, (const int32_t *)nullptr);
 }
 template <>
 void launch_rmsnorm<bf16_t>(float *h, int64_t rows, int d, const float *gain, float eps, bf16_t *out, PendingSums pend,
                             hipStream_t st) {
     if (d % 8 == 0 && d <= 8192)
-        hipLaunchKernelGGL(rmsnorm_bf16_vec_kernel, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out, pend, 0, 0, 0,
-                           (bf16_t *)nullptr);
+        hipLaunchKernelGGL(rmsnorm_bf16_vec_kernel, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out, pend, 0, BlockStart(), 0,
+                           (bf16_t *)nullptr, (const int32_t *)nullptr);
     else
-        hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out, 0, 0, 0,
-                           (bf16_t *)nullptr, pend);
+        hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3((unsigned)rows), dim3(256), 0, st, h, d, gain, eps, out, 0, BlockStart(), 0,
+                           (bf16_t *)nullptr, pend, (const int32_t *)nullptr);
 }
 template <typename T>
-void launch_rmsnorm_block(float *h, int S, int N, int block_start, int L, int d, const float *gain, float eps,
-                          T *out, T *packed, PendingSums pend, hipStream_t st) {
+void launch_rmsnorm_block(float *h, const int32_t *seq_rows, int S, int N, BlockStart block_start, int L, int d, const float *gain,
+                          float eps, T *out, T *packed, PendingSums pend, hipStream_t st) {
     hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3((unsigned)(S * L)), dim3(256), 0, st, h, d, gain, eps, out, N, block_start, L,
-                       packed, pend);
+                       packed, pend, seq_rows);
 }
 template <>
-void launch_rmsnorm_block<bf16_t>(float *h, int S, int N, int block_start, int L, int d, const float *gain, float eps,
-                                  bf16_t *out, bf16_t *packed, PendingSums pend, hipStream_t st) {
+void launch_rmsnorm_block<bf16_t>(float *h, const int32_t *seq_rows, int S, int N, BlockStart block_start, int L, int d,
+                                  const float *gain, float eps, bf16_t *out, bf16_t *packed, PendingSums pend, hipStream_t st) {
     if (d % 16 == 0 && d <= 8192)
         hipLaunchKernelGGL(rmsnorm_bf16_vec_kernel, dim3((unsigned)(S * L)), dim3(256), 0, st, h, d, gain, eps, out, pend, N,
-                           block_start, L, packed);
+                           block_start, L, packed, seq_rows);
     else
         hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3((unsigned)(S * L)), dim3(256), 0, st, h, d, gain, eps, out, N, block_start,
-                           L, packed, pend);
+                           L, packed, pend, seq_rows);
 }
 
 namespace {
@@ -298,7 +303,7 @@ void launch_rope<bf16_t>(bf16_t *qkv, int ld, int64_t tokens, int N, int pos0, i
 #define INSTANTIATE(T)                                                                                              \
     template void launch_embed<T>(const int32_t *, const int32_t *, int, int, const T *, int, int, float *, hipStream_t); \
     template void launch_rmsnorm<T>(float *, int64_t, int, const float *, float, T *, PendingSums, hipStream_t);    \
-    template void launch_rmsnorm_block<T>(float *, int, int, int, int, int, const float *, float, T *, T *,         \
+    template void launch_rmsnorm_block<T>(float *, const int32_t *, int, int, BlockStart, int, int, const float *, float, T *, T *, \
                                           PendingSums, hipStream_t);                                                \
     template void launch_rope<T>(T *, int, int64_t, int, int, int, int, int, const float *, const float *, hipStream_t);      \
     template void launch_embed_block<T>(const int32_t *, const int32_t *, int, int, int, int, const T *, int, int, float *, \

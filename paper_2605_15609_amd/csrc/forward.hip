@@ -94,6 +94,7 @@ struct Dispatch<bf16_t> {
                 (void)hipEventRecord(pr.ev[pr.used + 1], st);
                 pr.used += 2;
                 pr.flops += 2.0 * (double)M * Nout * Kin * (epi == EPI_SWIGLU ? 2.0 : 1.0);
+                pr.note(M, Nout);
             }
         }
         return pend;
@@ -115,7 +116,7 @@ struct Dispatch<bf16_t> {
 };
 
 template <typename T>
-int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N, int block_start,
+int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N, BlockStart block_start,
                             int L, char *ws, hipStream_t st, const KvCacheArg *store) {
     const psd_model_config &c = h->cfg;
     const ForwardPlan p = plan_forward(c, S, N, L);
@@ -161,9 +162,10 @@ int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t 
             at.stride_k = at.stride_vt = lay.per_seq;
             at.seq_rows = seq_rows;
             at.len = 0;
-            launch_kv_store<T>(qkv, ld_qkv, S, N, 0, block_start, H, Hkv, dh, k_cache, vt_cache, at, st);
-            at.len = block_start;
-            launch_kv_store<T>(qkv, ld_qkv, S, N, block_start + L, N - block_start - L, H, Hkv, dh, k_cache, vt_cache, at, st);
+            const int b0 = block_start.common;     // (a common block start: checked by run_forward_hidden)
+            launch_kv_store<T>(qkv, ld_qkv, S, N, 0, b0, H, Hkv, dh, k_cache, vt_cache, at, st);
+            at.len = b0;
+            launch_kv_store<T>(qkv, ld_qkv, S, N, b0 + L, N - b0 - L, H, Hkv, dh, k_cache, vt_cache, at, st);
         }
         // After the last attention only the block rows feed the LM-head: the rest of that layer (output
         // projection, FFN) and the final norm run on those S*L rows alone, gathered into a packed stream.
@@ -174,8 +176,8 @@ int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t 
             hs = (float *)(ws + p.off_hc);
             os = (T *)(ws + p.off_oc);
             nrow = (int64_t)S * L;
-            launch_gather_block_rows<float>(hbuf, hs, d, S, N, block_start, L, st);
-            launch_gather_block_rows<T>(o, os, H * dh, S, N, block_start, L, st);
+            launch_gather_block_rows<float>(hbuf, hs, d, seq_rows, S, N, block_start, L, st);
+            launch_gather_block_rows<T>(o, os, H * dh, seq_rows, S, N, block_start, L, st);
             final_in = hs;
         }
         pend = Dispatch<T>::gemm(h, os, H * dh, lw.wo, nullptr, H * dh, nrow, d, H * dh, EPI_RESIDUAL, nullptr, nullptr, hs, d, ksplit, st);
@@ -185,9 +187,9 @@ int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t 
     }
     T *ypack = (c.dtype == PSD_DTYPE_BF16 && h->lm_head_packed && head_stream_supported(S * L, d)) ? (T *)(ws + p.off_ypack) : nullptr;
     if (final_in != hbuf)   // already the packed block rows
-        launch_rmsnorm_block<T>(final_in, S, L, 0, L, d, h->final_norm, c.rms_eps, y, ypack, pend, st);
+        launch_rmsnorm_block<T>(final_in, nullptr, S, L, 0, L, d, h->final_norm, c.rms_eps, y, ypack, pend, st);
     else
-        launch_rmsnorm_block<T>(hbuf, S, N, block_start, L, d, h->final_norm, c.rms_eps, y, ypack, pend, st);
+        launch_rmsnorm_block<T>(hbuf, seq_rows, S, N, block_start, L, d, h->final_norm, c.rms_eps, y, ypack, pend, st);
     return PSD_OK;
 }
 
@@ -244,7 +246,7 @@ int32_t forward_cached_impl(psd_handle *h, const int32_t *tokens, const int32_t 
         pend = Dispatch<T>::gemm(h, act, ld_act, lw.w_down, nullptr, h->w_down_stride, nrow, d, F, EPI_RESIDUAL, nullptr, nullptr, hbuf, d, ksplit, st);
     }
     T *ypack = (c.dtype == PSD_DTYPE_BF16 && h->lm_head_packed && head_stream_supported(S * L, d)) ? (T *)(ws + p.off_ypack) : nullptr;
-    launch_rmsnorm_block<T>(hbuf, S, L, 0, L, d, h->final_norm, c.rms_eps, y, ypack, pend, st);
+    launch_rmsnorm_block<T>(hbuf, nullptr, S, L, 0, L, d, h->final_norm, c.rms_eps, y, ypack, pend, st);
     return PSD_OK;
 }
 
@@ -317,7 +319,7 @@ int32_t run_forward_cached(psd_handle *h, const int32_t *tokens, const int32_t *
     return PSD_OK;
 }
 
-int32_t run_forward_hidden(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N, int block_start,
+int32_t run_forward_hidden(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N, BlockStart block_start,
                            int L, void *ws, int64_t ws_bytes, hipStream_t st, const KvCacheArg *store) {
     const ForwardPlan p = plan_forward(h->cfg, S, N, L);
     if (ws == nullptr || ws_bytes < p.total)
@@ -326,6 +328,7 @@ int32_t run_forward_hidden(psd_handle *h, const int32_t *tokens, const int32_t *
     if ((reinterpret_cast<uintptr_t>(ws) & 255) != 0) PSD_FAIL(PSD_ERR_WORKSPACE, "workspace must be 256-byte aligned");
     if (store && (!store->base || !store->dual || store->capacity < N - L))
         PSD_FAIL(PSD_ERR_SHAPE, "storing the keys and values outside the block needs a cache of %d positions", N - L);
+    if (store && block_start.per_seq) PSD_FAIL(PSD_ERR_UNSUPPORTED, "the approximate cache needs one block start for the whole batch");
     int32_t rc;
     if (h->cfg.dtype == PSD_DTYPE_BF16)
         rc = forward_hidden_impl<bf16_t>(h, tokens, seq_rows, S, N, block_start, L, (char *)ws, st, store);
@@ -336,7 +339,7 @@ int32_t run_forward_hidden(psd_handle *h, const int32_t *tokens, const int32_t *
     return PSD_OK;
 }
 
-int32_t run_head_confidence(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N, int block_start,
+int32_t run_head_confidence(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N, BlockStart block_start,
                             int L, int32_t *top1, float *conf, const int32_t *out_rows, void *ws_, hipStream_t st, int plan_N) {
     const psd_model_config &c = h->cfg;
     const ForwardPlan p = plan_forward(c, S, plan_N > 0 ? plan_N : N, L);
@@ -351,14 +354,16 @@ int32_t run_head_confidence(psd_handle *h, const int32_t *tokens, const int32_t 
         bool on;
         hipStream_t st;
         double bytes;
+        int64_t rows;
         ~StopOnExit() {
             if (!on) return;
             (void)hipEventRecord(pr.ev[pr.used + 1], st);
             pr.used += 2;
             pr.flops += bytes;
+            pr.note(rows, 0);
         }
     } stop{pr, timed, st, (double)c.vocab * c.d_model * (c.dtype == PSD_DTYPE_BF16 ? 2.0 : 4.0) +
-                              (double)rows * c.d_model * (c.dtype == PSD_DTYPE_BF16 ? 2.0 : 4.0) + rows * 8.0};
+                              (double)rows * c.d_model * (c.dtype == PSD_DTYPE_BF16 ? 2.0 : 4.0) + rows * 8.0, rows};
     if (timed) (void)hipEventRecord(pr.ev[pr.used], st);
     if (c.dtype == PSD_DTYPE_BF16 && !(h->plain_mask & 4) && h->lm_head_packed && head_stream_supported(rows, c.d_model)) {
         // y was already written in fragment order by the final norm; the merge writes (top1, conf) directly

@@ -208,7 +208,7 @@ __global__ __launch_bounds__(256) void head_merge_finish_kernel(const float *__r
         const int s = r / fin.L, j = r % fin.L;
         const int64_t src = fin.seq_rows ? fin.seq_rows[s] : s;
         const int64_t dst = fin.out_rows ? fin.out_rows[s] : s;
-        const int32_t tok = fin.tokens[src * fin.N + fin.block_start + j];
+        const int32_t tok = fin.tokens[src * fin.N + fin.block_start.of_row(src) + j];
         const bool masked = tok == mask_id;
         // a row without one finite logit (a model call on invalid input) has no prediction: token 0, confidence 0
         const bool valid = (uint32_t)arg < (uint32_t)vocab && sum >= 1.0f;

@@ -176,14 +176,14 @@ __global__ __launch_bounds__(256) void logits_top1_kernel(const float *__restric
 // others the sentinel (own token, -1)
 __global__ void head_finish_kernel(const float *__restrict__ row_sum, const int32_t *__restrict__ row_arg,
                                    const int32_t *__restrict__ tokens, const int32_t *__restrict__ seq_rows,
-                                   const int32_t *__restrict__ out_rows, int S, int N, int block_start, int L,
+                                   const int32_t *__restrict__ out_rows, int S, int N, BlockStart block_start, int L,
                                    int mask_id, int vocab, int32_t *__restrict__ top1, float *__restrict__ conf) {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= S * L) return;
     const int s = idx / L, j = idx % L;
     const int64_t src = seq_rows ? seq_rows[s] : s;
     const int64_t dst = out_rows ? out_rows[s] : s;
-    const int32_t tok = tokens[src * N + block_start + j];
+    const int32_t tok = tokens[src * N + block_start.of_row(src) + j];
     const bool masked = tok == mask_id;
     // a row without one finite logit (a model call on invalid input) has no prediction: token 0, confidence 0
     const int32_t arg = row_arg[idx];
@@ -217,7 +217,7 @@ void launch_logits_top1(const float *logits, int rows, int V, int mask_id, float
 }
 
 void launch_head_finish(const float *row_sum, const int32_t *row_arg, const int32_t *tokens, const int32_t *seq_rows,
-                        const int32_t *out_rows, int S, int N, int block_start, int L, int mask_id, int vocab, int32_t *top1,
+                        const int32_t *out_rows, int S, int N, BlockStart block_start, int L, int mask_id, int vocab, int32_t *top1,
                         float *conf, hipStream_t st) {
     const int n = S * L;
     hipLaunchKernelGGL(head_finish_kernel, dim3((n + 255) / 256), dim3(256), 0, st, row_sum, row_arg, tokens, seq_rows,

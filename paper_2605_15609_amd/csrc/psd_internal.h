@@ -33,7 +33,13 @@ struct psd_handle {
         std::vector<hipEvent_t> ev;     // pairs (start, stop)
         size_t used = 0;                // events handed out
         double flops = 0.0;             // algorithmic work of the timed launches (FLOPs; bytes for the LM-head pass)
-    } probe, probe_head;
+        std::vector<int64_t> a, b;      // per timed launch: rows and output columns of a contraction; rows of an LM-head
+                                        // pass; sequences and drafts per sequence (1 = stage-1 call) of a model call
+        void note(int64_t x, int64_t y) {
+            a.push_back(x);
+            b.push_back(y);
+        }
+    } probe, probe_head, probe_call;
 };
 
 void psd_set_error(const char *fmt, ...);
@@ -62,22 +68,35 @@ static inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * 
 #define PSD_DEVSTAT_HIST 7
 #define PSD_DEVSTAT_WORDS (7 + PSD_MAX_NODES + PSD_MAX_BLOCK + 1)
 
+// Where the active block of a sequence begins: one position common to the whole batch, or one per sequence (device
+// array indexed by sequence).  Kernels that walk batch slots map a slot to its row of the token matrix first; the
+// sequence is that row divided by rows_per_seq (1 for the sequences themselves, K for their drafts [B, K, N]).
+struct BlockStart {
+    int common;
+    const int32_t *per_seq;
+    int rows_per_seq;
+    BlockStart(int c = 0) : common(c), per_seq(nullptr), rows_per_seq(1) {}
+    BlockStart(const int32_t *arr, int rps) : common(0), per_seq(arr), rows_per_seq(rps) {}
+    __host__ __device__ int of_row(int64_t row) const { return per_seq ? per_seq[row / rows_per_seq] : common; }
+};
+
 struct GraphArg {
     int32_t K;
     uint64_t rank_set[PSD_MAX_NODES];
 };
 
-void launch_eos_stop(const int32_t *tokens, int B, int N, int block_start, int L, int32_t eos_id, int32_t *n_left, int32_t *m,
+void launch_eos_stop(const int32_t *tokens, int B, int N, BlockStart block_start, int L, int32_t eos_id, int32_t *n_left, int32_t *m,
                      int32_t *devstats, hipStream_t st);
-void launch_finish_counts(const int32_t *tokens, int B, int N, int block_start, int L, int32_t mask_id, int32_t eos_stop,
-                          int32_t eos_id, int32_t *devstats, hipStream_t st);
-void launch_select_unmask(int32_t *tokens, int B, int N, int block_start, int L, const int32_t *top1,
+// only[b] != 0 selects the sequences to finish (NULL: all); their counters of resolved positions are ADDED to
+void launch_finish_counts(const int32_t *tokens, int B, int N, BlockStart block_start, int L, int32_t mask_id, int32_t eos_stop,
+                          int32_t eos_id, int32_t *devstats, const int32_t *only, hipStream_t st);
+void launch_select_unmask(int32_t *tokens, int B, int N, BlockStart block_start, int L, const int32_t *top1,
                           const float *conf, psd_policy policy, int32_t mask_id, uint8_t *transfer_mask,
                           int32_t *n_selected, int32_t *n_left, int32_t *devstats, hipStream_t st);
-void launch_build_drafts(const int32_t *tokens, int B, int N, int block_start, int L, const int32_t *top1,
+void launch_build_drafts(const int32_t *tokens, int B, int N, BlockStart block_start, int L, const int32_t *top1,
                          const float *conf, const GraphArg &g, int32_t mask_id, int32_t *sigma, int32_t *m,
                          int32_t *drafts, hipStream_t st);
-void launch_accept(int32_t *tokens, const int32_t *drafts, int B, int N, int block_start, int L,
+void launch_accept(int32_t *tokens, const int32_t *drafts, int B, int N, BlockStart block_start, int L,
                    const int32_t *sigma, const int32_t *m, const GraphArg &g, psd_policy policy, int32_t mask_id,
                    const int32_t *v_top1, const float *v_conf, int32_t *k_star, uint8_t *accepted,
                    int32_t *n_left, int32_t *devstats, hipStream_t st);
@@ -96,11 +115,11 @@ ForwardPlan plan_forward(const psd_model_config &cfg, int64_t S, int64_t N, int6
 // sequences' caches (store->dual), compacted: prefix positions first, then the suffix.
 struct KvCacheArg;
 int32_t run_forward_hidden(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N,
-                           int block_start, int L, void *ws, int64_t ws_bytes, hipStream_t st,
+                           BlockStart block_start, int L, void *ws, int64_t ws_bytes, hipStream_t st,
                            const KvCacheArg *store = nullptr);
 // LM-head + top-1 confidence on y; out_rows (device, may be NULL) maps slot s -> row of top1/conf.
 int32_t run_head_confidence(psd_handle *h, const int32_t *tokens, const int32_t *seq_rows, int S, int N,
-                            int block_start, int L, int32_t *top1, float *conf, const int32_t *out_rows,
+                            BlockStart block_start, int L, int32_t *top1, float *conf, const int32_t *out_rows,
                             void *ws, hipStream_t st, int plan_N = -1 /* sequence length the workspace was planned
                             for, if not N (the cached forward plans for L rows per sequence) */);
 // forward over the L block rows of S sequences against their KV caches (context-causal block attention)
@@ -176,12 +195,13 @@ struct PendingSums {
 template <typename T>
 void launch_rmsnorm(float *h, int64_t rows, int d, const float *gain, float eps, T *out, PendingSums pend, hipStream_t st);
 template <typename T>
-void launch_rmsnorm_block(float *h, int S, int N, int block_start, int L, int d, const float *gain,
+void launch_rmsnorm_block(float *h, const int32_t *seq_rows, int S, int N, BlockStart block_start, int L, int d, const float *gain,
                           float eps, T *out, T *packed /* fragment-order copy, may be NULL */, PendingSums pend,
                           hipStream_t st);
 // dst [S*L, width] <- the L block rows of each of the S sequences of src [S*N, width]
 template <typename T>
-void launch_gather_block_rows(const T *src, T *dst, int width, int S, int N, int block_start, int L, hipStream_t st);
+void launch_gather_block_rows(const T *src, T *dst, int width, const int32_t *seq_rows, int S, int N, BlockStart block_start, int L,
+                              hipStream_t st);
 template <typename T>
 void launch_rope(T *qkv, int ld /* row stride */, int64_t tokens, int N, int pos0 /* position of row 0 of each sequence */, int n_heads, int n_kv_heads, int d_head, const float *cos_t,
                  const float *sin_t, hipStream_t st);
@@ -212,7 +232,7 @@ void launch_plain_attention(const T *qkv, int ld, int S, int N, int n_heads, int
 void launch_logits_top1(const float *logits, int rows, int V, int mask_id, float *row_sum, int32_t *row_arg,
                         hipStream_t st);
 void launch_head_finish(const float *row_sum, const int32_t *row_arg, const int32_t *tokens, const int32_t *seq_rows,
-                        const int32_t *out_rows, int S, int N, int block_start, int L, int mask_id, int vocab, int32_t *top1,
+                        const int32_t *out_rows, int S, int N, BlockStart block_start, int L, int mask_id, int vocab, int32_t *top1,
                         float *conf, hipStream_t st);
 
 // gemm_mfma.hip (bf16; Nout, Kin multiples of 64)
@@ -248,7 +268,9 @@ void launch_head_stream_bf16(const bf16_t *y_packed, const bf16_t *W_packed, int
 // where the streamed head's result goes: (row_sum, row_arg) and/or the final (top1, conf) tables with sentinels
 struct HeadFinish {
     const int32_t *tokens, *seq_rows, *out_rows;
-    int S, N, block_start, L;
+    int S, N;
+    BlockStart block_start;
+    int L;
     int32_t *top1;
     float *conf;
 };

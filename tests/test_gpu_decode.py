@@ -444,3 +444,71 @@ def test_config5_shape_two_layers_lockstep_inside_the_batch():
         x2, _ = orc.advance(o_dr[b], o_k, bs, L, vt[b], vc[b], opol, mask_id)
         assert int(ks_h[b]) == o_k and (acc_h[b] == o_acc).all() and (final[b] == x2).all(), b
     print(f"[decode] config 5 shape (2 layers) lock-step inside the batch: {log}", flush=True)
+
+
+def test_psd_decode_walks_every_sequence_through_its_own_blocks_like_the_oracle():
+    """The whole generation behind one C call, fp32 model, exact: three sequences with prompts of different lengths start on
+    different blocks and move on independently; tokens and counters of each must equal the oracle's decode of that sequence
+    alone (also with EOS early stopping), and a run cut into single iterations must give the same result."""
+    import paper_2605_15609_amd as psd
+    shape = inp.WORKLOADS[1].shape
+    N, L, B = 64, 16, 3
+    host = inp.draw_model(shape, N)
+    model = psd.Model.from_host(host, DEV)
+    fn = orc.model_confidence_fn(host)
+    prompts = (16, 32, 48)
+    tokens0 = np.full((B, N), shape.mask_id, dtype=np.int32)
+    for b, P in enumerate(prompts):
+        tokens0[b, :P] = inp.draw_prompt(shape.vocab, P, 700 + b, "uniform")
+    for K, tau in ((2, 0.9), (4, 0.02), (3, float("inf"))):
+        refs = [orc.decode(fn, tokens0[b], prompts[b], L, orc.Policy(tau, 1, 0), orc.chain_graph(K), shape.mask_id) for b in range(B)]
+        d = _dev(tokens0)
+        stats, starts, iters = psd.psd_decode(model, d, list(prompts), L, psd.Policy(tau, 1, 0), psd.chain_graph(K))
+        got = d.cpu().numpy()
+        assert all(s >= N for s in starts) and iters >= 1
+        for b in range(B):
+            assert (got[b] == refs[b][0]).all(), (K, tau, b)
+            assert _counters(stats[b]) == _counters(refs[b][1]), (K, tau, b)
+        # the same generation, one iteration of the batch per call
+        d1 = _dev(tokens0)
+        st, at, total = None, list(prompts), 0
+        for _ in range(10 * N):
+            st, at, n = psd.psd_decode(model, d1, at, L, psd.Policy(tau, 1, 0), psd.chain_graph(K), st, max_iterations=1)
+            total += n
+            if n == 0:
+                break
+        assert (d1.cpu().numpy() == got).all() and total == iters, (K, tau)
+        assert [_counters(s) for s in st] == [_counters(s) for s in stats]
+        # EOS early stopping: a token the free run of sequence 0 produces in its second block
+        eos = int(refs[0][0][prompts[0] + L + 3])
+        d2 = _dev(tokens0)
+        stats2, starts2, _ = psd.psd_decode(model, d2, list(prompts), L, psd.Policy(tau, 1, 0, eos_id=eos), psd.chain_graph(K))
+        for b in range(B):
+            ref, ost = orc.decode(fn, tokens0[b], prompts[b], L, orc.Policy(tau, 1, 0), orc.chain_graph(K), shape.mask_id, eos_id=eos)
+            assert (d2.cpu().numpy()[b] == ref).all(), (K, tau, b, "eos")
+            assert _counters(stats2[b]) == _counters(ost), (K, tau, b, "eos")
+        assert stats2[0].stopped
+    with pytest.raises(psd.PsdError):
+        psd.psd_decode(model, _dev(tokens0), [16, 30, 48], L, psd.Policy(), psd.chain_graph(2))     # not whole blocks
+
+
+def test_psd_decode_block_with_one_block_start_per_sequence():
+    import paper_2605_15609_amd as psd
+    shape = inp.cut_down(inp.WORKLOADS[2].shape, n_layers=2, vocab=4000, seed=33, logit_scale=14.0)
+    N, L, K, B = 160, 32, 3, 4
+    host = inp.draw_model(shape, N)
+    model = psd.Model.from_host(host, DEV)
+    policy, graph = psd.Policy(0.9, 1, 0), psd.chain_graph(K)
+    starts = [64, 96, 32, 64]
+    tokens = np.full((B, N), shape.mask_id, dtype=np.int32)
+    for b in range(B):
+        tokens[b, :starts[b]] = inp.draw_prompt(shape.vocab, starts[b], 80 + b)
+    together = _dev(tokens)
+    stats = psd.psd_decode_block(model, together, starts, L, policy, graph)
+    for b in range(B):
+        alone = _dev(tokens[b: b + 1])
+        s = psd.psd_decode_block(model, alone, starts[b], L, policy, graph)
+        assert (alone[0] == together[b]).all(), b
+        assert (s[0].invocations, s[0].tokens) == (stats[b].invocations, stats[b].tokens) and s[0].tokens == L
+        row = together[b].cpu().numpy()
+        assert (row[starts[b]: starts[b] + L] != shape.mask_id).all() and (row[starts[b] + L:] == shape.mask_id).all()
