@@ -480,7 +480,7 @@ def first_eos(tokens: np.ndarray, block_start: int, L: int, eos_id: Optional[int
 
 def decode_block(confidence_fn: ConfidenceFn, tokens: np.ndarray, block_start: int, L: int, policy: Policy,
                  graph: Graph, mask_id: int, stats: Optional[Stats] = None, trace: Optional[list] = None,
-                 eos_id: Optional[int] = None):
+                 eos_id: Optional[int] = None, single_forward: bool = False):
     """Alg. 1 on one block of one sequence.  ``confidence_fn(tokens, block_start, L)`` is the
     model call (forward + top-1 confidence); a batched verification is K such calls counted
     as one invocation.
@@ -491,7 +491,17 @@ def decode_block(confidence_fn: ConfidenceFn, tokens: np.ndarray, block_start: i
     ends if it is there, whatever is still masked.  ``tokens_counted`` is the number of positions this call
     resolved at or before the first EOS position (tokens unmasked beyond it are discarded from
     the statistic, in whichever iteration they were unmasked); without an EOS every resolved
-    position counts."""
+    position counts.
+
+    ``single_forward`` (a variant, NOT the literal Alg. 1): the last line of stage 3 commits the verifier's
+    predictions of the accepted draft k* that pass the policy; the literal loop then calls the model again on
+    the committed state (stage 1 of the next iteration).  The variant lets that post-verification commit BE
+    the next iteration's stage-1 commit and builds the next drafts from k*'s verifier output (x_hat_k*, c_k*)
+    -- the model's exact prediction on draft k*, i.e. on the state just before that commit -- so that an
+    iteration costs one model call (the batched verification) instead of two.  Only the call that enters a
+    block is a stage-1 call.  Every commit still comes from an exact forward of an exact state; what goes
+    stale is only the table the SPECULATION is drawn from.  Results differ from the literal loop in
+    general."""
     stats = stats if stats is not None else Stats()
     x = np.array(tokens, dtype=np.int32, copy=True)
     if eos_id is not None and eos_id == mask_id:
@@ -506,17 +516,19 @@ def decode_block(confidence_fn: ConfidenceFn, tokens: np.ndarray, block_start: i
         stats.tokens_counted += sum(1 for i in masked_on_entry if i <= limit and x[i] != mask_id)
         return x, stats
 
+    have_tables = False      # single_forward: (top1, conf) already hold the output the last commit was taken from
     while masked_in_block(x, block_start, L, mask_id):
-        top1, conf = confidence_fn(x, block_start, L)                       # stage 1
-        stats.invocations += 1
-        x, transfer = select_unmask(x, block_start, L, top1, conf, policy, mask_id)
-        stats.tokens_policy += int(transfer.sum())
-        if trace is not None:
-            trace.append(("commit", [block_start + j for j in range(L) if transfer[j]]))
-        if first_eos(x, block_start, L, eos_id) is not None:
-            break
-        if not masked_in_block(x, block_start, L, mask_id):
-            break
+        if not have_tables:
+            top1, conf = confidence_fn(x, block_start, L)                   # stage 1
+            stats.invocations += 1
+            x, transfer = select_unmask(x, block_start, L, top1, conf, policy, mask_id)
+            stats.tokens_policy += int(transfer.sum())
+            if trace is not None:
+                trace.append(("commit", [block_start + j for j in range(L) if transfer[j]]))
+            if first_eos(x, block_start, L, eos_id) is not None:
+                break
+            if not masked_in_block(x, block_start, L, mask_id):
+                break
         sigma, m, drafts = build_drafts(x, block_start, L, top1, conf, graph, mask_id)   # stage 2
         v = [confidence_fn(drafts[k], block_start, L) for k in range(graph.K)]            # stage 3
         stats.invocations += 1
@@ -533,12 +545,16 @@ def decode_block(confidence_fn: ConfidenceFn, tokens: np.ndarray, block_start: i
             trace.append(("verify", k_star, depth, n_post, accepted.copy()))
         if first_eos(x, block_start, L, eos_id) is not None:
             break
+        if single_forward:
+            # the post-verification commit above was the next iteration's stage-1 commit; its drafts come
+            # from the same output, the verifier's tables of draft k*
+            top1, conf, have_tables = v_top1[k_star], v_conf[k_star], True
     return finish(x)
 
 
 def decode(confidence_fn: ConfidenceFn, tokens: np.ndarray, prompt_len: int, L: int, policy: Policy,
            graph: Graph, mask_id: int, stats: Optional[Stats] = None, trace: Optional[list] = None,
-           eos_id: Optional[int] = None):
+           eos_id: Optional[int] = None, single_forward: bool = False):
     """Semi-autoregressive generation: blocks left to right, the next block starts only once
     the current one is fully resolved (App. B.1).  Later blocks stay masked meanwhile.  With
     ``eos_id`` the generation ends with the block that produced an EOS token."""
@@ -547,7 +563,7 @@ def decode(confidence_fn: ConfidenceFn, tokens: np.ndarray, prompt_len: int, L: 
     N = x.shape[0]
     for block_start in range(prompt_len, N, L):
         x, stats = decode_block(confidence_fn, x, block_start, min(L, N - block_start), policy, graph,
-                                mask_id, stats, trace, eos_id)
+                                mask_id, stats, trace, eos_id, single_forward)
         if stats.stopped:
             break
     return x, stats

@@ -37,6 +37,10 @@
 #define PSD_PRIO_HI
 #define PSD_PRIO_LO
 #endif
+// row tiles per band of the tile order (see the kernel); 4 unless a tuning run changes it (measured over the layer
+// contractions of the 8B shapes at 2048 - 163 840 rows: bands of 4 and 8 within 1 %, 1 and 16 about 5 % slower)
+int gemm_tile_group_m();
+
 namespace mfma {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -94,7 +98,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
                                                         const bf16_t *__restrict__ Y2, int M, int Nout, int Kin, int ldx, int ldy,
                                                         const float *__restrict__ bias, bf16_t *__restrict__ out,
                                                         float *__restrict__ resid, int ldo, int tiles_n, int n_tiles,
-                                                        Top1Args t1, int k_splits, float *__restrict__ partial) {
+                                                        Top1Args t1, int k_splits, float *__restrict__ partial, int group_m) {
     extern __shared__ __align__(16) unsigned char lds[];
     constexpr bool DUAL = EPI == EPI_SWIGLU;
     constexpr int BN_OUT = DUAL ? BN / 2 : BN;            // output columns per tile
@@ -112,18 +116,17 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
     }
     const int k_len = Kin / k_splits, k_beg = split * k_len;   // this workgroup's K range
     if (n_tiles % 8 == 0) pid = (pid % 8) * (n_tiles / 8) + pid / 8;
-    // Each XCD has its own L2, so its tile range should re-use what it fetches: the range is cut along the
-    // dimension of the LARGER operand (each XCD then reads an eighth of it, plus all of the small one), and
-    // inside the range the index of the small operand runs fastest.
+    // Each XCD has its own L2 and runs about 32 consecutive tile ids of its range at a time, all walking K roughly in
+    // step, so those 32 tiles should share operand tiles both ways: ids are laid out in bands of `group_m` row tiles,
+    // column-major inside a band, which makes 32 consecutive ids a patch of group_m x (32 / group_m) tiles (every
+    // activation K-slice is fetched once for 32 / group_m workgroups, every weight K-slice once for group_m).  With
+    // at most group_m row tiles this is the plain "rows fastest" order.
     const int tiles_m = n_tiles / tiles_n;
-    int tile_m, tile_n;
-    if (M <= Nout) {
-        tile_n = pid / tiles_m;
-        tile_m = pid % tiles_m;
-    } else {
-        tile_m = pid / tiles_n;
-        tile_n = pid % tiles_n;
-    }
+    const int band = group_m * tiles_n;
+    const int first_m = (pid / band) * group_m;
+    const int rows_in_band = min(tiles_m - first_m, group_m);
+    const int tile_m = first_m + (pid % band) % rows_in_band;
+    const int tile_n = (pid % band) / rows_in_band;
     const int m0 = tile_m * BM, n0 = tile_n * BN_OUT;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -389,7 +392,7 @@ void launch_cfg(const bf16_t *X, const bf16_t *Y, const bf16_t *Y2, int M, int N
     }
     if (EPI != EPI_RESIDUAL) k_splits = 1;
     hipLaunchKernelGGL(kern, dim3(n_tiles * k_splits), dim3(WGM * WGN * 64), smem, st, X, Y, Y2, M, Nout, Kin, ldx, ldy, bias, out, resid,
-                       ldo, tiles_n, n_tiles, t1, k_splits, partial);
+                       ldo, tiles_n, n_tiles, t1, k_splits, partial, gemm_tile_group_m());
 }
 
 }   // namespace mfma

@@ -22,6 +22,7 @@ constexpr TileCfg kTiles[] = {
     {128, 64, "128x64, 4 wavefronts, LDS rings 4/4"},     // lone workgroup per CU: fetches several stages ahead
     {128, 128, "128x128, 4 wavefronts, LDS rings 4/4"},
     {64, 64, "64x64, 4 wavefronts, LDS rings 4/4"},
+    {256, 128, "256x128, 8 wavefronts, LDS rings 2/4"},   // one full round of 256 workgroups for 2048 x 4096 outputs
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -38,6 +39,7 @@ void dispatch(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int M, int Nou
             case 3: return launch_cfg<128, 192, 2, 2, EPI, 2, 2>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
             case 4: return launch_cfg<128, 64, 2, 2, EPI, 4, 4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
             case 6: return launch_cfg<64, 64, 2, 2, EPI, 4, 4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+            case 7: return launch_cfg<256, 128, 4, 2, EPI, 2, 4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
             default: break;
         }
     }
@@ -52,11 +54,16 @@ bool tile_fits(int tile, int epi) { return epi != EPI_SWIGLU || tile == 0 || til
 
 }   // namespace
 
-static int g_force_tile = -1, g_force_splits = 0;
+static int g_force_tile = -1, g_force_splits = 0, g_group_m = 4;
+// tile < 0: automatic.  Otherwise bits 0-7 the tile, bits 8-15 the K-split of the residual hook, bits 16-23 the band
+// height of the tile order (0 = leave it)
 void gemm_bf16_force_tile(int tile) {
-    g_force_tile = tile < 0 ? -1 : (tile & 0xff);
-    g_force_splits = tile < 0 ? 0 : (tile >> 8);
+    g_force_tile = tile < 0 ? -1 : (tile & 0xff) == 0xff ? -1 : (tile & 0xff);
+    g_force_splits = tile < 0 ? 0 : ((tile >> 8) & 0xff);
+    if (tile < 0) g_group_m = 4;
+    else if ((tile >> 16) & 0xff) g_group_m = (tile >> 16) & 0xff;
 }
+int gemm_tile_group_m() { return g_group_m; }
 int gemm_bf16_tile_count() { return kNumTiles; }
 const char *gemm_bf16_tile_name(int tile) { return tile >= 0 && tile < kNumTiles ? kTiles[tile].name : "?"; }
 

@@ -559,3 +559,108 @@ def test_eos_ends_the_generation_after_its_block():
     assert (out[4:4 + L] == free[4:4 + L]).all() and st.stopped and 4 + L <= st.eos_pos < 4 + 2 * L
     assert (out[4 + 2 * L:] == mask).all()
     assert st.tokens_counted == L + int((out[4 + L: st.eos_pos + 1] != mask).sum())
+
+
+# ---------------------------------------------------------------- the single-forward variant
+
+
+@pytest.mark.parametrize("tau", [0.5, 0.9])
+def test_single_forward_with_the_root_only_graph_is_plain_parallel_decoding(tau):
+    """K = 1: every call, the first included, is a forward on the current state followed by the policy's commit."""
+    L, vocab = 16, 50
+    for seed in range(15):
+        tokens = np.full(24, vocab - 1, dtype=np.int32)
+        tokens[:8] = 3
+        ref, calls = plain_parallel(pseudo_model(vocab, seed), tokens, 8, L, vocab - 1, tau)
+        fn = Counting(pseudo_model(vocab, seed))
+        out, stats = orc.decode_block(fn, tokens, 8, L, orc.Policy(tau, 1), orc.chain_graph(1), vocab - 1, single_forward=True)
+        assert (out == ref).all()
+        assert stats.invocations == calls == fn.calls
+
+
+@pytest.mark.parametrize("K", [1, 2, 4, 8])
+def test_single_forward_with_the_greedy_policy_reproduces_plain_greedy_decoding(K):
+    """Every commit of the variant is taken from an exact forward of an exact state, and with greedy pi the acceptance
+    criterion lets through exactly what greedy decoding would reveal next: same tokens, fewer calls."""
+    L, vocab = 12, 40
+    fewer = 0
+    for seed in range(12):
+        fn = pseudo_model(vocab, seed, sticky=0.6)
+        tokens = np.full(20, vocab - 1, dtype=np.int32)
+        tokens[:8] = np.random.default_rng(seed).integers(0, vocab - 1, 8)
+        ref, _ = plain_greedy(fn, tokens, 8, L, vocab - 1)
+        out, stats = orc.decode_block(fn, tokens, 8, L, orc.Policy(INF, 1), orc.chain_graph(K), vocab - 1, single_forward=True)
+        _, literal = orc.decode_block(fn, tokens, 8, L, orc.Policy(INF, 1), orc.chain_graph(K), vocab - 1)
+        assert (out == ref).all()
+        assert stats.tokens == L and stats.invocations <= L and stats.tpf >= 1.0
+        fewer += int(stats.invocations < literal.invocations)
+    assert K == 1 or fewer > 0
+
+
+def test_single_forward_progress_calls_and_first_iteration():
+    L, vocab = 32, 200
+    for seed in range(20):
+        for K, tau, kind in ((4, 0.9, "uniform"), (8, 0.9, "low"), (2, 0.3, "uniform")):
+            tokens = np.full(48, vocab - 1, dtype=np.int32)
+            tokens[:16] = 1
+            fn = Counting(pseudo_model(vocab, seed, conf_kind=kind, sticky=0.7))
+            trace = []
+            out, stats = orc.decode_block(fn, tokens, 16, L, orc.Policy(tau, 1), orc.chain_graph(K), vocab - 1, trace=trace,
+                                          single_forward=True)
+            assert not (out[16:48] == vocab - 1).any() and (out[:16] == 1).all()
+            n_verify = sum(stats.depth_hist)
+            assert stats.tokens == L and stats.tpf >= 1.0
+            assert stats.invocations == 1 + n_verify                 # one stage-1 call per block, then verifications only
+            assert fn.calls == 1 + K * n_verify
+            assert [e[0] for e in trace] == ["commit"] + ["verify"] * n_verify
+            # up to and including the first verification the variant IS the literal loop
+            lit = []
+            orc.decode_block(pseudo_model(vocab, seed, conf_kind=kind, sticky=0.7), tokens, 16, L, orc.Policy(tau, 1),
+                             orc.chain_graph(K), vocab - 1, trace=lit)
+            assert trace[0] == lit[0]
+            if n_verify:
+                assert trace[1][1:4] == lit[1][1:4] and (trace[1][4] == lit[1][4]).all()
+
+
+def test_single_forward_refreshes_its_tables_with_every_new_block_and_stops_on_eos():
+    vocab, L = 60, 8
+    fn = Counting(pseudo_model(vocab, 11, sticky=0.5))
+    tokens = np.full(4 + 3 * L, vocab - 1, dtype=np.int32)
+    tokens[:4] = 2
+    out, stats = orc.decode(fn, tokens, 4, L, orc.Policy(0.9, 1), orc.chain_graph(3), vocab - 1, single_forward=True)
+    assert not (out == vocab - 1).any()
+    n_verify = sum(stats.depth_hist)
+    assert stats.invocations == 3 + n_verify and fn.calls == 3 + 3 * n_verify        # one stage-1 call per block
+    eos = int(out[4 + L + 2])
+    cut, st = orc.decode(pseudo_model(vocab, 11, sticky=0.5), tokens, 4, L, orc.Policy(0.9, 1), orc.chain_graph(3), vocab - 1,
+                         eos_id=eos, single_forward=True)
+    assert st.stopped and cut[st.eos_pos] == eos and st.eos_pos <= 4 + L + 2
+    assert (cut[4 + ((st.eos_pos - 4) // L + 1) * L:] == vocab - 1).all()
+
+
+def test_single_forward_hand_worked_trace_fixture():
+    """tests/golden/single_forward_trace.txt, worked by hand from the variant's definition."""
+    import os
+    rows = []
+    with open(os.path.join(os.path.dirname(__file__), "golden", "single_forward_trace.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                rows.append(line.split())
+    vocab, L = 30, 16
+    fn = pseudo_model(vocab, 3, conf_kind="low", sticky=1.0)
+    tokens = np.full(L, vocab - 1, dtype=np.int32)
+    trace = []
+    out, stats = orc.decode_block(fn, tokens, 0, L, orc.Policy(0.9, 1), orc.chain_graph(4), vocab - 1, trace=trace, single_forward=True)
+    got, masks = [], L
+    for n, e in enumerate(trace, 1):
+        if e[0] == "commit":
+            got.append([str(n), str(masks), "stage1", str(len(e[1])), "-", "-"])
+            masks -= len(e[1])
+        else:
+            _, _, depth, n_post, _ = e
+            got.append([str(n), str(masks), "verify", "-", str(depth), str(n_post)])
+            masks -= depth + n_post
+    assert got == rows
+    assert masks == 0 and stats.tokens == 16 and stats.invocations == 5
+    literal, _ = orc.decode_block(fn, tokens, 0, L, orc.Policy(0.9, 1), orc.chain_graph(4), vocab - 1)
+    assert (out == literal).all()            # predictions never change here: same tokens, 5 calls instead of 7
