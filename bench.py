@@ -206,10 +206,27 @@ def bench_iterations(psd, inp, torch, w, model, steps, warmup, probe_steps):
     return {"elapsed": elapsed, "tokens": tokens, "invocations": inv, "stats": stats, "extra": extra, "positions": at}
 
 
-def bench_decodes(psd, inp, torch, w, model, steps, warmup, max_blocks, attention="bidirectional", probe=True):
+def bench_single_forward_iterations(psd, inp, torch, w, model, iterations):
+    """The single-forward variant of the loop on the workload's first iterations, in ONE psd_decode call (its tables live
+    for one call): one stage-1 call for the batch, then `iterations` passes of one batched verification each."""
+    policy, graph = psd.Policy(w.tau, w.k_min, w.k_max, single_forward=True), psd.chain_graph(w.n_drafts)
+    toks = torch.from_numpy(inp.initial_state(w)).to("cuda:0")
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    stats, _, done = psd.psd_decode(model, toks, [w.prompt_len] * w.batch, w.block_len, policy, graph, max_iterations=iterations)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    tokens, inv = stats_tokens(stats), sum(s.invocations for s in stats)
+    return {"workload": workload_name(w) + f"; the first {done} iterations in one call, single-forward loop (NOT the literal Alg. 1: "
+                        "the post-verification commit doubles as the next stage-1 commit, drafts from the accepted draft's verifier output)",
+            "tokens_per_s": tokens / elapsed, "ms_per_iteration": elapsed / max(1, done) * 1e3, "iterations": done,
+            "tpf": tokens / max(1, inv), "tokens": int(tokens), "model_calls_per_sequence": inv / w.batch}
+
+
+def bench_decodes(psd, inp, torch, w, model, steps, warmup, max_blocks, attention="bidirectional", probe=True, single_forward=False):
     """Whole decodes of the workload (all blocks, or the first max_blocks); a step = one decode."""
     cached, approx = attention == "block-causal", attention == "approx-cache"
-    policy, graph = psd.Policy(w.tau, w.k_min, w.k_max), psd.chain_graph(w.n_drafts)
+    policy, graph = psd.Policy(w.tau, w.k_min, w.k_max, single_forward=single_forward), psd.chain_graph(w.n_drafts)
     tokens0 = torch.from_numpy(inp.initial_state(w)).to("cuda:0")
     n_blocks = w.gen_len // w.block_len
     if max_blocks > 0:
@@ -382,11 +399,13 @@ def main():
     if args.attention == "approx-cache":
         out["config"]["workload"] += (", approximate prefix + suffix KV cache (one exact whole-sequence call per block, block rows "
                                       "against frozen keys / values otherwise; results differ from the exact decode)")
+    also = {}
+    if not args.no_also and per_iteration:
+        also[f"config {w.index}, single-forward loop"] = bench_single_forward_iterations(psd, inp, torch, w, model, 4)
     del model
     torch.cuda.empty_cache()
 
     if not args.no_also and per_iteration:
-        also = {}
         for cfg, kw in ((3, {"steps": 2, "warmup": 1, "max_blocks": 0}), (4, {"steps": 1, "warmup": 1, "max_blocks": 4}),
                         (2, {"steps": 5, "warmup": 1, "max_blocks": 0})):
             w2 = inp.WORKLOADS[cfg]
@@ -399,6 +418,12 @@ def main():
             if cfg == 2:
                 rec["bound"] = "kernel granularity (about 90 kernels of 3-14 us per model call); no roofline claim for the contractions"
             also[f"config {cfg}"] = rec
+            if cfg == 3:
+                r3 = bench_decodes(psd, inp, torch, w2, m2, kw["steps"], 0, 0, probe=False, single_forward=True)
+                also["config 3, single-forward loop"] = {
+                    "workload": workload_name(w2) + "; a step = one whole decode with the single-forward loop (NOT the literal Alg. 1; results differ)",
+                    "tokens_per_s": r3["tokens"] / r3["elapsed"], "ms_per_decode": r3["elapsed"] / kw["steps"] * 1e3,
+                    "tpf": r3["tokens"] / max(1, r3["invocations"]), "invocations_per_decode": r3["invocations"] // kw["steps"]}
             del m2
             torch.cuda.empty_cache()
         out["also"] = also

@@ -116,6 +116,17 @@ typedef struct {
      * if it is there the sequence takes part in no further model call, whatever is still masked. */
     int32_t eos_stop;
     int32_t eos_id;  /* 0 <= eos_id < vocab, not the mask token (checked when eos_stop = 1) */
+    /* Block loops only (psd_decode, psd_decode_block, psd_decode_block_cached); 0 = the literal Alg. 1.
+     * 1 = a variant that is NOT the literal Alg. 1 and gives different results in general: the last line
+     * of stage 3 commits, by pi, predictions of the accepted draft k* -- the literal loop then calls the
+     * model again on the committed state (stage 1 of the next iteration).  The variant takes that
+     * post-verification commit as the next iteration's stage-1 commit and draws the next speculative
+     * ordering and drafts from k*'s verifier output (x_hat_k*, c_k*), the model's exact prediction on the
+     * state just before that commit.  An iteration then costs one model call, the batched verification;
+     * only the call that enters a block is a stage-1 call.  Every committed token still comes from an
+     * exact forward of an exact state.  The tables live for one library call: each call starts with a
+     * stage-1 call for every sequence (so max_iterations = 1 gains nothing). */
+    int32_t single_forward;
 } psd_policy;
 
 /* Draft DAG (Sec. 3.2 stage 2).  Node k speculates on the ranks of the speculative

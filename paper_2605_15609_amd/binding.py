@@ -43,7 +43,7 @@ class _Weights(C.Structure):
 
 class _Policy(C.Structure):
     _fields_ = [("tau", C.c_float), ("k_min", C.c_int32), ("k_max", C.c_int32), ("eos_stop", C.c_int32),
-                ("eos_id", C.c_int32)]
+                ("eos_id", C.c_int32), ("single_forward", C.c_int32)]
 
 
 class _Graph(C.Structure):
@@ -170,10 +170,14 @@ class Policy:
     k_min: int = 1
     k_max: int = 0
     eos_id: Optional[int] = None     # EOS early stopping of the block loop (App. B.1); None = off
+    # block loops: the post-verification commit doubles as the next stage-1 commit and the next drafts come from the
+    # accepted draft's verifier output -- one model call per iteration; not the literal Alg. 1
+    single_forward: bool = False
 
     def c(self) -> _Policy:
         return _Policy(float(np.float32(self.tau)), int(self.k_min), int(self.k_max),
-                       0 if self.eos_id is None else 1, 0 if self.eos_id is None else int(self.eos_id))
+                       0 if self.eos_id is None else 1, 0 if self.eos_id is None else int(self.eos_id),
+                       1 if self.single_forward else 0)
 
 
 @dataclass(frozen=True)

@@ -396,7 +396,7 @@ int32_t psd_select_unmask(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, 
     CHECK(check_policy(policy));
     if (!tokens || !top1 || !conf) PSD_FAIL(PSD_ERR_INVALID_ARG, "NULL tokens/top1/conf");
     launch_select_unmask(tokens, B, N, block_start, L, top1, conf, *policy, h->cfg.mask_id, transfer_mask, n_selected,
-                         nullptr, nullptr, (hipStream_t)stream);
+                         nullptr, nullptr, nullptr, (hipStream_t)stream);
     PSD_HIP(hipGetLastError());
     return PSD_OK;
 }
@@ -422,7 +422,7 @@ int32_t psd_accept(psd_handle *h, int32_t *tokens, const int32_t *drafts, int32_
     CHECK(check_policy(policy));
     if (!tokens || !drafts || !sigma || !m || !v_top1 || !v_conf) PSD_FAIL(PSD_ERR_INVALID_ARG, "NULL argument");
     launch_accept(tokens, drafts, B, N, block_start, L, sigma, m, g, *policy, h->cfg.mask_id, v_top1, v_conf, k_star,
-                  accepted, nullptr, nullptr, (hipStream_t)stream);
+                  accepted, nullptr, nullptr, nullptr, nullptr, (hipStream_t)stream);
     PSD_HIP(hipGetLastError());
     return PSD_OK;
 }
@@ -441,7 +441,7 @@ int32_t psd_verify_accept(psd_handle *h, int32_t *tokens, const int32_t *drafts,
     CHECK(run_forward_hidden(h, drafts, nullptr, S, N, block_start, L, ws, ws_bytes, st));
     CHECK(run_head_confidence(h, drafts, nullptr, S, N, block_start, L, v_top1, v_conf, nullptr, ws, st));
     launch_accept(tokens, drafts, B, N, block_start, L, sigma, m, g, *policy, h->cfg.mask_id, v_top1, v_conf, k_star,
-                  accepted, nullptr, nullptr, st);
+                  accepted, nullptr, nullptr, nullptr, nullptr, st);
     PSD_HIP(hipGetLastError());
     return PSD_OK;
 }
@@ -453,7 +453,10 @@ namespace {
 // decodes that one block and is done; advance = true: a sequence whose block is resolved moves on to the next one
 // (start + L) in the following iteration, until the end of the sequence -- the semi-autoregressive outer loop.  An
 // iteration is one stage-1 call over all running sequences plus one batched verification call over those that still
-// have masks after the stage-1 commit.  max_iterations > 0 ends the call after that many iterations (starts then says
+// have masks after the stage-1 commit.  policy->single_forward: a sequence that went through a verification in this
+// call and is still inside its block has no stage-1 call in the next iteration -- the accept kernel left the verifier
+// output of its accepted draft in (top1, conf), its post-verification commit was the stage-1 commit, and the drafts
+// are built from those tables.  max_iterations > 0 ends the call after that many iterations (starts then says
 // where every sequence stands).  kv != NULL: model calls on the block rows against the sequences' KV caches; all
 // sequences must then share one block and advance must be false.
 int32_t decode_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_t *starts, int32_t L, const psd_policy *policy,
@@ -472,6 +475,9 @@ int32_t decode_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_
     CHECK(check_graph(graph, &g));
     CHECK(check_policy(policy));
     const bool eos_stop = policy->eos_stop != 0;
+    const bool single_forward = policy->single_forward != 0;
+    if (single_forward && kv && kv->dual)
+        PSD_FAIL(PSD_ERR_UNSUPPORTED, "the single-forward loop is not built for the approximate cache");
     if (eos_stop && (policy->eos_id < 0 || policy->eos_id >= h->cfg.vocab || policy->eos_id == h->cfg.mask_id))
         PSD_FAIL(PSD_ERR_INVALID_ARG, "eos_id %d: a token id below the vocabulary size %d other than the mask token",
                  policy->eos_id, h->cfg.vocab);
@@ -549,6 +555,7 @@ int32_t decode_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_
     std::vector<int64_t> invocations(B, 0);
     std::vector<int32_t> eos_pos(B, -1);
     std::vector<char> stopped(B, 0);
+    std::vector<char> have_tables(B, 0);   // single-forward loop: (top1, conf)[b] hold the accepted draft's verifier output
     for (int b = 0; b < B; ++b)
         if (advance && starts[b] >= N) state[b] = DONE;
     auto upload_starts = [&]() -> int32_t {
@@ -604,6 +611,7 @@ int32_t decode_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_
             std::vector<int> empty;
             for (int b = 0; b < B; ++b) {
                 if (state[b] != ENTER) continue;
+                have_tables[b] = 0;        // the call that enters a block is a stage-1 call
                 if (hc[b] > 0) state[b] = RUN;
                 else empty.push_back(b);
             }
@@ -623,13 +631,25 @@ int32_t decode_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_
             PSD_FAIL(PSD_ERR_DEVICE, "no block resolved in %d iterations: the model calls make no progress (k_min = %d; non-finite "
                      "logits?)", L + 1, policy->k_min);
         ++iterations;
-        // stage 1: one forward over the running sequences, policy commit, drafts
-        const int S1 = (int)active.size();
-        for (int s = 0; s < S1; ++s) hrows[s] = active[s];
-        PSD_HIP(hipMemcpyAsync(rows, hrows, sizeof(int32_t) * S1, hipMemcpyHostToDevice, st));
-        CHECK(model_call(tokens, rows, S1, 1, bs_seq, top1, conf, st));
-        for (int b : active) invocations[b] += 1;
-        launch_select_unmask(tokens, B, N, bs_seq, L, top1, conf, *policy, mask_id, nullptr, nullptr, n_left, devstats, st);
+        // stage 1: one forward over the running sequences (those without tables of their own), policy commit, drafts
+        std::vector<int> fresh;
+        for (int b : active)
+            if (!have_tables[b]) fresh.push_back(b);
+        const int S1 = (int)fresh.size();
+        if (S1 > 0) {
+            for (int s = 0; s < S1; ++s) hrows[s] = fresh[s];
+            PSD_HIP(hipMemcpyAsync(rows, hrows, sizeof(int32_t) * S1, hipMemcpyHostToDevice, st));
+            CHECK(model_call(tokens, rows, S1, 1, bs_seq, top1, conf, st));
+            for (int b : fresh) invocations[b] += 1;
+            const int32_t *only = nullptr;
+            if (single_forward) {   // the others committed already, by the policy on their accepted draft's output
+                std::vector<char> mark(B, 0);
+                for (int b : fresh) mark[b] = 1;
+                CHECK(upload_flags([&](int b) { return mark[b] != 0; }));
+                only = d_flags;
+            }
+            launch_select_unmask(tokens, B, N, bs_seq, L, top1, conf, *policy, mask_id, nullptr, nullptr, n_left, devstats, only, st);
+        }
         launch_build_drafts(tokens, B, N, bs_seq, L, top1, conf, g, mask_id, sigma, m, drafts, st);
         if (eos_stop) launch_eos_stop(tokens, B, N, bs_seq, L, policy->eos_id, n_left, m, devstats, st);
         PSD_HIP(hipMemcpyAsync(hc, m, sizeof(int32_t) * B, hipMemcpyDeviceToHost, st));
@@ -646,7 +666,9 @@ int32_t decode_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_
             CHECK(model_call(drafts, rows, S3, K, bs_draft, v_top1, v_conf, st));
             for (int b : vset) invocations[b] += 1;
             launch_accept(tokens, drafts, B, N, bs_seq, L, sigma, m, g, *policy, mask_id, v_top1, v_conf, k_star, accepted,
-                          n_left, devstats, st);
+                          n_left, devstats, single_forward ? top1 : nullptr, single_forward ? conf : nullptr, st);
+            if (single_forward)
+                for (int b : vset) have_tables[b] = 1;
             if (eos_stop) launch_eos_stop(tokens, B, N, bs_seq, L, policy->eos_id, n_left, nullptr, devstats, st);
         }
         // who is done with the block: no masks left, or stopped on an EOS token (its mask counts were zeroed)

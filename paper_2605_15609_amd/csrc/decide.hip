@@ -41,9 +41,11 @@ __global__ __launch_bounds__(WAVE) void select_unmask_kernel(int32_t *__restrict
                                                              int32_t mask_id, uint8_t *__restrict__ transfer_mask,
                                                              int32_t *__restrict__ n_selected,
                                                              int32_t *__restrict__ n_left,
-                                                             int32_t *__restrict__ devstats) {
+                                                             int32_t *__restrict__ devstats,
+                                                             const int32_t *__restrict__ only) {
     const int b = blockIdx.x;
     const int j = threadIdx.x;
+    if (only && only[b] == 0) return;   // uniform per workgroup: this sequence had no stage-1 call
     const int block_start = bs.of_row(b);
     int32_t *row = tokens + (int64_t)b * N + block_start;
     const bool in = j < L;
@@ -107,7 +109,8 @@ __global__ __launch_bounds__(WAVE) void accept_kernel(int32_t *__restrict__ toke
                                                       int32_t mask_id, const int32_t *__restrict__ v_top1,
                                                       const float *__restrict__ v_conf, int32_t *__restrict__ k_star_out,
                                                       uint8_t *__restrict__ accepted_out, int32_t *__restrict__ n_left,
-                                                      int32_t *__restrict__ devstats) {
+                                                      int32_t *__restrict__ devstats, int32_t *__restrict__ adopt_top1,
+                                                      float *__restrict__ adopt_conf) {
     __shared__ int s_rank[WAVE];              // block position -> rank in sigma, or -1
     __shared__ uint64_t s_S[PSD_MAX_NODES];   // S_k as a bit set over block positions
     __shared__ uint64_t s_ok[PSD_MAX_NODES][PSD_MAX_NODES];   // [p][k]: positions where edge test passes
@@ -206,6 +209,11 @@ __global__ __launch_bounds__(WAVE) void accept_kernel(int32_t *__restrict__ toke
     const bool live = in && dtok == mask_id;
     const bool take = live && ((s_commit[k_star] >> j) & 1ull);
     if (in) tokens[(int64_t)b * N + block_start + j] = take ? v_top1[((int64_t)b * K + k_star) * L + j] : dtok;
+    // single-forward loop: k*'s verifier output becomes the table the next drafts are drawn from
+    if (adopt_top1 && in) {
+        adopt_top1[(int64_t)b * L + j] = v_top1[((int64_t)b * K + k_star) * L + j];
+        adopt_conf[(int64_t)b * L + j] = v_conf[((int64_t)b * K + k_star) * L + j];
+    }
     const int n_live = __popcll(__ballot(live));
     const int n_take = __popcll(__ballot(take));
     if (j == 0) {
@@ -278,9 +286,9 @@ void launch_finish_counts(const int32_t *tokens, int B, int N, BlockStart block_
 
 void launch_select_unmask(int32_t *tokens, int B, int N, BlockStart block_start, int L, const int32_t *top1, const float *conf,
                           psd_policy policy, int32_t mask_id, uint8_t *transfer_mask, int32_t *n_selected,
-                          int32_t *n_left, int32_t *devstats, hipStream_t st) {
+                          int32_t *n_left, int32_t *devstats, const int32_t *only, hipStream_t st) {
     hipLaunchKernelGGL(select_unmask_kernel, dim3(B), dim3(WAVE), 0, st, tokens, N, block_start, L, top1, conf, policy,
-                       mask_id, transfer_mask, n_selected, n_left, devstats);
+                       mask_id, transfer_mask, n_selected, n_left, devstats, only);
 }
 
 void launch_build_drafts(const int32_t *tokens, int B, int N, BlockStart block_start, int L, const int32_t *top1,
@@ -293,7 +301,7 @@ void launch_build_drafts(const int32_t *tokens, int B, int N, BlockStart block_s
 void launch_accept(int32_t *tokens, const int32_t *drafts, int B, int N, BlockStart block_start, int L, const int32_t *sigma,
                    const int32_t *m, const GraphArg &g, psd_policy policy, int32_t mask_id, const int32_t *v_top1,
                    const float *v_conf, int32_t *k_star, uint8_t *accepted, int32_t *n_left, int32_t *devstats,
-                   hipStream_t st) {
+                   int32_t *adopt_top1, float *adopt_conf, hipStream_t st) {
     hipLaunchKernelGGL(accept_kernel, dim3(B), dim3(WAVE), 0, st, tokens, drafts, N, block_start, L, sigma, m, g, policy,
-                       mask_id, v_top1, v_conf, k_star, accepted, n_left, devstats);
+                       mask_id, v_top1, v_conf, k_star, accepted, n_left, devstats, adopt_top1, adopt_conf);
 }

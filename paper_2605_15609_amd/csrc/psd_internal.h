@@ -90,16 +90,18 @@ void launch_eos_stop(const int32_t *tokens, int B, int N, BlockStart block_start
 // only[b] != 0 selects the sequences to finish (NULL: all); their counters of resolved positions are ADDED to
 void launch_finish_counts(const int32_t *tokens, int B, int N, BlockStart block_start, int L, int32_t mask_id, int32_t eos_stop,
                           int32_t eos_id, int32_t *devstats, const int32_t *only, hipStream_t st);
+// only[b] != 0 selects the sequences the policy is applied to (NULL: all); the others keep tokens and n_left
 void launch_select_unmask(int32_t *tokens, int B, int N, BlockStart block_start, int L, const int32_t *top1,
                           const float *conf, psd_policy policy, int32_t mask_id, uint8_t *transfer_mask,
-                          int32_t *n_selected, int32_t *n_left, int32_t *devstats, hipStream_t st);
+                          int32_t *n_selected, int32_t *n_left, int32_t *devstats, const int32_t *only, hipStream_t st);
 void launch_build_drafts(const int32_t *tokens, int B, int N, BlockStart block_start, int L, const int32_t *top1,
                          const float *conf, const GraphArg &g, int32_t mask_id, int32_t *sigma, int32_t *m,
                          int32_t *drafts, hipStream_t st);
 void launch_accept(int32_t *tokens, const int32_t *drafts, int B, int N, BlockStart block_start, int L,
                    const int32_t *sigma, const int32_t *m, const GraphArg &g, psd_policy policy, int32_t mask_id,
                    const int32_t *v_top1, const float *v_conf, int32_t *k_star, uint8_t *accepted,
-                   int32_t *n_left, int32_t *devstats, hipStream_t st);
+                   int32_t *n_left, int32_t *devstats, int32_t *adopt_top1, float *adopt_conf, hipStream_t st);
+// (adopt_top1 / adopt_conf [B, L], or NULL: receive the verifier output of the accepted draft k* of every sequence with m > 0)
 
 // ---------------------------------------------------------------- forward (forward.hip)
 // workspace for the K-split partial sums of a residual contraction: at most 7 parts of at most 128 rows

@@ -165,6 +165,34 @@ def test_fp32_free_running_cached_decode_matches_the_oracle_decode():
                (o2.invocations, o2.tokens, o2.tokens_counted, o2.stopped, o2.eos_pos)
 
 
+def test_fp32_single_forward_cached_decode_matches_the_oracle_variant():
+    """The single-forward loop on the KV-cached model calls: tokens and counters equal the oracle's single-forward decode
+    with the block-causal model, block by block."""
+    import paper_2605_15609_amd as psd
+    shape = FP32
+    L, P, G = 16, 32, 48
+    N = P + G
+    host = inp.draw_model(shape, N)
+    model = psd.Model.from_host(host, DEV)
+    for K, tau in ((3, 0.9), (4, 0.05)):
+        tokens0 = np.full((1, N), shape.mask_id, dtype=np.int32)
+        tokens0[0, :P] = inp.draw_prompt(shape.vocab, P, 61)
+        d = _dev(tokens0)
+        cache = psd.KvCache(model, 1, N)
+        psd.psd_kv_prefill(model, d, P, L, cache)
+        stats = [psd.Stats()]
+        for start in range(P, N, L):
+            stats = psd.psd_decode_block_cached(model, d, start, L, psd.Policy(tau, 1, 0, single_forward=True), psd.chain_graph(K),
+                                                cache, stats)
+        ref, ostats = orc.decode(orc.model_confidence_fn(host, block_causal=True), tokens0[0], P, L, orc.Policy(tau, 1, 0),
+                                 orc.chain_graph(K), shape.mask_id, single_forward=True)
+        assert (d.cpu().numpy()[0] == ref).all(), (K, tau)
+        s = stats[0]
+        assert (s.invocations, s.tokens_policy, s.tokens_draft, s.tokens_postverify) == \
+               (ostats.invocations, ostats.tokens_policy, ostats.tokens_draft, ostats.tokens_postverify)
+        assert s.invocations == G // L + sum(s.depth_hist)
+
+
 def test_bf16_batched_cached_decode_equals_sequences_alone_and_the_masked_decode():
     import paper_2605_15609_amd as psd
     shape = dataclasses.replace(BF16["mha-dh64"], logit_scale=14.0)

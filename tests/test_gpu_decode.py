@@ -492,6 +492,90 @@ def test_psd_decode_walks_every_sequence_through_its_own_blocks_like_the_oracle(
         psd.psd_decode(model, _dev(tokens0), [16, 30, 48], L, psd.Policy(), psd.chain_graph(2))     # not whole blocks
 
 
+def test_single_forward_loop_matches_the_oracle_variant_sequence_by_sequence():
+    """policy.single_forward: one model call per iteration -- the post-verification commit is the next stage-1 commit and the
+    next drafts come from the accepted draft's verifier output.  fp32 model, exact: three sequences on blocks of their own in
+    one batch; tokens and every counter must equal the oracle's single-forward decode of each sequence alone, for chains and
+    a subset lattice, with and without EOS early stopping; the calls saved against the literal loop are counted."""
+    import paper_2605_15609_amd as psd
+    from tests.gpu_common import gpu_graph
+    shape = inp.WORKLOADS[1].shape
+    N, L, B = 64, 16, 3
+    host = inp.draw_model(shape, N)
+    model = psd.Model.from_host(host, DEV)
+    fn = orc.model_confidence_fn(host)
+    prompts = (16, 32, 48)
+    tokens0 = np.full((B, N), shape.mask_id, dtype=np.int32)
+    for b, P in enumerate(prompts):
+        tokens0[b, :P] = inp.draw_prompt(shape.vocab, P, 700 + b, "uniform")
+    differs = 0
+    for ograph, tau, k_max in ((orc.chain_graph(2), 0.9, 0), (orc.chain_graph(4), 0.02, 0), (orc.chain_graph(3), float("inf"), 0),
+                               (orc.Graph((frozenset(), frozenset({0}), frozenset({1}), frozenset({0, 1}))), 0.05, 0), (orc.chain_graph(4), 0.02, 2)):
+        opol, ggraph = orc.Policy(tau, 1, k_max), gpu_graph(ograph)
+        refs = [orc.decode(fn, tokens0[b], prompts[b], L, opol, ograph, shape.mask_id, single_forward=True) for b in range(B)]
+        literal = [orc.decode(fn, tokens0[b], prompts[b], L, opol, ograph, shape.mask_id) for b in range(B)]
+        d = _dev(tokens0)
+        stats, starts, iters = psd.psd_decode(model, d, list(prompts), L, psd.Policy(tau, 1, k_max, single_forward=True), ggraph)
+        got = d.cpu().numpy()
+        assert all(s >= N for s in starts)
+        for b in range(B):
+            assert (got[b] == refs[b][0]).all(), (ograph.K, tau, b)
+            assert _counters(stats[b]) == _counters(refs[b][1]), (ograph.K, tau, b)
+            n_blocks = (N - prompts[b]) // L
+            # one stage-1 call per block entered, every other call is a batched verification
+            assert stats[b].invocations == n_blocks + sum(stats[b].depth_hist), (ograph.K, tau, b)
+            assert stats[b].invocations <= literal[b][1].invocations or not (got[b] == literal[b][0]).all()
+            differs += int(not (got[b] == literal[b][0]).all())
+        # the literal loop through the same entry point is untouched by the flag being there
+        d0 = _dev(tokens0)
+        st0, _, _ = psd.psd_decode(model, d0, list(prompts), L, psd.Policy(tau, 1, k_max), ggraph)
+        for b in range(B):
+            assert (d0.cpu().numpy()[b] == literal[b][0]).all() and _counters(st0[b]) == _counters(literal[b][1])
+        # EOS early stopping: a token the single-forward run of sequence 0 produces in its second block
+        eos = int(refs[0][0][prompts[0] + L + 3])
+        d2 = _dev(tokens0)
+        stats2, _, _ = psd.psd_decode(model, d2, list(prompts), L, psd.Policy(tau, 1, k_max, eos_id=eos, single_forward=True), ggraph)
+        for b in range(B):
+            ref, ost = orc.decode(fn, tokens0[b], prompts[b], L, opol, ograph, shape.mask_id, eos_id=eos, single_forward=True)
+            assert (d2.cpu().numpy()[b] == ref).all(), (ograph.K, tau, b, "eos")
+            assert _counters(stats2[b]) == _counters(ost), (ograph.K, tau, b, "eos")
+        assert stats2[0].stopped
+    print(f"[decode] single-forward loop: {differs} of {5 * B} generations differ from the literal loop's", flush=True)
+    # one block through psd_decode_block, every sequence on its own start
+    d = _dev(tokens0)
+    stats = psd.psd_decode_block(model, d, list(prompts), L, psd.Policy(0.9, 1, 0, single_forward=True), psd.chain_graph(3))
+    for b in range(B):
+        ref, ost = orc.decode_block(fn, tokens0[b], prompts[b], L, orc.Policy(0.9, 1, 0), orc.chain_graph(3), shape.mask_id,
+                                    single_forward=True)
+        assert (d.cpu().numpy()[b] == ref).all() and _counters(stats[b]) == _counters(ost), b
+
+
+def test_single_forward_loop_bf16_batch_equals_sequences_alone():
+    import paper_2605_15609_amd as psd
+    shape = inp.cut_down(inp.WORKLOADS[2].shape, n_layers=2, vocab=4000, seed=33, logit_scale=14.0)
+    N, L, K, B = 160, 32, 4, 4
+    host = inp.draw_model(shape, N)
+    model = psd.Model.from_host(host, DEV)
+    policy, graph = psd.Policy(0.9, 1, 0, single_forward=True), psd.chain_graph(K)
+    starts = [64, 96, 32, 64]
+    tokens = np.full((B, N), shape.mask_id, dtype=np.int32)
+    for b in range(B):
+        tokens[b, :starts[b]] = inp.draw_prompt(shape.vocab, starts[b], 80 + b)
+    together = _dev(tokens)
+    stats, at, _ = psd.psd_decode(model, together, starts, L, policy, graph)
+    saved = 0
+    for b in range(B):
+        alone = _dev(tokens[b: b + 1])
+        s, _, _ = psd.psd_decode(model, alone, [starts[b]], L, policy, graph)
+        assert (alone[0] == together[b]).all(), b
+        assert _counters(s[0]) == _counters(stats[b]), b
+        assert (together[b] != shape.mask_id).all() and stats[b].tokens == N - starts[b]
+        lit = _dev(tokens[b: b + 1])
+        s_lit, _, _ = psd.psd_decode(model, lit, [starts[b]], L, psd.Policy(0.9, 1, 0), graph)
+        saved += s_lit[0].invocations - s[0].invocations
+    print(f"[decode] single-forward loop, bf16: {saved} model calls fewer than the literal loop over {B} sequences", flush=True)
+
+
 def test_psd_decode_block_with_one_block_start_per_sequence():
     import paper_2605_15609_amd as psd
     shape = inp.cut_down(inp.WORKLOADS[2].shape, n_layers=2, vocab=4000, seed=33, logit_scale=14.0)

@@ -38,7 +38,7 @@ def test_structure_layouts_agree_with_the_binding(lib):
     assert lib.psd_struct_sizes(got, n) == n == 8
     assert list(got) == [ctypes.sizeof(t) for t in (B._Config, B._Weights, B._Policy, B._Graph, B._Stats, B._Work, B._GraphScore,
                                                     B._DebugLayout)]
-    assert got[2] == 20 and got[6] == 40           # psd_policy: float + 4 x int32; psd_graph_score: 3 doubles + 2 x int64
+    assert got[2] == 24 and got[6] == 40           # psd_policy: float + 5 x int32; psd_graph_score: 3 doubles + 2 x int64
 
 
 def test_host_only_entry_points(lib):
