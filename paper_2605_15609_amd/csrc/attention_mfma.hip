@@ -94,7 +94,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(const bf16_t *__r
     // K and V^T tiles go global -> LDS directly (buffer_load ... lds), 1 KB per instruction, with the XOR
     // swizzle applied on the global side: the lane that lands at (row, slot) fetches chunk slot ^ key(row),
     // key(row) = kkey(row) for K rows and (row >> 1) & 7 for the 128-byte V^T rows.  Row groups are dealt round-robin to the wavefronts.  Keys past the end of
-    // the sequence are rejected by the descriptor (K) or read the zero padding of vT.
+    // the sequence are rejected by the descriptor (K); value slots past it are zeroed in registers in the last tile.
     const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<bf16_t *>(seq) + (n_heads + kvh) * DH, 0, (int)(((int64_t)N * row_w - (n_heads + kvh) * DH) * 2), 0x00020000);
     const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(
@@ -238,7 +238,20 @@ __global__ __launch_bounds__(NW * 64, 2) void attention_kernel(const bf16_t *__r
             for (int ct = 0; ct < CT; ++ct) {
                 const int r = ct * 32 + lrow;
                 const int c = kg * 2 + lhalf;
-                const bf16x8 vf = *reinterpret_cast<const bf16x8 *>(sv + r * VROW + ((c ^ ((r >> 1) & 7)) << 4));
+                bf16x8 vf = *reinterpret_cast<const bf16x8 *>(sv + r * VROW + ((c ^ ((r >> 1) & 7)) << 4));
+                if (k0 + BKV > limit) {
+                    // value slots past the end of the segment hold whatever the memory held (the tail of a cache row,
+                    // the row padding): their probabilities are zero, but 0 x NaN is NaN, so the slots are zeroed
+                    // (slot order inside a group of 16 keys: this lane's elements 0-3 are keys 4*half + 0..3, elements
+                    // 4-7 keys 8 + 4*half + 0..3)
+                    const int n_lo = limit - (k0 + kg * 16 + 4 * lhalf), n_hi = n_lo - 8;
+                    u32x4 w = __builtin_bit_cast(u32x4, vf);
+                    w.x &= n_lo >= 2 ? 0xffffffffu : n_lo == 1 ? 0x0000ffffu : 0u;
+                    w.y &= n_lo >= 4 ? 0xffffffffu : n_lo == 3 ? 0x0000ffffu : 0u;
+                    w.z &= n_hi >= 2 ? 0xffffffffu : n_hi == 1 ? 0x0000ffffu : 0u;
+                    w.w &= n_hi >= 4 ? 0xffffffffu : n_hi == 3 ? 0x0000ffffu : 0u;
+                    vf = as_bf16x8(w);
+                }
                 acc_o[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kg], acc_o[ct], 0, 0, 0);
             }
         }
@@ -365,11 +378,8 @@ static void launch_att(const bf16_t *qkv, int ld_qkv, const bf16_t *vT, int S, i
     static_assert(smem <= 160 * 1024, "LDS rings exceed the 160 KB of a CU");
     static_assert(KSP == 1 || (2 + DH / 32 * 16) * 64 * 4 <= NSTG * (BKV * DH * 2 + DH * BKV * 2), "merge data fit a ring");
     auto kern = attention_kernel<DH, NW, NSTG, KSP>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        attr_done = true;
-    }
+    static std::atomic<uint64_t> lds_raised{0};   // one per instantiation
+    ensure_dynamic_lds(reinterpret_cast<const void *>(kern), smem, lds_raised);
     constexpr int q_per_wg = KSP > 1 ? 32 : 32 * NW;
     dim3 grid((N + q_per_wg - 1) / q_per_wg, n_heads, S);
     hipLaunchKernelGGL(kern, grid, dim3(NW * 64), smem, st, qkv, ld_qkv, vT, (int)vt_row_stride(N), N, n_heads, n_kv_heads, out,

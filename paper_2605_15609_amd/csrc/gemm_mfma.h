@@ -406,11 +406,8 @@ void launch_cfg(const bf16_t *X, const bf16_t *Y, const bf16_t *Y2, int M, int N
     constexpr int smem = (NSA * BM + NSB * BN) * ROW_BYTES;
     static_assert(smem <= 160 * 1024, "LDS ring exceeds the 160 KB of a CU");
     auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, EPI, NSA, NSB>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        attr_done = true;
-    }
+    static std::atomic<uint64_t> lds_raised{0};   // one per instantiation
+    ensure_dynamic_lds(reinterpret_cast<const void *>(kern), smem, lds_raised);
     if (EPI != EPI_RESIDUAL) k_splits = 1;
     hipLaunchKernelGGL(kern, dim3(n_tiles * k_splits), dim3(WGM * WGN * 64), smem, st, X, Y, Y2, M, Nout, Kin, ldx, ldy, bias, out, resid,
                        ldo, tiles_n, n_tiles, t1, k_splits, partial, gemm_tile_group_m());

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <vector>
 
 #include "psd.h"
@@ -84,6 +85,17 @@ struct GraphArg {
     int32_t K;
     uint64_t rank_set[PSD_MAX_NODES];
 };
+
+// Raises a kernel's dynamic LDS limit once per device (bit d of `done` = device d has it).  Callable from several
+// threads: two that race both set the same value.
+inline void ensure_dynamic_lds(const void *kernel, int bytes, std::atomic<uint64_t> &done) {
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return;
+    (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    done.fetch_or(bit, std::memory_order_release);
+}
 
 void launch_eos_stop(const int32_t *tokens, int B, int N, BlockStart block_start, int L, int32_t eos_id, int32_t *n_left, int32_t *m,
                      int32_t *devstats, hipStream_t st);
@@ -238,9 +250,8 @@ void launch_head_finish(const float *row_sum, const int32_t *row_arg, const int3
                         float *conf, hipStream_t st);
 
 // gemm_mfma.hip (bf16; Nout, Kin multiples of 64)
-// tile configuration the dispatcher picks for a shape (0: 128x128, 1: 256x256, 2: 256x128, 3: 128x64,
-// 4: 128x192 workgroup tiles on a 2-stage LDS ring; 5: 128x64, 6: 128x128, 7: 64x64 on a 4-stage ring;
-// 8, 9: 256x256 with 8 wavefronts as 2x4 / 4x2)
+// index of the tile configuration the dispatcher picks for a shape; gemm_bf16_tile_name(i) describes configuration i
+// (workgroup tile, wavefronts, LDS ring depths), 0 <= i < gemm_bf16_tile_count()
 int gemm_bf16_tile(int64_t M, int Nout, int epi);
 int gemm_bf16_tile_count();
 // K-split of a residual contraction (1 = none).  With s > 1 parts, launch_gemm_bf16_split adds part 0 into
@@ -250,7 +261,10 @@ void launch_gemm_bf16_split(const bf16_t *A, const bf16_t *W, int64_t M, int Nou
                             float *partial, int splits, hipStream_t st);
 void launch_fold_partials(float *resid, int64_t rows, int cols, int ldo, const float *partial, int n_partial, hipStream_t st);
 const char *gemm_bf16_tile_name(int tile);
-void gemm_bf16_force_tile(int tile);   // debug: -1 = automatic
+// debug, process-wide (not per handle; not for use while another thread launches): -1 = automatic; otherwise bits 0-7
+// the tile (0xff = automatic), bits 8-15 the K-split of residual contractions (0 = automatic), bits 16-23 the band
+// height of the tile order (0 = unchanged)
+void gemm_bf16_force_tile(int tile);
 // 256 workgroups x 4 wavefronts x iters x 16 MFMAs (32x32x16 bf16) on the given operand data; sink >= 4 MiB
 void launch_mfma_rate(const void *operands, int n_vec16, int iters, void *sink, hipStream_t st);
 // A [M, Kin] with row stride lda, W / W2 [Nout, Kin] with row stride ldw (elements)

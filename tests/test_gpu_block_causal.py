@@ -123,6 +123,31 @@ def test_bf16_cached_forward_matches_the_oracle_and_the_masked_device_path(name,
     assert np.abs(m_logits - v_logits).max() < 2e-2
 
 
+@pytest.mark.parametrize("name", list(BF16))
+def test_bf16_cached_forward_does_not_depend_on_what_the_cache_memory_held(name):
+    """Only the first block_start slots of a cache are context.  With the rest of the cache memory holding NaN bit patterns
+    (an allocation nobody cleared) the result must be bit-identical to the one over a cleared cache: the last, partial key
+    tile of the prefix reads value slots past the end, and 0 x NaN would poison every query."""
+    import paper_2605_15609_amd as psd
+    shape = BF16[name]
+    L = 32
+    P, N = 3 * L, 6 * L                                    # a prefix of 96 keys: one full 64-key tile and a half
+    model = psd.Model.from_host(inp.draw_model(shape, N), DEV)
+    t, start = _state(shape, N, P, L, 0, 33, 6)
+    d = _dev(np.stack([t, t]))
+    results = []
+    for poison in (False, True):
+        cache = psd.KvCache(model, 2, N)
+        if poison:
+            cache.mem.fill_(0xff)                          # bf16 0xffff: a NaN in every slot
+        psd.psd_kv_prefill(model, d, start, L, cache)
+        top1, conf, logits = psd.psd_forward_confidence_cached(model, d, start, L, cache, want_logits=True)
+        results.append((top1.cpu().numpy(), conf.cpu().numpy(), logits.cpu().numpy()))
+    assert np.isfinite(results[1][2]).all()
+    for a, b in zip(results[0], results[1]):
+        assert (a == b).all()
+
+
 def test_fp32_free_running_cached_decode_matches_the_oracle_decode():
     import paper_2605_15609_amd as psd
     shape = FP32
