@@ -203,7 +203,9 @@ int32_t psd_forward_logits(psd_handle *h, const int32_t *tokens, int32_t S, int3
                            void *ws, int64_t ws_bytes, void *stream);
 
 /* Debug switch for numeric cross-checks: bit 0 runs the layer contractions, bit 1 the
- * attention, bit 2 the LM-head on the plain (non-MFMA) kernels.  0 (default) = MFMA path. */
+ * attention, bit 2 the LM-head on the plain (non-MFMA) kernels; bit 3 keeps the rotary embedding and the
+ * transpose of V in a kernel of their own instead of the QKV projection's epilogue (same bits either way).
+ * 0 (default) = MFMA path. */
 int32_t psd_debug_set_plain(psd_handle *h, int32_t mask);
 
 /* Debug hook for parity checks of one layer at full width: runs layer `layer` of the model alone on a residual
@@ -228,6 +230,15 @@ int32_t psd_debug_layer(psd_handle *h, int32_t layer, float *hidden, int32_t S, 
  * and psd_kernel_gemm_tile_name for the numbering; -1 = pick per shape; a tile that cannot run the
  * epilogue asked for is ignored).  Process-wide. */
 int32_t psd_debug_force_gemm_tile(int32_t tile);
+/* Optional: the block loops (psd_decode, psd_decode_block) replay the whole-sequence model calls of a shape they have
+ * seen twice as HIP graphs.  Results are bit-identical to eager launches.  Off by default: on the one workload where
+ * a model call is ~75 kernels of 4-11 microseconds (8 layers, d_model 512) the queue already runs them back to back and
+ * the graph changes nothing (119 ms per decode either way); the time goes to the kernels' own floor, not to launches.
+ * enabled = 1 / 0 switches it on / off for the handle, a negative value leaves it; replays (may be NULL) receives the
+ * number of graph launches so far.  A graph holds the addresses the call was captured with (tokens, tables, workspace):
+ * up to 24 distinct calls are kept, least recently used replaced.  Calls that are being timed by psd_probe_begin and
+ * the KV-cached calls always launch eagerly. */
+int32_t psd_debug_set_graphs(psd_handle *h, int32_t enabled, int64_t *replays);
 
 /* Stage 1 commit (Eq. 1): applies pi to every sequence in place.
  *   tokens device int32 [B, N] (updated); top1/conf device [B, L] (read);

@@ -132,6 +132,7 @@ def load_library():
         "psd_kernel_head_scratch_bytes": (i64, [i32, i32]),
         "psd_kernel_head_confidence_bf16": (i32, [vp, vp, i32, i32, i32, C.c_float, i32, vp, vp, vp, vp]),
         "psd_debug_force_gemm_tile": (i32, [i32]),
+        "psd_debug_set_graphs": (i32, [vp, i32, C.POINTER(i64)]),
         "psd_kernel_packed_bytes": (i64, [i64, i32]),
         "psd_kernel_pack_rows": (i32, [vp, i64, i32, vp, vp]),
         "psd_kernel_head_stream_bf16": (i32, [vp, vp, i32, i32, i32, C.c_float, i32, vp, vp, vp, vp]),
@@ -364,6 +365,13 @@ class Model:
 
     def set_plain(self, mask: int):
         _check(self.lib.psd_debug_set_plain(self.handle, int(mask)))
+
+    def set_graphs(self, enabled: Optional[bool] = None) -> int:
+        """Switches the HIP-graph replay of the block loops' model calls on / off (None: leave); returns the number of
+        graph launches so far."""
+        n = C.c_int64()
+        _check(self.lib.psd_debug_set_graphs(self.handle, -1 if enabled is None else int(bool(enabled)), C.byref(n)))
+        return int(n.value)
 
     def probe_begin(self, epilogue: int, tile: int, max_launches: int = 65536):
         _check(self.lib.psd_probe_begin(self.handle, epilogue, tile, max_launches))

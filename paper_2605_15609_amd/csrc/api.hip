@@ -123,6 +123,10 @@ DecodeScratch plan_decode(int64_t B, int64_t N, int64_t L, int64_t K) {
 
 }   // namespace
 
+static std::atomic<int> g_kernel_choice_epoch{0};
+int kernel_choice_epoch() { return g_kernel_choice_epoch.load(); }
+void bump_kernel_choice_epoch() { g_kernel_choice_epoch.fetch_add(1); }
+
 extern "C" {
 
 const char *psd_status_string(int32_t status) {
@@ -222,6 +226,9 @@ int32_t psd_destroy(psd_handle *h) {
     for (hipEvent_t e : h->probe.ev) (void)hipEventDestroy(e);
     for (hipEvent_t e : h->probe_head.ev) (void)hipEventDestroy(e);
     for (hipEvent_t e : h->probe_call.ev) (void)hipEventDestroy(e);
+    for (psd_handle::GraphEntry &g : h->graphs)
+        if (g.exec) (void)hipGraphExecDestroy(g.exec);
+    if (h->capture_stream) (void)hipStreamDestroy(h->capture_stream);
     delete h;
     return PSD_OK;
 }
@@ -229,11 +236,20 @@ int32_t psd_destroy(psd_handle *h) {
 int32_t psd_debug_set_plain(psd_handle *h, int32_t mask) {
     if (!h) PSD_FAIL(PSD_ERR_INVALID_ARG, "handle is NULL");
     h->plain_mask = mask;
+    bump_kernel_choice_epoch();
     return PSD_OK;
 }
 
 int32_t psd_debug_force_gemm_tile(int32_t tile) {
     gemm_bf16_force_tile(tile);
+    bump_kernel_choice_epoch();
+    return PSD_OK;
+}
+
+int32_t psd_debug_set_graphs(psd_handle *h, int32_t enabled, int64_t *replays) {
+    if (!h) PSD_FAIL(PSD_ERR_INVALID_ARG, "handle is NULL");
+    if (replays) *replays = (int64_t)h->graph_replays;
+    if (enabled >= 0) h->graphs_enabled = enabled != 0;
     return PSD_OK;
 }
 
@@ -514,8 +530,8 @@ int32_t decode_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_
 
     // one model call: forward + top-1 confidence of the sequences listed in `rows` (device) out of src [*, N]
     bool refreshed = false;
-    auto model_call_untimed = [&](const int32_t *src, const int32_t *rows_dev, int S, int seqs_per_cache, const BlockStart &bs,
-                                  int32_t *t1, float *cf, hipStream_t st_) -> int32_t {
+    auto model_call_eager = [&](const int32_t *src, const int32_t *rows_dev, int S, int seqs_per_cache, const BlockStart &bs,
+                                int32_t *t1, float *cf, hipStream_t st_) -> int32_t {
         if (dual && !refreshed) {   // the stage-1 call that enters the block: exact, and it freezes the context
             refreshed = true;
             CHECK(run_forward_hidden(h, src, rows_dev, S, N, bs, L, ws, fwd_bytes, st_, kv));
@@ -530,6 +546,61 @@ int32_t decode_impl(psd_handle *h, int32_t *tokens, int32_t B, int32_t N, int32_
             CHECK(run_forward_hidden(h, src, rows_dev, S, N, bs, L, ws, fwd_bytes, st_));
         }
         return run_head_confidence(h, src, rows_dev, S, N, bs, L, t1, cf, rows_dev, ws, st_, plan_N);
+    };
+    // Whole-sequence calls go through the handle's graph cache: what changes between two calls of one key (the tokens,
+    // the row list, the block starts) lives in device memory the kernels read, not in their arguments.
+    auto model_call_untimed = [&](const int32_t *src, const int32_t *rows_dev, int S, int seqs_per_cache, const BlockStart &bs,
+                                  int32_t *t1, float *cf, hipStream_t st_) -> int32_t {
+        const bool probing = h->probe.enabled || h->probe_head.enabled || h->probe_call.enabled;
+        if (kv || !h->graphs_enabled || probing) return model_call_eager(src, rows_dev, S, seqs_per_cache, bs, t1, cf, st_);
+        const psd_handle::GraphKey key = {src, rows_dev, t1, cf, ws, bs.per_seq, fwd_bytes, S, N, L, bs.common, bs.rows_per_seq,
+                                          kernel_choice_epoch()};
+        psd_handle::GraphEntry *e = nullptr;
+        for (psd_handle::GraphEntry &g : h->graphs)
+            if (g.key == key) e = &g;
+        if (!e) {   // first sight: eager, and remember the key
+            if (h->graphs.size() < psd_handle::kMaxGraphs) {
+                h->graphs.emplace_back();
+                e = &h->graphs.back();
+            } else {
+                e = &h->graphs[0];
+                for (psd_handle::GraphEntry &g : h->graphs)
+                    if (g.last_use < e->last_use) e = &g;
+                if (e->exec) (void)hipGraphExecDestroy(e->exec);
+                *e = psd_handle::GraphEntry();
+            }
+            e->key = key;
+            e->last_use = ++h->graph_clock;
+            return model_call_eager(src, rows_dev, S, seqs_per_cache, bs, t1, cf, st_);
+        }
+        e->last_use = ++h->graph_clock;
+        if (!e->exec && !e->failed) {   // second sight: capture on the handle's own stream (the caller's may be the null stream)
+            if (!h->capture_stream && hipStreamCreateWithFlags(&h->capture_stream, hipStreamNonBlocking) != hipSuccess) {
+                h->capture_stream = nullptr;
+                e->failed = true;
+            }
+            if (!e->failed) {
+                hipGraph_t graph = nullptr;
+                int32_t rc = PSD_OK;
+                if (hipStreamBeginCapture(h->capture_stream, hipStreamCaptureModeThreadLocal) != hipSuccess) {
+                    e->failed = true;
+                } else {
+                    rc = model_call_eager(src, rows_dev, S, seqs_per_cache, bs, t1, cf, h->capture_stream);
+                    const hipError_t end = hipStreamEndCapture(h->capture_stream, &graph);
+                    if (rc != PSD_OK || end != hipSuccess || !graph ||
+                        hipGraphInstantiate(&e->exec, graph, nullptr, nullptr, 0) != hipSuccess) {
+                        e->exec = nullptr;
+                        e->failed = true;
+                    }
+                    if (graph) (void)hipGraphDestroy(graph);
+                }
+                (void)hipGetLastError();   // a refused capture must not be reported by the next call
+            }
+        }
+        if (!e->exec) return model_call_eager(src, rows_dev, S, seqs_per_cache, bs, t1, cf, st_);
+        PSD_HIP(hipGraphLaunch(e->exec, st_));
+        ++h->graph_replays;
+        return PSD_OK;
     };
     // the same between two HIP events when model calls are being timed (psd_probe_begin kind 5)
     auto model_call = [&](const int32_t *src, const int32_t *rows_dev, int S, int seqs_per_cache, const BlockStart &bs, int32_t *t1,

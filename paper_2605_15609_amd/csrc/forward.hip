@@ -61,8 +61,12 @@ struct Dispatch<float> {
                                         resid, ldo, st);
         return PendingSums();
     }
+    static bool qkv_fused(psd_handle *, const float *, const void *, int64_t, int, int, int, int, int, const float *, float *, int,
+                          float *, int, hipStream_t) {
+        return false;
+    }
     static void rope_attention(psd_handle *h, float *qkv, int ld_qkv, float *, int S, int N, int pos0, int H, int Hkv, int dh,
-                               float *out, const KvPrefix &pre, int block_len, hipStream_t st) {
+                               float *out, const KvPrefix &pre, int block_len, hipStream_t st, bool = false) {
         launch_rope<float>(qkv, ld_qkv, (int64_t)S * N, N, pos0, H, Hkv, dh, h->rope_cos, h->rope_sin, st);
         launch_plain_attention<float>(qkv, ld_qkv, S, N, H, Hkv, dh, out, pre, block_len, st);
     }
@@ -99,12 +103,29 @@ struct Dispatch<bf16_t> {
         }
         return pend;
     }
+    // The QKV projection of [M = S * N, d] rows with wq | wk | wv as one matrix, rotary and the V transpose in its
+    // epilogue; false (nothing launched) when the matrix-core attention will not run on its output, the shape has no
+    // tile that holds whole heads, or a debug switch (plain_mask bit 3) asks for the two-pass form.
+    static bool qkv_fused(psd_handle *h, const bf16_t *A, const void *W, int64_t M, int N, int pos0, int H, int Hkv, int dh,
+                          const float *bias, bf16_t *qkv, int ld_qkv, bf16_t *vT, int block_len, hipStream_t st) {
+        if ((h->plain_mask & (1 | 2 | 8)) || (N % 8) != 0 || (block_len > 0 && block_len < N)) return false;
+        if (h->probe.enabled && (h->probe.epi == EPI_STORE || h->probe.epi == EPI_BIAS)) return false;   // that probe times the plain store
+        const int d = h->cfg.d_model, qkv_w = (H + 2 * Hkv) * dh;
+        const int tile = gemm_bf16_qkv_tile(M, qkv_w, dh, (H + Hkv) * dh, N);
+        if (tile < 0) return false;
+        launch_gemm_bf16_qkv(A, (const bf16_t *)W, M, qkv_w, d, d, d, bias, qkv, ld_qkv, dh, (H + Hkv) * dh, N, pos0, h->rope_cos,
+                             h->rope_sin, vT, (int)vt_row_stride(N), tile, st);
+        return true;
+    }
     // Rotary on q and k (row i of a sequence sits at position pos0 + i), then attention.
     // pre: KV prefix that every own row sees; block_len > 0: context-causal blocks among the own rows (only the
-    // plain kernel masks; the product path of that attention mode keeps finished blocks in the prefix instead)
+    // plain kernel masks; the product path of that attention mode keeps finished blocks in the prefix instead).
+    // rotated: qkv_fused produced qkv and vT, only the attention is left.
     static void rope_attention(psd_handle *h, bf16_t *qkv, int ld_qkv, bf16_t *vT, int S, int N, int pos0, int H, int Hkv, int dh,
-                               bf16_t *out, const KvPrefix &pre, int block_len, hipStream_t st) {
-        if ((h->plain_mask & 2) || (N % 8) != 0 || (block_len > 0 && block_len < N)) {
+                               bf16_t *out, const KvPrefix &pre, int block_len, hipStream_t st, bool rotated = false) {
+        if (rotated) {
+            launch_attention_bf16(qkv, ld_qkv, vT, S, N, H, Hkv, dh, out, pre, st);
+        } else if ((h->plain_mask & 2) || (N % 8) != 0 || (block_len > 0 && block_len < N)) {
             launch_rope<bf16_t>(qkv, ld_qkv, (int64_t)S * N, N, pos0, H, Hkv, dh, h->rope_cos, h->rope_sin, st);
             launch_plain_attention<bf16_t>(qkv, ld_qkv, S, N, H, Hkv, dh, out, pre, block_len, st);
         } else {
@@ -143,15 +164,19 @@ int32_t forward_hidden_impl(psd_handle *h, const int32_t *tokens, const int32_t 
         const T *wq = (const T *)lw.wq, *wk = (const T *)lw.wk, *wv = (const T *)lw.wv;
         const bool fused = wk == wq + (int64_t)H * dh * d && wv == wk + (int64_t)Hkv * dh * d &&
                            (!c.qkv_bias || (lw.bk == lw.bq + H * dh && lw.bv == lw.bk + Hkv * dh));
+        const int block_len = c.attention == PSD_ATTN_BLOCK_CAUSAL ? L : 0;
+        bool rotated = false;
         if (fused) {
-            Dispatch<T>::gemm(h, a, d, wq, nullptr, d, ntok, qkv_w, d, epi_qkv, lw.bq, qkv, nullptr, ld_qkv, nullptr, st);
+            // (the approximate-cache refresh reads V row-major out of qkv afterwards: two-pass form there)
+            rotated = !store && ld_qkv == qkv_w &&
+                      Dispatch<T>::qkv_fused(h, a, wq, ntok, N, 0, H, Hkv, dh, c.qkv_bias ? lw.bq : nullptr, qkv, ld_qkv, vT, block_len, st);
+            if (!rotated) Dispatch<T>::gemm(h, a, d, wq, nullptr, d, ntok, qkv_w, d, epi_qkv, lw.bq, qkv, nullptr, ld_qkv, nullptr, st);
         } else {
             Dispatch<T>::gemm(h, a, d, wq, nullptr, d, ntok, H * dh, d, epi_qkv, lw.bq, qkv, nullptr, ld_qkv, nullptr, st);
             Dispatch<T>::gemm(h, a, d, wk, nullptr, d, ntok, Hkv * dh, d, epi_qkv, lw.bk, qkv + H * dh, nullptr, ld_qkv, nullptr, st);
             Dispatch<T>::gemm(h, a, d, wv, nullptr, d, ntok, Hkv * dh, d, epi_qkv, lw.bv, qkv + (H + Hkv) * dh, nullptr, ld_qkv, nullptr, st);
         }
-        Dispatch<T>::rope_attention(h, qkv, ld_qkv, vT, S, N, 0, H, Hkv, dh, o, KvPrefix(),
-                                    c.attention == PSD_ATTN_BLOCK_CAUSAL ? L : 0, st);
+        Dispatch<T>::rope_attention(h, qkv, ld_qkv, vT, S, N, 0, H, Hkv, dh, o, KvPrefix(), block_len, st, rotated);
         if (store) {
             // approximate cache: freeze this layer's keys / values of every position outside the block, prefix first
             const KvLayout lay = kv_layout(c, store->capacity);

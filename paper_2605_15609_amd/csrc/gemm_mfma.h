@@ -23,9 +23,16 @@
 //   EPI_SWIGLU             out = bf16(silu(X Yg^T) * (X Yu^T))              gate and up in one pass
 //   EPI_TOP1               per column j: running (max, argmax, sum-exp) over the rows i
 //                          (LM-head with X = W_lm, Y = hidden rows; logits never stored)
+//   EPI_QKV                QKV projection with what used to be a second pass over its output folded in: the tile
+//                          (+ bias) is rounded to bf16 into LDS (the operand rings are free by then); a tile of q / k
+//                          heads is read back row-wise, rotated (rotary position of row m: pos0 + m % N) and stored
+//                          with 16-byte accesses; a tile of V heads is read back column-wise and stored transposed,
+//                          key-contiguous, in the slot order the attention kernel's second MFMA wants.  Same values
+//                          as EPI_STORE / EPI_BIAS followed by the separate rotary / transpose kernel, bit for bit.
 #pragma once
 #include "psd_internal.h"
 #include "device_types.h"
+#include "rope_device.h"
 
 // With two wavefronts per SIMD in one workgroup (the 8-wavefront tiles) the one inside an MFMA cluster gets issue
 // priority over its sibling's loads and address arithmetic (measured: SwiGLU 362 -> 352 us at 2048 tokens; the
@@ -47,6 +54,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int EPI_TOP1 = 4;
+constexpr int EPI_QKV = 5;
 constexpr int BK = 64;                  // k extent per stage (bf16) = 128 bytes per row
 constexpr int ROW_BYTES = BK * 2;
 
@@ -57,6 +65,15 @@ struct Top1Args {
     float *psum;        // [slabs, cols] partial sum exp(z - pmax)
     int32_t *parg;      // [slabs, cols] partial argmax (lowest id on ties)
     int cols_total;
+};
+
+struct QkvArgs {
+    int d_head;           // 64 or 128; every tile holds whole heads (BN % d_head == 0)
+    int v_start;          // columns [0, v_start) are q and k heads, [v_start, Nout) V heads; a multiple of BN
+    int N, pos0;          // rows per sequence (a multiple of 16) and the rotary position of a sequence's first row
+    const float *cos_t, *sin_t;   // [positions, d_head / 2]
+    bf16_t *vT;           // [sequences][Nout - v_start][ld_vt]
+    int ld_vt;
 };
 
 // 64 LDS banks x 4 bytes: rows r and r+1 cover the two 128-byte halves, so the chunk slot is rotated by
@@ -98,7 +115,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
                                                         const bf16_t *__restrict__ Y2, int M, int Nout, int Kin, int ldx, int ldy,
                                                         const float *__restrict__ bias, bf16_t *__restrict__ out,
                                                         float *__restrict__ resid, int ldo, int tiles_n, int n_tiles,
-                                                        Top1Args t1, int k_splits, float *__restrict__ partial, int group_m) {
+                                                        Top1Args t1, int k_splits, float *__restrict__ partial, int group_m,
+                                                        QkvArgs qa) {
     extern __shared__ __align__(16) unsigned char lds[];
     constexpr bool DUAL = EPI == EPI_SWIGLU;
     constexpr int BN_OUT = DUAL ? BN / 2 : BN;            // output columns per tile
@@ -344,6 +362,76 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
             t1.psum[o] = sum;
             t1.parg[o] = arg;
         }
+    } else if constexpr (EPI == EPI_QKV) {
+        constexpr int NT = NW * 64;
+        constexpr int LDC = BN * 2 + 16;   // bytes per row of the row-major staging tile: the two half-waves (rows r, r + 4) land 64 bytes apart in the banks
+        constexpr int LDT = BM * 2 + 8;    // bytes per column of the column-major one: 32 lanes x 8 bytes cover all banks once
+        static_assert(BM * LDC <= (NSA * BM + NSB * BN) * ROW_BYTES && BN * LDT <= (NSA * BM + NSB * BN) * ROW_BYTES, "staging tile fits the rings");
+        __syncthreads();                   // every wavefront is done with the operand rings
+        if (n0 < qa.v_start) {
+            // ---- q / k heads: stage row-major, rotate pairs (j, j + d_head / 2), store 16 bytes per access
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int col = wn * WTN + j * 32 + lrow;
+                    const float bn = bias ? bias[min(n0 + col, Nout - 1)] : 0.f;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int row = wm * WTM + i * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
+                        *reinterpret_cast<uint16_t *>(lds + row * LDC + col * 2) = from_float<bf16_t>(acc[i][j][v] + bn).bits;
+                    }
+                }
+            __syncthreads();
+            const int half = qa.d_head >> 1, groups = half >> 3, heads = BN / qa.d_head;
+            const int units = BM * heads * groups;   // 8 pair indices of one head of one row each
+            for (int u = tid; u < units; u += NT) {
+                const int g = u % groups, hd = (u / groups) % heads, row = u / (groups * heads);
+                const int m = m0 + row, n = n0 + hd * qa.d_head + g * 8;
+                if (m >= M || n >= Nout) continue;
+                const unsigned char *src = lds + row * LDC + (hd * qa.d_head + g * 8) * 2;
+                const uint4 a = *reinterpret_cast<const uint4 *>(src), b = *reinterpret_cast<const uint4 *>(src + half * 2);
+                const int64_t t = (int64_t)(qa.pos0 + m % qa.N) * half + g * 8;
+                const float4 c0 = *reinterpret_cast<const float4 *>(qa.cos_t + t), c1 = *reinterpret_cast<const float4 *>(qa.cos_t + t + 4);
+                const float4 s0 = *reinterpret_cast<const float4 *>(qa.sin_t + t), s1 = *reinterpret_cast<const float4 *>(qa.sin_t + t + 4);
+                uint4 ra, rb;
+                rope_rotate8(a, b, c0, c1, s0, s1, ra, rb);
+                bf16_t *dst = out + (int64_t)m * ldo + n;
+                *reinterpret_cast<uint4 *>(dst) = ra;
+                *reinterpret_cast<uint4 *>(dst + half) = rb;
+            }
+        } else {
+            // ---- V heads: stage column-major (a lane's 4 consecutive rows are one 8-byte piece), store transposed.
+            // Inside every group of 16 keys the slots hold keys 0-3, 8-11, 4-7, 12-15.
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int col = wn * WTN + j * 32 + lrow;
+                    const float bn = bias ? bias[min(n0 + col, Nout - 1)] : 0.f;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int row = wm * WTM + i * 32 + 8 * q + 4 * lhalf;
+                        uint2 w;
+                        w.x = pack_bf16x2(acc[i][j][4 * q + 0] + bn, acc[i][j][4 * q + 1] + bn);
+                        w.y = pack_bf16x2(acc[i][j][4 * q + 2] + bn, acc[i][j][4 * q + 3] + bn);
+                        *reinterpret_cast<uint2 *>(lds + col * LDT + row * 2) = w;
+                    }
+                }
+            __syncthreads();
+            constexpr int G16 = BM / 16;
+            const int n_v = Nout - qa.v_start;
+            for (int u = tid; u < BN * G16 * 2; u += NT) {
+                const int h = u & 1, g = (u >> 1) % G16, col = u / (2 * G16);
+                const int m = m0 + g * 16, n = n0 + col;
+                if (m >= M || n >= Nout) continue;
+                const unsigned char *src = lds + col * LDT + (g * 16 + 4 * h) * 2;
+                const uint2 lo = *reinterpret_cast<const uint2 *>(src), hi = *reinterpret_cast<const uint2 *>(src + 16);
+                const int sq = m / qa.N, i0 = m % qa.N;   // N % 16 == 0: the 16 keys belong to one sequence
+                bf16_t *dst = qa.vT + ((int64_t)sq * n_v + (n - qa.v_start)) * qa.ld_vt + i0 + 8 * h;
+                *reinterpret_cast<uint4 *>(dst) = make_uint4(lo.x, lo.y, hi.x, hi.y);
+            }
+        }
     } else {
         constexpr int TN_OUT = DUAL ? TN / 2 : TN;
         constexpr int WTN_OUT = DUAL ? WTN / 2 : WTN;
@@ -374,6 +462,42 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
                 }
             return;
         }
+        // bf16 outputs.  A lane holds single columns: written straight to memory that is 2-byte stores, 64 bytes per row
+        // and instruction.  Where rows allow 16-byte accesses the tile is staged in LDS instead (the operand rings are
+        // free; row-major, rows padded by 16 bytes so that the two half-waves land 64 bytes apart in the banks) and
+        // stored with 16 bytes per lane (measured in one process at 163 840 rows: store epilogue 13.78 -> 13.52 ms, SwiGLU
+        // 26.57 -> 26.2 ms; within noise below 2048 rows).
+        constexpr int BNO = BN_OUT, LDC = BNO * 2 + 16, NT = NW * 64;
+        static_assert(BM * LDC <= (NSA * BM + NSB * BN) * ROW_BYTES, "staging tile fits the rings");
+        if ((ldo & 7) == 0 && (Nout & 7) == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0) {   // uniform
+            __syncthreads();   // every wavefront is done with the operand rings
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN_OUT; ++j) {
+                    const int col = wn * WTN_OUT + j * 32 + lrow;
+                    const float bn = (EPI == EPI_BIAS) ? bias[min(n0 + col, Nout - 1)] : 0.f;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int row = wm * WTM + i * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
+                        float x = acc[i][j][v];
+                        if (EPI == EPI_BIAS) x += bn;
+                        if (DUAL) {
+                            const float u = acc[i][j + TN / 2][v];
+                            x = x * __builtin_amdgcn_rcpf(1.0f + __expf(-x)) * u;
+                        }
+                        *reinterpret_cast<uint16_t *>(lds + row * LDC + col * 2) = from_float<bf16_t>(x).bits;
+                    }
+                }
+            __syncthreads();
+            for (int u = tid; u < BM * (BNO / 8); u += NT) {
+                const int c8 = u % (BNO / 8), row = u / (BNO / 8);
+                const int m = m0 + row, n = n0 + c8 * 8;
+                if (m < M && n < Nout)
+                    *reinterpret_cast<uint4 *>(out + (int64_t)m * ldo + n) = *reinterpret_cast<const uint4 *>(lds + row * LDC + c8 * 16);
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -399,7 +523,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
 
 template <int BM, int BN, int WGM, int WGN, int EPI, int NSA = 2, int NSB = NSA>
 void launch_cfg(const bf16_t *X, const bf16_t *Y, const bf16_t *Y2, int M, int Nout, int Kin, int ldx, int ldy, const float *bias,
-                bf16_t *out, float *resid, int ldo, Top1Args t1, hipStream_t st, int k_splits = 1, float *partial = nullptr) {
+                bf16_t *out, float *resid, int ldo, Top1Args t1, hipStream_t st, int k_splits = 1, float *partial = nullptr,
+                QkvArgs qa = QkvArgs()) {
     constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (Nout + BN_OUT - 1) / BN_OUT;
     const int n_tiles = tiles_m * tiles_n;
@@ -410,7 +535,7 @@ void launch_cfg(const bf16_t *X, const bf16_t *Y, const bf16_t *Y2, int M, int N
     ensure_dynamic_lds(reinterpret_cast<const void *>(kern), smem, lds_raised);
     if (EPI != EPI_RESIDUAL) k_splits = 1;
     hipLaunchKernelGGL(kern, dim3(n_tiles * k_splits), dim3(WGM * WGN * 64), smem, st, X, Y, Y2, M, Nout, Kin, ldx, ldy, bias, out, resid,
-                       ldo, tiles_n, n_tiles, t1, k_splits, partial, gemm_tile_group_m());
+                       ldo, tiles_n, n_tiles, t1, k_splits, partial, gemm_tile_group_m(), qa);
 }
 
 }   // namespace mfma

@@ -135,6 +135,41 @@ void launch_gemm_bf16_split(const bf16_t *A, const bf16_t *W, int64_t M, int Nou
                                                      splits, partial);
 }
 
+// QKV projection with rotary and the V transpose in its epilogue (EPI_QKV).  The tile is the one the plain store
+// would get, provided every tile then holds whole heads of one kind: the tile width a multiple of d_head and the first
+// V column a multiple of the tile width.  -1: no such tile, run the store epilogue and the separate kernel instead.
+int gemm_bf16_qkv_tile(int64_t M, int Nout, int d_head, int v_start, int rows_per_seq) {
+    if ((d_head != 64 && d_head != 128) || rows_per_seq % 16 != 0 || Nout % 8 != 0) return -1;
+    const int tile = gemm_bf16_tile(M, Nout, EPI_STORE);
+    const int bn = kTiles[tile].bn;
+    if (tile == 2 || tile == 3 || bn % d_head != 0 || v_start % bn != 0) return -1;
+    return tile;
+}
+
+void launch_gemm_bf16_qkv(const bf16_t *A, const bf16_t *W, int64_t M, int Nout, int Kin, int lda, int ldw, const float *bias, bf16_t *qkv,
+                          int ld_qkv, int d_head, int v_start, int rows_per_seq, int pos0, const float *cos_t, const float *sin_t,
+                          bf16_t *vT, int ld_vt, int tile, hipStream_t st) {
+    Top1Args none = {};
+    QkvArgs qa;
+    qa.d_head = d_head;
+    qa.v_start = v_start;
+    qa.N = rows_per_seq;
+    qa.pos0 = pos0;
+    qa.cos_t = cos_t;
+    qa.sin_t = sin_t;
+    qa.vT = vT;
+    qa.ld_vt = ld_vt;
+    const int m = (int)M;
+    switch (tile) {
+        case 1: return launch_cfg<256, 256, 4, 2, EPI_QKV, 2, 3>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
+        case 4: return launch_cfg<128, 64, 2, 2, EPI_QKV, 4, 4>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
+        case 5: return launch_cfg<128, 128, 2, 2, EPI_QKV, 4, 4>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
+        case 6: return launch_cfg<64, 64, 2, 2, EPI_QKV, 4, 4>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
+        case 7: return launch_cfg<256, 128, 4, 2, EPI_QKV, 2, 4>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
+        default: return launch_cfg<128, 128, 2, 2, EPI_QKV, 2, 3>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
+    }
+}
+
 void launch_gemm_bf16(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int64_t M, int Nout, int Kin, int lda, int ldw, int epi,
                       const float *bias, bf16_t *out, float *resid, int ldo, hipStream_t st) {
     const int m = (int)M;

@@ -24,7 +24,7 @@ struct psd_handle {
     std::vector<Layer> layers;
     int w_down_stride;       // row stride of every w_down (elements)
     int device;
-    int plain_mask;          // debug: bit 0 plain GEMM, bit 1 plain attention, bit 2 plain LM-head
+    int plain_mask;          // debug: bit 0 plain GEMM, bit 1 plain attention, bit 2 plain LM-head, bit 3 rotary / V transpose as a separate kernel
     void *lm_head_packed;    // bf16 models: fragment-order copy of lm_head owned by the handle (streaming LM-head)
     int32_t *host_counts;    // pinned host staging for psd_decode_block
     int host_counts_cap;
@@ -41,7 +41,35 @@ struct psd_handle {
             b.push_back(y);
         }
     } probe, probe_head, probe_call;
+    // Model calls of the block loops replayed as HIP graphs (launch-bound small models: ~90 kernels of a few
+    // microseconds each).  A call is identified by everything its kernels' arguments are derived from; the first time
+    // a key is seen the call runs eagerly (which also does the one-time set-up of its kernels), the second time it is
+    // captured on capture_stream and instantiated, from then on replayed on the caller's stream.
+    struct GraphKey {
+        const void *src, *rows, *top1, *conf, *ws, *starts;
+        int64_t ws_bytes;
+        int S, N, L, start_common, rows_per_seq, epoch;
+        bool operator==(const GraphKey &o) const {
+            return src == o.src && rows == o.rows && top1 == o.top1 && conf == o.conf && ws == o.ws && starts == o.starts &&
+                   ws_bytes == o.ws_bytes && S == o.S && N == o.N && L == o.L && start_common == o.start_common &&
+                   rows_per_seq == o.rows_per_seq && epoch == o.epoch;
+        }
+    };
+    struct GraphEntry {
+        GraphKey key;
+        hipGraphExec_t exec = nullptr;
+        bool failed = false;        // capture or instantiation was refused: this call stays eager
+        uint64_t last_use = 0;
+    };
+    std::vector<GraphEntry> graphs;   // at most kMaxGraphs, least recently used replaced
+    static constexpr size_t kMaxGraphs = 24;
+    hipStream_t capture_stream = nullptr;
+    int graphs_enabled = 0;   // off unless asked for: measured to gain nothing where it was expected to (see psd_debug_set_graphs)
+    uint64_t graph_clock = 0, graph_replays = 0;
 };
+// bumped by every debug switch that changes which kernels a model call launches: captured graphs of an older epoch are stale
+int kernel_choice_epoch();
+void bump_kernel_choice_epoch();
 
 void psd_set_error(const char *fmt, ...);
 
@@ -254,6 +282,14 @@ void launch_head_finish(const float *row_sum, const int32_t *row_arg, const int3
 // (workgroup tile, wavefronts, LDS ring depths), 0 <= i < gemm_bf16_tile_count()
 int gemm_bf16_tile(int64_t M, int Nout, int epi);
 int gemm_bf16_tile_count();
+// QKV projection that also applies the rotary embedding to the q / k heads and stores V transposed into vT (what
+// launch_rope_transpose_v does in a second pass), bit-identical to the two-pass form.  gemm_bf16_qkv_tile returns the tile
+// to pass on, or -1 when the shape has no tile that holds whole heads of one kind (then the two-pass form runs).
+// rows_per_seq: rows of A per sequence (a multiple of 16); v_start: first V column; pos0: position of a sequence's row 0.
+int gemm_bf16_qkv_tile(int64_t M, int Nout, int d_head, int v_start, int rows_per_seq);
+void launch_gemm_bf16_qkv(const bf16_t *A, const bf16_t *W, int64_t M, int Nout, int Kin, int lda, int ldw, const float *bias, bf16_t *qkv,
+                          int ld_qkv, int d_head, int v_start, int rows_per_seq, int pos0, const float *cos_t, const float *sin_t,
+                          bf16_t *vT, int ld_vt, int tile, hipStream_t st);
 // K-split of a residual contraction (1 = none).  With s > 1 parts, launch_gemm_bf16_split adds part 0 into
 // resid and stores parts 1..s-1 to partial [s-1][M][Nout] fp32; the next reader of resid adds them in order.
 int gemm_bf16_splits(int64_t M, int Nout, int Kin);

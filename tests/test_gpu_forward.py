@@ -146,6 +146,35 @@ def test_bf16_paths(name, plain):
     _compare(model, host, states, bs, L, 2e-2, f"{name}/mask{plain}")
 
 
+@pytest.mark.parametrize("name,N,S", [("small-2l", 192, 1), ("small-2l", 48, 11), ("small-2l", 384, 4), ("gqa-bias", 144, 1),
+                                      ("gqa-bias", 272, 5), ("gqa-bias", 1280, 2)])
+def test_rotary_and_value_transpose_in_the_qkv_epilogue_change_no_bit(name, N, S):
+    """The QKV projection applies the rotary embedding and stores V transposed from its own epilogue; bit 3 of the debug mask
+    asks for the older form (plain store, then a second kernel over the output).  Both must give the same logits bit for
+    bit -- the rounding points are the same -- for head widths 64 and 128, with and without biases and grouped KV heads,
+    for tiles that hold several sequences (N = 48), ragged last tiles, and rows past one tile."""
+    import paper_2605_15609_amd as psd
+    from tests.gpu_common import make_models, to_dev, say
+    shape = SHAPES[name][0]
+    L = 16
+    bs = N - 2 * L
+    host, model = make_models(shape, N)
+    states = np.stack([_state(shape, N, bs, L, 40 + s, (3 * s) % L) for s in range(S)])
+    d = to_dev(states)
+    out = {}
+    for mask in (0, 8):
+        model.set_plain(mask)
+        out[mask] = psd.psd_forward_logits(model, d, bs, L).cpu().numpy()
+    model.set_plain(0)
+    assert np.isfinite(out[0]).all()
+    assert (out[0] == out[8]).all(), f"{name} N={N} S={S}: max difference {np.abs(out[0] - out[8]).max():.3e}"
+    # and the result is the model's: one sequence against the oracle
+    z = orc.block_logits(host, states[S - 1], bs, L)
+    err = float(np.abs(out[0].reshape(S, L, -1)[S - 1] - z).max())
+    say(f"[forward] fused QKV epilogue {name} N={N} S={S}: bit-identical to the two-pass form; max-abs logit error vs oracle {err:.3e}")
+    assert err < 2e-2
+
+
 def test_batched_forward_equals_single(monkeypatch):
     """Batching S sequences must not change any sequence's (top1, conf) by more than rounding
     of the tile schedule; the decisions of the all-MFMA path must agree exactly here."""
