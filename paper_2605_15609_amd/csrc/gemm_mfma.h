@@ -38,8 +38,8 @@
 // priority over its sibling's loads and address arithmetic (measured: SwiGLU 362 -> 352 us at 2048 tokens; the
 // 4-wavefront tiles, whose SIMD siblings belong to another workgroup, lose 4 % with it).
 #ifndef PSD_NO_SETPRIO
-#define PSD_PRIO_HI if constexpr (NW == 8) __builtin_amdgcn_s_setprio(1);
-#define PSD_PRIO_LO if constexpr (NW == 8) __builtin_amdgcn_s_setprio(0);
+#define PSD_PRIO_HI if constexpr (NW == 8 && !NOPRIO) __builtin_amdgcn_s_setprio(1);
+#define PSD_PRIO_LO if constexpr (NW == 8 && !NOPRIO) __builtin_amdgcn_s_setprio(0);
 #else
 #define PSD_PRIO_HI
 #define PSD_PRIO_LO
@@ -55,8 +55,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int EPI_TOP1 = 4;
 constexpr int EPI_QKV = 5;
-constexpr int BK = 64;                  // k extent per stage (bf16) = 128 bytes per row
-constexpr int ROW_BYTES = BK * 2;
+constexpr int BK = 64;                  // default k extent per stage (bf16) = 128 bytes per LDS row
 
 struct Top1Args {
     float scale;        // logits = scale * acc
@@ -76,9 +75,14 @@ struct QkvArgs {
     int ld_vt;
 };
 
-// 64 LDS banks x 4 bytes: rows r and r+1 cover the two 128-byte halves, so the chunk slot is rotated by
-// (r >> 1): any 16 consecutive rows fetching the same logical chunk then hit 16 distinct bank groups
-__device__ __forceinline__ int swz(int row, int chunk) { return row * ROW_BYTES + ((chunk ^ ((row >> 1) & 7)) << 4); }
+// Swizzle key of an LDS row (64 banks x 4 bytes = 256 bytes per bank line; 16 consecutive rows fetching the same
+// logical 16-byte chunk must hit 16 distinct bank groups).  128-byte rows (64 k per stage): rows r and r+1 cover the
+// two halves of a bank line, the chunk slot is rotated by (r >> 1) over 8 slots.  64-byte rows (32 k per stage): four
+// rows per bank line, rotated by (r >> 2) over 4 slots.
+template <int BKT>
+__device__ __forceinline__ int row_key(int row) {
+    return BKT == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3);
+}
 
 // merge two (max, argmax, sum-exp) triples; ties go to the lower index
 __device__ __forceinline__ void top1_merge(float &b, int &a, float &s, float b2, int a2, float s2) {
@@ -110,7 +114,7 @@ __device__ __forceinline__ void sched_mix() {
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, int NSA, int NSB>
+template <int BM, int BN, int WGM, int WGN, int EPI, int NSA, int NSB, int BKT = BK, int SCHED = 0>
 __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Y,
                                                         const bf16_t *__restrict__ Y2, int M, int Nout, int Kin, int ldx, int ldy,
                                                         const float *__restrict__ bias, bf16_t *__restrict__ out,
@@ -118,13 +122,20 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
                                                         Top1Args t1, int k_splits, float *__restrict__ partial, int group_m,
                                                         QkvArgs qa) {
     extern __shared__ __align__(16) unsigned char lds[];
+    static_assert(BKT == 64 || BKT == 32, "k extent of a stage");
+    // schedule of the main loop: bit 0 ping-pong phases; bit 1 only the lower half of the wavefronts issues fetches (for
+    // itself and for wavefront w + NW/2); bit 2 no issue priority around the MFMA groups (the scheduler then
+    // interleaves them with the LDS reads and fetches); bit 3 the fetches of a stage spread over its first three k-steps
+    constexpr bool PP = (SCHED & 1) != 0, ASYM = (SCHED & 2) != 0, NOPRIO = (SCHED & 4) != 0, SPREAD = (SCHED & 8) != 0;
+    constexpr int BK = BKT, ROW_BYTES = BKT * 2;          // (shadows the default: everything below is per instantiation)
+    constexpr int LPR = ROW_BYTES / 16, RPI = 64 / LPR;   // lanes per LDS row and rows per DMA instruction (1 KB)
     constexpr bool DUAL = EPI == EPI_SWIGLU;
     constexpr int BN_OUT = DUAL ? BN / 2 : BN;            // output columns per tile
     constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES, B_RING = NSA * A_BYTES;   // X ring first, then the Y ring
     constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
     constexpr int NW = WGM * WGN;   // wavefronts per workgroup
     static_assert((NW == 4 || NW == 8) && TM >= 1 && TN >= 1 && (!DUAL || TN % 2 == 0), "tile shape");
-    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "every wavefront moves whole 8-row groups of both tiles");
+    static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "every wavefront moves whole row groups of both tiles");
 
     // XCD-aware tile id: ids i, i+8, i+16 ... land on the same XCD; give that XCD a contiguous tile range
     int pid = blockIdx.x, split = 0;
@@ -175,33 +186,46 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
     const __amdgpu_buffer_rsrc_t rsrc_y2 = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<bf16_t *>(DUAL ? Y2 : Y) + (int64_t)n0 * ldy + k_beg, 0, ((rows_y - 1) * ldy + Kin - k_beg) * 2, 0x00020000);
     const int uwave = __builtin_amdgcn_readfirstlane(wave);
-    const int dma_key = (((uwave & 1) << 2) + (lane >> 4)) & 7;
-    const int voff_x = (lane >> 3) * ldx * 2 + (((lane & 7) ^ dma_key) << 4);
-    const int voff_y = (lane >> 3) * ldy * 2 + (((lane & 7) ^ dma_key) << 4);
-    constexpr int GA = BM / 8 / NW, GB = BN / 8 / NW;   // row groups per wavefront, A and B tile
+    // (64-byte rows: a DMA instruction moves 16 rows; the key of row 16 g + l/4 is (l / 16) & 3 for every group g)
+    const int dma_key = BKT == 64 ? ((((uwave & 1) << 2) + (lane >> 4)) & 7) : ((lane >> 4) & 3);
+    const int voff_x = (lane / LPR) * ldx * 2 + (((lane % LPR) ^ dma_key) << 4);
+    const int voff_y = (lane / LPR) * ldy * 2 + (((lane % LPR) ^ dma_key) << 4);
+    constexpr int GA = BM / RPI / NW, GB = BN / RPI / NW;   // row groups per wavefront, A and B tile
     constexpr int NLD = GA + GB;                      // DMA instructions per wavefront per stage
     typedef __attribute__((address_space(3))) void lds_void;
 
 // global -> LDS: one stage of the X tile / of the Y tile, K position k0, into ring slot `slot`
-#define PSD_GEMM_DMA_A(slot, k0)                                                                              \
-    {                                                                                                         \
-        unsigned char *sa_ = lds + (slot) * A_BYTES + uwave * 1024;                                           \
-        _Pragma("unroll") for (int j = 0; j < GA; ++j)                                                        \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, (lds_void *)(sa_ + j * (NW * 1024)), 16, voff_x, \
-                                                     ((j * NW + uwave) * 8 * ldx + (k0)) * 2, 0, 0);          \
-    }
-#define PSD_GEMM_DMA_B(slot, k0)                                                                              \
-    {                                                                                                         \
-        unsigned char *sb_ = lds + B_RING + (slot) * B_BYTES + uwave * 1024;                                  \
-        _Pragma("unroll") for (int j = 0; j < GB; ++j) {                                                      \
-            if (DUAL && j * (8 * NW) >= BN / 2)                                                               \
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_y2, (lds_void *)(sb_ + j * (NW * 1024)), 16, voff_y, \
-                                                         (((j * NW + uwave) * 8 - BN / 2) * ldy + (k0)) * 2, 0, 0); \
-            else                                                                                              \
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_y, (lds_void *)(sb_ + j * (NW * 1024)), 16, voff_y, \
-                                                         ((j * NW + uwave) * 8 * ldy + (k0)) * 2, 0, 0);      \
+// `half`: -1 the whole stage, 0 / 1 the first / second half of this wavefront's row groups (an odd group goes first).
+// With ASYM the lower NW/2 wavefronts fetch for themselves and for wavefront w + NW/2, the others do nothing.
+#define PSD_GEMM_DMA_A_PART(slot, k0, half)                                                                   \
+    if (!ASYM || uwave < NW / 2) {                                                                            \
+        _Pragma("unroll") for (int hh = 0; hh < (ASYM ? 2 : 1); ++hh) {                                       \
+            const int uw_ = uwave + hh * (NW / 2);                                                            \
+            unsigned char *sa_ = lds + (slot) * A_BYTES + uw_ * 1024;                                         \
+            _Pragma("unroll") for (int j = 0; j < GA; ++j)                                                    \
+                if ((half) < 0 || (j < (GA + 1) / 2) == ((half) == 0))                                        \
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, (lds_void *)(sa_ + j * (NW * 1024)), 16, voff_x, \
+                                                             ((j * NW + uw_) * RPI * ldx + (k0)) * 2, 0, 0);  \
         }                                                                                                     \
     }
+#define PSD_GEMM_DMA_B_PART(slot, k0, half)                                                                   \
+    if (!ASYM || uwave < NW / 2) {                                                                            \
+        _Pragma("unroll") for (int hh = 0; hh < (ASYM ? 2 : 1); ++hh) {                                       \
+            const int uw_ = uwave + hh * (NW / 2);                                                            \
+            unsigned char *sb_ = lds + B_RING + (slot) * B_BYTES + uw_ * 1024;                                \
+            _Pragma("unroll") for (int j = 0; j < GB; ++j) {                                                  \
+                if (!((half) < 0 || (j < (GB + 1) / 2) == ((half) == 0))) continue;                           \
+                if (DUAL && j * (RPI * NW) >= BN / 2)                                                         \
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_y2, (lds_void *)(sb_ + j * (NW * 1024)), 16, voff_y, \
+                                                             (((j * NW + uw_) * RPI - BN / 2) * ldy + (k0)) * 2, 0, 0); \
+                else                                                                                          \
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_y, (lds_void *)(sb_ + j * (NW * 1024)), 16, voff_y, \
+                                                             ((j * NW + uw_) * RPI * ldy + (k0)) * 2, 0, 0);  \
+            }                                                                                                 \
+        }                                                                                                     \
+    }
+#define PSD_GEMM_DMA_A(slot, k0) PSD_GEMM_DMA_A_PART(slot, k0, -1)
+#define PSD_GEMM_DMA_B(slot, k0) PSD_GEMM_DMA_B_PART(slot, k0, -1)
 // Every iteration issues the fetch of the shallower ring first.  Memory returns in issue order, so
 // once the counter says that at most WAIT younger DMA instructions are in flight, both tiles of the
 // next stage have landed: with the X ring shallower, its stage kt+1 was issued NSA-2 iterations ago
@@ -216,7 +240,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
             PSD_GEMM_DMA_A(sa, ((kt_) + NSA - 1) * BK)                                                        \
         }                                                                                                     \
     }
-    constexpr int WAIT = NSA < NSB ? (NSA - 2) * NLD + GB : NSA > NSB ? (NSB - 2) * NLD + GA : (NSA - 2) * NLD;
+    constexpr int WAIT = (ASYM ? 2 : 1) * (NSA < NSB ? (NSA - 2) * NLD + GB : NSA > NSB ? (NSB - 2) * NLD + GA : (NSA - 2) * NLD);
 // the DMAs of the next stage have landed; then all wavefronts agree (s_barrier), and the compiler must
 // not move LDS accesses across the point
 #define PSD_GEMM_STAGE_SYNC(n)                                                                                \
@@ -244,7 +268,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
         }
         offb[j] = B_RING + r * ROW_BYTES;
     }
-    const int rsw = (lrow >> 1) & 7;   // swizzle key of every fragment row of this lane: rows differ by multiples of 32
+    const int rsw = row_key<BKT>(lrow);   // swizzle key of every fragment row of this lane: rows differ by multiples of 32
 
 // fragments of k-step kk of an LDS stage into register set `set`
 #define PSD_GEMM_LOAD_FRAGS(sa, sb, kk, set)                                                                  \
@@ -265,10 +289,110 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
         PSD_PRIO_LO                                                                                           \
     }
 
-    bf16x8 fa[2][TM], fb[2][TN];
     constexpr int NFRAG = TM + TN, NMFMA = TM * TN;
+    static_assert(NSA >= 2 && NSB >= 2 && (ASYM ? 2 : 1) * ((NSA - 1) * GA + (NSB - 1) * GB) <= 63, "DMA groups in flight must fit the vmcnt counter");
+    static_assert(!ASYM || (NW / 2) % 2 == 0, "wavefronts w and w + NW/2 share the swizzle key of their row groups");
+    if constexpr (PP) {
+        // Ping-pong schedule for the 8-wavefront tiles.  Wavefronts w and w + 4 sit on the same SIMD; they run the same
+        // sequence of phases -- per k-step a memory phase (fragment reads of that k-step, a quarter of the stage's
+        // fetches) and a compute phase (the k-step's MFMAs), every phase closed by a workgroup barrier -- but the upper
+        // four start one phase late.  So while one wavefront of a SIMD feeds the matrix core the other one reads LDS
+        // and issues fetches, instead of both doing the same thing at the same time and leaving the core idle in
+        // between.  Only the lower four wavefronts issue fetches (all of them): a wavefront is held up for some 20
+        // cycles per fetch instruction, time its sibling spends in MFMAs.  Fragments need no double buffering: a
+        // memory phase lasts as long as the sibling's compute phase, longer than the LDS latency.
+        static_assert(NW == 8 && BKT == 64 && NSA <= NSB && 2 * ((NSA - 1) * GA + (NSB - 1) * GB) <= 63, "ping-pong schedule");
+        const int grp = __builtin_amdgcn_readfirstlane(wave >> 2), lw = uwave & 3;
+        bf16x8 pa[TM], pb[TN];
+// one half (hh = 0, 1) of an operand tile's stage: the row groups of wavefronts lw + 4 hh
+#define PSD_PP_DMA_A(hh, slot, k0)                                                                            \
+    {                                                                                                         \
+        const int uw_ = lw + (hh) * 4;                                                                        \
+        unsigned char *sa_ = lds + (slot) * A_BYTES + uw_ * 1024;                                             \
+        _Pragma("unroll") for (int j = 0; j < GA; ++j)                                                        \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, (lds_void *)(sa_ + j * (NW * 1024)), 16, voff_x, \
+                                                     ((j * NW + uw_) * RPI * ldx + (k0)) * 2, 0, 0);          \
+    }
+#define PSD_PP_DMA_B(hh, slot, k0)                                                                            \
+    {                                                                                                         \
+        const int uw_ = lw + (hh) * 4;                                                                        \
+        unsigned char *sb_ = lds + B_RING + (slot) * B_BYTES + uw_ * 1024;                                    \
+        _Pragma("unroll") for (int j = 0; j < GB; ++j) {                                                      \
+            if (DUAL && j * (RPI * NW) >= BN / 2)                                                             \
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_y2, (lds_void *)(sb_ + j * (NW * 1024)), 16, voff_y, \
+                                                         (((j * NW + uw_) * RPI - BN / 2) * ldy + (k0)) * 2, 0, 0); \
+            else                                                                                              \
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_y, (lds_void *)(sb_ + j * (NW * 1024)), 16, voff_y, \
+                                                         ((j * NW + uw_) * RPI * ldy + (k0)) * 2, 0, 0);      \
+        }                                                                                                     \
+    }
+#define PSD_PP_BARRIER()                                                                                      \
+    {                                                                                                         \
+        asm volatile("" ::: "memory");                                                                        \
+        __builtin_amdgcn_s_barrier();                                                                         \
+        asm volatile("" ::: "memory");                                                                        \
+        __builtin_amdgcn_sched_barrier(0);                                                                    \
+    }
+        if (grp == 0) {
+#pragma unroll
+            for (int p = 0; p < NSA - 1; ++p) {
+                PSD_PP_DMA_A(0, p, p * BK)
+                PSD_PP_DMA_A(1, p, p * BK)
+            }
+#pragma unroll
+            for (int p = 0; p < NSB - 1; ++p) {
+                PSD_PP_DMA_B(0, p, p * BK)
+                PSD_PP_DMA_B(1, p, p * BK)
+            }
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        PSD_PP_BARRIER()
+        if (grp == 1) PSD_PP_BARRIER()   // the upper wavefronts run one phase behind
+        // fetches in flight that may still be outstanding when a stage ends: those of the deeper ring issued in that
+        // stage plus NSA - 2 whole stages (memory returns in issue order); twice the count of the symmetric schedule
+        constexpr int PP_WAIT = 2 * ((NSA - 2) * NLD + (NSA < NSB ? GB : 0));
+        int ca = 0, cb = 0;
+        for (int kt = 0; kt < nk; ++kt) {
+            const int na = (ca + 1 == NSA) ? 0 : ca + 1, nb = (cb + 1 == NSB) ? 0 : cb + 1;
+            const int fill_a = (ca == 0) ? NSA - 1 : ca - 1, fill_b = (cb == 0) ? NSB - 1 : cb - 1;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                // ---- memory phase
+                {
+                    const unsigned char *a_ = lds + ca * A_BYTES, *b_ = lds + cb * B_BYTES;
+                    const int co_ = (((kk * 2 + lhalf) ^ rsw) << 4);
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) pa[i] = *reinterpret_cast<const bf16x8 *>(a_ + offa[i] + co_);
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) pb[j] = *reinterpret_cast<const bf16x8 *>(b_ + offb[j] + co_);
+                }
+                if (grp == 0) {   // the slots being refilled were last read one phase before this stage began
+                    if (kk == 0) PSD_PP_DMA_A(0, fill_a, (kt + NSA - 1) * BK)
+                    if (kk == 1) PSD_PP_DMA_A(1, fill_a, (kt + NSA - 1) * BK)
+                    if (kk == 2) PSD_PP_DMA_B(0, fill_b, (kt + NSB - 1) * BK)
+                    if (kk == 3) PSD_PP_DMA_B(1, fill_b, (kt + NSB - 1) * BK)
+                }
+                PSD_PP_BARRIER()
+                // ---- compute phase
+                __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa[i], pb[j], acc[i][j], 0, 0, 0);
+                __builtin_amdgcn_s_setprio(0);
+                if (kk == 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PP_WAIT) : "memory");   // the next stage has landed
+                PSD_PP_BARRIER()
+            }
+            ca = na;
+            cb = nb;
+        }
+        if (grp == 0) PSD_PP_BARRIER()
+#undef PSD_PP_DMA_A
+#undef PSD_PP_DMA_B
+#undef PSD_PP_BARRIER
+    } else {
+    bf16x8 fa[2][TM], fb[2][TN];
 
-    static_assert(NSA >= 2 && NSB >= 2 && (NSA - 1) * GA + (NSB - 1) * GB <= 63, "DMA groups in flight must fit the vmcnt counter");
 #pragma unroll
     for (int p = 0; p < NSA - 1; ++p) PSD_GEMM_DMA_A(p, p * BK)
 #pragma unroll
@@ -286,15 +410,36 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
         const int na = (ca + 1 == NSA) ? 0 : ca + 1, nb = (cb + 1 == NSB) ? 0 : cb + 1;
         const int fill_a = (ca == 0) ? NSA - 1 : ca - 1, fill_b = (cb == 0) ? NSB - 1 : cb - 1;
         PSD_GEMM_LOAD_FRAGS(ca, cb, 1, 1)
-        PSD_GEMM_ISSUE(fill_a, fill_b, kt)
-        PSD_GEMM_MFMA(0)
-        sched_mix<0, NMFMA, NFRAG, 0, NLD>();
-        PSD_GEMM_LOAD_FRAGS(ca, cb, 2, 0)
-        PSD_GEMM_MFMA(1)
-        sched_mix<0, NMFMA, NFRAG, 0, 0>();
-        PSD_GEMM_LOAD_FRAGS(ca, cb, 3, 1)
-        PSD_GEMM_MFMA(0)
-        sched_mix<0, NMFMA, NFRAG, 0, 0>();
+        if constexpr (SPREAD && BKT == 64) {
+            // the shallower ring's stage in two halves during k-steps 0 and 1, the deeper ring's during k-step 2: the
+            // same issue order as PSD_GEMM_ISSUE, so the wait below counts the same
+            constexpr int MUL = ASYM ? 2 : 1;
+            constexpr int G1 = NSA <= NSB ? GA : GB, G2 = NSA <= NSB ? GB : GA;
+            if constexpr (NSA <= NSB) PSD_GEMM_DMA_A_PART(fill_a, (kt + NSA - 1) * BK, 0) else PSD_GEMM_DMA_B_PART(fill_b, (kt + NSB - 1) * BK, 0)
+            PSD_GEMM_MFMA(0)
+            sched_mix<0, NMFMA, NFRAG, 0, MUL * ((G1 + 1) / 2)>();
+            PSD_GEMM_LOAD_FRAGS(ca, cb, 2, 0)
+            if constexpr (NSA <= NSB) PSD_GEMM_DMA_A_PART(fill_a, (kt + NSA - 1) * BK, 1) else PSD_GEMM_DMA_B_PART(fill_b, (kt + NSB - 1) * BK, 1)
+            PSD_GEMM_MFMA(1)
+            sched_mix<0, NMFMA, NFRAG, 0, MUL * (G1 / 2)>();
+            PSD_GEMM_LOAD_FRAGS(ca, cb, 3, 1)
+            if constexpr (NSA <= NSB) PSD_GEMM_DMA_B(fill_b, (kt + NSB - 1) * BK) else PSD_GEMM_DMA_A(fill_a, (kt + NSA - 1) * BK)
+            PSD_GEMM_MFMA(0)
+            sched_mix<0, NMFMA, NFRAG, 0, MUL * G2>();
+        } else {
+            PSD_GEMM_ISSUE(fill_a, fill_b, kt)
+            PSD_GEMM_MFMA(0)
+            sched_mix<0, NMFMA, NFRAG, 0, (ASYM ? 2 : 1) * NLD>();
+            if constexpr (BKT == 64) {
+                PSD_GEMM_LOAD_FRAGS(ca, cb, 2, 0)
+                PSD_GEMM_MFMA(1)
+                sched_mix<0, NMFMA, NFRAG, 0, 0>();
+                PSD_GEMM_LOAD_FRAGS(ca, cb, 3, 1)
+                PSD_GEMM_MFMA(0)
+                sched_mix<0, NMFMA, NFRAG, 0, 0>();
+            }
+        }
+        // (a stage of 32 k has two k-steps: the second one computes behind the barrier)
         PSD_GEMM_STAGE_SYNC(WAIT)
         PSD_GEMM_LOAD_FRAGS(na, nb, 0, 0)
         PSD_GEMM_MFMA(1)
@@ -302,11 +447,14 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
         ca = na;
         cb = nb;
     }
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no DMA may outlive the loop
 #undef PSD_GEMM_LOAD_FRAGS
 #undef PSD_GEMM_MFMA
 #undef PSD_GEMM_DMA_A
 #undef PSD_GEMM_DMA_B
+#undef PSD_GEMM_DMA_A_PART
+#undef PSD_GEMM_DMA_B_PART
 #undef PSD_GEMM_ISSUE
 #undef PSD_GEMM_STAGE_SYNC
 
@@ -521,16 +669,16 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, int NSA = 2, int NSB = NSA>
+template <int BM, int BN, int WGM, int WGN, int EPI, int NSA = 2, int NSB = NSA, int BKT = BK, int SCHED = 0>
 void launch_cfg(const bf16_t *X, const bf16_t *Y, const bf16_t *Y2, int M, int Nout, int Kin, int ldx, int ldy, const float *bias,
                 bf16_t *out, float *resid, int ldo, Top1Args t1, hipStream_t st, int k_splits = 1, float *partial = nullptr,
                 QkvArgs qa = QkvArgs()) {
     constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (Nout + BN_OUT - 1) / BN_OUT;
     const int n_tiles = tiles_m * tiles_n;
-    constexpr int smem = (NSA * BM + NSB * BN) * ROW_BYTES;
+    constexpr int smem = (NSA * BM + NSB * BN) * BKT * 2;
     static_assert(smem <= 160 * 1024, "LDS ring exceeds the 160 KB of a CU");
-    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, EPI, NSA, NSB>;
+    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, EPI, NSA, NSB, BKT, SCHED>;
     static std::atomic<uint64_t> lds_raised{0};   // one per instantiation
     ensure_dynamic_lds(reinterpret_cast<const void *>(kern), smem, lds_raised);
     if (EPI != EPI_RESIDUAL) k_splits = 1;

@@ -23,6 +23,12 @@ constexpr TileCfg kTiles[] = {
     {128, 128, "128x128, 4 wavefronts, LDS rings 4/4"},
     {64, 64, "64x64, 4 wavefronts, LDS rings 4/4"},
     {256, 128, "256x128, 8 wavefronts, LDS rings 2/4"},   // one full round of 256 workgroups for 2048 x 4096 outputs
+    {256, 256, "256x256, 8 wavefronts, 32 k per stage, LDS rings 5/5"},   // both operands fetched 4 stages (128 k) ahead
+    {256, 256, "256x256, 8 wavefronts in ping-pong phases, LDS rings 2/3"},
+    {256, 256, "x 8 waves asym+noprio+spread"},
+    {256, 256, "x 4 waves spread"},
+    {256, 256, "x 4 waves"},
+    {256, 256, "x 8 waves noprio+spread"},
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -46,11 +52,17 @@ void dispatch(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int M, int Nou
     switch (tile) {
         case 1: return launch_cfg<256, 256, 4, 2, EPI, 2, 3>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
         case 5: return launch_cfg<128, 128, 2, 2, EPI, 4, 4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+        case 8: return launch_cfg<256, 256, 4, 2, EPI, 5, 5, 32>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+        case 9: return launch_cfg<256, 256, 4, 2, EPI, 2, 3, 64, 1>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+        case 10: return launch_cfg<256, 256, 4, 2, EPI, 2, 3, 64, 2 | 4 | 8>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+        case 11: return launch_cfg<256, 256, 2, 2, EPI, 2, 3, 64, 8>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+        case 12: return launch_cfg<256, 256, 2, 2, EPI, 2, 3, 64, 0>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+        case 13: return launch_cfg<256, 256, 4, 2, EPI, 2, 3, 64, 4 | 8>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
         default: return launch_cfg<128, 128, 2, 2, EPI, 2, 3>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
     }
 }
 
-bool tile_fits(int tile, int epi) { return epi != EPI_SWIGLU || tile == 0 || tile == 1 || tile == 5; }
+bool tile_fits(int tile, int epi) { return epi != EPI_SWIGLU || tile == 0 || tile == 1 || tile == 5 || tile >= 8; }
 
 }   // namespace
 
@@ -166,6 +178,7 @@ void launch_gemm_bf16_qkv(const bf16_t *A, const bf16_t *W, int64_t M, int Nout,
         case 5: return launch_cfg<128, 128, 2, 2, EPI_QKV, 4, 4>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
         case 6: return launch_cfg<64, 64, 2, 2, EPI_QKV, 4, 4>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
         case 7: return launch_cfg<256, 128, 4, 2, EPI_QKV, 2, 4>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
+        case 8: return launch_cfg<256, 256, 4, 2, EPI_QKV, 5, 5, 32>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
         default: return launch_cfg<128, 128, 2, 2, EPI_QKV, 2, 3>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
     }
 }

@@ -576,6 +576,36 @@ def test_single_forward_loop_bf16_batch_equals_sequences_alone():
     print(f"[decode] single-forward loop, bf16: {saved} model calls fewer than the literal loop over {B} sequences", flush=True)
 
 
+def test_model_calls_replayed_as_hip_graphs_give_the_same_generation():
+    """Optional HIP-graph replay of the block loop's model calls: a call seen twice is captured, then replayed.  Every
+    replay must leave what the eager launches leave: whole generations with graphs on equal those with graphs off, run
+    alternately (eager work and synchronisations between the replays), over several distinct batches so that a graph is
+    replayed on token contents it was not captured with."""
+    import paper_2605_15609_amd as psd
+    shape = inp.cut_down(inp.WORKLOADS[2].shape, n_layers=2, vocab=4000, seed=33, logit_scale=14.0)
+    N, L, K, B = 160, 32, 3, 3
+    model = psd.Model.from_host(inp.draw_model(shape, N), DEV)
+    policy, graph = psd.Policy(0.9, 1, 0), psd.chain_graph(K)
+    replays = 0
+    d = torch.empty((B, N), dtype=torch.int32, device=DEV)      # one buffer: the graphs hold its address
+    for round_ in range(3):
+        tokens = np.full((B, N), shape.mask_id, dtype=np.int32)
+        for b in range(B):
+            tokens[b, :64] = inp.draw_prompt(shape.vocab, 64, 500 + 10 * round_ + b)
+        results = []
+        for on in (False, True):
+            model.set_graphs(on)
+            d.copy_(torch.from_numpy(tokens))
+            stats, _, iters = psd.psd_decode(model, d, 64, L, policy, graph)
+            results.append((d.cpu().numpy(), [_counters(s) for s in stats], iters))
+        assert (results[0][0] == results[1][0]).all() and results[0][1:] == results[1][1:], round_
+        assert (results[1][0] != shape.mask_id).all()
+        now = model.set_graphs(False)
+        assert now > replays, "the graph path did not run"
+        replays = now
+    print(f"[decode] {replays} model calls replayed from HIP graphs", flush=True)
+
+
 def test_psd_decode_block_with_one_block_start_per_sequence():
     import paper_2605_15609_amd as psd
     shape = inp.cut_down(inp.WORKLOADS[2].shape, n_layers=2, vocab=4000, seed=33, logit_scale=14.0)
