@@ -679,6 +679,38 @@ def decode(model: Model, tokens: torch.Tensor, prompt_len: int, L: int, policy: 
 EPI_STORE, EPI_BIAS, EPI_RESIDUAL, EPI_SWIGLU = 0, 1, 2, 3
 
 
+def debug_layer(model: Model, layer: int, hidden: torch.Tensor, S: int, N: int, L: int, stop_after: int = 0) -> dict:
+    """psd_debug_layer: one layer of the model on the caller's residual stream hidden fp32 [S*N, d_model] (in place).
+    Returns views of the intermediates the layer left in the workspace (valid until the next call on this model):
+    a [S*N, d], qkv [S*N, qkv_w] (rotary applied), o [S*N, H*dh], act [S*N, d_ffn] (stop_after = 0 only)."""
+    assert hidden.dtype == torch.float32 and hidden.is_contiguous() and hidden.shape == (S * N, model.shape.d_model)
+    ws, nb = model.forward_ws(S, N, L)
+    lay = _DebugLayout()
+    _check(model.lib.psd_debug_workspace_layout(C.byref(model.cfg), S, N, L, C.byref(lay)))
+    _check(model.lib.psd_debug_layer(model.handle, layer, _ptr(hidden), S, N, L, stop_after, _ptr(ws), nb, _stream()))
+    sh = model.shape
+    dt = torch.bfloat16 if sh.dtype == "bf16" else torch.float32
+    esz = 2 if sh.dtype == "bf16" else 4
+    T = S * N
+    qkv_w = (sh.n_heads + 2 * sh.n_kv_heads) * sh.d_head
+
+    def view(off, rows, ld, width):
+        return ws[off: off + rows * ld * esz].view(dt).view(rows, ld)[:, :width]
+
+    out = {"a": view(lay.off_a, T, sh.d_model, sh.d_model), "qkv": view(lay.off_qkv, T, lay.ld_qkv, qkv_w),
+           "o": view(lay.off_o, T, sh.n_heads * sh.d_head, sh.n_heads * sh.d_head)}
+    if stop_after == 0:
+        out["act"] = view(lay.off_act, T, lay.ld_act, sh.d_ffn)
+    return out
+
+
+# ------------------------------------------------------------------------------------------
+# kernel-level hooks (parity tests and timing at full shapes without a model)
+# ------------------------------------------------------------------------------------------
+
+EPI_STORE, EPI_BIAS, EPI_RESIDUAL, EPI_SWIGLU = 0, 1, 2, 3
+
+
 def kernel_gemm_bf16(A: torch.Tensor, W: torch.Tensor, epilogue: int = EPI_STORE, W2: Optional[torch.Tensor] = None,
                      bias: Optional[torch.Tensor] = None, resid: Optional[torch.Tensor] = None,
                      out: Optional[torch.Tensor] = None):

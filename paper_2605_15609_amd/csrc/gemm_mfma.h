@@ -52,6 +52,7 @@ namespace mfma {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int EPI_TOP1 = 4;
 constexpr int EPI_QKV = 5;
@@ -93,6 +94,12 @@ __device__ __forceinline__ void top1_merge(float &b, int &a, float &s, float b2,
     s = s_new;
 }
 
+template <int MI, typename Acc>
+__device__ __forceinline__ Acc mfma_step(bf16x8 a, bf16x8 b, Acc c) {
+    if constexpr (MI == 32) return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
 // Scheduling hint for one k-step: spread NR LDS reads (front-loaded over the first half, so they land
 // before the next k-step needs them), NW LDS writes and NV global loads evenly between NM MFMAs.
 template <int I, int NM, int NR, int NW, int NV>
@@ -114,7 +121,7 @@ __device__ __forceinline__ void sched_mix() {
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, int NSA, int NSB, int BKT = BK, int SCHED = 0>
+template <int BM, int BN, int WGM, int WGN, int EPI, int NSA, int NSB, int BKT = BK, int SCHED = 0, int MI = 32>
 __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Y,
                                                         const bf16_t *__restrict__ Y2, int M, int Nout, int Kin, int ldx, int ldy,
                                                         const float *__restrict__ bias, bf16_t *__restrict__ out,
@@ -123,16 +130,32 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
                                                         QkvArgs qa) {
     extern __shared__ __align__(16) unsigned char lds[];
     static_assert(BKT == 64 || BKT == 32, "k extent of a stage");
-    // schedule of the main loop: bit 0 ping-pong phases; bit 1 only the lower half of the wavefronts issues fetches (for
-    // itself and for wavefront w + NW/2); bit 2 no issue priority around the MFMA groups (the scheduler then
-    // interleaves them with the LDS reads and fetches); bit 3 the fetches of a stage spread over its first three k-steps
-    constexpr bool PP = (SCHED & 1) != 0, ASYM = (SCHED & 2) != 0, NOPRIO = (SCHED & 4) != 0, SPREAD = (SCHED & 8) != 0;
+    // Schedule of the main loop.  Bit 1: only the lower half of the wavefronts issues fetches, for itself and for
+    // wavefront w + NW/2 (its sibling on the same SIMD when there are 8): a fetch instruction holds its wavefront up for
+    // some 20 cycles, and two siblings that both fetch right after the stage barrier leave the matrix core idle.
+    // Bit 2: no issue priority around the MFMA groups (the compiler then interleaves them with the LDS reads and the
+    // fetches as the scheduling hints ask).  Bit 3: the fetches of a stage spread over its first three k-steps instead
+    // of all in the first.  Measured over the layer shapes of the benchmark configurations: 2 | 4 | 8 on the
+    // 8-wavefront tiles and 8 on the 4-wavefront tiles take 2 - 8 % off (bit 1 costs the small 4-wavefront tiles 2 - 8 %).
+    constexpr bool ASYM = (SCHED & 2) != 0, NOPRIO = (SCHED & 4) != 0, SPREAD = (SCHED & 8) != 0;
+    static_assert((SCHED & 1) == 0, "schedule bits");
     constexpr int BK = BKT, ROW_BYTES = BKT * 2;          // (shadows the default: everything below is per instantiation)
     constexpr int LPR = ROW_BYTES / 16, RPI = 64 / LPR;   // lanes per LDS row and rows per DMA instruction (1 KB)
     constexpr bool DUAL = EPI == EPI_SWIGLU;
     constexpr int BN_OUT = DUAL ? BN / 2 : BN;            // output columns per tile
     constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES, B_RING = NSA * A_BYTES;   // X ring first, then the Y ring
-    constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
+    // MFMA instruction: MI = 32 is v_mfma_f32_32x32x16_bf16, MI = 16 is v_mfma_f32_16x16x32_bf16.  Same flops per cycle;
+    // under the chip's power limit the 16x16x32 form sustains 8 - 15 % more on random operands (a loop of nothing but
+    // MFMAs: 1.62 against 1.41 PFLOP/s with 4 wavefronts per CU, 1.81 against 1.67 with 8).  An operand fragment is
+    // MI rows x (16 or 32) k with every lane holding 8 consecutive k of row lane % MI, k-chunk lane / MI; a lane of the
+    // MI x MI result holds column lane % MI and NV rows.
+    static_assert(MI == 32 || MI == 16, "MFMA shape");
+    constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / MI, TN = WTN / MI;
+    constexpr int NV = MI * MI / 64;                 // accumulator values per lane and subtile
+    constexpr int KSTEP = MI == 32 ? 16 : 32;        // k extent of one MFMA
+    constexpr int KSTEPS = BKT / KSTEP;              // k-steps per stage
+    static_assert(KSTEPS == 2 || KSTEPS == 4, "k-steps per stage");
+    typedef float accv_t __attribute__((ext_vector_type(NV)));
     constexpr int NW = WGM * WGN;   // wavefronts per workgroup
     static_assert((NW == 4 || NW == 8) && TM >= 1 && TN >= 1 && (!DUAL || TN % 2 == 0), "tile shape");
     static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "every wavefront moves whole row groups of both tiles");
@@ -161,13 +184,13 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
 
-    floatx16 acc[TM][TN];
+    accv_t acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+            for (int v = 0; v < NV; ++v) acc[i][j][v] = 0.f;
 
     // Operand tiles go from global memory straight into LDS (buffer_load ... lds): no staging
     // registers and no ds_write traffic on the wavefronts' issue ports.  One such instruction moves
@@ -251,20 +274,22 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
     }
 
     const int nk = k_len / BK;
-    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int lrow = lane & (MI - 1), lhalf = lane / MI;   // row of this lane's fragments inside a subtile, and its k-chunk (0..1 or 0..3)
+    // row inside a subtile of accumulator value v of this lane
+    auto vrow = [&](int v) { return MI == 32 ? 8 * (v >> 2) + 4 * lhalf + (v & 3) : 4 * lhalf + v; };
 
     // LDS byte offsets of this lane's fragment rows (k-step 0); k-step kk flips the chunk index by 2*kk
     int offa[TM], offb[TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) offa[i] = (wm * WTM + i * 32 + lrow) * ROW_BYTES;
+    for (int i = 0; i < TM; ++i) offa[i] = (wm * WTM + i * MI + lrow) * ROW_BYTES;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         int r;
         if (DUAL) {   // first half of the subtiles: gate rows, second half: up rows of the same columns
             const int jj = j % (TN / 2);
-            r = (j >= TN / 2 ? BN / 2 : 0) + wn * (WTN / 2) + jj * 32 + lrow;
+            r = (j >= TN / 2 ? BN / 2 : 0) + wn * (WTN / 2) + jj * MI + lrow;
         } else {
-            r = wn * WTN + j * 32 + lrow;
+            r = wn * WTN + j * MI + lrow;
         }
         offb[j] = B_RING + r * ROW_BYTES;
     }
@@ -274,7 +299,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
 #define PSD_GEMM_LOAD_FRAGS(sa, sb, kk, set)                                                                  \
     {                                                                                                         \
         const unsigned char *a_ = lds + (sa) * A_BYTES, *b_ = lds + (sb) * B_BYTES;                           \
-        const int co_ = ((((kk) * 2 + lhalf) ^ rsw) << 4);                                                    \
+        const int co_ = ((((kk) * (KSTEP / 8) + lhalf) ^ rsw) << 4);                                          \
         _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                        \
             fa[set][i] = *reinterpret_cast<const bf16x8 *>(a_ + offa[i] + co_);                               \
         _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                        \
@@ -285,112 +310,13 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
         PSD_PRIO_HI                                                                                           \
         _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                        \
             _Pragma("unroll") for (int j = 0; j < TN; ++j)                                                    \
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0); \
+                acc[i][j] = mfma_step<MI>(fa[set][i], fb[set][j], acc[i][j]);                                 \
         PSD_PRIO_LO                                                                                           \
     }
 
     constexpr int NFRAG = TM + TN, NMFMA = TM * TN;
     static_assert(NSA >= 2 && NSB >= 2 && (ASYM ? 2 : 1) * ((NSA - 1) * GA + (NSB - 1) * GB) <= 63, "DMA groups in flight must fit the vmcnt counter");
     static_assert(!ASYM || (NW / 2) % 2 == 0, "wavefronts w and w + NW/2 share the swizzle key of their row groups");
-    if constexpr (PP) {
-        // Ping-pong schedule for the 8-wavefront tiles.  Wavefronts w and w + 4 sit on the same SIMD; they run the same
-        // sequence of phases -- per k-step a memory phase (fragment reads of that k-step, a quarter of the stage's
-        // fetches) and a compute phase (the k-step's MFMAs), every phase closed by a workgroup barrier -- but the upper
-        // four start one phase late.  So while one wavefront of a SIMD feeds the matrix core the other one reads LDS
-        // and issues fetches, instead of both doing the same thing at the same time and leaving the core idle in
-        // between.  Only the lower four wavefronts issue fetches (all of them): a wavefront is held up for some 20
-        // cycles per fetch instruction, time its sibling spends in MFMAs.  Fragments need no double buffering: a
-        // memory phase lasts as long as the sibling's compute phase, longer than the LDS latency.
-        static_assert(NW == 8 && BKT == 64 && NSA <= NSB && 2 * ((NSA - 1) * GA + (NSB - 1) * GB) <= 63, "ping-pong schedule");
-        const int grp = __builtin_amdgcn_readfirstlane(wave >> 2), lw = uwave & 3;
-        bf16x8 pa[TM], pb[TN];
-// one half (hh = 0, 1) of an operand tile's stage: the row groups of wavefronts lw + 4 hh
-#define PSD_PP_DMA_A(hh, slot, k0)                                                                            \
-    {                                                                                                         \
-        const int uw_ = lw + (hh) * 4;                                                                        \
-        unsigned char *sa_ = lds + (slot) * A_BYTES + uw_ * 1024;                                             \
-        _Pragma("unroll") for (int j = 0; j < GA; ++j)                                                        \
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_x, (lds_void *)(sa_ + j * (NW * 1024)), 16, voff_x, \
-                                                     ((j * NW + uw_) * RPI * ldx + (k0)) * 2, 0, 0);          \
-    }
-#define PSD_PP_DMA_B(hh, slot, k0)                                                                            \
-    {                                                                                                         \
-        const int uw_ = lw + (hh) * 4;                                                                        \
-        unsigned char *sb_ = lds + B_RING + (slot) * B_BYTES + uw_ * 1024;                                    \
-        _Pragma("unroll") for (int j = 0; j < GB; ++j) {                                                      \
-            if (DUAL && j * (RPI * NW) >= BN / 2)                                                             \
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_y2, (lds_void *)(sb_ + j * (NW * 1024)), 16, voff_y, \
-                                                         (((j * NW + uw_) * RPI - BN / 2) * ldy + (k0)) * 2, 0, 0); \
-            else                                                                                              \
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_y, (lds_void *)(sb_ + j * (NW * 1024)), 16, voff_y, \
-                                                         ((j * NW + uw_) * RPI * ldy + (k0)) * 2, 0, 0);      \
-        }                                                                                                     \
-    }
-#define PSD_PP_BARRIER()                                                                                      \
-    {                                                                                                         \
-        asm volatile("" ::: "memory");                                                                        \
-        __builtin_amdgcn_s_barrier();                                                                         \
-        asm volatile("" ::: "memory");                                                                        \
-        __builtin_amdgcn_sched_barrier(0);                                                                    \
-    }
-        if (grp == 0) {
-#pragma unroll
-            for (int p = 0; p < NSA - 1; ++p) {
-                PSD_PP_DMA_A(0, p, p * BK)
-                PSD_PP_DMA_A(1, p, p * BK)
-            }
-#pragma unroll
-            for (int p = 0; p < NSB - 1; ++p) {
-                PSD_PP_DMA_B(0, p, p * BK)
-                PSD_PP_DMA_B(1, p, p * BK)
-            }
-        }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        PSD_PP_BARRIER()
-        if (grp == 1) PSD_PP_BARRIER()   // the upper wavefronts run one phase behind
-        // fetches in flight that may still be outstanding when a stage ends: those of the deeper ring issued in that
-        // stage plus NSA - 2 whole stages (memory returns in issue order); twice the count of the symmetric schedule
-        constexpr int PP_WAIT = 2 * ((NSA - 2) * NLD + (NSA < NSB ? GB : 0));
-        int ca = 0, cb = 0;
-        for (int kt = 0; kt < nk; ++kt) {
-            const int na = (ca + 1 == NSA) ? 0 : ca + 1, nb = (cb + 1 == NSB) ? 0 : cb + 1;
-            const int fill_a = (ca == 0) ? NSA - 1 : ca - 1, fill_b = (cb == 0) ? NSB - 1 : cb - 1;
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                // ---- memory phase
-                {
-                    const unsigned char *a_ = lds + ca * A_BYTES, *b_ = lds + cb * B_BYTES;
-                    const int co_ = (((kk * 2 + lhalf) ^ rsw) << 4);
-#pragma unroll
-                    for (int i = 0; i < TM; ++i) pa[i] = *reinterpret_cast<const bf16x8 *>(a_ + offa[i] + co_);
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) pb[j] = *reinterpret_cast<const bf16x8 *>(b_ + offb[j] + co_);
-                }
-                if (grp == 0) {   // the slots being refilled were last read one phase before this stage began
-                    if (kk == 0) PSD_PP_DMA_A(0, fill_a, (kt + NSA - 1) * BK)
-                    if (kk == 1) PSD_PP_DMA_A(1, fill_a, (kt + NSA - 1) * BK)
-                    if (kk == 2) PSD_PP_DMA_B(0, fill_b, (kt + NSB - 1) * BK)
-                    if (kk == 3) PSD_PP_DMA_B(1, fill_b, (kt + NSB - 1) * BK)
-                }
-                PSD_PP_BARRIER()
-                // ---- compute phase
-                __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa[i], pb[j], acc[i][j], 0, 0, 0);
-                __builtin_amdgcn_s_setprio(0);
-                if (kk == 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PP_WAIT) : "memory");   // the next stage has landed
-                PSD_PP_BARRIER()
-            }
-            ca = na;
-            cb = nb;
-        }
-        if (grp == 0) PSD_PP_BARRIER()
-#undef PSD_PP_DMA_A
-#undef PSD_PP_DMA_B
-#undef PSD_PP_BARRIER
-    } else {
     bf16x8 fa[2][TM], fb[2][TN];
 
 #pragma unroll
@@ -410,7 +336,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
         const int na = (ca + 1 == NSA) ? 0 : ca + 1, nb = (cb + 1 == NSB) ? 0 : cb + 1;
         const int fill_a = (ca == 0) ? NSA - 1 : ca - 1, fill_b = (cb == 0) ? NSB - 1 : cb - 1;
         PSD_GEMM_LOAD_FRAGS(ca, cb, 1, 1)
-        if constexpr (SPREAD && BKT == 64) {
+        if constexpr (SPREAD && KSTEPS == 4) {
             // the shallower ring's stage in two halves during k-steps 0 and 1, the deeper ring's during k-step 2: the
             // same issue order as PSD_GEMM_ISSUE, so the wait below counts the same
             constexpr int MUL = ASYM ? 2 : 1;
@@ -430,7 +356,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
             PSD_GEMM_ISSUE(fill_a, fill_b, kt)
             PSD_GEMM_MFMA(0)
             sched_mix<0, NMFMA, NFRAG, 0, (ASYM ? 2 : 1) * NLD>();
-            if constexpr (BKT == 64) {
+            if constexpr (KSTEPS == 4) {
                 PSD_GEMM_LOAD_FRAGS(ca, cb, 2, 0)
                 PSD_GEMM_MFMA(1)
                 sched_mix<0, NMFMA, NFRAG, 0, 0>();
@@ -439,14 +365,13 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
                 sched_mix<0, NMFMA, NFRAG, 0, 0>();
             }
         }
-        // (a stage of 32 k has two k-steps: the second one computes behind the barrier)
+        // (with two k-steps per stage the second one computes behind the barrier)
         PSD_GEMM_STAGE_SYNC(WAIT)
         PSD_GEMM_LOAD_FRAGS(na, nb, 0, 0)
         PSD_GEMM_MFMA(1)
         sched_mix<0, NMFMA, NFRAG, 0, 0>();
         ca = na;
         cb = nb;
-    }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no DMA may outlive the loop
 #undef PSD_GEMM_LOAD_FRAGS
@@ -471,8 +396,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int m = m0 + wm * WTM + i * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
+                for (int v = 0; v < NV; ++v) {
+                    const int m = m0 + wm * WTM + i * MI + vrow(v);
                     float z = acc[i][j][v] * t1.scale;
                     if (m >= M || m == t1.mask_id) z = -INFINITY;
                     acc[i][j][v] = z;
@@ -486,14 +411,18 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) sum += __expf(acc[i][j][v] - best);
+                    for (int v = 0; v < NV; ++v) sum += __expf(acc[i][j][v] - best);
             }
-            const float b2 = __shfl_xor(best, 32, 64);
-            const int a2 = __shfl_xor(arg, 32, 64);
-            const float s2 = __shfl_xor(sum, 32, 64);
-            top1_merge(best, arg, sum, b2, a2, s2);
+            // the 64 / MI lanes that hold this column own disjoint row sets
+#pragma unroll
+            for (int off = 32; off >= MI; off >>= 1) {
+                const float b2 = __shfl_xor(best, off, 64);
+                const int a2 = __shfl_xor(arg, off, 64);
+                const float s2 = __shfl_xor(sum, off, 64);
+                top1_merge(best, arg, sum, b2, a2, s2);
+            }
             if (lhalf == 0) {
-                const int col = wn * WTN + j * 32 + lrow;
+                const int col = wn * WTN + j * MI + lrow;
                 s_b[wm][col] = best;
                 s_a[wm][col] = arg;
                 s_s[wm][col] = sum;
@@ -522,11 +451,11 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
-                    const int col = wn * WTN + j * 32 + lrow;
+                    const int col = wn * WTN + j * MI + lrow;
                     const float bn = bias ? bias[min(n0 + col, Nout - 1)] : 0.f;
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int row = wm * WTM + i * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
+                    for (int v = 0; v < NV; ++v) {
+                        const int row = wm * WTM + i * MI + vrow(v);
                         *reinterpret_cast<uint16_t *>(lds + row * LDC + col * 2) = from_float<bf16_t>(acc[i][j][v] + bn).bits;
                     }
                 }
@@ -555,11 +484,11 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
-                    const int col = wn * WTN + j * 32 + lrow;
+                    const int col = wn * WTN + j * MI + lrow;
                     const float bn = bias ? bias[min(n0 + col, Nout - 1)] : 0.f;
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int row = wm * WTM + i * 32 + 8 * q + 4 * lhalf;
+                    for (int q = 0; q < NV / 4; ++q) {
+                        const int row = wm * WTM + i * MI + vrow(4 * q);
                         uint2 w;
                         w.x = pack_bf16x2(acc[i][j][4 * q + 0] + bn, acc[i][j][4 * q + 1] + bn);
                         w.y = pack_bf16x2(acc[i][j][4 * q + 2] + bn, acc[i][j][4 * q + 3] + bn);
@@ -584,28 +513,37 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
         constexpr int TN_OUT = DUAL ? TN / 2 : TN;
         constexpr int WTN_OUT = DUAL ? WTN / 2 : WTN;
         if constexpr (EPI == EPI_RESIDUAL) {
-            // fp32 read-modify-write of the stream.  All 16 values of a 32x32 subtile are fetched before the first is
+            // fp32 read-modify-write of the stream.  16 values (a 32x32 subtile, or four 16x16 ones) are fetched before the first is
             // written back: written as one load-add-store per element, every load would wait for the store before it
             // (the compiler cannot tell rows m * ldo apart) and the epilogue becomes a chain of memory round trips
             // (measured: 6.45 -> 5.67 ms for the output projection at 163 840 rows; a whole row of subtiles per round trip
             // gains nothing more and spills registers on the 128x192 tile).
             float *dst = (split == 0) ? resid : partial + (int64_t)(split - 1) * M * Nout;
             const int ldd = (split == 0) ? ldo : Nout;
+            constexpr int JB = 16 / NV < TN ? 16 / NV : TN;   // subtiles per round trip: 16 values in flight per lane
+            static_assert(TN % JB == 0, "subtile batches");
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const int n = n0 + wn * WTN + j * 32 + lrow;
-                    float old[16];
+                for (int j0 = 0; j0 < TN; j0 += JB) {
+                    float old[JB][NV];
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int m = m0 + wm * WTM + i * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
-                        old[v] = (split == 0 && n < Nout && m < M) ? dst[(int64_t)m * ldd + n] : 0.f;
+                    for (int jj = 0; jj < JB; ++jj) {
+                        const int n = n0 + wn * WTN + (j0 + jj) * MI + lrow;
+#pragma unroll
+                        for (int v = 0; v < NV; ++v) {
+                            const int m = m0 + wm * WTM + i * MI + vrow(v);
+                            old[jj][v] = (split == 0 && n < Nout && m < M) ? dst[(int64_t)m * ldd + n] : 0.f;
+                        }
                     }
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int m = m0 + wm * WTM + i * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
-                        if (n < Nout && m < M) dst[(int64_t)m * ldd + n] = old[v] + acc[i][j][v];
+                    for (int jj = 0; jj < JB; ++jj) {
+                        const int n = n0 + wn * WTN + (j0 + jj) * MI + lrow;
+#pragma unroll
+                        for (int v = 0; v < NV; ++v) {
+                            const int m = m0 + wm * WTM + i * MI + vrow(v);
+                            if (n < Nout && m < M) dst[(int64_t)m * ldd + n] = old[jj][v] + acc[i][j0 + jj][v];
+                        }
                     }
                 }
             return;
@@ -623,11 +561,11 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN_OUT; ++j) {
-                    const int col = wn * WTN_OUT + j * 32 + lrow;
+                    const int col = wn * WTN_OUT + j * MI + lrow;
                     const float bn = (EPI == EPI_BIAS) ? bias[min(n0 + col, Nout - 1)] : 0.f;
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int row = wm * WTM + i * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
+                    for (int v = 0; v < NV; ++v) {
+                        const int row = wm * WTM + i * MI + vrow(v);
                         float x = acc[i][j][v];
                         if (EPI == EPI_BIAS) x += bn;
                         if (DUAL) {
@@ -650,12 +588,12 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN_OUT; ++j) {
-                const int n = n0 + wn * WTN_OUT + j * 32 + lrow;
+                const int n = n0 + wn * WTN_OUT + j * MI + lrow;
                 if (n >= Nout) continue;
                 const float bn = (EPI == EPI_BIAS) ? bias[n] : 0.f;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int m = m0 + wm * WTM + i * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
+                for (int v = 0; v < NV; ++v) {
+                    const int m = m0 + wm * WTM + i * MI + vrow(v);
                     if (m >= M) continue;
                     float x = acc[i][j][v];
                     if (EPI == EPI_BIAS) x += bn;
@@ -669,7 +607,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, int NSA = 2, int NSB = NSA, int BKT = BK, int SCHED = 0>
+template <int BM, int BN, int WGM, int WGN, int EPI, int NSA = 2, int NSB = NSA, int BKT = BK, int SCHED = 0, int MI = 32>
 void launch_cfg(const bf16_t *X, const bf16_t *Y, const bf16_t *Y2, int M, int Nout, int Kin, int ldx, int ldy, const float *bias,
                 bf16_t *out, float *resid, int ldo, Top1Args t1, hipStream_t st, int k_splits = 1, float *partial = nullptr,
                 QkvArgs qa = QkvArgs()) {
@@ -678,7 +616,7 @@ void launch_cfg(const bf16_t *X, const bf16_t *Y, const bf16_t *Y2, int M, int N
     const int n_tiles = tiles_m * tiles_n;
     constexpr int smem = (NSA * BM + NSB * BN) * BKT * 2;
     static_assert(smem <= 160 * 1024, "LDS ring exceeds the 160 KB of a CU");
-    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, EPI, NSA, NSB, BKT, SCHED>;
+    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, EPI, NSA, NSB, BKT, SCHED, MI>;
     static std::atomic<uint64_t> lds_raised{0};   // one per instantiation
     ensure_dynamic_lds(reinterpret_cast<const void *>(kern), smem, lds_raised);
     if (EPI != EPI_RESIDUAL) k_splits = 1;

@@ -9,6 +9,15 @@ namespace {
 
 using namespace mfma;
 
+// Main-loop schedule of the 8- and 4-wavefront tiles (bits as in gemm_bf16_kernel)
+#ifndef PSD_SCHED_8W
+#define PSD_SCHED_8W (2 | 4 | 8)
+#endif
+#ifndef PSD_SCHED_4W
+#define PSD_SCHED_4W 8
+#endif
+constexpr int S8 = PSD_SCHED_8W, S4 = PSD_SCHED_4W;
+
 struct TileCfg {
     int bm, bn;
     const char *name;
@@ -23,12 +32,8 @@ constexpr TileCfg kTiles[] = {
     {128, 128, "128x128, 4 wavefronts, LDS rings 4/4"},
     {64, 64, "64x64, 4 wavefronts, LDS rings 4/4"},
     {256, 128, "256x128, 8 wavefronts, LDS rings 2/4"},   // one full round of 256 workgroups for 2048 x 4096 outputs
-    {256, 256, "256x256, 8 wavefronts, 32 k per stage, LDS rings 5/5"},   // both operands fetched 4 stages (128 k) ahead
-    {256, 256, "256x256, 8 wavefronts in ping-pong phases, LDS rings 2/3"},
-    {256, 256, "x 8 waves asym+noprio+spread"},
-    {256, 256, "x 4 waves spread"},
-    {256, 256, "x 4 waves"},
-    {256, 256, "x 8 waves noprio+spread"},
+    {256, 256, "256x256, 8 wavefronts, 16x16x32 MFMAs, LDS rings 2/3"},
+    {128, 128, "128x128, 4 wavefronts, 16x16x32 MFMAs, LDS rings 2/3"},
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -41,28 +46,33 @@ void dispatch(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int M, int Nou
     // never returns the others for it
     if constexpr (EPI != EPI_SWIGLU) {
         switch (tile) {
-            case 2: return launch_cfg<256, 192, 4, 2, EPI, 2, 4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
-            case 3: return launch_cfg<128, 192, 2, 2, EPI, 2, 2>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
-            case 4: return launch_cfg<128, 64, 2, 2, EPI, 4, 4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
-            case 6: return launch_cfg<64, 64, 2, 2, EPI, 4, 4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
-            case 7: return launch_cfg<256, 128, 4, 2, EPI, 2, 4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+            case 2: return launch_cfg<256, 192, 4, 2, EPI, 2, 4, 64, S8>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+            case 3: return launch_cfg<128, 192, 2, 2, EPI, 2, 2, 64, S4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+            case 4: return launch_cfg<128, 64, 2, 2, EPI, 4, 4, 64, S4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+            case 6: return launch_cfg<64, 64, 2, 2, EPI, 4, 4, 64, S4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+            case 7: return launch_cfg<256, 128, 4, 2, EPI, 2, 4, 64, S8>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
             default: break;
         }
     }
     switch (tile) {
-        case 1: return launch_cfg<256, 256, 4, 2, EPI, 2, 3>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
-        case 5: return launch_cfg<128, 128, 2, 2, EPI, 4, 4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
-        case 8: return launch_cfg<256, 256, 4, 2, EPI, 5, 5, 32>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
-        case 9: return launch_cfg<256, 256, 4, 2, EPI, 2, 3, 64, 1>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
-        case 10: return launch_cfg<256, 256, 4, 2, EPI, 2, 3, 64, 2 | 4 | 8>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
-        case 11: return launch_cfg<256, 256, 2, 2, EPI, 2, 3, 64, 8>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
-        case 12: return launch_cfg<256, 256, 2, 2, EPI, 2, 3, 64, 0>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
-        case 13: return launch_cfg<256, 256, 4, 2, EPI, 2, 3, 64, 4 | 8>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
-        default: return launch_cfg<128, 128, 2, 2, EPI, 2, 3>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+        case 1:
+            // the 16x16x32 MFMA form of the same tile is 3 - 9 % faster on the store epilogues and on residual
+            // contractions with short K (measured at 2048 - 163 840 rows), level on SwiGLU, 4 - 7 % slower at K = 12288
+            if (EPI == EPI_STORE || EPI == EPI_BIAS || (EPI == EPI_RESIDUAL && Kin <= 4096))
+                return launch_cfg<256, 256, 4, 2, EPI, 2, 3, 64, S8, 16>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+            return launch_cfg<256, 256, 4, 2, EPI, 2, 3, 64, S8>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+        case 5: return launch_cfg<128, 128, 2, 2, EPI, 4, 4, 64, S4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+        case 8: return launch_cfg<256, 256, 4, 2, EPI, 2, 3, 64, S8, 16>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+        case 9: return launch_cfg<128, 128, 2, 2, EPI, 2, 3, 64, S4, 16>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+        default:
+            // (128x128 in the 16x16x32 form: SwiGLU 1.07 -> 1.29 PFLOP/s at 163 840 rows, the stores + 3 %, residual level)
+            if (EPI != EPI_RESIDUAL)
+                return launch_cfg<128, 128, 2, 2, EPI, 2, 3, 64, S4, 16>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+            return launch_cfg<128, 128, 2, 2, EPI, 2, 3, 64, S4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
     }
 }
 
-bool tile_fits(int tile, int epi) { return epi != EPI_SWIGLU || tile == 0 || tile == 1 || tile == 5 || tile >= 8; }
+bool tile_fits(int tile, int epi) { return epi != EPI_SWIGLU || tile == 0 || tile == 1 || tile == 5 ; }
 
 }   // namespace
 
@@ -143,7 +153,7 @@ int gemm_bf16_splits(int64_t M, int Nout, int Kin) {
 void launch_gemm_bf16_split(const bf16_t *A, const bf16_t *W, int64_t M, int Nout, int Kin, int lda, int ldw, float *resid, int ldo,
                             float *partial, int splits, hipStream_t st) {
     Top1Args none = {};
-    launch_cfg<128, 128, 2, 2, EPI_RESIDUAL, 4, 4>(A, W, nullptr, (int)M, Nout, Kin, lda, ldw, nullptr, nullptr, resid, ldo, none, st,
+    launch_cfg<128, 128, 2, 2, EPI_RESIDUAL, 4, 4, 64, S4>(A, W, nullptr, (int)M, Nout, Kin, lda, ldw, nullptr, nullptr, resid, ldo, none, st,
                                                      splits, partial);
 }
 
@@ -173,13 +183,14 @@ void launch_gemm_bf16_qkv(const bf16_t *A, const bf16_t *W, int64_t M, int Nout,
     qa.ld_vt = ld_vt;
     const int m = (int)M;
     switch (tile) {
-        case 1: return launch_cfg<256, 256, 4, 2, EPI_QKV, 2, 3>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
-        case 4: return launch_cfg<128, 64, 2, 2, EPI_QKV, 4, 4>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
-        case 5: return launch_cfg<128, 128, 2, 2, EPI_QKV, 4, 4>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
-        case 6: return launch_cfg<64, 64, 2, 2, EPI_QKV, 4, 4>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
-        case 7: return launch_cfg<256, 128, 4, 2, EPI_QKV, 2, 4>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
-        case 8: return launch_cfg<256, 256, 4, 2, EPI_QKV, 5, 5, 32>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
-        default: return launch_cfg<128, 128, 2, 2, EPI_QKV, 2, 3>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
+        case 1:   // (the 16x16x32 MFMA form: see dispatch)
+        case 8: return launch_cfg<256, 256, 4, 2, EPI_QKV, 2, 3, 64, S8, 16>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
+        case 4: return launch_cfg<128, 64, 2, 2, EPI_QKV, 4, 4, 64, S4>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
+        case 5: return launch_cfg<128, 128, 2, 2, EPI_QKV, 4, 4, 64, S4>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
+        case 6: return launch_cfg<64, 64, 2, 2, EPI_QKV, 4, 4, 64, S4>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
+        case 7: return launch_cfg<256, 128, 4, 2, EPI_QKV, 2, 4, 64, S8>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
+        case 9:
+        default: return launch_cfg<128, 128, 2, 2, EPI_QKV, 2, 3, 64, S4, 16>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
     }
 }
 
