@@ -32,9 +32,10 @@ HBM_PEAK_GBS = 8000.0
 # runs (FETCH_SIZE, WRITE_SIZE) scaled by what the same counters read for a plain 256 MiB copy; commands and tables in the
 # file named.  Stored figures of an earlier profile, not measured in this run: key = rows of the launch.
 SWIGLU_TRAFFIC = {
-    "source": "profiles/config3_hbm_traffic_pmc.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, copy-calibrated; taken at commit 9821292)",
+    "source": "profiles/config5_hbm_traffic_pmc.md and profiles/config3_hbm_traffic_pmc.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, "
+              "copy-calibrated; FETCH_SIZE counts what the L2s request from the fabric, Infinity-Cache hits included)",
     "d_model": 4096, "d_ffn": 12288,
-    "rows": {2048: (584.2 + 48.6) * 2 ** 20, 512: (230.6 + 12.0) * 2 ** 20},
+    "rows": {163840: (49.35 + 4.03) * 1e9, 20480: (6.17 + 0.50) * 1e9, 2048: (584.2 + 48.6) * 2 ** 20, 512: (230.6 + 12.0) * 2 ** 20},
 }
 
 
