@@ -57,8 +57,9 @@ void dispatch(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int M, int Nou
     switch (tile) {
         case 1:
             // the 16x16x32 MFMA form of the same tile is 3 - 9 % faster on the store epilogues and on residual
-            // contractions with short K (measured at 2048 - 163 840 rows), level on SwiGLU, 4 - 7 % slower at K = 12288
-            if (EPI == EPI_STORE || EPI == EPI_BIAS || (EPI == EPI_RESIDUAL && Kin <= 4096))
+            // contractions with short K (measured at 2048 - 163 840 rows), level to 5 % faster on SwiGLU (512 rows), 4 - 7 %
+            // slower on residual contractions at K = 12288
+            if (EPI != EPI_RESIDUAL || Kin <= 4096)
                 return launch_cfg<256, 256, 4, 2, EPI, 2, 3, 64, S8, 16>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
             return launch_cfg<256, 256, 4, 2, EPI, 2, 3, 64, S8>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
         case 5: return launch_cfg<128, 128, 2, 2, EPI, 4, 4, 64, S4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
