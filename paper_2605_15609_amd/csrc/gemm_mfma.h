@@ -341,15 +341,15 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
             // same issue order as PSD_GEMM_ISSUE, so the wait below counts the same
             constexpr int MUL = ASYM ? 2 : 1;
             constexpr int G1 = NSA <= NSB ? GA : GB, G2 = NSA <= NSB ? GB : GA;
-            if constexpr (NSA <= NSB) PSD_GEMM_DMA_A_PART(fill_a, (kt + NSA - 1) * BK, 0) else PSD_GEMM_DMA_B_PART(fill_b, (kt + NSB - 1) * BK, 0)
+            if constexpr (NSA <= NSB) { PSD_GEMM_DMA_A_PART(fill_a, (kt + NSA - 1) * BK, 0) } else { PSD_GEMM_DMA_B_PART(fill_b, (kt + NSB - 1) * BK, 0) }
             PSD_GEMM_MFMA(0)
             sched_mix<0, NMFMA, NFRAG, 0, MUL * ((G1 + 1) / 2)>();
             PSD_GEMM_LOAD_FRAGS(ca, cb, 2, 0)
-            if constexpr (NSA <= NSB) PSD_GEMM_DMA_A_PART(fill_a, (kt + NSA - 1) * BK, 1) else PSD_GEMM_DMA_B_PART(fill_b, (kt + NSB - 1) * BK, 1)
+            if constexpr (NSA <= NSB) { PSD_GEMM_DMA_A_PART(fill_a, (kt + NSA - 1) * BK, 1) } else { PSD_GEMM_DMA_B_PART(fill_b, (kt + NSB - 1) * BK, 1) }
             PSD_GEMM_MFMA(1)
             sched_mix<0, NMFMA, NFRAG, 0, MUL * (G1 / 2)>();
             PSD_GEMM_LOAD_FRAGS(ca, cb, 3, 1)
-            if constexpr (NSA <= NSB) PSD_GEMM_DMA_B(fill_b, (kt + NSB - 1) * BK) else PSD_GEMM_DMA_A(fill_a, (kt + NSA - 1) * BK)
+            if constexpr (NSA <= NSB) { PSD_GEMM_DMA_B(fill_b, (kt + NSB - 1) * BK) } else { PSD_GEMM_DMA_A(fill_a, (kt + NSA - 1) * BK) }
             PSD_GEMM_MFMA(0)
             sched_mix<0, NMFMA, NFRAG, 0, MUL * G2>();
         } else {
@@ -520,8 +520,9 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
             // gains nothing more and spills registers on the 128x192 tile).
             float *dst = (split == 0) ? resid : partial + (int64_t)(split - 1) * M * Nout;
             const int ldd = (split == 0) ? ldo : Nout;
-            constexpr int JB = 16 / NV < TN ? 16 / NV : TN;   // subtiles per round trip: 16 values in flight per lane
-            static_assert(TN % JB == 0, "subtile batches");
+            // subtiles per round trip: up to 16 values in flight per lane
+            constexpr int JB = NV >= 16 ? 1 : (TN % 4 == 0 ? 4 : TN % 2 == 0 ? 2 : 1);
+            static_assert(TN % JB == 0 && JB * NV <= 16, "subtile batches");
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
