@@ -247,6 +247,38 @@ def test_bf16_batched_cached_decode_equals_sequences_alone_and_the_masked_decode
         assert st[0].invocations == st_all[b].invocations and st[0].tokens == st_all[b].tokens == G
 
 
+def test_bf16_cached_call_at_128_and_256_rows_agrees_to_rounding():
+    """Block-row calls over at most 128 rows cut the residual contractions along K (a weight stream needs the workgroups),
+    larger ones do not: a sequence's fp32 sums, hence its logits, depend on whether 4 or 8 sequences share the call --
+    to rounding, not beyond.  Both stay within the logit tolerance of each other and of the oracle; exact batch
+    invariance is a property of the whole-sequence calls only."""
+    import paper_2605_15609_amd as psd
+    from tests.gpu_common import say
+    shape = BF16["gqa-bias-dh128"]
+    L = 32
+    P, N = 2 * L, 4 * L
+    host = inp.draw_model(shape, N)
+    model = psd.Model.from_host(host, DEV)
+    seqs = [_state(shape, N, P, L, 0, 50 + b, 3 + b) for b in range(8)]
+    start = seqs[0][1]
+    tokens = np.stack([t for t, _ in seqs])
+    out = {}
+    for S in (4, 8):
+        d = _dev(tokens[:S])
+        cache = psd.KvCache(model, S, N)
+        psd.psd_kv_prefill(model, d, start, L, cache)
+        top1, conf, logits = psd.psd_forward_confidence_cached(model, d, start, L, cache, want_logits=True)
+        out[S] = (top1.cpu().numpy(), conf.cpu().numpy(), logits.cpu().numpy().reshape(S, L, -1))
+    diff = float(np.abs(out[4][2] - out[8][2][:4]).max())
+    say(f"[block-causal] 128-row call (K-split) vs 256-row call: logits differ by {diff:.3e}; bit-identical: {diff == 0.0}")
+    assert diff <= 2e-2
+    for S in (4, 8):
+        _check(shape, host, out[S][2][1], out[S][0][1], out[S][1][1], seqs[1][0], start, L, 2e-2, f"cached call of {S} sequences")
+    masked = tokens[:4, start: start + L] == shape.mask_id
+    rel = np.abs(out[4][1][masked] / out[8][1][:4][masked] - 1.0).max()
+    assert rel <= np.expm1(2 * 2e-2)
+
+
 def test_empty_prefix_full_cache_and_argument_errors():
     import paper_2605_15609_amd as psd
     shape = FP32

@@ -86,6 +86,8 @@ def check_sequence(ref, logits, top1, conf, t, mask_id, block_start, L, tol_logi
         gap = z[j, o_top1[j]] - z[j, top1[j]]
         assert gap <= 2 * tol_logits, f"{label}: top-1 mismatch with oracle logit gap {gap:.3e}"
         wide += int(margin[j] >= 1e-3)
+    # such mismatches are the tail of the logit noise: a handful per block (measured 2 of 32 and 4 of 64 rows at full depth)
+    assert wide <= max(2, int(masked.sum()) // 8), f"{label}: {wide} top-1 mismatches beyond near-ties among {int(masked.sum())} rows"
     safe = masked & ~differ
     assert (top1[masked] != mask_id).all()
     rel = np.abs(conf[safe] / o_conf[safe] - 1.0).max() if safe.any() else 0.0

@@ -163,5 +163,5 @@ def test_full_size_model_call_against_golden_oracle_states(cfg):
     say(f"[golden] config {cfg}: {log}; sampled logits rms err {rms:.3e} over {n_samples} samples; oracle bf16-operand noise floor "
         f"max-abs {floor_max:.3e} rms {floor_rms:.3e}; tolerance used {tol:.3e} (the stated 2e-2 is not attainable at d_model {shape.d_model})")
     assert rms <= 1.25 * floor_rms, f"cfg{cfg}: sampled logits rms error {rms:.3e} > 1.25 x {floor_rms:.3e}"
-    assert log["top1_mismatch_inside_band"] <= log["rows"] // 4, log
+    assert log["top1_mismatch_inside_band"] <= log["rows"] // 8, log     # measured 19 / 280, 20 / 203, 9 / 540
     model.close()
