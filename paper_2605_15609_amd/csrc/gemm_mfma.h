@@ -56,7 +56,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int EPI_TOP1 = 4;
 constexpr int EPI_QKV = 5;
-constexpr int BK = 64;                  // default k extent per stage (bf16) = 128 bytes per LDS row
+constexpr int BK = 64;                  // k extent per stage (bf16) = 128 bytes per LDS row
 
 struct Top1Args {
     float scale;        // logits = scale * acc
@@ -76,14 +76,10 @@ struct QkvArgs {
     int ld_vt;
 };
 
-// Swizzle key of an LDS row (64 banks x 4 bytes = 256 bytes per bank line; 16 consecutive rows fetching the same
-// logical 16-byte chunk must hit 16 distinct bank groups).  128-byte rows (64 k per stage): rows r and r+1 cover the
-// two halves of a bank line, the chunk slot is rotated by (r >> 1) over 8 slots.  64-byte rows (32 k per stage): four
-// rows per bank line, rotated by (r >> 2) over 4 slots.
-template <int BKT>
-__device__ __forceinline__ int row_key(int row) {
-    return BKT == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3);
-}
+// Swizzle key of an LDS row: 64 banks x 4 bytes = 256 bytes per bank line, rows are 128 bytes, so rows r and r+1 cover
+// the two halves of a bank line and the chunk slot is rotated by (r >> 1) over the 8 slots of a row: 16 consecutive rows
+// fetching the same logical 16-byte chunk hit 16 distinct bank groups.
+__device__ __forceinline__ int row_key(int row) { return (row >> 1) & 7; }
 
 // merge two (max, argmax, sum-exp) triples; ties go to the lower index
 __device__ __forceinline__ void top1_merge(float &b, int &a, float &s, float b2, int a2, float s2) {
@@ -121,7 +117,7 @@ __device__ __forceinline__ void sched_mix() {
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, int NSA, int NSB, int BKT = BK, int SCHED = 0, int MI = 32>
+template <int BM, int BN, int WGM, int WGN, int EPI, int NSA, int NSB, int SCHED = 0, int MI = 32>
 __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Y,
                                                         const bf16_t *__restrict__ Y2, int M, int Nout, int Kin, int ldx, int ldy,
                                                         const float *__restrict__ bias, bf16_t *__restrict__ out,
@@ -129,7 +125,6 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
                                                         Top1Args t1, int k_splits, float *__restrict__ partial, int group_m,
                                                         QkvArgs qa) {
     extern __shared__ __align__(16) unsigned char lds[];
-    static_assert(BKT == 64 || BKT == 32, "k extent of a stage");
     // Schedule of the main loop.  Bit 1: only the lower half of the wavefronts issues fetches, for itself and for
     // wavefront w + NW/2 (its sibling on the same SIMD when there are 8): a fetch instruction holds its wavefront up for
     // some 20 cycles, and two siblings that both fetch right after the stage barrier leave the matrix core idle.
@@ -139,8 +134,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
     // 8-wavefront tiles and 8 on the 4-wavefront tiles take 2 - 8 % off (bit 1 costs the small 4-wavefront tiles 2 - 8 %).
     constexpr bool ASYM = (SCHED & 2) != 0, NOPRIO = (SCHED & 4) != 0, SPREAD = (SCHED & 8) != 0;
     static_assert((SCHED & 1) == 0, "schedule bits");
-    constexpr int BK = BKT, ROW_BYTES = BKT * 2;          // (shadows the default: everything below is per instantiation)
-    constexpr int LPR = ROW_BYTES / 16, RPI = 64 / LPR;   // lanes per LDS row and rows per DMA instruction (1 KB)
+    constexpr int ROW_BYTES = BK * 2;                     // an LDS row: one tile row of one stage
+    constexpr int LPR = ROW_BYTES / 16, RPI = 64 / LPR;   // lanes per LDS row (8) and rows per DMA instruction (8: 1 KB)
     constexpr bool DUAL = EPI == EPI_SWIGLU;
     constexpr int BN_OUT = DUAL ? BN / 2 : BN;            // output columns per tile
     constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES, B_RING = NSA * A_BYTES;   // X ring first, then the Y ring
@@ -153,7 +148,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
     constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / MI, TN = WTN / MI;
     constexpr int NV = MI * MI / 64;                 // accumulator values per lane and subtile
     constexpr int KSTEP = MI == 32 ? 16 : 32;        // k extent of one MFMA
-    constexpr int KSTEPS = BKT / KSTEP;              // k-steps per stage
+    constexpr int KSTEPS = BK / KSTEP;               // k-steps per stage
     static_assert(KSTEPS == 2 || KSTEPS == 4, "k-steps per stage");
     typedef float accv_t __attribute__((ext_vector_type(NV)));
     constexpr int NW = WGM * WGN;   // wavefronts per workgroup
@@ -209,8 +204,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
     const __amdgpu_buffer_rsrc_t rsrc_y2 = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<bf16_t *>(DUAL ? Y2 : Y) + (int64_t)n0 * ldy + k_beg, 0, ((rows_y - 1) * ldy + Kin - k_beg) * 2, 0x00020000);
     const int uwave = __builtin_amdgcn_readfirstlane(wave);
-    // (64-byte rows: a DMA instruction moves 16 rows; the key of row 16 g + l/4 is (l / 16) & 3 for every group g)
-    const int dma_key = BKT == 64 ? ((((uwave & 1) << 2) + (lane >> 4)) & 7) : ((lane >> 4) & 3);
+    const int dma_key = (((uwave & 1) << 2) + (lane >> 4)) & 7;
     const int voff_x = (lane / LPR) * ldx * 2 + (((lane % LPR) ^ dma_key) << 4);
     const int voff_y = (lane / LPR) * ldy * 2 + (((lane % LPR) ^ dma_key) << 4);
     constexpr int GA = BM / RPI / NW, GB = BN / RPI / NW;   // row groups per wavefront, A and B tile
@@ -285,7 +279,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         int r;
-        if (DUAL) {   // first half of the subtiles: gate rows, second half: up rows of the same columns
+        if constexpr (DUAL) {   // first half of the subtiles: gate rows, second half: up rows of the same columns
             const int jj = j % (TN / 2);
             r = (j >= TN / 2 ? BN / 2 : 0) + wn * (WTN / 2) + jj * MI + lrow;
         } else {
@@ -293,7 +287,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
         }
         offb[j] = B_RING + r * ROW_BYTES;
     }
-    const int rsw = row_key<BKT>(lrow);   // swizzle key of every fragment row of this lane: rows differ by multiples of 32
+    const int rsw = row_key(lrow);   // swizzle key of every fragment row of this lane: rows differ by multiples of 32
 
 // fragments of k-step kk of an LDS stage into register set `set`
 #define PSD_GEMM_LOAD_FRAGS(sa, sb, kk, set)                                                                  \
@@ -608,16 +602,16 @@ __global__ __launch_bounds__(WGM * WGN * 64) void gemm_bf16_kernel(const bf16_t 
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int EPI, int NSA = 2, int NSB = NSA, int BKT = BK, int SCHED = 0, int MI = 32>
+template <int BM, int BN, int WGM, int WGN, int EPI, int NSA = 2, int NSB = NSA, int SCHED = 0, int MI = 32>
 void launch_cfg(const bf16_t *X, const bf16_t *Y, const bf16_t *Y2, int M, int Nout, int Kin, int ldx, int ldy, const float *bias,
                 bf16_t *out, float *resid, int ldo, Top1Args t1, hipStream_t st, int k_splits = 1, float *partial = nullptr,
                 QkvArgs qa = QkvArgs()) {
     constexpr int BN_OUT = (EPI == EPI_SWIGLU) ? BN / 2 : BN;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (Nout + BN_OUT - 1) / BN_OUT;
     const int n_tiles = tiles_m * tiles_n;
-    constexpr int smem = (NSA * BM + NSB * BN) * BKT * 2;
+    constexpr int smem = (NSA * BM + NSB * BN) * BK * 2;
     static_assert(smem <= 160 * 1024, "LDS ring exceeds the 160 KB of a CU");
-    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, EPI, NSA, NSB, BKT, SCHED, MI>;
+    auto kern = gemm_bf16_kernel<BM, BN, WGM, WGN, EPI, NSA, NSB, SCHED, MI>;
     static std::atomic<uint64_t> lds_raised{0};   // one per instantiation
     ensure_dynamic_lds(reinterpret_cast<const void *>(kern), smem, lds_raised);
     if (EPI != EPI_RESIDUAL) k_splits = 1;

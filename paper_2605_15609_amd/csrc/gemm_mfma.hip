@@ -46,11 +46,11 @@ void dispatch(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int M, int Nou
     // never returns the others for it
     if constexpr (EPI != EPI_SWIGLU) {
         switch (tile) {
-            case 2: return launch_cfg<256, 192, 4, 2, EPI, 2, 4, 64, S8>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
-            case 3: return launch_cfg<128, 192, 2, 2, EPI, 2, 2, 64, S4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
-            case 4: return launch_cfg<128, 64, 2, 2, EPI, 4, 4, 64, S4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
-            case 6: return launch_cfg<64, 64, 2, 2, EPI, 4, 4, 64, S4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
-            case 7: return launch_cfg<256, 128, 4, 2, EPI, 2, 4, 64, S8>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+            case 2: return launch_cfg<256, 192, 4, 2, EPI, 2, 4, S8>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+            case 3: return launch_cfg<128, 192, 2, 2, EPI, 2, 2, S4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+            case 4: return launch_cfg<128, 64, 2, 2, EPI, 4, 4, S4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+            case 6: return launch_cfg<64, 64, 2, 2, EPI, 4, 4, S4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+            case 7: return launch_cfg<256, 128, 4, 2, EPI, 2, 4, S8>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
             default: break;
         }
     }
@@ -60,16 +60,16 @@ void dispatch(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int M, int Nou
             // contractions with short K (measured at 2048 - 163 840 rows), level to 5 % faster on SwiGLU (512 rows), 4 - 7 %
             // slower on residual contractions at K = 12288
             if (EPI != EPI_RESIDUAL || Kin <= 4096)
-                return launch_cfg<256, 256, 4, 2, EPI, 2, 3, 64, S8, 16>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
-            return launch_cfg<256, 256, 4, 2, EPI, 2, 3, 64, S8>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
-        case 5: return launch_cfg<128, 128, 2, 2, EPI, 4, 4, 64, S4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
-        case 8: return launch_cfg<256, 256, 4, 2, EPI, 2, 3, 64, S8, 16>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
-        case 9: return launch_cfg<128, 128, 2, 2, EPI, 2, 3, 64, S4, 16>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+                return launch_cfg<256, 256, 4, 2, EPI, 2, 3, S8, 16>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+            return launch_cfg<256, 256, 4, 2, EPI, 2, 3, S8>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+        case 5: return launch_cfg<128, 128, 2, 2, EPI, 4, 4, S4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+        case 8: return launch_cfg<256, 256, 4, 2, EPI, 2, 3, S8, 16>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+        case 9: return launch_cfg<128, 128, 2, 2, EPI, 2, 3, S4, 16>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
         default:
             // (128x128 in the 16x16x32 form: SwiGLU 1.07 -> 1.29 PFLOP/s at 163 840 rows, the stores + 3 %, residual level)
             if (EPI != EPI_RESIDUAL)
-                return launch_cfg<128, 128, 2, 2, EPI, 2, 3, 64, S4, 16>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
-            return launch_cfg<128, 128, 2, 2, EPI, 2, 3, 64, S4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+                return launch_cfg<128, 128, 2, 2, EPI, 2, 3, S4, 16>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
+            return launch_cfg<128, 128, 2, 2, EPI, 2, 3, S4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
     }
 }
 
@@ -154,7 +154,7 @@ int gemm_bf16_splits(int64_t M, int Nout, int Kin) {
 void launch_gemm_bf16_split(const bf16_t *A, const bf16_t *W, int64_t M, int Nout, int Kin, int lda, int ldw, float *resid, int ldo,
                             float *partial, int splits, hipStream_t st) {
     Top1Args none = {};
-    launch_cfg<128, 128, 2, 2, EPI_RESIDUAL, 4, 4, 64, S4>(A, W, nullptr, (int)M, Nout, Kin, lda, ldw, nullptr, nullptr, resid, ldo, none, st,
+    launch_cfg<128, 128, 2, 2, EPI_RESIDUAL, 4, 4, S4>(A, W, nullptr, (int)M, Nout, Kin, lda, ldw, nullptr, nullptr, resid, ldo, none, st,
                                                      splits, partial);
 }
 
@@ -188,13 +188,13 @@ void launch_gemm_bf16_qkv(const bf16_t *A, const bf16_t *W, int64_t M, int Nout,
     const int m = (int)M;
     switch (tile) {
         case 1:   // (the 16x16x32 MFMA form: see dispatch)
-        case 8: return launch_cfg<256, 256, 4, 2, EPI_QKV, 2, 3, 64, S8, 16>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
-        case 4: return launch_cfg<128, 64, 2, 2, EPI_QKV, 4, 4, 64, S4>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
-        case 5: return launch_cfg<128, 128, 2, 2, EPI_QKV, 4, 4, 64, S4>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
-        case 6: return launch_cfg<64, 64, 2, 2, EPI_QKV, 4, 4, 64, S4>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
-        case 7: return launch_cfg<256, 128, 4, 2, EPI_QKV, 2, 4, 64, S8>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
+        case 8: return launch_cfg<256, 256, 4, 2, EPI_QKV, 2, 3, S8, 16>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
+        case 4: return launch_cfg<128, 64, 2, 2, EPI_QKV, 4, 4, S4>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
+        case 5: return launch_cfg<128, 128, 2, 2, EPI_QKV, 4, 4, S4>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
+        case 6: return launch_cfg<64, 64, 2, 2, EPI_QKV, 4, 4, S4>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
+        case 7: return launch_cfg<256, 128, 4, 2, EPI_QKV, 2, 4, S8>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
         case 9:
-        default: return launch_cfg<128, 128, 2, 2, EPI_QKV, 2, 3, 64, S4, 16>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
+        default: return launch_cfg<128, 128, 2, 2, EPI_QKV, 2, 3, S4, 16>(A, W, nullptr, m, Nout, Kin, lda, ldw, bias, qkv, nullptr, ld_qkv, none, st, 1, nullptr, qa);
     }
 }
 
