@@ -35,7 +35,7 @@ SWIGLU_TRAFFIC = {
     "source": "profiles/config5_hbm_traffic_pmc.md and profiles/config3_hbm_traffic_pmc.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, "
               "copy-calibrated; FETCH_SIZE counts what the L2s request from the fabric, Infinity-Cache hits included)",
     "d_model": 4096, "d_ffn": 12288,
-    "rows": {163840: (49.35 + 4.03) * 1e9, 20480: (6.17 + 0.50) * 1e9, 2048: (584.2 + 48.6) * 2 ** 20, 512: (230.6 + 12.0) * 2 ** 20},
+    "rows": {163840: (49.35 + 4.03) * 1e9, 20480: (6.17 + 0.50) * 1e9, 2048: (589.1 + 48.0) * 2 ** 20, 512: (230.6 + 12.0) * 2 ** 20},
 }
 
 
