@@ -24,6 +24,8 @@ struct TileCfg {
 };
 // index = value returned by gemm_bf16_tile
 constexpr TileCfg kTiles[] = {
+    // (tiles 0 and 1 run in the 32x32x16 or the 16x16x32 MFMA form, whichever was measured faster for the epilogue; 8 and 9
+    // force the 16x16x32 form)
     {128, 128, "128x128, 4 wavefronts, LDS rings 2/3"},   // two workgroups per CU
     {256, 256, "256x256, 8 wavefronts, LDS rings 2/3"},   // least LDS traffic per FLOP; fills the 160 KB
     {256, 192, "256x192, 8 wavefronts, LDS rings 2/4"},
@@ -73,7 +75,7 @@ void dispatch(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int M, int Nou
     }
 }
 
-bool tile_fits(int tile, int epi) { return epi != EPI_SWIGLU || tile == 0 || tile == 1 || tile == 5 ; }
+bool tile_fits(int tile, int epi) { return epi != EPI_SWIGLU || tile == 0 || tile == 1 || tile == 5 || tile == 8 || tile == 9; }
 
 }   // namespace
 
