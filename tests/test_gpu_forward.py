@@ -177,6 +177,39 @@ def test_rotary_and_value_transpose_in_the_qkv_epilogue_change_no_bit(name, N, S
     assert err < 2e-2
 
 
+@pytest.mark.parametrize("name,N,S", [("small-2l", 96, 5), ("gqa-bias", 272, 3)])
+def test_qkv_epilogue_on_every_tile_configuration(name, N, S):
+    """The same comparison with every workgroup tile forced in turn (the forced tile serves all contractions of both runs):
+    every instantiation of the rotary / transpose epilogue that a shape can reach is run, ragged last tiles included."""
+    import paper_2605_15609_amd as psd
+    from paper_2605_15609_amd import binding as B
+    from tests.gpu_common import make_models, to_dev, say
+    lib = B.load_library()
+    shape = SHAPES[name][0]
+    L = 16
+    bs = N - 2 * L
+    host, model = make_models(shape, N)
+    states = np.stack([_state(shape, N, bs, L, 60 + s, (5 * s) % L) for s in range(S)])
+    d = to_dev(states)
+    reference = None
+    try:
+        for tile in range(lib.psd_kernel_gemm_tile_count()):
+            lib.psd_debug_force_gemm_tile(tile)
+            out = {}
+            for mask in (0, 8):
+                model.set_plain(mask)
+                out[mask] = psd.psd_forward_logits(model, d, bs, L).cpu().numpy()
+            assert (out[0] == out[8]).all(), f"{name} tile {tile}: max difference {np.abs(out[0] - out[8]).max():.3e}"
+            # a sequence's sums do not depend on the tile either
+            if reference is None:
+                reference = out[0]
+            assert (out[0] == reference).all(), f"{name}: tile {tile} changes the logits"
+    finally:
+        lib.psd_debug_force_gemm_tile(-1)
+        model.set_plain(0)
+    say(f"[forward] fused QKV epilogue {name}: bit-identical on all {lib.psd_kernel_gemm_tile_count()} tile configurations")
+
+
 def test_batched_forward_equals_single(monkeypatch):
     """Batching S sequences must not change any sequence's (top1, conf) by more than rounding
     of the tile schedule; the decisions of the all-MFMA path must agree exactly here."""
