@@ -90,7 +90,7 @@ struct Dispatch<bf16_t> {
             pend.stride = M * Nout;
         } else {
             psd_handle::Probe &pr = h->probe;
-            const bool timed = pr.enabled && epi == pr.epi && gemm_bf16_tile(M, Nout, epi) == pr.tile &&
+            const bool timed = pr.enabled && epi == pr.epi && gemm_bf16_tile(M, Nout, epi, Kin) == pr.tile &&
                                pr.used + 2 <= pr.ev.size();
             if (timed) (void)hipEventRecord(pr.ev[pr.used], st);
             launch_gemm_bf16(A, (const bf16_t *)W, (const bf16_t *)W2, M, Nout, Kin, lda, ldw, epi, bias, out, resid, ldo, st);

@@ -43,7 +43,7 @@ template <int EPI>
 void dispatch(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int M, int Nout, int Kin, int lda, int ldw, const float *bias,
               bf16_t *out, float *resid, int ldo, hipStream_t st) {
     Top1Args none = {};
-    const int tile = gemm_bf16_tile(M, Nout, EPI);
+    const int tile = gemm_bf16_tile(M, Nout, EPI, Kin);
     // SwiGLU needs an even number of 32-column subtiles per wavefront (gate and up halves); gemm_bf16_tile
     // never returns the others for it
     if constexpr (EPI != EPI_SWIGLU) {
@@ -68,8 +68,9 @@ void dispatch(const bf16_t *A, const bf16_t *W, const bf16_t *W2, int M, int Nou
         case 8: return launch_cfg<256, 256, 4, 2, EPI, 2, 3, S8, 16>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
         case 9: return launch_cfg<128, 128, 2, 2, EPI, 2, 3, S4, 16>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
         default:
-            // (128x128 in the 16x16x32 form: SwiGLU 1.07 -> 1.29 PFLOP/s at 163 840 rows, the stores + 3 %, residual level)
-            if (EPI != EPI_RESIDUAL)
+            // (128x128 in the 16x16x32 form: SwiGLU 1.07 -> 1.29 PFLOP/s at 163 840 rows, the stores + 3 %, residual
+            // contractions 81 -> 73 us at K = 4096 and level at K = 12288)
+            if (EPI != EPI_RESIDUAL || Kin <= 4096)
                 return launch_cfg<128, 128, 2, 2, EPI, 2, 3, S4, 16>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
             return launch_cfg<128, 128, 2, 2, EPI, 2, 3, S4>(A, W, W2, M, Nout, Kin, lda, ldw, bias, out, resid, ldo, none, st);
     }
@@ -92,7 +93,7 @@ int gemm_tile_group_m() { return g_group_m; }
 int gemm_bf16_tile_count() { return kNumTiles; }
 const char *gemm_bf16_tile_name(int tile) { return tile >= 0 && tile < kNumTiles ? kTiles[tile].name : "?"; }
 
-int gemm_bf16_tile(int64_t M, int Nout, int epi) {
+int gemm_bf16_tile(int64_t M, int Nout, int epi, int Kin) {
     if (g_force_tile >= 0 && g_force_tile < kNumTiles && tile_fits(g_force_tile, epi)) return g_force_tile;
     const bool dual = epi == EPI_SWIGLU;
     const int64_t cols = dual ? 2 * (int64_t)Nout : Nout;
@@ -115,9 +116,13 @@ int gemm_bf16_tile(int64_t M, int Nout, int epi) {
         int tile, per_round;
         double rate;
     };
-    // (the 256x192 tile pays its fp32 read-modify-write epilogue on twice the rows per workgroup: slower than
-    // 128x192 on the residual contractions, faster on the stores)
-    const Cand cand[] = {{1, 256, 1.25}, {2, 256, epi == EPI_RESIDUAL ? 1.12 : 1.16}, {3, 512, 1.15}, {0, 512, 1.00}};
+    // Residual contractions (fp32 read-modify-write epilogue), measured at 2048 x 4096 and 6144 x 3584 outputs: 256x192 beats
+    // 128x192 by 2 - 8 %; with a long K (12288: 215 against 235 us) one full round of 256x128 tiles beats two 128x128
+    // workgroups per CU, with K = 4096 it does not (the 128x128 tile in its 16x16x32 form: 73 against 77 us).  Kin = 0:
+    // unknown, taken as long.
+    const bool resid = epi == EPI_RESIDUAL;
+    const Cand cand[] = {{1, 256, 1.25}, {2, 256, 1.16}, {3, 512, resid ? 1.12 : 1.15}, {0, 512, 1.00},
+                         {7, 256, resid && (Kin == 0 || Kin > 4096) ? 1.08 : 0.90}};
     int best = 0;
     double best_cost = 0;
     for (const Cand &c : cand) {

@@ -280,7 +280,7 @@ void launch_head_finish(const float *row_sum, const int32_t *row_arg, const int3
 // gemm_mfma.hip (bf16; Nout, Kin multiples of 64)
 // index of the tile configuration the dispatcher picks for a shape; gemm_bf16_tile_name(i) describes configuration i
 // (workgroup tile, wavefronts, LDS ring depths), 0 <= i < gemm_bf16_tile_count()
-int gemm_bf16_tile(int64_t M, int Nout, int epi);
+int gemm_bf16_tile(int64_t M, int Nout, int epi, int Kin = 0);   // Kin = 0: not known (matters for residual contractions only)
 int gemm_bf16_tile_count();
 // QKV projection that also applies the rotary embedding to the q / k heads and stores V transposed into vT (what
 // launch_rope_transpose_v does in a second pass), bit-identical to the two-pass form.  gemm_bf16_qkv_tile returns the tile
