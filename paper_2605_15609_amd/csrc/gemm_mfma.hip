@@ -119,10 +119,11 @@ int gemm_bf16_tile(int64_t M, int Nout, int epi, int Kin) {
     // Residual contractions (fp32 read-modify-write epilogue), measured at 2048 x 4096 and 6144 x 3584 outputs: 256x192 beats
     // 128x192 by 2 - 8 %; with a long K (12288: 215 against 235 us) one full round of 256x128 tiles beats two 128x128
     // workgroups per CU, with K = 4096 it does not (the 128x128 tile in its 16x16x32 form: 73 against 77 us).  Kin = 0:
-    // unknown, taken as long.
+    // unknown, taken as long.  Store epilogues: per round of workgroups the 256x128 tile is 5 - 15 % ahead of 128x128 (512 x 12288
+    // outputs: 57 against 69 us) and behind 256x192.
     const bool resid = epi == EPI_RESIDUAL;
     const Cand cand[] = {{1, 256, 1.25}, {2, 256, 1.16}, {3, 512, resid ? 1.12 : 1.15}, {0, 512, 1.00},
-                         {7, 256, resid && (Kin == 0 || Kin > 4096) ? 1.08 : 0.90}};
+                         {7, 256, !resid ? 1.03 : (Kin == 0 || Kin > 4096) ? 1.08 : 0.90}};
     int best = 0;
     double best_cost = 0;
     for (const Cand &c : cand) {
